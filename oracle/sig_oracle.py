@@ -1,0 +1,124 @@
+"""ctypes front end of the fp64 CPU oracle (`sig_oracle.c`).  TEST INFRASTRUCTURE ONLY.
+
+Only the tests, `__graft_entry__.smoke()` and the benchmark's cpu_baseline leg may import
+this module.  It never touches the HIP library or the product package.
+
+The C file is compiled on demand with the host gcc (`ensure_built`); building the checker
+is not using it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import threading
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sig_oracle.c")
+_LIB = os.path.join(_HERE, "libsig_oracle.so")
+_lock = threading.Lock()
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile `sig_oracle.c` into `libsig_oracle.so` next to it; returns the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", tmp, _SRC]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    with _lock:
+        if _lib is None:
+            lib = ctypes.CDLL(build())
+            i64, i32 = ctypes.c_int64, ctypes.c_int
+            dp = ctypes.POINTER(ctypes.c_double)
+            lib.sig_oracle_channels.restype = i64
+            lib.sig_oracle_channels.argtypes = [i32, i32]
+            lib.sig_oracle_exp.restype = None
+            lib.sig_oracle_exp.argtypes = [dp, i32, i32, dp]
+            lib.sig_oracle_mul.restype = None
+            lib.sig_oracle_mul.argtypes = [dp, dp, i32, i32, dp]
+            lib.sig_oracle_forward_f64.restype = i32
+            lib.sig_oracle_forward_f64.argtypes = [dp, i64, i64, i32, i32, i32, i32, dp, i32]
+            lib.sig_oracle_max_threads.restype = i32
+            lib.sig_oracle_max_threads.argtypes = []
+            _lib = lib
+    return _lib
+
+
+def _dptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def channels(d: int, N: int) -> int:
+    """sum_{k=1..N} d^k, the number of scalars in a depth-N signature (section 2.4)."""
+    return int(_load().sig_oracle_channels(d, N))
+
+
+def max_threads() -> int:
+    return int(_load().sig_oracle_max_threads())
+
+
+def level_slices(d: int, N: int):
+    """Slices of levels 1..N inside a flat signature vector."""
+    out, off = [], 0
+    for k in range(1, N + 1):
+        out.append(slice(off, off + d ** k))
+        off += d ** k
+    return out
+
+
+def tensor_exp(z, N: int) -> np.ndarray:
+    """exp(z) = (z, z^{(x)2}/2!, ..., z^{(x)N}/N!) as a flat vector (section 2.2)."""
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    d = z.shape[0]
+    E = np.empty(channels(d, N), dtype=np.float64)
+    _load().sig_oracle_exp(_dptr(z), d, N, _dptr(E))
+    return E
+
+
+def group_mul(A, B, d: int, N: int) -> np.ndarray:
+    """A [x] B of two flat depth-N elements (section 2.2)."""
+    A = np.ascontiguousarray(A, dtype=np.float64)
+    B = np.ascontiguousarray(B, dtype=np.float64)
+    S = channels(d, N)
+    assert A.shape == (S,) and B.shape == (S,)
+    C = np.empty(S, dtype=np.float64)
+    _load().sig_oracle_mul(_dptr(A), _dptr(B), d, N, _dptr(C))
+    return C
+
+
+def signature(path, N: int, stream: bool = False, basepoint: bool = False,
+              num_threads: int = 0) -> np.ndarray:
+    """fp64 signatures of a batch of paths.
+
+    path: array `[B, L, d]` (any float dtype; widened exactly to float64).
+    Returns `[B, S]`, or `[B, n_inc, S]` in stream mode (entry j = signature after the
+    (j+1)-th increment), S = channels(d, N), n_inc = L - 1 (L with basepoint).
+    """
+    x = np.ascontiguousarray(path, dtype=np.float64)
+    if x.ndim != 3:
+        raise ValueError("path must have shape [B, L, d]")
+    B, L, d = x.shape
+    S = channels(d, N)
+    if S < 0:
+        raise ValueError("bad d or N")
+    n_inc = L if basepoint else L - 1
+    if n_inc < 1:
+        raise ValueError("a path needs at least two points (one with basepoint)")
+    shape = (B, n_inc, S) if stream else (B, S)
+    out = np.empty(shape, dtype=np.float64)
+    rc = _load().sig_oracle_forward_f64(_dptr(x), B, L, d, N, int(stream), int(basepoint),
+                                        _dptr(out), int(num_threads))
+    if rc != 0:
+        raise RuntimeError(f"sig_oracle_forward_f64 failed with code {rc}")
+    return out
