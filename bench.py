@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark of the signature hot path on one MI355X.
+
+A step is one `sig_forward` call over one batch of synthetic paths (increments are
+differenced, folded in with the fused multiply-exponentiate and the result stored, all
+inside the library).  Inputs and outputs are resident in HBM before the timed region.
+Prints ONE JSON line: paths/s, the roofline of the dominant kernel measured live with
+HIP events, and the CPU oracle timed on the host cores beside it.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# Published MI355X peaks used for the roofline fractions.
+PEAK_FP32_TFLOPS = 157.3   # fp32 matrix-core peak = fp32 vector peak (packed) = 256 CU x 256 flop/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+
+
+def flops_per_increment(d: int, N: int, fused_fmas: int) -> int:
+    """Algorithmic work of one fused multiply-exponentiate: M(d,N) multiply-adds plus the
+    d(N-1) scalings z/2..z/N and the dN additions of eq. "fusedterm"."""
+    return 2 * fused_fmas + d * (2 * N - 1)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=2, help="configuration number 1..5 (default: the metric's)")
+    ap.add_argument("--variant", choices=["auto", "generic", "mfma"], default="auto")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 "
+              "(paths are independent, so more GPUs would simply split the batch)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2001_00706_amd as sig
+    from paper_2001_00706_amd.inputs import workload, workload_paths
+
+    if not os.path.exists(sig.binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+
+    w = workload(args.workload)
+    variant = {"auto": sig.SIG_VARIANT_AUTO, "generic": sig.SIG_VARIANT_GENERIC, "mfma": sig.SIG_VARIANT_MFMA}[args.variant]
+    x_host = workload_paths(w)
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(x_host).to(dev)
+    S = sig.sig_signature_channels(w.d, w.N)
+    out_shape = (w.B, w.n_inc, S) if w.stream else (w.B, S)
+    out = torch.empty(out_shape, dtype=torch.float32, device=dev)
+    kernel = sig.sig_variant_name(w.B, w.L, w.d, w.N, w.stream, w.basepoint, sig.SIG_F32, variant)
+
+    def step():
+        sig.sig_forward(x, w.N, stream=w.stream, basepoint=w.basepoint, out=out, variant=variant)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # whole-job timing: K steps between two device synchronisations
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # kernel duration: one HIP event pair per launch, on the stream the kernel runs on
+    # (sig_forward enqueues on torch's current stream, which is what these events see)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+             for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    for a, b in pairs:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    durs_ms = np.array([a.elapsed_time(b) for a, b in pairs])
+    kern_ms = float(durs_ms.mean())
+
+    M = sig.sig_fused_fmas(w.d, w.N)
+    flops = w.B * w.n_inc * flops_per_increment(w.d, w.N, M)
+    bytes_io = 4 * (w.B * w.L * w.d + int(np.prod(out_shape)))
+    if w.stream:
+        roofline = {"bound": "hbm", "achieved": bytes_io / (kern_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s"}
+    else:
+        bound = "mfma" if kernel.startswith("mfma") else "alu"
+        roofline = {"bound": bound, "achieved": flops / (kern_ms * 1e-3) / 1e12, "peak": PEAK_FP32_TFLOPS,
+                    "unit": "TFLOP/s"}
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    roofline["traffic"] = None
+    roofline["kernel"] = kernel
+    roofline["kernel_ms_avg"] = kern_ms
+    roofline["kernel_ms_min"] = float(durs_ms.min())
+    roofline["algorithmic_flops_per_launch"] = flops
+    roofline["algorithmic_bytes_per_launch"] = bytes_io
+
+    result = {
+        "metric": "signatures/sec (paths/s)",
+        "value": w.B / (ms_per_step * 1e-3),
+        "unit": "paths/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "L": w.L, "d": w.d, "N": w.N,
+                   "mode": "stream" if w.stream else "final", "kernel": kernel,
+                   "device": torch.cuda.get_device_name(0)},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import sig_oracle
+        # bounded sample: whole paths of the same workload, sized for roughly 1-3 s per pass
+        per_path_cost = w.n_inc * (w.N - 1) * w.d ** w.N
+        n_sample = int(max(1, min(w.B, 4e9 // max(per_path_cost, 1))))
+        xs = x_host[:n_sample]
+        best = float("inf")
+        for _ in range(3):
+            t = time.perf_counter()
+            sig_oracle.signature(xs, w.N, stream=w.stream, basepoint=w.basepoint)
+            best = min(best, time.perf_counter() - t)
+        result["cpu_baseline"] = {
+            "value": n_sample / best,
+            "unit": "paths/s",
+            "cores": sig_oracle.max_threads(),
+            "kind": "oracle",
+            "sample": f"first {n_sample} of {w.B} paths of {w.name}, fp64 exp + group product per increment, "
+                      f"OpenMP over paths, best of 3 passes ({best:.3f} s)",
+        }
+
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,113 @@
+/*
+ * libsig — truncated signature transform of batched piecewise-linear paths on one
+ * AMD MI355X (gfx950).  C ABI: plain pointers and sizes, no C++ or framework types.
+ *
+ * The transform (paper, section 2.1 definitions 2 and 4, and section 2.2): a sequence
+ * x_1..x_L in R^d is read as the continuous piecewise-affine path through its points, and
+ *     Sig^N(x) = exp(x_2 - x_1) [x] exp(x_3 - x_2) [x] ... [x] exp(x_L - x_{L-1}),
+ * an element of prod_{k=1..N} (R^d)^{(x)k}.  The library folds the increments in one at a
+ * time with the fused multiply-exponentiate A <- A [x] exp(z) of section 4.1 (appendix
+ * A.1.2, eq. "fusedterm"), levels updated highest first so the update is in place.
+ *
+ * Layout of one signature: S = sum_{k=1..N} d^k scalars (section 2.4); levels k = 1..N
+ * concatenated (the constant k = 0 term is omitted, footnote of section 2.1); inside level
+ * k the coefficient of e_{i_1} (x) ... (x) e_{i_k} is at row-major offset
+ * sum_m i_m d^{k-m} (0-based letters, first letter slowest) — lexicographic word order
+ * under the identification of appendix A.2.2.
+ *
+ * All functions are thread-safe and keep no state between calls.  Nothing here allocates
+ * or frees device memory, and nothing synchronises the device.
+ */
+#ifndef SIG_H_
+#define SIG_H_
+
+#include <stdint.h>
+#include <hip/hip_runtime_api.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SIG_OK = 0,
+    SIG_ERR_INVALID_ARG = 1,  /* null pointer, negative size, d < 1, N < 1, too few points, bad enum */
+    SIG_ERR_UNSUPPORTED = 2,  /* valid request that no kernel variant can serve */
+    SIG_ERR_OVERFLOW = 3,     /* a size does not fit the library's 64-bit index budget */
+    SIG_ERR_HIP = 4           /* the HIP runtime refused the launch */
+} sig_status;
+
+typedef enum {
+    SIG_F32 = 0,  /* path and out are float; arithmetic in fp32 */
+    SIG_F64 = 1   /* path and out are double; arithmetic in fp64 */
+} sig_dtype;
+
+/* Which kernel family serves a call.  SIG_VARIANT_AUTO picks the fastest one that
+ * supports the shape; the others force one family (SIG_ERR_UNSUPPORTED if it cannot
+ * serve the shape) and exist so that every family can be tested on every shape. */
+typedef enum {
+    SIG_VARIANT_AUTO = 0,
+    SIG_VARIANT_GENERIC = 1,  /* any d, N, dtype: one workgroup per path, state in LDS or in `out` */
+    SIG_VARIANT_MFMA = 2      /* fp32, d in {4, 8, 16}: state in registers, outer products on the matrix cores */
+} sig_variant;
+
+/* Largest depth the kernels accept. */
+#define SIG_MAX_DEPTH 32
+
+/* Number of scalars in one depth-N signature over R^d: S(d, N) = sum_{k=1..N} d^k
+ * (section 2.4).  Returns -1 if d < 1, N < 1, N > SIG_MAX_DEPTH or S exceeds 2^40. */
+int64_t sig_signature_channels(int d, int N);
+
+/* Number of scalars `sig_forward` writes: B*S (stream == 0) or B*n_inc*S (stream != 0),
+ * n_inc = L - 1, or L with basepoint.  Returns -1 on invalid arguments (as sig_forward)
+ * or if the count exceeds 2^60. */
+int64_t sig_output_elems(int64_t B, int64_t L, int d, int N, int stream, int basepoint);
+
+/* Multiply-adds in one fused multiply-exponentiate, M(d, N) = sum_{i=2..N} (N-i+1) d^i:
+ * eq. "fusedterm" spends d^2 + ... + d^k of them on level k (appendix A.1.2).  The paper's
+ * multiplication count is F(d, N) = M(d, N) + d(N-1) (eq. "fusedresult").  -1 on bad args. */
+int64_t sig_fused_fmas(int d, int N);
+
+/* Batched forward signature.
+ *
+ *   path       DEVICE pointer, [B][L][d] contiguous row-major, element type `dtype`; read only.
+ *   B, L, d, N batch, points per path, channels, depth.
+ *   stream     0: out is [B][S], the signature of each whole path.
+ *              1: out is [B][n_inc][S]; entry j is the signature of the first j+2 points
+ *                 (first j+1 points after the basepoint, if basepoint != 0): the expanding
+ *                 intervals of section 5.5, all by-products of the same scan (eq. "iterative").
+ *   basepoint  0: n_inc = L - 1 increments x_{l+1} - x_l.
+ *              1: the origin of R^d is prepended as an extra first point, n_inc = L
+ *                 (this library's reading of the `basepoint` argument of section 5.5).
+ *   dtype      SIG_F32 or SIG_F64.
+ *   out        DEVICE pointer, caller-allocated, sig_output_elems(...) elements of `dtype`,
+ *              fully overwritten; must not overlap `path`.
+ *   hip_stream the work is enqueued on this stream; the call returns without waiting.
+ *
+ * The caller owns both buffers and must keep them alive until the stream has passed the
+ * enqueued work.  Returns SIG_OK, or an error code with nothing enqueued and `out`
+ * untouched: SIG_ERR_INVALID_ARG for null pointers (with B > 0), B < 0, d < 1, N < 1 or
+ * N > SIG_MAX_DEPTH, L < 2 (L < 1 with basepoint), an unknown dtype; SIG_ERR_OVERFLOW if a
+ * size overflows; SIG_ERR_HIP if the launch failed.  B == 0 is SIG_OK and enqueues nothing.
+ * Results are deterministic: the same inputs give bit-identical outputs on every call. */
+sig_status sig_forward(const void *path, int64_t B, int64_t L, int d, int N,
+                       int stream, int basepoint, sig_dtype dtype,
+                       void *out, hipStream_t hip_stream);
+
+/* As sig_forward, with the kernel family chosen by the caller (see sig_variant). */
+sig_status sig_forward_variant(const void *path, int64_t B, int64_t L, int d, int N,
+                               int stream, int basepoint, sig_dtype dtype,
+                               void *out, hipStream_t hip_stream, sig_variant variant);
+
+/* Name of the kernel family that `variant` resolves to for this shape ("generic",
+ * "mfma_d4", ...), or "unsupported" / "invalid".  The string is static. */
+const char *sig_variant_name(int64_t B, int64_t L, int d, int N, int stream, int basepoint,
+                             sig_dtype dtype, sig_variant variant);
+
+/* Static English text for a status code. */
+const char *sig_status_string(sig_status status);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* SIG_H_ */

@@ -1,0 +1,27 @@
+"""Truncated signature transform of batched piecewise-linear paths on AMD MI355X.
+
+`sig_forward` and the size helpers below are thin bindings of the C ABI in
+`include/sig.h`; the shared library is loaded on first use.
+"""
+from .binding import (  # noqa: F401
+    SIG_F32,
+    SIG_F64,
+    SIG_MAX_DEPTH,
+    SIG_OK,
+    SIG_ERR_HIP,
+    SIG_ERR_INVALID_ARG,
+    SIG_ERR_OVERFLOW,
+    SIG_ERR_UNSUPPORTED,
+    SIG_VARIANT_AUTO,
+    SIG_VARIANT_GENERIC,
+    SIG_VARIANT_MFMA,
+    SigError,
+    load_library,
+    sig_forward,
+    sig_forward_raw,
+    sig_fused_fmas,
+    sig_output_elems,
+    sig_signature_channels,
+    sig_status_string,
+    sig_variant_name,
+)

@@ -1,0 +1,146 @@
+"""Thin ctypes binding of `libsig.so` (the C ABI declared in `include/sig.h`).
+
+Argument marshalling only: every step of the signature computation runs in the HIP
+kernels.  PyTorch is used for device memory and for the current HIP stream, nothing else.
+There is no CPU fallback: if the library is missing or the tensor is not on a GPU the
+call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import threading
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG_DIR, "libsig.so")
+
+SIG_OK, SIG_ERR_INVALID_ARG, SIG_ERR_UNSUPPORTED, SIG_ERR_OVERFLOW, SIG_ERR_HIP = range(5)
+SIG_F32, SIG_F64 = 0, 1
+SIG_VARIANT_AUTO, SIG_VARIANT_GENERIC, SIG_VARIANT_MFMA = 0, 1, 2
+SIG_MAX_DEPTH = 32
+
+# every symbol include/sig.h declares
+EXPORTED_SYMBOLS = (
+    "sig_signature_channels",
+    "sig_output_elems",
+    "sig_fused_fmas",
+    "sig_forward",
+    "sig_forward_variant",
+    "sig_variant_name",
+    "sig_status_string",
+)
+
+_lock = threading.Lock()
+_lib = None
+
+
+class SigError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"libsig: {text} (status {status})")
+        self.status = status
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads `libsig.so`; raises if it has not been built (`__graft_entry__.build()`)."""
+    global _lib
+    with _lock:
+        if _lib is not None:
+            return _lib
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+        lib = ctypes.CDLL(LIB_PATH)
+        i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+        lib.sig_signature_channels.restype = i64
+        lib.sig_signature_channels.argtypes = [i32, i32]
+        lib.sig_output_elems.restype = i64
+        lib.sig_output_elems.argtypes = [i64, i64, i32, i32, i32, i32]
+        lib.sig_fused_fmas.restype = i64
+        lib.sig_fused_fmas.argtypes = [i32, i32]
+        lib.sig_forward.restype = i32
+        lib.sig_forward.argtypes = [vp, i64, i64, i32, i32, i32, i32, i32, vp, vp]
+        lib.sig_forward_variant.restype = i32
+        lib.sig_forward_variant.argtypes = [vp, i64, i64, i32, i32, i32, i32, i32, vp, vp, i32]
+        lib.sig_variant_name.restype = ctypes.c_char_p
+        lib.sig_variant_name.argtypes = [i64, i64, i32, i32, i32, i32, i32, i32]
+        lib.sig_status_string.restype = ctypes.c_char_p
+        lib.sig_status_string.argtypes = [i32]
+        _lib = lib
+        return lib
+
+
+def sig_status_string(status: int) -> str:
+    return load_library().sig_status_string(int(status)).decode()
+
+
+def sig_signature_channels(d: int, N: int) -> int:
+    return int(load_library().sig_signature_channels(d, N))
+
+
+def sig_output_elems(B: int, L: int, d: int, N: int, stream: bool, basepoint: bool) -> int:
+    return int(load_library().sig_output_elems(B, L, d, N, int(stream), int(basepoint)))
+
+
+def sig_fused_fmas(d: int, N: int) -> int:
+    return int(load_library().sig_fused_fmas(d, N))
+
+
+def sig_variant_name(B: int, L: int, d: int, N: int, stream: bool, basepoint: bool,
+                     dtype: int = SIG_F32, variant: int = SIG_VARIANT_AUTO) -> str:
+    return load_library().sig_variant_name(B, L, d, N, int(stream), int(basepoint), dtype, variant).decode()
+
+
+def sig_forward_raw(path_ptr: int, B: int, L: int, d: int, N: int, stream: int, basepoint: int,
+                    dtype: int, out_ptr: int, hip_stream: int, variant: int = SIG_VARIANT_AUTO) -> int:
+    """The C call itself, on raw device addresses; returns the status code."""
+    lib = load_library()
+    if variant == SIG_VARIANT_AUTO:
+        return int(lib.sig_forward(path_ptr, B, L, d, N, stream, basepoint, dtype, out_ptr, hip_stream))
+    return int(lib.sig_forward_variant(path_ptr, B, L, d, N, stream, basepoint, dtype, out_ptr,
+                                       hip_stream, variant))
+
+
+def sig_forward(path, N: int, stream: bool = False, basepoint: bool = False, out=None,
+                variant: int = SIG_VARIANT_AUTO):
+    """Signatures of a batch of paths held in a CUDA/HIP torch tensor.
+
+    path: `[B, L, d]` contiguous float32 or float64 tensor on the GPU.
+    Returns (and, if `out` is given, fills) a tensor `[B, S]`, or `[B, n_inc, S]` in stream
+    mode.  The work is enqueued on torch's current stream and not waited for.
+    """
+    import torch
+
+    if not isinstance(path, torch.Tensor) or not path.is_cuda:
+        raise TypeError("sig_forward needs a torch tensor on the GPU (there is no CPU path)")
+    if path.dim() != 3:
+        raise ValueError("path must have shape [B, L, d]")
+    if path.dtype == torch.float32:
+        dtype = SIG_F32
+    elif path.dtype == torch.float64:
+        dtype = SIG_F64
+    else:
+        raise TypeError("path must be float32 or float64")
+    if not path.is_contiguous():
+        raise ValueError("path must be contiguous")
+    B, L, d = path.shape
+    n_elems = sig_output_elems(B, L, d, N, stream, basepoint)
+    if n_elems < 0:
+        # let the library name the reason
+        status = sig_forward_raw(path.data_ptr(), B, L, d, N, int(stream), int(basepoint), dtype, 0, 0, variant)
+        raise SigError(status, sig_status_string(status))
+    S = sig_signature_channels(d, N)
+    n_inc = L if basepoint else L - 1
+    shape = (B, n_inc, S) if stream else (B, S)
+    if out is None:
+        out = torch.empty(shape, dtype=path.dtype, device=path.device)
+    else:
+        if out.dtype != path.dtype or out.device != path.device or tuple(out.shape) != shape \
+                or not out.is_contiguous():
+            raise ValueError(f"out must be a contiguous {path.dtype} tensor of shape {shape} on {path.device}")
+    with torch.cuda.device(path.device):
+        hip_stream = torch.cuda.current_stream().cuda_stream
+        status = sig_forward_raw(path.data_ptr(), B, L, d, N, int(stream), int(basepoint), dtype,
+                                 out.data_ptr(), hip_stream, variant)
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return out

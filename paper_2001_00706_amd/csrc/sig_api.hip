@@ -1,0 +1,162 @@
+// C ABI of libsig: argument validation, size helpers and kernel-family dispatch.
+// The operations are those declared in sig.h; nothing here touches device memory.
+#include "sig_internal.h"
+
+namespace {
+
+constexpr int64_t kMaxChannels = int64_t(1) << 40;
+constexpr int64_t kMaxElems = int64_t(1) << 60;
+
+// Fills pw/off/S; false if d, N are invalid or S exceeds kMaxChannels.
+bool fill_levels(int d, int N, sig::Shape &sh)
+{
+    if (d < 1 || N < 1 || N > SIG_MAX_DEPTH) return false;
+    sh.d = d;
+    sh.N = N;
+    sh.pw[0] = 1;
+    sh.off[1] = 0;
+    int64_t total = 0;
+    for (int k = 1; k <= N; ++k) {
+        if (sh.pw[k - 1] > kMaxChannels / d) return false;
+        sh.pw[k] = sh.pw[k - 1] * d;
+        total += sh.pw[k];
+        if (total > kMaxChannels) return false;
+        sh.off[k + 1] = total;
+    }
+    sh.off[0] = 0;
+    sh.S = total;
+    return true;
+}
+
+// Validates a whole call.  On SIG_OK `sh` is complete.
+sig_status make_shape(int64_t B, int64_t L, int d, int N, int stream, int basepoint, sig::Shape &sh)
+{
+    if (B < 0 || d < 1 || N < 1 || N > SIG_MAX_DEPTH) return SIG_ERR_INVALID_ARG;
+    if (basepoint ? (L < 1) : (L < 2)) return SIG_ERR_INVALID_ARG;
+    if (!fill_levels(d, N, sh)) return SIG_ERR_OVERFLOW;
+    sh.B = B;
+    sh.L = L;
+    sh.stream = stream ? 1 : 0;
+    sh.basepoint = basepoint ? 1 : 0;
+    sh.n_inc = basepoint ? L : L - 1;
+    // path elements B*L*d and output elements B*[n_inc*]S must stay below kMaxElems
+    if (L > kMaxElems / d) return SIG_ERR_OVERFLOW;
+    const int64_t per_path_in = L * d;
+    if (B > 0 && per_path_in > kMaxElems / B) return SIG_ERR_OVERFLOW;
+    int64_t per_path_out = sh.S;
+    if (sh.stream) {
+        if (sh.n_inc > kMaxElems / sh.S) return SIG_ERR_OVERFLOW;
+        per_path_out = sh.n_inc * sh.S;
+    }
+    if (B > 0 && per_path_out > kMaxElems / B) return SIG_ERR_OVERFLOW;
+    return SIG_OK;
+}
+
+enum class Family { Generic, Mfma, None };
+
+Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant)
+{
+    const bool mfma_ok = dtype == SIG_F32 && sig::mfma_kernel_name(sh) != nullptr;
+    const bool generic_ok = sig::generic_supported(sh, dtype);
+    switch (variant) {
+        case SIG_VARIANT_AUTO:
+            if (mfma_ok) return Family::Mfma;
+            return generic_ok ? Family::Generic : Family::None;
+        case SIG_VARIANT_GENERIC: return generic_ok ? Family::Generic : Family::None;
+        case SIG_VARIANT_MFMA: return mfma_ok ? Family::Mfma : Family::None;
+    }
+    return Family::None;
+}
+
+bool valid_enums(sig_dtype dtype, sig_variant variant)
+{
+    return (dtype == SIG_F32 || dtype == SIG_F64) &&
+           (variant == SIG_VARIANT_AUTO || variant == SIG_VARIANT_GENERIC || variant == SIG_VARIANT_MFMA);
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t sig_signature_channels(int d, int N)
+{
+    sig::Shape sh;
+    return fill_levels(d, N, sh) ? sh.S : -1;
+}
+
+int64_t sig_output_elems(int64_t B, int64_t L, int d, int N, int stream, int basepoint)
+{
+    sig::Shape sh;
+    if (make_shape(B, L, d, N, stream, basepoint, sh) != SIG_OK) return -1;
+    return B * (sh.stream ? sh.n_inc * sh.S : sh.S);
+}
+
+int64_t sig_fused_fmas(int d, int N)
+{
+    sig::Shape sh;
+    if (!fill_levels(d, N, sh)) return -1;
+    int64_t m = 0;
+    for (int i = 2; i <= N; ++i) m += int64_t(N - i + 1) * sh.pw[i];
+    return m;
+}
+
+sig_status sig_forward_variant(const void *path, int64_t B, int64_t L, int d, int N,
+                               int stream, int basepoint, sig_dtype dtype,
+                               void *out, hipStream_t hip_stream, sig_variant variant)
+{
+    if (!valid_enums(dtype, variant)) return SIG_ERR_INVALID_ARG;
+    sig::Shape sh;
+    const sig_status st = make_shape(B, L, d, N, stream, basepoint, sh);
+    if (st != SIG_OK) return st;
+    if (B == 0) return SIG_OK;
+    if (path == nullptr || out == nullptr) return SIG_ERR_INVALID_ARG;
+    hipError_t err = hipSuccess;
+    switch (resolve(sh, dtype, variant)) {
+        case Family::Mfma:
+            err = sig::launch_mfma_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
+            break;
+        case Family::Generic:
+            err = dtype == SIG_F32
+                      ? sig::launch_generic_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
+                      : sig::launch_generic_f64(sh, static_cast<const double *>(path), static_cast<double *>(out), hip_stream);
+            break;
+        case Family::None:
+            return SIG_ERR_UNSUPPORTED;
+    }
+    return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
+sig_status sig_forward(const void *path, int64_t B, int64_t L, int d, int N,
+                       int stream, int basepoint, sig_dtype dtype,
+                       void *out, hipStream_t hip_stream)
+{
+    return sig_forward_variant(path, B, L, d, N, stream, basepoint, dtype, out, hip_stream, SIG_VARIANT_AUTO);
+}
+
+const char *sig_variant_name(int64_t B, int64_t L, int d, int N, int stream, int basepoint,
+                             sig_dtype dtype, sig_variant variant)
+{
+    if (!valid_enums(dtype, variant)) return "invalid";
+    sig::Shape sh;
+    if (make_shape(B, L, d, N, stream, basepoint, sh) != SIG_OK) return "invalid";
+    switch (resolve(sh, dtype, variant)) {
+        case Family::Mfma: return sig::mfma_kernel_name(sh);
+        case Family::Generic: return "generic";
+        case Family::None: break;
+    }
+    return "unsupported";
+}
+
+const char *sig_status_string(sig_status status)
+{
+    switch (status) {
+        case SIG_OK: return "ok";
+        case SIG_ERR_INVALID_ARG: return "invalid argument";
+        case SIG_ERR_UNSUPPORTED: return "no kernel variant supports this request";
+        case SIG_ERR_OVERFLOW: return "size overflow";
+        case SIG_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

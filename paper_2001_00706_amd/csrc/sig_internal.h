@@ -1,0 +1,36 @@
+// Internal declarations shared by the translation units of libsig (not part of the C ABI).
+#ifndef SIG_INTERNAL_H_
+#define SIG_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sig.h"
+
+namespace sig {
+
+// A validated call: sizes, level sizes d^k and level offsets, passed by value to kernels.
+struct Shape {
+    int64_t B;       // paths
+    int64_t L;       // points per path
+    int64_t S;       // scalars per signature, sum_{k=1..N} d^k
+    int64_t n_inc;   // increments folded in: L - 1, or L with basepoint
+    int d, N;
+    int stream, basepoint;
+    int64_t pw[SIG_MAX_DEPTH + 1];   // pw[k] = d^k, k = 0..N
+    int64_t off[SIG_MAX_DEPTH + 2];  // off[k] = offset of level k (1-based) in a signature; off[N+1] = S
+};
+
+// Generic family: any d, N; one workgroup per path.  `generic_supported` is false only when
+// the per-step scalings z/1..z/N (N*d scalars) do not fit the workgroup's LDS.
+bool generic_supported(const Shape &sh, sig_dtype dtype);
+hipError_t launch_generic_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
+hipError_t launch_generic_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
+
+// Matrix-core family (fp32 only).  `mfma_kernel_name` returns nullptr for shapes it cannot serve.
+const char *mfma_kernel_name(const Shape &sh);
+hipError_t launch_mfma_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
+
+}  // namespace sig
+
+#endif  // SIG_INTERNAL_H_

@@ -1,0 +1,135 @@
+"""Host-side checks of the C ABI: exported symbols, size helpers, argument validation.
+
+None of these launches a kernel, so they run without a GPU.
+"""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2001_00706_amd as sig
+from paper_2001_00706_amd import binding
+from paper_2001_00706_amd.inputs import WORKLOADS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2001_00706_amd.build import build_lib
+        build_lib()
+    return sig.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "sig.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sig_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    declared = _declared_functions()
+    assert declared == sorted(binding.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_channels(lib):
+    assert sig.sig_signature_channels(2, 4) == 30
+    assert sig.sig_signature_channels(4, 6) == 5460
+    assert sig.sig_signature_channels(16, 4) == 69904
+    assert sig.sig_signature_channels(1, 32) == 32
+    assert sig.sig_signature_channels(0, 3) == -1
+    assert sig.sig_signature_channels(3, 0) == -1
+    assert sig.sig_signature_channels(1, 33) == -1
+    assert sig.sig_signature_channels(2, 32) == 2 ** 33 - 2
+    assert sig.sig_signature_channels(1024, 5) == -1          # beyond 2^40
+    for w in WORKLOADS:
+        assert sig.sig_signature_channels(w.d, w.N) == w.channels
+
+
+def test_output_elems(lib):
+    assert sig.sig_output_elems(32, 16, 2, 4, False, False) == 32 * 30
+    # stream mode: one entry per increment (section 5.5: prefixes of length 2..L)
+    assert sig.sig_output_elems(128, 256, 4, 5, True, False) == 128 * 255 * 1364
+    assert sig.sig_output_elems(128, 256, 4, 5, True, True) == 128 * 256 * 1364
+    assert sig.sig_output_elems(0, 2, 3, 3, False, False) == 0
+    assert sig.sig_output_elems(4, 1, 3, 3, False, False) == -1   # a single point is no path
+    assert sig.sig_output_elems(4, 1, 3, 3, False, True) == 4 * 39
+    assert sig.sig_output_elems(-1, 4, 3, 3, False, False) == -1
+    assert sig.sig_output_elems(2 ** 40, 2 ** 30, 2, 20, True, False) == -1
+
+
+def _F_closed_form(d, N):
+    # appendix A.1.3, closed form of F(d, N) for d >= 2
+    return (d ** (N + 2) - d ** 3 - (N - 1) * d ** 2 + (N - 1) * d) // ((d - 1) ** 2)
+
+
+@pytest.mark.parametrize("d,N", [(2, 4), (4, 6), (8, 5), (4, 5), (16, 4), (3, 3), (7, 7), (2, 1)])
+def test_fused_fma_count_matches_the_papers_multiplication_count(lib, d, N):
+    # appendix A.1.2: F(d, N) = d(N-1) + sum_{k=1..N} sum_{i=2..k} d^i; M = F - d(N-1)
+    M = sig.sig_fused_fmas(d, N)
+    assert M == sum(sum(d ** i for i in range(2, k + 1)) for k in range(1, N + 1))
+    assert M + d * (N - 1) == _F_closed_form(d, N)
+
+
+def test_fused_fma_count_of_the_benchmark_shapes(lib):
+    got = [sig.sig_fused_fmas(w.d, w.N) for w in WORKLOADS]
+    assert got == [44, 7248, 42752, 1792, 74496]
+
+
+def test_status_strings(lib):
+    texts = [sig.sig_status_string(s) for s in range(5)]
+    assert texts[0] == "ok" and len(set(texts)) == 5
+    assert sig.sig_status_string(99) == "unknown status"
+
+
+def test_validation_happens_before_any_device_work(lib):
+    raw = sig.sig_forward_raw
+    dummy = 0x1000  # never dereferenced: every call below fails validation or has B == 0
+    assert raw(dummy, -1, 4, 2, 2, 0, 0, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_INVALID_ARG
+    assert raw(dummy, 2, 1, 2, 2, 0, 0, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_INVALID_ARG
+    assert raw(dummy, 2, 0, 2, 2, 0, 1, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_INVALID_ARG
+    assert raw(dummy, 2, 4, 0, 2, 0, 0, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_INVALID_ARG
+    assert raw(dummy, 2, 4, 2, 0, 0, 0, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_INVALID_ARG
+    assert raw(dummy, 2, 4, 2, 33, 0, 0, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_INVALID_ARG
+    assert raw(dummy, 2, 4, 2, 2, 0, 0, 7, dummy, 0) == sig.SIG_ERR_INVALID_ARG
+    assert raw(0, 2, 4, 2, 2, 0, 0, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_INVALID_ARG
+    assert raw(dummy, 2, 4, 2, 2, 0, 0, sig.SIG_F32, 0, 0) == sig.SIG_ERR_INVALID_ARG
+    assert raw(dummy, 2, 4, 1024, 5, 0, 0, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_OVERFLOW
+    assert raw(dummy, 2 ** 40, 2 ** 30, 2, 20, 1, 0, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_OVERFLOW
+    assert raw(dummy, 2, 4, 2, 2, 0, 0, sig.SIG_F32, dummy, 0, variant=9) == sig.SIG_ERR_INVALID_ARG
+    # the matrix-core family is fp32 only
+    assert raw(dummy, 2, 4, 4, 3, 0, 0, sig.SIG_F64, dummy, 0, variant=sig.SIG_VARIANT_MFMA) \
+        == sig.SIG_ERR_UNSUPPORTED
+    # an empty batch is fine and enqueues nothing, even with null pointers
+    assert raw(0, 0, 4, 2, 2, 0, 0, sig.SIG_F32, 0, 0) == sig.SIG_OK
+
+
+def test_variant_names(lib):
+    assert sig.sig_variant_name(32, 16, 2, 4, False, False, variant=sig.SIG_VARIANT_GENERIC) == "generic"
+    assert sig.sig_variant_name(32, 1, 2, 4, False, False) == "invalid"
+    assert sig.sig_variant_name(32, 16, 3, 4, False, False, variant=sig.SIG_VARIANT_MFMA) == "unsupported"
+
+
+def test_python_binding_refuses_cpu_tensors(lib):
+    import torch
+    with pytest.raises(TypeError):
+        sig.sig_forward(torch.zeros(2, 3, 2), 2)
+    with pytest.raises(TypeError):
+        sig.sig_forward([[0.0, 1.0]], 2)
+
+
+def test_product_package_does_not_touch_the_oracle():
+    pkg_dir = os.path.join(ROOT, "paper_2001_00706_amd")
+    for dirpath, _, files in os.walk(pkg_dir):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "sig_oracle" not in text and "import oracle" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c", ".h")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2001_00706_amd" not in text and "libsig.so" not in text, f

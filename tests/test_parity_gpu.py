@@ -1,0 +1,199 @@
+"""Parity of the HIP path with the fp64 CPU oracle, element by element, through the C ABI.
+
+Error measure (per level k): e_k = ||G_k - O_k||_2 / ||O_k||_2 with the norm taken over
+all paths and stream positions of that level.  Bars: fp32 e_k <= 1e-4, fp64 e_k <= 1e-10.
+"""
+import numpy as np
+import pytest
+
+import paper_2001_00706_amd as sig
+from oracle import sig_oracle as orc
+from paper_2001_00706_amd.inputs import WORKLOADS, brownian_paths, uniform_paths, workload_paths
+
+pytestmark = pytest.mark.gpu
+
+TOL = {np.float32: 1e-4, np.float64: 1e-10}
+# worst single path may sit somewhat above the batch-wide figure
+TOL_SINGLE = {np.float32: 5e-4, np.float64: 5e-10}
+
+
+def torch_mod():
+    import torch
+    return torch
+
+
+def gpu_signature(x, N, stream=False, basepoint=False, variant=sig.SIG_VARIANT_AUTO, poison=True):
+    torch = torch_mod()
+    xt = torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
+    B, L, d = x.shape
+    S = sig.sig_signature_channels(d, N)
+    n_inc = L if basepoint else L - 1
+    shape = (B, n_inc, S) if stream else (B, S)
+    out = torch.full(shape, float("nan"), dtype=xt.dtype, device=xt.device) if poison else None
+    got = sig.sig_forward(xt, N, stream=stream, basepoint=basepoint, out=out, variant=variant)
+    torch.cuda.synchronize()
+    return got.cpu().numpy()
+
+
+def level_errors(got, want, d, N):
+    """Batch-wide and worst-single-path relative L2 error of every level."""
+    got = np.asarray(got, dtype=np.float64)
+    B = got.shape[0]
+    batch, single = [], []
+    for sl in orc.level_slices(d, N):
+        g, w = got[..., sl].reshape(B, -1), want[..., sl].reshape(B, -1)
+        den = np.linalg.norm(w)
+        batch.append(np.linalg.norm(g - w) / (den if den > 0 else 1.0))
+        dens = np.linalg.norm(w, axis=1)
+        dens[dens == 0] = 1.0
+        single.append(float(np.max(np.linalg.norm(g - w, axis=1) / dens)))
+    return np.array(batch), np.array(single)
+
+
+def check(x, N, stream=False, basepoint=False, variant=sig.SIG_VARIANT_AUTO, sample=None):
+    dt = x.dtype.type
+    got = gpu_signature(x, N, stream, basepoint, variant)
+    assert np.all(np.isfinite(got)), "output not fully written"
+    idx = np.arange(x.shape[0]) if sample is None else np.asarray(sample)
+    want = orc.signature(x[idx], N, stream=stream, basepoint=basepoint)
+    batch, single = level_errors(got[idx], want, x.shape[2], N)
+    assert np.all(batch <= TOL[dt]), f"per-level rel L2 {batch}"
+    assert np.all(single <= TOL_SINGLE[dt]), f"worst single-path rel L2 {single}"
+    return got
+
+
+VARIANTS = [sig.SIG_VARIANT_AUTO, sig.SIG_VARIANT_GENERIC]
+
+
+# ------------------------------------------------------------------ benchmark workloads
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("w", WORKLOADS, ids=lambda w: w.name)
+def test_benchmark_workloads_full_size(w, variant):
+    """Full-size launch, as bench.py times it; the oracle recomputes a seeded sample of
+    whole paths (every element of those paths is compared)."""
+    x = workload_paths(w)
+    rng = np.random.default_rng(w.seed)
+    n_sample = min(w.B, 24 if w.channels * w.L < 2_000_000 else 6)
+    sample = np.sort(rng.choice(w.B, size=n_sample, replace=False))
+    if n_sample < w.B:
+        sample = np.unique(np.concatenate([[0, w.B - 1], sample]))
+    check(x, w.N, stream=w.stream, basepoint=w.basepoint, variant=variant, sample=sample)
+
+
+@pytest.mark.parametrize("w", [WORKLOADS[0], WORKLOADS[3]], ids=lambda w: w.name)
+def test_small_workloads_every_path(w):
+    check(workload_paths(w), w.N, stream=w.stream, basepoint=w.basepoint)
+
+
+# ------------------------------------------------------------------------ shape sweep
+SWEEP = [
+    # (B, L, d, N)
+    (1, 2, 1, 1), (3, 2, 1, 5), (2, 5, 2, 1), (5, 3, 2, 2), (4, 17, 3, 4), (2, 9, 5, 3),
+    (3, 6, 7, 3), (2, 33, 2, 7), (1, 4, 6, 4), (7, 12, 4, 4), (2, 5, 9, 2), (3, 70, 3, 5),
+    (2, 11, 4, 6), (5, 19, 8, 3), (2, 7, 16, 3), (1, 3, 33, 2),
+]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("B,L,d,N", SWEEP)
+def test_shape_sweep(B, L, d, N, dtype, variant):
+    x = uniform_paths(B, L, d, seed=1000 + 7 * L + d, lo=-0.5, hi=0.5).astype(dtype)
+    for stream in (False, True):
+        for basepoint in (False, True):
+            check(x, N, stream=stream, basepoint=basepoint, variant=variant)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_state_too_large_for_lds(variant):
+    # d = 16, N = 4: 69904 scalars per path, several tiles of every level and ragged tails
+    x = brownian_paths(3, 9, 16, seed=77)
+    check(x, 4, variant=variant)
+    check(x.astype(np.float64), 4, variant=variant)
+    x = brownian_paths(2, 6, 11, seed=78)   # 11^4: not a multiple of the workgroup size
+    check(x, 4, variant=variant)
+    check(x, 4, stream=True, variant=variant)
+
+
+# -------------------------------------------------------------------------- edge cases
+def test_single_increment_with_and_without_basepoint():
+    x = uniform_paths(4, 2, 3, seed=5)
+    check(x, 4)
+    check(x[:, :1], 4, basepoint=True)
+    check(x[:, :1], 4, basepoint=True, stream=True)
+
+
+def test_zero_increments_leave_the_identity():
+    x = np.ones((3, 6, 4), dtype=np.float32) * 0.37
+    got = gpu_signature(x, 4)
+    assert np.all(got == 0.0)
+    got = gpu_signature(x, 4, stream=True)
+    assert np.all(got == 0.0)
+
+
+def test_repeated_points_do_not_change_the_result():
+    x = brownian_paths(3, 10, 3, seed=9)
+    y = np.repeat(x, 2, axis=1)
+    a, b = gpu_signature(x, 4), gpu_signature(y, 4)
+    np.testing.assert_array_equal(a, b)
+
+
+def test_empty_batch():
+    torch = torch_mod()
+    x = torch.zeros((0, 5, 3), dtype=torch.float32, device="cuda:0")
+    assert tuple(sig.sig_forward(x, 3).shape) == (0, 39)
+    assert tuple(sig.sig_forward(x, 3, stream=True).shape) == (0, 4, 39)
+
+
+def test_many_paths_more_than_one_grid_pass():
+    # more paths than the launch has workgroups: the grid-stride loop over paths
+    B = (1 << 20) + 37
+    x = uniform_paths(B, 2, 1, seed=3)
+    got = gpu_signature(x, 2, variant=sig.SIG_VARIANT_GENERIC)
+    dz = (x[:, 1, 0].astype(np.float64) - x[:, 0, 0])
+    np.testing.assert_allclose(got[:, 0], dz, rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(got[:, 1], dz * dz / 2, rtol=1e-5, atol=1e-7)
+
+
+def test_stream_last_entry_equals_final_result():
+    for w in (WORKLOADS[0], WORKLOADS[3]):
+        x = workload_paths(w)[:8]
+        fin = gpu_signature(x, w.N)
+        st = gpu_signature(x, w.N, stream=True)
+        np.testing.assert_allclose(st[:, -1], fin, rtol=2e-6, atol=1e-9)
+
+
+def test_runs_are_bit_identical():
+    for w in WORKLOADS[:4]:
+        x = workload_paths(w)[:16]
+        a = gpu_signature(x, w.N, stream=w.stream)
+        b = gpu_signature(x, w.N, stream=w.stream)
+        np.testing.assert_array_equal(a, b)
+
+
+def test_errors_leave_the_output_untouched():
+    torch = torch_mod()
+    x = torch.zeros((2, 1, 3), dtype=torch.float32, device="cuda:0")
+    out = torch.full((2, 39), 7.0, dtype=torch.float32, device="cuda:0")
+    st = sig.sig_forward_raw(x.data_ptr(), 2, 1, 3, 3, 0, 0, sig.SIG_F32, out.data_ptr(),
+                             torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert st == sig.SIG_ERR_INVALID_ARG
+    assert bool(torch.all(out == 7.0))
+    with pytest.raises(sig.SigError):
+        sig.sig_forward(x, 3)
+    with pytest.raises(sig.SigError):
+        sig.sig_forward(torch.zeros((2, 4, 3), device="cuda:0"), 3, variant=sig.SIG_VARIANT_MFMA)
+
+
+def test_work_is_enqueued_on_the_callers_stream():
+    torch = torch_mod()
+    w = WORKLOADS[0]
+    x = torch.from_numpy(workload_paths(w)).to("cuda:0")
+    ref = sig.sig_forward(x, w.N)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        got = sig.sig_forward(x, w.N)
+    side.synchronize()
+    assert torch.equal(ref, got)
