@@ -160,7 +160,12 @@ def test_stream_last_entry_equals_final_result():
         x = workload_paths(w)[:8]
         fin = gpu_signature(x, w.N)
         st = gpu_signature(x, w.N, stream=True)
-        np.testing.assert_allclose(st[:, -1], fin, rtol=2e-6, atol=1e-9)
+        # the two modes may be served by different kernels: equal up to fp32 rounding
+        batch, _ = level_errors(st[:, -1], fin.astype(np.float64), w.d, w.N)
+        assert np.all(batch <= 1e-5), batch
+        same = gpu_signature(x, w.N, variant=sig.SIG_VARIANT_GENERIC)
+        st_g = gpu_signature(x, w.N, stream=True, variant=sig.SIG_VARIANT_GENERIC)
+        np.testing.assert_array_equal(st_g[:, -1], same)   # same kernel, same arithmetic
 
 
 def test_runs_are_bit_identical():
