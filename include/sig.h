@@ -81,6 +81,8 @@ int64_t sig_fused_fmas(int d, int N);
  *   dtype      SIG_F32 or SIG_F64.
  *   out        DEVICE pointer, caller-allocated, sig_output_elems(...) elements of `dtype`,
  *              fully overwritten; must not overlap `path`.
+ *              For `path` and `out` any alignment natural for `dtype` is accepted; 16-byte
+ *              alignment of both lets the fastest kernels serve the call.
  *   hip_stream the work is enqueued on this stream; the call returns without waiting.
  *
  * The caller owns both buffers and must keep them alive until the stream has passed the

@@ -20,6 +20,9 @@ HIPCC_FLAGS = [
     "-Wall",
     # packed-FP32 instructions are kept out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # keep matrix-core operands and results in ordinary vector registers: the kernels chain the
+    # result of one outer product into the operand of the next, and the AGPR form costs copies
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
 ]
 
 

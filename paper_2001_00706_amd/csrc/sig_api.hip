@@ -54,9 +54,11 @@ sig_status make_shape(int64_t B, int64_t L, int d, int N, int stream, int basepo
 
 enum class Family { Generic, Mfma, None };
 
-Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant)
+// The pointers decide only alignment: the matrix-core family loads and stores 16 bytes per lane.
+Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const void *path, const void *out)
 {
-    const bool mfma_ok = dtype == SIG_F32 && sig::mfma_kernel_name(sh) != nullptr;
+    const bool aligned = reinterpret_cast<uintptr_t>(out) % 16 == 0 && reinterpret_cast<uintptr_t>(path) % 16 == 0;
+    const bool mfma_ok = dtype == SIG_F32 && aligned && sig::mfma_kernel_name(sh) != nullptr;
     const bool generic_ok = sig::generic_supported(sh, dtype);
     switch (variant) {
         case SIG_VARIANT_AUTO:
@@ -111,7 +113,7 @@ sig_status sig_forward_variant(const void *path, int64_t B, int64_t L, int d, in
     if (B == 0) return SIG_OK;
     if (path == nullptr || out == nullptr) return SIG_ERR_INVALID_ARG;
     hipError_t err = hipSuccess;
-    switch (resolve(sh, dtype, variant)) {
+    switch (resolve(sh, dtype, variant, path, out)) {
         case Family::Mfma:
             err = sig::launch_mfma_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
             break;
@@ -139,7 +141,7 @@ const char *sig_variant_name(int64_t B, int64_t L, int d, int N, int stream, int
     if (!valid_enums(dtype, variant)) return "invalid";
     sig::Shape sh;
     if (make_shape(B, L, d, N, stream, basepoint, sh) != SIG_OK) return "invalid";
-    switch (resolve(sh, dtype, variant)) {
+    switch (resolve(sh, dtype, variant, nullptr, nullptr)) {
         case Family::Mfma: return sig::mfma_kernel_name(sh);
         case Family::Generic: return "generic";
         case Family::None: break;
