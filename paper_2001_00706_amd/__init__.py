@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     SIG_VARIANT_AUTO,
     SIG_VARIANT_GENERIC,
     SIG_VARIANT_MFMA,
+    SIG_VARIANT_MFMA_PAIR,
     SigError,
     load_library,
     sig_forward,

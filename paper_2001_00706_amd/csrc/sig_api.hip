@@ -52,20 +52,24 @@ sig_status make_shape(int64_t B, int64_t L, int d, int N, int stream, int basepo
     return SIG_OK;
 }
 
-enum class Family { Generic, Mfma, None };
+enum class Family { Generic, Mfma, MfmaPair, None };
 
 // The pointers decide only alignment: the matrix-core family loads and stores 16 bytes per lane.
 Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const void *path, const void *out)
 {
     const bool aligned = reinterpret_cast<uintptr_t>(out) % 16 == 0 && reinterpret_cast<uintptr_t>(path) % 16 == 0;
-    const bool mfma_ok = dtype == SIG_F32 && aligned && sig::mfma_kernel_name(sh) != nullptr;
+    const bool mfma_ok = dtype == SIG_F32 && aligned && sig::mfma_kernel_name(sh, false) != nullptr;
+    const bool pair_ok = dtype == SIG_F32 && aligned && sig::mfma_kernel_name(sh, true) != nullptr;
     const bool generic_ok = sig::generic_supported(sh, dtype);
     switch (variant) {
         case SIG_VARIANT_AUTO:
+            // the two-wavefront family is measured slower than the one-wavefront one on every
+            // shape tried so far, so it is only ever chosen explicitly
             if (mfma_ok) return Family::Mfma;
             return generic_ok ? Family::Generic : Family::None;
         case SIG_VARIANT_GENERIC: return generic_ok ? Family::Generic : Family::None;
         case SIG_VARIANT_MFMA: return mfma_ok ? Family::Mfma : Family::None;
+        case SIG_VARIANT_MFMA_PAIR: return pair_ok ? Family::MfmaPair : Family::None;
     }
     return Family::None;
 }
@@ -73,7 +77,8 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
 bool valid_enums(sig_dtype dtype, sig_variant variant)
 {
     return (dtype == SIG_F32 || dtype == SIG_F64) &&
-           (variant == SIG_VARIANT_AUTO || variant == SIG_VARIANT_GENERIC || variant == SIG_VARIANT_MFMA);
+           (variant == SIG_VARIANT_AUTO || variant == SIG_VARIANT_GENERIC || variant == SIG_VARIANT_MFMA ||
+            variant == SIG_VARIANT_MFMA_PAIR);
 }
 
 }  // namespace
@@ -115,7 +120,10 @@ sig_status sig_forward_variant(const void *path, int64_t B, int64_t L, int d, in
     hipError_t err = hipSuccess;
     switch (resolve(sh, dtype, variant, path, out)) {
         case Family::Mfma:
-            err = sig::launch_mfma_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
+            err = sig::launch_mfma_f32(sh, false, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
+            break;
+        case Family::MfmaPair:
+            err = sig::launch_mfma_f32(sh, true, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
             break;
         case Family::Generic:
             err = dtype == SIG_F32
@@ -142,7 +150,8 @@ const char *sig_variant_name(int64_t B, int64_t L, int d, int N, int stream, int
     sig::Shape sh;
     if (make_shape(B, L, d, N, stream, basepoint, sh) != SIG_OK) return "invalid";
     switch (resolve(sh, dtype, variant, nullptr, nullptr)) {
-        case Family::Mfma: return sig::mfma_kernel_name(sh);
+        case Family::Mfma: return sig::mfma_kernel_name(sh, false);
+        case Family::MfmaPair: return sig::mfma_kernel_name(sh, true);
         case Family::Generic: return "generic";
         case Family::None: break;
     }

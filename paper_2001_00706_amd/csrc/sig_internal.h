@@ -27,9 +27,10 @@ bool generic_supported(const Shape &sh, sig_dtype dtype);
 hipError_t launch_generic_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_generic_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
 
-// Matrix-core family (fp32 only).  `mfma_kernel_name` returns nullptr for shapes it cannot serve.
-const char *mfma_kernel_name(const Shape &sh);
-hipError_t launch_mfma_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
+// Matrix-core families (fp32 only): one wavefront per path, or (`pair`) a producer/consumer pair
+// of wavefronts per path.  `mfma_kernel_name` returns nullptr for shapes the family cannot serve.
+const char *mfma_kernel_name(const Shape &sh, bool pair);
+hipError_t launch_mfma_f32(const Shape &sh, bool pair, const float *path, float *out, hipStream_t st);
 
 }  // namespace sig
 

@@ -83,24 +83,28 @@ __device__ __forceinline__ Row<N> load_row(const float *tab, int w1, int w2, int
     return R;
 }
 
-// One fused multiply-exponentiate A <- A [x] exp(z).
+// Levels 1..3 of one fused multiply-exponentiate A <- A [x] exp(z), one scalar per lane, and
+// the level-3 Horner terms t3[k] = T_k^(3) of the higher targets k = 4..N.
 template <int N>
-__device__ __forceinline__ void fused_step(State<N> &S, const Row<N> &R)
+__device__ __forceinline__ void low_levels(State<N> &S, const Row<N> &R, float (&t3)[N + 1])
 {
-    const float zA = R.zA;
-    const float *zB = R.zB, *zC = R.zC;
+    float t1[N + 1], t2[N + 1];
+#pragma unroll
+    for (int k = 2; k <= N; ++k) t1[k] = __builtin_fmaf(R.zA, 1.0f / k, S.A1);
+#pragma unroll
+    for (int k = 2; k <= N; ++k) t2[k] = __builtin_fmaf(t1[k], R.zB[k - 1], S.A2);
+#pragma unroll
+    for (int k = 3; k <= N; ++k) t3[k] = __builtin_fmaf(t2[k], R.zC[k - 2], S.A3);
+    S.A3 = t3[3];
+    S.A2 = t2[2];
+    S.A1 += R.zA;
+}
 
-    // low levels, one scalar per lane
-    float t1[N + 1], t2[N + 1], t3[N + 1];
-#pragma unroll
-    for (int k = 2; k <= N; ++k) t1[k] = __builtin_fmaf(zA, 1.0f / k, S.A1);
-#pragma unroll
-    for (int k = 2; k <= N; ++k) t2[k] = __builtin_fmaf(t1[k], zB[k - 1], S.A2);
-#pragma unroll
-    for (int k = 3; k <= N; ++k) t3[k] = __builtin_fmaf(t2[k], zC[k - 2], S.A3);
-
-    // levels 4.., outer products on the matrix cores; higher targets first, so that each A_i is
-    // read by every stage that needs its old value before it is overwritten
+// Levels 4..N: outer products on the matrix cores; higher targets first, so that each A_i is
+// read by every stage that needs its old value before it is overwritten.  zC[m] = z[q]/m.
+template <int N>
+__device__ __forceinline__ void high_levels(State<N> &S, const float (&t3)[N + 1], const float *zC)
+{
     f4 t4[N + 1];
 #pragma unroll
     for (int k = N; k >= 5; --k) t4[k] = outer4(t3[k], zC[k - 3], S.A4[0]);
@@ -118,9 +122,15 @@ __device__ __forceinline__ void fused_step(State<N> &S, const Row<N> &R)
             for (int g = 0; g < 16; ++g) S.A6[g] = outer4(t5[g >> 2][g & 3], zC[1], S.A6[g]);
         }
     }
-    S.A3 = t3[3];
-    S.A2 = t2[2];
-    S.A1 += zA;
+}
+
+// One fused multiply-exponentiate A <- A [x] exp(z).
+template <int N>
+__device__ __forceinline__ void fused_step(State<N> &S, const Row<N> &R)
+{
+    float t3[N + 1];
+    low_levels<N>(S, R, t3);
+    high_levels<N>(S, t3, R.zC);
 }
 
 // Where word number i of a level (lexicographic) is parked in LDS on its way to `out`.  The
@@ -236,18 +246,197 @@ sig_mfma_d4_kernel(const float *__restrict__ path, float *__restrict__ out, int6
     }
 }
 
-}  // namespace
+// ---------------------------------------------------------------------------------------------
+// Two wavefronts per path.
+//
+// A lone wavefront on a SIMD issues roughly one instruction every 8 clocks whatever its kind, so
+// the one-wavefront kernel above is bound by its instruction count, not by the matrix cores.  Here
+// the work of a path is cut along its only one-way dependency: wavefront 1 (the producer) folds
+// each increment into levels 1..3 and hands the level-3 Horner terms t3[k], k = 4..N, over
+// through LDS; wavefront 0 (the consumer) owns levels 4..N and does nothing but outer products.
+// Nothing flows back, so the producer simply runs one chunk of increments ahead.  Both
+// wavefronts run the same loop with one workgroup barrier per trip, hence cannot fall out of step.
+constexpr int kChunk = 4;      // increments per hand-over
+constexpr int kPairTile = 64;  // increments per staged LDS tile; two tiles are used alternately
 
-const char *mfma_kernel_name(const Shape &sh)
+template <int N>
+struct PairLds {
+    static constexpr int kRow = 4 * (N - 1);                    // floats per staged increment
+    static constexpr int kTab = 2 * kPairTile * kRow;           // two tiles of scaled increments
+    static constexpr int kRec = N - 3;                          // floats per lane handed over per increment
+    static constexpr int kXchg = 2 * kChunk * 64 * kRec;        // two chunks of hand-over records
+    static constexpr int kFloats = (kTab + kXchg > kChannels<N> ? kTab + kXchg : kChannels<N>);
+};
+
+// Producer side of one chunk: `rows` points at the chunk's first staged increment, `rec` at this
+// lane's slot of the chunk's first hand-over record.  FULL: the chunk has all kChunk increments.
+template <int N, bool FULL>
+__device__ __forceinline__ void produce_chunk(State<N> &S, const float *rows, float *rec, int ns, int w1, int w2, int q)
 {
-    if (sh.d == 4 && sh.N >= 4 && sh.N <= 6 && !sh.stream && sh.B <= 0x7fffffff) return "mfma_d4";
-    return nullptr;
+    constexpr int kRow = 4 * (N - 1), kRec = N - 3;
+    Row<N> R[kChunk];
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i) R[i] = load_row<N>(rows + (FULL || i < ns ? i : 0) * kRow, w1, w2, q);
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i) {
+        if (FULL || i < ns) {
+            float t3[N + 1];
+            low_levels<N>(S, R[i], t3);
+#pragma unroll
+            for (int k = 4; k <= N; ++k) rec[i * 64 * kRec + (k - 4)] = t3[k];
+        }
+    }
 }
 
-hipError_t launch_mfma_f32(const Shape &sh, const float *path, float *out, hipStream_t st)
+// Consumer side of one chunk.
+template <int N, bool FULL>
+__device__ __forceinline__ void consume_chunk(State<N> &S, const float *rows, const float *rec, int ns, int q)
 {
-    if (mfma_kernel_name(sh) == nullptr) return hipErrorNotSupported;
-    const dim3 grid(static_cast<unsigned>(sh.B)), block(64);
+    constexpr int kRow = 4 * (N - 1), kRec = N - 3;
+    float t3[kChunk][N + 1], zC[kChunk][N];
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i) {
+        const int ii = FULL || i < ns ? i : 0;
+#pragma unroll
+        for (int k = 4; k <= N; ++k) t3[i][k] = rec[ii * 64 * kRec + (k - 4)];
+#pragma unroll
+        for (int m = 1; m <= N - 3; ++m) zC[i][m] = rows[ii * kRow + (m - 1) * 4 + q];
+    }
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i)
+        if (FULL || i < ns) high_levels<N>(S, t3[i], zC[i]);
+}
+
+template <int N>
+__global__ void __launch_bounds__(128)
+sig_mfma_d4_pair_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint)
+{
+    static_assert(N >= 5 && N <= 6, "depths served by this kernel");
+    using Lds = PairLds<N>;
+    constexpr int kRow = Lds::kRow, kRec = Lds::kRec;
+    __shared__ __align__(16) float lds[Lds::kFloats];
+    float *tab = lds;
+    float *xchg = lds + Lds::kTab;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const bool producer = __builtin_amdgcn_readfirstlane(tid >> 6) == 1;
+    const int w1 = lane >> 4, w2 = (lane >> 2) & 3, q = lane & 3;
+    const int64_t b = blockIdx.x;
+    const f4 *x4 = reinterpret_cast<const f4 *>(path) + b * L;  // point l of this path
+
+    State<N> S;
+    S.A4[0] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int g = 0; g < 4; ++g) S.A5[g] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int g = 0; g < (N >= 6 ? 16 : 1); ++g) S.A6[g] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+
+    // producer: the two points around increment number s (zeros past the end of the path)
+    f4 p_hi = (f4){0.0f, 0.0f, 0.0f, 0.0f}, p_lo = p_hi;
+    auto fetch_points = [&](int64_t s) {
+        p_hi = p_lo = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+        if (s < n_inc) {
+            const int64_t i_hi = basepoint ? s : s + 1;
+            p_hi = x4[i_hi];
+            if (i_hi > 0) p_lo = x4[i_hi - 1];
+        }
+    };
+    if (producer) fetch_points(lane);
+
+    const int64_t n_chunks = (n_inc + kChunk - 1) / kChunk;
+    for (int64_t c = 0; c <= n_chunks; ++c) {
+        if (producer) {
+            if (c < n_chunks) {
+                const int64_t s0 = c * kChunk;
+                const int in_tile = int(s0 % kPairTile);
+                float *tile = tab + int((s0 / kPairTile) & 1) * (kPairTile * kRow);
+                if (in_tile == 0) {
+                    // stage this tile from the points fetched one tile ago, then fetch the next tile's
+                    if (s0 + lane < n_inc) {
+                        const f4 z = p_hi - p_lo;
+                        f4 *row = reinterpret_cast<f4 *>(tile + lane * kRow);
+                        row[0] = z;
+#pragma unroll
+                        for (int m = 2; m <= N - 1; ++m) row[m - 1] = z * (1.0f / m);
+                    }
+                    fetch_points(s0 + kPairTile + lane);
+                }
+                const int ns = int(n_inc - s0 < kChunk ? n_inc - s0 : kChunk);
+                float *rec = xchg + (int(c & 1) * kChunk * 64 + lane) * kRec;
+                if (ns == kChunk) {
+                    produce_chunk<N, true>(S, tile + in_tile * kRow, rec, kChunk, w1, w2, q);
+                } else {
+                    produce_chunk<N, false>(S, tile + in_tile * kRow, rec, ns, w1, w2, q);
+                }
+            }
+        } else {
+            if (c > 0) {
+                const int64_t s0 = (c - 1) * kChunk;
+                const int in_tile = int(s0 % kPairTile);
+                const float *tile = tab + int((s0 / kPairTile) & 1) * (kPairTile * kRow);
+                const int ns = int(n_inc - s0 < kChunk ? n_inc - s0 : kChunk);
+                const float *rec = xchg + (int((c - 1) & 1) * kChunk * 64 + lane) * kRec;
+                if (ns == kChunk) {
+                    consume_chunk<N, true>(S, tile + in_tile * kRow, rec, kChunk, q);
+                } else {
+                    consume_chunk<N, false>(S, tile + in_tile * kRow, rec, ns, q);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // park the state in LDS in word order (levels 1..3 from the producer, the rest from the
+    // consumer), then both wavefronts copy it out 16 bytes per lane
+    const int blk = lane >> 2;
+    if (producer) {
+        if ((lane & 15) == 0) lds[w1] = S.A1;
+        if (q == 0) lds[4 + (lane >> 2)] = S.A2;
+        lds[20 + lane] = S.A3;
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) lds[kOff4 + park4(blk * 16 + r * 4 + q)] = S.A4[0][r];
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) lds[kOff5 + park5(blk * 64 + g * 16 + r * 4 + q)] = S.A5[g][r];
+        if constexpr (N >= 6) {
+#pragma unroll
+            for (int g = 0; g < 16; ++g)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) lds[kOff6 + park6(blk * 256 + g * 16 + r * 4 + q)] = S.A6[g][r];
+        }
+    }
+    __syncthreads();
+    f4 *o4 = reinterpret_cast<f4 *>(out + b * kChannels<N>);
+    for (int j = tid; j < kChannels<N> / 4; j += 128) {
+        const int i = 4 * j;
+        const int at = i < kOff4 ? i : i < kOff5 ? kOff4 + park4(i - kOff4) : i < kOff6 ? kOff5 + park5(i - kOff5) : kOff6 + park6(i - kOff6);
+        o4[j] = *reinterpret_cast<const f4 *>(lds + at);
+    }
+}
+
+}  // namespace
+
+const char *mfma_kernel_name(const Shape &sh, bool pair)
+{
+    if (sh.d != 4 || sh.stream || sh.B > 0x7fffffff) return nullptr;
+    if (pair) return (sh.N == 5 || sh.N == 6) ? "mfma_d4_pair" : nullptr;
+    return (sh.N >= 4 && sh.N <= 6) ? "mfma_d4" : nullptr;
+}
+
+hipError_t launch_mfma_f32(const Shape &sh, bool pair, const float *path, float *out, hipStream_t st)
+{
+    if (mfma_kernel_name(sh, pair) == nullptr) return hipErrorNotSupported;
+    const dim3 grid(static_cast<unsigned>(sh.B));
+    if (pair) {
+        const dim3 block(128);
+        if (sh.N == 5) hipLaunchKernelGGL(sig_mfma_d4_pair_kernel<5>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint);
+        else hipLaunchKernelGGL(sig_mfma_d4_pair_kernel<6>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint);
+        return hipGetLastError();
+    }
+    const dim3 block(64);
     switch (sh.N) {
         case 4: hipLaunchKernelGGL(sig_mfma_d4_kernel<4>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint); break;
         case 5: hipLaunchKernelGGL(sig_mfma_d4_kernel<5>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint); break;

@@ -112,6 +112,10 @@ def test_variant_names(lib):
     assert sig.sig_variant_name(32, 16, 2, 4, False, False, variant=sig.SIG_VARIANT_GENERIC) == "generic"
     assert sig.sig_variant_name(32, 1, 2, 4, False, False) == "invalid"
     assert sig.sig_variant_name(32, 16, 3, 4, False, False, variant=sig.SIG_VARIANT_MFMA) == "unsupported"
+    assert sig.sig_variant_name(32, 16, 4, 4, False, False, variant=sig.SIG_VARIANT_MFMA) == "mfma_d4"
+    assert sig.sig_variant_name(32, 16, 4, 4, False, False, variant=sig.SIG_VARIANT_MFMA_PAIR) == "unsupported"
+    assert sig.sig_variant_name(32, 16, 4, 6, False, False, variant=sig.SIG_VARIANT_MFMA_PAIR) == "mfma_d4_pair"
+    assert sig.sig_variant_name(32, 16, 4, 6, True, False, variant=sig.SIG_VARIANT_MFMA) == "unsupported"
 
 
 def test_python_binding_refuses_cpu_tensors(lib):

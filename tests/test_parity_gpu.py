@@ -50,7 +50,17 @@ def level_errors(got, want, d, N):
     return np.array(batch), np.array(single)
 
 
+def served(x, N, stream, basepoint, variant):
+    B, L, d = x.shape
+    dtype = sig.SIG_F32 if x.dtype == np.float32 else sig.SIG_F64
+    return sig.sig_variant_name(B, L, d, N, stream, basepoint, dtype, variant) != "unsupported"
+
+
 def check(x, N, stream=False, basepoint=False, variant=sig.SIG_VARIANT_AUTO, sample=None):
+    """Runs the HIP path and compares with the oracle; returns None (nothing compared) when the
+    forced kernel family does not serve the shape."""
+    if not served(x, N, stream, basepoint, variant):
+        return None
     dt = x.dtype.type
     got = gpu_signature(x, N, stream, basepoint, variant)
     assert np.all(np.isfinite(got)), "output not fully written"
@@ -62,11 +72,12 @@ def check(x, N, stream=False, basepoint=False, variant=sig.SIG_VARIANT_AUTO, sam
     return got
 
 
-VARIANTS = [sig.SIG_VARIANT_AUTO, sig.SIG_VARIANT_GENERIC]
+VARIANTS = [sig.SIG_VARIANT_AUTO, sig.SIG_VARIANT_GENERIC, sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_PAIR]
+VARIANT_IDS = ["auto", "generic", "mfma", "mfma_pair"]
 
 
 # ------------------------------------------------------------------ benchmark workloads
-@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
 @pytest.mark.parametrize("w", WORKLOADS, ids=lambda w: w.name)
 def test_benchmark_workloads_full_size(w, variant):
     """Full-size launch, as bench.py times it; the oracle recomputes a seeded sample of
@@ -77,7 +88,8 @@ def test_benchmark_workloads_full_size(w, variant):
     sample = np.sort(rng.choice(w.B, size=n_sample, replace=False))
     if n_sample < w.B:
         sample = np.unique(np.concatenate([[0, w.B - 1], sample]))
-    check(x, w.N, stream=w.stream, basepoint=w.basepoint, variant=variant, sample=sample)
+    if check(x, w.N, stream=w.stream, basepoint=w.basepoint, variant=variant, sample=sample) is None:
+        pytest.skip("kernel family does not serve this workload")
 
 
 @pytest.mark.parametrize("w", [WORKLOADS[0], WORKLOADS[3]], ids=lambda w: w.name)
@@ -94,7 +106,7 @@ SWEEP = [
 ]
 
 
-@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 @pytest.mark.parametrize("B,L,d,N", SWEEP)
 def test_shape_sweep(B, L, d, N, dtype, variant):
@@ -104,7 +116,7 @@ def test_shape_sweep(B, L, d, N, dtype, variant):
             check(x, N, stream=stream, basepoint=basepoint, variant=variant)
 
 
-@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
 def test_state_too_large_for_lds(variant):
     # d = 16, N = 4: 69904 scalars per path, several tiles of every level and ragged tails
     x = brownian_paths(3, 9, 16, seed=77)
@@ -113,6 +125,43 @@ def test_state_too_large_for_lds(variant):
     x = brownian_paths(2, 6, 11, seed=78)   # 11^4: not a multiple of the workgroup size
     check(x, 4, variant=variant)
     check(x, 4, stream=True, variant=variant)
+
+
+# ----------------------------------------------------- matrix-core kernels, d = 4
+D4_SHAPES = [
+    # (B, L, N): odd and even increment counts, one increment, tile and chunk boundaries
+    (3, 2, 4), (2, 3, 5), (3, 2, 6), (2, 5, 6), (5, 6, 6), (2, 64, 6), (3, 65, 6), (2, 66, 5), (1, 129, 6),
+    (2, 130, 5), (2, 257, 6), (1, 258, 4), (2, 300, 6), (7, 31, 5), (4, 70, 4),
+]
+
+
+@pytest.mark.parametrize("variant", [sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_PAIR], ids=["mfma", "mfma_pair"])
+@pytest.mark.parametrize("B,L,N", D4_SHAPES)
+def test_d4_matrix_core_kernels(B, L, N, variant):
+    x = uniform_paths(B, L, 4, seed=2000 + 3 * L + N, lo=-0.5, hi=0.5)
+    if L > 40:
+        x = brownian_paths(B, L, 4, seed=2000 + 3 * L + N)
+    ran = [check(x, N, basepoint=bp, variant=variant) is not None for bp in (False, True)]
+    if not any(ran):
+        pytest.skip("kernel family does not serve this depth")
+
+
+def test_unaligned_buffers_fall_back_to_the_generic_kernel():
+    torch = torch_mod()
+    w = WORKLOADS[1]
+    x = workload_paths(w)[:4]
+    want = orc.signature(x, w.N)
+    big = torch.zeros(x.size + 1, dtype=torch.float32, device="cuda:0")
+    xt = big[1:].view(x.shape)                      # 4-byte aligned only
+    xt.copy_(torch.from_numpy(x))
+    obig = torch.full((want.size + 1,), float("nan"), dtype=torch.float32, device="cuda:0")
+    ot = obig[1:].view(want.shape)
+    sig.sig_forward(xt, w.N, out=ot)
+    torch.cuda.synchronize()
+    batch, _ = level_errors(ot.cpu().numpy(), want, w.d, w.N)
+    assert np.all(batch <= 1e-4)
+    with pytest.raises(sig.SigError):
+        sig.sig_forward(xt, w.N, out=ot, variant=sig.SIG_VARIANT_MFMA)
 
 
 # -------------------------------------------------------------------------- edge cases
