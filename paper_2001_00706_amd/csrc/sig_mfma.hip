@@ -191,23 +191,17 @@ sig_mfma_d4_kernel(const float *__restrict__ path, float *__restrict__ out, int6
             }
         }
         __syncthreads();
-        // two increments per trip; the rows of the next two are fetched from LDS while the
-        // current ones are being folded in, so the scan never waits for the LDS latency
-        Row<N> r0 = load_row<N>(lds, w1, w2, q);
-        Row<N> r1 = load_row<N>(lds + (nt > 1 ? kRow : 0), w1, w2, q);
+        // four increments per trip: their rows are fetched from LDS together, so the LDS latency
+        // is paid once per trip and no register is copied between trips
         int s = 0;
-        for (; s + 1 < nt; s += 2) {
-            const int s2 = s + 2 < nt ? s + 2 : nt - 1, s3 = s + 3 < nt ? s + 3 : nt - 1;
-            const Row<N> n0 = load_row<N>(lds + s2 * kRow, w1, w2, q);
-            __builtin_amdgcn_sched_barrier(0);
-            fused_step<N>(S, r0);
-            const Row<N> n1 = load_row<N>(lds + s3 * kRow, w1, w2, q);
-            __builtin_amdgcn_sched_barrier(0);
-            fused_step<N>(S, r1);
-            r0 = n0;
-            r1 = n1;
+        for (; s + 4 <= nt; s += 4) {
+            Row<N> R[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) R[i] = load_row<N>(lds + (s + i) * kRow, w1, w2, q);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) fused_step<N>(S, R[i]);
         }
-        if (s < nt) fused_step<N>(S, r0);
+        for (; s < nt; ++s) fused_step<N>(S, load_row<N>(lds + s * kRow, w1, w2, q));
     }
 
     // park the state in LDS in word order, then copy it out 16 bytes per lane, fully coalesced
