@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     SIG_VARIANT_GENERIC,
     SIG_VARIANT_MFMA,
     SIG_VARIANT_MFMA_PAIR,
+    SIG_VARIANT_MFMA_SHARD,
     SigError,
     load_library,
     sig_forward,

@@ -32,6 +32,11 @@ hipError_t launch_generic_f64(const Shape &sh, const double *path, double *out, 
 const char *mfma_kernel_name(const Shape &sh, bool pair);
 hipError_t launch_mfma_f32(const Shape &sh, bool pair, const float *path, float *out, hipStream_t st);
 
+// Matrix-core family with four wavefronts per path, one per first letter (fp32, d = 4, N = 4..7,
+// final and stream mode).
+const char *mfma_shard_kernel_name(const Shape &sh);
+hipError_t launch_mfma_shard_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
+
 }  // namespace sig
 
 #endif  // SIG_INTERNAL_H_

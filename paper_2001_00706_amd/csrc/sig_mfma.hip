@@ -29,11 +29,10 @@
 // vector block is kept short: the scaled increments z/m come ready-made from an LDS table that
 // is filled once per tile of increments.
 #include "sig_internal.h"
+#include "sig_mfma_common.h"
 
 namespace sig {
 namespace {
-
-typedef float f4 __attribute__((ext_vector_type(4)));
 
 // Scalars in a depth-N signature over 4 channels, and the offset of each level.
 template <int N>
@@ -46,13 +45,6 @@ constexpr int kTile = (N == 6 ? 256 : 64);
 
 template <int N>
 constexpr int kLdsFloats = (kTile<N> * 4 * (N - 1) > kChannels<N> ? kTile<N> * 4 * (N - 1) : kChannels<N>);
-
-__device__ __forceinline__ f4 outer4(float a, float b, f4 c)
-{
-    // 16 blocks of D[i][j] = a[i] * b[j] + C[i][j]; lane 4*blk + i supplies a[i], lane 4*blk + j supplies b[j];
-    // register i of lane 4*blk + j receives D[i][j]
-    return __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, c, 0, 0, 0);
-}
 
 template <int N>
 struct State {

@@ -1,0 +1,264 @@
+// Matrix-core kernel family (fp32), d = 4 channels, depth N = 4..7, final and stream mode,
+// four wavefronts per path with no communication between them.
+//
+// The words that start with a given first letter f, together with the one-letter word f itself,
+// are closed under the fused multiply-exponentiate (paper section 4.1, eq. "fusedterm"): the
+// new coefficient of a word depends only on the old coefficients of its prefixes.  So a path is
+// cut into four shards by first letter, one wavefront each, and every shard scans all the
+// increments on its own; each writes its own slice of every level, and the slices tile the output.
+// This gives a batch of B paths 4B wavefronts, which is what stream mode needs: there every
+// prefix signature is written out (section 5.5, "expanding intervals"), the kernel is bound by
+// HBM writes, and one wavefront per path cannot issue stores fast enough.
+//
+// Register layout of shard f (lane = 16*w_2 + 4*w_3 + q):
+//   A_1[f]                 the same scalar in every lane
+//   A_2[f w_2], A_3[f w_2 w_3], A_4[f w_2 w_3 q]      one scalar per lane (replicated where needed)
+//   A_k, k >= 5            4^(k-5) groups of 4 registers: group g spells letters w_4..w_{k-2},
+//                          register r is letter w_{k-1}, lane q is letter w_k, block (lane/4) is w_2 w_3
+// Levels 1..4 are plain vector FMAs; from level 5 on each Horner stage is a batch of 4x4 outer
+// products on the matrix cores whose result registers are, as they stand, the left operand of the
+// next stage.  The top level feeds no further stage, so its outer product is taken with the two
+// operands swapped: register r is then the LAST letter w_N and lane q the letter before it, a lane
+// holds 4 consecutive words, and a wavefront store covers 1 KB of contiguous output with no
+// shuffling at all.  Lower matrix-core levels (only present for N >= 6) are transposed inside each
+// lane quad with DPP moves before they are stored.  The 21 words of levels 1..3 go out in one store
+// instruction: every lane writes one of them (several lanes the same word with the same value).
+#include "sig_internal.h"
+#include "sig_mfma_common.h"
+
+namespace sig {
+namespace {
+
+// offsets of levels 1..8 in a d = 4 signature
+constexpr int kLevelOff[9] = {0, 0, 4, 20, 84, 340, 1364, 5460, 21844};
+
+template <int N>
+constexpr int kTileShard = 64;  // increments staged in LDS at a time
+
+template <int N>
+struct ShardState {
+    float A1 = 0.0f, A2 = 0.0f, A3 = 0.0f, A4 = 0.0f;
+    f4 A5[1];
+    f4 A6[N >= 6 ? 4 : 1];
+    f4 A7[N >= 7 ? 16 : 1];
+};
+
+// This lane's view of one staged increment.
+template <int N>
+struct ShardRow {
+    float zf;      // z[f]
+    float zB[N];   // zB[m] = z[w_2]/m, m = 1..N-1
+    float zC[N];   // zC[m] = z[w_3]/m, m = 1..N-2
+    float zQ[N];   // zQ[m] = z[q]/m,   m = 1..N-3
+};
+
+// `tab` points at one increment's scaled copies in LDS: tab[(m-1)*4 + c] = z[c]/m, m = 1..N-1.
+template <int N>
+__device__ __forceinline__ ShardRow<N> load_shard_row(const float *tab, int f, int w2, int w3, int q)
+{
+    ShardRow<N> R;
+    R.zf = tab[f];
+#pragma unroll
+    for (int m = 1; m <= N - 1; ++m) R.zB[m] = tab[(m - 1) * 4 + w2];
+#pragma unroll
+    for (int m = 1; m <= N - 2; ++m) R.zC[m] = tab[(m - 1) * 4 + w3];
+#pragma unroll
+    for (int m = 1; m <= N - 3; ++m) R.zQ[m] = tab[(m - 1) * 4 + q];
+    return R;
+}
+
+// One fused multiply-exponentiate restricted to the words of this shard.
+template <int N>
+__device__ __forceinline__ void shard_step(ShardState<N> &S, const ShardRow<N> &R)
+{
+    float t1[N + 1], t2[N + 1], t3[N + 1], t4[N + 1];
+#pragma unroll
+    for (int k = 2; k <= N; ++k) t1[k] = __builtin_fmaf(R.zf, 1.0f / k, S.A1);
+#pragma unroll
+    for (int k = 2; k <= N; ++k) t2[k] = __builtin_fmaf(t1[k], R.zB[k - 1], S.A2);
+#pragma unroll
+    for (int k = 3; k <= N; ++k) t3[k] = __builtin_fmaf(t2[k], R.zC[k - 2], S.A3);
+#pragma unroll
+    for (int k = 4; k <= N; ++k) t4[k] = __builtin_fmaf(t3[k], R.zQ[k - 3], S.A4);
+
+    // levels 5.., higher targets first so that every stage reads the old A_i
+    if constexpr (N >= 5) {
+        f4 t5[N + 1];
+#pragma unroll
+        for (int k = N; k >= 6; --k) t5[k] = outer4(t4[k], R.zQ[k - 4], S.A5[0]);
+        if constexpr (N == 5) S.A5[0] = outer4(R.zQ[1], t4[5], S.A5[0]);  // top level: operands swapped
+        else S.A5[0] = outer4(t4[5], R.zQ[1], S.A5[0]);
+        if constexpr (N >= 6) {
+            f4 t6[4];
+            if constexpr (N >= 7) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) t6[g] = outer4(t5[7][g], R.zQ[2], S.A6[g]);
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                if constexpr (N == 6) S.A6[g] = outer4(R.zQ[1], t5[6][g], S.A6[g]);  // top level: swapped
+                else S.A6[g] = outer4(t5[6][g], R.zQ[1], S.A6[g]);
+            }
+            if constexpr (N >= 7) {
+#pragma unroll
+                for (int g = 0; g < 16; ++g) S.A7[g] = outer4(R.zQ[1], t6[g >> 2][g & 3], S.A7[g]);  // top: swapped
+            }
+        }
+    }
+    S.A4 = t4[4];
+    S.A3 = t3[3];
+    S.A2 = t2[2];
+    S.A1 += R.zf;
+}
+
+// Per-lane constants of the store of levels 1..3: which word this lane writes and from which level.
+struct LowStore {
+    int off;    // word offset inside the signature
+    int level;  // 1, 2 or 3
+};
+
+__device__ __forceinline__ LowStore low_store_plan(int f, int lane)
+{
+    // lanes 1, 17, 33, 49 carry A_2[f w_2]; lane 5 carries A_1[f]; every other lane carries
+    // A_3[f w_2 w_3] (the four lanes of a quad hold the same value and write it to the same word)
+    LowStore p;
+    if ((lane & 15) == 1) {
+        p.level = 2;
+        p.off = kLevelOff[2] + 4 * f + (lane >> 4);
+    } else if (lane == 5) {
+        p.level = 1;
+        p.off = f;
+    } else {
+        p.level = 3;
+        p.off = kLevelOff[3] + 16 * f + (lane >> 2);
+    }
+    return p;
+}
+
+// Writes this shard's slice of every level of one signature starting at `o`.
+template <int N>
+__device__ __forceinline__ void store_shard(const ShardState<N> &S, float *o, int f, int lane, const LowStore &plan)
+{
+    o[plan.off] = plan.level == 3 ? S.A3 : plan.level == 2 ? S.A2 : S.A1;
+    o[kLevelOff[4] + 64 * f + lane] = S.A4;
+    const int blk = lane >> 2, q = lane & 3;
+    if constexpr (N >= 5) {
+        // level k occupies 4^(k-5) groups; group g of block blk starts at word (blk*G + g)*16
+        f4 *o5 = reinterpret_cast<f4 *>(o + kLevelOff[5] + 256 * f);
+        o5[lane] = N == 5 ? S.A5[0] : quad_transpose(S.A5[0], lane);
+    }
+    if constexpr (N >= 6) {
+        f4 *o6 = reinterpret_cast<f4 *>(o + kLevelOff[6] + 1024 * f);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) o6[blk * 16 + g * 4 + q] = N == 6 ? S.A6[g] : quad_transpose(S.A6[g], lane);
+    }
+    if constexpr (N >= 7) {
+        f4 *o7 = reinterpret_cast<f4 *>(o + kLevelOff[7] + 4096 * f);
+#pragma unroll
+        for (int g = 0; g < 16; ++g) o7[blk * 64 + g * 4 + q] = S.A7[g];
+    }
+}
+
+template <int N, bool STREAM>
+__global__ void __launch_bounds__(64)
+sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint)
+{
+    static_assert(N >= 4 && N <= 7, "depths served by this kernel");
+    constexpr int kRow = 4 * (N - 1);  // floats per staged increment
+    constexpr int kTile = kTileShard<N>;
+    constexpr int kS = kLevelOff[N + 1];
+    __shared__ __align__(16) float lds[kTile * kRow];
+
+    const int lane = threadIdx.x;
+    const int w2 = lane >> 4, w3 = (lane >> 2) & 3, q = lane & 3;
+    const int64_t b = blockIdx.x >> 2;
+    const int f = blockIdx.x & 3;
+    const f4 *x4 = reinterpret_cast<const f4 *>(path) + b * L;  // point l of this path
+    float *o = out + b * (STREAM ? n_inc * kS : int64_t(kS));
+
+    const LowStore plan = low_store_plan(f, lane);
+
+    ShardState<N> S;
+    S.A5[0] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int g = 0; g < (N >= 6 ? 4 : 1); ++g) S.A6[g] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int g = 0; g < (N >= 7 ? 16 : 1); ++g) S.A7[g] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+
+    // the two points around increment number s (zeros past the end of the path); the points of
+    // a tile are fetched while the tile before it is being scanned
+    f4 p_hi, p_lo;
+    auto fetch_points = [&](int64_t s) {
+        p_hi = p_lo = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+        if (s < n_inc) {
+            const int64_t i_hi = basepoint ? s : s + 1;
+            p_hi = x4[i_hi];
+            if (i_hi > 0) p_lo = x4[i_hi - 1];
+        }
+    };
+    fetch_points(lane);
+
+    for (int64_t t0 = 0; t0 < n_inc; t0 += kTile) {
+        const int nt = int(n_inc - t0 < kTile ? n_inc - t0 : kTile);
+        __syncthreads();
+        if (lane < nt) {
+            const f4 z = p_hi - p_lo;
+            f4 *row = reinterpret_cast<f4 *>(lds + lane * kRow);
+            row[0] = z;
+#pragma unroll
+            for (int m = 2; m <= N - 1; ++m) row[m - 1] = z * (1.0f / m);
+        }
+        __syncthreads();
+        fetch_points(t0 + kTile + lane);
+        int s = 0;
+        for (; s + 4 <= nt; s += 4) {
+            ShardRow<N> R[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) R[i] = load_shard_row<N>(lds + (s + i) * kRow, f, w2, w3, q);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                shard_step<N>(S, R[i]);
+                if constexpr (STREAM) store_shard<N>(S, o + (t0 + s + i) * kS, f, lane, plan);
+            }
+        }
+        for (; s < nt; ++s) {
+            shard_step<N>(S, load_shard_row<N>(lds + s * kRow, f, w2, w3, q));
+            if constexpr (STREAM) store_shard<N>(S, o + (t0 + s) * kS, f, lane, plan);
+        }
+    }
+    if constexpr (!STREAM) store_shard<N>(S, o, f, lane, plan);
+}
+
+template <int N>
+hipError_t launch_shard(const Shape &sh, const float *path, float *out, hipStream_t st)
+{
+    const dim3 grid(static_cast<unsigned>(sh.B * 4)), block(64);
+    if (sh.stream) {
+        hipLaunchKernelGGL((sig_mfma_d4_shard_kernel<N, true>), grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint);
+    } else {
+        hipLaunchKernelGGL((sig_mfma_d4_shard_kernel<N, false>), grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+const char *mfma_shard_kernel_name(const Shape &sh)
+{
+    if (sh.d != 4 || sh.N < 4 || sh.N > 7 || sh.B > 0x1fffffff) return nullptr;
+    return "mfma_d4_shard";
+}
+
+hipError_t launch_mfma_shard_f32(const Shape &sh, const float *path, float *out, hipStream_t st)
+{
+    if (mfma_shard_kernel_name(sh) == nullptr) return hipErrorNotSupported;
+    switch (sh.N) {
+        case 4: return launch_shard<4>(sh, path, out, st);
+        case 5: return launch_shard<5>(sh, path, out, st);
+        case 6: return launch_shard<6>(sh, path, out, st);
+        case 7: return launch_shard<7>(sh, path, out, st);
+    }
+    return hipErrorNotSupported;
+}
+
+}  // namespace sig

@@ -72,8 +72,9 @@ def check(x, N, stream=False, basepoint=False, variant=sig.SIG_VARIANT_AUTO, sam
     return got
 
 
-VARIANTS = [sig.SIG_VARIANT_AUTO, sig.SIG_VARIANT_GENERIC, sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_PAIR]
-VARIANT_IDS = ["auto", "generic", "mfma", "mfma_pair"]
+VARIANTS = [sig.SIG_VARIANT_AUTO, sig.SIG_VARIANT_GENERIC, sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_PAIR,
+            sig.SIG_VARIANT_MFMA_SHARD]
+VARIANT_IDS = ["auto", "generic", "mfma", "mfma_pair", "mfma_shard"]
 
 
 # ------------------------------------------------------------------ benchmark workloads
@@ -135,15 +136,28 @@ D4_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("variant", [sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_PAIR], ids=["mfma", "mfma_pair"])
+@pytest.mark.parametrize("variant", [sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_PAIR, sig.SIG_VARIANT_MFMA_SHARD],
+                         ids=["mfma", "mfma_pair", "mfma_shard"])
 @pytest.mark.parametrize("B,L,N", D4_SHAPES)
 def test_d4_matrix_core_kernels(B, L, N, variant):
     x = uniform_paths(B, L, 4, seed=2000 + 3 * L + N, lo=-0.5, hi=0.5)
     if L > 40:
         x = brownian_paths(B, L, 4, seed=2000 + 3 * L + N)
-    ran = [check(x, N, basepoint=bp, variant=variant) is not None for bp in (False, True)]
+    ran = []
+    for stream in (False, True):
+        if stream and L > 140:
+            continue
+        for bp in (False, True):
+            ran.append(check(x, N, stream=stream, basepoint=bp, variant=variant) is not None)
     if not any(ran):
-        pytest.skip("kernel family does not serve this depth")
+        pytest.skip("kernel family does not serve this shape")
+
+
+def test_d4_depth_seven():
+    x = brownian_paths(3, 21, 4, seed=707)
+    check(x, 7)
+    check(x, 7, stream=True, basepoint=True)
+    assert sig.sig_variant_name(3, 21, 4, 7, False, False) == "mfma_d4_shard"
 
 
 def test_unaligned_buffers_fall_back_to_the_generic_kernel():
