@@ -111,52 +111,70 @@ __device__ __forceinline__ void shard_step(ShardState<N> &S, const ShardRow<N> &
     S.A1 += R.zf;
 }
 
-// Per-lane constants of the store of levels 1..3: which word this lane writes and from which level.
-struct LowStore {
-    int off;    // word offset inside the signature
-    int level;  // 1, 2 or 3
+// Per-lane constants of the stores, all in bytes from the start of a signature.
+struct StorePlan {
+    int low_off;             // the word of levels 1..3 this lane writes
+    unsigned m1, m2, m3;     // all-ones for the level that word belongs to, zero otherwise
+    int off4;                // this lane's word of level 4
+    int off5, off6, off7;    // this lane's first 16 bytes of levels 5, 6 (group 0), 7 (group 0)
 };
 
-__device__ __forceinline__ LowStore low_store_plan(int f, int lane)
+template <int N>
+__device__ __forceinline__ StorePlan make_store_plan(int f, int lane)
 {
-    // lanes 1, 17, 33, 49 carry A_2[f w_2]; lane 5 carries A_1[f]; every other lane carries
-    // A_3[f w_2 w_3] (the four lanes of a quad hold the same value and write it to the same word)
-    LowStore p;
-    if ((lane & 15) == 1) {
-        p.level = 2;
-        p.off = kLevelOff[2] + 4 * f + (lane >> 4);
-    } else if (lane == 5) {
-        p.level = 1;
-        p.off = f;
-    } else {
-        p.level = 3;
-        p.off = kLevelOff[3] + 16 * f + (lane >> 2);
-    }
+    // levels 1..3: lanes 1, 17, 33, 49 carry A_2[f w_2]; lane 5 carries A_1[f]; every other lane
+    // carries A_3[f w_2 w_3] (the lanes of a quad hold the same value and write it to the same word)
+    StorePlan p;
+    const bool is2 = (lane & 15) == 1, is1 = lane == 5;
+    p.m1 = is1 ? ~0u : 0u;
+    p.m2 = is2 ? ~0u : 0u;
+    p.m3 = (is1 || is2) ? 0u : ~0u;
+    p.low_off = 4 * (is2 ? kLevelOff[2] + 4 * f + (lane >> 4) : is1 ? f : kLevelOff[3] + 16 * f + (lane >> 2));
+    p.off4 = 4 * (kLevelOff[4] + 64 * f + lane);
+    // level k >= 5 occupies G = 4^(k-5) groups per block; group g of block blk starts at word (blk*G + g)*16,
+    // and inside a group lane q holds words 4q..4q+3
+    const int blk = lane >> 2, q = lane & 3;
+    p.off5 = 4 * (kLevelOff[5] + 256 * f) + 16 * lane;
+    p.off6 = 4 * (kLevelOff[6] + 1024 * f) + 16 * (blk * 16 + q);
+    p.off7 = 4 * (kLevelOff[7] + 4096 * f) + 16 * (blk * 64 + q);
     return p;
 }
 
-// Writes this shard's slice of every level of one signature starting at `o`.
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+
+// Writes this shard's slice of every level of one signature.  The signature starts `row_bytes`
+// into the buffer described by `rsrc` (a wave-uniform scalar), so the stores need no per-lane
+// address arithmetic; stores beyond the descriptor's range would be dropped by the hardware.
 template <int N>
-__device__ __forceinline__ void store_shard(const ShardState<N> &S, float *o, int f, int lane, const LowStore &plan)
+__device__ __forceinline__ void store_shard(const ShardState<N> &S, __amdgpu_buffer_rsrc_t rsrc, int row_bytes,
+                                            const StorePlan &p, int lane)
 {
-    o[plan.off] = plan.level == 3 ? S.A3 : plan.level == 2 ? S.A2 : S.A1;
-    o[kLevelOff[4] + 64 * f + lane] = S.A4;
-    const int blk = lane >> 2, q = lane & 3;
+    const unsigned low = (__builtin_bit_cast(unsigned, S.A1) & p.m1) | (__builtin_bit_cast(unsigned, S.A2) & p.m2) |
+                         (__builtin_bit_cast(unsigned, S.A3) & p.m3);
+    __builtin_amdgcn_raw_buffer_store_b32(low, rsrc, p.low_off, row_bytes, 0);
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, S.A4), rsrc, p.off4, row_bytes, 0);
     if constexpr (N >= 5) {
-        // level k occupies 4^(k-5) groups; group g of block blk starts at word (blk*G + g)*16
-        f4 *o5 = reinterpret_cast<f4 *>(o + kLevelOff[5] + 256 * f);
-        o5[lane] = N == 5 ? S.A5[0] : quad_transpose(S.A5[0], lane);
+        const f4 v = N == 5 ? S.A5[0] : quad_transpose(S.A5[0], lane);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), rsrc, p.off5, row_bytes, 0);
     }
     if constexpr (N >= 6) {
-        f4 *o6 = reinterpret_cast<f4 *>(o + kLevelOff[6] + 1024 * f);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) o6[blk * 16 + g * 4 + q] = N == 6 ? S.A6[g] : quad_transpose(S.A6[g], lane);
+        for (int g = 0; g < 4; ++g) {
+            const f4 v = N == 6 ? S.A6[g] : quad_transpose(S.A6[g], lane);
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), rsrc, p.off6 + 64 * g, row_bytes, 0);
+        }
     }
     if constexpr (N >= 7) {
-        f4 *o7 = reinterpret_cast<f4 *>(o + kLevelOff[7] + 4096 * f);
 #pragma unroll
-        for (int g = 0; g < 16; ++g) o7[blk * 64 + g * 4 + q] = S.A7[g];
+        for (int g = 0; g < 16; ++g)
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, S.A7[g]), rsrc, p.off7 + 64 * g, row_bytes, 0);
     }
+}
+
+// Buffer descriptor for `bytes` bytes at `base` (raw buffer, no swizzle, 32-bit offsets).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(float *base, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(base, 0, int(bytes), 0x00020000);
 }
 
 template <int N, bool STREAM>
@@ -176,7 +194,7 @@ sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out
     const f4 *x4 = reinterpret_cast<const f4 *>(path) + b * L;  // point l of this path
     float *o = out + b * (STREAM ? n_inc * kS : int64_t(kS));
 
-    const LowStore plan = low_store_plan(f, lane);
+    const StorePlan plan = make_store_plan<N>(f, lane);
 
     ShardState<N> S;
     S.A5[0] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
@@ -210,6 +228,8 @@ sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out
         }
         __syncthreads();
         fetch_points(t0 + kTile + lane);
+        // stream mode: one descriptor per tile of prefix signatures (a tile is at most 64 * 87376 bytes)
+        const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(o + (STREAM ? t0 * kS : 0), unsigned(STREAM ? nt : 1) * kS * 4u);
         int s = 0;
         for (; s + 4 <= nt; s += 4) {
             ShardRow<N> R[4];
@@ -218,15 +238,15 @@ sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 shard_step<N>(S, R[i]);
-                if constexpr (STREAM) store_shard<N>(S, o + (t0 + s + i) * kS, f, lane, plan);
+                if constexpr (STREAM) store_shard<N>(S, rsrc, (s + i) * kS * 4, plan, lane);
             }
         }
         for (; s < nt; ++s) {
             shard_step<N>(S, load_shard_row<N>(lds + s * kRow, f, w2, w3, q));
-            if constexpr (STREAM) store_shard<N>(S, o + (t0 + s) * kS, f, lane, plan);
+            if constexpr (STREAM) store_shard<N>(S, rsrc, s * kS * 4, plan, lane);
         }
     }
-    if constexpr (!STREAM) store_shard<N>(S, o, f, lane, plan);
+    if constexpr (!STREAM) store_shard<N>(S, make_rsrc(o, kS * 4u), 0, plan, lane);
 }
 
 template <int N>
