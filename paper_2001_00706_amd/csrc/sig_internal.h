@@ -37,6 +37,10 @@ hipError_t launch_mfma_f32(const Shape &sh, bool pair, const float *path, float 
 const char *mfma_shard_kernel_name(const Shape &sh);
 hipError_t launch_mfma_shard_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 
+// Matrix-core kernel for d = 16, N = 4, final mode: one workgroup of 8 wavefronts per path.
+const char *mfma_d16_kernel_name(const Shape &sh);
+hipError_t launch_mfma_d16_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
+
 }  // namespace sig
 
 #endif  // SIG_INTERNAL_H_

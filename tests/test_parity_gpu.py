@@ -160,6 +160,14 @@ def test_d4_depth_seven():
     assert sig.sig_variant_name(3, 21, 4, 7, False, False) == "mfma_d4_shard"
 
 
+@pytest.mark.parametrize("B,L", [(1, 2), (2, 3), (3, 9), (2, 128), (1, 129), (2, 130), (1, 300)])
+def test_d16_matrix_core_kernel(B, L):
+    x = brownian_paths(B, L, 16, seed=1600 + L) if L > 20 else uniform_paths(B, L, 16, seed=1600 + L, lo=-0.3, hi=0.3)
+    assert sig.sig_variant_name(B, L, 16, 4, False, False, variant=sig.SIG_VARIANT_MFMA) == "mfma_d16"
+    for bp in (False, True):
+        check(x, 4, basepoint=bp, variant=sig.SIG_VARIANT_MFMA)
+
+
 def test_unaligned_buffers_fall_back_to_the_generic_kernel():
     torch = torch_mod()
     w = WORKLOADS[1]
