@@ -41,6 +41,10 @@ hipError_t launch_mfma_shard_f32(const Shape &sh, const float *path, float *out,
 const char *mfma_d16_kernel_name(const Shape &sh);
 hipError_t launch_mfma_d16_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 
+// Matrix-core kernel for d = 8, N = 4..6, final mode: 64 independent wavefronts per path.
+const char *mfma_d8_kernel_name(const Shape &sh);
+hipError_t launch_mfma_d8_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
+
 }  // namespace sig
 
 #endif  // SIG_INTERNAL_H_

@@ -1,0 +1,241 @@
+// Matrix-core kernel family (fp32), d = 8 channels, depth N = 4..6, final mode, 64 independent
+// wavefronts per path.
+//
+// Small batches of wide, deep signatures (e.g. 32 paths of 8 channels at depth 5) are bound by the
+// chain of dependent increments, not by arithmetic: the only way to use the chip is to cut one path
+// into many independent pieces.  The words that start with a given two-letter prefix f = f_1 f_2,
+// together with f_1 and f_1 f_2 themselves, are closed under the fused multiply-exponentiate (paper
+// section 4.1, eq. "fusedterm"), so each of the 64 prefixes gets a wavefront of its own that scans all
+// the increments and writes its own slice of every level.
+//
+// Register layout of shard f (lane = 8*w_3 + w_4; as a matrix-core lane: block = lane/4, q = lane%4):
+//   A_1[f_1], A_2[f_1 f_2]      the same scalar in every lane
+//   A_3[f w_3], A_4[f w_3 w_4]  one scalar per lane (A_3 replicated over w_4)
+//   A_5[f w_3 w_4 w_5]          2 groups (w_5 / 4) of 4 registers
+//   A_6[f w_3 .. w_6]           16 groups (w_5/4, w_5%4, w_6/4) of 4 registers
+// A level-k stage for k >= 5 is a batch of 4x4 outer products (v_mfma_f32_4x4x1_16b_f32): the left
+// operand a[i] sits in lane 4*block + i, i.e. letter w_{k-1} % 4 with the block carrying the letters
+// before it; the right operand is z[4*g + j] for the half g of the new letter.  Result register r, lane
+// q hold (w_{k-1}%4, w_k%4), which is again a left operand for the next level.  The top level swaps
+// the operands, so that a lane ends up with 4 consecutive words.
+#include "sig_internal.h"
+#include "sig_mfma_common.h"
+
+namespace sig {
+namespace {
+
+constexpr int kD8 = 8;
+constexpr int kTile8 = 64;  // increments staged in LDS at a time
+
+__host__ __device__ constexpr int level_off8(int k)  // offset of level k (1-based) in a d = 8 signature
+{
+    int off = 0, p = 1;
+    for (int j = 1; j < k; ++j) {
+        p *= kD8;
+        off += p;
+    }
+    return off;
+}
+
+template <int N>
+struct State8 {
+    float A1 = 0.0f, A2 = 0.0f, A3 = 0.0f, A4 = 0.0f;
+    f4 A5[2];
+    f4 A6[N >= 6 ? 16 : 1];
+};
+
+// This lane's view of one staged increment; X[m] is the value divided by m.
+template <int N>
+struct Row8 {
+    float zf1;
+    float zf2[N], z3[N], z4[N], zlo[N], zhi[N];
+};
+
+// `tab` points at one increment's scaled copies in LDS: tab[(m-1)*8 + c] = z[c]/m, m = 1..N-1.
+template <int N>
+__device__ __forceinline__ Row8<N> load_row8(const float *tab, int f1, int f2, int w3, int w4, int q)
+{
+    Row8<N> R;
+    R.zf1 = tab[f1];
+#pragma unroll
+    for (int m = 1; m <= N - 1; ++m) R.zf2[m] = tab[(m - 1) * 8 + f2];
+#pragma unroll
+    for (int m = 1; m <= N - 2; ++m) R.z3[m] = tab[(m - 1) * 8 + w3];
+#pragma unroll
+    for (int m = 1; m <= N - 3; ++m) R.z4[m] = tab[(m - 1) * 8 + w4];
+#pragma unroll
+    for (int m = 1; m <= N - 4; ++m) {
+        R.zlo[m] = tab[(m - 1) * 8 + q];
+        R.zhi[m] = tab[(m - 1) * 8 + 4 + q];
+    }
+    return R;
+}
+
+// One fused multiply-exponentiate restricted to the words of this shard.
+template <int N>
+__device__ __forceinline__ void step8(State8<N> &S, const Row8<N> &R)
+{
+    float t1[N + 1], t2[N + 1], t3[N + 1], t4[N + 1];
+#pragma unroll
+    for (int k = 2; k <= N; ++k) t1[k] = __builtin_fmaf(R.zf1, 1.0f / k, S.A1);
+#pragma unroll
+    for (int k = 2; k <= N; ++k) t2[k] = __builtin_fmaf(t1[k], R.zf2[k - 1], S.A2);
+#pragma unroll
+    for (int k = 3; k <= N; ++k) t3[k] = __builtin_fmaf(t2[k], R.z3[k - 2], S.A3);
+#pragma unroll
+    for (int k = 4; k <= N; ++k) t4[k] = __builtin_fmaf(t3[k], R.z4[k - 3], S.A4);
+
+    if constexpr (N >= 5) {
+        if constexpr (N >= 6) {
+            // T_6^(5), then the level-6 update (top level: operands swapped)
+            f4 t5[2];
+            t5[0] = outer4(t4[6], R.zlo[2], S.A5[0]);
+            t5[1] = outer4(t4[6], R.zhi[2], S.A5[1]);
+#pragma unroll
+            for (int g5 = 0; g5 < 2; ++g5)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    S.A6[(g5 * 4 + r) * 2 + 0] = outer4(R.zlo[1], t5[g5][r], S.A6[(g5 * 4 + r) * 2 + 0]);
+                    S.A6[(g5 * 4 + r) * 2 + 1] = outer4(R.zhi[1], t5[g5][r], S.A6[(g5 * 4 + r) * 2 + 1]);
+                }
+            S.A5[0] = outer4(t4[5], R.zlo[1], S.A5[0]);
+            S.A5[1] = outer4(t4[5], R.zhi[1], S.A5[1]);
+        } else {
+            S.A5[0] = outer4(R.zlo[1], t4[5], S.A5[0]);  // top level: operands swapped
+            S.A5[1] = outer4(R.zhi[1], t4[5], S.A5[1]);
+        }
+    }
+    S.A4 = t4[4];
+    S.A3 = t3[3];
+    S.A2 = t2[2];
+    S.A1 += R.zf1;
+}
+
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+
+template <int N>
+__global__ void __launch_bounds__(64)
+sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint)
+{
+    static_assert(N >= 4 && N <= 6, "depths served by this kernel");
+    constexpr int kRow = kD8 * (N - 1);
+    constexpr int kS = level_off8(N + 1);
+    __shared__ __align__(16) float lds[kTile8 * kRow];
+
+    const int lane = threadIdx.x;
+    const int w3 = lane >> 3, w4 = lane & 7, q = lane & 3;
+    const int64_t b = blockIdx.x >> 6;
+    const int f1 = (blockIdx.x >> 3) & 7, f2 = blockIdx.x & 7;
+    const f4 *x4 = reinterpret_cast<const f4 *>(path) + b * L * 2;  // 2 chunks of 16 bytes per point
+    float *o = out + b * kS;
+
+    State8<N> S;
+    S.A5[0] = S.A5[1] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int g = 0; g < (N >= 6 ? 16 : 1); ++g) S.A6[g] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+
+    // the two points around increment number s (zeros past the end of the path); the points of a
+    // tile are fetched while the tile before it is being scanned
+    f4 hi0, hi1, lo0, lo1;
+    auto fetch_points = [&](int64_t s) {
+        hi0 = hi1 = lo0 = lo1 = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+        if (s < n_inc) {
+            const int64_t i_hi = basepoint ? s : s + 1;
+            hi0 = x4[i_hi * 2];
+            hi1 = x4[i_hi * 2 + 1];
+            if (i_hi > 0) {
+                lo0 = x4[(i_hi - 1) * 2];
+                lo1 = x4[(i_hi - 1) * 2 + 1];
+            }
+        }
+    };
+    fetch_points(lane);
+
+    for (int64_t t0 = 0; t0 < n_inc; t0 += kTile8) {
+        const int nt = int(n_inc - t0 < kTile8 ? n_inc - t0 : kTile8);
+        __syncthreads();
+        if (lane < nt) {
+            const f4 z0 = hi0 - lo0, z1 = hi1 - lo1;
+            f4 *row = reinterpret_cast<f4 *>(lds + lane * kRow);
+            row[0] = z0;
+            row[1] = z1;
+#pragma unroll
+            for (int m = 2; m <= N - 1; ++m) {
+                row[2 * (m - 1)] = z0 * (1.0f / m);
+                row[2 * (m - 1) + 1] = z1 * (1.0f / m);
+            }
+        }
+        __syncthreads();
+        fetch_points(t0 + kTile8 + lane);
+        int s = 0;
+        for (; s + 4 <= nt; s += 4) {
+            Row8<N> R[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) R[i] = load_row8<N>(lds + (s + i) * kRow, f1, f2, w3, w4, q);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) step8<N>(S, R[i]);
+        }
+        for (; s < nt; ++s) step8<N>(S, load_row8<N>(lds + s * kRow, f1, f2, w3, w4, q));
+    }
+
+    // store this shard's slice of every level
+    const int f = f1 * 8 + f2;
+    if (f2 == 0 && lane == 0) o[f1] = S.A1;
+    if (lane == 0) o[level_off8(2) + f] = S.A2;
+    if (w4 == 0) o[level_off8(3) + f * 8 + w3] = S.A3;
+    o[level_off8(4) + f * 64 + lane] = S.A4;
+    if constexpr (N == 5) {
+        // register r, lane (block, q) of group g: word 8*(lane/4 * 4 + q) + 4*g + r of the 512-word slice
+        f4 *o5 = reinterpret_cast<f4 *>(o + level_off8(5) + f * 512);
+#pragma unroll
+        for (int g = 0; g < 2; ++g) o5[lane * 2 + g] = S.A5[g];
+    }
+    if constexpr (N == 6) {
+        // level 5 in chaining orientation: register r = w_4 % 4, lane q = w_5 % 4
+        float *o5 = o + level_off8(5) + f * 512;
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o5[(w3 * 8 + 4 * ((lane >> 2) & 1) + r) * 8 + 4 * g + q] = S.A5[g][r];
+        // level 6 (swapped): group (g5, r5, g6), register r = w_6 % 4, lane q = w_5 % 4
+        f4 *o6 = reinterpret_cast<f4 *>(o + level_off8(6) + f * 4096);
+#pragma unroll
+        for (int g5 = 0; g5 < 2; ++g5)
+#pragma unroll
+            for (int r5 = 0; r5 < 4; ++r5)
+#pragma unroll
+                for (int g6 = 0; g6 < 2; ++g6) {
+                    const int w4v = 4 * ((lane >> 2) & 1) + r5, w5v = 4 * g5 + q;
+                    o6[(((w3 * 8 + w4v) * 8 + w5v) * 8 + 4 * g6) / 4] = S.A6[(g5 * 4 + r5) * 2 + g6];
+                }
+    }
+}
+
+template <int N>
+hipError_t launch8(const Shape &sh, const float *path, float *out, hipStream_t st)
+{
+    hipLaunchKernelGGL(sig_mfma_d8_shard_kernel<N>, dim3(static_cast<unsigned>(sh.B * 64)), dim3(64), 0, st, path, out,
+                       sh.L, sh.n_inc, sh.basepoint);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+const char *mfma_d8_kernel_name(const Shape &sh)
+{
+    if (sh.d != 8 || sh.N < 4 || sh.N > 6 || sh.stream || sh.B > 0x1ffffff) return nullptr;
+    return "mfma_d8_shard";
+}
+
+hipError_t launch_mfma_d8_f32(const Shape &sh, const float *path, float *out, hipStream_t st)
+{
+    if (mfma_d8_kernel_name(sh) == nullptr) return hipErrorNotSupported;
+    switch (sh.N) {
+        case 4: return launch8<4>(sh, path, out, st);
+        case 5: return launch8<5>(sh, path, out, st);
+        case 6: return launch8<6>(sh, path, out, st);
+    }
+    return hipErrorNotSupported;
+}
+
+}  // namespace sig

@@ -168,6 +168,15 @@ def test_d16_matrix_core_kernel(B, L):
         check(x, 4, basepoint=bp, variant=sig.SIG_VARIANT_MFMA)
 
 
+@pytest.mark.parametrize("B,L,N", [(1, 2, 4), (2, 3, 5), (1, 4, 6), (3, 9, 5), (2, 64, 5), (1, 65, 6), (2, 66, 4),
+                                   (2, 130, 5), (1, 200, 5)])
+def test_d8_matrix_core_kernel(B, L, N):
+    x = brownian_paths(B, L, 8, seed=800 + L) if L > 20 else uniform_paths(B, L, 8, seed=800 + L, lo=-0.4, hi=0.4)
+    assert sig.sig_variant_name(B, L, 8, N, False, False, variant=sig.SIG_VARIANT_MFMA) == "mfma_d8_shard"
+    for bp in (False, True):
+        check(x, N, basepoint=bp, variant=sig.SIG_VARIANT_MFMA)
+
+
 def test_unaligned_buffers_fall_back_to_the_generic_kernel():
     torch = torch_mod()
     w = WORKLOADS[1]
