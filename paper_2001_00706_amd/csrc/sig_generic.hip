@@ -26,7 +26,9 @@ namespace {
 constexpr int kMaxThreads = 1024;
 constexpr size_t kLdsBudget = 64 * 1024;  // dynamic LDS a workgroup may ask for without opting in
 
-template <typename T>
+// I: type of the word indices inside one signature (32-bit whenever S < 2^31: integer division,
+// which decodes the letters of a word, is several times cheaper than in 64 bits).
+template <typename T, typename I>
 __global__ void __launch_bounds__(kMaxThreads)
 sig_generic_kernel(Shape sh, const T *__restrict__ path, T *out, int state_in_lds)
 {
@@ -75,20 +77,20 @@ sig_generic_kernel(Shape sh, const T *__restrict__ path, T *out, int state_in_ld
             __syncthreads();
 
             for (int k = N; k >= 1; --k) {
-                const int64_t n_pref = sh.pw[k - 1];
-                for (int64_t p = tid; p < n_pref; p += nt) {
+                const I n_pref = I(sh.pw[k - 1]);
+                for (I p = tid; p < n_pref; p += nt) {
                     T u = T(0);
                     if (k >= 2) {
-                        int64_t q = p / sh.pw[k - 2];  // first letter
-                        u = zs[(k - 1) * d + q] + (prev ? prev[sh.off[1] + q] : T(0));
+                        I q = p / I(sh.pw[k - 2]);  // first letter
+                        u = zs[(k - 1) * d + q] + (prev ? prev[I(sh.off[1]) + q] : T(0));
                         for (int i = 2; i <= k - 1; ++i) {
-                            q = p / sh.pw[k - 1 - i];  // index of the i-letter prefix
-                            const int w = int(q % d);  // its last letter
-                            u = u * zs[(k - i) * d + w] + (prev ? prev[sh.off[i] + q] : T(0));
+                            q = p / I(sh.pw[k - 1 - i]);   // index of the i-letter prefix
+                            const int w = int(q % I(d));   // its last letter
+                            u = u * zs[(k - i) * d + w] + (prev ? prev[I(sh.off[i]) + q] : T(0));
                         }
                     }
-                    T *dst = cur + sh.off[k] + p * d;
-                    const T *src = prev ? prev + sh.off[k] + p * d : nullptr;
+                    T *dst = cur + I(sh.off[k]) + p * I(d);
+                    const T *src = prev ? prev + I(sh.off[k]) + p * I(d) : nullptr;
                     if (k >= 2) {
                         for (int j = 0; j < d; ++j) dst[j] = u * zs[j] + (src ? src[j] : T(0));
                     } else {
@@ -129,7 +131,11 @@ hipError_t launch_generic(const Shape &sh, const T *path, T *out, hipStream_t st
     while (threads < kMaxThreads && threads < widest) threads *= 2;
     const int64_t max_grid = 1 << 20;
     const unsigned grid = unsigned(sh.B < max_grid ? sh.B : max_grid);
-    hipLaunchKernelGGL(sig_generic_kernel<T>, dim3(grid), dim3(threads), lds, st, sh, path, out, state_in_lds);
+    if (sh.S < (int64_t(1) << 31)) {
+        hipLaunchKernelGGL((sig_generic_kernel<T, uint32_t>), dim3(grid), dim3(threads), lds, st, sh, path, out, state_in_lds);
+    } else {
+        hipLaunchKernelGGL((sig_generic_kernel<T, int64_t>), dim3(grid), dim3(threads), lds, st, sh, path, out, state_in_lds);
+    }
     return hipGetLastError();
 }
 

@@ -51,22 +51,29 @@ struct Row8 {
     float zf2[N], z3[N], z4[N], zlo[N], zhi[N];
 };
 
-// `tab` points at one increment's scaled copies in LDS: tab[(m-1)*8 + c] = z[c]/m, m = 1..N-1.
+// `tab` points at one staged increment z[0..7] in LDS.  Eight wavefronts share a compute unit's
+// LDS port, so only z itself is read from LDS and the scalings z/m are formed in registers.
 template <int N>
 __device__ __forceinline__ Row8<N> load_row8(const float *tab, int f1, int f2, int w3, int w4, int q)
 {
     Row8<N> R;
     R.zf1 = tab[f1];
+    const float zf2 = tab[f2], z3 = tab[w3], z4 = tab[w4], zlo = tab[q], zhi = tab[4 + q];
+    R.zf2[1] = zf2;
+    R.z3[1] = z3;
+    R.z4[1] = z4;
+    R.zlo[1] = zlo;
+    R.zhi[1] = zhi;
 #pragma unroll
-    for (int m = 1; m <= N - 1; ++m) R.zf2[m] = tab[(m - 1) * 8 + f2];
+    for (int m = 2; m <= N - 1; ++m) R.zf2[m] = zf2 * (1.0f / m);
 #pragma unroll
-    for (int m = 1; m <= N - 2; ++m) R.z3[m] = tab[(m - 1) * 8 + w3];
+    for (int m = 2; m <= N - 2; ++m) R.z3[m] = z3 * (1.0f / m);
 #pragma unroll
-    for (int m = 1; m <= N - 3; ++m) R.z4[m] = tab[(m - 1) * 8 + w4];
+    for (int m = 2; m <= N - 3; ++m) R.z4[m] = z4 * (1.0f / m);
 #pragma unroll
-    for (int m = 1; m <= N - 4; ++m) {
-        R.zlo[m] = tab[(m - 1) * 8 + q];
-        R.zhi[m] = tab[(m - 1) * 8 + 4 + q];
+    for (int m = 2; m <= N - 4; ++m) {
+        R.zlo[m] = zlo * (1.0f / m);
+        R.zhi[m] = zhi * (1.0f / m);
     }
     return R;
 }
@@ -118,7 +125,7 @@ __global__ void __launch_bounds__(64)
 sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint)
 {
     static_assert(N >= 4 && N <= 6, "depths served by this kernel");
-    constexpr int kRow = kD8 * (N - 1);
+    constexpr int kRow = kD8;  // floats per staged increment
     constexpr int kS = level_off8(N + 1);
     __shared__ __align__(16) float lds[kTile8 * kRow];
 
@@ -159,11 +166,6 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
             f4 *row = reinterpret_cast<f4 *>(lds + lane * kRow);
             row[0] = z0;
             row[1] = z1;
-#pragma unroll
-            for (int m = 2; m <= N - 1; ++m) {
-                row[2 * (m - 1)] = z0 * (1.0f / m);
-                row[2 * (m - 1) + 1] = z1 * (1.0f / m);
-            }
         }
         __syncthreads();
         fetch_points(t0 + kTile8 + lane);
