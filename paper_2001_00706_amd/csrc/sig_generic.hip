@@ -30,11 +30,12 @@ constexpr size_t kLdsBudget = 64 * 1024;  // dynamic LDS a workgroup may ask for
 // which decodes the letters of a word, is several times cheaper than in 64 bits).
 template <typename T, typename I>
 __global__ void __launch_bounds__(kMaxThreads)
-sig_generic_kernel(Shape sh, const T *__restrict__ path, T *out, int state_in_lds)
+sig_generic_kernel(Shape sh, const T *__restrict__ path, T *out, int state_in_lds, int tile)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     T *zs = reinterpret_cast<T *>(smem_raw);  // zs[(m-1)*d + c] = z[c] / m, m = 1..N
-    T *lds_state = zs + int64_t(sh.N) * sh.d;
+    T *zinc = zs + int64_t(sh.N) * sh.d;      // increments of the current tile, [tile][d]
+    T *lds_state = zinc + int64_t(tile) * sh.d;
 
     const int tid = threadIdx.x;
     const int nt = blockDim.x;
@@ -56,19 +57,31 @@ sig_generic_kernel(Shape sh, const T *__restrict__ path, T *out, int state_in_ld
         __syncthreads();
 
         for (int64_t s = 0; s < sh.n_inc; ++s) {
-            // increment s and its scalings z/1 .. z/N (true divisions)
+            const int in_tile = int(s % tile);
+            if (in_tile == 0) {
+                // stage the increments of the next `tile` steps: one trip to memory per tile, not per step
+                const int64_t left = sh.n_inc - s;
+                const int n_stage = int(left < tile ? left : tile) * d;
+                for (int i = tid; i < n_stage; i += nt) {
+                    const int64_t si = s + i / d;
+                    const int c = i % d;
+                    T hi, lo;
+                    if (sh.basepoint) {
+                        hi = x[si * d + c];
+                        lo = si == 0 ? T(0) : x[(si - 1) * d + c];
+                    } else {
+                        hi = x[(si + 1) * d + c];
+                        lo = x[si * d + c];
+                    }
+                    zinc[i] = hi - lo;
+                }
+                __syncthreads();
+            }
+            // the scalings z/1 .. z/N of increment s (true divisions)
             for (int i = tid; i < N * d; i += nt) {
                 const int m = i / d + 1;
                 const int c = i - (m - 1) * d;
-                T hi, lo;
-                if (sh.basepoint) {
-                    hi = x[s * d + c];
-                    lo = s == 0 ? T(0) : x[(s - 1) * d + c];
-                } else {
-                    hi = x[(s + 1) * d + c];
-                    lo = x[s * d + c];
-                }
-                zs[i] = (hi - lo) / T(m);
+                zs[i] = zinc[in_tile * d + c] / T(m);
             }
             if (sh.stream) {
                 cur = obase + s * S;
@@ -120,7 +133,14 @@ sig_generic_kernel(Shape sh, const T *__restrict__ path, T *out, int state_in_ld
 template <typename T>
 hipError_t launch_generic(const Shape &sh, const T *path, T *out, hipStream_t st)
 {
-    const size_t zs_bytes = sizeof(T) * size_t(sh.N) * size_t(sh.d);
+    size_t zs_bytes = sizeof(T) * size_t(sh.N) * size_t(sh.d);
+    if (zs_bytes > kLdsBudget) return hipErrorInvalidValue;
+    // increments staged per tile: up to 8 KB of them, at least one
+    int64_t tile = int64_t(8192 / (sizeof(T) * size_t(sh.d)));
+    if (tile < 1) tile = 1;
+    if (tile > sh.n_inc) tile = sh.n_inc;
+    while (tile > 1 && zs_bytes + sizeof(T) * size_t(tile) * size_t(sh.d) > kLdsBudget) tile /= 2;
+    zs_bytes += sizeof(T) * size_t(tile) * size_t(sh.d);
     if (zs_bytes > kLdsBudget) return hipErrorInvalidValue;
     const size_t state_bytes = sizeof(T) * size_t(sh.S);
     const int state_in_lds = (!sh.stream && zs_bytes + state_bytes <= kLdsBudget) ? 1 : 0;
@@ -132,9 +152,9 @@ hipError_t launch_generic(const Shape &sh, const T *path, T *out, hipStream_t st
     const int64_t max_grid = 1 << 20;
     const unsigned grid = unsigned(sh.B < max_grid ? sh.B : max_grid);
     if (sh.S < (int64_t(1) << 31)) {
-        hipLaunchKernelGGL((sig_generic_kernel<T, uint32_t>), dim3(grid), dim3(threads), lds, st, sh, path, out, state_in_lds);
+        hipLaunchKernelGGL((sig_generic_kernel<T, uint32_t>), dim3(grid), dim3(threads), lds, st, sh, path, out, state_in_lds, int(tile));
     } else {
-        hipLaunchKernelGGL((sig_generic_kernel<T, int64_t>), dim3(grid), dim3(threads), lds, st, sh, path, out, state_in_lds);
+        hipLaunchKernelGGL((sig_generic_kernel<T, int64_t>), dim3(grid), dim3(threads), lds, st, sh, path, out, state_in_lds, int(tile));
     }
     return hipGetLastError();
 }
@@ -144,7 +164,7 @@ hipError_t launch_generic(const Shape &sh, const T *path, T *out, hipStream_t st
 bool generic_supported(const Shape &sh, sig_dtype dtype)
 {
     const size_t elem = dtype == SIG_F64 ? sizeof(double) : sizeof(float);
-    return elem * size_t(sh.N) * size_t(sh.d) <= kLdsBudget;
+    return elem * (size_t(sh.N) + 1) * size_t(sh.d) <= kLdsBudget;  // the scalings and one staged increment
 }
 
 hipError_t launch_generic_f32(const Shape &sh, const float *path, float *out, hipStream_t st)
