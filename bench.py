@@ -30,6 +30,21 @@ def flops_per_increment(d: int, N: int, fused_fmas: int) -> int:
     return 2 * fused_fmas + d * (2 * N - 1)
 
 
+def recorded_traffic(workload_key: str, kernel: str):
+    """HBM bytes per launch (fetched + written) recorded from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    runs of this command (see profiles/); None if no record matches the workload and kernel."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    try:
+        with open(path) as fh:
+            for line in fh:
+                parts = line.split()
+                if len(parts) == 4 and parts[0] == workload_key and parts[1] == kernel:
+                    return int(parts[2]) + int(parts[3])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -38,6 +53,10 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=2, help="configuration number 1..5 (default: the metric's)")
     ap.add_argument("--variant", choices=["auto", "generic", "mfma"], default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 256 MiB device-to-device copies before the timed region, so that "
+                         "a rocprofv3 --pmc run of this command sees a copy kernel of known size next to the "
+                         "signature kernel (used to scale FETCH_SIZE / WRITE_SIZE into bytes)")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -70,6 +89,14 @@ def main() -> int:
 
     def step():
         sig.sig_forward(x, w.N, stream=w.stream, basepoint=w.basepoint, out=out, variant=variant)
+
+    if args.copy_calibration:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)   # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -107,7 +134,7 @@ def main() -> int:
         roofline = {"bound": bound, "achieved": flops / (kern_ms * 1e-3) / 1e12, "peak": PEAK_FP32_TFLOPS,
                     "unit": "TFLOP/s"}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
-    roofline["traffic"] = None
+    roofline["traffic"] = recorded_traffic(f"cfg{w.index}", kernel)
     roofline["kernel"] = kernel
     roofline["kernel_ms_avg"] = kern_ms
     roofline["kernel_ms_min"] = float(durs_ms.min())
