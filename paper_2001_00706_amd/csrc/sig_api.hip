@@ -52,7 +52,7 @@ sig_status make_shape(int64_t B, int64_t L, int d, int N, int stream, int basepo
     return SIG_OK;
 }
 
-enum class Family { Generic, Mfma, MfmaPair, MfmaShard, MfmaD16, MfmaD8, None };
+enum class Family { Generic, Mfma, MfmaPair, MfmaShard, MfmaD16, MfmaD8, Small, None };
 
 // The pointers decide only alignment: the matrix-core family loads and stores 16 bytes per lane.
 Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const void *path, const void *out)
@@ -64,6 +64,7 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
     const bool d16_ok = dtype == SIG_F32 && aligned && sig::mfma_d16_kernel_name(sh) != nullptr;
     const bool d8_ok = dtype == SIG_F32 && aligned && sig::mfma_d8_kernel_name(sh) != nullptr;
     const bool generic_ok = sig::generic_supported(sh, dtype);
+    const bool small_ok = sig::small_supported(sh);
     switch (variant) {
         case SIG_VARIANT_AUTO:
             // the two-wavefront family is measured slower than the one-wavefront one on every
@@ -74,12 +75,14 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
             if (mfma_ok) return Family::Mfma;
             if (d16_ok) return Family::MfmaD16;
             if (d8_ok) return Family::MfmaD8;
+            if (small_ok) return Family::Small;
             return generic_ok ? Family::Generic : Family::None;
         case SIG_VARIANT_GENERIC: return generic_ok ? Family::Generic : Family::None;
         case SIG_VARIANT_MFMA:
             return mfma_ok ? Family::Mfma : d16_ok ? Family::MfmaD16 : d8_ok ? Family::MfmaD8 : Family::None;
         case SIG_VARIANT_MFMA_PAIR: return pair_ok ? Family::MfmaPair : Family::None;
         case SIG_VARIANT_MFMA_SHARD: return shard_ok ? Family::MfmaShard : Family::None;
+        case SIG_VARIANT_SMALL: return small_ok ? Family::Small : Family::None;
     }
     return Family::None;
 }
@@ -88,7 +91,7 @@ bool valid_enums(sig_dtype dtype, sig_variant variant)
 {
     return (dtype == SIG_F32 || dtype == SIG_F64) &&
            (variant == SIG_VARIANT_AUTO || variant == SIG_VARIANT_GENERIC || variant == SIG_VARIANT_MFMA ||
-            variant == SIG_VARIANT_MFMA_PAIR || variant == SIG_VARIANT_MFMA_SHARD);
+            variant == SIG_VARIANT_MFMA_PAIR || variant == SIG_VARIANT_MFMA_SHARD || variant == SIG_VARIANT_SMALL);
 }
 
 }  // namespace
@@ -144,6 +147,11 @@ sig_status sig_forward_variant(const void *path, int64_t B, int64_t L, int d, in
         case Family::MfmaD8:
             err = sig::launch_mfma_d8_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
             break;
+        case Family::Small:
+            err = dtype == SIG_F32
+                      ? sig::launch_small_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
+                      : sig::launch_small_f64(sh, static_cast<const double *>(path), static_cast<double *>(out), hip_stream);
+            break;
         case Family::Generic:
             err = dtype == SIG_F32
                       ? sig::launch_generic_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
@@ -174,6 +182,7 @@ const char *sig_variant_name(int64_t B, int64_t L, int d, int N, int stream, int
         case Family::MfmaShard: return sig::mfma_shard_kernel_name(sh);
         case Family::MfmaD16: return sig::mfma_d16_kernel_name(sh);
         case Family::MfmaD8: return sig::mfma_d8_kernel_name(sh);
+        case Family::Small: return "small";
         case Family::Generic: return "generic";
         case Family::None: break;
     }

@@ -27,6 +27,11 @@ bool generic_supported(const Shape &sh, sig_dtype dtype);
 hipError_t launch_generic_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_generic_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
 
+// Small-state family: S <= 512 scalars, one wavefront per path, state in LDS, words decoded once.
+bool small_supported(const Shape &sh);
+hipError_t launch_small_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
+hipError_t launch_small_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
+
 // Matrix-core families (fp32 only): one wavefront per path, or (`pair`) a producer/consumer pair
 // of wavefronts per path.  `mfma_kernel_name` returns nullptr for shapes the family cannot serve.
 const char *mfma_kernel_name(const Shape &sh, bool pair);

@@ -73,8 +73,8 @@ def check(x, N, stream=False, basepoint=False, variant=sig.SIG_VARIANT_AUTO, sam
 
 
 VARIANTS = [sig.SIG_VARIANT_AUTO, sig.SIG_VARIANT_GENERIC, sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_PAIR,
-            sig.SIG_VARIANT_MFMA_SHARD]
-VARIANT_IDS = ["auto", "generic", "mfma", "mfma_pair", "mfma_shard"]
+            sig.SIG_VARIANT_MFMA_SHARD, sig.SIG_VARIANT_SMALL]
+VARIANT_IDS = ["auto", "generic", "mfma", "mfma_pair", "mfma_shard", "small"]
 
 
 # ------------------------------------------------------------------ benchmark workloads
@@ -100,7 +100,8 @@ def test_small_workloads_every_path(w):
 
 # ------------------------------------------------------------------------ shape sweep
 SWEEP = [
-    # (B, L, d, N)
+    # (B, L, d, N); the last rows sit at the limits of the small-state family (S = 510, 363, 512 / d = 64)
+    (2, 70, 2, 8), (3, 9, 3, 5), (1, 5, 22, 2), (2, 4, 64, 1), (2, 130, 2, 4),
     (1, 2, 1, 1), (3, 2, 1, 5), (2, 5, 2, 1), (5, 3, 2, 2), (4, 17, 3, 4), (2, 9, 5, 3),
     (3, 6, 7, 3), (2, 33, 2, 7), (1, 4, 6, 4), (7, 12, 4, 4), (2, 5, 9, 2), (3, 70, 3, 5),
     (2, 11, 4, 6), (5, 19, 8, 3), (2, 7, 16, 3), (1, 3, 33, 2),
@@ -112,12 +113,15 @@ SWEEP = [
 @pytest.mark.parametrize("B,L,d,N", SWEEP)
 def test_shape_sweep(B, L, d, N, dtype, variant):
     x = uniform_paths(B, L, d, seed=1000 + 7 * L + d, lo=-0.5, hi=0.5).astype(dtype)
+    ran = []
     for stream in (False, True):
         for basepoint in (False, True):
-            check(x, N, stream=stream, basepoint=basepoint, variant=variant)
+            ran.append(check(x, N, stream=stream, basepoint=basepoint, variant=variant) is not None)
+    if not any(ran):
+        pytest.skip("kernel family does not serve this shape")
 
 
-@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
+@pytest.mark.parametrize("variant", VARIANTS[:2], ids=VARIANT_IDS[:2])
 def test_state_too_large_for_lds(variant):
     # d = 16, N = 4: 69904 scalars per path, several tiles of every level and ragged tails
     x = brownian_paths(3, 9, 16, seed=77)
@@ -225,11 +229,12 @@ def test_empty_batch():
     assert tuple(sig.sig_forward(x, 3, stream=True).shape) == (0, 4, 39)
 
 
-def test_many_paths_more_than_one_grid_pass():
+@pytest.mark.parametrize("variant", [sig.SIG_VARIANT_GENERIC, sig.SIG_VARIANT_SMALL], ids=["generic", "small"])
+def test_many_paths_more_than_one_grid_pass(variant):
     # more paths than the launch has workgroups: the grid-stride loop over paths
     B = (1 << 20) + 37
     x = uniform_paths(B, 2, 1, seed=3)
-    got = gpu_signature(x, 2, variant=sig.SIG_VARIANT_GENERIC)
+    got = gpu_signature(x, 2, variant=variant)
     dz = (x[:, 1, 0].astype(np.float64) - x[:, 0, 0])
     np.testing.assert_allclose(got[:, 0], dz, rtol=1e-6, atol=1e-7)
     np.testing.assert_allclose(got[:, 1], dz * dz / 2, rtol=1e-5, atol=1e-7)
