@@ -38,6 +38,52 @@ __device__ __forceinline__ f16v outer16(float a, float b, f16v c)
     return __builtin_amdgcn_mfma_f32_16x16x1f32(a, b, c, 0, 0, 0);
 }
 
+// This lane's view of one staged increment.
+struct Row16 {
+    float zw, zx, zB, zC;   // z[w1], z[x], z[x]/(k-1), z[x]/(k-2) for this lane's block target k
+};
+
+__device__ __forceinline__ Row16 load_row16(const float *tab, int w1, int x, int off_zB, int off_zC)
+{
+    Row16 r;
+    r.zw = tab[w1];
+    r.zx = tab[x];
+    r.zB = tab[off_zB];
+    r.zC = tab[off_zC];
+    return r;
+}
+
+// Folds one increment into levels 1..3 (result in `cur`) and the previous increment's pending
+// T_4^(3) (in `prev`, with its z[x] in `pzx`) into level 4.
+__device__ __forceinline__ void half_trip(float &A1, float &A2, f16v (&A4)[8], const f16v &prev, f16v &cur, float &pzx,
+                                          const Row16 &r, float inv_k)
+{
+    // level 1 and 2 terms of this block's target level k, then the level-2 update itself
+    const float t1 = __builtin_fmaf(r.zw, inv_k, A1);        // z[w1]/k + A_1[w1]
+    const float t2 = __builtin_fmaf(t1, r.zB, A2);           // T_k^(2)[w1, x]
+    const float u1 = __builtin_fmaf(r.zw, 0.5f, A1);         // target level 2
+    A2 = __builtin_fmaf(u1, r.zx, A2);
+    A1 += r.zw;
+
+    // level 3: blocks 0,1 -> T_4^(3) = T_4^(2) (x) z/2 + A_3 ; blocks 2,3 -> A_3 <- T_3^(2) (x) z + A_3
+    f16v C3;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        C3[i] = prev[8 + i];
+        C3[8 + i] = prev[8 + i];
+    }
+    cur = outer16(t2, r.zC, C3);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // level 4 of the previous increment: A_4 += T_4^(3) (x) z
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int ee = 0; ee < 2; ++ee) A4[2 * c + ee] = outer16(prev[4 * ee + c], pzx, A4[2 * c + ee]);
+    pzx = r.zx;
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 __global__ void __launch_bounds__(512)
 sig_mfma_d16_n4_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint)
 {
@@ -57,14 +103,19 @@ sig_mfma_d16_n4_kernel(const float *__restrict__ path, float *__restrict__ out, 
     // state
     float A1 = 0.0f;                  // A_1[w1]
     float A2 = 0.0f;                  // A_2[w1, x]
-    f16v A3;                          // blocks 2,3 (registers 8..15): A_3[w1, 4*(lane/16) + c, x], register 4*b + c
+    // Result of the last level-3 instruction: registers 0..7 (blocks 0,1) = T_4^(3) of that increment,
+    // still to be folded into level 4; registers 8..15 (blocks 2,3) = A_3[w1, 4*(lane/16) + c, x], register
+    // 4*b + c.  Two buffers, used alternately.
+    f16v Da, Db;
     f16v A4[8];                       // group (c, e'): index 2*c + e'
 #pragma unroll
-    for (int i = 0; i < 16; ++i) A3[i] = 0.0f;
+    for (int i = 0; i < 16; ++i) Da[i] = Db[i] = 0.0f;
 #pragma unroll
     for (int g = 0; g < 8; ++g)
 #pragma unroll
         for (int i = 0; i < 16; ++i) A4[g][i] = 0.0f;
+
+    float pzx = 0.0f;                 // z[x] of the increment whose level-4 update is pending
 
     // per-lane constants of the low-level stages
     const float inv_k = k4 ? 0.25f : 1.0f / 3.0f;            // 1/k of this block's target level
@@ -91,40 +142,31 @@ sig_mfma_d16_n4_kernel(const float *__restrict__ path, float *__restrict__ out, 
         }
         __syncthreads();
 
-        for (int s = 0; s < nt; ++s) {
-            const float *tab = lds + s * kRow16;
-            const float zw = tab[w1];         // z[w1]
-            const float zx = tab[x];          // z[x]
-            const float zB = tab[off_zB];
-            const float zC = tab[off_zC];
-
-            // level 1 and 2 terms of this block's target level k, then the level-2 update itself
-            const float t1 = __builtin_fmaf(zw, inv_k, A1);        // z[w1]/k + A_1[w1]
-            const float t2 = __builtin_fmaf(t1, zB, A2);           // T_k^(2)[w1, x]
-            const float u1 = __builtin_fmaf(zw, 0.5f, A1);         // target level 2
-            const float A2n = __builtin_fmaf(u1, zx, A2);
-
-            // level 3: blocks 0,1 -> T_4^(3) = T_4^(2) (x) z/2 + A_3 ; blocks 2,3 -> A_3 <- T_3^(2) (x) z + A_3
-            f16v C3;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                C3[i] = A3[8 + i];
-                C3[8 + i] = A3[8 + i];
-            }
-            const f16v D3 = outer16(t2, zC, C3);
-
-            // level 4: A_4 += T_4^(3) (x) z
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-#pragma unroll
-                for (int ee = 0; ee < 2; ++ee) A4[2 * c + ee] = outer16(D3[4 * ee + c], zx, A4[2 * c + ee]);
-
-#pragma unroll
-            for (int i = 8; i < 16; ++i) A3[i] = D3[i];
-            A2 = A2n;
-            A1 += zw;
+        // Software pipeline, two increments per trip with two result buffers (no register copies of
+        // matrix results on the critical path): in each half-trip the level-3 instruction of the new
+        // increment is issued first, then the eight level-4 instructions of the increment before it.
+        // Level 4 feeds nothing else and level 3 needs only levels 1..3, so the matrix pipe never
+        // waits for a result: the eight long instructions cover the latency of the level-3 result.
+        Row16 r = load_row16(lds, w1, x, off_zB, off_zC);
+        int s = 0;
+        for (; s + 2 <= nt; s += 2) {
+            const Row16 r1 = load_row16(lds + (s + 1) * kRow16, w1, x, off_zB, off_zC);
+            half_trip(A1, A2, A4, Da, Db, pzx, r, inv_k);
+            const Row16 r2 = load_row16(lds + (s + 2 < nt ? s + 2 : s + 1) * kRow16, w1, x, off_zB, off_zC);
+            half_trip(A1, A2, A4, Db, Da, pzx, r1, inv_k);
+            r = r2;
+        }
+        if (s < nt) {
+            half_trip(A1, A2, A4, Da, Db, pzx, r, inv_k);
+            Da = Db;   // keep "Da = result of the last increment" across tiles (odd tile length only)
         }
     }
+    // the last increment's level-4 update is still pending
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int ee = 0; ee < 2; ++ee) A4[2 * c + ee] = outer16(Da[4 * ee + c], pzx, A4[2 * c + ee]);
+    f16v A3 = Da;   // registers 8..15 hold A_3
 
     // store (levels concatenated, lexicographic word order)
     float *o = out + path_no * kS16;
