@@ -50,11 +50,9 @@ typedef enum {
     SIG_VARIANT_MFMA = 2,     /* fp32, final mode, state in registers, outer products on the matrix cores:
                                  d = 4, N = 4..6 (one wavefront per path); d = 8, N = 4..6 (64 wavefronts per
                                  path); d = 16, N = 4 (8 wavefronts per path) */
-    SIG_VARIANT_MFMA_PAIR = 3,/* fp32, d = 4, N = 5..6, final mode: as above with the low levels and the
-                                 outer products of a path on two cooperating wavefronts */
-    SIG_VARIANT_MFMA_SHARD = 4,/* fp32, d = 4, N = 4..7, final and stream mode: four independent wavefronts
+    SIG_VARIANT_MFMA_SHARD = 3,/* fp32, d = 4, N = 4..7, final and stream mode: four independent wavefronts
                                  per path, one per first letter */
-    SIG_VARIANT_SMALL = 5     /* any dtype and mode, S <= 512, N <= 8, d <= 64: one wavefront per path, state in LDS */
+    SIG_VARIANT_SMALL = 4     /* any dtype and mode, S <= 512, N <= 8, d <= 64: one wavefront per path, state in LDS */
 } sig_variant;
 
 /* Largest depth the kernels accept. */

@@ -15,7 +15,6 @@ from .binding import (  # noqa: F401
     SIG_VARIANT_AUTO,
     SIG_VARIANT_GENERIC,
     SIG_VARIANT_MFMA,
-    SIG_VARIANT_MFMA_PAIR,
     SIG_VARIANT_MFMA_SHARD,
     SIG_VARIANT_SMALL,
     SigError,

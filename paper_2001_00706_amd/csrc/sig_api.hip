@@ -52,14 +52,13 @@ sig_status make_shape(int64_t B, int64_t L, int d, int N, int stream, int basepo
     return SIG_OK;
 }
 
-enum class Family { Generic, Mfma, MfmaPair, MfmaShard, MfmaD16, MfmaD8, Small, None };
+enum class Family { Generic, Mfma, MfmaShard, MfmaD16, MfmaD8, Small, None };
 
 // The pointers decide only alignment: the matrix-core family loads and stores 16 bytes per lane.
 Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const void *path, const void *out)
 {
     const bool aligned = reinterpret_cast<uintptr_t>(out) % 16 == 0 && reinterpret_cast<uintptr_t>(path) % 16 == 0;
-    const bool mfma_ok = dtype == SIG_F32 && aligned && sig::mfma_kernel_name(sh, false) != nullptr;
-    const bool pair_ok = dtype == SIG_F32 && aligned && sig::mfma_kernel_name(sh, true) != nullptr;
+    const bool mfma_ok = dtype == SIG_F32 && aligned && sig::mfma_kernel_name(sh) != nullptr;
     const bool shard_ok = dtype == SIG_F32 && aligned && sig::mfma_shard_kernel_name(sh) != nullptr;
     const bool d16_ok = dtype == SIG_F32 && aligned && sig::mfma_d16_kernel_name(sh) != nullptr;
     const bool d8_ok = dtype == SIG_F32 && aligned && sig::mfma_d8_kernel_name(sh) != nullptr;
@@ -67,8 +66,6 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
     const bool small_ok = sig::small_supported(sh);
     switch (variant) {
         case SIG_VARIANT_AUTO:
-            // the two-wavefront family is measured slower than the one-wavefront one on every
-            // shape tried so far, so it is only ever chosen explicitly
             // four wavefronts per path when one per path would leave most of the chip idle, when every
             // prefix is stored (stream mode) or when the state does not fit one wavefront (N = 7)
             if (shard_ok && (!mfma_ok || sh.B < 512)) return Family::MfmaShard;
@@ -80,7 +77,6 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
         case SIG_VARIANT_GENERIC: return generic_ok ? Family::Generic : Family::None;
         case SIG_VARIANT_MFMA:
             return mfma_ok ? Family::Mfma : d16_ok ? Family::MfmaD16 : d8_ok ? Family::MfmaD8 : Family::None;
-        case SIG_VARIANT_MFMA_PAIR: return pair_ok ? Family::MfmaPair : Family::None;
         case SIG_VARIANT_MFMA_SHARD: return shard_ok ? Family::MfmaShard : Family::None;
         case SIG_VARIANT_SMALL: return small_ok ? Family::Small : Family::None;
     }
@@ -91,7 +87,7 @@ bool valid_enums(sig_dtype dtype, sig_variant variant)
 {
     return (dtype == SIG_F32 || dtype == SIG_F64) &&
            (variant == SIG_VARIANT_AUTO || variant == SIG_VARIANT_GENERIC || variant == SIG_VARIANT_MFMA ||
-            variant == SIG_VARIANT_MFMA_PAIR || variant == SIG_VARIANT_MFMA_SHARD || variant == SIG_VARIANT_SMALL);
+            variant == SIG_VARIANT_MFMA_SHARD || variant == SIG_VARIANT_SMALL);
 }
 
 }  // namespace
@@ -133,10 +129,7 @@ sig_status sig_forward_variant(const void *path, int64_t B, int64_t L, int d, in
     hipError_t err = hipSuccess;
     switch (resolve(sh, dtype, variant, path, out)) {
         case Family::Mfma:
-            err = sig::launch_mfma_f32(sh, false, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
-            break;
-        case Family::MfmaPair:
-            err = sig::launch_mfma_f32(sh, true, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
+            err = sig::launch_mfma_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
             break;
         case Family::MfmaShard:
             err = sig::launch_mfma_shard_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
@@ -177,8 +170,7 @@ const char *sig_variant_name(int64_t B, int64_t L, int d, int N, int stream, int
     sig::Shape sh;
     if (make_shape(B, L, d, N, stream, basepoint, sh) != SIG_OK) return "invalid";
     switch (resolve(sh, dtype, variant, nullptr, nullptr)) {
-        case Family::Mfma: return sig::mfma_kernel_name(sh, false);
-        case Family::MfmaPair: return sig::mfma_kernel_name(sh, true);
+        case Family::Mfma: return sig::mfma_kernel_name(sh);
         case Family::MfmaShard: return sig::mfma_shard_kernel_name(sh);
         case Family::MfmaD16: return sig::mfma_d16_kernel_name(sh);
         case Family::MfmaD8: return sig::mfma_d8_kernel_name(sh);

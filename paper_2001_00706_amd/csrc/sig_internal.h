@@ -32,10 +32,10 @@ bool small_supported(const Shape &sh);
 hipError_t launch_small_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_small_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
 
-// Matrix-core families (fp32 only): one wavefront per path, or (`pair`) a producer/consumer pair
-// of wavefronts per path.  `mfma_kernel_name` returns nullptr for shapes the family cannot serve.
-const char *mfma_kernel_name(const Shape &sh, bool pair);
-hipError_t launch_mfma_f32(const Shape &sh, bool pair, const float *path, float *out, hipStream_t st);
+// Matrix-core family for d = 4, N = 4..6, final mode (fp32): one wavefront per path.
+// `mfma_kernel_name` returns nullptr for shapes the family cannot serve.
+const char *mfma_kernel_name(const Shape &sh);
+hipError_t launch_mfma_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 
 // Matrix-core family with four wavefronts per path, one per first letter (fp32, d = 4, N = 4..7,
 // final and stream mode).

@@ -11,8 +11,8 @@
 // each slice's left factor depends on the state the previous slice produced.
 //
 // Register layout (lane = 16*w_1 + 4*w_2 + q, 0 <= q < 4):
-//   level 1..3 ("low levels", plain VALU, one scalar per lane, replicated where the level
-//       has fewer than 64 words):   A_1[w_1], A_2[w_1 w_2], A_3[w_1 w_2 q]   (q = w_3)
+//   level 2, 3 (plain VALU, one scalar per lane, level 2 replicated over q):
+//       A_2[w_1 w_2], A_3[w_1 w_2 q]   (q = w_3)
 //   level k >= 4 (matrix cores): 4^(k-4) groups of 4 registers; group g holds the words
 //       whose letters w_3..w_{k-2} spell g in base 4; register r of the group is letter
 //       w_{k-1} = r; lane q is the last letter w_k = q; the block index (lane / 4) is w_1 w_2.
@@ -20,14 +20,16 @@
 // the level-(k+1) stage (register r of group g feeds group 4g + r), and the B operand is
 // always z[lane & 3] times a reciprocal, so no data ever moves between lanes.
 //
+// Level 1 is not carried at all: A_1 after s increments is the displacement x_s - x_first, so the
+// innermost Horner terms z/k + A_1 of all target levels are tabulated, with the scaled increments
+// z/m, when a tile of points is staged in LDS.
+//
 // Levels are updated highest first; the temporaries T^(i) of a higher target level are
 // formed from the old A_i before A_i itself is overwritten, so the update is in place.
 //
-// A single wavefront issues in order, and on this chip vector and matrix-core instructions of
-// one wavefront do not overlap (alternating them is slower than running them in blocks), so a
-// step is laid out as one block of vector work followed by one block of outer products, and the
-// vector block is kept short: the scaled increments z/m come ready-made from an LDS table that
-// is filled once per tile of increments.
+// A lone wavefront on a SIMD issues in order and its vector and matrix-core instructions do not
+// overlap (alternating them is slower than running them in blocks), so the kernel is bound by
+// its instruction count: a step is 9 vector FMAs, 5 LDS reads and 27 outer products at N = 6.
 #include "sig_internal.h"
 #include "sig_mfma_common.h"
 
@@ -39,90 +41,75 @@ template <int N>
 constexpr int kChannels = (N == 4 ? 340 : N == 5 ? 1364 : 5460);
 constexpr int kOff4 = 84, kOff5 = 340, kOff6 = 1364;
 
-// Increments staged in LDS at a time.  Each staged increment takes 4*(N-1) floats (z/1 .. z/(N-1)).
-template <int N>
-constexpr int kTile = (N == 6 ? 256 : 64);
+// One staged increment is 64 floats (in a row of 68): for each channel c, 8 floats t1[c][k-2] = z[c]/k + A_1[c]
+// (k = 2..N, padded) at c*8, then 8 floats zs[c][m-1] = z[c]/m (m = 1..N-1, padded) at 32 + c*8.
+constexpr int kRow = 68;  // 64 used + 4 of padding: rows land on different LDS banks when 64 lanes write one row each
+constexpr int kTile = 64;  // increments staged in LDS at a time (one per lane)
 
 template <int N>
-constexpr int kLdsFloats = (kTile<N> * 4 * (N - 1) > kChannels<N> ? kTile<N> * 4 * (N - 1) : kChannels<N>);
+constexpr int kLdsFloats = (kTile * kRow > kChannels<N> ? kTile * kRow : kChannels<N>);
 
 template <int N>
 struct State {
-    float A1 = 0.0f, A2 = 0.0f, A3 = 0.0f;
+    float A2 = 0.0f, A3 = 0.0f;
     f4 A4[1];
     f4 A5[N >= 5 ? 4 : 1];
     f4 A6[N >= 6 ? 16 : 1];
 };
 
-// This lane's view of one staged increment: z[w_1], z[w_2]/m and z[q]/m.
+// This lane's view of one staged increment.
 template <int N>
 struct Row {
-    float zA;
-    float zB[N];  // zB[m] = z[w_2]/m, m = 1..N-1
-    float zC[N];  // zC[m] = z[q]/m,   m = 1..N-2
+    float t1[N + 1];  // t1[k] = z[w_1]/k + A_1[w_1], k = 2..N
+    float zB[N];      // zB[m] = z[w_2]/m, m = 1..N-1
+    float zC[N];      // zC[m] = z[q]/m,   m = 1..N-2
 };
 
-// `tab` points at one increment's scaled copies in LDS: tab[(m-1)*4 + c] = z[c]/m, m = 1..N-1.
 template <int N>
-__device__ __forceinline__ Row<N> load_row(const float *tab, int w1, int w2, int q)
+__device__ __forceinline__ Row<N> load_row(const float *row, int w1, int w2, int q)
 {
     Row<N> R;
-    R.zA = tab[w1];
 #pragma unroll
-    for (int m = 1; m <= N - 1; ++m) R.zB[m] = tab[(m - 1) * 4 + w2];
+    for (int k = 2; k <= N; ++k) R.t1[k] = row[w1 * 8 + (k - 2)];
 #pragma unroll
-    for (int m = 1; m <= N - 2; ++m) R.zC[m] = tab[(m - 1) * 4 + q];
+    for (int m = 1; m <= N - 1; ++m) R.zB[m] = row[32 + w2 * 8 + (m - 1)];
+#pragma unroll
+    for (int m = 1; m <= N - 2; ++m) R.zC[m] = row[32 + q * 8 + (m - 1)];
     return R;
 }
 
-// Levels 1..3 of one fused multiply-exponentiate A <- A [x] exp(z), one scalar per lane, and
-// the level-3 Horner terms t3[k] = T_k^(3) of the higher targets k = 4..N.
+// One fused multiply-exponentiate A <- A [x] exp(z) on levels 2..N.
 template <int N>
-__device__ __forceinline__ void low_levels(State<N> &S, const Row<N> &R, float (&t3)[N + 1])
+__device__ __forceinline__ void fused_step(State<N> &S, const Row<N> &R)
 {
-    float t1[N + 1], t2[N + 1];
+    // levels 2 and 3, one scalar per lane
+    float t2[N + 1], t3[N + 1];
 #pragma unroll
-    for (int k = 2; k <= N; ++k) t1[k] = __builtin_fmaf(R.zA, 1.0f / k, S.A1);
-#pragma unroll
-    for (int k = 2; k <= N; ++k) t2[k] = __builtin_fmaf(t1[k], R.zB[k - 1], S.A2);
+    for (int k = 2; k <= N; ++k) t2[k] = __builtin_fmaf(R.t1[k], R.zB[k - 1], S.A2);
 #pragma unroll
     for (int k = 3; k <= N; ++k) t3[k] = __builtin_fmaf(t2[k], R.zC[k - 2], S.A3);
     S.A3 = t3[3];
     S.A2 = t2[2];
-    S.A1 += R.zA;
-}
 
-// Levels 4..N: outer products on the matrix cores; higher targets first, so that each A_i is
-// read by every stage that needs its old value before it is overwritten.  zC[m] = z[q]/m.
-template <int N>
-__device__ __forceinline__ void high_levels(State<N> &S, const float (&t3)[N + 1], const float *zC)
-{
+    // levels 4..N: outer products on the matrix cores; higher targets first, so that each A_i is
+    // read by every stage that needs its old value before it is overwritten
     f4 t4[N + 1];
 #pragma unroll
-    for (int k = N; k >= 5; --k) t4[k] = outer4(t3[k], zC[k - 3], S.A4[0]);
-    S.A4[0] = outer4(t3[4], zC[1], S.A4[0]);
+    for (int k = N; k >= 5; --k) t4[k] = outer4(t3[k], R.zC[k - 3], S.A4[0]);
+    S.A4[0] = outer4(t3[4], R.zC[1], S.A4[0]);
     if constexpr (N >= 5) {
         f4 t5[4];
         if constexpr (N >= 6) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) t5[g] = outer4(t4[6][g], zC[2], S.A5[g]);
+            for (int g = 0; g < 4; ++g) t5[g] = outer4(t4[6][g], R.zC[2], S.A5[g]);
         }
 #pragma unroll
-        for (int g = 0; g < 4; ++g) S.A5[g] = outer4(t4[5][g], zC[1], S.A5[g]);
+        for (int g = 0; g < 4; ++g) S.A5[g] = outer4(t4[5][g], R.zC[1], S.A5[g]);
         if constexpr (N >= 6) {
 #pragma unroll
-            for (int g = 0; g < 16; ++g) S.A6[g] = outer4(t5[g >> 2][g & 3], zC[1], S.A6[g]);
+            for (int g = 0; g < 16; ++g) S.A6[g] = outer4(t5[g >> 2][g & 3], R.zC[1], S.A6[g]);
         }
     }
-}
-
-// One fused multiply-exponentiate A <- A [x] exp(z).
-template <int N>
-__device__ __forceinline__ void fused_step(State<N> &S, const Row<N> &R)
-{
-    float t3[N + 1];
-    low_levels<N>(S, R, t3);
-    high_levels<N>(S, t3, R.zC);
 }
 
 // Where word number i of a level (lexicographic) is parked in LDS on its way to `out`.  The
@@ -144,45 +131,59 @@ sig_mfma_d4_kernel(const float *__restrict__ path, float *__restrict__ out, int6
     const int w1 = lane >> 4, w2 = (lane >> 2) & 3, q = lane & 3;
     const int64_t b = blockIdx.x;
     const f4 *x4 = reinterpret_cast<const f4 *>(path) + b * L;  // point l of this path
+    const f4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    const f4 x_first = basepoint ? zero4 : x4[0];
 
     State<N> S;
-    S.A4[0] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+    S.A4[0] = zero4;
 #pragma unroll
-    for (int g = 0; g < (N >= 5 ? 4 : 1); ++g) S.A5[g] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+    for (int g = 0; g < (N >= 5 ? 4 : 1); ++g) S.A5[g] = zero4;
 #pragma unroll
-    for (int g = 0; g < (N >= 6 ? 16 : 1); ++g) S.A6[g] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+    for (int g = 0; g < (N >= 6 ? 16 : 1); ++g) S.A6[g] = zero4;
 
-    constexpr int kRow = 4 * (N - 1);  // floats per staged increment
-    for (int64_t t0 = 0; t0 < n_inc; t0 += kTile<N>) {
-        const int nt = int(n_inc - t0 < kTile<N> ? n_inc - t0 : kTile<N>);
+    // the two points around increment number s (zeros past the end of the path); the points of a
+    // tile are fetched while the tile before it is being scanned
+    f4 p_hi, p_lo;
+    auto fetch_points = [&](int64_t s) {
+        p_hi = p_lo = zero4;
+        if (s < n_inc) {
+            const int64_t i_hi = basepoint ? s : s + 1;
+            p_hi = x4[i_hi];
+            if (i_hi > 0) p_lo = x4[i_hi - 1];
+        }
+    };
+    fetch_points(lane);
+
+    for (int64_t t0 = 0; t0 < n_inc; t0 += kTile) {
+        const int nt = int(n_inc - t0 < kTile ? n_inc - t0 : kTile);
         __syncthreads();
-        // every lane fetches its points of the tile with independent 16-byte loads (all in
-        // flight together: one memory round trip per tile), then differences, scales and stages
-        constexpr int kPer = kTile<N> / 64;
-        f4 hi[kPer], lo[kPer];
+        if (lane < nt) {
+            // lane i stages increment t0 + i: z = hi - lo, and A_1 before it = lo - x_first
+            const f4 z = p_hi - p_lo;
+            const f4 a1 = p_lo - x_first;
+            float *row = lds + lane * kRow;
 #pragma unroll
-        for (int j = 0; j < kPer; ++j) {
-            const int i = lane + 64 * j;
-            const int64_t s = t0 + i;  // increment number
-            hi[j] = lo[j] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
-            if (i < nt) {
-                const int64_t p_hi = basepoint ? s : s + 1;
-                hi[j] = x4[p_hi];
-                if (p_hi > 0) lo[j] = x4[p_hi - 1];
+            for (int c = 0; c < 4; ++c) {
+                f4 lo4, hi4 = zero4, zlo, zhi = zero4;
+                lo4[0] = __builtin_fmaf(z[c], 1.0f / 2, a1[c]);
+                lo4[1] = __builtin_fmaf(z[c], 1.0f / 3, a1[c]);
+                lo4[2] = __builtin_fmaf(z[c], 1.0f / 4, a1[c]);
+                lo4[3] = __builtin_fmaf(z[c], 1.0f / 5, a1[c]);
+                hi4[0] = __builtin_fmaf(z[c], 1.0f / 6, a1[c]);
+                zlo[0] = z[c];
+                zlo[1] = z[c] * (1.0f / 2);
+                zlo[2] = z[c] * (1.0f / 3);
+                zlo[3] = z[c] * (1.0f / 4);
+                zhi[0] = z[c] * (1.0f / 5);
+                f4 *r4 = reinterpret_cast<f4 *>(row + c * 8);
+                r4[0] = lo4;
+                r4[1] = hi4;
+                r4[8] = zlo;
+                r4[9] = zhi;
             }
         }
-#pragma unroll
-        for (int j = 0; j < kPer; ++j) {
-            const int i = lane + 64 * j;
-            if (i < nt) {
-                const f4 z = hi[j] - lo[j];
-                f4 *row = reinterpret_cast<f4 *>(lds + i * kRow);
-                row[0] = z;
-#pragma unroll
-                for (int m = 2; m <= N - 1; ++m) row[m - 1] = z * (1.0f / m);
-            }
-        }
         __syncthreads();
+        fetch_points(t0 + kTile + lane);
         // four increments per trip: their rows are fetched from LDS together, so the LDS latency
         // is paid once per trip and no register is copied between trips
         int s = 0;
@@ -196,9 +197,12 @@ sig_mfma_d4_kernel(const float *__restrict__ path, float *__restrict__ out, int6
         for (; s < nt; ++s) fused_step<N>(S, load_row<N>(lds + s * kRow, w1, w2, q));
     }
 
+    // level 1 is the total displacement
+    const f4 a1 = x4[L - 1] - x_first;
+
     // park the state in LDS in word order, then copy it out 16 bytes per lane, fully coalesced
     __syncthreads();
-    if ((lane & 15) == 0) lds[w1] = S.A1;
+    if (lane == 0) *reinterpret_cast<f4 *>(lds) = a1;
     if (q == 0) lds[4 + (lane >> 2)] = S.A2;
     lds[20 + lane] = S.A3;
     const int blk = lane >> 2;
@@ -232,197 +236,18 @@ sig_mfma_d4_kernel(const float *__restrict__ path, float *__restrict__ out, int6
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Two wavefronts per path.
-//
-// A lone wavefront on a SIMD issues roughly one instruction every 8 clocks whatever its kind, so
-// the one-wavefront kernel above is bound by its instruction count, not by the matrix cores.  Here
-// the work of a path is cut along its only one-way dependency: wavefront 1 (the producer) folds
-// each increment into levels 1..3 and hands the level-3 Horner terms t3[k], k = 4..N, over
-// through LDS; wavefront 0 (the consumer) owns levels 4..N and does nothing but outer products.
-// Nothing flows back, so the producer simply runs one chunk of increments ahead.  Both
-// wavefronts run the same loop with one workgroup barrier per trip, hence cannot fall out of step.
-constexpr int kChunk = 4;      // increments per hand-over
-constexpr int kPairTile = 64;  // increments per staged LDS tile; two tiles are used alternately
-
-template <int N>
-struct PairLds {
-    static constexpr int kRow = 4 * (N - 1);                    // floats per staged increment
-    static constexpr int kTab = 2 * kPairTile * kRow;           // two tiles of scaled increments
-    static constexpr int kRec = N - 3;                          // floats per lane handed over per increment
-    static constexpr int kXchg = 2 * kChunk * 64 * kRec;        // two chunks of hand-over records
-    static constexpr int kFloats = (kTab + kXchg > kChannels<N> ? kTab + kXchg : kChannels<N>);
-};
-
-// Producer side of one chunk: `rows` points at the chunk's first staged increment, `rec` at this
-// lane's slot of the chunk's first hand-over record.  FULL: the chunk has all kChunk increments.
-template <int N, bool FULL>
-__device__ __forceinline__ void produce_chunk(State<N> &S, const float *rows, float *rec, int ns, int w1, int w2, int q)
-{
-    constexpr int kRow = 4 * (N - 1), kRec = N - 3;
-    Row<N> R[kChunk];
-#pragma unroll
-    for (int i = 0; i < kChunk; ++i) R[i] = load_row<N>(rows + (FULL || i < ns ? i : 0) * kRow, w1, w2, q);
-#pragma unroll
-    for (int i = 0; i < kChunk; ++i) {
-        if (FULL || i < ns) {
-            float t3[N + 1];
-            low_levels<N>(S, R[i], t3);
-#pragma unroll
-            for (int k = 4; k <= N; ++k) rec[i * 64 * kRec + (k - 4)] = t3[k];
-        }
-    }
-}
-
-// Consumer side of one chunk.
-template <int N, bool FULL>
-__device__ __forceinline__ void consume_chunk(State<N> &S, const float *rows, const float *rec, int ns, int q)
-{
-    constexpr int kRow = 4 * (N - 1), kRec = N - 3;
-    float t3[kChunk][N + 1], zC[kChunk][N];
-#pragma unroll
-    for (int i = 0; i < kChunk; ++i) {
-        const int ii = FULL || i < ns ? i : 0;
-#pragma unroll
-        for (int k = 4; k <= N; ++k) t3[i][k] = rec[ii * 64 * kRec + (k - 4)];
-#pragma unroll
-        for (int m = 1; m <= N - 3; ++m) zC[i][m] = rows[ii * kRow + (m - 1) * 4 + q];
-    }
-#pragma unroll
-    for (int i = 0; i < kChunk; ++i)
-        if (FULL || i < ns) high_levels<N>(S, t3[i], zC[i]);
-}
-
-template <int N>
-__global__ void __launch_bounds__(128)
-sig_mfma_d4_pair_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint)
-{
-    static_assert(N >= 5 && N <= 6, "depths served by this kernel");
-    using Lds = PairLds<N>;
-    constexpr int kRow = Lds::kRow, kRec = Lds::kRec;
-    __shared__ __align__(16) float lds[Lds::kFloats];
-    float *tab = lds;
-    float *xchg = lds + Lds::kTab;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const bool producer = __builtin_amdgcn_readfirstlane(tid >> 6) == 1;
-    const int w1 = lane >> 4, w2 = (lane >> 2) & 3, q = lane & 3;
-    const int64_t b = blockIdx.x;
-    const f4 *x4 = reinterpret_cast<const f4 *>(path) + b * L;  // point l of this path
-
-    State<N> S;
-    S.A4[0] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-    for (int g = 0; g < 4; ++g) S.A5[g] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-    for (int g = 0; g < (N >= 6 ? 16 : 1); ++g) S.A6[g] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
-
-    // producer: the two points around increment number s (zeros past the end of the path)
-    f4 p_hi = (f4){0.0f, 0.0f, 0.0f, 0.0f}, p_lo = p_hi;
-    auto fetch_points = [&](int64_t s) {
-        p_hi = p_lo = (f4){0.0f, 0.0f, 0.0f, 0.0f};
-        if (s < n_inc) {
-            const int64_t i_hi = basepoint ? s : s + 1;
-            p_hi = x4[i_hi];
-            if (i_hi > 0) p_lo = x4[i_hi - 1];
-        }
-    };
-    if (producer) fetch_points(lane);
-
-    const int64_t n_chunks = (n_inc + kChunk - 1) / kChunk;
-    for (int64_t c = 0; c <= n_chunks; ++c) {
-        if (producer) {
-            if (c < n_chunks) {
-                const int64_t s0 = c * kChunk;
-                const int in_tile = int(s0 % kPairTile);
-                float *tile = tab + int((s0 / kPairTile) & 1) * (kPairTile * kRow);
-                if (in_tile == 0) {
-                    // stage this tile from the points fetched one tile ago, then fetch the next tile's
-                    if (s0 + lane < n_inc) {
-                        const f4 z = p_hi - p_lo;
-                        f4 *row = reinterpret_cast<f4 *>(tile + lane * kRow);
-                        row[0] = z;
-#pragma unroll
-                        for (int m = 2; m <= N - 1; ++m) row[m - 1] = z * (1.0f / m);
-                    }
-                    fetch_points(s0 + kPairTile + lane);
-                }
-                const int ns = int(n_inc - s0 < kChunk ? n_inc - s0 : kChunk);
-                float *rec = xchg + (int(c & 1) * kChunk * 64 + lane) * kRec;
-                if (ns == kChunk) {
-                    produce_chunk<N, true>(S, tile + in_tile * kRow, rec, kChunk, w1, w2, q);
-                } else {
-                    produce_chunk<N, false>(S, tile + in_tile * kRow, rec, ns, w1, w2, q);
-                }
-            }
-        } else {
-            if (c > 0) {
-                const int64_t s0 = (c - 1) * kChunk;
-                const int in_tile = int(s0 % kPairTile);
-                const float *tile = tab + int((s0 / kPairTile) & 1) * (kPairTile * kRow);
-                const int ns = int(n_inc - s0 < kChunk ? n_inc - s0 : kChunk);
-                const float *rec = xchg + (int((c - 1) & 1) * kChunk * 64 + lane) * kRec;
-                if (ns == kChunk) {
-                    consume_chunk<N, true>(S, tile + in_tile * kRow, rec, kChunk, q);
-                } else {
-                    consume_chunk<N, false>(S, tile + in_tile * kRow, rec, ns, q);
-                }
-            }
-        }
-        __syncthreads();
-    }
-
-    // park the state in LDS in word order (levels 1..3 from the producer, the rest from the
-    // consumer), then both wavefronts copy it out 16 bytes per lane
-    const int blk = lane >> 2;
-    if (producer) {
-        if ((lane & 15) == 0) lds[w1] = S.A1;
-        if (q == 0) lds[4 + (lane >> 2)] = S.A2;
-        lds[20 + lane] = S.A3;
-    } else {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) lds[kOff4 + park4(blk * 16 + r * 4 + q)] = S.A4[0][r];
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) lds[kOff5 + park5(blk * 64 + g * 16 + r * 4 + q)] = S.A5[g][r];
-        if constexpr (N >= 6) {
-#pragma unroll
-            for (int g = 0; g < 16; ++g)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) lds[kOff6 + park6(blk * 256 + g * 16 + r * 4 + q)] = S.A6[g][r];
-        }
-    }
-    __syncthreads();
-    f4 *o4 = reinterpret_cast<f4 *>(out + b * kChannels<N>);
-    for (int j = tid; j < kChannels<N> / 4; j += 128) {
-        const int i = 4 * j;
-        const int at = i < kOff4 ? i : i < kOff5 ? kOff4 + park4(i - kOff4) : i < kOff6 ? kOff5 + park5(i - kOff5) : kOff6 + park6(i - kOff6);
-        o4[j] = *reinterpret_cast<const f4 *>(lds + at);
-    }
-}
-
 }  // namespace
 
-const char *mfma_kernel_name(const Shape &sh, bool pair)
+const char *mfma_kernel_name(const Shape &sh)
 {
     if (sh.d != 4 || sh.stream || sh.B > 0x7fffffff) return nullptr;
-    if (pair) return (sh.N == 5 || sh.N == 6) ? "mfma_d4_pair" : nullptr;
     return (sh.N >= 4 && sh.N <= 6) ? "mfma_d4" : nullptr;
 }
 
-hipError_t launch_mfma_f32(const Shape &sh, bool pair, const float *path, float *out, hipStream_t st)
+hipError_t launch_mfma_f32(const Shape &sh, const float *path, float *out, hipStream_t st)
 {
-    if (mfma_kernel_name(sh, pair) == nullptr) return hipErrorNotSupported;
-    const dim3 grid(static_cast<unsigned>(sh.B));
-    if (pair) {
-        const dim3 block(128);
-        if (sh.N == 5) hipLaunchKernelGGL(sig_mfma_d4_pair_kernel<5>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint);
-        else hipLaunchKernelGGL(sig_mfma_d4_pair_kernel<6>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint);
-        return hipGetLastError();
-    }
-    const dim3 block(64);
+    if (mfma_kernel_name(sh) == nullptr) return hipErrorNotSupported;
+    const dim3 grid(static_cast<unsigned>(sh.B)), block(64);
     switch (sh.N) {
         case 4: hipLaunchKernelGGL(sig_mfma_d4_kernel<4>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint); break;
         case 5: hipLaunchKernelGGL(sig_mfma_d4_kernel<5>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint); break;

@@ -113,8 +113,9 @@ def test_variant_names(lib):
     assert sig.sig_variant_name(32, 1, 2, 4, False, False) == "invalid"
     assert sig.sig_variant_name(32, 16, 3, 4, False, False, variant=sig.SIG_VARIANT_MFMA) == "unsupported"
     assert sig.sig_variant_name(32, 16, 4, 4, False, False, variant=sig.SIG_VARIANT_MFMA) == "mfma_d4"
-    assert sig.sig_variant_name(32, 16, 4, 4, False, False, variant=sig.SIG_VARIANT_MFMA_PAIR) == "unsupported"
-    assert sig.sig_variant_name(32, 16, 4, 6, False, False, variant=sig.SIG_VARIANT_MFMA_PAIR) == "mfma_d4_pair"
+    assert sig.sig_variant_name(32, 16, 4, 7, False, False, variant=sig.SIG_VARIANT_MFMA) == "unsupported"
+    assert sig.sig_variant_name(32, 16, 4, 7, False, False, variant=sig.SIG_VARIANT_MFMA_SHARD) == "mfma_d4_shard"
+    assert sig.sig_variant_name(32, 16, 2, 4, True, True, sig.SIG_F64, sig.SIG_VARIANT_SMALL) == "small"
     assert sig.sig_variant_name(32, 16, 4, 6, True, False, variant=sig.SIG_VARIANT_MFMA) == "unsupported"
 
 

@@ -72,9 +72,9 @@ def check(x, N, stream=False, basepoint=False, variant=sig.SIG_VARIANT_AUTO, sam
     return got
 
 
-VARIANTS = [sig.SIG_VARIANT_AUTO, sig.SIG_VARIANT_GENERIC, sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_PAIR,
-            sig.SIG_VARIANT_MFMA_SHARD, sig.SIG_VARIANT_SMALL]
-VARIANT_IDS = ["auto", "generic", "mfma", "mfma_pair", "mfma_shard", "small"]
+VARIANTS = [sig.SIG_VARIANT_AUTO, sig.SIG_VARIANT_GENERIC, sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_SHARD,
+            sig.SIG_VARIANT_SMALL]
+VARIANT_IDS = ["auto", "generic", "mfma", "mfma_shard", "small"]
 
 
 # ------------------------------------------------------------------ benchmark workloads
@@ -140,8 +140,7 @@ D4_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("variant", [sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_PAIR, sig.SIG_VARIANT_MFMA_SHARD],
-                         ids=["mfma", "mfma_pair", "mfma_shard"])
+@pytest.mark.parametrize("variant", [sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_SHARD], ids=["mfma", "mfma_shard"])
 @pytest.mark.parametrize("B,L,N", D4_SHAPES)
 def test_d4_matrix_core_kernels(B, L, N, variant):
     x = uniform_paths(B, L, 4, seed=2000 + 3 * L + N, lo=-0.5, hi=0.5)
