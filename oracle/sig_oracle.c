@@ -26,7 +26,13 @@
  *
  * Pinned by tests/test_oracle_pins.py against closed forms, invariants, brute force from
  * the integral definition and a hand-computed example; nothing here is "parity unpinned".
+ *
+ * SIG_ORACLE_MUTANT (never defined in a normal build) plants one deliberate mistake, numbered
+ * below, so that tests/test_oracle_mutants.py can check that the pins notice each of them.
  */
+#ifndef SIG_ORACLE_MUTANT
+#define SIG_ORACLE_MUTANT 0
+#endif
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -64,6 +70,7 @@ static int64_t level_offset(int d, int k)
 {
     int64_t off = 0;
     for (int j = 1; j < k; ++j) off += ipow64(d, j);
+    if (SIG_ORACLE_MUTANT == 8 && k == 3) off -= 1; /* mutant 8: level 3 overlaps level 2 */
     return off;
 }
 
@@ -78,7 +85,7 @@ void sig_oracle_exp(const double *z, int d, int N, double *E)
         const int64_t n_prev = ipow64(d, k - 1);
         for (int64_t w = 0; w < n_prev; ++w)
             for (int j = 0; j < d; ++j)
-                cur[w * d + j] = prev[w] * z[j] / (double)k;
+                cur[w * d + j] = prev[w] * z[j] / (double)(SIG_ORACLE_MUTANT == 1 ? 2 : k); /* mutant 1: wrong factorial */
     }
 }
 
@@ -92,8 +99,9 @@ void sig_oracle_mul(const double *A, const double *B, int d, int N, double *C)
         const int64_t off_k = level_offset(d, k);
         const int64_t n_k = ipow64(d, k);
         double *Ck = C + off_k;
-        for (int64_t w = 0; w < n_k; ++w) Ck[w] = B[off_k + w] + A[off_k + w];
-        for (int j = 1; j <= k - 1; ++j) {
+        for (int64_t w = 0; w < n_k; ++w)
+            Ck[w] = B[off_k + w] + (SIG_ORACLE_MUTANT == 2 ? 0.0 : A[off_k + w]); /* mutant 2: A_k (x) B_0 dropped */
+        for (int j = (SIG_ORACLE_MUTANT == 3 ? 2 : 1); j <= k - 1; ++j) { /* mutant 3: the j = 1 term dropped */
             const int m = k - j;
             const double *Aj = A + level_offset(d, j);
             const double *Bm = B + level_offset(d, m);
@@ -101,7 +109,7 @@ void sig_oracle_mul(const double *A, const double *B, int d, int N, double *C)
             const int64_t n_m = ipow64(d, m);
             for (int64_t u = 0; u < n_j; ++u)
                 for (int64_t v = 0; v < n_m; ++v)
-                    Ck[u * n_m + v] += Aj[u] * Bm[v];
+                    Ck[SIG_ORACLE_MUTANT == 4 ? v * n_j + u : u * n_m + v] += Aj[u] * Bm[v]; /* mutant 4: operands transposed */
         }
     }
 }
@@ -134,7 +142,8 @@ static int one_path(const double *x, int64_t L, int d, int N, int stream, int ba
                 hi = x[(s + 1) * d + c];
                 lo = x[s * d + c];
             }
-            z[c] = hi - lo;
+            z[c] = SIG_ORACLE_MUTANT == 5 ? lo - hi : hi - lo; /* mutant 5: sign of the increment */
+            if (SIG_ORACLE_MUTANT == 6 && basepoint && s == 0) z[c] = 0.0; /* mutant 6: basepoint ignored */
         }
         if (s == 0) {
             sig_oracle_exp(z, d, N, cur);
@@ -143,7 +152,9 @@ static int one_path(const double *x, int64_t L, int d, int N, int stream, int ba
             sig_oracle_mul(cur, E, d, N, nxt);
             double *t = cur; cur = nxt; nxt = t;
         }
-        if (stream) memcpy(out + s * S, cur, sizeof(double) * (size_t)S);
+        if (stream && !(SIG_ORACLE_MUTANT == 7 && s + 1 < n_inc)) /* mutant 7: only the last prefix written */
+            memcpy(out + s * S, cur, sizeof(double) * (size_t)S);
+        if (stream && SIG_ORACLE_MUTANT == 7 && s + 1 < n_inc) memset(out + s * S, 0, sizeof(double) * (size_t)S);
     }
     if (!stream) memcpy(out, cur, sizeof(double) * (size_t)S);
     free(z); free(cur); free(E); free(nxt);

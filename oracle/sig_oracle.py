@@ -3,8 +3,8 @@
 Only the tests, `__graft_entry__.smoke()` and the benchmark's cpu_baseline leg may import
 this module.  It never touches the HIP library or the product package.
 
-The C file is compiled on demand with the host gcc (`ensure_built`); building the checker
-is not using it.
+The C file is compiled on demand with the host gcc (`build`); building the checker is not
+using it.
 """
 from __future__ import annotations
 
@@ -22,35 +22,65 @@ _lock = threading.Lock()
 _lib = None
 
 
+def _compile(out_path: str, defines=()) -> None:
+    tmp = out_path + f".tmp{os.getpid()}"
+    cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+           "-Wall", "-Wextra", *[f"-D{d}" for d in defines], "-o", tmp, _SRC]
+    subprocess.run(cmd, check=True)
+    os.replace(tmp, out_path)
+
+
 def build(force: bool = False) -> str:
     """Compile `sig_oracle.c` into `libsig_oracle.so` next to it; returns the library path."""
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
-        tmp = _LIB + f".tmp{os.getpid()}"
-        cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
-               "-Wall", "-Wextra", "-o", tmp, _SRC]
-        subprocess.run(cmd, check=True)
-        os.replace(tmp, _LIB)
+        _compile(_LIB)
     return _LIB
+
+
+def _declare(lib):
+    i64, i32 = ctypes.c_int64, ctypes.c_int
+    dp = ctypes.POINTER(ctypes.c_double)
+    lib.sig_oracle_channels.restype = i64
+    lib.sig_oracle_channels.argtypes = [i32, i32]
+    lib.sig_oracle_exp.restype = None
+    lib.sig_oracle_exp.argtypes = [dp, i32, i32, dp]
+    lib.sig_oracle_mul.restype = None
+    lib.sig_oracle_mul.argtypes = [dp, dp, i32, i32, dp]
+    lib.sig_oracle_forward_f64.restype = i32
+    lib.sig_oracle_forward_f64.argtypes = [dp, i64, i64, i32, i32, i32, i32, dp, i32]
+    lib.sig_oracle_max_threads.restype = i32
+    lib.sig_oracle_max_threads.argtypes = []
+    return lib
+
+
+class use_mutant:
+    """Context manager for the mutation tests: inside it, every function of this module runs a copy
+    of the oracle compiled with one deliberate mistake (`-DSIG_ORACLE_MUTANT=n`) into `workdir`."""
+
+    def __init__(self, number: int, workdir: str):
+        self.path = os.path.join(workdir, f"libsig_oracle_mutant{number}.so")
+        _compile(self.path, [f"SIG_ORACLE_MUTANT={number}"])
+
+    def __enter__(self):
+        global _lib
+        _load()
+        with _lock:
+            self.saved, _lib = _lib, _declare(ctypes.CDLL(self.path))
+        return self
+
+    def __exit__(self, *exc):
+        global _lib
+        with _lock:
+            _lib = self.saved
+        return False
 
 
 def _load():
     global _lib
     with _lock:
         if _lib is None:
-            lib = ctypes.CDLL(build())
-            i64, i32 = ctypes.c_int64, ctypes.c_int
-            dp = ctypes.POINTER(ctypes.c_double)
-            lib.sig_oracle_channels.restype = i64
-            lib.sig_oracle_channels.argtypes = [i32, i32]
-            lib.sig_oracle_exp.restype = None
-            lib.sig_oracle_exp.argtypes = [dp, i32, i32, dp]
-            lib.sig_oracle_mul.restype = None
-            lib.sig_oracle_mul.argtypes = [dp, dp, i32, i32, dp]
-            lib.sig_oracle_forward_f64.restype = i32
-            lib.sig_oracle_forward_f64.argtypes = [dp, i64, i64, i32, i32, i32, i32, dp, i32]
-            lib.sig_oracle_max_threads.restype = i32
-            lib.sig_oracle_max_threads.argtypes = []
+            lib = _declare(ctypes.CDLL(build()))
             _lib = lib
     return _lib
 

@@ -1,0 +1,59 @@
+"""Each deliberate mistake that can be planted in the oracle (`-DSIG_ORACLE_MUTANT=n`, CPU only)
+must be noticed by at least one pin of tests/test_oracle_pins.py; the unmodified oracle by none."""
+import inspect
+
+import pytest
+
+from oracle import sig_oracle as orc
+from tests import test_oracle_pins as pins
+
+MUTANTS = {
+    1: "exp divides by 2 instead of k",
+    2: "A_k (x) B_0 dropped from the group product",
+    3: "the j = 1 cross term dropped from the group product",
+    4: "cross terms written transposed",
+    5: "increment sign flipped",
+    6: "basepoint ignored",
+    7: "stream mode writes only the last prefix",
+    8: "level 3 stored one scalar too early",
+}
+
+
+def _pin_calls():
+    """(name, callable) for every pin, with its parametrisations expanded."""
+    calls = []
+    for name, fn in inspect.getmembers(pins, inspect.isfunction):
+        if not name.startswith("test_"):
+            continue
+        marks = [m for m in getattr(fn, "pytestmark", []) if m.name == "parametrize"]
+        if not marks:
+            calls.append((name, fn, {}))
+            continue
+        assert len(marks) == 1, name
+        argnames, values = marks[0].args
+        argnames = [a.strip() for a in argnames.split(",")]
+        for v in values:
+            v = v if isinstance(v, (tuple, list)) else (v,)
+            calls.append((f"{name}[{v}]", fn, dict(zip(argnames, v))))
+    return calls
+
+
+def _failing_pins():
+    failed = []
+    for name, fn, kwargs in _pin_calls():
+        try:
+            fn(**kwargs)
+        except Exception:  # an assertion, or an exception the pin does not expect
+            failed.append(name)
+    return failed
+
+
+def test_the_unmodified_oracle_passes_every_pin():
+    assert _failing_pins() == []
+
+
+@pytest.mark.parametrize("number", sorted(MUTANTS), ids=lambda n: f"mutant{n}")
+def test_every_planted_mistake_is_caught(number, tmp_path):
+    with orc.use_mutant(number, str(tmp_path)):
+        failed = _failing_pins()
+    assert failed, f"no pin notices: {MUTANTS[number]}"
