@@ -286,3 +286,65 @@ def test_work_is_enqueued_on_the_callers_stream():
         got = sig.sig_forward(x, w.N)
     side.synchronize()
     assert torch.equal(ref, got)
+
+
+def test_long_paths_cross_many_tiles():
+    # every family with a staged tile: several tiles, ragged last tile
+    check(brownian_paths(2, 1000, 4, seed=31), 6)                                  # mfma_d4, 64-increment tiles
+    check(brownian_paths(1, 333, 4, seed=32), 5, stream=True)                      # mfma_d4_shard
+    check(brownian_paths(1, 333, 4, seed=32), 7, basepoint=True)                   # mfma_d4_shard, depth 7
+    check(brownian_paths(1, 450, 8, seed=33), 5)                                   # mfma_d8_shard
+    check(brownian_paths(1, 700, 16, seed=34), 4)                                  # mfma_d16, 128-increment tiles
+    check(brownian_paths(2, 3000, 2, seed=35), 4, stream=True)                     # small
+    check(brownian_paths(1, 2500, 3, seed=36).astype(np.float64), 6)               # generic, fp64
+
+
+def test_calls_can_be_captured_in_a_graph_and_replayed():
+    # nothing in the library allocates, synchronises or memsets, so a call can sit in a HIP graph
+    torch = torch_mod()
+    for w in (WORKLOADS[0], WORKLOADS[1], WORKLOADS[3]):
+        x_host = workload_paths(w)[:16]
+        x = torch.from_numpy(x_host).to("cuda:0")
+        eager = sig.sig_forward(x, w.N, stream=w.stream)
+        torch.cuda.synchronize()
+        out = torch.zeros_like(eager)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            sig.sig_forward(x, w.N, stream=w.stream, out=out)      # warm-up on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            sig.sig_forward(x, w.N, stream=w.stream, out=out)
+        for rep in range(3):
+            out.fill_(float("nan"))
+            x.copy_(torch.from_numpy(x_host * (rep + 1)).to("cuda:0"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            want = sig.sig_forward(x, w.N, stream=w.stream)
+            torch.cuda.synchronize()
+            assert torch.equal(out, want), (w.name, rep)
+
+
+def test_two_streams_at_once():
+    torch = torch_mod()
+    wa, wb = WORKLOADS[1], WORKLOADS[3]
+    xa = torch.from_numpy(workload_paths(wa)[:256]).to("cuda:0")
+    xb = torch.from_numpy(workload_paths(wb)[:32]).to("cuda:0")
+    ra = sig.sig_forward(xa, wa.N)
+    rb = sig.sig_forward(xb, wb.N, stream=True)
+    torch.cuda.synchronize()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for _ in range(4):
+        with torch.cuda.stream(sa):
+            ga = sig.sig_forward(xa, wa.N)
+        with torch.cuda.stream(sb):
+            gb = sig.sig_forward(xb, wb.N, stream=True)
+        outs.append((ga, gb))
+    sa.synchronize()
+    sb.synchronize()
+    for ga, gb in outs:
+        assert torch.equal(ga, ra) and torch.equal(gb, rb)
