@@ -105,6 +105,18 @@ sig_status sig_forward_variant(const void *path, int64_t B, int64_t L, int d, in
                                int stream, int basepoint, sig_dtype dtype,
                                void *out, hipStream_t hip_stream, sig_variant variant);
 
+/* Group product of two batches of signatures: out[b] = a[b] [x] b[b], with
+ * (A [x] B)_k = sum_{j=0..k} A_j (x) B_{k-j}, A_0 = B_0 = 1 (section 2.2).  By Chen's identity
+ * (eq. "grouplike") this joins the signatures of two adjacent intervals that share their
+ * boundary point, Sig(x_1..x_L) = Sig(x_1..x_j) [x] Sig(x_j..x_L), without going back to the data
+ * (section 5.5, "combining adjacent intervals").
+ *
+ *   a, b, out  DEVICE pointers, [B][S] contiguous, S = sig_signature_channels(d, N), element type
+ *              `dtype`; `out` is fully overwritten and must not overlap `a` or `b`.
+ * Enqueued on `hip_stream`, no wait.  Errors as for sig_forward (SIG_ERR_UNSUPPORTED if S >= 2^31). */
+sig_status sig_combine(const void *a, const void *b, int64_t B, int d, int N, sig_dtype dtype,
+                       void *out, hipStream_t hip_stream);
+
 /* Name of the kernel family that `variant` resolves to for this shape ("generic",
  * "mfma_d4", ...), or "unsupported" / "invalid".  The string is static. */
 const char *sig_variant_name(int64_t B, int64_t L, int d, int N, int stream, int basepoint,

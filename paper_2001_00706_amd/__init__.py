@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     SIG_VARIANT_SMALL,
     SigError,
     load_library,
+    sig_combine,
     sig_forward,
     sig_forward_raw,
     sig_fused_fmas,

@@ -26,6 +26,7 @@ EXPORTED_SYMBOLS = (
     "sig_fused_fmas",
     "sig_forward",
     "sig_forward_variant",
+    "sig_combine",
     "sig_variant_name",
     "sig_status_string",
 )
@@ -61,6 +62,8 @@ def load_library() -> ctypes.CDLL:
         lib.sig_forward.argtypes = [vp, i64, i64, i32, i32, i32, i32, i32, vp, vp]
         lib.sig_forward_variant.restype = i32
         lib.sig_forward_variant.argtypes = [vp, i64, i64, i32, i32, i32, i32, i32, vp, vp, i32]
+        lib.sig_combine.restype = i32
+        lib.sig_combine.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
         lib.sig_variant_name.restype = ctypes.c_char_p
         lib.sig_variant_name.argtypes = [i64, i64, i32, i32, i32, i32, i32, i32]
         lib.sig_status_string.restype = ctypes.c_char_p
@@ -141,6 +144,39 @@ def sig_forward(path, N: int, stream: bool = False, basepoint: bool = False, out
         hip_stream = torch.cuda.current_stream().cuda_stream
         status = sig_forward_raw(path.data_ptr(), B, L, d, N, int(stream), int(basepoint), dtype,
                                  out.data_ptr(), hip_stream, variant)
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return out
+
+
+def sig_combine(a, b, d: int, N: int, out=None):
+    """Group product a [x] b of two batches of signatures `[B, S]` held in GPU torch tensors
+    (the signature of two adjacent intervals joined, by Chen's identity)."""
+    import torch
+
+    for t in (a, b):
+        if not isinstance(t, torch.Tensor) or not t.is_cuda:
+            raise TypeError("sig_combine needs torch tensors on the GPU (there is no CPU path)")
+    if a.dtype != b.dtype or a.device != b.device or a.shape != b.shape or a.dim() != 2:
+        raise ValueError("a and b must be [B, S] tensors of the same dtype, shape and device")
+    if a.dtype == torch.float32:
+        dtype = SIG_F32
+    elif a.dtype == torch.float64:
+        dtype = SIG_F64
+    else:
+        raise TypeError("signatures must be float32 or float64")
+    S = sig_signature_channels(d, N)
+    if S < 0 or a.shape[1] != S:
+        raise ValueError(f"signatures of d={d}, N={N} have {S} channels, got {a.shape[1]}")
+    if not (a.is_contiguous() and b.is_contiguous()):
+        raise ValueError("a and b must be contiguous")
+    if out is None:
+        out = torch.empty_like(a)
+    elif out.dtype != a.dtype or out.device != a.device or out.shape != a.shape or not out.is_contiguous():
+        raise ValueError("out must match a")
+    with torch.cuda.device(a.device):
+        status = int(load_library().sig_combine(a.data_ptr(), b.data_ptr(), a.shape[0], d, N, dtype,
+                                                out.data_ptr(), torch.cuda.current_stream().cuda_stream))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out

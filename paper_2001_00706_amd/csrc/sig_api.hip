@@ -156,6 +156,30 @@ sig_status sig_forward_variant(const void *path, int64_t B, int64_t L, int d, in
     return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
 }
 
+sig_status sig_combine(const void *a, const void *b, int64_t B, int d, int N, sig_dtype dtype,
+                       void *out, hipStream_t hip_stream)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
+    if (B < 0 || d < 1 || N < 1 || N > SIG_MAX_DEPTH) return SIG_ERR_INVALID_ARG;
+    sig::Shape sh;
+    if (!fill_levels(d, N, sh)) return SIG_ERR_OVERFLOW;
+    if (B > 0 && sh.S > kMaxElems / B) return SIG_ERR_OVERFLOW;
+    sh.B = B;
+    sh.L = 0;
+    sh.n_inc = 0;
+    sh.stream = sh.basepoint = 0;
+    if (B == 0) return SIG_OK;
+    if (a == nullptr || b == nullptr || out == nullptr) return SIG_ERR_INVALID_ARG;
+    if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
+    const hipError_t err =
+        dtype == SIG_F32
+            ? sig::launch_combine_f32(sh, static_cast<const float *>(a), static_cast<const float *>(b),
+                                      static_cast<float *>(out), hip_stream)
+            : sig::launch_combine_f64(sh, static_cast<const double *>(a), static_cast<const double *>(b),
+                                      static_cast<double *>(out), hip_stream);
+    return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
 sig_status sig_forward(const void *path, int64_t B, int64_t L, int d, int N,
                        int stream, int basepoint, sig_dtype dtype,
                        void *out, hipStream_t hip_stream)

@@ -27,6 +27,11 @@ bool generic_supported(const Shape &sh, sig_dtype dtype);
 hipError_t launch_generic_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_generic_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
 
+// Group product of two batches of signatures (any d, N with S < 2^31).
+bool combine_supported(const Shape &sh);
+hipError_t launch_combine_f32(const Shape &sh, const float *a, const float *b, float *out, hipStream_t st);
+hipError_t launch_combine_f64(const Shape &sh, const double *a, const double *b, double *out, hipStream_t st);
+
 // Small-state family: S <= 512 scalars, one wavefront per path, state in LDS, words decoded once.
 bool small_supported(const Shape &sh);
 hipError_t launch_small_f32(const Shape &sh, const float *path, float *out, hipStream_t st);

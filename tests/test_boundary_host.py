@@ -108,6 +108,19 @@ def test_validation_happens_before_any_device_work(lib):
     assert raw(0, 0, 4, 2, 2, 0, 0, sig.SIG_F32, 0, 0) == sig.SIG_OK
 
 
+def test_combine_validation(lib):
+    f = lib.sig_combine
+    dummy = 0x1000
+    assert f(dummy, dummy, -1, 2, 2, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_INVALID_ARG
+    assert f(dummy, dummy, 2, 0, 2, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_INVALID_ARG
+    assert f(dummy, dummy, 2, 2, 0, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_INVALID_ARG
+    assert f(dummy, dummy, 2, 2, 2, 5, dummy, 0) == sig.SIG_ERR_INVALID_ARG
+    assert f(0, dummy, 2, 2, 2, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_INVALID_ARG
+    assert f(dummy, dummy, 2, 1024, 5, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_OVERFLOW
+    assert f(dummy, dummy, 2, 2, 32, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_UNSUPPORTED
+    assert f(0, 0, 0, 2, 2, sig.SIG_F32, 0, 0) == sig.SIG_OK
+
+
 def test_variant_names(lib):
     assert sig.sig_variant_name(32, 16, 2, 4, False, False, variant=sig.SIG_VARIANT_GENERIC) == "generic"
     assert sig.sig_variant_name(32, 1, 2, 4, False, False) == "invalid"

@@ -348,3 +348,38 @@ def test_two_streams_at_once():
     sb.synchronize()
     for ga, gb in outs:
         assert torch.equal(ga, ra) and torch.equal(gb, rb)
+
+
+# ------------------------------------------------------------------ group product
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("B,d,N", [(3, 1, 4), (2, 2, 1), (5, 2, 7), (4, 3, 4), (2, 4, 6), (1, 8, 4), (2, 16, 3)])
+def test_combine_matches_the_oracle_group_product(B, d, N, dtype):
+    torch = torch_mod()
+    xa = uniform_paths(B, 5, d, seed=300 + d, lo=-0.6, hi=0.6)
+    xb = uniform_paths(B, 4, d, seed=400 + N, lo=-0.6, hi=0.6)
+    a64, b64 = orc.signature(xa, N), orc.signature(xb, N)
+    a, b = a64.astype(dtype), b64.astype(dtype)
+    want = np.stack([orc.group_mul(a[i].astype(np.float64), b[i].astype(np.float64), d, N) for i in range(B)])
+    out = torch.full((B, a.shape[1]), float("nan"), dtype=torch.from_numpy(a).dtype, device="cuda:0")
+    got = sig.sig_combine(torch.from_numpy(a).to("cuda:0"), torch.from_numpy(b).to("cuda:0"), d, N, out=out)
+    torch.cuda.synchronize()
+    batch, single = level_errors(got.cpu().numpy(), want, d, N)
+    assert np.all(batch <= TOL[dtype]) and np.all(single <= TOL_SINGLE[dtype]), (batch, single)
+
+
+def test_chunked_scan_plus_combine_equals_the_whole_scan():
+    # Chen's identity on the GPU path: scan two halves that share the middle point, then join them
+    torch = torch_mod()
+    w = WORKLOADS[1]
+    x = workload_paths(w)[:64]
+    xt = torch.from_numpy(x).to("cuda:0")
+    whole = sig.sig_forward(xt, w.N)
+    left = sig.sig_forward(xt[:, :65].contiguous(), w.N)
+    right = sig.sig_forward(xt[:, 64:].contiguous(), w.N)
+    joined = sig.sig_combine(left, right, w.d, w.N)
+    torch.cuda.synchronize()
+    batch, _ = level_errors(joined.cpu().numpy(), whole.cpu().numpy().astype(np.float64), w.d, w.N)
+    assert np.all(batch <= 1e-5), batch
+    want = orc.signature(x[:8], w.N)
+    batch, _ = level_errors(joined[:8].cpu().numpy(), want, w.d, w.N)
+    assert np.all(batch <= 1e-4), batch
