@@ -11,12 +11,15 @@
 namespace sig {
 namespace {
 
-template <typename T>
+// D: the channel count when it is one of the common ones (division by a constant is a multiply
+// and a shift), 0 for any other d (division by the runtime value).
+template <typename T, int D>
 __global__ void __launch_bounds__(256)
 sig_combine_kernel(Shape sh, const T *__restrict__ a, const T *__restrict__ b, T *__restrict__ out)
 {
     const uint32_t S = uint32_t(sh.S);
     const int N = sh.N;
+    const uint32_t d = D > 0 ? uint32_t(D) : uint32_t(sh.d);
     for (int64_t p = blockIdx.y; p < sh.B; p += gridDim.y) {
         const T *ap = a + p * int64_t(S);
         const T *bp = b + p * int64_t(S);
@@ -26,11 +29,52 @@ sig_combine_kernel(Shape sh, const T *__restrict__ a, const T *__restrict__ b, T
             while (k < N && i >= uint32_t(sh.off[k + 1])) ++k;
             const uint32_t idx = i - uint32_t(sh.off[k]);
             T acc = ap[i] + bp[i];
-            for (int j = 1; j < k; ++j) {
-                const uint32_t tail = uint32_t(sh.pw[k - j]);  // d^(k-j) words of length k-j
-                acc += ap[uint32_t(sh.off[j]) + idx / tail] * bp[uint32_t(sh.off[k - j]) + idx % tail];
+            // peel letters off the end of the word: prefix w_1..w_j and suffix w_{j+1}..w_k, j = k-1 .. 1
+            uint32_t prefix = idx, suffix = 0, scale = 1;
+            for (int j = k - 1; j >= 1; --j) {
+                const uint32_t letter = prefix % d;
+                prefix /= d;
+                suffix += letter * scale;
+                scale *= d;
+                acc += ap[uint32_t(sh.off[j]) + prefix] * bp[uint32_t(sh.off[k - j]) + suffix];
             }
             op[i] = acc;
+        }
+    }
+}
+
+// Four consecutive words per thread, for channel counts that are multiples of 4 (then every level
+// size and offset is a multiple of 4 too): the four words differ only in their last letter, so each
+// term is one broadcast scalar of `a` times four consecutive scalars of `b`, and all traffic moves
+// in 4-scalar vectors.
+template <typename T, int D>
+__global__ void __launch_bounds__(256)
+sig_combine_vec4_kernel(Shape sh, const T *__restrict__ a, const T *__restrict__ b, T *__restrict__ out)
+{
+    static_assert(D % 4 == 0, "vector path needs d to be a multiple of 4");
+    typedef T T4 __attribute__((ext_vector_type(4)));
+    const uint32_t S4 = uint32_t(sh.S) / 4;
+    const int N = sh.N;
+    for (int64_t p = blockIdx.y; p < sh.B; p += gridDim.y) {
+        const T *ap = a + p * sh.S;
+        const T *bp = b + p * sh.S;
+        T *op = out + p * sh.S;
+        for (uint32_t v = blockIdx.x * blockDim.x + threadIdx.x; v < S4; v += gridDim.x * blockDim.x) {
+            const uint32_t i = 4 * v;
+            int k = 1;
+            while (k < N && i >= uint32_t(sh.off[k + 1])) ++k;
+            const uint32_t idx = i - uint32_t(sh.off[k]);
+            T4 acc = *reinterpret_cast<const T4 *>(ap + i) + *reinterpret_cast<const T4 *>(bp + i);
+            uint32_t prefix = idx, suffix = 0, scale = 1;
+            for (int j = k - 1; j >= 1; --j) {
+                const uint32_t letter = prefix % D;   // for j = k-1 this is the (4-aligned) last letter
+                prefix /= D;
+                suffix += letter * scale;
+                scale *= D;
+                acc += ap[uint32_t(sh.off[j]) + prefix] *
+                       *reinterpret_cast<const T4 *>(bp + uint32_t(sh.off[k - j]) + suffix);
+            }
+            *reinterpret_cast<T4 *>(op + i) = acc;
         }
     }
 }
@@ -40,7 +84,27 @@ hipError_t launch_combine(const Shape &sh, const T *a, const T *b, T *out, hipSt
 {
     const unsigned bx = unsigned((sh.S + 255) / 256 < 4096 ? (sh.S + 255) / 256 : 4096);
     const unsigned by = unsigned(sh.B < 65535 ? sh.B : 65535);
-    hipLaunchKernelGGL(sig_combine_kernel<T>, dim3(bx, by), dim3(256), 0, st, sh, a, b, out);
+    const dim3 grid(bx, by), block(256);
+    const bool aligned = (reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) | reinterpret_cast<uintptr_t>(out)) %
+                             (4 * sizeof(T)) == 0;
+    if (aligned && (sh.d == 4 || sh.d == 8 || sh.d == 16)) {
+        const dim3 grid4(unsigned((sh.S / 4 + 255) / 256 < 4096 ? (sh.S / 4 + 255) / 256 : 4096), by);
+        if (sh.d == 4) hipLaunchKernelGGL((sig_combine_vec4_kernel<T, 4>), grid4, block, 0, st, sh, a, b, out);
+        if (sh.d == 8) hipLaunchKernelGGL((sig_combine_vec4_kernel<T, 8>), grid4, block, 0, st, sh, a, b, out);
+        if (sh.d == 16) hipLaunchKernelGGL((sig_combine_vec4_kernel<T, 16>), grid4, block, 0, st, sh, a, b, out);
+        return hipGetLastError();
+    }
+    switch (sh.d) {
+        case 2: hipLaunchKernelGGL((sig_combine_kernel<T, 2>), grid, block, 0, st, sh, a, b, out); break;
+        case 3: hipLaunchKernelGGL((sig_combine_kernel<T, 3>), grid, block, 0, st, sh, a, b, out); break;
+        case 4: hipLaunchKernelGGL((sig_combine_kernel<T, 4>), grid, block, 0, st, sh, a, b, out); break;
+        case 5: hipLaunchKernelGGL((sig_combine_kernel<T, 5>), grid, block, 0, st, sh, a, b, out); break;
+        case 6: hipLaunchKernelGGL((sig_combine_kernel<T, 6>), grid, block, 0, st, sh, a, b, out); break;
+        case 7: hipLaunchKernelGGL((sig_combine_kernel<T, 7>), grid, block, 0, st, sh, a, b, out); break;
+        case 8: hipLaunchKernelGGL((sig_combine_kernel<T, 8>), grid, block, 0, st, sh, a, b, out); break;
+        case 16: hipLaunchKernelGGL((sig_combine_kernel<T, 16>), grid, block, 0, st, sh, a, b, out); break;
+        default: hipLaunchKernelGGL((sig_combine_kernel<T, 0>), grid, block, 0, st, sh, a, b, out); break;
+    }
     return hipGetLastError();
 }
 
