@@ -1,54 +1,64 @@
 // Small-state kernel family: signatures of at most 512 scalars (e.g. d = 2 up to depth 8, d = 3 up
 // to depth 5, any d at depth 1 or 2 while S <= 512), fp32 or fp64, final and stream mode.
 //
-// One wavefront scans one path; the state lives in LDS and every lane owns up to 8 words of it.
+// One wavefront scans one path; the state lives in LDS and every lane owns up to 8 words of it (1, 2, 4 or 8: a template parameter).
 // The fused multiply-exponentiate (paper section 4.1, eq. "fusedterm") is applied element-wise:
 // the new coefficient of a word w = w_1..w_k is the end of the scalar Horner chain
-//     u_1 = z[w_1]/k + A_1[w_1],  u_i = u_{i-1} * z[w_i]/(k-i+1) + A_i[w_1..w_i],  A_k[w] <- u_k
+//     u_0 = 1,  u_i = u_{i-1} * z[w_i]/(k-i+1) + A_i[w_1..w_i],  A_k[w] <- u_k
 // over the prefixes of w.  Which prefixes and letters a lane needs never changes, so they are
-// decoded once, before the scan, into registers; a step is then a handful of LDS reads and FMAs.
-// All words are updated at once from the old state: read everything, barrier, write back.
+// decoded once, before the scan, into registers.  Every chain is run at full length N: a word of
+// level k < N starts with N-k idle links u <- u * 1 + 0, which read a constant 1 kept at the end
+// of every row of scaled increments and a constant 0 kept behind the state, so the step has no
+// divergent control flow.  The scaled increments z/m, m = 1..N, are tabulated for a whole tile of
+// increments at a time; a step is then 2N LDS reads and N FMAs per word.  A workgroup is a single
+// wavefront, whose LDS accesses complete in program order, so a step reads all of its operands from
+// the old state and then overwrites the state in place.
 #include "sig_internal.h"
 
 namespace sig {
 namespace {
 
 constexpr int kSmallMaxWords = 512;   // S this family accepts
-constexpr int kSmallWordsPerLane = 8;
 constexpr int kSmallTile = 64;        // increments staged in LDS at a time
 
-template <typename T, int N>
+// n / d for 0 <= n < 4096 and 1 <= d <= 64 with magic = ceil(2^20 / d): the product stays below 2^32
+// and the excess n * (magic*d - 2^20) / (d * 2^20) < n / 2^20 < 1/d never carries into the quotient.
+__device__ __forceinline__ int small_div(int n, unsigned magic) { return int((unsigned(n) * magic) >> 20); }
+
+// W = words of the state per lane (the state has at most 64 W scalars).
+template <typename T, int N, int W>
 __global__ void __launch_bounds__(64)
 sig_small_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
 {
+    __shared__ T st[kSmallMaxWords + 64];             // state; st[S] stays 0
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    T *st = reinterpret_cast<T *>(smem_raw);          // state, S scalars (padded to kSmallMaxWords)
-    T *zs = st + kSmallMaxWords;                      // zs[(m-1)*d + c] = z[c]/m for the current increment
-    T *inc = zs + N * sh.d;                           // staged increments [kSmallTile][d]
+    T *zt = reinterpret_cast<T *>(smem_raw);          // zt[s*row + (m-1)*d + c] = z_s[c]/m, zt[s*row + N*d] = 1
 
     const int lane = threadIdx.x;
     const int d = sh.d;
     const int S = int(sh.S);
+    const int row = N * d + 1;
+    const unsigned magic = ((1u << 20) + unsigned(d) - 1u) / unsigned(d);
 
-    // decode this lane's words once: level, letters and prefix offsets
-    int level[kSmallWordsPerLane];
-    int where[kSmallWordsPerLane][N];  // where[j][i-1] = (offset of the i-letter prefix) << 8 | (i-th letter)
+    // decode this lane's words once: link i of word j reads the state at where[j][i] >> 16 and the
+    // scaled increment at (where[j][i] & 0xffff) of the current row
+    int where[W][N];
 #pragma unroll
-    for (int j = 0; j < kSmallWordsPerLane; ++j) {
+    for (int j = 0; j < W; ++j) {
         const int wi = lane + 64 * j;
-        level[j] = 0;
 #pragma unroll
-        for (int i = 0; i < N; ++i) where[j][i] = 0;
+        for (int i = 0; i < N; ++i) where[j][i] = (S << 16) | (N * d);   // idle link
         if (wi < S) {
             int k = 1;
             while (k < N && wi >= int(sh.off[k + 1])) ++k;
-            level[j] = k;
             int idx = wi - int(sh.off[k]);  // index inside level k
 #pragma unroll
             for (int i = N; i >= 1; --i) {
                 if (i <= k) {
-                    where[j][i - 1] = ((int(sh.off[i]) + idx) << 8) | (idx % d);
-                    idx /= d;
+                    // prefix of i letters; its last letter is scaled by 1/(k-i+1)
+                    const int q = small_div(idx, magic);
+                    where[j][N - k + i - 1] = ((int(sh.off[i]) + idx) << 16) | ((k - i) * d + idx - q * d);
+                    idx = q;
                 }
             }
         }
@@ -57,14 +67,15 @@ sig_small_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
     for (int64_t b = blockIdx.x; b < sh.B; b += gridDim.x) {
         const T *x = path + b * sh.L * d;
         T *o = out + b * (sh.stream ? sh.n_inc * int64_t(S) : int64_t(S));
-        for (int i = lane; i < S; i += 64) st[i] = T(0);
+        for (int i = lane; i <= S; i += 64) st[i] = T(0);
 
         for (int64_t t0 = 0; t0 < sh.n_inc; t0 += kSmallTile) {
             const int nt = int(sh.n_inc - t0 < kSmallTile ? sh.n_inc - t0 : kSmallTile);
             __syncthreads();
             for (int i = lane; i < nt * d; i += 64) {
-                const int64_t s = t0 + i / d;
-                const int c = i % d;
+                const int si = small_div(i, magic);
+                const int c = i - si * d;
+                const int64_t s = t0 + si;
                 T hi, lo;
                 if (sh.basepoint) {
                     hi = x[s * d + c];
@@ -73,44 +84,40 @@ sig_small_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
                     hi = x[(s + 1) * d + c];
                     lo = x[s * d + c];
                 }
-                inc[i] = hi - lo;
+                const T z = hi - lo;
+#pragma unroll
+                for (int m = 1; m <= N; ++m) zt[si * row + (m - 1) * d + c] = z / T(m);
             }
+            if (lane < nt) zt[lane * row + N * d] = T(1);
             __syncthreads();
             for (int s = 0; s < nt; ++s) {
-                for (int i = lane; i < N * d; i += 64) {
-                    const int m = i / d + 1;
-                    zs[i] = inc[s * d + (i - (m - 1) * d)] / T(m);
-                }
-                __syncthreads();
-                T fresh[kSmallWordsPerLane];
+                const T *zr = zt + s * row;
+                T fresh[W];
 #pragma unroll
-                for (int j = 0; j < kSmallWordsPerLane; ++j) {
-                    const int k = level[j];
-                    T u = T(0);
+                for (int j = 0; j < W; ++j) {
+                    T zi[N], a[N];
 #pragma unroll
-                    for (int i = 1; i <= N; ++i) {
-                        if (i <= k) {
-                            const int wd = where[j][i - 1];
-                            const T zi = zs[(k - i) * d + (wd & 255)];   // z[w_i] / (k - i + 1)
-                            const T a = st[wd >> 8];
-                            u = i == 1 ? zi + a : u * zi + a;
-                        }
+                    for (int i = 0; i < N; ++i) {
+                        zi[i] = zr[where[j][i] & 0xffff];
+                        a[i] = st[where[j][i] >> 16];
                     }
+                    T u = T(1);
+#pragma unroll
+                    for (int i = 0; i < N; ++i) u = u * zi[i] + a[i];
                     fresh[j] = u;
                 }
                 __syncthreads();
 #pragma unroll
-                for (int j = 0; j < kSmallWordsPerLane; ++j) {
+                for (int j = 0; j < W; ++j) {
                     const int wi = lane + 64 * j;
                     if (wi < S) {
                         st[wi] = fresh[j];
                         if (sh.stream) o[(t0 + s) * S + wi] = fresh[j];
                     }
                 }
-                // the next step's zs and reads come after the barrier at the top of that step
+                __syncthreads();
             }
         }
-        __syncthreads();
         if (!sh.stream)
             for (int i = lane; i < S; i += 64) o[i] = st[i];
         __syncthreads();
@@ -120,10 +127,17 @@ sig_small_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
 template <typename T, int N>
 hipError_t launch_small_n(const Shape &sh, const T *path, T *out, hipStream_t st)
 {
-    const size_t lds = sizeof(T) * (size_t(kSmallMaxWords) + size_t(N) * size_t(sh.d) + size_t(kSmallTile) * size_t(sh.d));
+    const size_t lds = sizeof(T) * size_t(kSmallTile) * (size_t(N) * size_t(sh.d) + 1);
     const int64_t max_grid = 1 << 20;
     const unsigned grid = unsigned(sh.B < max_grid ? sh.B : max_grid);
-    hipLaunchKernelGGL((sig_small_kernel<T, N>), dim3(grid), dim3(64), lds, st, sh, path, out);
+    if (sh.S <= 64)
+        hipLaunchKernelGGL((sig_small_kernel<T, N, 1>), dim3(grid), dim3(64), lds, st, sh, path, out);
+    else if (sh.S <= 128)
+        hipLaunchKernelGGL((sig_small_kernel<T, N, 2>), dim3(grid), dim3(64), lds, st, sh, path, out);
+    else if (sh.S <= 256)
+        hipLaunchKernelGGL((sig_small_kernel<T, N, 4>), dim3(grid), dim3(64), lds, st, sh, path, out);
+    else
+        hipLaunchKernelGGL((sig_small_kernel<T, N, 8>), dim3(grid), dim3(64), lds, st, sh, path, out);
     return hipGetLastError();
 }
 
@@ -147,8 +161,8 @@ hipError_t launch_small(const Shape &sh, const T *path, T *out, hipStream_t st)
 
 bool small_supported(const Shape &sh)
 {
-    // letters are packed into 8 bits; the state, the per-step scalings and one tile of increments
-    // (at most (512 + 8*64 + 64*64) scalars) must fit the 64 KB of LDS a workgroup gets by default
+    // S <= 512 bounds N*d by 64 (d = 64 at depth 1), so one tile of scaled increments is at most
+    // 64 * 65 scalars: with the state, well inside the 64 KB of LDS a workgroup gets by default
     return sh.S <= kSmallMaxWords && sh.N <= 8 && sh.d <= 64;
 }
 
