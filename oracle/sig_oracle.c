@@ -25,7 +25,9 @@
  * the identification of appendix A.2.2.
  *
  * Pinned by tests/test_oracle_pins.py against closed forms, invariants, brute force from
- * the integral definition and a hand-computed example; nothing here is "parity unpinned".
+ * the integral definition and a hand-computed example; the gradient (second half of the file)
+ * by tests/test_oracle_backward_pins.py against finite differences of the pinned forward and
+ * closed forms.  Nothing here is "parity unpinned".
  *
  * SIG_ORACLE_MUTANT (never defined in a normal build) plants one deliberate mistake, numbered
  * below, so that tests/test_oracle_mutants.py can check that the pins notice each of them.
@@ -186,6 +188,147 @@ int sig_oracle_forward_f64(const double *path, int64_t B, int64_t L, int d, int 
 #pragma omp parallel for schedule(dynamic, 1) reduction(| : failed)
     for (int64_t b = 0; b < B; ++b)
         failed |= one_path(path + b * L * d, L, d, N, stream, basepoint, out + b * out_stride, S);
+    return failed ? 2 : 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Gradient of a scalar loss with respect to the path, given the gradient with respect to the
+ * signature (section 5.3, appendix C).  The paper obtains it by treating the transform as a
+ * composition of differentiable primitives (appendix C, first paragraph); this is that chain
+ * rule written out over the oracle's own forward computation: every intermediate signature and
+ * every exponential is kept in memory, and each primitive's adjoint is the transpose of the
+ * loops above.  No reversibility, no recomputation, no Horner scheme.
+ * ------------------------------------------------------------------------------------------ */
+
+/* Adjoint of sig_oracle_mul: C = A [x] B, gC given; ADDS the gradients into gA and gB.
+ * C_k = B_k + A_k + sum_{j=1..k-1} A_j (x) B_{k-j}. */
+static void mul_adjoint(const double *A, const double *B, const double *gC, int d, int N, double *gA, double *gB)
+{
+    for (int k = 1; k <= N; ++k) {
+        const int64_t off_k = level_offset(d, k);
+        const int64_t n_k = ipow64(d, k);
+        const double *gk = gC + off_k;
+        for (int64_t w = 0; w < n_k; ++w) {
+            if (SIG_ORACLE_MUTANT != 9) gB[off_k + w] += gk[w]; /* mutant 9: the A_0 (x) B_k term forgotten */
+            gA[off_k + w] += gk[w];
+        }
+        for (int j = 1; j <= k - 1; ++j) {
+            const int m = k - j;
+            const int64_t off_j = level_offset(d, j), off_m = level_offset(d, m);
+            const int64_t n_j = ipow64(d, j), n_m = ipow64(d, m);
+            for (int64_t u = 0; u < n_j; ++u)
+                for (int64_t v = 0; v < n_m; ++v) {
+                    const double g = gk[u * n_m + v];
+                    gA[off_j + u] += g * B[off_m + v];
+                    gB[off_m + v] += A[off_j + u] * g;
+                }
+        }
+    }
+}
+
+/* Adjoint of sig_oracle_exp: E_1 = z, E_k[w j] = E_{k-1}[w] z[j] / k.  gE is consumed (its lower
+ * levels are used as accumulators); the gradient with respect to z is WRITTEN to gz. */
+static void exp_adjoint(const double *z, const double *E, double *gE, int d, int N, double *gz)
+{
+    for (int j = 0; j < d; ++j) gz[j] = 0.0;
+    for (int k = N; k >= 2; --k) {
+        const double *prev = E + level_offset(d, k - 1);
+        double *g_prev = gE + level_offset(d, k - 1);
+        const double *g_cur = gE + level_offset(d, k);
+        const int64_t n_prev = ipow64(d, k - 1);
+        const double div = (double)(SIG_ORACLE_MUTANT == 10 ? 1 : k); /* mutant 10: the 1/k of the recurrence forgotten */
+        for (int64_t w = 0; w < n_prev; ++w)
+            for (int j = 0; j < d; ++j) {
+                const double g = g_cur[w * d + j];
+                g_prev[w] += g * z[j] / div;
+                gz[j] += g * prev[w] / div;
+            }
+    }
+    for (int j = 0; j < d; ++j) gz[j] += gE[j];
+}
+
+static int one_path_backward(const double *x, const double *gout, int64_t L, int d, int N, int stream, int basepoint,
+                             double *gx, int64_t S)
+{
+    const int64_t n_inc = basepoint ? L : L - 1;
+    double *z = (double *)malloc(sizeof(double) * (size_t)(n_inc * d));
+    double *A = (double *)calloc((size_t)((n_inc + 1) * S), sizeof(double)); /* A[s] = signature after s increments; A[0] = identity = 0 */
+    double *E = (double *)malloc(sizeof(double) * (size_t)(n_inc * S));
+    double *gA = (double *)calloc((size_t)S, sizeof(double));
+    double *gA_prev = (double *)malloc(sizeof(double) * (size_t)S);
+    double *gE = (double *)malloc(sizeof(double) * (size_t)S);
+    double *gz = (double *)malloc(sizeof(double) * (size_t)d);
+    if (!z || !A || !E || !gA || !gA_prev || !gE || !gz) {
+        free(z); free(A); free(E); free(gA); free(gA_prev); free(gE); free(gz);
+        return 1;
+    }
+    /* forward, everything kept */
+    for (int64_t s = 0; s < n_inc; ++s) {
+        for (int c = 0; c < d; ++c) {
+            double hi, lo;
+            if (basepoint) {
+                hi = x[s * d + c];
+                lo = (s == 0) ? 0.0 : x[(s - 1) * d + c];
+            } else {
+                hi = x[(s + 1) * d + c];
+                lo = x[s * d + c];
+            }
+            z[s * d + c] = hi - lo;
+        }
+        sig_oracle_exp(z + s * d, d, N, E + s * S);
+        sig_oracle_mul(A + s * S, E + s * S, d, N, A + (s + 1) * S);
+    }
+    /* backward */
+    for (int64_t i = 0; i < L * d; ++i) gx[i] = 0.0;
+    if (!stream) memcpy(gA, gout, sizeof(double) * (size_t)S);
+    for (int64_t s = n_inc - 1; s >= 0; --s) {
+        if (stream) { /* entry s of the output is A[s+1] */
+            const double *g = gout + (SIG_ORACLE_MUTANT == 11 && s > 0 ? s - 1 : s) * S; /* mutant 11: stream gradients shifted by one entry */
+            for (int64_t w = 0; w < S; ++w) gA[w] += g[w];
+        }
+        memset(gA_prev, 0, sizeof(double) * (size_t)S);
+        memset(gE, 0, sizeof(double) * (size_t)S);
+        mul_adjoint(A + s * S, E + s * S, gA, d, N, gA_prev, gE);
+        exp_adjoint(z + s * d, E + s * S, gE, d, N, gz);
+        for (int c = 0; c < d; ++c) {
+            if (basepoint) {
+                gx[s * d + c] += gz[c];
+                if (s > 0) gx[(s - 1) * d + c] -= gz[c];
+            } else {
+                gx[(s + 1) * d + c] += gz[c];
+                gx[s * d + c] -= (SIG_ORACLE_MUTANT == 12 ? -gz[c] : gz[c]); /* mutant 12: sign of the lower end point */
+            }
+        }
+        double *t = gA; gA = gA_prev; gA_prev = t;
+    }
+    free(z); free(A); free(E); free(gA); free(gA_prev); free(gE); free(gz);
+    return 0;
+}
+
+/* Batched gradient, host pointers, fp64.
+ *   path: [B][L][d];  grad_out: same shape as the forward output ([B][S] or [B][n_inc][S]);
+ *   grad_path: [B][L][d], overwritten with d(loss)/d(path) where d(loss)/d(output) = grad_out.
+ * Same argument checks and return codes as sig_oracle_forward_f64. */
+int sig_oracle_backward_f64(const double *path, const double *grad_out, int64_t B, int64_t L, int d, int N,
+                            int stream, int basepoint, double *grad_path, int num_threads)
+{
+    const int64_t S = sig_oracle_channels(d, N);
+    if (S < 0 || B < 0) return 1;
+    if (basepoint ? (L < 1) : (L < 2)) return 1;
+    if (B == 0) return 0;
+    if (!path || !grad_out || !grad_path) return 1;
+    const int64_t n_inc = basepoint ? L : L - 1;
+    const int64_t out_stride = stream ? n_inc * S : S;
+    int failed = 0;
+#ifdef _OPENMP
+    if (num_threads > 0) omp_set_num_threads(num_threads);
+#else
+    (void)num_threads;
+#endif
+#pragma omp parallel for schedule(dynamic, 1) reduction(| : failed)
+    for (int64_t b = 0; b < B; ++b)
+        failed |= one_path_backward(path + b * L * d, grad_out + b * out_stride, L, d, N, stream, basepoint,
+                                    grad_path + b * L * d, S);
     return failed ? 2 : 0;
 }
 

@@ -49,6 +49,8 @@ def _declare(lib):
     lib.sig_oracle_mul.argtypes = [dp, dp, i32, i32, dp]
     lib.sig_oracle_forward_f64.restype = i32
     lib.sig_oracle_forward_f64.argtypes = [dp, i64, i64, i32, i32, i32, i32, dp, i32]
+    lib.sig_oracle_backward_f64.restype = i32
+    lib.sig_oracle_backward_f64.argtypes = [dp, dp, i64, i64, i32, i32, i32, i32, dp, i32]
     lib.sig_oracle_max_threads.restype = i32
     lib.sig_oracle_max_threads.argtypes = []
     return lib
@@ -152,3 +154,32 @@ def signature(path, N: int, stream: bool = False, basepoint: bool = False,
     if rc != 0:
         raise RuntimeError(f"sig_oracle_forward_f64 failed with code {rc}")
     return out
+
+
+def signature_backward(path, grad_out, N: int, stream: bool = False, basepoint: bool = False,
+                       num_threads: int = 0) -> np.ndarray:
+    """fp64 gradient with respect to the path of a loss whose gradient with respect to
+    `signature(path, N, stream, basepoint)` is `grad_out` (section 5.3, appendix C).
+
+    path `[B, L, d]`, grad_out `[B, S]` or `[B, n_inc, S]`; returns `[B, L, d]`.
+    """
+    x = np.ascontiguousarray(path, dtype=np.float64)
+    g = np.ascontiguousarray(grad_out, dtype=np.float64)
+    if x.ndim != 3:
+        raise ValueError("path must have shape [B, L, d]")
+    B, L, d = x.shape
+    S = channels(d, N)
+    if S < 0:
+        raise ValueError("bad d or N")
+    n_inc = L if basepoint else L - 1
+    if n_inc < 1:
+        raise ValueError("a path needs at least two points (one with basepoint)")
+    want = (B, n_inc, S) if stream else (B, S)
+    if g.shape != want:
+        raise ValueError(f"grad_out has shape {g.shape}, expected {want}")
+    gx = np.empty_like(x)
+    rc = _load().sig_oracle_backward_f64(_dptr(x), _dptr(g), B, L, d, N, int(stream), int(basepoint),
+                                         _dptr(gx), int(num_threads))
+    if rc != 0:
+        raise RuntimeError(f"sig_oracle_backward_f64 failed with code {rc}")
+    return gx

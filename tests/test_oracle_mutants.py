@@ -1,10 +1,11 @@
 """Each deliberate mistake that can be planted in the oracle (`-DSIG_ORACLE_MUTANT=n`, CPU only)
-must be noticed by at least one pin of tests/test_oracle_pins.py; the unmodified oracle by none."""
+must be noticed by at least one pin of tests/test_oracle_pins.py or tests/test_oracle_backward_pins.py; the unmodified oracle by none."""
 import inspect
 
 import pytest
 
 from oracle import sig_oracle as orc
+from tests import test_oracle_backward_pins as backward_pins
 from tests import test_oracle_pins as pins
 
 MUTANTS = {
@@ -16,13 +17,18 @@ MUTANTS = {
     6: "basepoint ignored",
     7: "stream mode writes only the last prefix",
     8: "level 3 stored one scalar too early",
+    9: "gradient: the A_0 (x) B_k term of the product forgotten",
+    10: "gradient: the 1/k of the exponential recurrence forgotten",
+    11: "gradient: stream-mode output gradients shifted by one entry",
+    12: "gradient: wrong sign at the lower end point of an increment",
 }
 
 
 def _pin_calls():
     """(name, callable) for every pin, with its parametrisations expanded."""
     calls = []
-    for name, fn in inspect.getmembers(pins, inspect.isfunction):
+    members = inspect.getmembers(pins, inspect.isfunction) + inspect.getmembers(backward_pins, inspect.isfunction)
+    for name, fn in members:
         if not name.startswith("test_"):
             continue
         marks = [m for m in getattr(fn, "pytestmark", []) if m.name == "parametrize"]
