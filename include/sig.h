@@ -16,7 +16,8 @@
  * under the identification of appendix A.2.2.
  *
  * All functions are thread-safe and keep no state between calls.  Nothing here allocates
- * or frees device memory, and nothing synchronises the device.
+ * or frees device memory (sig_backward takes its workspace from the caller), and nothing
+ * synchronises the device.
  */
 #ifndef SIG_H_
 #define SIG_H_
@@ -116,6 +117,31 @@ sig_status sig_forward_variant(const void *path, int64_t B, int64_t L, int d, in
  * Enqueued on `hip_stream`, no wait.  Errors as for sig_forward (SIG_ERR_UNSUPPORTED if S >= 2^31). */
 sig_status sig_combine(const void *a, const void *b, int64_t B, int d, int N, sig_dtype dtype,
                        void *out, hipStream_t hip_stream);
+
+/* Gradient of a scalar loss with respect to the path, given its gradient with respect to the output of
+ * sig_forward called with the same arguments (section 5.3; appendix C).  Nothing from the forward pass is kept
+ * but its output: each earlier signature is recovered from the next one by undoing the increment between them
+ * (appendix C.1, reversibility, eq. "reverse"), and the increment's gradient comes from the transpose of the fused
+ * multiply-exponentiate (section 4.1, eq. "fusedterm").
+ *
+ *   path       DEVICE pointer, [B][L][d], as given to sig_forward; read only.
+ *   sig        DEVICE pointer, the forward output for (path, N, stream, basepoint): [B][S], or [B][n_inc][S] in
+ *              stream mode; read only.
+ *   grad_out   DEVICE pointer, same shape as `sig`: d(loss)/d(output); read only.
+ *   grad_path  DEVICE pointer, [B][L][d], fully overwritten with d(loss)/d(path); must not overlap the inputs.
+ *   workspace  DEVICE pointer to at least sig_backward_workspace_bytes(...) bytes, 16-byte aligned, contents
+ *              irrelevant on entry and undefined on return; may be NULL when that size is 0.  Calls that overlap
+ *              in time must not share a workspace.
+ * Enqueued on `hip_stream`, no wait.  d <= 64 and S < 2^30 (else SIG_ERR_UNSUPPORTED).  Other errors as for
+ * sig_forward; a missing or short workspace is SIG_ERR_INVALID_ARG.  Deterministic. */
+sig_status sig_backward(const void *path, const void *sig, const void *grad_out, int64_t B, int64_t L, int d, int N,
+                        int stream, int basepoint, sig_dtype dtype, void *grad_path,
+                        void *workspace, int64_t workspace_bytes, hipStream_t hip_stream);
+
+/* Bytes of device workspace sig_backward needs for these arguments on the current device: 0 when the per-path
+ * working set (the signature, its cotangent and the Horner terms, about 2.7 S scalars) fits on chip.
+ * -1 on invalid or unsupported arguments. */
+int64_t sig_backward_workspace_bytes(int64_t B, int64_t L, int d, int N, int stream, int basepoint, sig_dtype dtype);
 
 /* Name of the kernel family that `variant` resolves to for this shape ("generic",
  * "mfma_d4", ...), or "unsupported" / "invalid".  The string is static. */

@@ -19,6 +19,8 @@ from .binding import (  # noqa: F401
     SIG_VARIANT_SMALL,
     SigError,
     load_library,
+    sig_backward,
+    sig_backward_workspace_bytes,
     sig_combine,
     sig_forward,
     sig_forward_raw,

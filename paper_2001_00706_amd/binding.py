@@ -27,6 +27,8 @@ EXPORTED_SYMBOLS = (
     "sig_forward",
     "sig_forward_variant",
     "sig_combine",
+    "sig_backward",
+    "sig_backward_workspace_bytes",
     "sig_variant_name",
     "sig_status_string",
 )
@@ -64,6 +66,10 @@ def load_library() -> ctypes.CDLL:
         lib.sig_forward_variant.argtypes = [vp, i64, i64, i32, i32, i32, i32, i32, vp, vp, i32]
         lib.sig_combine.restype = i32
         lib.sig_combine.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
+        lib.sig_backward.restype = i32
+        lib.sig_backward.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, vp, i64, vp]
+        lib.sig_backward_workspace_bytes.restype = i64
+        lib.sig_backward_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32, i32]
         lib.sig_variant_name.restype = ctypes.c_char_p
         lib.sig_variant_name.argtypes = [i64, i64, i32, i32, i32, i32, i32, i32]
         lib.sig_status_string.restype = ctypes.c_char_p
@@ -180,3 +186,58 @@ def sig_combine(a, b, d: int, N: int, out=None):
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out
+
+
+def sig_backward_workspace_bytes(B: int, L: int, d: int, N: int, stream: bool, basepoint: bool,
+                                 dtype: int = SIG_F32) -> int:
+    return int(load_library().sig_backward_workspace_bytes(B, L, d, N, int(stream), int(basepoint), dtype))
+
+
+def sig_backward(path, sig, grad_out, N: int, stream: bool = False, basepoint: bool = False,
+                 grad_path=None, workspace=None):
+    """Gradient with respect to `path` of a loss whose gradient with respect to
+    `sig = sig_forward(path, N, stream, basepoint)` is `grad_out`; all GPU torch tensors.
+
+    Returns (and, if given, fills) `grad_path`, shaped like `path`.  `workspace` is a uint8 GPU
+    tensor of at least `sig_backward_workspace_bytes(...)` bytes; one is allocated through torch
+    when the call needs it and none is given.
+    """
+    import torch
+
+    for t in (path, sig, grad_out):
+        if not isinstance(t, torch.Tensor) or not t.is_cuda:
+            raise TypeError("sig_backward needs torch tensors on the GPU (there is no CPU path)")
+    if path.dim() != 3:
+        raise ValueError("path must have shape [B, L, d]")
+    if path.dtype == torch.float32:
+        dtype = SIG_F32
+    elif path.dtype == torch.float64:
+        dtype = SIG_F64
+    else:
+        raise TypeError("path must be float32 or float64")
+    B, L, d = path.shape
+    S = sig_signature_channels(d, N)
+    n_inc = L if basepoint else L - 1
+    shape = (B, n_inc, S) if stream else (B, S)
+    for name, t in (("sig", sig), ("grad_out", grad_out)):
+        if t.dtype != path.dtype or t.device != path.device or tuple(t.shape) != shape or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous {path.dtype} tensor of shape {shape} on {path.device}")
+    if not path.is_contiguous():
+        raise ValueError("path must be contiguous")
+    if grad_path is None:
+        grad_path = torch.empty_like(path)
+    elif grad_path.dtype != path.dtype or grad_path.device != path.device or grad_path.shape != path.shape \
+            or not grad_path.is_contiguous():
+        raise ValueError("grad_path must match path")
+    with torch.cuda.device(path.device):
+        need = sig_backward_workspace_bytes(B, L, d, N, stream, basepoint, dtype)
+        if need > 0 and workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=path.device)
+        ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) \
+            if workspace is not None else (0, 0)
+        status = int(load_library().sig_backward(path.data_ptr(), sig.data_ptr(), grad_out.data_ptr(), B, L, d, N,
+                                                 int(stream), int(basepoint), dtype, grad_path.data_ptr(),
+                                                 ws_ptr, ws_bytes, torch.cuda.current_stream().cuda_stream))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return grad_path

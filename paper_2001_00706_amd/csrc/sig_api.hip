@@ -180,6 +180,39 @@ sig_status sig_combine(const void *a, const void *b, int64_t B, int d, int N, si
     return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
 }
 
+int64_t sig_backward_workspace_bytes(int64_t B, int64_t L, int d, int N, int stream, int basepoint, sig_dtype dtype)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return -1;
+    sig::Shape sh;
+    if (make_shape(B, L, d, N, stream, basepoint, sh) != SIG_OK) return -1;
+    if (B == 0) return 0;
+    return sig::backward_workspace_bytes(sh, dtype);
+}
+
+sig_status sig_backward(const void *path, const void *sig, const void *grad_out, int64_t B, int64_t L, int d, int N,
+                        int stream, int basepoint, sig_dtype dtype, void *grad_path,
+                        void *workspace, int64_t workspace_bytes, hipStream_t hip_stream)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
+    sig::Shape sh;
+    const sig_status st = make_shape(B, L, d, N, stream, basepoint, sh);
+    if (st != SIG_OK) return st;
+    if (B == 0) return SIG_OK;
+    if (path == nullptr || sig == nullptr || grad_out == nullptr || grad_path == nullptr) return SIG_ERR_INVALID_ARG;
+    const int64_t need = sig::backward_workspace_bytes(sh, dtype);
+    if (need < 0) return SIG_ERR_UNSUPPORTED;
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return SIG_ERR_INVALID_ARG;
+    const hipError_t err =
+        dtype == SIG_F32
+            ? sig::launch_backward_f32(sh, static_cast<const float *>(path), static_cast<const float *>(sig),
+                                       static_cast<const float *>(grad_out), static_cast<float *>(grad_path), workspace,
+                                       workspace_bytes, hip_stream)
+            : sig::launch_backward_f64(sh, static_cast<const double *>(path), static_cast<const double *>(sig),
+                                       static_cast<const double *>(grad_out), static_cast<double *>(grad_path), workspace,
+                                       workspace_bytes, hip_stream);
+    return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
 sig_status sig_forward(const void *path, int64_t B, int64_t L, int d, int N,
                        int stream, int basepoint, sig_dtype dtype,
                        void *out, hipStream_t hip_stream)

@@ -32,6 +32,15 @@ bool combine_supported(const Shape &sh);
 hipError_t launch_combine_f32(const Shape &sh, const float *a, const float *b, float *out, hipStream_t st);
 hipError_t launch_combine_f64(const Shape &sh, const double *a, const double *b, double *out, hipStream_t st);
 
+// Gradient with respect to the path (any N, d <= 64, S < 2^30).  `backward_workspace_bytes` is what the launch
+// needs in `workspace` (0 when everything fits LDS, -1 if unsupported).
+bool backward_supported(const Shape &sh);
+int64_t backward_workspace_bytes(const Shape &sh, sig_dtype dtype);
+hipError_t launch_backward_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
+                               void *workspace, int64_t workspace_bytes, hipStream_t st);
+hipError_t launch_backward_f64(const Shape &sh, const double *path, const double *sig, const double *gout, double *gpath,
+                               void *workspace, int64_t workspace_bytes, hipStream_t st);
+
 // Small-state family: S <= 512 scalars, one wavefront per path, state in LDS, words decoded once.
 bool small_supported(const Shape &sh);
 hipError_t launch_small_f32(const Shape &sh, const float *path, float *out, hipStream_t st);

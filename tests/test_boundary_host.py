@@ -121,6 +121,28 @@ def test_combine_validation(lib):
     assert f(0, 0, 0, 2, 2, sig.SIG_F32, 0, 0) == sig.SIG_OK
 
 
+def test_backward_validation(lib):
+    f = lib.sig_backward
+    p = 0x1000
+    args = lambda **kw: [kw.get("path", p), kw.get("sig", p), kw.get("gout", p), kw.get("B", 2), kw.get("L", 4),
+                         kw.get("d", 2), kw.get("N", 2), 0, kw.get("basepoint", 0), kw.get("dtype", sig.SIG_F32),
+                         kw.get("gpath", p), 0, 0, 0]
+    assert f(*args(B=-1)) == sig.SIG_ERR_INVALID_ARG
+    assert f(*args(d=0)) == sig.SIG_ERR_INVALID_ARG
+    assert f(*args(N=33)) == sig.SIG_ERR_INVALID_ARG
+    assert f(*args(L=1)) == sig.SIG_ERR_INVALID_ARG
+    assert f(*args(dtype=7)) == sig.SIG_ERR_INVALID_ARG
+    for name in ("path", "sig", "gout", "gpath"):
+        assert f(*args(**{name: 0})) == sig.SIG_ERR_INVALID_ARG
+    assert f(*args(d=1024, N=5)) == sig.SIG_ERR_OVERFLOW
+    assert f(*args(d=65, N=1)) == sig.SIG_ERR_UNSUPPORTED          # more channels than the smallest workgroup has threads
+    assert f(*args(d=2, N=31)) == sig.SIG_ERR_UNSUPPORTED          # 2^32 scalars per signature
+    assert f(*args(B=0, path=0, sig=0, gout=0, gpath=0)) == sig.SIG_OK
+    assert sig.sig_backward_workspace_bytes(2, 1, 2, 2, False, False) == -1
+    assert sig.sig_backward_workspace_bytes(2, 4, 65, 1, False, False) == -1
+    assert sig.sig_backward_workspace_bytes(0, 4, 2, 2, False, False) == 0
+
+
 def test_variant_names(lib):
     assert sig.sig_variant_name(32, 16, 2, 4, False, False, variant=sig.SIG_VARIANT_GENERIC) == "generic"
     assert sig.sig_variant_name(32, 1, 2, 4, False, False) == "invalid"
