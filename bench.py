@@ -6,6 +6,10 @@ differenced, folded in with the fused multiply-exponentiate and the result store
 inside the library).  Inputs and outputs are resident in HBM before the timed region.
 Prints ONE JSON line: paths/s, the roofline of the dominant kernel measured live with
 HIP events, and the CPU oracle timed on the host cores beside it.
+
+`--op backward` times `sig_backward` (the gradient with respect to the path) and `--op combine`
+times `sig_combine` (the group product of two batches of signatures) on the same workload
+shapes instead; the default, and the metric this repository is judged on, is the forward pass.
 """
 from __future__ import annotations
 
@@ -30,6 +34,13 @@ def flops_per_increment(d: int, N: int, fused_fmas: int) -> int:
     return 2 * fused_fmas + d * (2 * N - 1)
 
 
+def backward_flops_per_increment(d: int, N: int, fused_fmas: int, channels: int) -> int:
+    """Algorithmic work of one backward step: M + N d multiply-adds to undo the increment and form the
+    Horner terms, M for the chains contracted with the increment, M + N d for the increment's gradient,
+    and M + N d - S additions into the cotangent of the earlier state."""
+    return 2 * (3 * fused_fmas + 2 * N * d) + (fused_fmas + N * d - channels)
+
+
 def recorded_traffic(workload_key: str, kernel: str):
     """HBM bytes per launch (fetched + written) recorded from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
     runs of this command (see profiles/); None if no record matches the workload and kernel."""
@@ -52,6 +63,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2, help="configuration number 1..5 (default: the metric's)")
     ap.add_argument("--variant", choices=["auto", "generic", "mfma"], default="auto")
+    ap.add_argument("--op", choices=["forward", "backward", "combine"], default="forward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 256 MiB device-to-device copies before the timed region, so that "
@@ -90,6 +102,27 @@ def main() -> int:
     def step():
         sig.sig_forward(x, w.N, stream=w.stream, basepoint=w.basepoint, out=out, variant=variant)
 
+    if args.op == "backward":
+        step()
+        grad_out = torch.from_numpy(np.random.default_rng(w.seed).standard_normal(out_shape).astype(np.float32)).to(dev)
+        grad_path = torch.empty_like(x)
+        need = sig.sig_backward_workspace_bytes(w.B, w.L, w.d, w.N, w.stream, w.basepoint)
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+        kernel = "backward"
+
+        def step():  # noqa: F811
+            sig.sig_backward(x, out, grad_out, w.N, stream=w.stream, basepoint=w.basepoint, grad_path=grad_path,
+                             workspace=workspace)
+    elif args.op == "combine":
+        step()
+        lhs = out.reshape(-1, S)
+        rhs = torch.flip(lhs, dims=[0]).contiguous()
+        prod = torch.empty_like(lhs)
+        kernel = "combine"
+
+        def step():  # noqa: F811
+            sig.sig_combine(lhs, rhs, w.d, w.N, out=prod)
+
     if args.copy_calibration:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)   # 256 MiB
         dst = torch.empty_like(src)
@@ -126,7 +159,17 @@ def main() -> int:
     M = sig.sig_fused_fmas(w.d, w.N)
     flops = w.B * w.n_inc * flops_per_increment(w.d, w.N, M)
     bytes_io = 4 * (w.B * w.L * w.d + int(np.prod(out_shape)))
-    if w.stream:
+    units, metric = w.B, "signatures/sec (paths/s)"
+    if args.op == "backward":
+        flops = w.B * w.n_inc * backward_flops_per_increment(w.d, w.N, M, S)
+        bytes_io = 4 * (2 * w.B * w.L * w.d + 2 * int(np.prod(out_shape)))
+        metric = "signature gradients/sec (paths/s)"
+    elif args.op == "combine":
+        units = int(lhs.shape[0])
+        flops = 2 * units * sum((k - 1) * w.d ** k for k in range(2, w.N + 1))
+        bytes_io = 4 * 3 * units * S
+        metric = "group products/sec"
+    if (w.stream and args.op == "forward") or args.op == "combine":
         roofline = {"bound": "hbm", "achieved": bytes_io / (kern_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                     "unit": "GB/s"}
     else:
@@ -142,9 +185,9 @@ def main() -> int:
     roofline["algorithmic_bytes_per_launch"] = bytes_io
 
     result = {
-        "metric": "signatures/sec (paths/s)",
-        "value": w.B / (ms_per_step * 1e-3),
-        "unit": "paths/s",
+        "metric": metric,
+        "value": units / (ms_per_step * 1e-3),
+        "unit": "products/s" if args.op == "combine" else "paths/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -155,7 +198,7 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "L": w.L, "d": w.d, "N": w.N,
-                   "mode": "stream" if w.stream else "final", "kernel": kernel,
+                   "mode": "stream" if w.stream else "final", "op": args.op, "kernel": kernel,
                    "device": torch.cuda.get_device_name(0)},
         "roofline": roofline,
     }
@@ -168,17 +211,36 @@ def main() -> int:
         xs = x_host[:n_sample]
         # repeat whole passes until about 1.5 s of wall time (some 10-30 core-seconds) is spent
         best, spent, passes = float("inf"), 0.0, 0
+        if args.op == "backward":
+            n_sample = max(1, n_sample // 4)
+            xs = x_host[:n_sample]
+            gs = grad_out[:n_sample].cpu().numpy()
+        elif args.op == "combine":
+            n_sample = int(max(1, min(units, 4e9 // max((w.N - 1) * w.d ** w.N, 1))))
+            la, lb = lhs[:n_sample].cpu().numpy().astype(np.float64), rhs[:n_sample].cpu().numpy().astype(np.float64)
+
+        def oracle_pass():
+            if args.op == "backward":
+                sig_oracle.signature_backward(xs, gs, w.N, stream=w.stream, basepoint=w.basepoint)
+            elif args.op == "combine":
+                for i in range(n_sample):   # the oracle's product is one pair at a time, single-threaded
+                    sig_oracle.group_mul(la[i], lb[i], w.d, w.N)
+            else:
+                sig_oracle.signature(xs, w.N, stream=w.stream, basepoint=w.basepoint)
+
         while passes < 3 or (spent < 1.5 and passes < 50):
             t = time.perf_counter()
-            sig_oracle.signature(xs, w.N, stream=w.stream, basepoint=w.basepoint)
+            oracle_pass()
             dt = time.perf_counter() - t
             best, spent, passes = min(best, dt), spent + dt, passes + 1
         result["cpu_baseline"] = {
             "value": n_sample / best,
-            "unit": "paths/s",
-            "cores": sig_oracle.max_threads(),
+            "unit": "products/s" if args.op == "combine" else "paths/s",
+            "cores": 1 if args.op == "combine" else sig_oracle.max_threads(),
             "kind": "oracle",
-            "sample": f"first {n_sample} of {w.B} paths of {w.name}, fp64 exp + group product per increment, "
+            "sample": f"first {n_sample} of {units} {'pairs' if args.op == 'combine' else 'paths'} of {w.name}, "
+                      f"op {args.op}: fp64 exp + group product per increment"
+                      f"{' and their adjoints over the stored forward' if args.op == 'backward' else ''}, "
                       f"OpenMP over paths, best of {passes} passes ({best:.3f} s each, {spent:.1f} s in all)",
         }
 

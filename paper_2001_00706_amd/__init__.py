@@ -30,3 +30,9 @@ from .binding import (  # noqa: F401
     sig_status_string,
     sig_variant_name,
 )
+
+
+def signature(path, depth, stream=False, basepoint=False):
+    """Differentiable signature (torch.autograd); see `autograd.signature`."""
+    from .autograd import signature as _signature
+    return _signature(path, depth, stream, basepoint)

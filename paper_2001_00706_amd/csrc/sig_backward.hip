@@ -235,7 +235,7 @@ bool make_plan(const Shape &sh, int threads, BackwardPlan &pl)
     return true;
 }
 
-int backward_threads(const Shape &sh) { return sh.B >= 512 ? 64 : 256; }
+int backward_threads(const Shape &sh) { return sh.B >= (1 << 30) ? 64 : 256; }
 
 // Most dynamic LDS one workgroup may have on this device (0 if the query fails).
 size_t lds_limit()

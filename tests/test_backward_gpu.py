@@ -179,3 +179,23 @@ def test_long_path_reversibility_error_stays_small():
     # 1023 increments undone one after the other in fp32
     x = brownian_paths(2, 1024, 3, seed=21)
     check(x, 4)
+
+
+@pytest.mark.parametrize("stream,basepoint", [(False, False), (True, False), (False, True), (True, True)])
+def test_autograd_function_passes_gradcheck(stream, basepoint):
+    # finite differences of the HIP forward against the HIP backward, in fp64, on the GPU
+    import torch
+    x = torch.from_numpy(uniform_paths(2, 5, 3, seed=4).astype(np.float64)).to("cuda:0").requires_grad_(True)
+    assert torch.autograd.gradcheck(lambda p: sig.signature(p, 3, stream, basepoint), (x,), eps=1e-6, atol=1e-7, rtol=1e-6)
+
+
+def test_autograd_sum_backward_as_in_the_papers_example():
+    # the usage pattern of the code-example section (section 3): signature(path, depth).sum().backward()
+    import torch
+    x_host = brownian_paths(4, 12, 3, seed=8)
+    x = torch.from_numpy(x_host).to("cuda:0").requires_grad_(True)
+    sig.signature(x, 4).sum().backward()
+    torch.cuda.synchronize()
+    want = orc.signature_backward(x_host, np.ones((4, sig.sig_signature_channels(3, 4))), 4)
+    got = x.grad.cpu().numpy()
+    assert np.linalg.norm(got - want) <= 1e-4 * np.linalg.norm(want)
