@@ -118,25 +118,58 @@ sig_status sig_forward_variant(const void *path, int64_t B, int64_t L, int d, in
 sig_status sig_combine(const void *a, const void *b, int64_t B, int d, int N, sig_dtype dtype,
                        void *out, hipStream_t hip_stream);
 
+/* As sig_combine, for signatures that are not packed: signature p of `a` starts at a + p * a_stride scalars
+ * (likewise b, out; a stride of 0 repeats one signature for every p).  out_stride >= S; `out` must not overlap
+ * the inputs.  With a = the inverted signatures of the prefixes x_1..x_i of a path and b = the signatures of its
+ * prefixes x_1..x_j, both rows of stream-mode outputs, this answers Sig(x_i..x_j) in one product, independent of
+ * the length of the path (section 4.2). */
+sig_status sig_combine_strided(const void *a, int64_t a_stride, const void *b, int64_t b_stride, int64_t B, int d, int N,
+                               sig_dtype dtype, void *out, int64_t out_stride, hipStream_t hip_stream);
+
+/* Group inverse of `rows` signatures: out[r] = sig[r]^{-1}, which is the signature of the same path traversed
+ * backwards (section 5.4).  It is a signed permutation of the scalars: level k of the inverse holds
+ * (-1)^k times the coefficient of the reversed word.
+ *   sig, out   DEVICE pointers, [rows][S]; `out` may be `sig` itself (in place) but must not overlap it otherwise.
+ * Errors as for sig_combine. */
+sig_status sig_invert(const void *sig, int64_t rows, int d, int N, sig_dtype dtype, void *out, hipStream_t hip_stream);
+
+/* The signature with every option of section 5.5: sig_forward, then
+ *   basepoint_value  DEVICE pointer [B][d] or NULL.  With basepoint != 0 the point prepended to path b is
+ *              basepoint_value[b] (the origin if NULL); must be NULL when basepoint == 0.  16-byte alignment lets
+ *              the fastest kernels serve the call.
+ *   initial    DEVICE pointer [B][S] or NULL: the signature of the data that came before this path (whose last
+ *              point is this path's first point, or its basepoint).  The result is initial [x] Sig(path), in stream
+ *              mode for every prefix: the signature of everything so far (section 5.5, "keeping the signature
+ *              up-to-date").  Applied by one product per output signature, in place, after the scan.
+ *   inverse    != 0: every signature written is replaced by its group inverse (section 5.4), after `initial` has
+ *              been applied; `initial` itself is always a plain (not inverted) signature.
+ * Everything else, and the errors, as for sig_forward; with `initial` or `inverse`, S must be below 2^31. */
+sig_status sig_signature(const void *path, int64_t B, int64_t L, int d, int N, int stream, int basepoint,
+                         const void *basepoint_value, const void *initial, int inverse, sig_dtype dtype,
+                         void *out, hipStream_t hip_stream);
+
 /* Gradient of a scalar loss with respect to the path, given its gradient with respect to the output of
- * sig_forward called with the same arguments (section 5.3; appendix C).  Nothing from the forward pass is kept
- * but its output: each earlier signature is recovered from the next one by undoing the increment between them
- * (appendix C.1, reversibility, eq. "reverse"), and the increment's gradient comes from the transpose of the fused
- * multiply-exponentiate (section 4.1, eq. "fusedterm").
+ * sig_forward (or sig_signature without `initial` and `inverse`) called with the same arguments (section 5.3;
+ * appendix C).  Nothing from the forward pass is kept but its output: each earlier signature is recovered from the
+ * next one by undoing the increment between them (appendix C.1, reversibility, eq. "reverse"), and the increment's
+ * gradient comes from the transpose of the fused multiply-exponentiate (section 4.1, eq. "fusedterm").
  *
- *   path       DEVICE pointer, [B][L][d], as given to sig_forward; read only.
+ *   path       DEVICE pointer, [B][L][d], as given to the forward call; read only.
  *   sig        DEVICE pointer, the forward output for (path, N, stream, basepoint): [B][S], or [B][n_inc][S] in
  *              stream mode; read only.
  *   grad_out   DEVICE pointer, same shape as `sig`: d(loss)/d(output); read only.
+ *   basepoint_value  DEVICE pointer [B][d] or NULL: as for sig_signature; only with basepoint != 0.
  *   grad_path  DEVICE pointer, [B][L][d], fully overwritten with d(loss)/d(path); must not overlap the inputs.
+ *   grad_basepoint  DEVICE pointer [B][d] or NULL: if given (only with basepoint != 0), receives the gradient with
+ *              respect to the basepoint.
  *   workspace  DEVICE pointer to at least sig_backward_workspace_bytes(...) bytes, 16-byte aligned, contents
  *              irrelevant on entry and undefined on return; may be NULL when that size is 0.  Calls that overlap
  *              in time must not share a workspace.
  * Enqueued on `hip_stream`, no wait.  d <= 64 and S < 2^30 (else SIG_ERR_UNSUPPORTED).  Other errors as for
  * sig_forward; a missing or short workspace is SIG_ERR_INVALID_ARG.  Deterministic. */
 sig_status sig_backward(const void *path, const void *sig, const void *grad_out, int64_t B, int64_t L, int d, int N,
-                        int stream, int basepoint, sig_dtype dtype, void *grad_path,
-                        void *workspace, int64_t workspace_bytes, hipStream_t hip_stream);
+                        int stream, int basepoint, const void *basepoint_value, sig_dtype dtype, void *grad_path,
+                        void *grad_basepoint, void *workspace, int64_t workspace_bytes, hipStream_t hip_stream);
 
 /* Bytes of device workspace sig_backward needs for these arguments on the current device: 0 when the per-path
  * working set (the signature, its cotangent and the Horner terms, about 2.7 S scalars) fits on chip.

@@ -22,6 +22,9 @@ from .binding import (  # noqa: F401
     sig_backward,
     sig_backward_workspace_bytes,
     sig_combine,
+    sig_combine_strided,
+    sig_invert,
+    sig_signature,
     sig_forward,
     sig_forward_raw,
     sig_fused_fmas,
@@ -32,7 +35,14 @@ from .binding import (  # noqa: F401
 )
 
 
-def signature(path, depth, stream=False, basepoint=False):
+def signature(path, depth, stream=False, basepoint=False, inverse=False):
     """Differentiable signature (torch.autograd); see `autograd.signature`."""
     from .autograd import signature as _signature
-    return _signature(path, depth, stream, basepoint)
+    return _signature(path, depth, stream, basepoint, inverse)
+
+
+def __getattr__(name):
+    if name == "Path":   # needs torch, so it is imported on first use
+        from .path import Path
+        return Path
+    raise AttributeError(name)

@@ -28,6 +28,9 @@ EXPORTED_SYMBOLS = (
     "sig_forward_variant",
     "sig_combine",
     "sig_backward",
+    "sig_combine_strided",
+    "sig_invert",
+    "sig_signature",
     "sig_backward_workspace_bytes",
     "sig_variant_name",
     "sig_status_string",
@@ -67,7 +70,13 @@ def load_library() -> ctypes.CDLL:
         lib.sig_combine.restype = i32
         lib.sig_combine.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
         lib.sig_backward.restype = i32
-        lib.sig_backward.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, vp, i64, vp]
+        lib.sig_backward.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, i32, vp, i32, vp, vp, vp, i64, vp]
+        lib.sig_combine_strided.restype = i32
+        lib.sig_combine_strided.argtypes = [vp, i64, vp, i64, i64, i32, i32, i32, vp, i64, vp]
+        lib.sig_invert.restype = i32
+        lib.sig_invert.argtypes = [vp, i64, i32, i32, i32, vp, vp]
+        lib.sig_signature.restype = i32
+        lib.sig_signature.argtypes = [vp, i64, i64, i32, i32, i32, i32, vp, vp, i32, i32, vp, vp]
         lib.sig_backward_workspace_bytes.restype = i64
         lib.sig_backward_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32, i32]
         lib.sig_variant_name.restype = ctypes.c_char_p
@@ -193,31 +202,54 @@ def sig_backward_workspace_bytes(B: int, L: int, d: int, N: int, stream: bool, b
     return int(load_library().sig_backward_workspace_bytes(B, L, d, N, int(stream), int(basepoint), dtype))
 
 
-def sig_backward(path, sig, grad_out, N: int, stream: bool = False, basepoint: bool = False,
-                 grad_path=None, workspace=None):
+def _dtype_of(t):
+    import torch
+    if t.dtype == torch.float32:
+        return SIG_F32
+    if t.dtype == torch.float64:
+        return SIG_F64
+    raise TypeError("tensors must be float32 or float64")
+
+
+def _check_gpu(name, *tensors):
+    import torch
+    for t in tensors:
+        if not isinstance(t, torch.Tensor) or not t.is_cuda:
+            raise TypeError(f"{name} needs torch tensors on the GPU (there is no CPU path)")
+
+
+def _basepoint_args(path, basepoint):
+    """(flag, tensor or None) from False / True / a `[B, d]` tensor."""
+    import torch
+    if isinstance(basepoint, torch.Tensor):
+        B, _, d = path.shape
+        if basepoint.dtype != path.dtype or basepoint.device != path.device or tuple(basepoint.shape) != (B, d) \
+                or not basepoint.is_contiguous():
+            raise ValueError(f"basepoint must be a contiguous {path.dtype} tensor of shape {(B, d)} on {path.device}")
+        return 1, basepoint
+    return int(bool(basepoint)), None
+
+
+def sig_backward(path, sig, grad_out, N: int, stream: bool = False, basepoint=False,
+                 grad_path=None, workspace=None, grad_basepoint=None):
     """Gradient with respect to `path` of a loss whose gradient with respect to
     `sig = sig_forward(path, N, stream, basepoint)` is `grad_out`; all GPU torch tensors.
 
-    Returns (and, if given, fills) `grad_path`, shaped like `path`.  `workspace` is a uint8 GPU
-    tensor of at least `sig_backward_workspace_bytes(...)` bytes; one is allocated through torch
-    when the call needs it and none is given.
+    Returns (and, if given, fills) `grad_path`, shaped like `path`.  `basepoint` may be a `[B, d]` tensor
+    (then `sig` comes from `sig_signature`); `grad_basepoint`, if given, receives its gradient.
+    `workspace` is a uint8 GPU tensor of at least `sig_backward_workspace_bytes(...)` bytes; one is
+    allocated through torch when the call needs it and none is given.
     """
     import torch
 
-    for t in (path, sig, grad_out):
-        if not isinstance(t, torch.Tensor) or not t.is_cuda:
-            raise TypeError("sig_backward needs torch tensors on the GPU (there is no CPU path)")
+    _check_gpu("sig_backward", path, sig, grad_out)
     if path.dim() != 3:
         raise ValueError("path must have shape [B, L, d]")
-    if path.dtype == torch.float32:
-        dtype = SIG_F32
-    elif path.dtype == torch.float64:
-        dtype = SIG_F64
-    else:
-        raise TypeError("path must be float32 or float64")
+    dtype = _dtype_of(path)
     B, L, d = path.shape
+    bp_flag, bp_value = _basepoint_args(path, basepoint)
     S = sig_signature_channels(d, N)
-    n_inc = L if basepoint else L - 1
+    n_inc = L if bp_flag else L - 1
     shape = (B, n_inc, S) if stream else (B, S)
     for name, t in (("sig", sig), ("grad_out", grad_out)):
         if t.dtype != path.dtype or t.device != path.device or tuple(t.shape) != shape or not t.is_contiguous():
@@ -229,15 +261,100 @@ def sig_backward(path, sig, grad_out, N: int, stream: bool = False, basepoint: b
     elif grad_path.dtype != path.dtype or grad_path.device != path.device or grad_path.shape != path.shape \
             or not grad_path.is_contiguous():
         raise ValueError("grad_path must match path")
+    if grad_basepoint is not None and (grad_basepoint.dtype != path.dtype or grad_basepoint.device != path.device
+                                       or tuple(grad_basepoint.shape) != (B, d) or not grad_basepoint.is_contiguous()):
+        raise ValueError("grad_basepoint must be a contiguous [B, d] tensor like path")
     with torch.cuda.device(path.device):
-        need = sig_backward_workspace_bytes(B, L, d, N, stream, basepoint, dtype)
+        need = sig_backward_workspace_bytes(B, L, d, N, stream, bool(bp_flag), dtype)
         if need > 0 and workspace is None:
             workspace = torch.empty(need, dtype=torch.uint8, device=path.device)
         ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) \
             if workspace is not None else (0, 0)
-        status = int(load_library().sig_backward(path.data_ptr(), sig.data_ptr(), grad_out.data_ptr(), B, L, d, N,
-                                                 int(stream), int(basepoint), dtype, grad_path.data_ptr(),
-                                                 ws_ptr, ws_bytes, torch.cuda.current_stream().cuda_stream))
+        status = int(load_library().sig_backward(
+            path.data_ptr(), sig.data_ptr(), grad_out.data_ptr(), B, L, d, N, int(stream), bp_flag,
+            bp_value.data_ptr() if bp_value is not None else 0, dtype, grad_path.data_ptr(),
+            grad_basepoint.data_ptr() if grad_basepoint is not None else 0,
+            ws_ptr, ws_bytes, torch.cuda.current_stream().cuda_stream))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return grad_path
+
+
+def sig_signature(path, N: int, stream: bool = False, basepoint=False, inverse: bool = False, initial=None, out=None):
+    """`sig_forward` with every option of section 5.5: `basepoint` False / True / a `[B, d]` tensor,
+    `initial` a `[B, S]` signature of the data that came before, `inverse` for the inverted signature."""
+    import torch
+
+    _check_gpu("sig_signature", path)
+    if path.dim() != 3 or not path.is_contiguous():
+        raise ValueError("path must be a contiguous tensor of shape [B, L, d]")
+    dtype = _dtype_of(path)
+    B, L, d = path.shape
+    bp_flag, bp_value = _basepoint_args(path, basepoint)
+    S = sig_signature_channels(d, N)
+    n_inc = L if bp_flag else L - 1
+    if sig_output_elems(B, L, d, N, stream, bool(bp_flag)) < 0:
+        status = int(load_library().sig_signature(path.data_ptr(), B, L, d, N, int(stream), bp_flag, 0, 0, 0, dtype, 0, 0))
+        raise SigError(status, sig_status_string(status))
+    shape = (B, n_inc, S) if stream else (B, S)
+    if initial is not None:
+        _check_gpu("sig_signature", initial)
+        if initial.dtype != path.dtype or initial.device != path.device or tuple(initial.shape) != (B, S) \
+                or not initial.is_contiguous():
+            raise ValueError(f"initial must be a contiguous {path.dtype} tensor of shape {(B, S)} on {path.device}")
+    if out is None:
+        out = torch.empty(shape, dtype=path.dtype, device=path.device)
+    elif out.dtype != path.dtype or out.device != path.device or tuple(out.shape) != shape or not out.is_contiguous():
+        raise ValueError(f"out must be a contiguous {path.dtype} tensor of shape {shape} on {path.device}")
+    with torch.cuda.device(path.device):
+        status = int(load_library().sig_signature(
+            path.data_ptr(), B, L, d, N, int(stream), bp_flag, bp_value.data_ptr() if bp_value is not None else 0,
+            initial.data_ptr() if initial is not None else 0, int(bool(inverse)), dtype, out.data_ptr(),
+            torch.cuda.current_stream().cuda_stream))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return out
+
+
+def sig_invert(sig, d: int, N: int, out=None):
+    """Group inverses of signatures `[..., S]` (the signatures of the reversed paths); `out` may be `sig`."""
+    import torch
+
+    _check_gpu("sig_invert", sig)
+    dtype = _dtype_of(sig)
+    S = sig_signature_channels(d, N)
+    if S < 0 or sig.shape[-1] != S or not sig.is_contiguous():
+        raise ValueError(f"sig must be contiguous with {S} channels last")
+    if out is None:
+        out = torch.empty_like(sig)
+    elif out.dtype != sig.dtype or out.device != sig.device or out.shape != sig.shape or not out.is_contiguous():
+        raise ValueError("out must match sig")
+    rows = sig.numel() // S if S > 0 else 0
+    with torch.cuda.device(sig.device):
+        status = int(load_library().sig_invert(sig.data_ptr(), rows, d, N, dtype, out.data_ptr(),
+                                               torch.cuda.current_stream().cuda_stream))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return out
+
+
+def sig_combine_strided(a, a_stride: int, b, b_stride: int, B: int, d: int, N: int, out, out_stride: int):
+    """`out[p] = a[p] [x] b[p]` for p < B where signature p of each operand starts `p * stride` scalars
+    after the tensor's first element (the tensors must be large enough for that; not checked beyond size)."""
+    import torch
+
+    _check_gpu("sig_combine_strided", a, b, out)
+    dtype = _dtype_of(a)
+    S = sig_signature_channels(d, N)
+    for t, stride in ((a, a_stride), (b, b_stride), (out, out_stride)):
+        if t.dtype != a.dtype or t.device != a.device or not t.is_contiguous():
+            raise ValueError("a, b and out must be contiguous tensors of one dtype on one device")
+        if B > 0 and (B - 1) * stride + S > t.numel():
+            raise ValueError("an operand is too small for B signatures at this stride")
+    with torch.cuda.device(a.device):
+        status = int(load_library().sig_combine_strided(a.data_ptr(), a_stride, b.data_ptr(), b_stride, B, d, N, dtype,
+                                                        out.data_ptr(), out_stride,
+                                                        torch.cuda.current_stream().cuda_stream))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return out

@@ -38,6 +38,7 @@ sig_status make_shape(int64_t B, int64_t L, int d, int N, int stream, int basepo
     sh.L = L;
     sh.stream = stream ? 1 : 0;
     sh.basepoint = basepoint ? 1 : 0;
+    sh.basepoint_value = nullptr;
     sh.n_inc = basepoint ? L : L - 1;
     // path elements B*L*d and output elements B*[n_inc*]S must stay below kMaxElems
     if (L > kMaxElems / d) return SIG_ERR_OVERFLOW;
@@ -57,7 +58,8 @@ enum class Family { Generic, Mfma, MfmaShard, MfmaD16, MfmaD8, Small, None };
 // The pointers decide only alignment: the matrix-core family loads and stores 16 bytes per lane.
 Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const void *path, const void *out)
 {
-    const bool aligned = reinterpret_cast<uintptr_t>(out) % 16 == 0 && reinterpret_cast<uintptr_t>(path) % 16 == 0;
+    const bool aligned = reinterpret_cast<uintptr_t>(out) % 16 == 0 && reinterpret_cast<uintptr_t>(path) % 16 == 0 &&
+                         reinterpret_cast<uintptr_t>(sh.basepoint_value) % 16 == 0;
     const bool mfma_ok = dtype == SIG_F32 && aligned && sig::mfma_kernel_name(sh) != nullptr;
     const bool shard_ok = dtype == SIG_F32 && aligned && sig::mfma_shard_kernel_name(sh) != nullptr;
     const bool d16_ok = dtype == SIG_F32 && aligned && sig::mfma_d16_kernel_name(sh) != nullptr;
@@ -81,6 +83,32 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
         case SIG_VARIANT_SMALL: return small_ok ? Family::Small : Family::None;
     }
     return Family::None;
+}
+
+// Launches the scan of one kernel family (not Family::None).
+hipError_t launch_family(Family family, const sig::Shape &sh, sig_dtype dtype, const void *path, void *out,
+                         hipStream_t hip_stream)
+{
+    switch (family) {
+        case Family::Mfma:
+            return sig::launch_mfma_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
+        case Family::MfmaShard:
+            return sig::launch_mfma_shard_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
+        case Family::MfmaD16:
+            return sig::launch_mfma_d16_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
+        case Family::MfmaD8:
+            return sig::launch_mfma_d8_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
+        case Family::Small:
+            return dtype == SIG_F32
+                       ? sig::launch_small_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
+                       : sig::launch_small_f64(sh, static_cast<const double *>(path), static_cast<double *>(out), hip_stream);
+        case Family::Generic:
+            return dtype == SIG_F32
+                       ? sig::launch_generic_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
+                       : sig::launch_generic_f64(sh, static_cast<const double *>(path), static_cast<double *>(out), hip_stream);
+        case Family::None: break;
+    }
+    return hipErrorNotSupported;
 }
 
 bool valid_enums(sig_dtype dtype, sig_variant variant)
@@ -126,33 +154,9 @@ sig_status sig_forward_variant(const void *path, int64_t B, int64_t L, int d, in
     if (st != SIG_OK) return st;
     if (B == 0) return SIG_OK;
     if (path == nullptr || out == nullptr) return SIG_ERR_INVALID_ARG;
-    hipError_t err = hipSuccess;
-    switch (resolve(sh, dtype, variant, path, out)) {
-        case Family::Mfma:
-            err = sig::launch_mfma_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
-            break;
-        case Family::MfmaShard:
-            err = sig::launch_mfma_shard_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
-            break;
-        case Family::MfmaD16:
-            err = sig::launch_mfma_d16_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
-            break;
-        case Family::MfmaD8:
-            err = sig::launch_mfma_d8_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
-            break;
-        case Family::Small:
-            err = dtype == SIG_F32
-                      ? sig::launch_small_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
-                      : sig::launch_small_f64(sh, static_cast<const double *>(path), static_cast<double *>(out), hip_stream);
-            break;
-        case Family::Generic:
-            err = dtype == SIG_F32
-                      ? sig::launch_generic_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
-                      : sig::launch_generic_f64(sh, static_cast<const double *>(path), static_cast<double *>(out), hip_stream);
-            break;
-        case Family::None:
-            return SIG_ERR_UNSUPPORTED;
-    }
+    const Family family = resolve(sh, dtype, variant, path, out);
+    if (family == Family::None) return SIG_ERR_UNSUPPORTED;
+    const hipError_t err = launch_family(family, sh, dtype, path, out, hip_stream);
     return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
 }
 
@@ -168,6 +172,7 @@ sig_status sig_combine(const void *a, const void *b, int64_t B, int d, int N, si
     sh.L = 0;
     sh.n_inc = 0;
     sh.stream = sh.basepoint = 0;
+    sh.basepoint_value = nullptr;
     if (B == 0) return SIG_OK;
     if (a == nullptr || b == nullptr || out == nullptr) return SIG_ERR_INVALID_ARG;
     if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
@@ -190,8 +195,8 @@ int64_t sig_backward_workspace_bytes(int64_t B, int64_t L, int d, int N, int str
 }
 
 sig_status sig_backward(const void *path, const void *sig, const void *grad_out, int64_t B, int64_t L, int d, int N,
-                        int stream, int basepoint, sig_dtype dtype, void *grad_path,
-                        void *workspace, int64_t workspace_bytes, hipStream_t hip_stream)
+                        int stream, int basepoint, const void *basepoint_value, sig_dtype dtype, void *grad_path,
+                        void *grad_basepoint, void *workspace, int64_t workspace_bytes, hipStream_t hip_stream)
 {
     if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
     sig::Shape sh;
@@ -199,18 +204,107 @@ sig_status sig_backward(const void *path, const void *sig, const void *grad_out,
     if (st != SIG_OK) return st;
     if (B == 0) return SIG_OK;
     if (path == nullptr || sig == nullptr || grad_out == nullptr || grad_path == nullptr) return SIG_ERR_INVALID_ARG;
+    if (!sh.basepoint && (basepoint_value != nullptr || grad_basepoint != nullptr)) return SIG_ERR_INVALID_ARG;
+    sh.basepoint_value = basepoint_value;
     const int64_t need = sig::backward_workspace_bytes(sh, dtype);
     if (need < 0) return SIG_ERR_UNSUPPORTED;
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return SIG_ERR_INVALID_ARG;
     const hipError_t err =
         dtype == SIG_F32
             ? sig::launch_backward_f32(sh, static_cast<const float *>(path), static_cast<const float *>(sig),
-                                       static_cast<const float *>(grad_out), static_cast<float *>(grad_path), workspace,
-                                       workspace_bytes, hip_stream)
+                                       static_cast<const float *>(grad_out), static_cast<float *>(grad_path),
+                                       static_cast<float *>(grad_basepoint), workspace, workspace_bytes, hip_stream)
             : sig::launch_backward_f64(sh, static_cast<const double *>(path), static_cast<const double *>(sig),
-                                       static_cast<const double *>(grad_out), static_cast<double *>(grad_path), workspace,
-                                       workspace_bytes, hip_stream);
+                                       static_cast<const double *>(grad_out), static_cast<double *>(grad_path),
+                                       static_cast<double *>(grad_basepoint), workspace, workspace_bytes, hip_stream);
     return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
+// Shape of a batch of `rows` signatures with no path attached.
+static sig_status make_rows_shape(int64_t rows, int d, int N, sig::Shape &sh)
+{
+    if (rows < 0 || d < 1 || N < 1 || N > SIG_MAX_DEPTH) return SIG_ERR_INVALID_ARG;
+    if (!fill_levels(d, N, sh)) return SIG_ERR_OVERFLOW;
+    if (rows > 0 && sh.S > kMaxElems / rows) return SIG_ERR_OVERFLOW;
+    sh.B = rows;
+    sh.L = 0;
+    sh.n_inc = 0;
+    sh.stream = sh.basepoint = 0;
+    sh.basepoint_value = nullptr;
+    return SIG_OK;
+}
+
+sig_status sig_invert(const void *sig, int64_t rows, int d, int N, sig_dtype dtype, void *out, hipStream_t hip_stream)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
+    sig::Shape sh;
+    const sig_status st = make_rows_shape(rows, d, N, sh);
+    if (st != SIG_OK) return st;
+    if (rows == 0) return SIG_OK;
+    if (sig == nullptr || out == nullptr) return SIG_ERR_INVALID_ARG;
+    if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
+    const hipError_t err =
+        dtype == SIG_F32 ? sig::launch_invert_f32(sh, static_cast<const float *>(sig), static_cast<float *>(out), hip_stream)
+                         : sig::launch_invert_f64(sh, static_cast<const double *>(sig), static_cast<double *>(out), hip_stream);
+    return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
+sig_status sig_combine_strided(const void *a, int64_t a_stride, const void *b, int64_t b_stride, int64_t B, int d, int N,
+                               sig_dtype dtype, void *out, int64_t out_stride, hipStream_t hip_stream)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
+    sig::Shape sh;
+    const sig_status st = make_rows_shape(B, d, N, sh);
+    if (st != SIG_OK) return st;
+    if (a_stride < 0 || b_stride < 0 || out_stride < sh.S) return SIG_ERR_INVALID_ARG;
+    if (B > 0 && (a_stride > kMaxElems / B || b_stride > kMaxElems / B || out_stride > kMaxElems / B)) return SIG_ERR_OVERFLOW;
+    if (B == 0) return SIG_OK;
+    if (a == nullptr || b == nullptr || out == nullptr) return SIG_ERR_INVALID_ARG;
+    if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
+    const int64_t strides[3] = {a_stride, b_stride, out_stride};
+    const hipError_t err =
+        dtype == SIG_F32
+            ? sig::launch_combine_f32(sh, static_cast<const float *>(a), static_cast<const float *>(b),
+                                      static_cast<float *>(out), hip_stream, strides)
+            : sig::launch_combine_f64(sh, static_cast<const double *>(a), static_cast<const double *>(b),
+                                      static_cast<double *>(out), hip_stream, strides);
+    return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
+sig_status sig_signature(const void *path, int64_t B, int64_t L, int d, int N, int stream, int basepoint,
+                         const void *basepoint_value, const void *initial, int inverse, sig_dtype dtype,
+                         void *out, hipStream_t hip_stream)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
+    sig::Shape sh;
+    const sig_status st = make_shape(B, L, d, N, stream, basepoint, sh);
+    if (st != SIG_OK) return st;
+    if (!sh.basepoint && basepoint_value != nullptr) return SIG_ERR_INVALID_ARG;
+    if (B == 0) return SIG_OK;
+    if (path == nullptr || out == nullptr) return SIG_ERR_INVALID_ARG;
+    sh.basepoint_value = basepoint_value;
+    if ((initial != nullptr || inverse) && !sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
+    const Family family = resolve(sh, dtype, SIG_VARIANT_AUTO, path, out);
+    if (family == Family::None) return SIG_ERR_UNSUPPORTED;
+    hipError_t err = launch_family(family, sh, dtype, path, out, hip_stream);
+    if (err != hipSuccess) return SIG_ERR_HIP;
+    // what follows works on the rows of `out`, in place, behind the scan on the same stream
+    sig::Shape rows = sh;
+    rows.B = sh.B * (sh.stream ? sh.n_inc : 1);
+    if (initial != nullptr) {
+        const int64_t group = sh.stream ? sh.n_inc : 1;
+        err = dtype == SIG_F32
+                  ? sig::launch_left_mul_f32(rows, static_cast<const float *>(initial), group, static_cast<float *>(out), hip_stream)
+                  : sig::launch_left_mul_f64(rows, static_cast<const double *>(initial), group, static_cast<double *>(out), hip_stream);
+        if (err != hipSuccess) return SIG_ERR_HIP;
+    }
+    if (inverse) {
+        err = dtype == SIG_F32
+                  ? sig::launch_invert_f32(rows, static_cast<const float *>(out), static_cast<float *>(out), hip_stream)
+                  : sig::launch_invert_f64(rows, static_cast<const double *>(out), static_cast<double *>(out), hip_stream);
+        if (err != hipSuccess) return SIG_ERR_HIP;
+    }
+    return SIG_OK;
 }
 
 sig_status sig_forward(const void *path, int64_t B, int64_t L, int d, int N,

@@ -39,7 +39,7 @@ struct BackwardPlan {
 template <typename T, int NT, bool kLds>
 __global__ void __launch_bounds__(NT)
 sig_backward_kernel(Shape sh, BackwardPlan pl, const T *__restrict__ path, const T *__restrict__ sig,
-                    const T *__restrict__ gout, T *__restrict__ gpath, T *__restrict__ ws)
+                    const T *__restrict__ gout, T *__restrict__ gpath, T *__restrict__ gbase, T *__restrict__ ws)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int d = sh.d, N = sh.N, S = int(sh.S);
@@ -68,6 +68,7 @@ sig_backward_kernel(Shape sh, BackwardPlan pl, const T *__restrict__ path, const
 
     for (int64_t b = blockIdx.x; b < sh.B; b += gridDim.x) {
         const T *x = path + b * sh.L * d;
+        const T *bpv = static_cast<const T *>(sh.basepoint_value);
         T *gp = gpath + b * sh.L * d;
         const int64_t per_path = sh.stream ? sh.n_inc * int64_t(S) : int64_t(S);
         const T *sg = sig + b * per_path;
@@ -84,7 +85,7 @@ sig_backward_kernel(Shape sh, BackwardPlan pl, const T *__restrict__ path, const
         auto fetch = [&](int64_t s) -> T {
             if (tid >= d || s < 0) return T(0);
             const int64_t hi = sh.basepoint ? s : s + 1;
-            const T lo = hi > 0 ? x[(hi - 1) * d + tid] : T(0);
+            const T lo = hi > 0 ? x[(hi - 1) * d + tid] : bpv != nullptr ? bpv[b * d + tid] : T(0);
             return x[hi * d + tid] - lo;
         };
         T z_next = fetch(sh.n_inc - 1);
@@ -197,6 +198,8 @@ sig_backward_kernel(Shape sh, BackwardPlan pl, const T *__restrict__ path, const
         }
         // the first point only starts increment 0 (with a basepoint it was written above: it ends increment 0)
         if (!sh.basepoint && tid < d) gp[tid] = -dzv[d + tid];
+        // a basepoint only starts increment 0
+        if (sh.basepoint && gbase != nullptr && tid < d) gbase[b * d + tid] = -dzv[d + tid];
         __syncthreads();
     }
 }
@@ -254,7 +257,7 @@ bool fits_lds(const BackwardPlan &pl)
 
 template <typename T, int NT>
 hipError_t launch_backward_nt(const Shape &sh, const BackwardPlan &pl, const T *path, const T *sig, const T *gout,
-                              T *gpath, void *workspace, int64_t workspace_bytes, hipStream_t st)
+                              T *gpath, T *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st)
 {
     if (fits_lds<T>(pl)) {
         const size_t lds = (size_t(pl.small_elems) + size_t(pl.big_elems)) * sizeof(T);
@@ -265,7 +268,8 @@ hipError_t launch_backward_nt(const Shape &sh, const BackwardPlan &pl, const T *
             if (e != hipSuccess) return e;
         }
         const unsigned grid = unsigned(sh.B < (int64_t(1) << 20) ? sh.B : (int64_t(1) << 20));
-        hipLaunchKernelGGL(kernel, dim3(grid), dim3(NT), lds, st, sh, pl, path, sig, gout, gpath, static_cast<T *>(nullptr));
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(NT), lds, st, sh, pl, path, sig, gout, gpath, gbase,
+                           static_cast<T *>(nullptr));
         return hipGetLastError();
     }
     const int64_t grid = sh.B < kBackwardMaxGrid ? sh.B : kBackwardMaxGrid;
@@ -273,19 +277,20 @@ hipError_t launch_backward_nt(const Shape &sh, const BackwardPlan &pl, const T *
         return hipErrorInvalidValue;
     const size_t lds = size_t(pl.small_elems) * sizeof(T);
     hipLaunchKernelGGL((sig_backward_kernel<T, NT, false>), dim3(unsigned(grid)), dim3(NT), lds, st, sh, pl, path, sig,
-                       gout, gpath, static_cast<T *>(workspace));
+                       gout, gpath, gbase, static_cast<T *>(workspace));
     return hipGetLastError();
 }
 
 template <typename T>
-hipError_t launch_backward(const Shape &sh, const T *path, const T *sig, const T *gout, T *gpath, void *workspace,
-                           int64_t workspace_bytes, hipStream_t st)
+hipError_t launch_backward(const Shape &sh, const T *path, const T *sig, const T *gout, T *gpath, T *gbase,
+                           void *workspace, int64_t workspace_bytes, hipStream_t st)
 {
     BackwardPlan pl;
     const int threads = backward_threads(sh);
     if (!backward_supported(sh) || !make_plan(sh, threads, pl)) return hipErrorNotSupported;
-    return threads == 64 ? launch_backward_nt<T, 64>(sh, pl, path, sig, gout, gpath, workspace, workspace_bytes, st)
-                         : launch_backward_nt<T, 256>(sh, pl, path, sig, gout, gpath, workspace, workspace_bytes, st);
+    return threads == 64
+               ? launch_backward_nt<T, 64>(sh, pl, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st)
+               : launch_backward_nt<T, 256>(sh, pl, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
 }
 
 }  // namespace
@@ -308,15 +313,15 @@ int64_t backward_workspace_bytes(const Shape &sh, sig_dtype dtype)
 }
 
 hipError_t launch_backward_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
-                               void *workspace, int64_t workspace_bytes, hipStream_t st)
+                               float *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st)
 {
-    return launch_backward<float>(sh, path, sig, gout, gpath, workspace, workspace_bytes, st);
+    return launch_backward<float>(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
 }
 
 hipError_t launch_backward_f64(const Shape &sh, const double *path, const double *sig, const double *gout, double *gpath,
-                               void *workspace, int64_t workspace_bytes, hipStream_t st)
+                               double *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st)
 {
-    return launch_backward<double>(sh, path, sig, gout, gpath, workspace, workspace_bytes, st);
+    return launch_backward<double>(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
 }
 
 }  // namespace sig

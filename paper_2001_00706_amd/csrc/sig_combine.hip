@@ -11,19 +11,24 @@
 namespace sig {
 namespace {
 
+// Distance, in scalars, between consecutive signatures of each operand (S when they are packed).
+struct Strides {
+    int64_t a, b, out;
+};
+
 // D: the channel count when it is one of the common ones (division by a constant is a multiply
 // and a shift), 0 for any other d (division by the runtime value).
 template <typename T, int D>
 __global__ void __launch_bounds__(256)
-sig_combine_kernel(Shape sh, const T *__restrict__ a, const T *__restrict__ b, T *__restrict__ out)
+sig_combine_kernel(Shape sh, Strides rs, const T *__restrict__ a, const T *__restrict__ b, T *__restrict__ out)
 {
     const uint32_t S = uint32_t(sh.S);
     const int N = sh.N;
     const uint32_t d = D > 0 ? uint32_t(D) : uint32_t(sh.d);
     for (int64_t p = blockIdx.y; p < sh.B; p += gridDim.y) {
-        const T *ap = a + p * int64_t(S);
-        const T *bp = b + p * int64_t(S);
-        T *op = out + p * int64_t(S);
+        const T *ap = a + p * rs.a;
+        const T *bp = b + p * rs.b;
+        T *op = out + p * rs.out;
         for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < S; i += gridDim.x * blockDim.x) {
             int k = 1;
             while (k < N && i >= uint32_t(sh.off[k + 1])) ++k;
@@ -49,16 +54,16 @@ sig_combine_kernel(Shape sh, const T *__restrict__ a, const T *__restrict__ b, T
 // in 4-scalar vectors.
 template <typename T, int D>
 __global__ void __launch_bounds__(256)
-sig_combine_vec4_kernel(Shape sh, const T *__restrict__ a, const T *__restrict__ b, T *__restrict__ out)
+sig_combine_vec4_kernel(Shape sh, Strides rs, const T *__restrict__ a, const T *__restrict__ b, T *__restrict__ out)
 {
     static_assert(D % 4 == 0, "vector path needs d to be a multiple of 4");
     typedef T T4 __attribute__((ext_vector_type(4)));
     const uint32_t S4 = uint32_t(sh.S) / 4;
     const int N = sh.N;
     for (int64_t p = blockIdx.y; p < sh.B; p += gridDim.y) {
-        const T *ap = a + p * sh.S;
-        const T *bp = b + p * sh.S;
-        T *op = out + p * sh.S;
+        const T *ap = a + p * rs.a;
+        const T *bp = b + p * rs.b;
+        T *op = out + p * rs.out;
         for (uint32_t v = blockIdx.x * blockDim.x + threadIdx.x; v < S4; v += gridDim.x * blockDim.x) {
             const uint32_t i = 4 * v;
             int k = 1;
@@ -80,30 +85,32 @@ sig_combine_vec4_kernel(Shape sh, const T *__restrict__ a, const T *__restrict__
 }
 
 template <typename T>
-hipError_t launch_combine(const Shape &sh, const T *a, const T *b, T *out, hipStream_t st)
+hipError_t launch_combine(const Shape &sh, const T *a, const T *b, T *out, hipStream_t st, const int64_t *strides)
 {
+    const Strides rs = strides != nullptr ? Strides{strides[0], strides[1], strides[2]} : Strides{sh.S, sh.S, sh.S};
     const unsigned bx = unsigned((sh.S + 255) / 256 < 4096 ? (sh.S + 255) / 256 : 4096);
     const unsigned by = unsigned(sh.B < 65535 ? sh.B : 65535);
     const dim3 grid(bx, by), block(256);
     const bool aligned = (reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) | reinterpret_cast<uintptr_t>(out)) %
-                             (4 * sizeof(T)) == 0;
+                                 (4 * sizeof(T)) == 0 &&
+                         (rs.a | rs.b | rs.out) % 4 == 0;
     if (aligned && (sh.d == 4 || sh.d == 8 || sh.d == 16)) {
         const dim3 grid4(unsigned((sh.S / 4 + 255) / 256 < 4096 ? (sh.S / 4 + 255) / 256 : 4096), by);
-        if (sh.d == 4) hipLaunchKernelGGL((sig_combine_vec4_kernel<T, 4>), grid4, block, 0, st, sh, a, b, out);
-        if (sh.d == 8) hipLaunchKernelGGL((sig_combine_vec4_kernel<T, 8>), grid4, block, 0, st, sh, a, b, out);
-        if (sh.d == 16) hipLaunchKernelGGL((sig_combine_vec4_kernel<T, 16>), grid4, block, 0, st, sh, a, b, out);
+        if (sh.d == 4) hipLaunchKernelGGL((sig_combine_vec4_kernel<T, 4>), grid4, block, 0, st, sh, rs, a, b, out);
+        if (sh.d == 8) hipLaunchKernelGGL((sig_combine_vec4_kernel<T, 8>), grid4, block, 0, st, sh, rs, a, b, out);
+        if (sh.d == 16) hipLaunchKernelGGL((sig_combine_vec4_kernel<T, 16>), grid4, block, 0, st, sh, rs, a, b, out);
         return hipGetLastError();
     }
     switch (sh.d) {
-        case 2: hipLaunchKernelGGL((sig_combine_kernel<T, 2>), grid, block, 0, st, sh, a, b, out); break;
-        case 3: hipLaunchKernelGGL((sig_combine_kernel<T, 3>), grid, block, 0, st, sh, a, b, out); break;
-        case 4: hipLaunchKernelGGL((sig_combine_kernel<T, 4>), grid, block, 0, st, sh, a, b, out); break;
-        case 5: hipLaunchKernelGGL((sig_combine_kernel<T, 5>), grid, block, 0, st, sh, a, b, out); break;
-        case 6: hipLaunchKernelGGL((sig_combine_kernel<T, 6>), grid, block, 0, st, sh, a, b, out); break;
-        case 7: hipLaunchKernelGGL((sig_combine_kernel<T, 7>), grid, block, 0, st, sh, a, b, out); break;
-        case 8: hipLaunchKernelGGL((sig_combine_kernel<T, 8>), grid, block, 0, st, sh, a, b, out); break;
-        case 16: hipLaunchKernelGGL((sig_combine_kernel<T, 16>), grid, block, 0, st, sh, a, b, out); break;
-        default: hipLaunchKernelGGL((sig_combine_kernel<T, 0>), grid, block, 0, st, sh, a, b, out); break;
+        case 2: hipLaunchKernelGGL((sig_combine_kernel<T, 2>), grid, block, 0, st, sh, rs, a, b, out); break;
+        case 3: hipLaunchKernelGGL((sig_combine_kernel<T, 3>), grid, block, 0, st, sh, rs, a, b, out); break;
+        case 4: hipLaunchKernelGGL((sig_combine_kernel<T, 4>), grid, block, 0, st, sh, rs, a, b, out); break;
+        case 5: hipLaunchKernelGGL((sig_combine_kernel<T, 5>), grid, block, 0, st, sh, rs, a, b, out); break;
+        case 6: hipLaunchKernelGGL((sig_combine_kernel<T, 6>), grid, block, 0, st, sh, rs, a, b, out); break;
+        case 7: hipLaunchKernelGGL((sig_combine_kernel<T, 7>), grid, block, 0, st, sh, rs, a, b, out); break;
+        case 8: hipLaunchKernelGGL((sig_combine_kernel<T, 8>), grid, block, 0, st, sh, rs, a, b, out); break;
+        case 16: hipLaunchKernelGGL((sig_combine_kernel<T, 16>), grid, block, 0, st, sh, rs, a, b, out); break;
+        default: hipLaunchKernelGGL((sig_combine_kernel<T, 0>), grid, block, 0, st, sh, rs, a, b, out); break;
     }
     return hipGetLastError();
 }
@@ -112,14 +119,16 @@ hipError_t launch_combine(const Shape &sh, const T *a, const T *b, T *out, hipSt
 
 bool combine_supported(const Shape &sh) { return sh.S < (int64_t(1) << 31); }
 
-hipError_t launch_combine_f32(const Shape &sh, const float *a, const float *b, float *out, hipStream_t st)
+hipError_t launch_combine_f32(const Shape &sh, const float *a, const float *b, float *out, hipStream_t st,
+                              const int64_t *strides)
 {
-    return launch_combine<float>(sh, a, b, out, st);
+    return launch_combine<float>(sh, a, b, out, st, strides);
 }
 
-hipError_t launch_combine_f64(const Shape &sh, const double *a, const double *b, double *out, hipStream_t st)
+hipError_t launch_combine_f64(const Shape &sh, const double *a, const double *b, double *out, hipStream_t st,
+                              const int64_t *strides)
 {
-    return launch_combine<double>(sh, a, b, out, st);
+    return launch_combine<double>(sh, a, b, out, st, strides);
 }
 
 }  // namespace sig

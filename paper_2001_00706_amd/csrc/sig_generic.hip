@@ -45,6 +45,7 @@ sig_generic_kernel(Shape sh, const T *__restrict__ path, T *out, int state_in_ld
 
     for (int64_t b = blockIdx.x; b < sh.B; b += gridDim.x) {
         const T *x = path + b * sh.L * d;
+        const T *bpv = static_cast<const T *>(sh.basepoint_value);
         T *obase = out + b * (sh.stream ? sh.n_inc * S : S);
         T *cur = nullptr;
         const T *prev = nullptr;
@@ -68,7 +69,7 @@ sig_generic_kernel(Shape sh, const T *__restrict__ path, T *out, int state_in_ld
                     T hi, lo;
                     if (sh.basepoint) {
                         hi = x[si * d + c];
-                        lo = si == 0 ? T(0) : x[(si - 1) * d + c];
+                        lo = si > 0 ? x[(si - 1) * d + c] : bpv != nullptr ? bpv[b * d + c] : T(0);
                     } else {
                         hi = x[(si + 1) * d + c];
                         lo = x[si * d + c];

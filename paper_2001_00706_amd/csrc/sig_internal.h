@@ -17,6 +17,7 @@ struct Shape {
     int64_t n_inc;   // increments folded in: L - 1, or L with basepoint
     int d, N;
     int stream, basepoint;
+    const void *basepoint_value;     // DEVICE [B][d]: the point prepended when basepoint != 0; null = the origin
     int64_t pw[SIG_MAX_DEPTH + 1];   // pw[k] = d^k, k = 0..N
     int64_t off[SIG_MAX_DEPTH + 2];  // off[k] = offset of level k (1-based) in a signature; off[N+1] = S
 };
@@ -29,17 +30,28 @@ hipError_t launch_generic_f64(const Shape &sh, const double *path, double *out, 
 
 // Group product of two batches of signatures (any d, N with S < 2^31).
 bool combine_supported(const Shape &sh);
-hipError_t launch_combine_f32(const Shape &sh, const float *a, const float *b, float *out, hipStream_t st);
-hipError_t launch_combine_f64(const Shape &sh, const double *a, const double *b, double *out, hipStream_t st);
+// `strides`: distances in scalars between consecutive signatures of a, b, out; null = packed (S each).
+hipError_t launch_combine_f32(const Shape &sh, const float *a, const float *b, float *out, hipStream_t st,
+                              const int64_t *strides = nullptr);
+hipError_t launch_combine_f64(const Shape &sh, const double *a, const double *b, double *out, hipStream_t st,
+                              const int64_t *strides = nullptr);
+
+// Inverse of each of sh.B signatures (a signed permutation; `out` may be `in`), and multiplication on the
+// left in place: out[r] <- a[r / group] [x] out[r] for sh.B rows.  Both need S < 2^31.
+hipError_t launch_invert_f32(const Shape &sh, const float *in, float *out, hipStream_t st);
+hipError_t launch_invert_f64(const Shape &sh, const double *in, double *out, hipStream_t st);
+hipError_t launch_left_mul_f32(const Shape &sh, const float *a, int64_t group, float *out, hipStream_t st);
+hipError_t launch_left_mul_f64(const Shape &sh, const double *a, int64_t group, double *out, hipStream_t st);
 
 // Gradient with respect to the path (any N, d <= 64, S < 2^30).  `backward_workspace_bytes` is what the launch
 // needs in `workspace` (0 when everything fits LDS, -1 if unsupported).
 bool backward_supported(const Shape &sh);
 int64_t backward_workspace_bytes(const Shape &sh, sig_dtype dtype);
+// `gbase` (may be null): [B][d] gradient of the basepoint, written when sh.basepoint != 0.
 hipError_t launch_backward_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
-                               void *workspace, int64_t workspace_bytes, hipStream_t st);
+                               float *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st);
 hipError_t launch_backward_f64(const Shape &sh, const double *path, const double *sig, const double *gout, double *gpath,
-                               void *workspace, int64_t workspace_bytes, hipStream_t st);
+                               double *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st);
 
 // Small-state family: S <= 512 scalars, one wavefront per path, state in LDS, words decoded once.
 bool small_supported(const Shape &sh);

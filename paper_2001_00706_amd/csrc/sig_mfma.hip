@@ -122,7 +122,8 @@ __device__ __forceinline__ int park6(int i) { return i ^ ((i >> 8) << 2); }
 
 template <int N>
 __global__ void __launch_bounds__(64)
-sig_mfma_d4_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint)
+sig_mfma_d4_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint,
+                   const float *__restrict__ bpv)
 {
     static_assert(N >= 4 && N <= 6, "depths served by this kernel");
     __shared__ __align__(16) float lds[kLdsFloats<N>];
@@ -132,7 +133,9 @@ sig_mfma_d4_kernel(const float *__restrict__ path, float *__restrict__ out, int6
     const int64_t b = blockIdx.x;
     const f4 *x4 = reinterpret_cast<const f4 *>(path) + b * L;  // point l of this path
     const f4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
-    const f4 x_first = basepoint ? zero4 : x4[0];
+    // the point before the first increment: the path's first point, or the basepoint (the origin unless given)
+    const f4 x_base = bpv != nullptr ? reinterpret_cast<const f4 *>(bpv)[b] : zero4;
+    const f4 x_first = basepoint ? x_base : x4[0];
 
     State<N> S;
     S.A4[0] = zero4;
@@ -149,7 +152,7 @@ sig_mfma_d4_kernel(const float *__restrict__ path, float *__restrict__ out, int6
         if (s < n_inc) {
             const int64_t i_hi = basepoint ? s : s + 1;
             p_hi = x4[i_hi];
-            if (i_hi > 0) p_lo = x4[i_hi - 1];
+            p_lo = i_hi > 0 ? x4[i_hi - 1] : x_base;
         }
     };
     fetch_points(lane);
@@ -248,10 +251,11 @@ hipError_t launch_mfma_f32(const Shape &sh, const float *path, float *out, hipSt
 {
     if (mfma_kernel_name(sh) == nullptr) return hipErrorNotSupported;
     const dim3 grid(static_cast<unsigned>(sh.B)), block(64);
+    const float *bpv = static_cast<const float *>(sh.basepoint_value);
     switch (sh.N) {
-        case 4: hipLaunchKernelGGL(sig_mfma_d4_kernel<4>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint); break;
-        case 5: hipLaunchKernelGGL(sig_mfma_d4_kernel<5>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint); break;
-        case 6: hipLaunchKernelGGL(sig_mfma_d4_kernel<6>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint); break;
+        case 4: hipLaunchKernelGGL(sig_mfma_d4_kernel<4>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint, bpv); break;
+        case 5: hipLaunchKernelGGL(sig_mfma_d4_kernel<5>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint, bpv); break;
+        case 6: hipLaunchKernelGGL(sig_mfma_d4_kernel<6>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint, bpv); break;
         default: return hipErrorNotSupported;
     }
     return hipGetLastError();

@@ -85,7 +85,8 @@ __device__ __forceinline__ void half_trip(float &A1, float &A2, f16v (&A4)[8], c
 }
 
 __global__ void __launch_bounds__(512)
-sig_mfma_d16_n4_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint)
+sig_mfma_d16_n4_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint,
+                       const float *__restrict__ bpv)
 {
     __shared__ __align__(16) float lds[kTile16 * kRow16];
 
@@ -132,7 +133,9 @@ sig_mfma_d16_n4_kernel(const float *__restrict__ path, float *__restrict__ out, 
                 const int64_t s = t0 + i;
                 const int64_t i_hi = basepoint ? s : s + 1;
                 const f4 hi = x4[i_hi * 4 + c4];
-                const f4 lo = i_hi > 0 ? x4[(i_hi - 1) * 4 + c4] : (f4){0.0f, 0.0f, 0.0f, 0.0f};
+                const f4 lo = i_hi > 0         ? x4[(i_hi - 1) * 4 + c4]
+                              : bpv != nullptr ? reinterpret_cast<const f4 *>(bpv)[path_no * 4 + c4]
+                                               : (f4){0.0f, 0.0f, 0.0f, 0.0f};
                 const f4 z = hi - lo;
                 f4 *row = reinterpret_cast<f4 *>(lds + i * kRow16) + c4;
                 row[0] = z;
@@ -206,7 +209,7 @@ hipError_t launch_mfma_d16_f32(const Shape &sh, const float *path, float *out, h
 {
     if (mfma_d16_kernel_name(sh) == nullptr) return hipErrorNotSupported;
     hipLaunchKernelGGL(sig_mfma_d16_n4_kernel, dim3(static_cast<unsigned>(sh.B)), dim3(512), 0, st, path, out, sh.L,
-                       sh.n_inc, sh.basepoint);
+                       sh.n_inc, sh.basepoint, static_cast<const float *>(sh.basepoint_value));
     return hipGetLastError();
 }
 

@@ -179,7 +179,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(float *base, unsigne
 
 template <int N, bool STREAM>
 __global__ void __launch_bounds__(64)
-sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint)
+sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint,
+                         const float *__restrict__ bpv)
 {
     static_assert(N >= 4 && N <= 7, "depths served by this kernel");
     constexpr int kRow = 4 * (N - 1);  // floats per staged increment
@@ -212,6 +213,7 @@ sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out
             const int64_t i_hi = basepoint ? s : s + 1;
             p_hi = x4[i_hi];
             if (i_hi > 0) p_lo = x4[i_hi - 1];
+            else if (bpv != nullptr) p_lo = reinterpret_cast<const f4 *>(bpv)[b];
         }
     };
     fetch_points(lane);
@@ -254,9 +256,11 @@ hipError_t launch_shard(const Shape &sh, const float *path, float *out, hipStrea
 {
     const dim3 grid(static_cast<unsigned>(sh.B * 4)), block(64);
     if (sh.stream) {
-        hipLaunchKernelGGL((sig_mfma_d4_shard_kernel<N, true>), grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint);
+        hipLaunchKernelGGL((sig_mfma_d4_shard_kernel<N, true>), grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint,
+                           static_cast<const float *>(sh.basepoint_value));
     } else {
-        hipLaunchKernelGGL((sig_mfma_d4_shard_kernel<N, false>), grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint);
+        hipLaunchKernelGGL((sig_mfma_d4_shard_kernel<N, false>), grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint,
+                           static_cast<const float *>(sh.basepoint_value));
     }
     return hipGetLastError();
 }

@@ -122,7 +122,8 @@ typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 
 template <int N>
 __global__ void __launch_bounds__(64)
-sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint)
+sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint,
+                         const float *__restrict__ bpv)
 {
     static_assert(N >= 4 && N <= 6, "depths served by this kernel");
     constexpr int kRow = kD8;  // floats per staged increment
@@ -153,6 +154,9 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
             if (i_hi > 0) {
                 lo0 = x4[(i_hi - 1) * 2];
                 lo1 = x4[(i_hi - 1) * 2 + 1];
+            } else if (bpv != nullptr) {
+                lo0 = reinterpret_cast<const f4 *>(bpv)[b * 2];
+                lo1 = reinterpret_cast<const f4 *>(bpv)[b * 2 + 1];
             }
         }
     };
@@ -217,7 +221,7 @@ template <int N>
 hipError_t launch8(const Shape &sh, const float *path, float *out, hipStream_t st)
 {
     hipLaunchKernelGGL(sig_mfma_d8_shard_kernel<N>, dim3(static_cast<unsigned>(sh.B * 64)), dim3(64), 0, st, path, out,
-                       sh.L, sh.n_inc, sh.basepoint);
+                       sh.L, sh.n_inc, sh.basepoint, static_cast<const float *>(sh.basepoint_value));
     return hipGetLastError();
 }
 

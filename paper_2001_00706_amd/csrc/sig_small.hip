@@ -66,6 +66,7 @@ sig_small_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
 
     for (int64_t b = blockIdx.x; b < sh.B; b += gridDim.x) {
         const T *x = path + b * sh.L * d;
+        const T *bpv = static_cast<const T *>(sh.basepoint_value);
         T *o = out + b * (sh.stream ? sh.n_inc * int64_t(S) : int64_t(S));
         for (int i = lane; i <= S; i += 64) st[i] = T(0);
 
@@ -79,7 +80,7 @@ sig_small_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
                 T hi, lo;
                 if (sh.basepoint) {
                     hi = x[s * d + c];
-                    lo = s == 0 ? T(0) : x[(s - 1) * d + c];
+                    lo = s > 0 ? x[(s - 1) * d + c] : bpv != nullptr ? bpv[b * d + c] : T(0);
                 } else {
                     hi = x[(s + 1) * d + c];
                     lo = x[s * d + c];

@@ -125,8 +125,8 @@ def test_backward_validation(lib):
     f = lib.sig_backward
     p = 0x1000
     args = lambda **kw: [kw.get("path", p), kw.get("sig", p), kw.get("gout", p), kw.get("B", 2), kw.get("L", 4),
-                         kw.get("d", 2), kw.get("N", 2), 0, kw.get("basepoint", 0), kw.get("dtype", sig.SIG_F32),
-                         kw.get("gpath", p), 0, 0, 0]
+                         kw.get("d", 2), kw.get("N", 2), 0, kw.get("basepoint", 0), kw.get("bpv", 0),
+                         kw.get("dtype", sig.SIG_F32), kw.get("gpath", p), kw.get("gbp", 0), 0, 0, 0]
     assert f(*args(B=-1)) == sig.SIG_ERR_INVALID_ARG
     assert f(*args(d=0)) == sig.SIG_ERR_INVALID_ARG
     assert f(*args(N=33)) == sig.SIG_ERR_INVALID_ARG
@@ -138,9 +138,35 @@ def test_backward_validation(lib):
     assert f(*args(d=65, N=1)) == sig.SIG_ERR_UNSUPPORTED          # more channels than the smallest workgroup has threads
     assert f(*args(d=2, N=31)) == sig.SIG_ERR_UNSUPPORTED          # 2^32 scalars per signature
     assert f(*args(B=0, path=0, sig=0, gout=0, gpath=0)) == sig.SIG_OK
+    # a basepoint value or its gradient without the basepoint flag
+    assert f(*args(bpv=p)) == sig.SIG_ERR_INVALID_ARG
+    assert f(*args(gbp=p)) == sig.SIG_ERR_INVALID_ARG
     assert sig.sig_backward_workspace_bytes(2, 1, 2, 2, False, False) == -1
     assert sig.sig_backward_workspace_bytes(2, 4, 65, 1, False, False) == -1
     assert sig.sig_backward_workspace_bytes(0, 4, 2, 2, False, False) == 0
+
+
+def test_signature_invert_and_strided_combine_validation(lib):
+    p = 0x1000
+    f = lib.sig_signature
+    # path, B, L, d, N, stream, basepoint, basepoint_value, initial, inverse, dtype, out, hip_stream
+    assert f(p, 2, 4, 2, 2, 0, 0, 0, 0, 0, sig.SIG_F32, 0, 0) == sig.SIG_ERR_INVALID_ARG      # null out
+    assert f(p, 2, 4, 2, 2, 0, 0, p, 0, 0, sig.SIG_F32, p, 0) == sig.SIG_ERR_INVALID_ARG      # value without the flag
+    assert f(p, 2, 1, 2, 2, 0, 0, 0, 0, 0, sig.SIG_F32, p, 0) == sig.SIG_ERR_INVALID_ARG      # one point
+    assert f(p, 2, 4, 2, 2, 0, 0, 0, 0, 0, 9, p, 0) == sig.SIG_ERR_INVALID_ARG
+    assert f(p, 2, 4, 2, 31, 0, 0, 0, p, 0, sig.SIG_F32, p, 0) == sig.SIG_ERR_UNSUPPORTED     # S >= 2^31 with initial
+    assert f(0, 0, 4, 2, 2, 0, 0, 0, 0, 1, sig.SIG_F32, 0, 0) == sig.SIG_OK
+    g = lib.sig_invert
+    assert g(p, -1, 2, 2, sig.SIG_F32, p, 0) == sig.SIG_ERR_INVALID_ARG
+    assert g(0, 3, 2, 2, sig.SIG_F32, p, 0) == sig.SIG_ERR_INVALID_ARG
+    assert g(p, 3, 2, 32, sig.SIG_F32, p, 0) == sig.SIG_ERR_UNSUPPORTED
+    assert g(0, 0, 2, 2, sig.SIG_F64, 0, 0) == sig.SIG_OK
+    h = lib.sig_combine_strided
+    # a, a_stride, b, b_stride, B, d, N, dtype, out, out_stride, hip_stream
+    assert h(p, 6, p, 6, 2, 2, 2, sig.SIG_F32, p, 5, 0) == sig.SIG_ERR_INVALID_ARG            # out rows would overlap
+    assert h(p, -1, p, 6, 2, 2, 2, sig.SIG_F32, p, 6, 0) == sig.SIG_ERR_INVALID_ARG
+    assert h(p, 0, 0, 6, 2, 2, 2, sig.SIG_F32, p, 6, 0) == sig.SIG_ERR_INVALID_ARG
+    assert h(0, 0, 0, 0, 0, 2, 2, sig.SIG_F32, 0, 6, 0) == sig.SIG_OK
 
 
 def test_variant_names(lib):

@@ -1,0 +1,190 @@
+"""GPU parity of the options built on top of the scan (paper sections 4.2, 5.4, 5.5): a basepoint
+given by value, `initial`, `inverse`, inverses of stored signatures, strided products and `Path`.
+
+Every expected value comes from the fp64 oracle applied to a path that spells the option out:
+the basepoint prepended as a point, the earlier data concatenated in front, the path reversed.
+"""
+import numpy as np
+import pytest
+
+import paper_2001_00706_amd as sig
+from oracle import sig_oracle as orc
+from paper_2001_00706_amd.inputs import brownian_paths, uniform_paths
+
+pytestmark = pytest.mark.gpu
+
+TOL = {np.float32: 1e-4, np.float64: 1e-10}
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def host(t):
+    import torch
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def assert_levels_close(got, want, d, N, dt):
+    got = np.asarray(got, dtype=np.float64)
+    for sl in orc.level_slices(d, N):
+        den = np.linalg.norm(want[..., sl])
+        err = np.linalg.norm(got[..., sl] - want[..., sl]) / (den if den > 0 else 1.0)
+        assert err <= TOL[dt], err
+
+
+def reversed_prefix_signatures(x, N):
+    """Inverted signature of every prefix = signature of the prefix traversed backwards (section 5.4)."""
+    B, L, d = x.shape
+    out = np.empty((B, L - 1, orc.channels(d, N)))
+    for j in range(2, L + 1):
+        out[:, j - 2] = orc.signature(x[:, :j][:, ::-1], N)
+    return out
+
+
+# shapes chosen to reach every kernel family: d=4 N=6 (one wavefront per path), d=4 N=5 stream and N=7 (four
+# per path), d=8 N=5, d=16 N=4, a small state, and the fallback
+FAMILY_SHAPES = [(5, 9, 4, 6), (3, 20, 4, 7), (2, 7, 8, 5), (2, 5, 16, 4), (4, 11, 2, 5), (3, 8, 5, 4), (2, 6, 3, 6)]
+
+
+@pytest.mark.parametrize("stream", [False, True])
+@pytest.mark.parametrize("B,L,d,N", FAMILY_SHAPES)
+def test_basepoint_given_by_value(B, L, d, N, stream):
+    x = brownian_paths(B, L, d, seed=L + d) + 0.25
+    bp = uniform_paths(B, 1, d, seed=N)[:, 0]
+    got = host(sig.sig_signature(dev(x), N, stream=stream, basepoint=dev(bp)))
+    want = orc.signature(np.concatenate([bp[:, None], x], axis=1), N, stream=stream)
+    assert_levels_close(got, want, d, N, np.float32)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("stream", [False, True])
+@pytest.mark.parametrize("B,L,d,N", [(3, 9, 4, 5), (2, 6, 3, 4), (2, 5, 8, 4), (4, 7, 2, 6)])
+def test_initial_continues_an_earlier_signature(B, L, d, N, stream, dtype):
+    # earlier data y (ending where x begins) then x: initial = Sig(y); the result is the signature of everything
+    whole = brownian_paths(B, L + 5, d, seed=3 * L + d).astype(dtype)
+    y, x = whole[:, :6], whole[:, 5:]
+    initial = orc.signature(y, N).astype(dtype)
+    got = host(sig.sig_signature(dev(x), N, stream=stream, initial=dev(initial)))
+    if stream:
+        want = orc.signature(whole, N, stream=True)[:, 5:]
+    else:
+        want = orc.signature(whole, N)
+    assert_levels_close(got, want, d, N, dtype)
+    # the same through a basepoint: x without its first point, that point given as the basepoint
+    got = host(sig.sig_signature(dev(x[:, 1:]), N, stream=stream, basepoint=dev(x[:, 0]), initial=dev(initial)))
+    assert_levels_close(got, want, d, N, dtype)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("B,L,d,N", [(3, 9, 4, 5), (2, 6, 3, 4), (2, 5, 7, 3), (4, 7, 2, 7), (2, 4, 1, 5), (3, 5, 6, 1)])
+def test_inverse_is_the_signature_of_the_reversed_path(B, L, d, N, dtype):
+    x = uniform_paths(B, L, d, seed=L * d + N).astype(dtype)
+    got = host(sig.sig_signature(dev(x), N, inverse=True))
+    assert_levels_close(got, orc.signature(x[:, ::-1], N), d, N, dtype)
+    got = host(sig.sig_signature(dev(x), N, stream=True, inverse=True))
+    assert_levels_close(got, reversed_prefix_signatures(x.astype(np.float64), N), d, N, dtype)
+    # with a basepoint (the origin) the reversed path ends there
+    got = host(sig.sig_signature(dev(x), N, basepoint=True, inverse=True))
+    x0 = np.concatenate([np.zeros((B, 1, d), dtype=dtype), x], axis=1)
+    assert_levels_close(got, orc.signature(x0[:, ::-1], N), d, N, dtype)
+
+
+def test_invert_in_place_out_of_place_and_twice():
+    import torch
+    x = brownian_paths(6, 12, 3, seed=4)
+    s = sig.sig_forward(dev(x), 5)
+    inv = sig.sig_invert(s, 3, 5)
+    assert_levels_close(host(inv), orc.signature(x[:, ::-1], 5), 3, 5, np.float32)
+    again = sig.sig_invert(inv, 3, 5)
+    assert torch.equal(again, s)                      # a signed permutation: exact
+    t = s.clone()
+    sig.sig_invert(t, 3, 5, out=t)
+    assert torch.equal(t, inv)
+    # inverse [x] signature = identity (all zeros, the constant term being implicit)
+    prod = host(sig.sig_combine(inv, s, 3, 5))
+    assert np.abs(prod).max() <= 1e-5
+
+
+def test_strided_combine_reads_rows_of_stream_outputs():
+    x = brownian_paths(4, 10, 4, seed=2).astype(np.float64)
+    N, S = 4, orc.channels(4, 4)
+    st = sig.sig_forward(dev(x), N, stream=True)           # [4, 9, S]
+    inv = sig.sig_invert(st, 4, N)
+    import torch
+    out = torch.full((4, S + 3), float("nan"), dtype=torch.float64, device="cuda:0")
+    # Sig(x_3..x_8) = Sig(x_0..x_3)^{-1} [x] Sig(x_0..x_8): rows 2 and 7 of every path
+    sig.sig_combine_strided(inv.reshape(-1)[2 * S:], 9 * S, st.reshape(-1)[7 * S:], 9 * S, 4, 4, N, out, S + 3)
+    got = host(out)
+    assert_levels_close(got[:, :S], orc.signature(x[:, 3:9], N), 4, N, np.float64)
+    assert np.all(np.isnan(got[:, S:]))                      # the gap between output rows is left alone
+    # stride 0 repeats one left factor
+    one = dev(orc.signature(x[:1, :4], N))
+    out2 = torch.empty((4, S), dtype=torch.float64, device="cuda:0")
+    sig.sig_combine_strided(one, 0, st.reshape(-1)[7 * S:], 9 * S, 4, 4, N, out2, S)
+    want = np.stack([orc.group_mul(orc.signature(x[:1, :4], N)[0], orc.signature(x[b:b + 1, :9], N)[0], 4, N)
+                     for b in range(4)])
+    assert_levels_close(host(out2), want, 4, N, np.float64)
+
+
+def assert_query_close(got, x, i, j, N, dt):
+    """A query is a product of two long-prefix signatures whose terms largely cancel (section 4.2 ends with a
+    warning about exactly this), so its rounding error scales with the factors, not with the result: per level,
+    |error| <= c * sum_m |Sig(x_0..x_i)^{-1}|_m |Sig(x_0..x_j)|_{k-m}, c a few roundings of the working precision."""
+    d = x.shape[2]
+    want = orc.signature(x[:, i:j + 1], N)
+    if i == 0:
+        return assert_levels_close(got, want, d, N, dt)
+    sl = orc.level_slices(d, N)
+    left = orc.signature(x[:, :i + 1][:, ::-1], N)
+    right = orc.signature(x[:, :j + 1], N)
+    norm = lambda a, k: 1.0 if k == 0 else np.linalg.norm(a[:, sl[k - 1]])
+    c = 4e-6 if dt == np.float32 else 1e-14
+    for k in range(1, N + 1):
+        scale = sum(norm(left, m) * norm(right, k - m) for m in range(k + 1))
+        err = np.linalg.norm(np.asarray(got, dtype=np.float64)[:, sl[k - 1]] - want[:, sl[k - 1]])
+        assert err <= c * scale, (k, err, scale)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_path_queries_and_update(dtype):
+    B, L, d, N = 3, 14, 3, 4
+    x = brownian_paths(B, L + 6, d, seed=11).astype(dtype)
+    p = sig.Path(dev(x[:, :L]), N)
+    assert p.length == L
+    for i, j in [(0, L - 1), (0, 1), (3, 4), (2, 9), (L - 2, L - 1), (5, L - 1)]:
+        assert_query_close(host(p.signature(i, j)), x, i, j, N, dtype)
+    p.update(dev(x[:, L:L + 4]))
+    p.update(dev(x[:, L + 4:]))
+    assert p.length == L + 6
+    for i, j in [(0, L + 5), (4, L + 2), (L - 1, L), (L + 1, L + 5)]:
+        assert_query_close(host(p.signature(i, j)), x, i, j, N, dtype)
+    with pytest.raises(ValueError):
+        p.signature(5, 5)
+
+
+@pytest.mark.parametrize("stream", [False, True])
+def test_backward_with_a_basepoint_value_and_its_gradient(stream):
+    import torch
+    B, L, d, N = 3, 7, 3, 4
+    x = brownian_paths(B, L, d, seed=5).astype(np.float64) + 0.1
+    bp = uniform_paths(B, 1, d, seed=6)[:, 0].astype(np.float64)
+    S = orc.channels(d, N)
+    g = np.random.default_rng(1).standard_normal((B, L, S) if stream else (B, S))
+    xt, bt = dev(x), dev(bp)
+    s = sig.sig_signature(xt, N, stream=stream, basepoint=bt)
+    gb = torch.empty_like(bt)
+    gp = sig.sig_backward(xt, s, dev(g), N, stream=stream, basepoint=bt, grad_basepoint=gb)
+    want = orc.signature_backward(np.concatenate([bp[:, None], x], axis=1), g, N, stream=stream)
+    np.testing.assert_allclose(host(gp), want[:, 1:], rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(host(gb), want[:, 0], rtol=1e-9, atol=1e-11)
+
+
+def test_autograd_through_inverse_and_basepoint_value():
+    import torch
+    x = dev(uniform_paths(2, 5, 2, seed=9).astype(np.float64)).requires_grad_(True)
+    bp = dev(uniform_paths(2, 1, 2, seed=10)[:, 0].astype(np.float64)).requires_grad_(True)
+    assert torch.autograd.gradcheck(lambda p, q: sig.signature(p, 3, True, q, True), (x, bp), eps=1e-6, atol=1e-7, rtol=1e-6)
+    assert torch.autograd.gradcheck(lambda p: sig.signature(p, 4, False, False, True), (x,), eps=1e-6, atol=1e-7, rtol=1e-6)
