@@ -27,7 +27,8 @@
  * Pinned by tests/test_oracle_pins.py against closed forms, invariants, brute force from
  * the integral definition and a hand-computed example; the gradient (second half of the file)
  * by tests/test_oracle_backward_pins.py against finite differences of the pinned forward and
- * closed forms.  Nothing here is "parity unpinned".
+ * closed forms; the logarithm (third part) by tests/test_oracle_log_pins.py.  Nothing here is
+ * "parity unpinned".
  *
  * SIG_ORACLE_MUTANT (never defined in a normal build) plants one deliberate mistake, numbered
  * below, so that tests/test_oracle_mutants.py can check that the pins notice each of them.
@@ -330,6 +331,54 @@ int sig_oracle_backward_f64(const double *path, const double *grad_out, int64_t 
         failed |= one_path_backward(path + b * L * d, grad_out + b * out_stride, L, d, N, stream, basepoint,
                                     grad_path + b * L * d, S);
     return failed ? 2 : 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Logarithm in the truncated tensor algebra (section 2.3, eq. "logarithm"): the inverse of the
+ * tensor exponential, given by the power series  log(1 + x) = sum_{m=1..N} (-1)^{m+1} x^{[x] m} / m,
+ * where x is the element without its constant term 1 (powers beyond N vanish in the truncation).
+ * Written out literally: every power by one more product with x, every term added in turn.
+ * ------------------------------------------------------------------------------------------ */
+
+/* Product of two elements WITHOUT constant terms: C_k = sum_{j=1..k-1} A_j (x) B_{k-j}. */
+static void mul_no_unit(const double *A, const double *B, int d, int N, double *C)
+{
+    const int64_t S = sig_oracle_channels(d, N);
+    for (int64_t i = 0; i < S; ++i) C[i] = 0.0;
+    for (int k = 2; k <= N; ++k)
+        for (int j = 1; j <= k - 1; ++j) {
+            const int m = k - j;
+            const double *Aj = A + level_offset(d, j);
+            const double *Bm = B + level_offset(d, m);
+            double *Ck = C + level_offset(d, k);
+            const int64_t n_j = ipow64(d, j), n_m = ipow64(d, m);
+            for (int64_t u = 0; u < n_j; ++u)
+                for (int64_t v = 0; v < n_m; ++v) Ck[u * n_m + v] += Aj[u] * Bm[v];
+        }
+}
+
+/* out = log(1 + x) for one element x (S scalars, constant term implicit).  Returns 0, or 2 if memory ran out. */
+int sig_oracle_log(const double *x, int d, int N, double *out)
+{
+    const int64_t S = sig_oracle_channels(d, N);
+    if (S < 0) return 1;
+    double *power = (double *)malloc(sizeof(double) * (size_t)S);
+    double *next = (double *)malloc(sizeof(double) * (size_t)S);
+    if (!power || !next) {
+        free(power); free(next);
+        return 2;
+    }
+    memcpy(power, x, sizeof(double) * (size_t)S);   /* x^1 */
+    for (int64_t i = 0; i < S; ++i) out[i] = x[i];
+    for (int m = 2; m <= N; ++m) {
+        mul_no_unit(power, x, d, N, next);           /* x^m = x^{m-1} [x] x */
+        double *t = power; power = next; next = t;
+        const double sign = (SIG_ORACLE_MUTANT == 13 || m % 2 == 0) ? -1.0 : 1.0; /* mutant 13: every term after the first subtracted */
+        const double div = (double)(SIG_ORACLE_MUTANT == 14 && m == 3 ? 2 : m);   /* mutant 14: the cube divided by 2 */
+        for (int64_t i = 0; i < S; ++i) out[i] += sign * power[i] / div;
+    }
+    free(power); free(next);
+    return 0;
 }
 
 /* Threads an OpenMP region would use right now (1 when built without OpenMP). */

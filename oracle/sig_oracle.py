@@ -51,6 +51,8 @@ def _declare(lib):
     lib.sig_oracle_forward_f64.argtypes = [dp, i64, i64, i32, i32, i32, i32, dp, i32]
     lib.sig_oracle_backward_f64.restype = i32
     lib.sig_oracle_backward_f64.argtypes = [dp, dp, i64, i64, i32, i32, i32, i32, dp, i32]
+    lib.sig_oracle_log.restype = i32
+    lib.sig_oracle_log.argtypes = [dp, i32, i32, dp]
     lib.sig_oracle_max_threads.restype = i32
     lib.sig_oracle_max_threads.argtypes = []
     return lib
@@ -183,3 +185,54 @@ def signature_backward(path, grad_out, N: int, stream: bool = False, basepoint: 
     if rc != 0:
         raise RuntimeError(f"sig_oracle_backward_f64 failed with code {rc}")
     return gx
+
+
+def tensor_log(sig, d: int, N: int) -> np.ndarray:
+    """log of signatures `[..., S]` in the truncated tensor algebra (section 2.3): same shape, all words kept."""
+    a = np.ascontiguousarray(sig, dtype=np.float64)
+    S = channels(d, N)
+    if a.shape[-1] != S:
+        raise ValueError(f"last dimension must be {S}")
+    flat = a.reshape(-1, S)
+    out = np.empty_like(flat)
+    lib = _load()
+    for r in range(flat.shape[0]):
+        rc = lib.sig_oracle_log(_dptr(flat[r]), d, N, _dptr(out[r]))
+        if rc != 0:
+            raise RuntimeError(f"sig_oracle_log failed with code {rc}")
+    return out.reshape(a.shape)
+
+
+def lyndon_words(d: int, N: int):
+    """All Lyndon words over d letters of length 1..N as tuples of 0-based letters, by length and then
+    lexicographically: a word is Lyndon when it is strictly earlier than each of its proper rotations
+    (appendix A.2.1).  Straight from that definition, every word tried."""
+    import itertools
+    out = []
+    for k in range(1, N + 1):
+        for w in itertools.product(range(d), repeat=k):
+            if all(w < w[i:] + w[:i] for i in range(1, k)):
+                out.append(w)
+    return out
+
+
+def lyndon_indices(d: int, N: int) -> np.ndarray:
+    """Offsets, inside a flat depth-N element, of the coefficients of the Lyndon words (in the order of
+    `lyndon_words`)."""
+    offs = [sl.start for sl in level_slices(d, N)]
+    idx = []
+    for w in lyndon_words(d, N):
+        flat = 0
+        for letter in w:
+            flat = flat * d + letter
+        idx.append(offs[len(w) - 1] + flat)
+    return np.asarray(idx, dtype=np.int64)
+
+
+def logsignature(path, N: int, stream: bool = False, basepoint: bool = False) -> np.ndarray:
+    """psi(log(Sig(path))): the coefficients of the Lyndon words in the logarithm of the signature, the basis of
+    appendix A.2.4.  Shape `[B, w]` or `[B, n_inc, w]`, w = number of Lyndon words of length <= N."""
+    x = np.ascontiguousarray(path, dtype=np.float64)
+    d = x.shape[2]
+    full = tensor_log(signature(x, N, stream, basepoint), d, N)
+    return full[..., lyndon_indices(d, N)]

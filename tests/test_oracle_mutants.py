@@ -6,6 +6,7 @@ import pytest
 
 from oracle import sig_oracle as orc
 from tests import test_oracle_backward_pins as backward_pins
+from tests import test_oracle_log_pins as log_pins
 from tests import test_oracle_pins as pins
 
 MUTANTS = {
@@ -21,13 +22,16 @@ MUTANTS = {
     10: "gradient: the 1/k of the exponential recurrence forgotten",
     11: "gradient: stream-mode output gradients shifted by one entry",
     12: "gradient: wrong sign at the lower end point of an increment",
+    13: "logarithm: every term after the first subtracted",
+    14: "logarithm: the cube divided by 2 instead of 3",
 }
 
 
 def _pin_calls():
     """(name, callable) for every pin, with its parametrisations expanded."""
     calls = []
-    members = inspect.getmembers(pins, inspect.isfunction) + inspect.getmembers(backward_pins, inspect.isfunction)
+    members = (inspect.getmembers(pins, inspect.isfunction) + inspect.getmembers(backward_pins, inspect.isfunction) +
+               [m for m in inspect.getmembers(log_pins, inspect.isfunction) if m[1].__module__ == log_pins.__name__])
     for name, fn in members:
         if not name.startswith("test_"):
             continue
