@@ -148,6 +148,31 @@ sig_status sig_signature(const void *path, int64_t B, int64_t L, int d, int N, i
                          const void *basepoint_value, const void *initial, int inverse, sig_dtype dtype,
                          void *out, hipStream_t hip_stream);
 
+/* Logarithm in the truncated tensor algebra of `rows` signatures (section 2.3, eq. "logarithm"): with x the
+ * signature without its constant term, log(1 + x) = sum_{m=1..N} (-1)^{m+1} x^{[x] m} / m.  The result has the
+ * same layout as a signature (every word kept).
+ *   sig, out   DEVICE pointers, [rows][S]; must not overlap (and must differ).
+ * Errors as for sig_combine. */
+sig_status sig_log(const void *sig, int64_t rows, int d, int N, sig_dtype dtype, void *out, hipStream_t hip_stream);
+
+/* Number of Lyndon words of length 1..N over d letters = the dimension w(d, N) of the logsignature (Witt's formula,
+ * section 2.3).  -1 on bad arguments or if S >= 2^31. */
+int64_t sig_logsignature_channels(int d, int N);
+
+/* Offsets, inside a flat depth-N element, of the coefficients of the Lyndon words (appendix A.2.1: the words that
+ * come strictly before all of their rotations), ordered by length and lexicographically inside a length.
+ *   indices    HOST pointer to `capacity` >= sig_logsignature_channels(d, N) entries, filled on return.
+ * A host function: nothing is enqueued.  SIG_ERR_INVALID_ARG if the capacity is too small. */
+sig_status sig_lyndon_indices(int d, int N, int64_t *indices, int64_t capacity);
+
+/* Logsignature in the basis of appendix A.2.4, psi(log(Sig)): from the logarithms computed by sig_log, keep the
+ * coefficients of the Lyndon words.  out[r][i] = log_sig[r][indices[i]].
+ *   log_sig    DEVICE pointer [rows][S];  indices  DEVICE pointer to n offsets in [0, S) (sig_lyndon_indices, copied
+ *              to the device by the caller);  out  DEVICE pointer [rows][n].
+ * Errors as for sig_combine. */
+sig_status sig_lyndon_gather(const void *log_sig, int64_t rows, int d, int N, const int64_t *indices, int64_t n,
+                             sig_dtype dtype, void *out, hipStream_t hip_stream);
+
 /* Gradient of a scalar loss with respect to the path, given its gradient with respect to the output of
  * sig_forward (or sig_signature without `initial` and `inverse`) called with the same arguments (section 5.3;
  * appendix C).  Nothing from the forward pass is kept but its output: each earlier signature is recovered from the

@@ -24,6 +24,11 @@ from .binding import (  # noqa: F401
     sig_combine,
     sig_combine_strided,
     sig_invert,
+    sig_log,
+    sig_logsignature,
+    sig_logsignature_channels,
+    sig_lyndon_gather,
+    sig_lyndon_indices,
     sig_signature,
     sig_forward,
     sig_forward_raw,

@@ -30,6 +30,10 @@ EXPORTED_SYMBOLS = (
     "sig_backward",
     "sig_combine_strided",
     "sig_invert",
+    "sig_log",
+    "sig_logsignature_channels",
+    "sig_lyndon_indices",
+    "sig_lyndon_gather",
     "sig_signature",
     "sig_backward_workspace_bytes",
     "sig_variant_name",
@@ -73,6 +77,14 @@ def load_library() -> ctypes.CDLL:
         lib.sig_backward.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, i32, vp, i32, vp, vp, vp, i64, vp]
         lib.sig_combine_strided.restype = i32
         lib.sig_combine_strided.argtypes = [vp, i64, vp, i64, i64, i32, i32, i32, vp, i64, vp]
+        lib.sig_log.restype = i32
+        lib.sig_log.argtypes = [vp, i64, i32, i32, i32, vp, vp]
+        lib.sig_logsignature_channels.restype = i64
+        lib.sig_logsignature_channels.argtypes = [i32, i32]
+        lib.sig_lyndon_indices.restype = i32
+        lib.sig_lyndon_indices.argtypes = [i32, i32, ctypes.POINTER(i64), i64]
+        lib.sig_lyndon_gather.restype = i32
+        lib.sig_lyndon_gather.argtypes = [vp, i64, i32, i32, vp, i64, i32, vp, vp]
         lib.sig_invert.restype = i32
         lib.sig_invert.argtypes = [vp, i64, i32, i32, i32, vp, vp]
         lib.sig_signature.restype = i32
@@ -358,3 +370,93 @@ def sig_combine_strided(a, a_stride: int, b, b_stride: int, B: int, d: int, N: i
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out
+
+
+def sig_logsignature_channels(d: int, N: int) -> int:
+    return int(load_library().sig_logsignature_channels(d, N))
+
+
+def sig_lyndon_indices(d: int, N: int):
+    """Offsets of the Lyndon-word coefficients inside a flat depth-N element, as a Python list (host side)."""
+    n = sig_logsignature_channels(d, N)
+    if n < 0:
+        raise SigError(SIG_ERR_INVALID_ARG, "bad d or N")
+    buf = (ctypes.c_int64 * max(n, 1))()
+    status = int(load_library().sig_lyndon_indices(d, N, buf, n))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return list(buf[:n])
+
+
+def sig_log(sig, d: int, N: int, out=None):
+    """Logarithm in the tensor algebra of signatures `[..., S]`; same shape, every word kept."""
+    import torch
+
+    _check_gpu("sig_log", sig)
+    dtype = _dtype_of(sig)
+    S = sig_signature_channels(d, N)
+    if S < 0 or sig.shape[-1] != S or not sig.is_contiguous():
+        raise ValueError(f"sig must be contiguous with {S} channels last")
+    if out is None:
+        out = torch.empty_like(sig)
+    elif out.dtype != sig.dtype or out.device != sig.device or out.shape != sig.shape or not out.is_contiguous() \
+            or out.data_ptr() == sig.data_ptr():
+        raise ValueError("out must match sig and be a different tensor")
+    rows = sig.numel() // S
+    with torch.cuda.device(sig.device):
+        status = int(load_library().sig_log(sig.data_ptr(), rows, d, N, dtype, out.data_ptr(),
+                                            torch.cuda.current_stream().cuda_stream))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return out
+
+
+_lyndon_tables = {}
+
+
+def _lyndon_table(d: int, N: int, device):
+    """The Lyndon index table on `device`, built once per (d, N, device)."""
+    import torch
+    key = (d, N, str(device))
+    with _lock:
+        t = _lyndon_tables.get(key)
+    if t is None:
+        t = torch.tensor(sig_lyndon_indices(d, N), dtype=torch.int64, device=device)
+        with _lock:
+            _lyndon_tables[key] = t
+    return t
+
+
+def sig_lyndon_gather(log_sig, d: int, N: int, out=None):
+    """Coefficients of the Lyndon words of logarithms `[..., S]` -> `[..., w(d, N)]`."""
+    import torch
+
+    _check_gpu("sig_lyndon_gather", log_sig)
+    dtype = _dtype_of(log_sig)
+    S = sig_signature_channels(d, N)
+    if S < 0 or log_sig.shape[-1] != S or not log_sig.is_contiguous():
+        raise ValueError(f"log_sig must be contiguous with {S} channels last")
+    table = _lyndon_table(d, N, log_sig.device)
+    n = table.numel()
+    shape = tuple(log_sig.shape[:-1]) + (n,)
+    if out is None:
+        out = torch.empty(shape, dtype=log_sig.dtype, device=log_sig.device)
+    elif out.dtype != log_sig.dtype or out.device != log_sig.device or tuple(out.shape) != shape or not out.is_contiguous():
+        raise ValueError(f"out must be a contiguous tensor of shape {shape}")
+    rows = log_sig.numel() // S
+    with torch.cuda.device(log_sig.device):
+        status = int(load_library().sig_lyndon_gather(log_sig.data_ptr(), rows, d, N, table.data_ptr(), n, dtype,
+                                                      out.data_ptr(), torch.cuda.current_stream().cuda_stream))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return out
+
+
+def sig_logsignature(path, N: int, stream: bool = False, basepoint=False, inverse: bool = False, mode: str = "words"):
+    """Logsignature of a batch of paths (sections 2.3, 4.3): `sig_signature`, then `sig_log`, then, for
+    mode "words", the coefficients of the Lyndon words (mode "expand" keeps every word)."""
+    if mode not in ("words", "expand"):
+        raise ValueError('mode must be "words" or "expand"')
+    d = path.shape[2]
+    full = sig_log(sig_signature(path, N, stream=stream, basepoint=basepoint, inverse=inverse), d, N)
+    return full if mode == "expand" else sig_lyndon_gather(full, d, N)

@@ -271,6 +271,55 @@ sig_status sig_combine_strided(const void *a, int64_t a_stride, const void *b, i
     return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
 }
 
+int64_t sig_logsignature_channels(int d, int N)
+{
+    sig::Shape sh;
+    if (make_rows_shape(0, d, N, sh) != SIG_OK || sh.S >= (int64_t(1) << 31)) return -1;
+    return sig::lyndon_indices_host(sh, nullptr, 0);
+}
+
+sig_status sig_lyndon_indices(int d, int N, int64_t *indices, int64_t capacity)
+{
+    sig::Shape sh;
+    const sig_status st = make_rows_shape(0, d, N, sh);
+    if (st != SIG_OK) return st;
+    if (sh.S >= (int64_t(1) << 31)) return SIG_ERR_UNSUPPORTED;
+    if (indices == nullptr || capacity < 0) return SIG_ERR_INVALID_ARG;
+    return sig::lyndon_indices_host(sh, indices, capacity) < 0 ? SIG_ERR_INVALID_ARG : SIG_OK;
+}
+
+sig_status sig_log(const void *sig, int64_t rows, int d, int N, sig_dtype dtype, void *out, hipStream_t hip_stream)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
+    sig::Shape sh;
+    const sig_status st = make_rows_shape(rows, d, N, sh);
+    if (st != SIG_OK) return st;
+    if (rows == 0) return SIG_OK;
+    if (sig == nullptr || out == nullptr || sig == out) return SIG_ERR_INVALID_ARG;
+    if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
+    const hipError_t err =
+        dtype == SIG_F32 ? sig::launch_log_f32(sh, static_cast<const float *>(sig), static_cast<float *>(out), hip_stream)
+                         : sig::launch_log_f64(sh, static_cast<const double *>(sig), static_cast<double *>(out), hip_stream);
+    return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
+sig_status sig_lyndon_gather(const void *log_sig, int64_t rows, int d, int N, const int64_t *indices, int64_t n,
+                             sig_dtype dtype, void *out, hipStream_t hip_stream)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
+    sig::Shape sh;
+    const sig_status st = make_rows_shape(rows, d, N, sh);
+    if (st != SIG_OK) return st;
+    if (n < 0 || n > sh.S) return SIG_ERR_INVALID_ARG;
+    if (rows == 0 || n == 0) return SIG_OK;
+    if (log_sig == nullptr || indices == nullptr || out == nullptr) return SIG_ERR_INVALID_ARG;
+    const hipError_t err =
+        dtype == SIG_F32
+            ? sig::launch_gather_f32(sh, static_cast<const float *>(log_sig), indices, n, static_cast<float *>(out), hip_stream)
+            : sig::launch_gather_f64(sh, static_cast<const double *>(log_sig), indices, n, static_cast<double *>(out), hip_stream);
+    return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
 sig_status sig_signature(const void *path, int64_t B, int64_t L, int d, int N, int stream, int basepoint,
                          const void *basepoint_value, const void *initial, int inverse, sig_dtype dtype,
                          void *out, hipStream_t hip_stream)

@@ -53,6 +53,15 @@ hipError_t launch_backward_f32(const Shape &sh, const float *path, const float *
 hipError_t launch_backward_f64(const Shape &sh, const double *path, const double *sig, const double *gout, double *gpath,
                                double *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st);
 
+// Logarithm of sh.B signatures in the tensor algebra (out != in), the gather of n coefficients per signature by a
+// device index table, and that table for the Lyndon words, built on the host (returns the count; `indices` may be
+// null to count only; -1 if `cap` is too small).
+hipError_t launch_log_f32(const Shape &sh, const float *in, float *out, hipStream_t st);
+hipError_t launch_log_f64(const Shape &sh, const double *in, double *out, hipStream_t st);
+hipError_t launch_gather_f32(const Shape &sh, const float *in, const int64_t *index, int64_t n, float *out, hipStream_t st);
+hipError_t launch_gather_f64(const Shape &sh, const double *in, const int64_t *index, int64_t n, double *out, hipStream_t st);
+int64_t lyndon_indices_host(const Shape &sh, int64_t *indices, int64_t cap);
+
 // Small-state family: S <= 512 scalars, one wavefront per path, state in LDS, words decoded once.
 bool small_supported(const Shape &sh);
 hipError_t launch_small_f32(const Shape &sh, const float *path, float *out, hipStream_t st);

@@ -169,6 +169,26 @@ def test_signature_invert_and_strided_combine_validation(lib):
     assert h(0, 0, 0, 0, 0, 2, 2, sig.SIG_F32, 0, 6, 0) == sig.SIG_OK
 
 
+def test_lyndon_table_is_built_on_the_host(lib):
+    # appendix A.2.1; d = 2, N = 4: a, b, ab, aab, abb, aaab, aabb, abbb at offsets 0,1 | 2+1 | 6+1, 6+3 | 14+1, 14+3, 14+7
+    assert sig.sig_lyndon_indices(2, 4) == [0, 1, 3, 7, 9, 15, 17, 21]
+    assert sig.sig_logsignature_channels(2, 4) == 8
+    assert sig.sig_logsignature_channels(4, 6) == 964        # Witt's formula (section 2.3): 4 + 6 + 20 + 60 + 204 + 670
+    assert sig.sig_logsignature_channels(3, 1) == 3
+    assert sig.sig_logsignature_channels(0, 3) == -1
+    assert sig.sig_logsignature_channels(2, 32) == -1
+    import ctypes
+    buf = (ctypes.c_int64 * 4)()
+    assert lib.sig_lyndon_indices(2, 4, buf, 4) == sig.SIG_ERR_INVALID_ARG      # room for 4 of 8
+    assert lib.sig_lyndon_indices(2, 4, None, 8) == sig.SIG_ERR_INVALID_ARG
+    p = 0x1000
+    assert lib.sig_log(p, 2, 2, 2, sig.SIG_F32, p, 0) == sig.SIG_ERR_INVALID_ARG   # in place
+    assert lib.sig_log(p, -2, 2, 2, sig.SIG_F32, p + 64, 0) == sig.SIG_ERR_INVALID_ARG
+    assert lib.sig_lyndon_gather(p, 2, 2, 2, p, 7, sig.SIG_F32, p, 0) == sig.SIG_ERR_INVALID_ARG   # more entries than S
+    assert lib.sig_lyndon_gather(p, 2, 2, 2, 0, 3, sig.SIG_F32, p, 0) == sig.SIG_ERR_INVALID_ARG
+    assert lib.sig_lyndon_gather(0, 0, 2, 2, 0, 3, sig.SIG_F32, 0, 0) == sig.SIG_OK
+
+
 def test_variant_names(lib):
     assert sig.sig_variant_name(32, 16, 2, 4, False, False, variant=sig.SIG_VARIANT_GENERIC) == "generic"
     assert sig.sig_variant_name(32, 1, 2, 4, False, False) == "invalid"
