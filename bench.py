@@ -8,8 +8,8 @@ Prints ONE JSON line: paths/s, the roofline of the dominant kernel measured live
 HIP events, and the CPU oracle timed on the host cores beside it.
 
 `--op backward` times `sig_backward` (the gradient with respect to the path) and `--op combine`
-times `sig_combine` (the group product of two batches of signatures) on the same workload
-shapes instead; the default, and the metric this repository is judged on, is the forward pass.
+times `sig_combine` (the group product of two batches of signatures) and `--op logsignature` the
+forward pass followed by `sig_log` and `sig_lyndon_gather`, on the same workload shapes instead; the default, and the metric this repository is judged on, is the forward pass.
 """
 from __future__ import annotations
 
@@ -63,7 +63,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2, help="configuration number 1..5 (default: the metric's)")
     ap.add_argument("--variant", choices=["auto", "generic", "mfma"], default="auto")
-    ap.add_argument("--op", choices=["forward", "backward", "combine"], default="forward")
+    ap.add_argument("--op", choices=["forward", "backward", "combine", "logsignature"], default="forward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 256 MiB device-to-device copies before the timed region, so that "
@@ -113,6 +113,16 @@ def main() -> int:
         def step():  # noqa: F811
             sig.sig_backward(x, out, grad_out, w.N, stream=w.stream, basepoint=w.basepoint, grad_path=grad_path,
                              workspace=workspace)
+    elif args.op == "logsignature":
+        log_full = torch.empty_like(out)
+        n_words = sig.sig_logsignature_channels(w.d, w.N)
+        log_words = torch.empty(out_shape[:-1] + (n_words,), dtype=torch.float32, device=dev)
+        kernel = kernel + "+log+gather"
+
+        def step():  # noqa: F811
+            sig.sig_forward(x, w.N, stream=w.stream, basepoint=w.basepoint, out=out, variant=variant)
+            sig.sig_log(out, w.d, w.N, out=log_full)
+            sig.sig_lyndon_gather(log_full, w.d, w.N, out=log_words)
     elif args.op == "combine":
         step()
         lhs = out.reshape(-1, S)
@@ -164,6 +174,12 @@ def main() -> int:
         flops = w.B * w.n_inc * backward_flops_per_increment(w.d, w.N, M, S)
         bytes_io = 4 * (2 * w.B * w.L * w.d + 2 * int(np.prod(out_shape)))
         metric = "signature gradients/sec (paths/s)"
+    elif args.op == "logsignature":
+        rows = int(np.prod(out_shape[:-1]))
+        # the logarithm by Horner's rule: pass m forms levels 1..N-m+1, a level-k word costs k-1 multiply-adds
+        flops += 2 * rows * sum((k - 1) * w.d ** k for m in range(1, w.N + 1) for k in range(2, w.N - m + 2))
+        bytes_io = 4 * (w.B * w.L * w.d + rows * n_words)
+        metric = "logsignatures/sec (paths/s)"
     elif args.op == "combine":
         units = int(lhs.shape[0])
         flops = 2 * units * sum((k - 1) * w.d ** k for k in range(2, w.N + 1))
@@ -225,6 +241,8 @@ def main() -> int:
             elif args.op == "combine":
                 for i in range(n_sample):   # the oracle's product is one pair at a time, single-threaded
                     sig_oracle.group_mul(la[i], lb[i], w.d, w.N)
+            elif args.op == "logsignature":
+                sig_oracle.logsignature(xs, w.N, stream=w.stream, basepoint=w.basepoint)
             else:
                 sig_oracle.signature(xs, w.N, stream=w.stream, basepoint=w.basepoint)
 
@@ -238,10 +256,12 @@ def main() -> int:
             "unit": "products/s" if args.op == "combine" else "paths/s",
             "cores": 1 if args.op == "combine" else sig_oracle.max_threads(),
             "kind": "oracle",
-            "sample": f"first {n_sample} of {units} {'pairs' if args.op == 'combine' else 'paths'} of {w.name}, "
-                      f"op {args.op}: fp64 exp + group product per increment"
-                      f"{' and their adjoints over the stored forward' if args.op == 'backward' else ''}, "
-                      f"OpenMP over paths, best of {passes} passes ({best:.3f} s each, {spent:.1f} s in all)",
+            "sample": f"first {n_sample} of {units} {'pairs' if args.op == 'combine' else 'paths'} of {w.name}, op {args.op}: " + {
+                "forward": "fp64 exp + group product per increment, OpenMP over paths",
+                "backward": "fp64 exp + group product per increment and their adjoints over the stored forward, OpenMP over paths",
+                "combine": "fp64 group product, one pair at a time on one core",
+                "logsignature": "fp64 signature (OpenMP over paths), then the power series of log one row at a time on one core",
+            }[args.op] + f", best of {passes} passes ({best:.3f} s each, {spent:.1f} s in all)",
         }
 
     print(json.dumps(result), flush=True)

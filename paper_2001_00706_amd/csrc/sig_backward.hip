@@ -315,6 +315,10 @@ int64_t backward_workspace_bytes(const Shape &sh, sig_dtype dtype)
 hipError_t launch_backward_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
                                float *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st)
 {
+    const bool aligned = (reinterpret_cast<uintptr_t>(path) | reinterpret_cast<uintptr_t>(sig) |
+                          reinterpret_cast<uintptr_t>(gout) | reinterpret_cast<uintptr_t>(sh.basepoint_value)) % 16 == 0;
+    if (aligned && backward_d4_supported(sh))
+        return launch_backward_d4_f32(sh, path, sig, gout, gpath, gbase, st);
     return launch_backward<float>(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
 }
 

@@ -62,6 +62,11 @@ hipError_t launch_gather_f32(const Shape &sh, const float *in, const int64_t *in
 hipError_t launch_gather_f64(const Shape &sh, const double *in, const int64_t *index, int64_t n, double *out, hipStream_t st);
 int64_t lyndon_indices_host(const Shape &sh, int64_t *indices, int64_t cap);
 
+// Register-resident gradient kernel: fp32, d = 4, N = 4..6, 16-byte aligned buffers; needs no workspace.
+bool backward_d4_supported(const Shape &sh);
+hipError_t launch_backward_d4_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
+                                  float *gbase, hipStream_t st);
+
 // Small-state family: S <= 512 scalars, one wavefront per path, state in LDS, words decoded once.
 bool small_supported(const Shape &sh);
 hipError_t launch_small_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
