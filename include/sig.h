@@ -106,6 +106,26 @@ sig_status sig_forward_variant(const void *path, int64_t B, int64_t L, int d, in
                                int stream, int basepoint, sig_dtype dtype,
                                void *out, hipStream_t hip_stream, sig_variant variant);
 
+/* sig_forward (final mode) as a parallel reduction over the length of the path (section 5.1: the scan is a
+ * reduction with respect to an associative operation, so it may be split into chunks): every path is cut into
+ * `chunks` stretches of ceil(n_inc / chunks) increments, all B * chunks stretches are scanned at once by the
+ * kernels of sig_forward, and neighbouring results are joined pairwise by sig_combine's product (Chen's identity,
+ * eq. "grouplike") in log2(chunks) rounds.  Worth it when B alone cannot fill the device and L is long.
+ *   chunks     a power of two, 2 .. 65536 (stretches past the end of a short path are empty and count as the
+ *              identity).
+ *   basepoint_value  as for sig_signature.
+ *   workspace  DEVICE pointer, 16-byte aligned, at least sig_forward_chunked_workspace_bytes(...) bytes
+ *              (1.5 * B * chunks signatures); contents undefined on return; calls that overlap in time must not
+ *              share it.
+ * Same result as sig_forward up to rounding.  Errors as for sig_forward; SIG_ERR_INVALID_ARG for a bad `chunks` or a
+ * missing, short or misaligned workspace; SIG_ERR_UNSUPPORTED if S >= 2^31. */
+sig_status sig_forward_chunked(const void *path, int64_t B, int64_t L, int d, int N, int basepoint,
+                               const void *basepoint_value, int chunks, sig_dtype dtype, void *out,
+                               void *workspace, int64_t workspace_bytes, hipStream_t hip_stream);
+
+/* Bytes of workspace sig_forward_chunked needs; -1 on invalid arguments. */
+int64_t sig_forward_chunked_workspace_bytes(int64_t B, int64_t L, int d, int N, int basepoint, int chunks, sig_dtype dtype);
+
 /* Group product of two batches of signatures: out[b] = a[b] [x] b[b], with
  * (A [x] B)_k = sum_{j=0..k} A_j (x) B_{k-j}, A_0 = B_0 = 1 (section 2.2).  By Chen's identity
  * (eq. "grouplike") this joins the signatures of two adjacent intervals that share their

@@ -31,6 +31,8 @@ from .binding import (  # noqa: F401
     sig_lyndon_indices,
     sig_signature,
     sig_forward,
+    sig_forward_chunked,
+    sig_forward_chunked_workspace_bytes,
     sig_forward_raw,
     sig_fused_fmas,
     sig_output_elems,

@@ -26,6 +26,8 @@ EXPORTED_SYMBOLS = (
     "sig_fused_fmas",
     "sig_forward",
     "sig_forward_variant",
+    "sig_forward_chunked",
+    "sig_forward_chunked_workspace_bytes",
     "sig_combine",
     "sig_backward",
     "sig_combine_strided",
@@ -71,6 +73,10 @@ def load_library() -> ctypes.CDLL:
         lib.sig_forward.argtypes = [vp, i64, i64, i32, i32, i32, i32, i32, vp, vp]
         lib.sig_forward_variant.restype = i32
         lib.sig_forward_variant.argtypes = [vp, i64, i64, i32, i32, i32, i32, i32, vp, vp, i32]
+        lib.sig_forward_chunked.restype = i32
+        lib.sig_forward_chunked.argtypes = [vp, i64, i64, i32, i32, i32, vp, i32, i32, vp, vp, i64, vp]
+        lib.sig_forward_chunked_workspace_bytes.restype = i64
+        lib.sig_forward_chunked_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32, i32]
         lib.sig_combine.restype = i32
         lib.sig_combine.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
         lib.sig_backward.restype = i32
@@ -460,3 +466,40 @@ def sig_logsignature(path, N: int, stream: bool = False, basepoint=False, invers
     d = path.shape[2]
     full = sig_log(sig_signature(path, N, stream=stream, basepoint=basepoint, inverse=inverse), d, N)
     return full if mode == "expand" else sig_lyndon_gather(full, d, N)
+
+
+def sig_forward_chunked_workspace_bytes(B: int, L: int, d: int, N: int, basepoint: bool, chunks: int,
+                                        dtype: int = SIG_F32) -> int:
+    return int(load_library().sig_forward_chunked_workspace_bytes(B, L, d, N, int(bool(basepoint)), chunks, dtype))
+
+
+def sig_forward_chunked(path, N: int, chunks: int, basepoint=False, out=None, workspace=None):
+    """`sig_forward` (final mode) with every path cut into `chunks` stretches (a power of two) that are scanned
+    in parallel and joined by group products; `workspace` (uint8, GPU) is allocated through torch if not given."""
+    import torch
+
+    _check_gpu("sig_forward_chunked", path)
+    if path.dim() != 3 or not path.is_contiguous():
+        raise ValueError("path must be a contiguous tensor of shape [B, L, d]")
+    dtype = _dtype_of(path)
+    B, L, d = path.shape
+    bp_flag, bp_value = _basepoint_args(path, basepoint)
+    S = sig_signature_channels(d, N)
+    need = sig_forward_chunked_workspace_bytes(B, L, d, N, bool(bp_flag), chunks, dtype)
+    if need < 0:
+        status = int(load_library().sig_forward_chunked(path.data_ptr(), B, L, d, N, bp_flag, 0, chunks, dtype, 0, 0, 0, 0))
+        raise SigError(status, sig_status_string(status))
+    if out is None:
+        out = torch.empty((B, S), dtype=path.dtype, device=path.device)
+    elif out.dtype != path.dtype or out.device != path.device or tuple(out.shape) != (B, S) or not out.is_contiguous():
+        raise ValueError(f"out must be a contiguous {path.dtype} tensor of shape {(B, S)} on {path.device}")
+    with torch.cuda.device(path.device):
+        if workspace is None:
+            workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=path.device)
+        status = int(load_library().sig_forward_chunked(
+            path.data_ptr(), B, L, d, N, bp_flag, bp_value.data_ptr() if bp_value is not None else 0, chunks, dtype,
+            out.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+            torch.cuda.current_stream().cuda_stream))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return out

@@ -39,6 +39,8 @@ sig_status make_shape(int64_t B, int64_t L, int d, int N, int stream, int basepo
     sh.stream = stream ? 1 : 0;
     sh.basepoint = basepoint ? 1 : 0;
     sh.basepoint_value = nullptr;
+    sh.chunks = 1;
+    sh.chunk_len = 0;
     sh.n_inc = basepoint ? L : L - 1;
     // path elements B*L*d and output elements B*[n_inc*]S must stay below kMaxElems
     if (L > kMaxElems / d) return SIG_ERR_OVERFLOW;
@@ -173,6 +175,8 @@ sig_status sig_combine(const void *a, const void *b, int64_t B, int d, int N, si
     sh.n_inc = 0;
     sh.stream = sh.basepoint = 0;
     sh.basepoint_value = nullptr;
+    sh.chunks = 1;
+    sh.chunk_len = 0;
     if (B == 0) return SIG_OK;
     if (a == nullptr || b == nullptr || out == nullptr) return SIG_ERR_INVALID_ARG;
     if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
@@ -231,6 +235,8 @@ static sig_status make_rows_shape(int64_t rows, int d, int N, sig::Shape &sh)
     sh.n_inc = 0;
     sh.stream = sh.basepoint = 0;
     sh.basepoint_value = nullptr;
+    sh.chunks = 1;
+    sh.chunk_len = 0;
     return SIG_OK;
 }
 
@@ -269,6 +275,72 @@ sig_status sig_combine_strided(const void *a, int64_t a_stride, const void *b, i
             : sig::launch_combine_f64(sh, static_cast<const double *>(a), static_cast<const double *>(b),
                                       static_cast<double *>(out), hip_stream, strides);
     return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
+// Shape of a chunked scan: B * chunks rows, each a stretch of chunk_len increments.  SIG_OK or why not.
+static sig_status make_chunked_shape(int64_t B, int64_t L, int d, int N, int basepoint, int chunks, sig::Shape &sh)
+{
+    const sig_status st = make_shape(B, L, d, N, 0, basepoint, sh);
+    if (st != SIG_OK) return st;
+    if (chunks < 2 || chunks > 65536 || (chunks & (chunks - 1)) != 0) return SIG_ERR_INVALID_ARG;
+    if (B > 0 && sh.S > kMaxElems / 2 / chunks / B) return SIG_ERR_OVERFLOW;
+    sh.chunks = chunks;
+    sh.chunk_len = (sh.n_inc + chunks - 1) / chunks;
+    sh.B = B * chunks;
+    return SIG_OK;
+}
+
+int64_t sig_forward_chunked_workspace_bytes(int64_t B, int64_t L, int d, int N, int basepoint, int chunks, sig_dtype dtype)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return -1;
+    sig::Shape sh;
+    if (make_chunked_shape(B, L, d, N, basepoint, chunks, sh) != SIG_OK) return -1;
+    // the chunk signatures, and half as much again for the first round of products
+    return (sh.B + sh.B / 2) * sh.S * int64_t(dtype == SIG_F32 ? sizeof(float) : sizeof(double));
+}
+
+sig_status sig_forward_chunked(const void *path, int64_t B, int64_t L, int d, int N, int basepoint,
+                               const void *basepoint_value, int chunks, sig_dtype dtype, void *out,
+                               void *workspace, int64_t workspace_bytes, hipStream_t hip_stream)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
+    sig::Shape sh;
+    const sig_status st = make_chunked_shape(B, L, d, N, basepoint, chunks, sh);
+    if (st != SIG_OK) return st;
+    if (!sh.basepoint && basepoint_value != nullptr) return SIG_ERR_INVALID_ARG;
+    if (B == 0) return SIG_OK;
+    if (path == nullptr || out == nullptr || workspace == nullptr) return SIG_ERR_INVALID_ARG;
+    const int64_t elem = dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double));
+    if (workspace_bytes < (sh.B + sh.B / 2) * sh.S * elem || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)
+        return SIG_ERR_INVALID_ARG;
+    if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
+    sh.basepoint_value = basepoint_value;
+    const Family family = resolve(sh, dtype, SIG_VARIANT_AUTO, path, workspace);
+    if (family == Family::None) return SIG_ERR_UNSUPPORTED;
+    // every chunk scanned on its own ...
+    char *ws0 = static_cast<char *>(workspace);
+    char *ws1 = ws0 + sh.B * sh.S * elem;
+    if (launch_family(family, sh, dtype, path, ws0, hip_stream) != hipSuccess) return SIG_ERR_HIP;
+    // ... then neighbours joined pairwise (Chen's identity), halving the count each round
+    sig::Shape rows = sh;
+    rows.chunks = 1;
+    const char *src = ws0;
+    char *spare = ws1;
+    for (int64_t count = sh.B / 2; count >= B; count /= 2) {
+        rows.B = count;
+        char *dst = count == B ? static_cast<char *>(out) : spare;
+        const int64_t strides[3] = {2 * sh.S, 2 * sh.S, sh.S};
+        const hipError_t err =
+            dtype == SIG_F32
+                ? sig::launch_combine_f32(rows, reinterpret_cast<const float *>(src), reinterpret_cast<const float *>(src) + sh.S,
+                                          reinterpret_cast<float *>(dst), hip_stream, strides)
+                : sig::launch_combine_f64(rows, reinterpret_cast<const double *>(src), reinterpret_cast<const double *>(src) + sh.S,
+                                          reinterpret_cast<double *>(dst), hip_stream, strides);
+        if (err != hipSuccess) return SIG_ERR_HIP;
+        spare = const_cast<char *>(src);
+        src = dst;
+    }
+    return SIG_OK;
 }
 
 int64_t sig_logsignature_channels(int d, int N)

@@ -44,7 +44,9 @@ sig_generic_kernel(Shape sh, const T *__restrict__ path, T *out, int state_in_ld
     const int64_t S = sh.S;
 
     for (int64_t b = blockIdx.x; b < sh.B; b += gridDim.x) {
-        const T *x = path + b * sh.L * d;
+        const ChunkView cv = chunk_view(b, sh.chunks, sh.chunk_len, sh.n_inc);
+        const int64_t n_inc = cv.n;
+        const T *x = path + cv.path * sh.L * d;
         const T *bpv = static_cast<const T *>(sh.basepoint_value);
         T *obase = out + b * (sh.stream ? sh.n_inc * S : S);
         T *cur = nullptr;
@@ -57,19 +59,19 @@ sig_generic_kernel(Shape sh, const T *__restrict__ path, T *out, int state_in_ld
         }
         __syncthreads();
 
-        for (int64_t s = 0; s < sh.n_inc; ++s) {
+        for (int64_t s = 0; s < n_inc; ++s) {
             const int in_tile = int(s % tile);
             if (in_tile == 0) {
                 // stage the increments of the next `tile` steps: one trip to memory per tile, not per step
-                const int64_t left = sh.n_inc - s;
+                const int64_t left = n_inc - s;
                 const int n_stage = int(left < tile ? left : tile) * d;
                 for (int i = tid; i < n_stage; i += nt) {
-                    const int64_t si = s + i / d;
+                    const int64_t si = cv.inc0 + s + i / d;
                     const int c = i % d;
                     T hi, lo;
                     if (sh.basepoint) {
                         hi = x[si * d + c];
-                        lo = si > 0 ? x[(si - 1) * d + c] : bpv != nullptr ? bpv[b * d + c] : T(0);
+                        lo = si > 0 ? x[(si - 1) * d + c] : bpv != nullptr ? bpv[cv.path * d + c] : T(0);
                     } else {
                         hi = x[(si + 1) * d + c];
                         lo = x[si * d + c];

@@ -18,9 +18,30 @@ struct Shape {
     int d, N;
     int stream, basepoint;
     const void *basepoint_value;     // DEVICE [B][d]: the point prepended when basepoint != 0; null = the origin
+    // Chunked scans (final mode only): B counts chunks, `chunks` consecutive ones belong to one path of L points
+    // and n_inc increments; chunk c folds in the increments c*chunk_len .. min((c+1)*chunk_len, n_inc) - 1 and
+    // basepoint_value is indexed by path.  chunks == 1: B counts paths.
+    int chunks;
+    int64_t chunk_len;
     int64_t pw[SIG_MAX_DEPTH + 1];   // pw[k] = d^k, k = 0..N
     int64_t off[SIG_MAX_DEPTH + 2];  // off[k] = offset of level k (1-based) in a signature; off[N+1] = S
 };
+
+// Which stretch of which path the scan of output row `row` folds in.
+struct ChunkView {
+    int64_t path;   // index of the path (for the path pointer and the basepoint value)
+    int64_t inc0;   // number of its first increment inside that path
+    int64_t n;      // increments to fold in (0 for a chunk past the end: its result is the identity)
+};
+
+__host__ __device__ inline ChunkView chunk_view(int64_t row, int chunks, int64_t chunk_len, int64_t n_inc_total)
+{
+    if (chunks <= 1) return {row, 0, n_inc_total};
+    const int64_t p = row / chunks;
+    const int64_t inc0 = (row - p * chunks) * chunk_len;
+    const int64_t left = n_inc_total - inc0;
+    return {p, inc0, left < 0 ? 0 : left < chunk_len ? left : chunk_len};
+}
 
 // Generic family: any d, N; one workgroup per path.  `generic_supported` is false only when
 // the per-step scalings z/1..z/N (N*d scalars) do not fit the workgroup's LDS.

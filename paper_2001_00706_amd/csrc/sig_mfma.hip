@@ -122,20 +122,24 @@ __device__ __forceinline__ int park6(int i) { return i ^ ((i >> 8) << 2); }
 
 template <int N>
 __global__ void __launch_bounds__(64)
-sig_mfma_d4_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint,
-                   const float *__restrict__ bpv)
+sig_mfma_d4_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc_total, int basepoint,
+                   const float *__restrict__ bpv, int chunks, int64_t chunk_len)
 {
     static_assert(N >= 4 && N <= 6, "depths served by this kernel");
     __shared__ __align__(16) float lds[kLdsFloats<N>];
 
     const int lane = threadIdx.x;
     const int w1 = lane >> 4, w2 = (lane >> 2) & 3, q = lane & 3;
-    const int64_t b = blockIdx.x;
-    const f4 *x4 = reinterpret_cast<const f4 *>(path) + b * L;  // point l of this path
+    const int64_t b = blockIdx.x;   // output row: a path, or one chunk of a path
+    const ChunkView cv = chunk_view(b, chunks, chunk_len, n_inc_total);
+    const int64_t n_inc = cv.n;
+    const f4 *x4 = reinterpret_cast<const f4 *>(path) + cv.path * L;  // point l of this path
     const f4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
-    // the point before the first increment: the path's first point, or the basepoint (the origin unless given)
-    const f4 x_base = bpv != nullptr ? reinterpret_cast<const f4 *>(bpv)[b] : zero4;
-    const f4 x_first = basepoint ? x_base : x4[0];
+    // the point before the first increment: the path's first point, or the basepoint (the origin unless given),
+    // or the point a later chunk starts from
+    const f4 x_base = bpv != nullptr ? reinterpret_cast<const f4 *>(bpv)[cv.path] : zero4;
+    const int64_t i_first = basepoint ? cv.inc0 - 1 : cv.inc0;
+    const f4 x_first = n_inc == 0 ? zero4 : i_first >= 0 ? x4[i_first] : x_base;
 
     State<N> S;
     S.A4[0] = zero4;
@@ -150,7 +154,7 @@ sig_mfma_d4_kernel(const float *__restrict__ path, float *__restrict__ out, int6
     auto fetch_points = [&](int64_t s) {
         p_hi = p_lo = zero4;
         if (s < n_inc) {
-            const int64_t i_hi = basepoint ? s : s + 1;
+            const int64_t i_hi = cv.inc0 + (basepoint ? s : s + 1);
             p_hi = x4[i_hi];
             p_lo = i_hi > 0 ? x4[i_hi - 1] : x_base;
         }
@@ -201,7 +205,7 @@ sig_mfma_d4_kernel(const float *__restrict__ path, float *__restrict__ out, int6
     }
 
     // level 1 is the total displacement
-    const f4 a1 = x4[L - 1] - x_first;
+    const f4 a1 = n_inc == 0 ? zero4 : x4[i_first + n_inc] - x_first;
 
     // park the state in LDS in word order, then copy it out 16 bytes per lane, fully coalesced
     __syncthreads();
@@ -253,9 +257,9 @@ hipError_t launch_mfma_f32(const Shape &sh, const float *path, float *out, hipSt
     const dim3 grid(static_cast<unsigned>(sh.B)), block(64);
     const float *bpv = static_cast<const float *>(sh.basepoint_value);
     switch (sh.N) {
-        case 4: hipLaunchKernelGGL(sig_mfma_d4_kernel<4>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint, bpv); break;
-        case 5: hipLaunchKernelGGL(sig_mfma_d4_kernel<5>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint, bpv); break;
-        case 6: hipLaunchKernelGGL(sig_mfma_d4_kernel<6>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint, bpv); break;
+        case 4: hipLaunchKernelGGL(sig_mfma_d4_kernel<4>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint, bpv, sh.chunks, sh.chunk_len); break;
+        case 5: hipLaunchKernelGGL(sig_mfma_d4_kernel<5>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint, bpv, sh.chunks, sh.chunk_len); break;
+        case 6: hipLaunchKernelGGL(sig_mfma_d4_kernel<6>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint, bpv, sh.chunks, sh.chunk_len); break;
         default: return hipErrorNotSupported;
     }
     return hipGetLastError();

@@ -85,8 +85,8 @@ __device__ __forceinline__ void half_trip(float &A1, float &A2, f16v (&A4)[8], c
 }
 
 __global__ void __launch_bounds__(512)
-sig_mfma_d16_n4_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint,
-                       const float *__restrict__ bpv)
+sig_mfma_d16_n4_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc_total, int basepoint,
+                       const float *__restrict__ bpv, int chunks, int64_t chunk_len)
 {
     __shared__ __align__(16) float lds[kTile16 * kRow16];
 
@@ -98,8 +98,10 @@ sig_mfma_d16_n4_kernel(const float *__restrict__ path, float *__restrict__ out, 
     const int e = b & 1;                          // which of the two owned first letters this block serves
     const int w1 = 4 * (2 * h + e) + y;           // that first letter
     const bool k4 = b < 2;                        // blocks 0,1 serve target level 4, blocks 2,3 level 3
-    const int64_t path_no = blockIdx.x;
-    const f4 *x4 = reinterpret_cast<const f4 *>(path) + path_no * L * 4;  // 4 chunks of 16 bytes per point
+    const int64_t path_no = blockIdx.x;   // output row: a path, or one chunk of a path
+    const ChunkView cv = chunk_view(path_no, chunks, chunk_len, n_inc_total);
+    const int64_t n_inc = cv.n;
+    const f4 *x4 = reinterpret_cast<const f4 *>(path) + cv.path * L * 4;  // 4 pieces of 16 bytes per point
 
     // state
     float A1 = 0.0f;                  // A_1[w1]
@@ -131,10 +133,10 @@ sig_mfma_d16_n4_kernel(const float *__restrict__ path, float *__restrict__ out, 
             const int i = tid >> 2, c4 = tid & 3;
             if (i < nt) {
                 const int64_t s = t0 + i;
-                const int64_t i_hi = basepoint ? s : s + 1;
+                const int64_t i_hi = cv.inc0 + (basepoint ? s : s + 1);
                 const f4 hi = x4[i_hi * 4 + c4];
                 const f4 lo = i_hi > 0         ? x4[(i_hi - 1) * 4 + c4]
-                              : bpv != nullptr ? reinterpret_cast<const f4 *>(bpv)[path_no * 4 + c4]
+                              : bpv != nullptr ? reinterpret_cast<const f4 *>(bpv)[cv.path * 4 + c4]
                                                : (f4){0.0f, 0.0f, 0.0f, 0.0f};
                 const f4 z = hi - lo;
                 f4 *row = reinterpret_cast<f4 *>(lds + i * kRow16) + c4;
@@ -209,7 +211,7 @@ hipError_t launch_mfma_d16_f32(const Shape &sh, const float *path, float *out, h
 {
     if (mfma_d16_kernel_name(sh) == nullptr) return hipErrorNotSupported;
     hipLaunchKernelGGL(sig_mfma_d16_n4_kernel, dim3(static_cast<unsigned>(sh.B)), dim3(512), 0, st, path, out, sh.L,
-                       sh.n_inc, sh.basepoint, static_cast<const float *>(sh.basepoint_value));
+                       sh.n_inc, sh.basepoint, static_cast<const float *>(sh.basepoint_value), sh.chunks, sh.chunk_len);
     return hipGetLastError();
 }
 

@@ -179,8 +179,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(float *base, unsigne
 
 template <int N, bool STREAM>
 __global__ void __launch_bounds__(64)
-sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint,
-                         const float *__restrict__ bpv)
+sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc_total,
+                         int basepoint, const float *__restrict__ bpv, int chunks, int64_t chunk_len)
 {
     static_assert(N >= 4 && N <= 7, "depths served by this kernel");
     constexpr int kRow = 4 * (N - 1);  // floats per staged increment
@@ -190,9 +190,11 @@ sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out
 
     const int lane = threadIdx.x;
     const int w2 = lane >> 4, w3 = (lane >> 2) & 3, q = lane & 3;
-    const int64_t b = blockIdx.x >> 2;
+    const int64_t b = blockIdx.x >> 2;   // output row: a path, or one chunk of a path
     const int f = blockIdx.x & 3;
-    const f4 *x4 = reinterpret_cast<const f4 *>(path) + b * L;  // point l of this path
+    const ChunkView cv = chunk_view(b, chunks, chunk_len, n_inc_total);
+    const int64_t n_inc = cv.n;
+    const f4 *x4 = reinterpret_cast<const f4 *>(path) + cv.path * L;  // point l of this path
     float *o = out + b * (STREAM ? n_inc * kS : int64_t(kS));
 
     const StorePlan plan = make_store_plan<N>(f, lane);
@@ -210,10 +212,10 @@ sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out
     auto fetch_points = [&](int64_t s) {
         p_hi = p_lo = (f4){0.0f, 0.0f, 0.0f, 0.0f};
         if (s < n_inc) {
-            const int64_t i_hi = basepoint ? s : s + 1;
+            const int64_t i_hi = cv.inc0 + (basepoint ? s : s + 1);
             p_hi = x4[i_hi];
             if (i_hi > 0) p_lo = x4[i_hi - 1];
-            else if (bpv != nullptr) p_lo = reinterpret_cast<const f4 *>(bpv)[b];
+            else if (bpv != nullptr) p_lo = reinterpret_cast<const f4 *>(bpv)[cv.path];
         }
     };
     fetch_points(lane);
@@ -257,10 +259,10 @@ hipError_t launch_shard(const Shape &sh, const float *path, float *out, hipStrea
     const dim3 grid(static_cast<unsigned>(sh.B * 4)), block(64);
     if (sh.stream) {
         hipLaunchKernelGGL((sig_mfma_d4_shard_kernel<N, true>), grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint,
-                           static_cast<const float *>(sh.basepoint_value));
+                           static_cast<const float *>(sh.basepoint_value), sh.chunks, sh.chunk_len);
     } else {
         hipLaunchKernelGGL((sig_mfma_d4_shard_kernel<N, false>), grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint,
-                           static_cast<const float *>(sh.basepoint_value));
+                           static_cast<const float *>(sh.basepoint_value), sh.chunks, sh.chunk_len);
     }
     return hipGetLastError();
 }

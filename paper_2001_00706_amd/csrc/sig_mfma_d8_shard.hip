@@ -122,8 +122,8 @@ typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 
 template <int N>
 __global__ void __launch_bounds__(64)
-sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint,
-                         const float *__restrict__ bpv)
+sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc_total,
+                         int basepoint, const float *__restrict__ bpv, int chunks, int64_t chunk_len)
 {
     static_assert(N >= 4 && N <= 6, "depths served by this kernel");
     constexpr int kRow = kD8;  // floats per staged increment
@@ -132,9 +132,11 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
 
     const int lane = threadIdx.x;
     const int w3 = lane >> 3, w4 = lane & 7, q = lane & 3;
-    const int64_t b = blockIdx.x >> 6;
+    const int64_t b = blockIdx.x >> 6;   // output row: a path, or one chunk of a path
     const int f1 = (blockIdx.x >> 3) & 7, f2 = blockIdx.x & 7;
-    const f4 *x4 = reinterpret_cast<const f4 *>(path) + b * L * 2;  // 2 chunks of 16 bytes per point
+    const ChunkView cv = chunk_view(b, chunks, chunk_len, n_inc_total);
+    const int64_t n_inc = cv.n;
+    const f4 *x4 = reinterpret_cast<const f4 *>(path) + cv.path * L * 2;  // 2 pieces of 16 bytes per point
     float *o = out + b * kS;
 
     State8<N> S;
@@ -148,15 +150,15 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
     auto fetch_points = [&](int64_t s) {
         hi0 = hi1 = lo0 = lo1 = (f4){0.0f, 0.0f, 0.0f, 0.0f};
         if (s < n_inc) {
-            const int64_t i_hi = basepoint ? s : s + 1;
+            const int64_t i_hi = cv.inc0 + (basepoint ? s : s + 1);
             hi0 = x4[i_hi * 2];
             hi1 = x4[i_hi * 2 + 1];
             if (i_hi > 0) {
                 lo0 = x4[(i_hi - 1) * 2];
                 lo1 = x4[(i_hi - 1) * 2 + 1];
             } else if (bpv != nullptr) {
-                lo0 = reinterpret_cast<const f4 *>(bpv)[b * 2];
-                lo1 = reinterpret_cast<const f4 *>(bpv)[b * 2 + 1];
+                lo0 = reinterpret_cast<const f4 *>(bpv)[cv.path * 2];
+                lo1 = reinterpret_cast<const f4 *>(bpv)[cv.path * 2 + 1];
             }
         }
     };
@@ -221,7 +223,7 @@ template <int N>
 hipError_t launch8(const Shape &sh, const float *path, float *out, hipStream_t st)
 {
     hipLaunchKernelGGL(sig_mfma_d8_shard_kernel<N>, dim3(static_cast<unsigned>(sh.B * 64)), dim3(64), 0, st, path, out,
-                       sh.L, sh.n_inc, sh.basepoint, static_cast<const float *>(sh.basepoint_value));
+                       sh.L, sh.n_inc, sh.basepoint, static_cast<const float *>(sh.basepoint_value), sh.chunks, sh.chunk_len);
     return hipGetLastError();
 }
 

@@ -65,22 +65,24 @@ sig_small_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
     }
 
     for (int64_t b = blockIdx.x; b < sh.B; b += gridDim.x) {
-        const T *x = path + b * sh.L * d;
+        const ChunkView cv = chunk_view(b, sh.chunks, sh.chunk_len, sh.n_inc);
+        const int64_t n_inc = cv.n;
+        const T *x = path + cv.path * sh.L * d;
         const T *bpv = static_cast<const T *>(sh.basepoint_value);
         T *o = out + b * (sh.stream ? sh.n_inc * int64_t(S) : int64_t(S));
         for (int i = lane; i <= S; i += 64) st[i] = T(0);
 
-        for (int64_t t0 = 0; t0 < sh.n_inc; t0 += kSmallTile) {
-            const int nt = int(sh.n_inc - t0 < kSmallTile ? sh.n_inc - t0 : kSmallTile);
+        for (int64_t t0 = 0; t0 < n_inc; t0 += kSmallTile) {
+            const int nt = int(n_inc - t0 < kSmallTile ? n_inc - t0 : kSmallTile);
             __syncthreads();
             for (int i = lane; i < nt * d; i += 64) {
                 const int si = small_div(i, magic);
                 const int c = i - si * d;
-                const int64_t s = t0 + si;
+                const int64_t s = cv.inc0 + t0 + si;
                 T hi, lo;
                 if (sh.basepoint) {
                     hi = x[s * d + c];
-                    lo = s > 0 ? x[(s - 1) * d + c] : bpv != nullptr ? bpv[b * d + c] : T(0);
+                    lo = s > 0 ? x[(s - 1) * d + c] : bpv != nullptr ? bpv[cv.path * d + c] : T(0);
                 } else {
                     hi = x[(s + 1) * d + c];
                     lo = x[s * d + c];

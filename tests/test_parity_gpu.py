@@ -383,3 +383,45 @@ def test_chunked_scan_plus_combine_equals_the_whole_scan():
     want = orc.signature(x[:8], w.N)
     batch, _ = level_errors(joined[:8].cpu().numpy(), want, w.d, w.N)
     assert np.all(batch <= 1e-4), batch
+
+
+# ------------------------------------------------------------- scan as a parallel reduction over L
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("B,L,d,N,chunks", [
+    (3, 130, 4, 6, 4),     # one wavefront per path family (B * chunks small -> four per path), ragged last chunk
+    (600, 40, 4, 5, 2),    # B * chunks >= 512: one wavefront per chunk
+    (2, 128, 8, 5, 8),     # 127 increments in 8 chunks of 16 (the last one 15)
+    (2, 300, 16, 4, 4),
+    (3, 50, 2, 6, 16),     # small-state family
+    (2, 33, 5, 3, 4),      # fallback family
+    (2, 5, 3, 4, 8),       # more chunks than increments: empty chunks are the identity
+    (1, 2, 4, 4, 2),
+])
+def test_chunked_scan_equals_the_plain_scan(B, L, d, N, chunks, dtype):
+    torch = torch_mod()
+    x = brownian_paths(B, L, d, seed=L + d + chunks).astype(dtype)
+    want = orc.signature(x, N)
+    got = sig.sig_forward_chunked(torch.from_numpy(x).to("cuda:0"), N, chunks)
+    torch.cuda.synchronize()
+    batch, single = level_errors(got.cpu().numpy(), want, d, N)
+    assert np.all(batch <= TOL[dtype]), batch
+    # with a basepoint by value
+    bp = uniform_paths(B, 1, d, seed=3)[:, 0].astype(dtype)
+    want = orc.signature(np.concatenate([bp[:, None], x], axis=1), N)
+    got = sig.sig_forward_chunked(torch.from_numpy(x).to("cuda:0"), N, chunks, basepoint=torch.from_numpy(bp).to("cuda:0"))
+    torch.cuda.synchronize()
+    batch, single = level_errors(got.cpu().numpy(), want, d, N)
+    assert np.all(batch <= TOL[dtype]), batch
+
+
+def test_chunked_scan_argument_checks():
+    torch = torch_mod()
+    x = torch.zeros((2, 9, 4), device="cuda:0")
+    for bad in (0, 1, 3, 6, 1 << 17):
+        with pytest.raises(sig.SigError) as e:
+            sig.sig_forward_chunked(x, 4, bad)
+        assert e.value.status == sig.SIG_ERR_INVALID_ARG
+    need = sig.sig_forward_chunked_workspace_bytes(2, 9, 4, 4, False, 4)
+    assert need == 6 * 2 * 340 * 4
+    with pytest.raises(sig.SigError):
+        sig.sig_forward_chunked(x, 4, 4, workspace=torch.empty(need - 4, dtype=torch.uint8, device="cuda:0"))
