@@ -319,6 +319,8 @@ hipError_t launch_backward_f32(const Shape &sh, const float *path, const float *
                           reinterpret_cast<uintptr_t>(gout) | reinterpret_cast<uintptr_t>(sh.basepoint_value)) % 16 == 0;
     if (aligned && backward_d4_supported(sh))
         return launch_backward_d4_f32(sh, path, sig, gout, gpath, gbase, st);
+    if (aligned && backward_pow2_supported(sh))
+        return launch_backward_pow2_f32(sh, path, sig, gout, gpath, gbase, st);
     return launch_backward<float>(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
 }
 

@@ -88,6 +88,11 @@ bool backward_d4_supported(const Shape &sh);
 hipError_t launch_backward_d4_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
                                   float *gbase, hipStream_t st);
 
+// The same scheme for d = 2 (N = 2..9) and d = 8 (N = 2..5); buffers aligned to min(d, 4) floats.
+bool backward_pow2_supported(const Shape &sh);
+hipError_t launch_backward_pow2_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
+                                    float *gbase, hipStream_t st);
+
 // Small-state family: S <= 512 scalars, one wavefront per path, state in LDS, words decoded once.
 bool small_supported(const Shape &sh);
 hipError_t launch_small_f32(const Shape &sh, const float *path, float *out, hipStream_t st);

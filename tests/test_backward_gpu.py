@@ -71,6 +71,18 @@ def test_shape_sweep(B, L, d, N, dtype):
             check(x, N, stream=stream, basepoint=basepoint)
 
 
+POW2 = [(2, N) for N in range(2, 10)] + [(8, N) for N in range(2, 6)] + [(4, 4), (4, 5), (4, 6)]
+
+
+@pytest.mark.parametrize("d,N", POW2)
+def test_register_resident_kernels_every_depth(d, N):
+    # fp32, d = 2, 4, 8: a thread per word, cotangents summed over siblings with lane exchanges
+    x = brownian_paths(3, 70, d, seed=10 * d + N)      # 69 increments: two tiles, the first one ragged
+    for stream in (False, True):
+        for basepoint in (False, True):
+            check(x, N, stream=stream, basepoint=basepoint)
+
+
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 def test_one_wavefront_per_path_launch(dtype):
     # B >= 512 selects 64-thread workgroups
