@@ -39,83 +39,108 @@ __host__ __device__ constexpr int level_off8(int k)  // offset of level k (1-bas
 
 template <int N>
 struct State8 {
-    float A1 = 0.0f, A2 = 0.0f, A3 = 0.0f, A4 = 0.0f;
+    float A4 = 0.0f;
     f4 A5[2];
     f4 A6[N >= 6 ? 16 : 1];
 };
 
-// This lane's view of one staged increment; X[m] is the value divided by m.
+// Levels 1..3 of a shard do not wait for the levels above them, and inside the shard they are running sums:
+//   A_1[f_1] before increment s is a coordinate of the path itself,
+//   A_2[f] = sum over earlier increments of T_2^(1) z[f_2],    T_k^(1) = z[f_1]/k + A_1,
+//   A_3[f w_3] = sum over earlier increments of T_3^(2) z[w_3], T_k^(2) = T_k^(1) z[f_2]/(k-1) + A_2.
+// So a whole tile of increments is handled at once, one lane per increment, with prefix sums over the lanes,
+// and what the sequential part of the scan needs from the low levels, T_k^(3)[w_3] = T_k^(2) z[w_3]/(k-2) +
+// A_3[w_3] for k = 4..N, is tabulated in LDS next to the increment.  Every one of the 64 shards of a path
+// would otherwise repeat that arithmetic in each lane at each increment.
+//
+// Row of the table for one increment: z[0..7], then T_k^(3)[0..7] for k = 4..N.
+template <int N>
+constexpr int kRow8 = kD8 * (N - 2);
+
+// Inclusive prefix sum over the 64 lanes (lane i receives v_0 + .. + v_i).
+__device__ __forceinline__ float wave_inclusive_scan(float v, int lane)
+{
+    const int in_row = lane & 15;
+    float t;
+    t = quad_swap<0x111>(v);   // row_shr:1
+    if (in_row >= 1) v += t;
+    t = quad_swap<0x112>(v);   // row_shr:2
+    if (in_row >= 2) v += t;
+    t = quad_swap<0x114>(v);   // row_shr:4
+    if (in_row >= 4) v += t;
+    t = quad_swap<0x118>(v);   // row_shr:8
+    if (in_row >= 8) v += t;
+    t = quad_swap<0x142>(v);   // row_bcast:15: the last lane of a row, to the next row
+    if ((lane & 31) >= 16) v += t;
+    t = quad_swap<0x143>(v);   // row_bcast:31: lane 31, to the upper two rows
+    if (lane >= 32) v += t;
+    return v;
+}
+
+// Exclusive prefix sum (lane i receives v_0 + .. + v_{i-1}) and, in `total`, the sum over all lanes.
+__device__ __forceinline__ float wave_exclusive_scan(float v, int lane, float &total)
+{
+    const float incl = wave_inclusive_scan(v, lane);
+    total = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, incl), 63));
+    return incl - v;
+}
+
+// Element i (the same in every lane) of the 8 floats (a, b).
+__device__ __forceinline__ float pick8(f4 a, f4 b, int i)
+{
+    const f4 h = (i & 4) ? b : a;
+    const float lo = (i & 1) ? h[1] : h[0], hi = (i & 1) ? h[3] : h[2];
+    return (i & 2) ? hi : lo;
+}
+
+// One fused multiply-exponentiate restricted to the words of this shard, levels 4..N.  `row` is the table row
+// of the increment.
 template <int N>
 struct Row8 {
-    float zf1;
-    float zf2[N], z3[N], z4[N], zlo[N], zhi[N];
+    float z4, zlo, zhi;
+    float t3[N + 1];   // T_k^(3)[w_3], k = 4..N
 };
 
-// `tab` points at one staged increment z[0..7] in LDS.  Eight wavefronts share a compute unit's
-// LDS port, so only z itself is read from LDS and the scalings z/m are formed in registers.
 template <int N>
-__device__ __forceinline__ Row8<N> load_row8(const float *tab, int f1, int f2, int w3, int w4, int q)
+__device__ __forceinline__ Row8<N> load_row8(const float *row, int w3, int w4, int q)
 {
     Row8<N> R;
-    R.zf1 = tab[f1];
-    const float zf2 = tab[f2], z3 = tab[w3], z4 = tab[w4], zlo = tab[q], zhi = tab[4 + q];
-    R.zf2[1] = zf2;
-    R.z3[1] = z3;
-    R.z4[1] = z4;
-    R.zlo[1] = zlo;
-    R.zhi[1] = zhi;
+    R.z4 = row[w4];
+    R.zlo = row[q];
+    R.zhi = row[4 + q];
 #pragma unroll
-    for (int m = 2; m <= N - 1; ++m) R.zf2[m] = zf2 * (1.0f / m);
-#pragma unroll
-    for (int m = 2; m <= N - 2; ++m) R.z3[m] = z3 * (1.0f / m);
-#pragma unroll
-    for (int m = 2; m <= N - 3; ++m) R.z4[m] = z4 * (1.0f / m);
-#pragma unroll
-    for (int m = 2; m <= N - 4; ++m) {
-        R.zlo[m] = zlo * (1.0f / m);
-        R.zhi[m] = zhi * (1.0f / m);
-    }
+    for (int k = 4; k <= N; ++k) R.t3[k] = row[kD8 * (k - 3) + w3];
     return R;
 }
 
-// One fused multiply-exponentiate restricted to the words of this shard.
 template <int N>
 __device__ __forceinline__ void step8(State8<N> &S, const Row8<N> &R)
 {
-    float t1[N + 1], t2[N + 1], t3[N + 1], t4[N + 1];
+    float t4[N + 1];
 #pragma unroll
-    for (int k = 2; k <= N; ++k) t1[k] = __builtin_fmaf(R.zf1, 1.0f / k, S.A1);
-#pragma unroll
-    for (int k = 2; k <= N; ++k) t2[k] = __builtin_fmaf(t1[k], R.zf2[k - 1], S.A2);
-#pragma unroll
-    for (int k = 3; k <= N; ++k) t3[k] = __builtin_fmaf(t2[k], R.z3[k - 2], S.A3);
-#pragma unroll
-    for (int k = 4; k <= N; ++k) t4[k] = __builtin_fmaf(t3[k], R.z4[k - 3], S.A4);
+    for (int k = 4; k <= N; ++k) t4[k] = __builtin_fmaf(R.t3[k], k == 4 ? R.z4 : R.z4 * (1.0f / (k - 3)), S.A4);
 
     if constexpr (N >= 5) {
         if constexpr (N >= 6) {
             // T_6^(5), then the level-6 update (top level: operands swapped)
             f4 t5[2];
-            t5[0] = outer4(t4[6], R.zlo[2], S.A5[0]);
-            t5[1] = outer4(t4[6], R.zhi[2], S.A5[1]);
+            t5[0] = outer4(t4[6], R.zlo * 0.5f, S.A5[0]);
+            t5[1] = outer4(t4[6], R.zhi * 0.5f, S.A5[1]);
 #pragma unroll
             for (int g5 = 0; g5 < 2; ++g5)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    S.A6[(g5 * 4 + r) * 2 + 0] = outer4(R.zlo[1], t5[g5][r], S.A6[(g5 * 4 + r) * 2 + 0]);
-                    S.A6[(g5 * 4 + r) * 2 + 1] = outer4(R.zhi[1], t5[g5][r], S.A6[(g5 * 4 + r) * 2 + 1]);
+                    S.A6[(g5 * 4 + r) * 2 + 0] = outer4(R.zlo, t5[g5][r], S.A6[(g5 * 4 + r) * 2 + 0]);
+                    S.A6[(g5 * 4 + r) * 2 + 1] = outer4(R.zhi, t5[g5][r], S.A6[(g5 * 4 + r) * 2 + 1]);
                 }
-            S.A5[0] = outer4(t4[5], R.zlo[1], S.A5[0]);
-            S.A5[1] = outer4(t4[5], R.zhi[1], S.A5[1]);
+            S.A5[0] = outer4(t4[5], R.zlo, S.A5[0]);
+            S.A5[1] = outer4(t4[5], R.zhi, S.A5[1]);
         } else {
-            S.A5[0] = outer4(R.zlo[1], t4[5], S.A5[0]);  // top level: operands swapped
-            S.A5[1] = outer4(R.zhi[1], t4[5], S.A5[1]);
+            S.A5[0] = outer4(R.zlo, t4[5], S.A5[0]);  // top level: operands swapped
+            S.A5[1] = outer4(R.zhi, t4[5], S.A5[1]);
         }
     }
     S.A4 = t4[4];
-    S.A3 = t3[3];
-    S.A2 = t2[2];
-    S.A1 += R.zf1;
 }
 
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
@@ -126,7 +151,7 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
                          int basepoint, const float *__restrict__ bpv, int chunks, int64_t chunk_len)
 {
     static_assert(N >= 4 && N <= 6, "depths served by this kernel");
-    constexpr int kRow = kD8;  // floats per staged increment
+    constexpr int kRow = kRow8<N>;
     constexpr int kS = level_off8(N + 1);
     __shared__ __align__(16) float lds[kTile8 * kRow];
 
@@ -138,17 +163,35 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
     const int64_t n_inc = cv.n;
     const f4 *x4 = reinterpret_cast<const f4 *>(path) + cv.path * L * 2;  // 2 pieces of 16 bytes per point
     float *o = out + b * kS;
+    const f4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
 
     State8<N> S;
-    S.A5[0] = S.A5[1] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+    S.A5[0] = S.A5[1] = zero4;
 #pragma unroll
-    for (int g = 0; g < (N >= 6 ? 16 : 1); ++g) S.A6[g] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+    for (int g = 0; g < (N >= 6 ? 16 : 1); ++g) S.A6[g] = zero4;
 
-    // the two points around increment number s (zeros past the end of the path); the points of a
+    // the point the scan starts from: the chunk's first point, or the basepoint (the origin unless given)
+    f4 base0 = zero4, base1 = zero4;
+    if (bpv != nullptr) {
+        base0 = reinterpret_cast<const f4 *>(bpv)[cv.path * 2];
+        base1 = reinterpret_cast<const f4 *>(bpv)[cv.path * 2 + 1];
+    }
+    const int64_t i_first = basepoint ? cv.inc0 - 1 : cv.inc0;
+    float x_first = 0.0f, x_last = 0.0f;   // coordinate f_1 of the first and last point of the scan
+    if (n_inc > 0) {
+        x_first = i_first >= 0 ? pick8(x4[i_first * 2], x4[i_first * 2 + 1], f1) : pick8(base0, base1, f1);
+        x_last = pick8(x4[(i_first + n_inc) * 2], x4[(i_first + n_inc) * 2 + 1], f1);
+    }
+    float A2 = 0.0f;   // A_2[f] before the current tile
+    float A3[kD8];     // A_3[f w], w = 0..7, before the current tile
+#pragma unroll
+    for (int w = 0; w < kD8; ++w) A3[w] = 0.0f;
+
+    // the two points around increment number s (zeros past the end of the scan); the points of a
     // tile are fetched while the tile before it is being scanned
     f4 hi0, hi1, lo0, lo1;
     auto fetch_points = [&](int64_t s) {
-        hi0 = hi1 = lo0 = lo1 = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+        hi0 = hi1 = lo0 = lo1 = zero4;
         if (s < n_inc) {
             const int64_t i_hi = cv.inc0 + (basepoint ? s : s + 1);
             hi0 = x4[i_hi * 2];
@@ -156,9 +199,9 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
             if (i_hi > 0) {
                 lo0 = x4[(i_hi - 1) * 2];
                 lo1 = x4[(i_hi - 1) * 2 + 1];
-            } else if (bpv != nullptr) {
-                lo0 = reinterpret_cast<const f4 *>(bpv)[cv.path * 2];
-                lo1 = reinterpret_cast<const f4 *>(bpv)[cv.path * 2 + 1];
+            } else {
+                lo0 = base0;
+                lo1 = base1;
             }
         }
     };
@@ -167,11 +210,40 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
     for (int64_t t0 = 0; t0 < n_inc; t0 += kTile8) {
         const int nt = int(n_inc - t0 < kTile8 ? n_inc - t0 : kTile8);
         __syncthreads();
-        if (lane < nt) {
+        {
+            // lane r stages increment t0 + r; lanes past the end of the scan carry zero increments, which add
+            // nothing to the running sums
             const f4 z0 = hi0 - lo0, z1 = hi1 - lo1;
-            f4 *row = reinterpret_cast<f4 *>(lds + lane * kRow);
-            row[0] = z0;
-            row[1] = z1;
+            const float zf1 = pick8(z0, z1, f1), zf2 = pick8(z0, z1, f2);
+            const float a1 = lane < nt ? pick8(lo0, lo1, f1) - x_first : 0.0f;   // A_1[f_1] before this increment
+            float t1[N + 1], t2[N + 1];
+#pragma unroll
+            for (int k = 2; k <= N; ++k) t1[k] = __builtin_fmaf(zf1, 1.0f / k, a1);
+            float sum2;
+            const float a2 = A2 + wave_exclusive_scan(t1[2] * zf2, lane, sum2);
+            A2 += sum2;
+#pragma unroll
+            for (int k = 3; k <= N; ++k) t2[k] = __builtin_fmaf(t1[k], zf2 * (1.0f / (k - 1)), a2);
+            f4 tab[N + 1][2];   // T_k^(3)[w], k = 4..N
+#pragma unroll
+            for (int w = 0; w < kD8; ++w) {
+                const float zw = w < 4 ? z0[w & 3] : z1[w & 3];
+                float sum3;
+                const float a3 = A3[w] + wave_exclusive_scan(t2[3] * zw, lane, sum3);
+                A3[w] += sum3;
+#pragma unroll
+                for (int k = 4; k <= N; ++k) tab[k][w >> 2][w & 3] = __builtin_fmaf(t2[k], zw * (1.0f / (k - 2)), a3);
+            }
+            if (lane < nt) {
+                f4 *row = reinterpret_cast<f4 *>(lds + lane * kRow);
+                row[0] = z0;
+                row[1] = z1;
+#pragma unroll
+                for (int k = 4; k <= N; ++k) {
+                    row[2 * (k - 3)] = tab[k][0];
+                    row[2 * (k - 3) + 1] = tab[k][1];
+                }
+            }
         }
         __syncthreads();
         fetch_points(t0 + kTile8 + lane);
@@ -179,18 +251,22 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
         for (; s + 4 <= nt; s += 4) {
             Row8<N> R[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) R[i] = load_row8<N>(lds + (s + i) * kRow, f1, f2, w3, w4, q);
+            for (int i = 0; i < 4; ++i) R[i] = load_row8<N>(lds + (s + i) * kRow, w3, w4, q);
 #pragma unroll
             for (int i = 0; i < 4; ++i) step8<N>(S, R[i]);
         }
-        for (; s < nt; ++s) step8<N>(S, load_row8<N>(lds + s * kRow, f1, f2, w3, w4, q));
+        for (; s < nt; ++s) step8<N>(S, load_row8<N>(lds + s * kRow, w3, w4, q));
     }
+    // this lane's A_3[f w_3]
+    float a3_mine = A3[0];
+#pragma unroll
+    for (int w = 1; w < kD8; ++w) a3_mine = w3 == w ? A3[w] : a3_mine;
 
     // store this shard's slice of every level
     const int f = f1 * 8 + f2;
-    if (f2 == 0 && lane == 0) o[f1] = S.A1;
-    if (lane == 0) o[level_off8(2) + f] = S.A2;
-    if (w4 == 0) o[level_off8(3) + f * 8 + w3] = S.A3;
+    if (f2 == 0 && lane == 0) o[f1] = x_last - x_first;   // level 1 is the total displacement
+    if (lane == 0) o[level_off8(2) + f] = A2;
+    if (w4 == 0) o[level_off8(3) + f * 8 + w3] = a3_mine;
     o[level_off8(4) + f * 64 + lane] = S.A4;
     if constexpr (N == 5) {
         // register r, lane (block, q) of group g: word 8*(lane/4 * 4 + q) + 4*g + r of the 512-word slice
