@@ -190,8 +190,23 @@ sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out
 
     const int lane = threadIdx.x;
     const int w2 = lane >> 4, w3 = (lane >> 2) & 3, q = lane & 3;
-    const int64_t b = blockIdx.x >> 2;   // output row: a path, or one chunk of a path
-    const int f = blockIdx.x & 3;
+    // Workgroups are handed to the chip's 8 XCDs (each with its own L2) round-robin by number.  The four shards
+    // of a path write interleaved pieces of the same output rows, pieces that do not end on cache-line boundaries,
+    // so they are kept on one XCD, where the L2 merges them into whole lines: inside every run of 32 workgroups
+    // (8 paths x 4 shards) the XCD number picks the path and the rest picks the shard.
+    int64_t b;   // output row: a path, or one chunk of a path
+    int f;       // first letter
+    {
+        const unsigned id = blockIdx.x, full = gridDim.x & ~31u;
+        if (id < full) {
+            const unsigned slot = id >> 3;
+            b = int64_t(slot >> 2) * 8 + (id & 7);
+            f = int(slot & 3);
+        } else {
+            b = id >> 2;
+            f = int(id & 3);
+        }
+    }
     const ChunkView cv = chunk_view(b, chunks, chunk_len, n_inc_total);
     const int64_t n_inc = cv.n;
     const f4 *x4 = reinterpret_cast<const f4 *>(path) + cv.path * L;  // point l of this path
