@@ -5,9 +5,9 @@
 // c_m = (-1)^{m+1} / m, evaluated by Horner's rule from the inside out:
 //     R_N = c_N x,   R_m = c_m x + x [x] R_{m+1},   log = R_1.
 // R_m is needed at levels 1..N-m+1 only (a product of m or more factors has no lower levels to feed), so
-// the top level is computed once.  A product x [x] R reads strictly lower levels of R, so R lives in `out`
-// and is updated in place, levels highest first, with a workgroup barrier between levels; one workgroup
-// per signature.
+// the top level is computed once.  A product x [x] R reads strictly lower levels of R, so R is updated in
+// place, levels highest first, with a workgroup barrier between levels; one workgroup per signature, with
+// the signature and R in LDS when they fit (else in global memory, R in `out`).
 //
 // logsignature: psi(log(Sig)) is the vector of coefficients of the Lyndon words (appendix A.2.4): a gather
 // with an index table that `sig_lyndon_indices` computes on the host.
@@ -18,19 +18,37 @@
 namespace sig {
 namespace {
 
-template <typename T>
+// kLds: the signature and R are kept in LDS (2 S scalars) and R is copied out at the end; otherwise both stay in
+// global memory (R in `out`).
+// D: the channel count when it is one of the common ones (the letters of a word are then peeled off with
+// divisions by a constant), 0 for any other d.
+template <typename T, bool kLds, int D>
 __global__ void __launch_bounds__(256)
 sig_log_kernel(Shape sh, const T *__restrict__ in, T *__restrict__ out)
 {
-    const uint32_t d = uint32_t(sh.d);
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    __shared__ uint32_t off[SIG_MAX_DEPTH + 2];   // level offsets: indexed by loop variables, so not left in the kernel arguments
+    const uint32_t d = D > 0 ? uint32_t(D) : uint32_t(sh.d);
     const int N = sh.N;
+    if (threadIdx.x <= unsigned(N) + 1) off[threadIdx.x] = uint32_t(sh.off[threadIdx.x]);
+    __syncthreads();
     for (int64_t r = blockIdx.x; r < sh.B; r += gridDim.x) {
-        const T *x = in + r * sh.S;
-        T *R = out + r * sh.S;
+        const T *x;
+        T *R;
+        if constexpr (kLds) {
+            T *xs = reinterpret_cast<T *>(smem_raw);
+            for (uint32_t i = threadIdx.x; i < uint32_t(sh.S); i += blockDim.x) xs[i] = in[r * sh.S + i];
+            x = xs;
+            R = xs + sh.S;
+            __syncthreads();
+        } else {
+            x = in + r * sh.S;
+            R = out + r * sh.S;
+        }
         for (int m = N; m >= 1; --m) {
             const T c = (m & 1 ? T(1) : T(-1)) / T(m);
             for (int k = N - m + 1; k >= 1; --k) {
-                const uint32_t n_k = uint32_t(sh.pw[k]), off_k = uint32_t(sh.off[k]);
+                const uint32_t off_k = off[k], n_k = off[k + 1] - off_k;
                 for (uint32_t idx = threadIdx.x; idx < n_k; idx += blockDim.x) {
                     T acc = c * x[off_k + idx];
                     // splits of the word into a prefix of x (j letters) and a suffix of R (k - j letters)
@@ -40,14 +58,87 @@ sig_log_kernel(Shape sh, const T *__restrict__ in, T *__restrict__ out)
                         prefix /= d;
                         suffix += letter * scale;
                         scale *= d;
-                        acc += x[uint32_t(sh.off[j]) + prefix] * R[uint32_t(sh.off[k - j]) + suffix];
+                        acc += x[off[j] + prefix] * R[off[k - j] + suffix];
                     }
                     R[off_k + idx] = acc;
                 }
                 __syncthreads();
             }
         }
+        if constexpr (kLds) {
+            for (uint32_t i = threadIdx.x; i < uint32_t(sh.S); i += blockDim.x) out[r * sh.S + i] = R[i];
+            __syncthreads();
+        }
     }
+}
+
+__host__ __device__ constexpr uint32_t fixed_off(int d, int k)   // offset of level k (1-based) for d channels
+{
+    uint32_t off = 0, p = 1;
+    for (int j = 1; j < k; ++j) {
+        p *= uint32_t(d);
+        off += p;
+    }
+    return off;
+}
+
+// The same computation for a channel count and depth known at compile time, signature and R in LDS: every loop
+// over passes, levels and splits is unrolled, so the offsets are constants, the letters come off with shifts or
+// multiplications, and the operands of all splits of a word are fetched before any of them is used (the generic
+// kernel above waits for two LDS round trips per split).
+template <typename T, int D, int N>
+__global__ void __launch_bounds__(256)
+sig_log_fixed_kernel(int64_t rows, const T *__restrict__ in, T *__restrict__ out)
+{
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    constexpr uint32_t S = fixed_off(D, N + 1);
+    T *x = reinterpret_cast<T *>(smem_raw);
+    T *R = x + S;
+    for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
+        for (uint32_t i = threadIdx.x; i < S; i += 256) x[i] = in[r * S + i];
+        __syncthreads();
+#pragma unroll
+        for (int m = N; m >= 1; --m) {
+            const T c = (m & 1 ? T(1) : T(-1)) / T(m);
+#pragma unroll
+            for (int k = N - m + 1; k >= 1; --k) {
+                const uint32_t off_k = fixed_off(D, k), n_k = fixed_off(D, k + 1) - off_k;
+                for (uint32_t idx = threadIdx.x; idx < n_k; idx += 256) {
+                    T xv[N], rv[N];
+                    uint32_t prefix = idx, suffix = 0, scale = 1;
+#pragma unroll
+                    for (int j = k - 1; j >= 1; --j) {
+                        const uint32_t letter = prefix % uint32_t(D);
+                        prefix /= uint32_t(D);
+                        suffix += letter * scale;
+                        scale *= uint32_t(D);
+                        xv[j] = x[fixed_off(D, j) + prefix];
+                        rv[j] = R[fixed_off(D, k - j) + suffix];
+                    }
+                    T acc = c * x[off_k + idx];
+#pragma unroll
+                    for (int j = k - 1; j >= 1; --j) acc += xv[j] * rv[j];
+                    R[off_k + idx] = acc;
+                }
+                __syncthreads();
+            }
+        }
+        for (uint32_t i = threadIdx.x; i < S; i += 256) out[r * S + i] = R[i];
+        __syncthreads();
+    }
+}
+
+template <typename T, int D, int N>
+bool try_fixed(const Shape &sh, const T *in, T *out, unsigned grid, hipStream_t st)
+{
+    constexpr size_t lds = 2 * size_t(fixed_off(D, N + 1)) * sizeof(T);
+    if constexpr (lds <= 64 * 1024) {
+        if (sh.d == D && sh.N == N) {
+            hipLaunchKernelGGL((sig_log_fixed_kernel<T, D, N>), dim3(grid), dim3(256), lds, st, sh.B, in, out);
+            return true;
+        }
+    }
+    return false;
 }
 
 template <typename T>
@@ -64,7 +155,28 @@ template <typename T>
 hipError_t launch_log(const Shape &sh, const T *in, T *out, hipStream_t st)
 {
     const unsigned grid = unsigned(sh.B < (int64_t(1) << 20) ? sh.B : (int64_t(1) << 20));
-    hipLaunchKernelGGL((sig_log_kernel<T>), dim3(grid), dim3(256), 0, st, sh, in, out);
+    if (try_fixed<T, 2, 2>(sh, in, out, grid, st) || try_fixed<T, 2, 3>(sh, in, out, grid, st) ||
+        try_fixed<T, 2, 4>(sh, in, out, grid, st) || try_fixed<T, 2, 5>(sh, in, out, grid, st) ||
+        try_fixed<T, 2, 6>(sh, in, out, grid, st) || try_fixed<T, 2, 7>(sh, in, out, grid, st) ||
+        try_fixed<T, 3, 2>(sh, in, out, grid, st) || try_fixed<T, 3, 3>(sh, in, out, grid, st) ||
+        try_fixed<T, 3, 4>(sh, in, out, grid, st) || try_fixed<T, 3, 5>(sh, in, out, grid, st) ||
+        try_fixed<T, 3, 6>(sh, in, out, grid, st) || try_fixed<T, 4, 2>(sh, in, out, grid, st) ||
+        try_fixed<T, 4, 3>(sh, in, out, grid, st) || try_fixed<T, 4, 4>(sh, in, out, grid, st) ||
+        try_fixed<T, 4, 5>(sh, in, out, grid, st) || try_fixed<T, 4, 6>(sh, in, out, grid, st) ||
+        try_fixed<T, 8, 2>(sh, in, out, grid, st) || try_fixed<T, 8, 3>(sh, in, out, grid, st) ||
+        try_fixed<T, 8, 4>(sh, in, out, grid, st))
+        return hipGetLastError();
+    const size_t lds = 2 * size_t(sh.S) * sizeof(T);
+    const bool in_lds = lds <= 64 * 1024;
+#define SIG_LOG_LAUNCH(DD)                                                                                        \
+    do {                                                                                                          \
+        if (in_lds)                                                                                               \
+            hipLaunchKernelGGL((sig_log_kernel<T, true, DD>), dim3(grid), dim3(256), lds, st, sh, in, out);       \
+        else                                                                                                      \
+            hipLaunchKernelGGL((sig_log_kernel<T, false, DD>), dim3(grid), dim3(256), 0, st, sh, in, out);        \
+    } while (0)
+    SIG_LOG_LAUNCH(0);
+#undef SIG_LOG_LAUNCH
     return hipGetLastError();
 }
 
