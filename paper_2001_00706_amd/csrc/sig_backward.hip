@@ -238,7 +238,9 @@ bool make_plan(const Shape &sh, int threads, BackwardPlan &pl)
     return true;
 }
 
-int backward_threads(const Shape &sh) { return sh.B >= (1 << 30) ? 64 : 256; }
+// Threads per workgroup.  (A single wavefront per path, which needs no hardware barriers, was measured too: twice
+// as slow on 1024 paths of d = 4, N = 6, since nothing hides the LDS latency of the one wavefront.)
+constexpr int kBackwardThreads = 256;
 
 // Most dynamic LDS one workgroup may have on this device (0 if the query fails).
 size_t lds_limit()
@@ -286,11 +288,8 @@ hipError_t launch_backward(const Shape &sh, const T *path, const T *sig, const T
                            void *workspace, int64_t workspace_bytes, hipStream_t st)
 {
     BackwardPlan pl;
-    const int threads = backward_threads(sh);
-    if (!backward_supported(sh) || !make_plan(sh, threads, pl)) return hipErrorNotSupported;
-    return threads == 64
-               ? launch_backward_nt<T, 64>(sh, pl, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st)
-               : launch_backward_nt<T, 256>(sh, pl, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
+    if (!backward_supported(sh) || !make_plan(sh, kBackwardThreads, pl)) return hipErrorNotSupported;
+    return launch_backward_nt<T, kBackwardThreads>(sh, pl, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
 }
 
 }  // namespace
@@ -298,14 +297,14 @@ hipError_t launch_backward(const Shape &sh, const T *path, const T *sig, const T
 bool backward_supported(const Shape &sh)
 {
     BackwardPlan pl;
-    // a thread keeps one letter in the per-letter sums, so d may not exceed the smallest workgroup
-    return sh.d <= 64 && make_plan(sh, backward_threads(sh), pl);
+    // a thread keeps one letter in the per-letter sums; the limit leaves room for a one-wavefront workgroup
+    return sh.d <= 64 && make_plan(sh, kBackwardThreads, pl);
 }
 
 int64_t backward_workspace_bytes(const Shape &sh, sig_dtype dtype)
 {
     BackwardPlan pl;
-    if (!backward_supported(sh) || !make_plan(sh, backward_threads(sh), pl)) return -1;
+    if (!backward_supported(sh) || !make_plan(sh, kBackwardThreads, pl)) return -1;
     const bool lds = dtype == SIG_F32 ? fits_lds<float>(pl) : fits_lds<double>(pl);
     if (lds) return 0;
     const int64_t grid = sh.B < kBackwardMaxGrid ? sh.B : kBackwardMaxGrid;

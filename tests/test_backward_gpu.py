@@ -84,8 +84,7 @@ def test_register_resident_kernels_every_depth(d, N):
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
-def test_one_wavefront_per_path_launch(dtype):
-    # B >= 512 selects 64-thread workgroups
+def test_more_paths_than_compute_units(dtype):
     x = brownian_paths(515, 9, 3, seed=77).astype(dtype)
     check(x, 4, sample=[0, 1, 100, 513, 514])
     check(x, 3, stream=True, basepoint=True, sample=[0, 255, 514])

@@ -135,7 +135,7 @@ def test_backward_validation(lib):
     for name in ("path", "sig", "gout", "gpath"):
         assert f(*args(**{name: 0})) == sig.SIG_ERR_INVALID_ARG
     assert f(*args(d=1024, N=5)) == sig.SIG_ERR_OVERFLOW
-    assert f(*args(d=65, N=1)) == sig.SIG_ERR_UNSUPPORTED          # more channels than the smallest workgroup has threads
+    assert f(*args(d=65, N=1)) == sig.SIG_ERR_UNSUPPORTED          # more than 64 channels
     assert f(*args(d=2, N=31)) == sig.SIG_ERR_UNSUPPORTED          # 2^32 scalars per signature
     assert f(*args(B=0, path=0, sig=0, gout=0, gpath=0)) == sig.SIG_OK
     # a basepoint value or its gradient without the basepoint flag
