@@ -11,9 +11,9 @@
 // word with no communication at all.  "Down", the chains D^(k)_i contracted with the increment, needs
 // sums over the 4 threads of a quad (level 4 -> 3), the 4 quads of a 16-lane row (3 -> 2) and the 4 rows
 // of a wavefront (2 -> 1): lane permutes inside a wavefront, no LDS, no barrier; wavefronts (first
-// letters) never exchange anything.  The only workgroup-wide step is the sum of the increment's gradient
-// over the four wavefronts: one barrier per increment.  Redundant holders weigh their contribution to
-// that sum by 1/4, 1/16, 1/64 (exact in binary).
+// letters) never exchange anything.  The only workgroup-wide step is the sum of the increments' gradients
+// over the four wavefronts, done once per tile of 64 increments from partial sums left in LDS.  Redundant
+// holders weigh their contribution to that sum by 1/4, 1/16, 1/64 (exact in binary).
 //
 // Stream mode reads the earlier signature from the forward output instead of undoing the increment, and
 // adds the output gradient of every entry on the way; both are fetched one increment ahead.
@@ -64,7 +64,9 @@ sig_backward_d4_kernel(const float *__restrict__ path, const float *__restrict__
     constexpr float rk[7] = {0.0f, 1.0f, r2, r3, r4, r5, r6};
 
     __shared__ __align__(16) float zt[kTileB * 4];   // the increments of the current tile
-    __shared__ float part[2][4][4];                  // [parity of the step][wavefront][letter]
+    __shared__ float part[kTileB][4][4];             // [increment of the tile][wavefront][letter]: partial gradients
+    __shared__ float dzs[kTileB][4];                 // gradients of the tile's increments
+    __shared__ float dz_after[4];                    // gradient of the increment that follows the tile's last one
 
     const int t = threadIdx.x;
     const int wave = t >> 6;
@@ -110,7 +112,7 @@ sig_backward_d4_kernel(const float *__restrict__ path, const float *__restrict__
     Share nextA = {}, nextG = {};   // stream mode: signature before, and output gradient of, the step to come
     if constexpr (!STREAM) A = load_share(sg, false);
 
-    float dz_prev = 0.0f;   // threads 0..3: gradient of the increment after the current one, component t
+    if (t < 4) dz_after[t] = 0.0f;   // no increment follows the last one
 
     for (int64_t t0 = ((n_inc - 1) / kTileB) * kTileB; t0 >= 0; t0 -= kTileB) {
         const int nt = int(n_inc - t0 < kTileB ? n_inc - t0 : kTileB);
@@ -287,16 +289,8 @@ sig_backward_d4_kernel(const float *__restrict__ path, const float *__restrict__
             const f4 tr = quad_transpose(dz, t & 63);
             float mine = (tr[0] + tr[1]) + (tr[2] + tr[3]);
             mine = wave_sum_of_rows(row_sum_of_quads(mine));   // over the 16 quads: lanes 0..3 hold letters 0..3
-            const int parity = int(s & 1);
-            if ((t & 63) < 4) part[parity][wave][t & 3] = mine;
-            __syncthreads();
-            if (t < 4) {
-                const float sum = (part[parity][0][t] + part[parity][1][t]) + (part[parity][2][t] + part[parity][3][t]);
-                // the point above this increment ends it and starts the next one
-                const int64_t point = basepoint ? s : s + 1;
-                gp[point * 4 + t] = sum - dz_prev;
-                dz_prev = sum;
-            }
+            // the four wavefronts never wait for one another inside a tile: each leaves its partial sums in LDS
+            if ((t & 63) < 4) part[i][wave][t & 3] = mine;
 
             if constexpr (STREAM) {
                 if (s > 0) {
@@ -310,10 +304,30 @@ sig_backward_d4_kernel(const float *__restrict__ path, const float *__restrict__
                 }
             }
         }
+
+        // the tile's gradients: sum over the wavefronts, then every point of the tile gets the gradient of the
+        // increment it ends minus that of the increment it starts
+        __syncthreads();
+        if (t < nt * 4) {
+            const int i = t >> 2, c = t & 3;
+            dzs[i][c] = (part[i][0][c] + part[i][1][c]) + (part[i][2][c] + part[i][3][c]);
+        }
+        __syncthreads();
+        float first = 0.0f;
+        if (t < nt * 4) {
+            const int i = t >> 2, c = t & 3;
+            const int64_t point = (basepoint ? t0 : t0 + 1) + i;
+            gp[point * 4 + c] = dzs[i][c] - (i + 1 < nt ? dzs[i + 1][c] : dz_after[c]);
+            if (i == 0) first = dzs[0][c];
+        }
+        __syncthreads();
+        if (t < 4) dz_after[t] = first;   // this tile's first increment follows the last one of the tile before it
     }
+    __syncthreads();
     if (t < 4) {
-        if (!basepoint) gp[t] = -dz_prev;                                 // the first point only starts increment 0
-        else if (gbase != nullptr) gbase[b * 4 + t] = -dz_prev;           // and so does a basepoint
+        // dz_after now holds the gradient of increment 0
+        if (!basepoint) gp[t] = -dz_after[t];                             // the first point only starts increment 0
+        else if (gbase != nullptr) gbase[b * 4 + t] = -dz_after[t];       // and so does a basepoint
     }
 }
 

@@ -8,8 +8,8 @@
 // threads below an ancestor carry the same value), and the up to two levels below its word as small arrays.
 // "Up" (undo the increment, Horner terms T^(k)_i) is a scalar chain along the thread's word.  "Down" sums
 // the chains D^(k)_i over the d siblings of each level with lane exchanges inside the wavefront; the only
-// workgroup-wide step is the sum of the increment's gradient, one barrier per increment.  See
-// sig_backward.hip for the recurrences.
+// workgroup-wide step is the sum of the increments' gradients over the wavefronts, once per tile of 64
+// increments.  See sig_backward.hip for the recurrences.
 #include "sig_internal.h"
 #include "sig_mfma_common.h"
 
@@ -137,7 +137,9 @@ sig_backward_pow2_kernel(const float *__restrict__ path, const float *__restrict
     constexpr bool kPrefetch = H1 + H2 <= 24;
 
     __shared__ __align__(16) float zt[kTileP * D];   // the increments of the current tile
-    __shared__ float part[2][NW][D];                 // [parity of the step][wavefront][letter]
+    __shared__ float part[kTileP][NW][D];            // [increment of the tile][wavefront][letter]: partial gradients
+    __shared__ float dzs[kTileP][D];                 // gradients of the tile's increments
+    __shared__ float dz_after[D];                    // gradient of the increment that follows the tile's last one
 
     const int tl = threadIdx.x;
     const bool active = tl < NT;
@@ -192,7 +194,7 @@ sig_backward_pow2_kernel(const float *__restrict__ path, const float *__restrict
     Share A = {}, nextA = {}, nextG = {};
     if constexpr (!STREAM) A = load_share(sg, U >= 2, false);
 
-    float dz_prev = 0.0f;   // threads 0..D-1: gradient of the increment after the current one, component tl
+    if (tl < D) dz_after[tl] = 0.0f;   // no increment follows the last one
 
     for (int64_t t0 = ((n_inc - 1) / kTileP) * kTileP; t0 >= 0; t0 -= kTileP) {
         const int nt = int(n_inc - t0 < kTileP ? n_inc - t0 : kTileP);
@@ -312,21 +314,12 @@ sig_backward_pow2_kernel(const float *__restrict__ path, const float *__restrict
             // levels P .. 1, one scalar per thread and chain; level j is shared by the D^(P-j) threads below it
             ScalarLevels<D, N, PS::P>::run(G.lo, T, Dc, dz, zc, cl, rk);
 
-            // ---- the increment's gradient: sum over the wavefront, then over the wavefronts
-            const int parity = int(s & 1);
+            // ---- the increment's gradient: sum over the wavefront; the wavefronts leave their partial sums in
+            // LDS and do not wait for one another inside a tile
 #pragma unroll
             for (int c = 0; c < D; ++c) {
                 const float total = group_sum<0, 6>(active ? dz[c] : 0.0f);
-                if ((tl & 63) == 0) part[parity][wave][c] = total;
-            }
-            __syncthreads();
-            if (tl < D) {
-                float sum = 0.0f;
-#pragma unroll
-                for (int w = 0; w < NW; ++w) sum += part[parity][w][tl];
-                const int64_t point = basepoint ? s : s + 1;   // ends this increment, starts the next one
-                gp[point * D + tl] = sum - dz_prev;
-                dz_prev = sum;
+                if ((tl & 63) == 0) part[i][wave][c] = total;
             }
 
             if constexpr (STREAM) {
@@ -345,10 +338,31 @@ sig_backward_pow2_kernel(const float *__restrict__ path, const float *__restrict
                 }
             }
         }
+
+        // the tile's gradients: sum over the wavefronts, then every point of the tile gets the gradient of the
+        // increment it ends minus that of the increment it starts
+        __syncthreads();
+        for (int e = tl; e < nt * D; e += PS::NTL) {
+            const int i = e / D, c = e % D;
+            float sum = 0.0f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) sum += part[i][w][c];
+            dzs[i][c] = sum;
+        }
+        __syncthreads();
+        for (int e = tl; e < nt * D; e += PS::NTL) {
+            const int i = e / D, c = e % D;
+            const int64_t point = (basepoint ? t0 : t0 + 1) + i;
+            gp[point * D + c] = dzs[i][c] - (i + 1 < nt ? dzs[i + 1][c] : dz_after[c]);
+        }
+        __syncthreads();
+        if (tl < D) dz_after[tl] = dzs[0][tl];   // this tile's first increment follows the last one of the tile before it
     }
+    __syncthreads();
     if (tl < D) {
-        if (!basepoint) gp[tl] = -dz_prev;                                // the first point only starts increment 0
-        else if (gbase != nullptr) gbase[b * D + tl] = -dz_prev;          // and so does a basepoint
+        // dz_after now holds the gradient of increment 0
+        if (!basepoint) gp[tl] = -dz_after[tl];                           // the first point only starts increment 0
+        else if (gbase != nullptr) gbase[b * D + tl] = -dz_after[tl];     // and so does a basepoint
     }
 }
 
