@@ -55,7 +55,7 @@ sig_status make_shape(int64_t B, int64_t L, int d, int N, int stream, int basepo
     return SIG_OK;
 }
 
-enum class Family { Generic, Mfma, MfmaShard, MfmaD16, MfmaD8, Small, None };
+enum class Family { Generic, Mfma, MfmaShard, MfmaD16, MfmaD8, Small, Tree, None };
 
 // The pointers decide only alignment: the matrix-core family loads and stores 16 bytes per lane.
 Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const void *path, const void *out)
@@ -68,6 +68,7 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
     const bool d8_ok = dtype == SIG_F32 && aligned && sig::mfma_d8_kernel_name(sh) != nullptr;
     const bool generic_ok = sig::generic_supported(sh, dtype);
     const bool small_ok = sig::small_supported(sh);
+    const bool tree_ok = dtype == SIG_F32 && sig::tree_supported(sh);
     switch (variant) {
         case SIG_VARIANT_AUTO:
             // four wavefronts per path when one per path would leave most of the chip idle, when every
@@ -77,12 +78,14 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
             if (d16_ok) return Family::MfmaD16;
             if (d8_ok) return Family::MfmaD8;
             if (small_ok) return Family::Small;
+            if (tree_ok) return Family::Tree;
             return generic_ok ? Family::Generic : Family::None;
         case SIG_VARIANT_GENERIC: return generic_ok ? Family::Generic : Family::None;
         case SIG_VARIANT_MFMA:
             return mfma_ok ? Family::Mfma : d16_ok ? Family::MfmaD16 : d8_ok ? Family::MfmaD8 : Family::None;
         case SIG_VARIANT_MFMA_SHARD: return shard_ok ? Family::MfmaShard : Family::None;
         case SIG_VARIANT_SMALL: return small_ok ? Family::Small : Family::None;
+        case SIG_VARIANT_TREE: return tree_ok ? Family::Tree : Family::None;
     }
     return Family::None;
 }
@@ -100,6 +103,8 @@ hipError_t launch_family(Family family, const sig::Shape &sh, sig_dtype dtype, c
             return sig::launch_mfma_d16_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
         case Family::MfmaD8:
             return sig::launch_mfma_d8_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
+        case Family::Tree:
+            return sig::launch_tree_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
         case Family::Small:
             return dtype == SIG_F32
                        ? sig::launch_small_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
@@ -117,7 +122,7 @@ bool valid_enums(sig_dtype dtype, sig_variant variant)
 {
     return (dtype == SIG_F32 || dtype == SIG_F64) &&
            (variant == SIG_VARIANT_AUTO || variant == SIG_VARIANT_GENERIC || variant == SIG_VARIANT_MFMA ||
-            variant == SIG_VARIANT_MFMA_SHARD || variant == SIG_VARIANT_SMALL);
+            variant == SIG_VARIANT_MFMA_SHARD || variant == SIG_VARIANT_SMALL || variant == SIG_VARIANT_TREE);
 }
 
 }  // namespace
@@ -447,6 +452,7 @@ const char *sig_variant_name(int64_t B, int64_t L, int d, int N, int stream, int
         case Family::MfmaD16: return sig::mfma_d16_kernel_name(sh);
         case Family::MfmaD8: return sig::mfma_d8_kernel_name(sh);
         case Family::Small: return "small";
+        case Family::Tree: return "tree";
         case Family::Generic: return "generic";
         case Family::None: break;
     }

@@ -93,6 +93,11 @@ bool backward_pow2_supported(const Shape &sh);
 hipError_t launch_backward_pow2_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
                                     float *gbase, hipStream_t st);
 
+// Prefix-tree family (fp32, final mode, d = 2..8, N = 2..9): a thread per word of N-2 letters carries the word's
+// prefixes and the two levels below it; no communication, any number of workgroups per path.
+bool tree_supported(const Shape &sh);
+hipError_t launch_tree_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
+
 // Small-state family: S <= 512 scalars, one wavefront per path, state in LDS, words decoded once.
 bool small_supported(const Shape &sh);
 hipError_t launch_small_f32(const Shape &sh, const float *path, float *out, hipStream_t st);

@@ -73,8 +73,8 @@ def check(x, N, stream=False, basepoint=False, variant=sig.SIG_VARIANT_AUTO, sam
 
 
 VARIANTS = [sig.SIG_VARIANT_AUTO, sig.SIG_VARIANT_GENERIC, sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_SHARD,
-            sig.SIG_VARIANT_SMALL]
-VARIANT_IDS = ["auto", "generic", "mfma", "mfma_shard", "small"]
+            sig.SIG_VARIANT_SMALL, sig.SIG_VARIANT_TREE]
+VARIANT_IDS = ["auto", "generic", "mfma", "mfma_shard", "small", "tree"]
 
 
 # ------------------------------------------------------------------ benchmark workloads
@@ -425,3 +425,17 @@ def test_chunked_scan_argument_checks():
     assert need == 6 * 2 * 340 * 4
     with pytest.raises(sig.SigError):
         sig.sig_forward_chunked(x, 4, 4, workspace=torch.empty(need - 4, dtype=torch.uint8, device="cuda:0"))
+
+
+# ------------------------------------------------------------------ prefix-tree family
+@pytest.mark.parametrize("B,L,d,N", [
+    (3, 9, 7, 7),      # 16 807 words per path over 66 workgroups; 960 799 scalars per signature
+    (2, 20, 4, 9), (2, 12, 4, 8), (3, 15, 5, 7), (2, 10, 6, 7), (5, 40, 3, 7), (4, 70, 2, 9),
+    (37, 6, 3, 4),     # 9 words per path: 16 paths share a workgroup, the last workgroup is ragged
+    (5, 5, 8, 2), (3, 7, 6, 3), (1, 2, 2, 2),
+])
+def test_prefix_tree_family(B, L, d, N):
+    x = brownian_paths(B, L, d, seed=B + L + d + N)
+    for basepoint in (False, True):
+        assert check(x, N, basepoint=basepoint, variant=sig.SIG_VARIANT_TREE) is not None
+    assert sig.sig_variant_name(B, L, d, N, True, False, variant=sig.SIG_VARIANT_TREE) == "unsupported"
