@@ -24,10 +24,14 @@ def out_shape(B, L, d, N, stream, basepoint):
     return (B, n_inc, S) if stream else (B, S)
 
 
-def gpu_backward(x, g, N, stream, basepoint):
+def gpu_backward(x, g, N, stream, basepoint, misalign=False):
     import torch
     xt = torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
     gt = torch.from_numpy(np.ascontiguousarray(g)).to("cuda:0")
+    if misalign:   # an output gradient that starts 4 bytes off a 16-byte boundary: the vector-loading kernels step aside
+        holder = torch.empty(gt.numel() + 1, dtype=gt.dtype, device=gt.device)
+        holder[1:].copy_(gt.reshape(-1))
+        gt = holder[1:].view(gt.shape)
     st = sig.sig_forward(xt, N, stream=stream, basepoint=basepoint)
     gp = torch.full_like(xt, float("nan"))
     sig.sig_backward(xt, st, gt, N, stream=stream, basepoint=basepoint, grad_path=gp)
@@ -35,12 +39,12 @@ def gpu_backward(x, g, N, stream, basepoint):
     return gp.cpu().numpy()
 
 
-def check(x, N, stream=False, basepoint=False, sample=None, seed=0):
+def check(x, N, stream=False, basepoint=False, sample=None, seed=0, misalign=False):
     dt = x.dtype.type
     B, L, d = x.shape
     rng = np.random.default_rng(seed + 31 * L + d + N)
     g = rng.standard_normal(out_shape(B, L, d, N, stream, basepoint)).astype(dt)
-    got = gpu_backward(x, g, N, stream, basepoint)
+    got = gpu_backward(x, g, N, stream, basepoint, misalign)
     assert np.all(np.isfinite(got)), "gradient not fully written"
     idx = np.arange(B) if sample is None else np.asarray(sample)
     want = orc.signature_backward(x[idx], g[idx], N, stream, basepoint)
@@ -83,6 +87,30 @@ def test_register_resident_kernels_every_depth(d, N):
             check(x, N, stream=stream, basepoint=basepoint)
 
 
+@pytest.mark.parametrize("B,L,d,N", [
+    (2, 6, 7, 7),      # 16 807 threads per path over 66 workgroups, 960 799 scalars per signature
+    (2, 8, 4, 9), (2, 10, 4, 8), (2, 9, 4, 7), (3, 40, 3, 7), (2, 12, 5, 7), (2, 9, 6, 7), (2, 70, 5, 4),
+    (37, 6, 3, 4),     # 9 threads per path: 16 paths share a workgroup, the last workgroup is ragged
+    (5, 5, 7, 2), (3, 7, 6, 3), (4, 9, 3, 2),
+])
+def test_prefix_tree_kernels(B, L, d, N):
+    # fp32 shapes that neither the d = 4 nor the power-of-two register kernels serve
+    x = brownian_paths(B, L, d, seed=B + L + d + N)
+    for stream in (False, True):
+        if stream and d ** N > 100000:
+            continue   # the stream output of the largest shapes would only slow the oracle down
+        for basepoint in (False, True):
+            check(x, N, stream=stream, basepoint=basepoint)
+
+
+@pytest.mark.parametrize("d,N", [(2, 3), (2, 9), (4, 5), (4, 6), (8, 3), (8, 5)])
+def test_prefix_tree_kernels_on_unaligned_buffers(d, N):
+    # the same shapes the register kernels serve, pushed to the prefix-tree kernels by a misaligned buffer
+    x = brownian_paths(3, 40, d, seed=d + N)
+    for stream in (False, True):
+        check(x, N, stream=stream, basepoint=stream, misalign=True)
+
+
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 def test_more_paths_than_compute_units(dtype):
     x = brownian_paths(515, 9, 3, seed=77).astype(dtype)
@@ -92,8 +120,9 @@ def test_more_paths_than_compute_units(dtype):
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 def test_working_set_in_global_memory(dtype):
-    # d = 8, N = 5: 37 448 scalars per signature; the arena does not fit on chip and lives in the workspace
-    B, L, d, N = 3, 6, 8, 5
+    # d = 9, N = 5: 66 429 scalars per signature; the generic kernel's arena does not fit on chip and lives in the
+    # workspace
+    B, L, d, N = 3, 6, 9, 5
     dt = sig.SIG_F32 if dtype == np.float32 else sig.SIG_F64
     assert sig.sig_backward_workspace_bytes(B, L, d, N, False, False, dt) > 0
     x = brownian_paths(B, L, d, seed=5).astype(dtype)
@@ -103,7 +132,7 @@ def test_working_set_in_global_memory(dtype):
 
 def test_more_paths_than_persistent_workgroups_in_global_memory():
     # 1030 paths over 1024 workgroups: some workgroups scan two paths with the same arena
-    B, L, d, N = 1030, 3, 16, 4
+    B, L, d, N = 1030, 3, 16, 4   # the generic kernel (d > 8)
     assert sig.sig_backward_workspace_bytes(B, L, d, N, False, False, sig.SIG_F32) > 0
     x = brownian_paths(B, L, d, seed=6)
     check(x, N, sample=[0, 5, 1023, 1024, 1029])
@@ -118,7 +147,7 @@ def test_large_lds_arena_fp64_depth_six():
 
 def test_missing_or_short_workspace_is_refused():
     import torch
-    B, L, d, N = 2, 4, 8, 5
+    B, L, d, N = 2, 4, 9, 5
     need = sig.sig_backward_workspace_bytes(B, L, d, N, False, False, sig.SIG_F32)
     assert need > 0
     x = torch.zeros((B, L, d), device="cuda:0")
@@ -132,6 +161,18 @@ def test_missing_or_short_workspace_is_refused():
     out = sig.sig_backward(x, s, g, N, workspace=exact)
     torch.cuda.synchronize()
     assert torch.all(out == 0)
+
+
+def test_short_workspace_of_the_prefix_tree_kernels_is_refused():
+    import torch
+    B, L, d, N = 3, 12, 3, 5
+    need = sig.sig_backward_workspace_bytes(B, L, d, N, False, False, sig.SIG_F32)
+    assert need == B * 27 * (L - 1) * d * 4          # one partial sum per thread (27 three-letter words), increment, channel
+    x = torch.from_numpy(brownian_paths(B, L, d, seed=1)).to("cuda:0")
+    s = sig.sig_forward(x, N)
+    with pytest.raises(sig.SigError) as e:
+        sig.sig_backward(x, s, torch.ones_like(s), N, workspace=torch.empty(need - 4, dtype=torch.uint8, device="cuda:0"))
+    assert e.value.status == sig.SIG_ERR_INVALID_ARG
 
 
 def test_unsupported_and_invalid_arguments():
