@@ -128,6 +128,108 @@ sig_log_fixed_kernel(int64_t rows, const T *__restrict__ in, T *__restrict__ out
     }
 }
 
+// Depths up to 9 at any size, with no pass structure at all: one thread per word w of the result, which sums
+// the power series term by term,
+//     log(1 + x)[w] = sum_m c_m sum over the ways to cut w into m consecutive pieces of  prod x[piece],
+// by dynamic programming over the cuts: P_m[j] = sum_{i < j} P_{m-1}[i] x[w_{i+1}..w_j] is the sum over the cuts
+// of the first j letters into m pieces, P_0[0] = 1, and the result is sum_m c_m P_m[k].  A word of k letters
+// reads the k(k+1)/2 coefficients of its sub-words (neighbouring threads share all but k of them) and spends
+// about k^3/6 multiply-adds.  Nothing is written but the result, so signatures of any size spread over the
+// whole chip without synchronisation.
+constexpr int kDirectMaxDepth = 9;
+
+template <typename T, int D, int K>
+__device__ __forceinline__ T log_of_word(const T *__restrict__ x, uint32_t idx, uint32_t d, const uint32_t (&off)[kDirectMaxDepth + 2])
+{
+    uint32_t w[K];   // letters, first to last
+    {
+        uint32_t rest = idx;
+#pragma unroll
+        for (int t = K - 1; t >= 0; --t) {
+            w[t] = D > 0 ? rest % uint32_t(D) : rest % d;
+            rest = D > 0 ? rest / uint32_t(D) : rest / d;
+        }
+    }
+    T xs[K][K + 1];  // xs[i][j] = x[w_{i+1}..w_j], 0 <= i < j <= K
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+        uint32_t val = 0;
+#pragma unroll
+        for (int j = i + 1; j <= K; ++j) {
+            val = val * (D > 0 ? uint32_t(D) : d) + w[j - 1];
+            xs[i][j] = x[off[j - i] + val];
+        }
+    }
+    T prev[K + 1], cur[K + 1];
+#pragma unroll
+    for (int j = 0; j <= K; ++j) prev[j] = T(0);
+    prev[0] = T(1);
+    T result = T(0);
+#pragma unroll
+    for (int m = 1; m <= K; ++m) {
+#pragma unroll
+        for (int j = 0; j <= K; ++j) {
+            T acc = T(0);
+            if (j >= m) {
+#pragma unroll
+                for (int i = m - 1; i < j; ++i) acc += prev[i] * xs[i][j];
+            }
+            cur[j] = acc;
+        }
+        result += ((m & 1) ? T(1) : T(-1)) / T(m) * cur[K];
+#pragma unroll
+        for (int j = 0; j <= K; ++j) prev[j] = cur[j];
+    }
+    return result;
+}
+
+template <typename T, int D>
+__global__ void __launch_bounds__(256)
+sig_log_direct_kernel(Shape sh, const T *__restrict__ in, T *__restrict__ out)
+{
+    const uint32_t d = uint32_t(sh.d);
+    const int N = sh.N;
+    uint32_t off[kDirectMaxDepth + 2];
+#pragma unroll
+    for (int k = 0; k <= kDirectMaxDepth + 1; ++k) off[k] = k <= N + 1 ? uint32_t(sh.off[k]) : 0xffffffffu;
+    const uint32_t S = uint32_t(sh.S);
+    const int64_t total = sh.B * int64_t(S);
+    for (int64_t e = blockIdx.x * int64_t(blockDim.x) + threadIdx.x; e < total; e += int64_t(gridDim.x) * blockDim.x) {
+        const int64_t r = e / S;
+        const uint32_t i = uint32_t(e - r * S);
+        const T *x = in + r * S;
+        int k = 1;
+#pragma unroll
+        for (int j = 2; j <= kDirectMaxDepth; ++j) k += (j <= N && i >= off[j]) ? 1 : 0;
+        // off[k] as a select over constants indices (the array lives in registers)
+        uint32_t base = 0;
+#pragma unroll
+        for (int j = 2; j <= kDirectMaxDepth; ++j) base = (j == k) ? off[j] : base;
+        const uint32_t idx = i - base;
+        T v;
+        switch (k) {
+            case 1: v = x[i]; break;
+            case 2: v = log_of_word<T, D, 2>(x, idx, d, off); break;
+            case 3: v = log_of_word<T, D, 3>(x, idx, d, off); break;
+            case 4: v = log_of_word<T, D, 4>(x, idx, d, off); break;
+            case 5: v = log_of_word<T, D, 5>(x, idx, d, off); break;
+            case 6: v = log_of_word<T, D, 6>(x, idx, d, off); break;
+            case 7: v = log_of_word<T, D, 7>(x, idx, d, off); break;
+            case 8: v = log_of_word<T, D, 8>(x, idx, d, off); break;
+            default: v = log_of_word<T, D, 9>(x, idx, d, off); break;
+        }
+        out[e] = v;
+    }
+}
+
+template <typename T, int D>
+void launch_direct(const Shape &sh, const T *in, T *out, hipStream_t st)
+{
+    const int64_t total = sh.B * sh.S;
+    const unsigned grid = unsigned((total + 255) / 256 < (1 << 20) ? (total + 255) / 256 : (1 << 20));
+    hipLaunchKernelGGL((sig_log_direct_kernel<T, D>), dim3(grid), dim3(256), 0, st, sh, in, out);
+}
+
 template <typename T, int D, int N>
 bool try_fixed(const Shape &sh, const T *in, T *out, unsigned grid, hipStream_t st)
 {
@@ -166,6 +268,19 @@ hipError_t launch_log(const Shape &sh, const T *in, T *out, hipStream_t st)
         try_fixed<T, 8, 2>(sh, in, out, grid, st) || try_fixed<T, 8, 3>(sh, in, out, grid, st) ||
         try_fixed<T, 8, 4>(sh, in, out, grid, st))
         return hipGetLastError();
+    if (sh.N <= kDirectMaxDepth) {
+        switch (sh.d) {
+            case 2: launch_direct<T, 2>(sh, in, out, st); break;
+            case 3: launch_direct<T, 3>(sh, in, out, st); break;
+            case 4: launch_direct<T, 4>(sh, in, out, st); break;
+            case 5: launch_direct<T, 5>(sh, in, out, st); break;
+            case 6: launch_direct<T, 6>(sh, in, out, st); break;
+            case 7: launch_direct<T, 7>(sh, in, out, st); break;
+            case 8: launch_direct<T, 8>(sh, in, out, st); break;
+            default: launch_direct<T, 0>(sh, in, out, st); break;
+        }
+        return hipGetLastError();
+    }
     const size_t lds = 2 * size_t(sh.S) * sizeof(T);
     const bool in_lds = lds <= 64 * 1024;
 #define SIG_LOG_LAUNCH(DD)                                                                                        \
