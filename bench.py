@@ -63,6 +63,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2, help="configuration number 1..5 (default: the metric's)")
     ap.add_argument("--variant", choices=["auto", "generic", "mfma"], default="auto")
+    ap.add_argument("--shape", default=None, metavar="B,L,d,N[,stream]",
+                    help="a shape of your own instead of one of the five workloads (same input recipe, seed index 0), "
+                         "e.g. 32,128,7,7 for the largest case of the paper's benchmark grid")
     ap.add_argument("--op", choices=["forward", "backward", "combine", "logsignature"], default="forward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -90,6 +93,11 @@ def main() -> int:
         return 2
 
     w = workload(args.workload)
+    if args.shape:
+        from paper_2001_00706_amd.inputs import Workload
+        parts = args.shape.split(",")
+        B_, L_, d_, N_ = (int(v) for v in parts[:4])
+        w = Workload(0, B=B_, L=L_, d=d_, N=N_, stream=len(parts) > 4 and parts[4] == "stream", basepoint=False)
     variant = {"auto": sig.SIG_VARIANT_AUTO, "generic": sig.SIG_VARIANT_GENERIC, "mfma": sig.SIG_VARIANT_MFMA}[args.variant]
     x_host = workload_paths(w)
     dev = torch.device("cuda:0")

@@ -13,7 +13,7 @@
 //     gradient of an increment is the sum of every thread's contribution.  (The cotangent a prefix has of
 //     its own in the output gradient is given to the first thread below it.)
 //   * That one sum, over all threads of a path and per increment, is left to a second kernel: every
-//     wavefront (or, for paths of fewer than 256 words, every thread) writes its partial sums to a
+//     workgroup (or, for paths of fewer than 256 words, every thread) writes its partial sums to a
 //     workspace [row][group][increment][d].
 #include "sig_internal.h"
 #include "sig_lane_ops.h"
@@ -42,7 +42,7 @@ struct TbShape {
     static constexpr bool kWide = kWords >= 256;   // one path per workgroup, partial sums per wavefront
     static constexpr int kPathsPerGroup = kWide ? 1 : (256 / kWords < kTbMaxPaths ? int(256 / kWords) : kTbMaxPaths);
     static constexpr int64_t kGroupsPerPath = kWide ? (kWords + 255) / 256 : 1;   // workgroups per path
-    static constexpr int64_t kPartials = kWide ? kGroupsPerPath * 4 : kWords;     // partial sums per path and increment
+    static constexpr int64_t kPartials = kWide ? kGroupsPerPath : kWords;         // partial sums per path and increment
     static constexpr int64_t kS = tb_off(D, N + 1);
 };
 
@@ -56,6 +56,7 @@ sig_tree_backward_kernel(Shape sh, const float *__restrict__ path, const float *
     constexpr int H1 = U >= 1 ? D : 1, H2 = U >= 2 ? D * D : 1;
     constexpr int64_t kS = TS::kS;
     __shared__ float zt[PPG * kTbTile * D];
+    __shared__ float part[TS::kWide ? kTbTile * 4 * D : 1];   // [increment of the tile][wavefront][channel]
 
     const int tid = threadIdx.x;
     const int slot_raw = TS::kWide ? 0 : tid / int(TS::kWords);
@@ -123,7 +124,7 @@ sig_tree_backward_kernel(Shape sh, const float *__restrict__ path, const float *
     const int64_t row0 = TS::kWide ? int64_t(blockIdx.x / TS::kGroupsPerPath) : int64_t(blockIdx.x) * PPG;
     const float *bpv = static_cast<const float *>(sh.basepoint_value);
     // where this thread's (or wavefront's) partial sums go: [row][group][increment][D]
-    const int64_t group = TS::kWide ? int64_t(blockIdx.x % TS::kGroupsPerPath) * 4 + (tid >> 6) : u;
+    const int64_t group = TS::kWide ? int64_t(blockIdx.x % TS::kGroupsPerPath) : u;
     float *pp = partial + (my_row * TS::kPartials + group) * sh.n_inc * D;
 
     for (int64_t t0 = ((sh.n_inc - 1) / kTbTile) * kTbTile; t0 >= 0; t0 -= kTbTile) {
@@ -248,10 +249,11 @@ sig_tree_backward_kernel(Shape sh, const float *__restrict__ path, const float *
 
             // ---- this thread's (wavefront's) part of the increment's gradient
             if constexpr (TS::kWide) {
+                // the wavefronts do not wait for one another inside a tile: their sums meet in LDS at its end
 #pragma unroll
                 for (int c = 0; c < D; ++c) {
                     const float total = group_sum<0, 6>(live ? dz[c] : 0.0f);
-                    if ((tid & 63) == c) pp[s * D + c] = total;
+                    if ((tid & 63) == c) part[(i * 4 + (tid >> 6)) * D + c] = total;
                 }
             } else {
                 if (live) {
@@ -274,6 +276,14 @@ sig_tree_backward_kernel(Shape sh, const float *__restrict__ path, const float *
                         for (int c = 0; c < D * D; ++c) G.h2[c] += add.h2[c];
                     }
                 }
+            }
+        }
+        if constexpr (TS::kWide) {
+            __syncthreads();
+            for (int e = tid; e < nt * D; e += 256) {
+                const int i = e / D, c = e % D;
+                const float *q = part + i * 4 * D + c;
+                pp[(t0 + i) * D + c] = (q[0] + q[D]) + (q[2 * D] + q[3 * D]);
             }
         }
     }

@@ -34,7 +34,8 @@ class Workload:
     @property
     def name(self) -> str:
         mode = "stream" if self.stream else "final"
-        return f"cfg{self.index}:B{self.B}xL{self.L}xd{self.d},N{self.N},{mode}"
+        tag = f"cfg{self.index}" if self.index > 0 else "custom"
+        return f"{tag}:B{self.B}xL{self.L}xd{self.d},N{self.N},{mode}"
 
     @property
     def seed(self) -> int:

@@ -144,9 +144,9 @@ def test_backward_validation(lib):
     assert sig.sig_backward_workspace_bytes(2, 1, 2, 2, False, False) == -1
     assert sig.sig_backward_workspace_bytes(2, 4, 65, 1, False, False) == -1
     assert sig.sig_backward_workspace_bytes(0, 4, 2, 2, False, False) == 0
-    # fp32, d <= 8, N <= 9: the partial gradients of the prefix-tree kernels, one per wavefront (7^5 words in 66
-    # workgroups of 4 wavefronts), increment and channel
-    assert sig.sig_backward_workspace_bytes(32, 128, 7, 7, False, False) == 32 * 264 * 127 * 7 * 4
+    # fp32, d <= 8, N <= 9: the partial gradients of the prefix-tree kernels, one per workgroup (7^5 words in 66
+    # workgroups), increment and channel
+    assert sig.sig_backward_workspace_bytes(32, 128, 7, 7, False, False) == 32 * 66 * 127 * 7 * 4
 
 
 def test_signature_invert_and_strided_combine_validation(lib):
