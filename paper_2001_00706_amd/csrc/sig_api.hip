@@ -68,7 +68,7 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
     const bool d8_ok = dtype == SIG_F32 && aligned && sig::mfma_d8_kernel_name(sh) != nullptr;
     const bool generic_ok = sig::generic_supported(sh, dtype);
     const bool small_ok = sig::small_supported(sh);
-    const bool tree_ok = dtype == SIG_F32 && sig::tree_supported(sh);
+    const bool tree_ok = sig::tree_supported(sh);
     switch (variant) {
         case SIG_VARIANT_AUTO:
             // four wavefronts per path when one per path would leave most of the chip idle, when every
@@ -104,7 +104,9 @@ hipError_t launch_family(Family family, const sig::Shape &sh, sig_dtype dtype, c
         case Family::MfmaD8:
             return sig::launch_mfma_d8_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
         case Family::Tree:
-            return sig::launch_tree_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
+            return dtype == SIG_F32
+                       ? sig::launch_tree_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
+                       : sig::launch_tree_f64(sh, static_cast<const double *>(path), static_cast<double *>(out), hip_stream);
         case Family::Small:
             return dtype == SIG_F32
                        ? sig::launch_small_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)

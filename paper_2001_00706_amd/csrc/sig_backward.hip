@@ -303,8 +303,8 @@ bool backward_supported(const Shape &sh)
 
 int64_t backward_workspace_bytes(const Shape &sh, sig_dtype dtype)
 {
-    // fp32 signatures of up to 8 channels and depth 9 never reach the generic kernel
-    if (dtype == SIG_F32 && tree_backward_supported(sh)) return tree_backward_workspace_bytes(sh);
+    // signatures of up to 8 channels and depth 9 never reach the generic kernel
+    if (tree_backward_supported(sh)) return tree_backward_workspace_bytes(sh, dtype);
     BackwardPlan pl;
     if (!backward_supported(sh) || !make_plan(sh, kBackwardThreads, pl)) return -1;
     const bool lds = dtype == SIG_F32 ? fits_lds<float>(pl) : fits_lds<double>(pl);
@@ -330,6 +330,8 @@ hipError_t launch_backward_f32(const Shape &sh, const float *path, const float *
 hipError_t launch_backward_f64(const Shape &sh, const double *path, const double *sig, const double *gout, double *gpath,
                                double *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st)
 {
+    if (tree_backward_supported(sh))
+        return launch_tree_backward_f64(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
     return launch_backward<double>(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
 }
 

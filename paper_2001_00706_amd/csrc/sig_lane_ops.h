@@ -20,14 +20,29 @@ __device__ __forceinline__ float neighbour(float v)
     else return __shfl_xor(v, MASK);
 }
 
+// The same for a double: its two halves travel separately.
+template <int MASK>
+__device__ __forceinline__ double neighbour(double v)
+{
+    if constexpr (MASK >= 16) {
+        return __shfl_xor(v, MASK);
+    } else {
+        const unsigned long long bits = __builtin_bit_cast(unsigned long long, v);
+        const float lo = neighbour<MASK>(__builtin_bit_cast(float, unsigned(bits)));
+        const float hi = neighbour<MASK>(__builtin_bit_cast(float, unsigned(bits >> 32)));
+        return __builtin_bit_cast(double, (unsigned long long)(__builtin_bit_cast(unsigned, hi)) << 32 |
+                                              __builtin_bit_cast(unsigned, lo));
+    }
+}
+
 // Sum of v over the 2^CNT groups of 2^LO lanes that differ in lane-number bits LO .. LO+CNT-1, in every lane.
 // v must be the same throughout each aligned group of 2^LO lanes.
-template <int LO, int CNT>
-__device__ __forceinline__ float group_sum(float v)
+template <int LO, int CNT, typename T>
+__device__ __forceinline__ T group_sum(T v)
 {
     if constexpr (CNT > 0) {
         v += neighbour<(1 << LO)>(v);
-        return group_sum<LO + 1, CNT - 1>(v);
+        return group_sum<LO + 1, CNT - 1, T>(v);
     } else {
         return v;
     }

@@ -1,4 +1,4 @@
-// Prefix-tree kernel family (fp32, final mode): any d = 2..8 at depths 2..9 whose state is too large for the
+// Prefix-tree kernel family (fp32 and fp64, final mode): any d = 2..8 at depths 2..9 whose state is too large for the
 // small-state kernel and that the matrix-core families do not serve - in particular few paths with a large
 // signature, where the state of one path (up to millions of scalars) has to be spread over the whole chip.
 //
@@ -40,14 +40,17 @@ struct TreeShape {
     static constexpr int64_t kS = tree_off(D, N + 1);
 };
 
-template <int D, int N>
+__device__ __forceinline__ float fma_t(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ double fma_t(double a, double b, double c) { return __builtin_fma(a, b, c); }
+
+template <typename T, int D, int N>
 __global__ void __launch_bounds__(256)
-sig_tree_kernel(Shape sh, const float *__restrict__ path, float *__restrict__ out)
+sig_tree_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
 {
     using TS = TreeShape<D, N>;
     constexpr int U = TS::U, P = TS::P, PPG = TS::kPathsPerGroup;
     constexpr int H1 = U >= 1 ? D : 1, H2 = U >= 2 ? D * D : 1;
-    __shared__ float zt[PPG * kTreeTile * D];
+    __shared__ T zt[PPG * kTreeTile * D];
 
     const int tid = threadIdx.x;
     // which path of the workgroup, which word of the path
@@ -66,19 +69,19 @@ sig_tree_kernel(Shape sh, const float *__restrict__ path, float *__restrict__ ou
             rest /= D;
         }
     }
-    float rk[N + 2];
+    T rk[N + 2];
 #pragma unroll
-    for (int m = 1; m <= N + 1; ++m) rk[m] = 1.0f / float(m);
+    for (int m = 1; m <= N + 1; ++m) rk[m] = T(1) / T(m);
 
-    float A[P + 1];      // coefficients of the prefixes of the word, and of the word itself (level P)
-    float B1[H1];        // words u c
-    float B2[H2];        // words u c c'
+    T A[P + 1];      // coefficients of the prefixes of the word, and of the word itself (level P)
+    T B1[H1];        // words u c
+    T B2[H2];        // words u c c'
 #pragma unroll
-    for (int i = 0; i <= P; ++i) A[i] = 0.0f;
+    for (int i = 0; i <= P; ++i) A[i] = T(0);
 #pragma unroll
-    for (int c = 0; c < H1; ++c) B1[c] = 0.0f;
+    for (int c = 0; c < H1; ++c) B1[c] = T(0);
 #pragma unroll
-    for (int c = 0; c < H2; ++c) B2[c] = 0.0f;
+    for (int c = 0; c < H2; ++c) B2[c] = T(0);
 
     // the rows (paths or chunks of paths) this workgroup serves, for the staging of their increments
     const int64_t row0 = TS::kWords >= 256 ? int64_t(blockIdx.x / TS::kGroupsPerPath) : int64_t(blockIdx.x) * PPG;
@@ -88,19 +91,19 @@ sig_tree_kernel(Shape sh, const float *__restrict__ path, float *__restrict__ ou
             const ChunkView cv = chunk_view(row0 + p, sh.chunks, sh.chunk_len, sh.n_inc);
             n_max = cv.n > n_max ? cv.n : n_max;
         }
-    const float *bpv = static_cast<const float *>(sh.basepoint_value);
+    const T *bpv = static_cast<const T *>(sh.basepoint_value);
 
     for (int64_t t0 = 0; t0 < n_max; t0 += kTreeTile) {
         __syncthreads();
         for (int e = tid; e < PPG * kTreeTile * D; e += 256) {
             const int p = e / (kTreeTile * D), i = (e / D) % kTreeTile, c = e % D;
-            float z = 0.0f;   // rows past the end of the batch and increments past the end of a row add nothing
+            T z = T(0);   // rows past the end of the batch and increments past the end of a row add nothing
             if (row0 + p < sh.B) {
                 const ChunkView cv = chunk_view(row0 + p, sh.chunks, sh.chunk_len, sh.n_inc);
                 if (t0 + i < cv.n) {
-                    const float *x = path + cv.path * sh.L * D;
+                    const T *x = path + cv.path * sh.L * D;
                     const int64_t i_hi = cv.inc0 + t0 + i + (sh.basepoint ? 0 : 1);
-                    const float lo = i_hi > 0 ? x[(i_hi - 1) * D + c] : bpv != nullptr ? bpv[cv.path * D + c] : 0.0f;
+                    const T lo = i_hi > 0 ? x[(i_hi - 1) * D + c] : bpv != nullptr ? bpv[cv.path * D + c] : T(0);
                     z = x[i_hi * D + c] - lo;
                 }
             }
@@ -108,38 +111,38 @@ sig_tree_kernel(Shape sh, const float *__restrict__ path, float *__restrict__ ou
         }
         __syncthreads();
         const int nt = int(n_max - t0 < kTreeTile ? n_max - t0 : kTreeTile);
-        const float *zrow = zt + slot * kTreeTile * D;
+        const T *zrow = zt + slot * kTreeTile * D;
         for (int s = 0; s < nt; ++s, zrow += D) {
-            // Horner terms along the word: T[k] = T^(k)_i for the level i just passed, k > i
-            float T[N + 2];
+            // Horner terms along the word: Hn[k] = T^(k)_i for the level i just passed, k > i
+            T Hn[N + 2];
             {
-                const float zc = zrow[cl[1]];
+                const T zc = zrow[cl[1]];
 #pragma unroll
-                for (int k = 2; k <= N; ++k) T[k] = __builtin_fmaf(zc, rk[k], A[1]);
+                for (int k = 2; k <= N; ++k) Hn[k] = fma_t(zc, rk[k], A[1]);
                 A[1] += zc;
             }
 #pragma unroll
             for (int i = 2; i <= P; ++i) {
-                const float zc = zrow[cl[i]];
-                const float a = A[i];
-                A[i] = __builtin_fmaf(T[i], zc, a);
+                const T zc = zrow[cl[i]];
+                const T a = A[i];
+                A[i] = fma_t(Hn[i], zc, a);
 #pragma unroll
-                for (int k = i + 1; k <= N; ++k) T[k] = __builtin_fmaf(T[k], zc * rk[k - i + 1], a);
+                for (int k = i + 1; k <= N; ++k) Hn[k] = fma_t(Hn[k], zc * rk[k - i + 1], a);
             }
             if constexpr (U >= 1) {
-                float zu[D];
+                T zu[D];
 #pragma unroll
                 for (int c = 0; c < D; ++c) zu[c] = zrow[c];
                 if constexpr (U == 1) {
 #pragma unroll
-                    for (int c = 0; c < D; ++c) B1[c] = __builtin_fmaf(T[P + 1], zu[c], B1[c]);
+                    for (int c = 0; c < D; ++c) B1[c] = fma_t(Hn[P + 1], zu[c], B1[c]);
                 } else {
 #pragma unroll
                     for (int c = 0; c < D; ++c) {
-                        const float t1 = __builtin_fmaf(T[P + 2], zu[c] * rk[2], B1[c]);   // T^(N)_{P+1}[u c]
-                        B1[c] = __builtin_fmaf(T[P + 1], zu[c], B1[c]);
+                        const T t1 = fma_t(Hn[P + 2], zu[c] * rk[2], B1[c]);   // T^(N)_{P+1}[u c]
+                        B1[c] = fma_t(Hn[P + 1], zu[c], B1[c]);
 #pragma unroll
-                        for (int j = 0; j < D; ++j) B2[c * D + j] = __builtin_fmaf(t1, zu[j], B2[c * D + j]);
+                        for (int j = 0; j < D; ++j) B2[c * D + j] = fma_t(t1, zu[j], B2[c * D + j]);
                     }
                 }
             }
@@ -147,7 +150,7 @@ sig_tree_kernel(Shape sh, const float *__restrict__ path, float *__restrict__ ou
     }
 
     if (!live) return;
-    float *o = out + row * TS::kS;
+    T *o = out + row * TS::kS;
     // a prefix is written by the first thread below it
     {
         int64_t q = u, width = 1;
@@ -168,28 +171,28 @@ sig_tree_kernel(Shape sh, const float *__restrict__ path, float *__restrict__ ou
     }
 }
 
-template <int D, int N>
-hipError_t launch_tree_dn(const Shape &sh, const float *path, float *out, hipStream_t st)
+template <typename T, int D, int N>
+hipError_t launch_tree_dn(const Shape &sh, const T *path, T *out, hipStream_t st)
 {
     using TS = TreeShape<D, N>;
     const int64_t groups = TS::kWords >= 256 ? sh.B * TS::kGroupsPerPath : (sh.B + TS::kPathsPerGroup - 1) / TS::kPathsPerGroup;
     if (groups > 0x7fffffff) return hipErrorNotSupported;
-    hipLaunchKernelGGL((sig_tree_kernel<D, N>), dim3(unsigned(groups)), dim3(256), 0, st, sh, path, out);
+    hipLaunchKernelGGL((sig_tree_kernel<T, D, N>), dim3(unsigned(groups)), dim3(256), 0, st, sh, path, out);
     return hipGetLastError();
 }
 
-template <int D>
-hipError_t launch_tree_d(const Shape &sh, const float *path, float *out, hipStream_t st)
+template <typename T, int D>
+hipError_t launch_tree_d(const Shape &sh, const T *path, T *out, hipStream_t st)
 {
     switch (sh.N) {
-        case 2: return launch_tree_dn<D, 2>(sh, path, out, st);
-        case 3: return launch_tree_dn<D, 3>(sh, path, out, st);
-        case 4: return launch_tree_dn<D, 4>(sh, path, out, st);
-        case 5: return launch_tree_dn<D, 5>(sh, path, out, st);
-        case 6: return launch_tree_dn<D, 6>(sh, path, out, st);
-        case 7: return launch_tree_dn<D, 7>(sh, path, out, st);
-        case 8: return launch_tree_dn<D, 8>(sh, path, out, st);
-        case 9: return launch_tree_dn<D, 9>(sh, path, out, st);
+        case 2: return launch_tree_dn<T, D, 2>(sh, path, out, st);
+        case 3: return launch_tree_dn<T, D, 3>(sh, path, out, st);
+        case 4: return launch_tree_dn<T, D, 4>(sh, path, out, st);
+        case 5: return launch_tree_dn<T, D, 5>(sh, path, out, st);
+        case 6: return launch_tree_dn<T, D, 6>(sh, path, out, st);
+        case 7: return launch_tree_dn<T, D, 7>(sh, path, out, st);
+        case 8: return launch_tree_dn<T, D, 8>(sh, path, out, st);
+        case 9: return launch_tree_dn<T, D, 9>(sh, path, out, st);
     }
     return hipErrorNotSupported;
 }
@@ -201,19 +204,23 @@ bool tree_supported(const Shape &sh)
     return !sh.stream && sh.d >= 2 && sh.d <= 8 && sh.N >= 2 && sh.N <= 9 && sh.S < (int64_t(1) << 31);
 }
 
-hipError_t launch_tree_f32(const Shape &sh, const float *path, float *out, hipStream_t st)
+template <typename T>
+hipError_t launch_tree_t(const Shape &sh, const T *path, T *out, hipStream_t st)
 {
     if (!tree_supported(sh)) return hipErrorNotSupported;
     switch (sh.d) {
-        case 2: return launch_tree_d<2>(sh, path, out, st);
-        case 3: return launch_tree_d<3>(sh, path, out, st);
-        case 4: return launch_tree_d<4>(sh, path, out, st);
-        case 5: return launch_tree_d<5>(sh, path, out, st);
-        case 6: return launch_tree_d<6>(sh, path, out, st);
-        case 7: return launch_tree_d<7>(sh, path, out, st);
-        case 8: return launch_tree_d<8>(sh, path, out, st);
+        case 2: return launch_tree_d<T, 2>(sh, path, out, st);
+        case 3: return launch_tree_d<T, 3>(sh, path, out, st);
+        case 4: return launch_tree_d<T, 4>(sh, path, out, st);
+        case 5: return launch_tree_d<T, 5>(sh, path, out, st);
+        case 6: return launch_tree_d<T, 6>(sh, path, out, st);
+        case 7: return launch_tree_d<T, 7>(sh, path, out, st);
+        case 8: return launch_tree_d<T, 8>(sh, path, out, st);
     }
     return hipErrorNotSupported;
 }
+
+hipError_t launch_tree_f32(const Shape &sh, const float *path, float *out, hipStream_t st) { return launch_tree_t<float>(sh, path, out, st); }
+hipError_t launch_tree_f64(const Shape &sh, const double *path, double *out, hipStream_t st) { return launch_tree_t<double>(sh, path, out, st); }
 
 }  // namespace sig

@@ -434,8 +434,9 @@ def test_chunked_scan_argument_checks():
     (37, 6, 3, 4),     # 9 words per path: 16 paths share a workgroup, the last workgroup is ragged
     (5, 5, 8, 2), (3, 7, 6, 3), (1, 2, 2, 2),
 ])
-def test_prefix_tree_family(B, L, d, N):
-    x = brownian_paths(B, L, d, seed=B + L + d + N)
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_prefix_tree_family(B, L, d, N, dtype):
+    x = brownian_paths(B, L, d, seed=B + L + d + N).astype(dtype)
     for basepoint in (False, True):
         assert check(x, N, basepoint=basepoint, variant=sig.SIG_VARIANT_TREE) is not None
     assert sig.sig_variant_name(B, L, d, N, True, False, variant=sig.SIG_VARIANT_TREE) == "unsupported"
