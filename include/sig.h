@@ -54,7 +54,7 @@ typedef enum {
     SIG_VARIANT_MFMA_SHARD = 3,/* fp32, d = 4, N = 4..7, final and stream mode: four independent wavefronts
                                  per path, one per first letter */
     SIG_VARIANT_SMALL = 4,    /* any dtype and mode, S <= 512, N <= 8, d <= 64: one wavefront per path, state in LDS */
-    SIG_VARIANT_TREE = 5      /* any dtype, final mode, d = 2..8, N = 2..9: a thread per word of N-2 letters, state in
+    SIG_VARIANT_TREE = 5      /* any dtype and mode, d = 2..8, N = 2..9: a thread per word of N-2 letters, state in
                                  registers, any number of workgroups per path (large signatures, few paths) */
 } sig_variant;
 

@@ -1,4 +1,4 @@
-// Prefix-tree kernel family (fp32 and fp64, final mode): any d = 2..8 at depths 2..9 whose state is too large for the
+// Prefix-tree kernel family (fp32 and fp64, final and stream mode): any d = 2..8 at depths 2..9 whose state is too large for the
 // small-state kernel and that the matrix-core families do not serve - in particular few paths with a large
 // signature, where the state of one path (up to millions of scalars) has to be spread over the whole chip.
 //
@@ -93,6 +93,25 @@ sig_tree_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
         }
     const T *bpv = static_cast<const T *>(sh.basepoint_value);
 
+    // this thread's words of one signature; a prefix is written by the first thread below it
+    auto store = [&](T *o) {
+        int64_t q = u, width = 1;
+#pragma unroll
+        for (int i = P; i >= 1; --i) {
+            if (u % width == 0) o[tree_off(D, i) + q] = A[i];
+            q /= D;
+            width *= D;
+        }
+        if constexpr (U >= 1) {
+#pragma unroll
+            for (int c = 0; c < D; ++c) o[tree_off(D, P + 1) + u * D + c] = B1[c];
+        }
+        if constexpr (U >= 2) {
+#pragma unroll
+            for (int c = 0; c < D * D; ++c) o[tree_off(D, P + 2) + u * (D * D) + c] = B2[c];
+        }
+    };
+
     for (int64_t t0 = 0; t0 < n_max; t0 += kTreeTile) {
         __syncthreads();
         for (int e = tid; e < PPG * kTreeTile * D; e += 256) {
@@ -146,29 +165,12 @@ sig_tree_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
                     }
                 }
             }
+            // stream mode (never chunked: every row has all n_max = n_inc increments): the signature so far
+            if (sh.stream && live) store(out + (row * sh.n_inc + t0 + s) * TS::kS);
         }
     }
 
-    if (!live) return;
-    T *o = out + row * TS::kS;
-    // a prefix is written by the first thread below it
-    {
-        int64_t q = u, width = 1;
-#pragma unroll
-        for (int i = P; i >= 1; --i) {
-            if (u % width == 0) o[tree_off(D, i) + q] = A[i];
-            q /= D;
-            width *= D;
-        }
-    }
-    if constexpr (U >= 1) {
-#pragma unroll
-        for (int c = 0; c < D; ++c) o[tree_off(D, P + 1) + u * D + c] = B1[c];
-    }
-    if constexpr (U >= 2) {
-#pragma unroll
-        for (int c = 0; c < D * D; ++c) o[tree_off(D, P + 2) + u * (D * D) + c] = B2[c];
-    }
+    if (live && !sh.stream) store(out + row * TS::kS);
 }
 
 template <typename T, int D, int N>
@@ -201,7 +203,7 @@ hipError_t launch_tree_d(const Shape &sh, const T *path, T *out, hipStream_t st)
 
 bool tree_supported(const Shape &sh)
 {
-    return !sh.stream && sh.d >= 2 && sh.d <= 8 && sh.N >= 2 && sh.N <= 9 && sh.S < (int64_t(1) << 31);
+    return sh.d >= 2 && sh.d <= 8 && sh.N >= 2 && sh.N <= 9 && sh.S < (int64_t(1) << 31);
 }
 
 template <typename T>
