@@ -148,6 +148,20 @@ sig_status sig_combine(const void *a, const void *b, int64_t B, int d, int N, si
 sig_status sig_combine_strided(const void *a, int64_t a_stride, const void *b, int64_t b_stride, int64_t B, int d, int N,
                                sig_dtype dtype, void *out, int64_t out_stride, hipStream_t hip_stream);
 
+/* Group product of n signatures per batch row, in order: out[b] = sigs[b][0] [x] sigs[b][1] [x] ... [x] sigs[b][n-1]
+ * (section 5.5, "combining adjacent intervals": the signatures of n consecutive intervals, each starting at the
+ * point where the one before ends, joined without going back to the data).  Neighbours are multiplied pairwise in
+ * ceil(log2 n) rounds.
+ *   sigs       DEVICE pointer [B][n][S]; read only.   out  DEVICE pointer [B][S]; must not overlap `sigs`.
+ *   workspace  DEVICE pointer, 16-byte aligned, at least sig_combine_many_workspace_bytes(...) bytes (0 for n <= 2,
+ *              then it may be NULL); contents undefined on return.
+ * Errors as for sig_combine; n < 1 and a missing or short workspace are SIG_ERR_INVALID_ARG. */
+sig_status sig_combine_many(const void *sigs, int64_t B, int64_t n, int d, int N, sig_dtype dtype, void *out,
+                            void *workspace, int64_t workspace_bytes, hipStream_t hip_stream);
+
+/* Bytes of workspace sig_combine_many needs; -1 on invalid arguments. */
+int64_t sig_combine_many_workspace_bytes(int64_t B, int64_t n, int d, int N, sig_dtype dtype);
+
 /* Group inverse of `rows` signatures: out[r] = sig[r]^{-1}, which is the signature of the same path traversed
  * backwards (section 5.4).  It is a signed permutation of the scalars: level k of the inverse holds
  * (-1)^k times the coefficient of the reversed word.

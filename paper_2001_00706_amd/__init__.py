@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     sig_backward,
     sig_backward_workspace_bytes,
     sig_combine,
+    sig_combine_many,
     sig_combine_strided,
     sig_invert,
     sig_log,

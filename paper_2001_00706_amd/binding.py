@@ -32,6 +32,8 @@ EXPORTED_SYMBOLS = (
     "sig_combine",
     "sig_backward",
     "sig_combine_strided",
+    "sig_combine_many",
+    "sig_combine_many_workspace_bytes",
     "sig_invert",
     "sig_log",
     "sig_logsignature_channels",
@@ -82,6 +84,10 @@ def load_library() -> ctypes.CDLL:
         lib.sig_combine.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
         lib.sig_backward.restype = i32
         lib.sig_backward.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, i32, vp, i32, vp, vp, vp, i64, vp]
+        lib.sig_combine_many.restype = i32
+        lib.sig_combine_many.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, i64, vp]
+        lib.sig_combine_many_workspace_bytes.restype = i64
+        lib.sig_combine_many_workspace_bytes.argtypes = [i64, i64, i32, i32, i32]
         lib.sig_combine_strided.restype = i32
         lib.sig_combine_strided.argtypes = [vp, i64, vp, i64, i64, i32, i32, i32, vp, i64, vp]
         lib.sig_log.restype = i32
@@ -501,6 +507,34 @@ def sig_forward_chunked(path, N: int, chunks: int, basepoint=False, out=None, wo
             path.data_ptr(), B, L, d, N, bp_flag, bp_value.data_ptr() if bp_value is not None else 0, chunks, dtype,
             out.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
             torch.cuda.current_stream().cuda_stream))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return out
+
+
+def sig_combine_many(sigs, d: int, N: int, out=None, workspace=None):
+    """Ordered group product of the `n` signatures of every batch row of `sigs` `[B, n, S]` -> `[B, S]`."""
+    import torch
+
+    _check_gpu("sig_combine_many", sigs)
+    dtype = _dtype_of(sigs)
+    S = sig_signature_channels(d, N)
+    if sigs.dim() != 3 or sigs.shape[2] != S or sigs.shape[1] < 1 or not sigs.is_contiguous():
+        raise ValueError(f"sigs must be a contiguous [B, n, {S}] tensor with n >= 1")
+    B, n, _ = sigs.shape
+    if out is None:
+        out = torch.empty((B, S), dtype=sigs.dtype, device=sigs.device)
+    elif out.dtype != sigs.dtype or out.device != sigs.device or tuple(out.shape) != (B, S) or not out.is_contiguous():
+        raise ValueError(f"out must be a contiguous tensor of shape {(B, S)} like sigs")
+    lib = load_library()
+    with torch.cuda.device(sigs.device):
+        need = int(lib.sig_combine_many_workspace_bytes(B, n, d, N, dtype))
+        if need > 0 and workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=sigs.device)
+        ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) \
+            if workspace is not None else (0, 0)
+        status = int(lib.sig_combine_many(sigs.data_ptr(), B, n, d, N, dtype, out.data_ptr(), ws_ptr, ws_bytes,
+                                          torch.cuda.current_stream().cuda_stream))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out

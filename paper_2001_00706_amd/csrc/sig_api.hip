@@ -274,7 +274,7 @@ sig_status sig_combine_strided(const void *a, int64_t a_stride, const void *b, i
     if (B == 0) return SIG_OK;
     if (a == nullptr || b == nullptr || out == nullptr) return SIG_ERR_INVALID_ARG;
     if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
-    const int64_t strides[3] = {a_stride, b_stride, out_stride};
+    const int64_t strides[7] = {a_stride, b_stride, out_stride, 0, 0, 0, 0};
     const hipError_t err =
         dtype == SIG_F32
             ? sig::launch_combine_f32(sh, static_cast<const float *>(a), static_cast<const float *>(b),
@@ -336,7 +336,7 @@ sig_status sig_forward_chunked(const void *path, int64_t B, int64_t L, int d, in
     for (int64_t count = sh.B / 2; count >= B; count /= 2) {
         rows.B = count;
         char *dst = count == B ? static_cast<char *>(out) : spare;
-        const int64_t strides[3] = {2 * sh.S, 2 * sh.S, sh.S};
+        const int64_t strides[7] = {2 * sh.S, 2 * sh.S, sh.S, 0, 0, 0, 0};
         const hipError_t err =
             dtype == SIG_F32
                 ? sig::launch_combine_f32(rows, reinterpret_cast<const float *>(src), reinterpret_cast<const float *>(src) + sh.S,
@@ -346,6 +346,71 @@ sig_status sig_forward_chunked(const void *path, int64_t B, int64_t L, int d, in
         if (err != hipSuccess) return SIG_ERR_HIP;
         spare = const_cast<char *>(src);
         src = dst;
+    }
+    return SIG_OK;
+}
+
+int64_t sig_combine_many_workspace_bytes(int64_t B, int64_t n, int d, int N, sig_dtype dtype)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return -1;
+    sig::Shape sh;
+    if (n < 1 || make_rows_shape(B, d, N, sh) != SIG_OK) return -1;
+    if (B > 0 && n > kMaxElems / sh.S / B) return -1;
+    // two buffers: the results of the first round and of the second, reused alternately afterwards
+    const int64_t first = (n + 1) / 2, second = (first + 1) / 2;
+    return n <= 2 ? 0 : B * (first + (first > 2 ? second : 0)) * sh.S * int64_t(dtype == SIG_F32 ? sizeof(float) : sizeof(double));
+}
+
+sig_status sig_combine_many(const void *sigs, int64_t B, int64_t n, int d, int N, sig_dtype dtype, void *out,
+                            void *workspace, int64_t workspace_bytes, hipStream_t hip_stream)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
+    if (n < 1) return SIG_ERR_INVALID_ARG;
+    sig::Shape sh;
+    const sig_status st = make_rows_shape(B, d, N, sh);
+    if (st != SIG_OK) return st;
+    if (B > 0 && n > kMaxElems / sh.S / B) return SIG_ERR_OVERFLOW;
+    if (B == 0) return SIG_OK;
+    if (sigs == nullptr || out == nullptr) return SIG_ERR_INVALID_ARG;
+    if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
+    const int64_t need = sig_combine_many_workspace_bytes(B, n, d, N, dtype);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16 != 0))
+        return SIG_ERR_INVALID_ARG;
+    const int64_t elem = dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double));
+    const int64_t S = sh.S;
+    // rounds of pairwise products in order (the product is associative, not commutative); an odd one out is carried
+    const char *src = static_cast<const char *>(sigs);
+    int64_t count = n;
+    const int64_t first = (n + 1) / 2;
+    char *bufs[2] = {static_cast<char *>(workspace), static_cast<char *>(workspace) + B * first * S * elem};
+    int which = 0;
+    if (count == 1) {
+        return hipMemcpyAsync(out, sigs, size_t(B * S * elem), hipMemcpyDeviceToDevice, hip_stream) == hipSuccess ? SIG_OK
+                                                                                                             : SIG_ERR_HIP;
+    }
+    while (count > 1) {
+        const int64_t pairs = count / 2, next = (count + 1) / 2;
+        char *dst = next == 1 ? static_cast<char *>(out) : bufs[which];
+        sig::Shape rows = sh;
+        rows.B = B * pairs;
+        const int64_t strides[7] = {2 * S, 2 * S, S, pairs, count * S, count * S, next * S};
+        const hipError_t err =
+            dtype == SIG_F32
+                ? sig::launch_combine_f32(rows, reinterpret_cast<const float *>(src), reinterpret_cast<const float *>(src) + S,
+                                          reinterpret_cast<float *>(dst), hip_stream, strides)
+                : sig::launch_combine_f64(rows, reinterpret_cast<const double *>(src), reinterpret_cast<const double *>(src) + S,
+                                          reinterpret_cast<double *>(dst), hip_stream, strides);
+        if (err != hipSuccess) return SIG_ERR_HIP;
+        if (count % 2 == 1) {
+            // the last signature of every row moves on unchanged
+            if (hipMemcpy2DAsync(dst + pairs * S * elem, size_t(next * S * elem), src + (count - 1) * S * elem,
+                                 size_t(count * S * elem), size_t(S * elem), size_t(B), hipMemcpyDeviceToDevice,
+                                 hip_stream) != hipSuccess)
+                return SIG_ERR_HIP;
+        }
+        src = dst;
+        count = next;
+        which ^= 1;
     }
     return SIG_OK;
 }

@@ -11,9 +11,12 @@
 namespace sig {
 namespace {
 
-// Distance, in scalars, between consecutive signatures of each operand (S when they are packed).
+// Where product p finds its operands: with p = q * n_inner + i (i < n_inner), operand a starts at
+// a + q * a_outer + i * a_inner scalars, likewise b and out.  Packed operands: n_inner = everything, inner = S.
 struct Strides {
-    int64_t a, b, out;
+    int64_t a, b, out;                    // inner strides
+    int64_t n_inner;                      // products per outer step
+    int64_t a_outer, b_outer, out_outer;  // outer strides
 };
 
 // D: the channel count when it is one of the common ones (division by a constant is a multiply
@@ -26,9 +29,10 @@ sig_combine_kernel(Shape sh, Strides rs, const T *__restrict__ a, const T *__res
     const int N = sh.N;
     const uint32_t d = D > 0 ? uint32_t(D) : uint32_t(sh.d);
     for (int64_t p = blockIdx.y; p < sh.B; p += gridDim.y) {
-        const T *ap = a + p * rs.a;
-        const T *bp = b + p * rs.b;
-        T *op = out + p * rs.out;
+        const int64_t q = p / rs.n_inner, r = p - q * rs.n_inner;
+        const T *ap = a + q * rs.a_outer + r * rs.a;
+        const T *bp = b + q * rs.b_outer + r * rs.b;
+        T *op = out + q * rs.out_outer + r * rs.out;
         for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < S; i += gridDim.x * blockDim.x) {
             int k = 1;
             while (k < N && i >= uint32_t(sh.off[k + 1])) ++k;
@@ -61,9 +65,10 @@ sig_combine_vec4_kernel(Shape sh, Strides rs, const T *__restrict__ a, const T *
     const uint32_t S4 = uint32_t(sh.S) / 4;
     const int N = sh.N;
     for (int64_t p = blockIdx.y; p < sh.B; p += gridDim.y) {
-        const T *ap = a + p * rs.a;
-        const T *bp = b + p * rs.b;
-        T *op = out + p * rs.out;
+        const int64_t q = p / rs.n_inner, r = p - q * rs.n_inner;
+        const T *ap = a + q * rs.a_outer + r * rs.a;
+        const T *bp = b + q * rs.b_outer + r * rs.b;
+        T *op = out + q * rs.out_outer + r * rs.out;
         for (uint32_t v = blockIdx.x * blockDim.x + threadIdx.x; v < S4; v += gridDim.x * blockDim.x) {
             const uint32_t i = 4 * v;
             int k = 1;
@@ -87,13 +92,27 @@ sig_combine_vec4_kernel(Shape sh, Strides rs, const T *__restrict__ a, const T *
 template <typename T>
 hipError_t launch_combine(const Shape &sh, const T *a, const T *b, T *out, hipStream_t st, const int64_t *strides)
 {
-    const Strides rs = strides != nullptr ? Strides{strides[0], strides[1], strides[2]} : Strides{sh.S, sh.S, sh.S};
+    // strides: {a, b, out} or {a, b, out, n_inner, a_outer, b_outer, out_outer} (flagged by a negative first entry
+    // being impossible: the caller passes the count in strides[3] as 0 when there is no outer level)
+    const int64_t whole = int64_t(1) << 62;
+    Strides rs = {sh.S, sh.S, sh.S, whole, 0, 0, 0};
+    if (strides != nullptr) {
+        rs.a = strides[0];
+        rs.b = strides[1];
+        rs.out = strides[2];
+        if (strides[3] > 0) {
+            rs.n_inner = strides[3];
+            rs.a_outer = strides[4];
+            rs.b_outer = strides[5];
+            rs.out_outer = strides[6];
+        }
+    }
     const unsigned bx = unsigned((sh.S + 255) / 256 < 4096 ? (sh.S + 255) / 256 : 4096);
     const unsigned by = unsigned(sh.B < 65535 ? sh.B : 65535);
     const dim3 grid(bx, by), block(256);
     const bool aligned = (reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) | reinterpret_cast<uintptr_t>(out)) %
                                  (4 * sizeof(T)) == 0 &&
-                         (rs.a | rs.b | rs.out) % 4 == 0;
+                         (rs.a | rs.b | rs.out | rs.a_outer | rs.b_outer | rs.out_outer) % 4 == 0;
     if (aligned && (sh.d == 4 || sh.d == 8 || sh.d == 16)) {
         const dim3 grid4(unsigned((sh.S / 4 + 255) / 256 < 4096 ? (sh.S / 4 + 255) / 256 : 4096), by);
         if (sh.d == 4) hipLaunchKernelGGL((sig_combine_vec4_kernel<T, 4>), grid4, block, 0, st, sh, rs, a, b, out);

@@ -51,7 +51,8 @@ hipError_t launch_generic_f64(const Shape &sh, const double *path, double *out, 
 
 // Group product of two batches of signatures (any d, N with S < 2^31).
 bool combine_supported(const Shape &sh);
-// `strides`: distances in scalars between consecutive signatures of a, b, out; null = packed (S each).
+// `strides`: null = packed (S each), else 7 entries {a, b, out, n_inner, a_outer, b_outer, out_outer}: product
+// p = q * n_inner + i reads a + q * a_outer + i * a (likewise b, out); n_inner = 0 means no outer level.
 hipError_t launch_combine_f32(const Shape &sh, const float *a, const float *b, float *out, hipStream_t st,
                               const int64_t *strides = nullptr);
 hipError_t launch_combine_f64(const Shape &sh, const double *a, const double *b, double *out, hipStream_t st,

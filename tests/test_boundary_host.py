@@ -170,6 +170,18 @@ def test_signature_invert_and_strided_combine_validation(lib):
     assert h(p, -1, p, 6, 2, 2, 2, sig.SIG_F32, p, 6, 0) == sig.SIG_ERR_INVALID_ARG
     assert h(p, 0, 0, 6, 2, 2, 2, sig.SIG_F32, p, 6, 0) == sig.SIG_ERR_INVALID_ARG
     assert h(0, 0, 0, 0, 0, 2, 2, sig.SIG_F32, 0, 6, 0) == sig.SIG_OK
+    m, mb = lib.sig_combine_many, lib.sig_combine_many_workspace_bytes
+    # sigs, B, n, d, N, dtype, out, workspace, workspace_bytes, hip_stream
+    assert mb(3, 1, 2, 2, sig.SIG_F32) == 0 and mb(3, 2, 2, 2, sig.SIG_F32) == 0
+    assert mb(3, 3, 2, 2, sig.SIG_F32) == 3 * 2 * 6 * 4                       # one round of 2 per row
+    assert mb(3, 9, 2, 2, sig.SIG_F64) == 3 * (5 + 3) * 6 * 8                 # rounds of 5 and 3, then reuse
+    assert mb(3, 0, 2, 2, sig.SIG_F32) == -1 and mb(3, 3, 2, 2, 9) == -1
+    assert m(p, 3, 0, 2, 2, sig.SIG_F32, p, 0, 0, 0) == sig.SIG_ERR_INVALID_ARG
+    assert m(p, 3, 3, 2, 2, sig.SIG_F32, p, 0, 0, 0) == sig.SIG_ERR_INVALID_ARG   # workspace missing
+    assert m(p, 3, 3, 2, 2, sig.SIG_F32, p, p, 100, 0) == sig.SIG_ERR_INVALID_ARG  # workspace short
+    assert m(0, 3, 2, 2, 2, sig.SIG_F32, p, 0, 0, 0) == sig.SIG_ERR_INVALID_ARG
+    assert m(p, 3, 2, 2, 32, sig.SIG_F32, p, 0, 0, 0) == sig.SIG_ERR_UNSUPPORTED
+    assert m(0, 0, 5, 2, 2, sig.SIG_F32, 0, 0, 0, 0) == sig.SIG_OK
 
 
 def test_lyndon_table_is_built_on_the_host(lib):

@@ -129,6 +129,33 @@ def test_strided_combine_reads_rows_of_stream_outputs():
     assert_levels_close(host(out2), want, 4, N, np.float64)
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("B,n,d,N", [(3, 1, 3, 3), (4, 2, 4, 4), (3, 3, 2, 5), (2, 5, 4, 5), (5, 8, 3, 4), (2, 11, 8, 3),
+                                     (1, 37, 5, 3)])
+def test_combine_many_joins_adjacent_intervals(B, n, d, N, dtype):
+    """Signatures of n consecutive pieces of a path, pieces of different lengths sharing their end points,
+    multiplied in order give the signature of the whole path (section 5.5)."""
+    rng = np.random.default_rng(B * 100 + n)
+    cuts = np.concatenate([[0], np.cumsum(rng.integers(1, 4, size=n))])
+    x = brownian_paths(B, int(cuts[-1]) + 1, d, seed=n + d).astype(np.float64)
+    pieces = np.stack([orc.signature(x[:, cuts[i]:cuts[i + 1] + 1], N) for i in range(n)], axis=1)   # [B, n, S]
+    got = host(sig.sig_combine_many(dev(pieces.astype(dtype)), d, N))
+    assert_levels_close(got, orc.signature(x, N), d, N, dtype)
+
+
+def test_combine_many_keeps_the_order_of_the_factors():
+    # the product does not commute: reversing the pieces must change the result
+    x = brownian_paths(2, 7, 3, seed=5).astype(np.float64)
+    N = 4
+    pieces = np.stack([orc.signature(x[:, 2 * i:2 * i + 3], N) for i in range(3)], axis=1)
+    fwd = host(sig.sig_combine_many(dev(pieces), 3, N))
+    rev = host(sig.sig_combine_many(dev(pieces[:, ::-1]), 3, N))
+    want_rev = np.stack([orc.group_mul(orc.group_mul(pieces[b, 2], pieces[b, 1], 3, N), pieces[b, 0], 3, N)
+                         for b in range(2)])
+    assert_levels_close(rev, want_rev, 3, N, np.float64)
+    assert np.linalg.norm(fwd - rev) > 1e-3 * np.linalg.norm(fwd)
+
+
 def assert_query_close(got, x, i, j, N, dt):
     """A query is a product of two long-prefix signatures whose terms largely cancel (section 4.2 ends with a
     warning about exactly this), so its rounding error scales with the factors, not with the result: per level,
