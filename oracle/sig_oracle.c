@@ -27,8 +27,8 @@
  * Pinned by tests/test_oracle_pins.py against closed forms, invariants, brute force from
  * the integral definition and a hand-computed example; the gradient (second half of the file)
  * by tests/test_oracle_backward_pins.py against finite differences of the pinned forward and
- * closed forms; the logarithm (third part) by tests/test_oracle_log_pins.py.  Nothing here is
- * "parity unpinned".
+ * closed forms; the logarithm and its gradient (third part) by tests/test_oracle_log_pins.py.
+ * Nothing here is "parity unpinned".
  *
  * SIG_ORACLE_MUTANT (never defined in a normal build) plants one deliberate mistake, numbered
  * below, so that tests/test_oracle_mutants.py can check that the pins notice each of them.
@@ -378,6 +378,59 @@ int sig_oracle_log(const double *x, int d, int N, double *out)
         for (int64_t i = 0; i < S; ++i) out[i] += sign * power[i] / div;
     }
     free(power); free(next);
+    return 0;
+}
+
+/* Adjoint of mul_no_unit: C = A * B (no constant terms), gC given; ADDS into gA and gB. */
+static void mul_no_unit_adjoint(const double *A, const double *B, const double *gC, int d, int N, double *gA, double *gB)
+{
+    for (int k = 2; k <= N; ++k)
+        for (int j = 1; j <= k - 1; ++j) {
+            const int m = k - j;
+            const double *gk = gC + level_offset(d, k);
+            const int64_t off_j = level_offset(d, j), off_m = level_offset(d, m);
+            const int64_t n_j = ipow64(d, j), n_m = ipow64(d, m);
+            for (int64_t u = 0; u < n_j; ++u)
+                for (int64_t v = 0; v < n_m; ++v) {
+                    const double g = gk[u * n_m + v];
+                    /* mutant 15: for the first factor the cotangent is read as if the word were split the other way
+                     * round (for both factors at once that would be the mirrored, equally valid, chain rule) */
+                    gA[off_j + u] += (SIG_ORACLE_MUTANT == 15 ? gk[v * n_j + u] : g) * B[off_m + v];
+                    gB[off_m + v] += A[off_j + u] * g;
+                }
+        }
+}
+
+/* Gradient through sig_oracle_log (the chain rule over its own steps; section 5.3 treats the logarithm as one more
+ * differentiable primitive): given g = dLoss/d log(1 + x), WRITES gx = dLoss/dx.  Every power x^m is kept, then the
+ * loop of sig_oracle_log is walked backwards.  Returns 0, or 2 if memory ran out. */
+int sig_oracle_log_backward(const double *x, const double *g, int d, int N, double *gx)
+{
+    const int64_t S = sig_oracle_channels(d, N);
+    if (S < 0) return 1;
+    double *powers = (double *)malloc(sizeof(double) * (size_t)S * (size_t)N);   /* powers[m-1] = x^m */
+    double *g_pow = (double *)calloc((size_t)S, sizeof(double));                 /* cotangent of the current power */
+    double *g_prev = (double *)calloc((size_t)S, sizeof(double));
+    if (!powers || !g_pow || !g_prev) {
+        free(powers); free(g_pow); free(g_prev);
+        return 2;
+    }
+    memcpy(powers, x, sizeof(double) * (size_t)S);
+    for (int m = 2; m <= N; ++m) mul_no_unit(powers + (size_t)(m - 2) * S, x, d, N, powers + (size_t)(m - 1) * S);
+    for (int64_t i = 0; i < S; ++i) gx[i] = 0.0;
+    /* out = sum_m sign_m x^m / m: the cotangent of x^m is sign_m g / m plus what x^{m+1} = x^m * x sends back */
+    for (int m = N; m >= 1; --m) {
+        const double sign = (m % 2 == 0) ? -1.0 : 1.0;
+        /* mutant 16: the 1/m of the series left out of the gradient */
+        const double div = (double)(SIG_ORACLE_MUTANT == 16 ? 1 : m);
+        for (int64_t i = 0; i < S; ++i) g_pow[i] += sign * g[i] / div;
+        if (m == 1) break;
+        for (int64_t i = 0; i < S; ++i) g_prev[i] = 0.0;
+        mul_no_unit_adjoint(powers + (size_t)(m - 2) * S, x, g_pow, d, N, g_prev, gx);
+        double *t = g_pow; g_pow = g_prev; g_prev = t;
+    }
+    for (int64_t i = 0; i < S; ++i) gx[i] += g_pow[i];   /* x^1 = x */
+    free(powers); free(g_pow); free(g_prev);
     return 0;
 }
 

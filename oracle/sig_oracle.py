@@ -53,6 +53,8 @@ def _declare(lib):
     lib.sig_oracle_backward_f64.argtypes = [dp, dp, i64, i64, i32, i32, i32, i32, dp, i32]
     lib.sig_oracle_log.restype = i32
     lib.sig_oracle_log.argtypes = [dp, i32, i32, dp]
+    lib.sig_oracle_log_backward.restype = i32
+    lib.sig_oracle_log_backward.argtypes = [dp, dp, i32, i32, dp]
     lib.sig_oracle_max_threads.restype = i32
     lib.sig_oracle_max_threads.argtypes = []
     return lib
@@ -203,6 +205,23 @@ def tensor_log(sig, d: int, N: int) -> np.ndarray:
     return out.reshape(a.shape)
 
 
+def tensor_log_backward(sig, grad_log, d: int, N: int) -> np.ndarray:
+    """Gradient with respect to `sig` `[..., S]` of a loss whose gradient with respect to `tensor_log(sig)` is `grad_log`."""
+    a = np.ascontiguousarray(sig, dtype=np.float64)
+    g = np.ascontiguousarray(grad_log, dtype=np.float64)
+    S = channels(d, N)
+    if a.shape[-1] != S or g.shape != a.shape:
+        raise ValueError(f"sig and grad_log must both end in {S} channels and agree in shape")
+    flat, gflat = a.reshape(-1, S), g.reshape(-1, S)
+    out = np.empty_like(flat)
+    lib = _load()
+    for r in range(flat.shape[0]):
+        rc = lib.sig_oracle_log_backward(_dptr(flat[r]), _dptr(gflat[r]), d, N, _dptr(out[r]))
+        if rc != 0:
+            raise RuntimeError(f"sig_oracle_log_backward failed with code {rc}")
+    return out.reshape(a.shape)
+
+
 def lyndon_words(d: int, N: int):
     """All Lyndon words over d letters of length 1..N as tuples of 0-based letters, by length and then
     lexicographically: a word is Lyndon when it is strictly earlier than each of its proper rotations
@@ -236,3 +255,15 @@ def logsignature(path, N: int, stream: bool = False, basepoint: bool = False) ->
     d = x.shape[2]
     full = tensor_log(signature(x, N, stream, basepoint), d, N)
     return full[..., lyndon_indices(d, N)]
+
+
+def logsignature_backward(path, grad_out, N: int, stream: bool = False, basepoint: bool = False) -> np.ndarray:
+    """Gradient with respect to the path of a loss whose gradient with respect to `logsignature(path, ...)` is
+    `grad_out`: the selection of Lyndon words, the logarithm and the signature transposed in turn."""
+    x = np.ascontiguousarray(path, dtype=np.float64)
+    d = x.shape[2]
+    g = np.ascontiguousarray(grad_out, dtype=np.float64)
+    sig = signature(x, N, stream, basepoint)
+    g_log = np.zeros_like(sig)
+    g_log[..., lyndon_indices(d, N)] = g
+    return signature_backward(x, tensor_log_backward(sig, g_log, d, N), N, stream, basepoint)

@@ -153,3 +153,60 @@ def test_stream_and_basepoint_logsignatures_are_logs_of_the_prefix_signatures():
     for j in range(6):
         want = orc.tensor_log(orc.signature(x[:, :j + 1], 4, basepoint=True), 2, 4)[:, idx]
         np.testing.assert_allclose(ls[:, j], want, rtol=1e-13, atol=1e-15)
+
+
+# ---- gradient of the logarithm ------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("d,N", [(2, 2), (2, 5), (3, 4), (4, 3), (1, 4)])
+def test_log_gradient_matches_finite_differences_of_the_pinned_log(d, N):
+    # any element x (not only signatures): the adjoint must reproduce <g, d log(1 + x)[v]> for every direction v
+    rng = np.random.default_rng(10 * d + N)
+    S = orc.channels(d, N)
+    x, g = 0.6 * rng.standard_normal(S), rng.standard_normal(S)
+    gx = orc.tensor_log_backward(x, g, d, N)
+    h = 1e-6
+    for _ in range(6):
+        v = rng.standard_normal(S)
+        fd = np.dot(g, orc.tensor_log(x + h * v, d, N) - orc.tensor_log(x - h * v, d, N)) / (2 * h)
+        assert abs(np.dot(gx, v) - fd) <= 1e-8 * (1 + abs(fd))
+    # and coordinate by coordinate at the lowest and the highest level
+    for i in list(range(min(d, 3))) + [S - 1]:
+        e = np.zeros(S)
+        e[i] = h
+        fd = np.dot(g, orc.tensor_log(x + e, d, N) - orc.tensor_log(x - e, d, N)) / (2 * h)
+        assert abs(gx[i] - fd) <= 1e-8 * (1 + abs(fd))
+
+
+def test_log_gradient_closed_form_at_depth_two():
+    # log(1 + x) = (x_1, x_2 - x_1 (x) x_1 / 2)  =>  gx_2 = g_2,  gx_1 = g_1 - (g_2 x_1 + g_2^T x_1) / 2
+    d = 3
+    rng = np.random.default_rng(4)
+    x, g = rng.standard_normal(d + d * d), rng.standard_normal(d + d * d)
+    g2 = g[d:].reshape(d, d)
+    want = np.concatenate([g[:d] - 0.5 * (g2 @ x[:d] + g2.T @ x[:d]), g[d:]])
+    np.testing.assert_allclose(orc.tensor_log_backward(x, g, d, 2), want, rtol=0, atol=1e-14)
+
+
+def test_logsignature_gradient_of_a_single_segment_sees_only_level_one():
+    # log Sig of a straight segment is (z, 0, ..., 0) for every z, so only the cotangent of the letters reaches the
+    # two end points, with opposite signs; the cotangents of all longer Lyndon words are annihilated
+    d, N = 3, 4
+    rng = np.random.default_rng(8)
+    path = rng.standard_normal((2, 2, d))
+    g = rng.standard_normal((2, len(orc.lyndon_indices(d, N))))
+    got = orc.logsignature_backward(path, g, N)
+    np.testing.assert_allclose(got[:, 1], g[:, :d], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(got[:, 0], -g[:, :d], rtol=0, atol=1e-13)
+
+
+def test_logsignature_gradient_matches_finite_differences():
+    d, N = 2, 4
+    x = brownian_paths(2, 6, d, seed=3).astype(np.float64) * 2.0
+    rng = np.random.default_rng(2)
+    g = rng.standard_normal((2, 5, len(orc.lyndon_indices(d, N))))
+    got = orc.logsignature_backward(x, g, N, stream=True)
+    h = 1e-6
+    for _ in range(5):
+        v = rng.standard_normal(x.shape)
+        fd = np.sum(g * (orc.logsignature(x + h * v, N, stream=True) - orc.logsignature(x - h * v, N, stream=True))) / (2 * h)
+        assert abs(np.sum(got * v) - fd) <= 1e-8 * (1 + abs(fd))

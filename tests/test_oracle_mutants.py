@@ -24,6 +24,8 @@ MUTANTS = {
     12: "gradient: wrong sign at the lower end point of an increment",
     13: "logarithm: every term after the first subtracted",
     14: "logarithm: the cube divided by 2 instead of 3",
+    15: "logarithm gradient: cotangent of a product read with the word split the other way round, for the first factor only",
+    16: "logarithm gradient: the 1/m of the series left out",
 }
 
 
