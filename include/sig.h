@@ -209,6 +209,28 @@ sig_status sig_lyndon_indices(int d, int N, int64_t *indices, int64_t capacity);
 sig_status sig_lyndon_gather(const void *log_sig, int64_t rows, int d, int N, const int64_t *indices, int64_t n,
                              sig_dtype dtype, void *out, hipStream_t hip_stream);
 
+/* Gradient through sig_log (section 5.3 treats every operation as a differentiable primitive; the paper's
+ * benchmarks time the logsignature backwards as well): given grad_log = dLoss/d sig_log(sig), writes
+ * grad_sig = dLoss/d sig.  Deterministic: partial sums are added in a fixed order, no atomics.
+ *   sig, grad_log  DEVICE pointers [rows][S], read only.   grad_sig  DEVICE pointer [rows][S], overwritten; must
+ *              not overlap the other two.
+ *   workspace  DEVICE pointer, 16-byte aligned, at least sig_log_backward_workspace_bytes(...) bytes (0 for N = 1,
+ *              then it may be NULL); contents undefined on return.
+ * Errors as for sig_combine; a missing, short or misaligned workspace is SIG_ERR_INVALID_ARG. */
+sig_status sig_log_backward(const void *sig, const void *grad_log, int64_t rows, int d, int N, sig_dtype dtype,
+                            void *grad_sig, void *workspace, int64_t workspace_bytes, hipStream_t hip_stream);
+
+/* Bytes of workspace sig_log_backward needs; -1 on invalid arguments or S >= 2^31. */
+int64_t sig_log_backward_workspace_bytes(int64_t rows, int d, int N, sig_dtype dtype);
+
+/* Transpose of sig_lyndon_gather: grad_log[r][indices[i]] = grad_logsig[r][i], every other scalar of grad_log 0
+ * (the words that are not Lyndon words do not reach the logsignature, appendix A.2.4).
+ *   grad_logsig  DEVICE pointer [rows][n];  indices  DEVICE pointer to n distinct offsets in [0, S);
+ *   grad_log     DEVICE pointer [rows][S], overwritten.
+ * Errors as for sig_lyndon_gather. */
+sig_status sig_lyndon_scatter(const void *grad_logsig, int64_t rows, int d, int N, const int64_t *indices, int64_t n,
+                              sig_dtype dtype, void *grad_log, hipStream_t hip_stream);
+
 /* Gradient of a scalar loss with respect to the path, given its gradient with respect to the output of
  * sig_forward (or sig_signature without `initial` and `inverse`) called with the same arguments (section 5.3;
  * appendix C).  Nothing from the forward pass is kept but its output: each earlier signature is recovered from the

@@ -27,9 +27,12 @@ from .binding import (  # noqa: F401
     sig_combine_strided,
     sig_invert,
     sig_log,
+    sig_log_backward,
+    sig_log_backward_workspace_bytes,
     sig_logsignature,
     sig_logsignature_channels,
     sig_lyndon_gather,
+    sig_lyndon_scatter,
     sig_lyndon_indices,
     sig_signature,
     sig_forward,
@@ -48,6 +51,18 @@ def signature(path, depth, stream=False, basepoint=False, inverse=False):
     """Differentiable signature (torch.autograd); see `autograd.signature`."""
     from .autograd import signature as _signature
     return _signature(path, depth, stream, basepoint, inverse)
+
+
+def logsignature(path, depth, stream=False, basepoint=False, inverse=False, mode="words"):
+    """Differentiable logsignature (torch.autograd); see `autograd.logsignature`."""
+    from .autograd import logsignature as _logsignature
+    return _logsignature(path, depth, stream, basepoint, inverse, mode)
+
+
+def signature_to_logsignature(sig, channels, depth, mode="words"):
+    """Differentiable logsignature of given signatures; see `autograd.signature_to_logsignature`."""
+    from .autograd import signature_to_logsignature as _s2l
+    return _s2l(sig, channels, depth, mode)
 
 
 def __getattr__(name):

@@ -39,6 +39,9 @@ EXPORTED_SYMBOLS = (
     "sig_logsignature_channels",
     "sig_lyndon_indices",
     "sig_lyndon_gather",
+    "sig_lyndon_scatter",
+    "sig_log_backward",
+    "sig_log_backward_workspace_bytes",
     "sig_signature",
     "sig_backward_workspace_bytes",
     "sig_variant_name",
@@ -96,6 +99,12 @@ def load_library() -> ctypes.CDLL:
         lib.sig_logsignature_channels.argtypes = [i32, i32]
         lib.sig_lyndon_indices.restype = i32
         lib.sig_lyndon_indices.argtypes = [i32, i32, ctypes.POINTER(i64), i64]
+        lib.sig_lyndon_scatter.restype = i32
+        lib.sig_lyndon_scatter.argtypes = [vp, i64, i32, i32, vp, i64, i32, vp, vp]
+        lib.sig_log_backward.restype = i32
+        lib.sig_log_backward.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp, i64, vp]
+        lib.sig_log_backward_workspace_bytes.restype = i64
+        lib.sig_log_backward_workspace_bytes.argtypes = [i64, i32, i32, i32]
         lib.sig_lyndon_gather.restype = i32
         lib.sig_lyndon_gather.argtypes = [vp, i64, i32, i32, vp, i64, i32, vp, vp]
         lib.sig_invert.restype = i32
@@ -460,6 +469,71 @@ def sig_lyndon_gather(log_sig, d: int, N: int, out=None):
     with torch.cuda.device(log_sig.device):
         status = int(load_library().sig_lyndon_gather(log_sig.data_ptr(), rows, d, N, table.data_ptr(), n, dtype,
                                                       out.data_ptr(), torch.cuda.current_stream().cuda_stream))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return out
+
+
+def sig_lyndon_scatter(grad_logsig, d: int, N: int, out=None):
+    """Transpose of `sig_lyndon_gather`: `[..., w(d, N)]` -> `[..., S]`, zero at every word that is not a Lyndon word."""
+    import torch
+
+    _check_gpu("sig_lyndon_scatter", grad_logsig)
+    dtype = _dtype_of(grad_logsig)
+    S = sig_signature_channels(d, N)
+    table = _lyndon_table(d, N, grad_logsig.device)
+    n = table.numel()
+    if S < 0 or grad_logsig.shape[-1] != n or not grad_logsig.is_contiguous():
+        raise ValueError(f"grad_logsig must be contiguous with {n} channels last")
+    shape = tuple(grad_logsig.shape[:-1]) + (S,)
+    if out is None:
+        out = torch.empty(shape, dtype=grad_logsig.dtype, device=grad_logsig.device)
+    elif out.dtype != grad_logsig.dtype or out.device != grad_logsig.device or tuple(out.shape) != shape \
+            or not out.is_contiguous():
+        raise ValueError(f"out must be a contiguous tensor of shape {shape}")
+    rows = out.numel() // S
+    with torch.cuda.device(out.device):
+        status = int(load_library().sig_lyndon_scatter(grad_logsig.data_ptr(), rows, d, N, table.data_ptr(), n, dtype,
+                                                       out.data_ptr(), torch.cuda.current_stream().cuda_stream))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return out
+
+
+def sig_log_backward_workspace_bytes(rows: int, d: int, N: int, dtype: int = SIG_F32) -> int:
+    return int(load_library().sig_log_backward_workspace_bytes(rows, d, N, dtype))
+
+
+def sig_log_backward(sig, grad_log, d: int, N: int, out=None, workspace=None):
+    """Gradient with respect to signatures `sig` `[..., S]` of a loss whose gradient with respect to
+    `sig_log(sig, d, N)` is `grad_log`; `workspace` (uint8, GPU) is allocated through torch if not given."""
+    import torch
+
+    _check_gpu("sig_log_backward", sig)
+    dtype = _dtype_of(sig)
+    S = sig_signature_channels(d, N)
+    if S < 0 or sig.shape[-1] != S or not sig.is_contiguous():
+        raise ValueError(f"sig must be contiguous with {S} channels last")
+    if grad_log.dtype != sig.dtype or grad_log.device != sig.device or grad_log.shape != sig.shape \
+            or not grad_log.is_contiguous():
+        raise ValueError("grad_log must match sig")
+    if out is None:
+        out = torch.empty_like(sig)
+    elif out.dtype != sig.dtype or out.device != sig.device or out.shape != sig.shape or not out.is_contiguous() \
+            or out.data_ptr() in (sig.data_ptr(), grad_log.data_ptr()):
+        raise ValueError("out must match sig and be a different tensor")
+    rows = sig.numel() // S
+    lib = load_library()
+    with torch.cuda.device(sig.device):
+        need = int(lib.sig_log_backward_workspace_bytes(rows, d, N, dtype))
+        if need < 0:
+            raise SigError(SIG_ERR_UNSUPPORTED, "no workspace size for this shape")
+        if workspace is None and need > 0:
+            workspace = torch.empty(need, dtype=torch.uint8, device=sig.device)
+        ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) \
+            if workspace is not None else (0, 0)
+        status = int(lib.sig_log_backward(sig.data_ptr(), grad_log.data_ptr(), rows, d, N, dtype, out.data_ptr(), ws_ptr,
+                                          ws_bytes, torch.cuda.current_stream().cuda_stream))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out

@@ -464,6 +464,54 @@ sig_status sig_lyndon_gather(const void *log_sig, int64_t rows, int d, int N, co
     return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
 }
 
+int64_t sig_log_backward_workspace_bytes(int64_t rows, int d, int N, sig_dtype dtype)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return -1;
+    sig::Shape sh;
+    if (make_rows_shape(rows, d, N, sh) != SIG_OK || !sig::combine_supported(sh)) return -1;
+    return sig::log_backward_workspace_bytes(sh, dtype);
+}
+
+sig_status sig_log_backward(const void *sig, const void *grad_log, int64_t rows, int d, int N, sig_dtype dtype,
+                            void *grad_sig, void *workspace, int64_t workspace_bytes, hipStream_t hip_stream)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
+    sig::Shape sh;
+    const sig_status st = make_rows_shape(rows, d, N, sh);
+    if (st != SIG_OK) return st;
+    if (rows == 0) return SIG_OK;
+    if (sig == nullptr || grad_log == nullptr || grad_sig == nullptr || grad_sig == sig || grad_sig == grad_log)
+        return SIG_ERR_INVALID_ARG;
+    if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
+    const int64_t need = sig::log_backward_workspace_bytes(sh, dtype);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16 != 0))
+        return SIG_ERR_INVALID_ARG;
+    const hipError_t err =
+        dtype == SIG_F32 ? sig::launch_log_backward_f32(sh, static_cast<const float *>(sig), static_cast<const float *>(grad_log),
+                                                        static_cast<float *>(grad_sig), workspace, hip_stream)
+                         : sig::launch_log_backward_f64(sh, static_cast<const double *>(sig), static_cast<const double *>(grad_log),
+                                                        static_cast<double *>(grad_sig), workspace, hip_stream);
+    return err == hipSuccess ? SIG_OK : err == hipErrorNotSupported ? SIG_ERR_UNSUPPORTED : SIG_ERR_HIP;
+}
+
+sig_status sig_lyndon_scatter(const void *grad_logsig, int64_t rows, int d, int N, const int64_t *indices, int64_t n,
+                              sig_dtype dtype, void *grad_log, hipStream_t hip_stream)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
+    sig::Shape sh;
+    const sig_status st = make_rows_shape(rows, d, N, sh);
+    if (st != SIG_OK) return st;
+    if (n < 0 || n > sh.S) return SIG_ERR_INVALID_ARG;
+    if (rows == 0) return SIG_OK;
+    if (grad_log == nullptr || (n > 0 && (grad_logsig == nullptr || indices == nullptr))) return SIG_ERR_INVALID_ARG;
+    const hipError_t err =
+        dtype == SIG_F32 ? sig::launch_scatter_f32(sh, static_cast<const float *>(grad_logsig), indices, n,
+                                                   static_cast<float *>(grad_log), hip_stream)
+                         : sig::launch_scatter_f64(sh, static_cast<const double *>(grad_logsig), indices, n,
+                                                   static_cast<double *>(grad_log), hip_stream);
+    return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
 sig_status sig_signature(const void *path, int64_t B, int64_t L, int d, int N, int stream, int basepoint,
                          const void *basepoint_value, const void *initial, int inverse, sig_dtype dtype,
                          void *out, hipStream_t hip_stream)

@@ -84,6 +84,15 @@ hipError_t launch_gather_f32(const Shape &sh, const float *in, const int64_t *in
 hipError_t launch_gather_f64(const Shape &sh, const double *in, const int64_t *index, int64_t n, double *out, hipStream_t st);
 int64_t lyndon_indices_host(const Shape &sh, int64_t *indices, int64_t cap);
 
+// Gradient through the logarithm (sh.B rows; S < 2^31) and through the selection of the Lyndon words.
+int64_t log_backward_workspace_bytes(const Shape &sh, sig_dtype dtype);
+hipError_t launch_log_backward_f32(const Shape &sh, const float *sig, const float *grad_log, float *grad_sig, void *workspace,
+                                   hipStream_t st);
+hipError_t launch_log_backward_f64(const Shape &sh, const double *sig, const double *grad_log, double *grad_sig, void *workspace,
+                                   hipStream_t st);
+hipError_t launch_scatter_f32(const Shape &sh, const float *in, const int64_t *index, int64_t n, float *out, hipStream_t st);
+hipError_t launch_scatter_f64(const Shape &sh, const double *in, const int64_t *index, int64_t n, double *out, hipStream_t st);
+
 // Register-resident gradient kernel: fp32, d = 4, N = 4..6, 16-byte aligned buffers; needs no workspace.
 bool backward_d4_supported(const Shape &sh);
 hipError_t launch_backward_d4_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,

@@ -1,0 +1,432 @@
+// Gradient through the logarithm of signatures (the logarithm of section 2.3 as one more differentiable
+// primitive, section 5.3) and through the selection of the Lyndon words (appendix A.2.4).
+//
+// The forward value is Horner's rule  R_N = c_N x,  R_m = c_m x + x * R_{m+1},  log = R_1  (x the signature
+// without its constant term, c_m = (-1)^{m+1} / m, * the product of elements without constant terms, R_m kept
+// at levels 1..N-m+1).  Its reverse, with G_m the cotangent of R_m and G_1 the incoming gradient:
+//     gx       += c_m G_m
+//     gx[u]    += sum_v G_m[u v] R_{m+1}[v]        (every split of a word into a prefix u and a suffix v)
+//     G_{m+1}[v] = sum_u x[u] G_m[u v]
+// for m = 1..N-1, and gx += c_N G_N at the end.
+//
+// Layout makes both sums matrix-vector products.  In a flat element the levels l+1..n of G, read from the
+// offset of level l+1, ARE a row-major matrix M_l with d^l columns whose row number is the flat position of
+// the prefix u (levels 1..n-l of x or gx) and whose column is the suffix v (level l).  So per step and per l:
+//     a_l = x[0 .. U_l)^T M_l  -> level l of G_{m+1},        b_l = M_l R_{m+1, level l}  -> added into gx[0 .. U_l).
+// One launch per step walks every M_l once, in contiguous pieces: column sums stay in the lanes, row dots are
+// reduced inside a wavefront.  Pieces of one matrix go to different workgroups, which write partial sums; a
+// second launch adds them up in a fixed order (no atomics: the result does not depend on scheduling).
+// The R_m are recomputed first, one launch per m, into the workspace.
+#include "sig_internal.h"
+#include "sig_lane_ops.h"
+
+namespace sig {
+namespace {
+
+constexpr int kLbThreads = 256;
+constexpr int kLbWideRows = 16;   // rows a workgroup covers in a matrix with more than 256 columns
+
+struct LbLevel {               // the matrix M_l of one step
+    uint32_t C;                // columns, d^l
+    uint32_t U;                // rows, S(n - l)
+    uint32_t base;             // where the matrix starts inside G: offset of level l + 1
+    uint32_t wg_start;         // first workgroup (of those serving one batch row) that works on it
+    uint32_t wide;             // 0: C <= 256, several rows per pass; 1: 256 columns per workgroup, a row at a time
+    uint32_t rows_per_wg;
+    uint32_t tiles;            // column tiles (1 unless wide)
+    uint32_t chunks;           // row chunks = partial column sums per column
+    uint32_t rpw;              // narrow: rows per pass
+    uint32_t lg_tpr;           // narrow: log2 of the lanes that share one row dot
+    int64_t apart_off, bpart_off;   // where its partial sums start inside a batch row's share of the buffers
+};
+
+struct LbStep {
+    int count;                 // matrices: l = 1..count, G has count + 1 levels
+    uint32_t wgs;              // workgroups per batch row
+    uint32_t S_next, S_cur;    // S(n - 1), S(n)
+    int64_t apart_stride, bpart_stride;   // per batch row
+    LbLevel lv[SIG_MAX_DEPTH];
+};
+
+template <typename T>
+__device__ __forceinline__ T lanes_sum(T s, uint32_t lg)   // sum over aligned groups of 2^lg lanes (lg <= 6)
+{
+    switch (lg) {
+        case 1: return group_sum<0, 1, T>(s);
+        case 2: return group_sum<0, 2, T>(s);
+        case 3: return group_sum<0, 3, T>(s);
+        case 4: return group_sum<0, 4, T>(s);
+        case 5: return group_sum<0, 5, T>(s);
+        case 6: return group_sum<0, 6, T>(s);
+    }
+    return s;
+}
+
+// R_m = c_m x + x * R_{m+1} at levels 1..n (n = N - m + 1); R_{m+1} null for m = N.  One thread per scalar.
+template <typename T, int D>
+__global__ void __launch_bounds__(kLbThreads)
+log_bwd_horner_kernel(Shape sh, int n, T c_m, const T *__restrict__ x, const T *__restrict__ r_next, T *__restrict__ r_out,
+                      int64_t r_stride)
+{
+    const uint32_t d = D > 0 ? uint32_t(D) : uint32_t(sh.d);
+    const int64_t S_n = sh.off[n + 1];
+    const int64_t gid = int64_t(blockIdx.x) * kLbThreads + threadIdx.x;
+    if (gid >= sh.B * S_n) return;
+    const int64_t row = gid / S_n;
+    const uint32_t q = uint32_t(gid - row * S_n);
+    int k = 1;
+    while (k < n && q >= uint32_t(sh.off[k + 1])) ++k;
+    const T *xr = x + row * sh.S;
+    T acc = c_m * xr[q];
+    if (r_next != nullptr) {
+        const T *rr = r_next + row * r_stride;
+        uint32_t prefix = q - uint32_t(sh.off[k]), suffix = 0, scale = 1;
+        for (int j = k - 1; j >= 1; --j) {
+            const uint32_t letter = prefix % d;
+            prefix /= d;
+            suffix += letter * scale;
+            scale *= d;
+            acc += xr[uint32_t(sh.off[j]) + prefix] * rr[uint32_t(sh.off[k - j]) + suffix];
+        }
+    }
+    r_out[row * r_stride + q] = acc;
+}
+
+// One step: partial column sums (x^T M_l) and row dots (M_l R_l) of every matrix of the step.
+template <typename T>
+__global__ void __launch_bounds__(kLbThreads)
+log_bwd_main_kernel(LbStep stp, const T *__restrict__ x, int64_t x_stride, const T *__restrict__ G, int64_t g_stride,
+                    const T *__restrict__ R, int64_t r_stride, T *__restrict__ apart, T *__restrict__ bpart)
+{
+    __shared__ T prod[2][kLbThreads];
+    __shared__ T wsum[kLbWideRows][kLbThreads / 64];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t wg = blockIdx.x % stp.wgs;
+    const int64_t row = blockIdx.x / stp.wgs;
+    int li = 0;
+    for (int i = 1; i < stp.count; ++i)
+        if (wg >= stp.lv[i].wg_start) li = i;
+    const LbLevel lv = stp.lv[li];
+    const uint32_t C = lv.C, U = lv.U;
+    const T *xr = x + row * x_stride;
+    const T *M = G + row * g_stride + lv.base;
+    const T *Rl = R + row * r_stride + (lv.base - C);   // level l of R_{m+1}
+    T *ap = apart + row * stp.apart_stride + lv.apart_off;
+    T *bp = bpart + row * stp.bpart_stride + lv.bpart_off;
+    const uint32_t w = wg - lv.wg_start;
+
+    if (lv.wide == 0) {
+        const uint32_t rpw = lv.rpw;
+        const bool on = tid < rpw * C;
+        const uint32_t prow = on ? tid / C : 0, col = on ? tid - prow * C : 0;
+        const T rl = on ? Rl[col] : T(0);
+        const uint32_t row0 = w * lv.rows_per_wg;
+        const uint32_t row_end = row0 + lv.rows_per_wg < U ? row0 + lv.rows_per_wg : U;
+        const uint32_t tpr = 1u << lv.lg_tpr;
+        const uint32_t srow = tid >> lv.lg_tpr, sub = tid & (tpr - 1);
+        T acc = T(0);
+        int buf = 0;
+        for (uint32_t r = row0; r < row_end; r += rpw, buf ^= 1) {
+            const uint32_t mine = r + prow;
+            T g = T(0);
+            if (on && mine < row_end) {
+                g = M[uint64_t(mine) * C + col];
+                acc += xr[mine] * g;
+            }
+            prod[buf][tid] = g * rl;
+            __syncthreads();
+            // row dots: 2^lg_tpr lanes per row, each over a strided share of the row's products
+            T s = T(0);
+            if (srow < rpw)
+                for (uint32_t c = sub; c < C; c += tpr) s += prod[buf][srow * C + c];
+            s = lanes_sum(s, lv.lg_tpr);
+            if (sub == 0 && srow < rpw && r + srow < row_end) bp[r + srow] = s;
+        }
+        // column sums: fold the rows of a pass
+        __syncthreads();
+        prod[0][tid] = acc;
+        __syncthreads();
+        if (tid < C) {
+            T s = T(0);
+            for (uint32_t p = 0; p < rpw; ++p) s += prod[0][p * C + tid];
+            ap[uint64_t(w) * C + tid] = s;
+        }
+    } else {
+        const uint32_t tile = w % lv.tiles, chunk = w / lv.tiles;
+        const uint32_t col = tile * kLbThreads + tid;
+        const bool on = col < C;
+        const T rl = on ? Rl[col] : T(0);
+        const uint32_t row0 = chunk * lv.rows_per_wg;
+        const uint32_t row_end = row0 + lv.rows_per_wg < U ? row0 + lv.rows_per_wg : U;
+        T acc = T(0);
+        for (uint32_t r = row0; r < row_end; ++r) {
+            const T g = on ? M[uint64_t(r) * C + col] : T(0);
+            acc += xr[r] * g;
+            const T s = group_sum<0, 6, T>(g * rl);
+            if ((tid & 63) == 0) wsum[r - row0][tid >> 6] = s;
+        }
+        __syncthreads();
+        if (tid < row_end - row0) {
+            T s = wsum[tid][0];
+            for (int v = 1; v < kLbThreads / 64; ++v) s += wsum[tid][v];
+            bp[uint64_t(tile) * U + row0 + tid] = s;
+        }
+        if (on) ap[uint64_t(chunk) * C + col] = acc;
+    }
+}
+
+// Adds the partial sums of a step: G_{m+1} (unless this is the last step) and gx.
+//   first: gx is written, not added to.   last: G_{m+1} = G_N has one level and goes straight into gx with c_N.
+template <typename T>
+__global__ void __launch_bounds__(kLbThreads)
+log_bwd_finish_kernel(LbStep stp, int64_t rows, T c_m, T c_last, int first, int last, const T *__restrict__ G,
+                      int64_t g_stride, const T *__restrict__ apart, const T *__restrict__ bpart, T *__restrict__ G_next,
+                      int64_t gn_stride, T *__restrict__ gx, int64_t gx_stride)
+{
+    const int64_t per_row = int64_t(stp.S_next) + stp.S_cur;
+    const int64_t gid = int64_t(blockIdx.x) * kLbThreads + threadIdx.x;
+    if (gid >= rows * per_row) return;
+    const int64_t row = gid / per_row;
+    const uint32_t q = uint32_t(gid - row * per_row);
+    const T *ap = apart + row * stp.apart_stride;
+    const T *bp = bpart + row * stp.bpart_stride;
+    if (q < stp.S_next) {
+        if (last) return;
+        int li = 0;   // the level of G_{m+1} this scalar lies in: offset of level l = base_l - C_l
+        for (int i = 1; i < stp.count; ++i)
+            if (q >= stp.lv[i].base - stp.lv[i].C) li = i;
+        const LbLevel lv = stp.lv[li];
+        const uint32_t v = q - (lv.base - lv.C);
+        const T *p = ap + lv.apart_off + v;
+        T s = T(0);
+        for (uint32_t k = 0; k < lv.chunks; ++k) s += p[uint64_t(k) * lv.C];
+        G_next[row * gn_stride + q] = s;
+        return;
+    }
+    const uint32_t rho = q - stp.S_next;
+    T val = c_m * G[row * g_stride + rho];
+    if (!first) val += gx[row * gx_stride + rho];
+    for (int i = 0; i < stp.count; ++i) {
+        const uint32_t U = stp.lv[i].U;
+        if (rho >= U) break;   // U shrinks as l grows
+        const T *p = bp + stp.lv[i].bpart_off + rho;
+        const uint32_t tiles = stp.lv[i].tiles;
+        for (uint32_t t = 0; t < tiles; ++t) val += p[uint64_t(t) * U];
+    }
+    if (last && rho < stp.lv[0].C) {
+        const T *p = ap + stp.lv[0].apart_off + rho;
+        T s = T(0);
+        for (uint32_t k = 0; k < stp.lv[0].chunks; ++k) s += p[uint64_t(k) * stp.lv[0].C];
+        val += c_last * s;
+    }
+    gx[row * gx_stride + rho] = val;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(kLbThreads)
+fill_zero_kernel(T *__restrict__ p, int64_t n)
+{
+    for (int64_t i = int64_t(blockIdx.x) * kLbThreads + threadIdx.x; i < n; i += int64_t(gridDim.x) * kLbThreads) p[i] = T(0);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(kLbThreads)
+scatter_kernel(const T *__restrict__ in, const int64_t *__restrict__ index, int64_t n, int64_t rows, T *__restrict__ out,
+               int64_t out_stride)
+{
+    for (int64_t r = blockIdx.y; r < rows; r += gridDim.y)
+        for (int64_t i = int64_t(blockIdx.x) * kLbThreads + threadIdx.x; i < n; i += int64_t(gridDim.x) * kLbThreads)
+            out[r * out_stride + index[i]] = in[r * n + i];
+}
+
+int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+// The work of the step whose cotangent G has n levels (n >= 2).
+LbStep plan_step(const Shape &sh, int n)
+{
+    LbStep stp{};
+    stp.count = n - 1;
+    stp.S_next = uint32_t(sh.off[n]);
+    stp.S_cur = uint32_t(sh.off[n + 1]);
+    uint32_t wg = 0;
+    int64_t a_off = 0, b_off = 0;
+    for (int l = 1; l <= n - 1; ++l) {
+        LbLevel &lv = stp.lv[l - 1];
+        lv.C = uint32_t(sh.pw[l]);
+        lv.U = uint32_t(sh.off[n - l + 1]);
+        lv.base = uint32_t(sh.off[l + 1]);
+        lv.wg_start = wg;
+        if (lv.C <= uint32_t(kLbThreads)) {
+            lv.wide = 0;
+            lv.rpw = uint32_t(kLbThreads) / lv.C;
+            uint32_t tpr = uint32_t(kLbThreads) / lv.rpw;
+            tpr = tpr > 64 ? 64 : tpr;
+            lv.lg_tpr = 0;
+            while ((2u << lv.lg_tpr) <= tpr) ++lv.lg_tpr;
+            const uint32_t groups = (lv.U + lv.rpw - 1) / lv.rpw;
+            uint32_t passes = (groups + 63) / 64;
+            passes = passes < 4 ? 4 : passes;
+            lv.rows_per_wg = passes * lv.rpw;
+            lv.tiles = 1;
+            lv.chunks = (lv.U + lv.rows_per_wg - 1) / lv.rows_per_wg;
+            wg += lv.chunks;
+        } else {
+            lv.wide = 1;
+            lv.rpw = 1;
+            lv.lg_tpr = 0;
+            lv.rows_per_wg = lv.U < uint32_t(kLbWideRows) ? lv.U : uint32_t(kLbWideRows);
+            lv.tiles = (lv.C + kLbThreads - 1) / kLbThreads;
+            lv.chunks = (lv.U + lv.rows_per_wg - 1) / lv.rows_per_wg;
+            wg += lv.tiles * lv.chunks;
+        }
+        lv.apart_off = a_off;
+        lv.bpart_off = b_off;
+        a_off += int64_t(lv.chunks) * lv.C;
+        b_off += int64_t(lv.tiles) * lv.U;
+    }
+    stp.wgs = wg;
+    stp.apart_stride = a_off;
+    stp.bpart_stride = b_off;
+    return stp;
+}
+
+struct LbWorkspace {
+    int64_t r_stride;    // scalars of R_2..R_N per batch row
+    int64_t g_stride;    // S(N - 1)
+    int64_t r_off, g0_off, g1_off, a_off, b_off, total;   // in bytes
+};
+
+LbWorkspace plan_workspace(const Shape &sh, int64_t elem)
+{
+    LbWorkspace ws{};
+    for (int n = 1; n <= sh.N - 1; ++n) ws.r_stride += sh.off[n + 1];
+    ws.g_stride = sh.N >= 2 ? sh.off[sh.N] : 0;
+    const LbStep first = sh.N >= 2 ? plan_step(sh, sh.N) : LbStep{};
+    int64_t at = 0;
+    auto take = [&](int64_t scalars) {
+        const int64_t here = at;
+        at += round_up(scalars * sh.B * elem, 256);
+        return here;
+    };
+    ws.r_off = take(ws.r_stride);
+    ws.g0_off = take(ws.g_stride);
+    ws.g1_off = take(ws.g_stride);
+    ws.a_off = take(first.apart_stride);
+    ws.b_off = take(first.bpart_stride);
+    ws.total = at;
+    return ws;
+}
+
+// offset, inside a batch row's share of the R buffer, of R_m (m = 2..N): R_N first
+int64_t r_offset(const Shape &sh, int m)
+{
+    int64_t off = 0;
+    for (int mm = sh.N; mm > m; --mm) off += sh.off[sh.N - mm + 2];
+    return off;
+}
+
+template <typename T, int D>
+void launch_horner(const Shape &sh, int n, T c_m, const T *x, const T *r_next, T *r_out, int64_t r_stride, hipStream_t st)
+{
+    const int64_t threads = sh.B * sh.off[n + 1];
+    hipLaunchKernelGGL((log_bwd_horner_kernel<T, D>), dim3(unsigned((threads + kLbThreads - 1) / kLbThreads)), dim3(kLbThreads),
+                       0, st, sh, n, c_m, x, r_next, r_out, r_stride);
+}
+
+template <typename T>
+hipError_t launch_log_backward(const Shape &sh, const T *x, const T *g, T *gx, void *workspace, hipStream_t st)
+{
+    const int N = sh.N;
+    if (N == 1) return hipMemcpyAsync(gx, g, size_t(sh.B * sh.S) * sizeof(T), hipMemcpyDeviceToDevice, st);
+    const LbWorkspace ws = plan_workspace(sh, int64_t(sizeof(T)));
+    char *base = static_cast<char *>(workspace);
+    T *Rs = reinterpret_cast<T *>(base + ws.r_off);
+    T *Gb[2] = {reinterpret_cast<T *>(base + ws.g0_off), reinterpret_cast<T *>(base + ws.g1_off)};
+    T *apart = reinterpret_cast<T *>(base + ws.a_off);
+    T *bpart = reinterpret_cast<T *>(base + ws.b_off);
+    auto coef = [](int m) { return (m & 1 ? T(1) : T(-1)) / T(m); };
+
+    for (int m = N; m >= 2; --m) {
+        const int n = N - m + 1;
+        const T *r_next = m == N ? nullptr : Rs + r_offset(sh, m + 1);
+        T *r_out = Rs + r_offset(sh, m);
+        switch (sh.d) {
+            case 2: launch_horner<T, 2>(sh, n, coef(m), x, r_next, r_out, ws.r_stride, st); break;
+            case 3: launch_horner<T, 3>(sh, n, coef(m), x, r_next, r_out, ws.r_stride, st); break;
+            case 4: launch_horner<T, 4>(sh, n, coef(m), x, r_next, r_out, ws.r_stride, st); break;
+            case 5: launch_horner<T, 5>(sh, n, coef(m), x, r_next, r_out, ws.r_stride, st); break;
+            case 6: launch_horner<T, 6>(sh, n, coef(m), x, r_next, r_out, ws.r_stride, st); break;
+            case 7: launch_horner<T, 7>(sh, n, coef(m), x, r_next, r_out, ws.r_stride, st); break;
+            case 8: launch_horner<T, 8>(sh, n, coef(m), x, r_next, r_out, ws.r_stride, st); break;
+            default: launch_horner<T, 0>(sh, n, coef(m), x, r_next, r_out, ws.r_stride, st); break;
+        }
+        const hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+    for (int m = 1; m <= N - 1; ++m) {
+        const int n = N - m + 1;
+        const LbStep stp = plan_step(sh, n);
+        const T *G = m == 1 ? g : Gb[m & 1];
+        const int64_t g_stride = m == 1 ? sh.S : ws.g_stride;
+        T *G_next = Gb[(m + 1) & 1];
+        const int64_t wgs = sh.B * int64_t(stp.wgs);
+        if (wgs > 0x7fffffff) return hipErrorNotSupported;
+        hipLaunchKernelGGL((log_bwd_main_kernel<T>), dim3(unsigned(wgs)), dim3(kLbThreads), 0, st, stp, x, sh.S, G, g_stride,
+                           Rs + r_offset(sh, m + 1), ws.r_stride, apart, bpart);
+        hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
+        const int64_t threads = sh.B * (int64_t(stp.S_next) + stp.S_cur);
+        hipLaunchKernelGGL((log_bwd_finish_kernel<T>), dim3(unsigned((threads + kLbThreads - 1) / kLbThreads)), dim3(kLbThreads),
+                           0, st, stp, sh.B, coef(m), coef(N), int(m == 1), int(m == N - 1), G, g_stride, apart, bpart, G_next,
+                           ws.g_stride, gx, sh.S);
+        err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+    return hipSuccess;
+}
+
+template <typename T>
+hipError_t launch_scatter(const Shape &sh, const T *in, const int64_t *index, int64_t n, T *out, hipStream_t st)
+{
+    const int64_t total = sh.B * sh.S;
+    const int64_t fill_groups = (total + kLbThreads - 1) / kLbThreads;
+    hipLaunchKernelGGL((fill_zero_kernel<T>), dim3(unsigned(fill_groups < 65536 ? fill_groups : 65536)), dim3(kLbThreads), 0, st,
+                       out, total);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess || n == 0) return err;
+    const unsigned bx = unsigned((n + kLbThreads - 1) / kLbThreads < 4096 ? (n + kLbThreads - 1) / kLbThreads : 4096);
+    const unsigned by = unsigned(sh.B < 65535 ? sh.B : 65535);
+    hipLaunchKernelGGL((scatter_kernel<T>), dim3(bx, by), dim3(kLbThreads), 0, st, in, index, n, sh.B, out, sh.S);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+int64_t log_backward_workspace_bytes(const Shape &sh, sig_dtype dtype)
+{
+    return plan_workspace(sh, dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double))).total;
+}
+
+hipError_t launch_log_backward_f32(const Shape &sh, const float *sig, const float *grad_log, float *grad_sig, void *workspace,
+                                   hipStream_t st)
+{
+    return launch_log_backward<float>(sh, sig, grad_log, grad_sig, workspace, st);
+}
+
+hipError_t launch_log_backward_f64(const Shape &sh, const double *sig, const double *grad_log, double *grad_sig, void *workspace,
+                                   hipStream_t st)
+{
+    return launch_log_backward<double>(sh, sig, grad_log, grad_sig, workspace, st);
+}
+
+hipError_t launch_scatter_f32(const Shape &sh, const float *in, const int64_t *index, int64_t n, float *out, hipStream_t st)
+{
+    return launch_scatter<float>(sh, in, index, n, out, st);
+}
+
+hipError_t launch_scatter_f64(const Shape &sh, const double *in, const int64_t *index, int64_t n, double *out, hipStream_t st)
+{
+    return launch_scatter<double>(sh, in, index, n, out, st);
+}
+
+}  // namespace sig
