@@ -66,7 +66,7 @@ def main() -> int:
     ap.add_argument("--shape", default=None, metavar="B,L,d,N[,stream]",
                     help="a shape of your own instead of one of the five workloads (same input recipe, seed index 0), "
                          "e.g. 32,128,7,7 for the largest case of the paper's benchmark grid")
-    ap.add_argument("--op", choices=["forward", "backward", "combine", "logsignature"], default="forward")
+    ap.add_argument("--op", choices=["forward", "backward", "combine", "logsignature", "logsignature_backward"], default="forward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 256 MiB device-to-device copies before the timed region, so that "
@@ -131,6 +131,25 @@ def main() -> int:
             sig.sig_forward(x, w.N, stream=w.stream, basepoint=w.basepoint, out=out, variant=variant)
             sig.sig_log(out, w.d, w.N, out=log_full)
             sig.sig_lyndon_gather(log_full, w.d, w.N, out=log_words)
+    elif args.op == "logsignature_backward":
+        step()
+        n_words = sig.sig_logsignature_channels(w.d, w.N)
+        rows = int(np.prod(out_shape[:-1]))
+        grad_words = torch.from_numpy(np.random.default_rng(w.seed).standard_normal(out_shape[:-1] + (n_words,))
+                                      .astype(np.float32)).to(dev)
+        grad_log = torch.empty_like(out)
+        grad_sig = torch.empty_like(out)
+        grad_path = torch.empty_like(x)
+        ws_log = torch.empty(max(sig.sig_log_backward_workspace_bytes(rows, w.d, w.N), 16), dtype=torch.uint8, device=dev)
+        ws_sig = torch.empty(max(sig.sig_backward_workspace_bytes(w.B, w.L, w.d, w.N, w.stream, w.basepoint), 16),
+                             dtype=torch.uint8, device=dev)
+        kernel = "scatter+log_backward+backward"
+
+        def step():  # noqa: F811
+            sig.sig_lyndon_scatter(grad_words, w.d, w.N, out=grad_log)
+            sig.sig_log_backward(out, grad_log, w.d, w.N, out=grad_sig, workspace=ws_log)
+            sig.sig_backward(x, out, grad_sig, w.N, stream=w.stream, basepoint=w.basepoint, grad_path=grad_path,
+                             workspace=ws_sig)
     elif args.op == "combine":
         step()
         lhs = out.reshape(-1, S)
@@ -188,6 +207,13 @@ def main() -> int:
         flops += 2 * rows * sum((k - 1) * w.d ** k for m in range(1, w.N + 1) for k in range(2, w.N - m + 2))
         bytes_io = 4 * (w.B * w.L * w.d + rows * n_words)
         metric = "logsignatures/sec (paths/s)"
+    elif args.op == "logsignature_backward":
+        # signature gradient, the R_m of Horner's rule again, and two multiply-adds per scalar of every matrix M_l
+        flops = w.B * w.n_inc * backward_flops_per_increment(w.d, w.N, M, S)
+        flops += 2 * rows * sum((k - 1) * w.d ** k for m in range(2, w.N + 1) for k in range(2, w.N - m + 2))
+        flops += 2 * rows * sum(2 * (k - 1) * w.d ** k for m in range(1, w.N) for k in range(2, w.N - m + 2))
+        bytes_io = 4 * (2 * w.B * w.L * w.d + int(np.prod(out_shape)) + rows * n_words)
+        metric = "logsignature gradients/sec (paths/s)"
     elif args.op == "combine":
         units = int(lhs.shape[0])
         flops = 2 * units * sum((k - 1) * w.d ** k for k in range(2, w.N + 1))
@@ -239,6 +265,10 @@ def main() -> int:
             n_sample = max(1, n_sample // 4)
             xs = x_host[:n_sample]
             gs = grad_out[:n_sample].cpu().numpy()
+        elif args.op == "logsignature_backward":
+            n_sample = max(1, n_sample // 8)
+            xs = x_host[:n_sample]
+            gs = grad_words[:n_sample].cpu().numpy()
         elif args.op == "combine":
             n_sample = int(max(1, min(units, 4e9 // max((w.N - 1) * w.d ** w.N, 1))))
             la, lb = lhs[:n_sample].cpu().numpy().astype(np.float64), rhs[:n_sample].cpu().numpy().astype(np.float64)
@@ -251,6 +281,8 @@ def main() -> int:
                     sig_oracle.group_mul(la[i], lb[i], w.d, w.N)
             elif args.op == "logsignature":
                 sig_oracle.logsignature(xs, w.N, stream=w.stream, basepoint=w.basepoint)
+            elif args.op == "logsignature_backward":
+                sig_oracle.logsignature_backward(xs, gs, w.N, stream=w.stream, basepoint=w.basepoint)
             else:
                 sig_oracle.signature(xs, w.N, stream=w.stream, basepoint=w.basepoint)
 
@@ -269,6 +301,7 @@ def main() -> int:
                 "backward": "fp64 exp + group product per increment and their adjoints over the stored forward, OpenMP over paths",
                 "combine": "fp64 group product, one pair at a time on one core",
                 "logsignature": "fp64 signature (OpenMP over paths), then the power series of log one row at a time on one core",
+                "logsignature_backward": "fp64 signature and its stored-forward gradient (OpenMP over paths), the power series of log and its adjoint one row at a time on one core",
             }[args.op] + f", best of {passes} passes ({best:.3f} s each, {spent:.1f} s in all)",
         }
 

@@ -24,14 +24,16 @@ namespace sig {
 namespace {
 
 constexpr int kLbThreads = 256;
-constexpr int kLbWideRows = 16;   // rows a workgroup covers in a matrix with more than 256 columns
+constexpr int kLbWideRows = 16;   // rows between two workgroup barriers in a matrix with more than 256 columns
+constexpr int kLbWideCols = 8;    // columns per lane there: a workgroup spans 2048 columns
+constexpr uint32_t kLbMaxPartials = 32;   // partial sums per output the planner aims for
 
 struct LbLevel {               // the matrix M_l of one step
     uint32_t C;                // columns, d^l
     uint32_t U;                // rows, S(n - l)
     uint32_t base;             // where the matrix starts inside G: offset of level l + 1
     uint32_t wg_start;         // first workgroup (of those serving one batch row) that works on it
-    uint32_t wide;             // 0: C <= 256, several rows per pass; 1: 256 columns per workgroup, a row at a time
+    uint32_t wide;             // 0: C <= 256, several rows per pass; 1: 2048 columns per workgroup, a row at a time
     uint32_t rows_per_wg;
     uint32_t tiles;            // column tiles (1 unless wide)
     uint32_t chunks;           // row chunks = partial column sums per column
@@ -153,25 +155,45 @@ log_bwd_main_kernel(LbStep stp, const T *__restrict__ x, int64_t x_stride, const
         }
     } else {
         const uint32_t tile = w % lv.tiles, chunk = w / lv.tiles;
-        const uint32_t col = tile * kLbThreads + tid;
-        const bool on = col < C;
-        const T rl = on ? Rl[col] : T(0);
+        const uint32_t col0 = tile * (kLbThreads * kLbWideCols) + tid;   // this lane's columns: col0 + 256 v
+        T rl[kLbWideCols], acc[kLbWideCols];
+#pragma unroll
+        for (int v = 0; v < kLbWideCols; ++v) {
+            const uint32_t col = col0 + v * kLbThreads;
+            rl[v] = col < C ? Rl[col] : T(0);
+            acc[v] = T(0);
+        }
         const uint32_t row0 = chunk * lv.rows_per_wg;
         const uint32_t row_end = row0 + lv.rows_per_wg < U ? row0 + lv.rows_per_wg : U;
-        T acc = T(0);
-        for (uint32_t r = row0; r < row_end; ++r) {
-            const T g = on ? M[uint64_t(r) * C + col] : T(0);
-            acc += xr[r] * g;
-            const T s = group_sum<0, 6, T>(g * rl);
-            if ((tid & 63) == 0) wsum[r - row0][tid >> 6] = s;
+        for (uint32_t rb = row0; rb < row_end; rb += kLbWideRows) {
+            const uint32_t rb_end = rb + kLbWideRows < row_end ? rb + kLbWideRows : row_end;
+            for (uint32_t r = rb; r < rb_end; ++r) {
+                const T *mrow = M + uint64_t(r) * C;
+                const T xv = xr[r];
+                T s = T(0);
+#pragma unroll
+                for (int v = 0; v < kLbWideCols; ++v) {
+                    const uint32_t col = col0 + v * kLbThreads;
+                    const T g = col < C ? mrow[col] : T(0);
+                    acc[v] += xv * g;
+                    s += g * rl[v];
+                }
+                s = group_sum<0, 6, T>(s);
+                if ((tid & 63) == 0) wsum[r - rb][tid >> 6] = s;
+            }
+            __syncthreads();
+            if (tid < rb_end - rb) {
+                T s = wsum[tid][0];
+                for (int v = 1; v < kLbThreads / 64; ++v) s += wsum[tid][v];
+                bp[uint64_t(tile) * U + rb + tid] = s;
+            }
+            __syncthreads();
         }
-        __syncthreads();
-        if (tid < row_end - row0) {
-            T s = wsum[tid][0];
-            for (int v = 1; v < kLbThreads / 64; ++v) s += wsum[tid][v];
-            bp[uint64_t(tile) * U + row0 + tid] = s;
+#pragma unroll
+        for (int v = 0; v < kLbWideCols; ++v) {
+            const uint32_t col = col0 + v * kLbThreads;
+            if (col < C) ap[uint64_t(chunk) * C + col] = acc[v];
         }
-        if (on) ap[uint64_t(chunk) * C + col] = acc;
     }
 }
 
@@ -199,6 +221,7 @@ log_bwd_finish_kernel(LbStep stp, int64_t rows, T c_m, T c_last, int first, int 
         const uint32_t v = q - (lv.base - lv.C);
         const T *p = ap + lv.apart_off + v;
         T s = T(0);
+#pragma unroll 8
         for (uint32_t k = 0; k < lv.chunks; ++k) s += p[uint64_t(k) * lv.C];
         G_next[row * gn_stride + q] = s;
         return;
@@ -211,6 +234,7 @@ log_bwd_finish_kernel(LbStep stp, int64_t rows, T c_m, T c_last, int first, int 
         if (rho >= U) break;   // U shrinks as l grows
         const T *p = bp + stp.lv[i].bpart_off + rho;
         const uint32_t tiles = stp.lv[i].tiles;
+#pragma unroll 8
         for (uint32_t t = 0; t < tiles; ++t) val += p[uint64_t(t) * U];
     }
     if (last && rho < stp.lv[0].C) {
@@ -264,7 +288,7 @@ LbStep plan_step(const Shape &sh, int n)
             lv.lg_tpr = 0;
             while ((2u << lv.lg_tpr) <= tpr) ++lv.lg_tpr;
             const uint32_t groups = (lv.U + lv.rpw - 1) / lv.rpw;
-            uint32_t passes = (groups + 63) / 64;
+            uint32_t passes = (groups + kLbMaxPartials - 1) / kLbMaxPartials;
             passes = passes < 4 ? 4 : passes;
             lv.rows_per_wg = passes * lv.rpw;
             lv.tiles = 1;
@@ -274,8 +298,10 @@ LbStep plan_step(const Shape &sh, int n)
             lv.wide = 1;
             lv.rpw = 1;
             lv.lg_tpr = 0;
-            lv.rows_per_wg = lv.U < uint32_t(kLbWideRows) ? lv.U : uint32_t(kLbWideRows);
-            lv.tiles = (lv.C + kLbThreads - 1) / kLbThreads;
+            lv.rows_per_wg = (lv.U + kLbMaxPartials - 1) / kLbMaxPartials;
+            lv.rows_per_wg = lv.rows_per_wg < uint32_t(kLbWideRows) ? uint32_t(kLbWideRows) : lv.rows_per_wg;
+            lv.rows_per_wg = lv.rows_per_wg < lv.U ? lv.rows_per_wg : lv.U;
+            lv.tiles = (lv.C + kLbThreads * kLbWideCols - 1) / (kLbThreads * kLbWideCols);
             lv.chunks = (lv.U + lv.rows_per_wg - 1) / lv.rows_per_wg;
             wg += lv.tiles * lv.chunks;
         }
