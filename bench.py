@@ -9,7 +9,8 @@ HIP events, and the CPU oracle timed on the host cores beside it.
 
 `--op backward` times `sig_backward` (the gradient with respect to the path) and `--op combine`
 times `sig_combine` (the group product of two batches of signatures) and `--op logsignature` the
-forward pass followed by `sig_log` and `sig_lyndon_gather`, on the same workload shapes instead; the default, and the metric this repository is judged on, is the forward pass.
+forward pass followed by `sig_log` and `sig_lyndon_gather`, `--op logsignature_backward` the gradient of that
+(`sig_lyndon_scatter`, `sig_log_backward`, `sig_backward`), on the same workload shapes instead; the default, and the metric this repository is judged on, is the forward pass.
 """
 from __future__ import annotations
 
