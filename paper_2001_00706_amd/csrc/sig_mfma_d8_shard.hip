@@ -26,6 +26,8 @@ namespace {
 
 constexpr int kD8 = 8;
 constexpr int kTile8 = 64;  // increments staged in LDS at a time
+constexpr int kCol8 = kTile8 + 4;   // floats between two columns of the staged table: 16-byte aligned, and the
+                                    // 16-byte reads of eight different columns fall into different LDS banks
 
 __host__ __device__ constexpr int level_off8(int k)  // offset of level k (1-based) in a d = 8 signature
 {
@@ -53,7 +55,7 @@ struct State8 {
 // A_3[w_3] for k = 4..N, is tabulated in LDS next to the increment.  Every one of the 64 shards of a path
 // would otherwise repeat that arithmetic in each lane at each increment.
 //
-// Row of the table for one increment: z[0..7], then T_k^(3)[0..7] for k = 4..N.
+// Columns of the table: z[0..7], then T_k^(3)[0..7] / (k - 3) for k = 4..N; kTile8 increments per column.
 template <int N>
 constexpr int kRow8 = kD8 * (N - 2);
 
@@ -93,23 +95,55 @@ __device__ __forceinline__ float pick8(f4 a, f4 b, int i)
     return (i & 2) ? hi : lo;
 }
 
-// One fused multiply-exponentiate restricted to the words of this shard, levels 4..N.  `row` is the table row
-// of the increment.
+// One fused multiply-exponentiate restricted to the words of this shard, levels 4..N, needs from the table of
+// its increment z[w_4], z[q], z[4 + q] and t3[k] = T_k^(3)[w_3] / (k - 3) for k = 4..N (the divisor of the next
+// Horner step is folded into the table).  The table is stored column by column (kTile8 increments per column, kCol8 floats apart),
+// so one 16-byte LDS read brings a column's entries of four consecutive increments.
 template <int N>
 struct Row8 {
     float z4, zlo, zhi;
-    float t3[N + 1];   // T_k^(3)[w_3], k = 4..N
+    float t3[N + 1];
 };
 
 template <int N>
-__device__ __forceinline__ Row8<N> load_row8(const float *row, int w3, int w4, int q)
+struct Rows8 {   // four consecutive increments
+    f4 z4, zlo, zhi;
+    f4 t3[N + 1];
+};
+
+template <int N>
+__device__ __forceinline__ Row8<N> load_row8(const float *tab, int s, int w3, int w4, int q)
 {
     Row8<N> R;
-    R.z4 = row[w4];
-    R.zlo = row[q];
-    R.zhi = row[4 + q];
+    R.z4 = tab[w4 * kCol8 + s];
+    R.zlo = tab[q * kCol8 + s];
+    R.zhi = tab[(4 + q) * kCol8 + s];
 #pragma unroll
-    for (int k = 4; k <= N; ++k) R.t3[k] = row[kD8 * (k - 3) + w3];
+    for (int k = 4; k <= N; ++k) R.t3[k] = tab[(kD8 * (k - 3) + w3) * kCol8 + s];
+    return R;
+}
+
+template <int N>
+__device__ __forceinline__ Rows8<N> load_rows8(const float *tab, int s, int w3, int w4, int q)   // s a multiple of 4
+{
+    Rows8<N> R;
+    R.z4 = *reinterpret_cast<const f4 *>(tab + w4 * kCol8 + s);
+    R.zlo = *reinterpret_cast<const f4 *>(tab + q * kCol8 + s);
+    R.zhi = *reinterpret_cast<const f4 *>(tab + (4 + q) * kCol8 + s);
+#pragma unroll
+    for (int k = 4; k <= N; ++k) R.t3[k] = *reinterpret_cast<const f4 *>(tab + (kD8 * (k - 3) + w3) * kCol8 + s);
+    return R;
+}
+
+template <int N>
+__device__ __forceinline__ Row8<N> pick_row8(const Rows8<N> &V, int i)
+{
+    Row8<N> R;
+    R.z4 = V.z4[i];
+    R.zlo = V.zlo[i];
+    R.zhi = V.zhi[i];
+#pragma unroll
+    for (int k = 4; k <= N; ++k) R.t3[k] = V.t3[k][i];
     return R;
 }
 
@@ -118,7 +152,7 @@ __device__ __forceinline__ void step8(State8<N> &S, const Row8<N> &R)
 {
     float t4[N + 1];
 #pragma unroll
-    for (int k = 4; k <= N; ++k) t4[k] = __builtin_fmaf(R.t3[k], k == 4 ? R.z4 : R.z4 * (1.0f / (k - 3)), S.A4);
+    for (int k = 4; k <= N; ++k) t4[k] = __builtin_fmaf(R.t3[k], R.z4, S.A4);
 
     if constexpr (N >= 5) {
         if constexpr (N >= 6) {
@@ -153,7 +187,7 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
     static_assert(N >= 4 && N <= 6, "depths served by this kernel");
     constexpr int kRow = kRow8<N>;
     constexpr int kS = level_off8(N + 1);
-    __shared__ __align__(16) float lds[kTile8 * kRow];
+    __shared__ __align__(16) float lds[kCol8 * kRow];
 
     const int lane = threadIdx.x;
     const int w3 = lane >> 3, w4 = lane & 7, q = lane & 3;
@@ -232,30 +266,44 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
                 const float a3 = A3[w] + wave_exclusive_scan(t2[3] * zw, lane, sum3);
                 A3[w] += sum3;
 #pragma unroll
-                for (int k = 4; k <= N; ++k) tab[k][w >> 2][w & 3] = __builtin_fmaf(t2[k], zw * (1.0f / (k - 2)), a3);
+                for (int k = 4; k <= N; ++k)
+                    tab[k][w >> 2][w & 3] = __builtin_fmaf(t2[k], zw * (1.0f / (k - 2)), a3) * (1.0f / (k - 3));
             }
             if (lane < nt) {
-                f4 *row = reinterpret_cast<f4 *>(lds + lane * kRow);
-                row[0] = z0;
-                row[1] = z1;
 #pragma unroll
-                for (int k = 4; k <= N; ++k) {
-                    row[2 * (k - 3)] = tab[k][0];
-                    row[2 * (k - 3) + 1] = tab[k][1];
+                for (int w = 0; w < kD8; ++w) {
+                    lds[w * kCol8 + lane] = w < 4 ? z0[w & 3] : z1[w & 3];
+#pragma unroll
+                    for (int k = 4; k <= N; ++k) lds[(kD8 * (k - 3) + w) * kCol8 + lane] = tab[k][w >> 2][w & 3];
                 }
             }
         }
         __syncthreads();
         fetch_points(t0 + kTile8 + lane);
         int s = 0;
-        for (; s + 4 <= nt; s += 4) {
-            Row8<N> R[4];
+        if (nt >= 4) {
+            // four increments per LDS round trip, the next four fetched while these are folded in (two sets of
+            // registers taking turns, so that nothing is copied)
+            Rows8<N> V0 = load_rows8<N>(lds, 0, w3, w4, q);
+            for (; s + 12 <= nt; s += 8) {
+                const Rows8<N> V1 = load_rows8<N>(lds, s + 4, w3, w4, q);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) R[i] = load_row8<N>(lds + (s + i) * kRow, w3, w4, q);
+                for (int i = 0; i < 4; ++i) step8<N>(S, pick_row8<N>(V0, i));
+                V0 = load_rows8<N>(lds, s + 8, w3, w4, q);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) step8<N>(S, R[i]);
+                for (int i = 0; i < 4; ++i) step8<N>(S, pick_row8<N>(V1, i));
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) step8<N>(S, pick_row8<N>(V0, i));
+            s += 4;
+            if (s + 4 <= nt) {
+                const Rows8<N> V1 = load_rows8<N>(lds, s, w3, w4, q);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) step8<N>(S, pick_row8<N>(V1, i));
+                s += 4;
+            }
         }
-        for (; s < nt; ++s) step8<N>(S, load_row8<N>(lds + s * kRow, w3, w4, q));
+        for (; s < nt; ++s) step8<N>(S, load_row8<N>(lds, s, w3, w4, q));
     }
     // this lane's A_3[f w_3]
     float a3_mine = A3[0];
