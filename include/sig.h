@@ -162,6 +162,21 @@ sig_status sig_combine_many(const void *sigs, int64_t B, int64_t n, int d, int N
 /* Bytes of workspace sig_combine_many needs; -1 on invalid arguments. */
 int64_t sig_combine_many_workspace_bytes(int64_t B, int64_t n, int d, int N, sig_dtype dtype);
 
+/* Gradient through sig_combine (section 5.3: every operation is differentiable): given
+ * grad_out = dLoss/d(a [x] b), writes grad_a = dLoss/da and grad_b = dLoss/db,
+ *   grad_a[u] = grad_out[u] + sum_v grad_out[u v] b[v],   grad_b[v] = grad_out[v] + sum_u a[u] grad_out[u v]
+ * (u v: a word cut into a non-empty prefix and a non-empty suffix).  Deterministic (no atomics).
+ *   a, b, grad_out  DEVICE pointers [B][S], read only.   grad_a, grad_b  DEVICE pointers [B][S], overwritten; they
+ *              must differ from each other and from the inputs.
+ *   workspace  DEVICE pointer, 16-byte aligned, at least sig_combine_backward_workspace_bytes(...) bytes (0 for
+ *              N = 1, then it may be NULL); contents undefined on return.
+ * Errors as for sig_combine; a missing, short or misaligned workspace is SIG_ERR_INVALID_ARG. */
+sig_status sig_combine_backward(const void *a, const void *b, const void *grad_out, int64_t B, int d, int N, sig_dtype dtype,
+                                void *grad_a, void *grad_b, void *workspace, int64_t workspace_bytes, hipStream_t hip_stream);
+
+/* Bytes of workspace sig_combine_backward needs; -1 on invalid arguments or S >= 2^31. */
+int64_t sig_combine_backward_workspace_bytes(int64_t B, int d, int N, sig_dtype dtype);
+
 /* Group inverse of `rows` signatures: out[r] = sig[r]^{-1}, which is the signature of the same path traversed
  * backwards (section 5.4).  It is a signed permutation of the scalars: level k of the inverse holds
  * (-1)^k times the coefficient of the reversed word.

@@ -227,6 +227,14 @@ static void mul_adjoint(const double *A, const double *B, const double *gC, int 
     }
 }
 
+/* Gradient of one group product C = A [x] B: WRITES gA and gB given gC (the transpose of sig_oracle_mul). */
+void sig_oracle_mul_backward(const double *A, const double *B, const double *gC, int d, int N, double *gA, double *gB)
+{
+    const int64_t S = sig_oracle_channels(d, N);
+    for (int64_t i = 0; i < S; ++i) gA[i] = gB[i] = 0.0;
+    mul_adjoint(A, B, gC, d, N, gA, gB);
+}
+
 /* Adjoint of sig_oracle_exp: E_1 = z, E_k[w j] = E_{k-1}[w] z[j] / k.  gE is consumed (its lower
  * levels are used as accumulators); the gradient with respect to z is WRITTEN to gz. */
 static void exp_adjoint(const double *z, const double *E, double *gE, int d, int N, double *gz)

@@ -47,6 +47,8 @@ def _declare(lib):
     lib.sig_oracle_exp.argtypes = [dp, i32, i32, dp]
     lib.sig_oracle_mul.restype = None
     lib.sig_oracle_mul.argtypes = [dp, dp, i32, i32, dp]
+    lib.sig_oracle_mul_backward.restype = None
+    lib.sig_oracle_mul_backward.argtypes = [dp, dp, dp, i32, i32, dp, dp]
     lib.sig_oracle_forward_f64.restype = i32
     lib.sig_oracle_forward_f64.argtypes = [dp, i64, i64, i32, i32, i32, i32, dp, i32]
     lib.sig_oracle_backward_f64.restype = i32
@@ -131,6 +133,19 @@ def group_mul(A, B, d: int, N: int) -> np.ndarray:
     C = np.empty(S, dtype=np.float64)
     _load().sig_oracle_mul(_dptr(A), _dptr(B), d, N, _dptr(C))
     return C
+
+
+def group_mul_backward(A, B, gC, d: int, N: int):
+    """(gA, gB): gradients with respect to the two factors of `group_mul(A, B, d, N)`, given the gradient gC with
+    respect to the product (section 5.3)."""
+    A = np.ascontiguousarray(A, dtype=np.float64)
+    B = np.ascontiguousarray(B, dtype=np.float64)
+    gC = np.ascontiguousarray(gC, dtype=np.float64)
+    S = channels(d, N)
+    assert A.shape == (S,) and B.shape == (S,) and gC.shape == (S,)
+    gA, gB = np.empty(S), np.empty(S)
+    _load().sig_oracle_mul_backward(_dptr(A), _dptr(B), _dptr(gC), d, N, _dptr(gA), _dptr(gB))
+    return gA, gB
 
 
 def signature(path, N: int, stream: bool = False, basepoint: bool = False,

@@ -23,6 +23,8 @@ from .binding import (  # noqa: F401
     sig_backward,
     sig_backward_workspace_bytes,
     sig_combine,
+    sig_combine_backward,
+    sig_combine_backward_workspace_bytes,
     sig_combine_many,
     sig_combine_strided,
     sig_invert,
@@ -47,10 +49,22 @@ from .binding import (  # noqa: F401
 )
 
 
-def signature(path, depth, stream=False, basepoint=False, inverse=False):
+def signature(path, depth, stream=False, basepoint=False, inverse=False, initial=None):
     """Differentiable signature (torch.autograd); see `autograd.signature`."""
     from .autograd import signature as _signature
-    return _signature(path, depth, stream, basepoint, inverse)
+    return _signature(path, depth, stream, basepoint, inverse, initial)
+
+
+def signature_combine(sig1, sig2, channels, depth):
+    """Differentiable group product of two batches of signatures; see `autograd.signature_combine`."""
+    from .autograd import signature_combine as _combine
+    return _combine(sig1, sig2, channels, depth)
+
+
+def multi_signature_combine(sigs, channels, depth):
+    """Differentiable ordered product of a list of batches of signatures; see `autograd.multi_signature_combine`."""
+    from .autograd import multi_signature_combine as _combine
+    return _combine(sigs, channels, depth)
 
 
 def logsignature(path, depth, stream=False, basepoint=False, inverse=False, mode="words"):

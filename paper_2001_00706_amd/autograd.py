@@ -35,11 +35,76 @@ class _Signature(torch.autograd.Function):
         return grad_path, grad_bp, None, None, None, None
 
 
-def signature(path, depth: int, stream: bool = False, basepoint=False, inverse: bool = False):
-    """Depth-`depth` signature of a batch of paths `[B, L, d]` on the GPU, differentiable in `path`
-    and in `basepoint` when that is a `[B, d]` tensor (argument names as in section 5.5)."""
+class _Combine(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, a, b, channels, depth):
+        a, b = a.contiguous(), b.contiguous()
+        ctx.save_for_backward(a, b)
+        ctx.args = (channels, depth)
+        return binding.sig_combine(a, b, channels, depth)
+
+    @staticmethod
+    def backward(ctx, grad_out):
+        a, b = ctx.saved_tensors
+        channels, depth = ctx.args
+        grad_a, grad_b = binding.sig_combine_backward(a, b, grad_out.contiguous(), channels, depth)
+        return grad_a, grad_b, None, None
+
+
+def signature_combine(sig1, sig2, channels: int, depth: int):
+    """Group product `sig1 [x] sig2` of two batches of signatures `[B, S]` (section 5.5, "combining adjacent
+    intervals"), differentiable in both."""
+    return _Combine.apply(sig1, sig2, int(channels), int(depth))
+
+
+def multi_signature_combine(sigs, channels: int, depth: int):
+    """Ordered product of a list of batches of signatures `[B, S]`, differentiable in each: neighbours are joined
+    pairwise, in ceil(log2 n) rounds of products (the product is associative)."""
+    sigs = list(sigs)
+    if not sigs:
+        raise ValueError("at least one signature is needed")
+    while len(sigs) > 1:
+        joined = [signature_combine(sigs[i], sigs[i + 1], channels, depth) for i in range(0, len(sigs) - 1, 2)]
+        if len(sigs) % 2:
+            joined.append(sigs[-1])
+        sigs = joined
+    return sigs[0]
+
+
+def signature(path, depth: int, stream: bool = False, basepoint=False, inverse: bool = False, initial=None):
+    """Depth-`depth` signature of a batch of paths `[B, L, d]` on the GPU, differentiable in `path`,
+    in `basepoint` when that is a `[B, d]` tensor, and in `initial` (argument names as in section 5.5).
+
+    `initial` `[B, S]` is the signature of the data that came before; the result is `initial [x] Sig(path)`
+    (inverted as a whole if `inverse`).  With a gradient flowing into `initial` only final mode is served here
+    (in stream mode `sig_signature` applies it without a gradient)."""
     value = basepoint if isinstance(basepoint, torch.Tensor) else None
-    return _Signature.apply(path, value, int(depth), bool(stream), value is not None or bool(basepoint), bool(inverse))
+    flag = value is not None or bool(basepoint)
+    if initial is None:
+        return _Signature.apply(path, value, int(depth), bool(stream), flag, bool(inverse))
+    if stream:
+        if initial.requires_grad or path.requires_grad or (value is not None and value.requires_grad):
+            raise NotImplementedError("stream mode with `initial` is not differentiable here")
+        bp = value.contiguous() if value is not None else flag
+        return binding.sig_signature(path.contiguous(), int(depth), stream=True, basepoint=bp, inverse=bool(inverse),
+                                     initial=initial.contiguous())
+    d = path.shape[2]
+    joined = signature_combine(initial, _Signature.apply(path, value, int(depth), False, flag, False), d, depth)
+    return _Invert.apply(joined, d, int(depth)) if inverse else joined
+
+
+class _Invert(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, sig, channels, depth):
+        ctx.args = (channels, depth)
+        return binding.sig_invert(sig.contiguous(), channels, depth)
+
+    @staticmethod
+    def backward(ctx, grad_out):
+        # only used on signatures (group-like elements), where the inverse is a signed permutation of the scalars
+        # (section 5.4) and therefore its own transpose
+        channels, depth = ctx.args
+        return binding.sig_invert(grad_out.contiguous(), channels, depth), None, None
 
 
 class _SignatureToLogsignature(torch.autograd.Function):

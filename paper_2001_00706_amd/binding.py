@@ -32,6 +32,8 @@ EXPORTED_SYMBOLS = (
     "sig_combine",
     "sig_backward",
     "sig_combine_strided",
+    "sig_combine_backward",
+    "sig_combine_backward_workspace_bytes",
     "sig_combine_many",
     "sig_combine_many_workspace_bytes",
     "sig_invert",
@@ -87,6 +89,10 @@ def load_library() -> ctypes.CDLL:
         lib.sig_combine.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
         lib.sig_backward.restype = i32
         lib.sig_backward.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, i32, vp, i32, vp, vp, vp, i64, vp]
+        lib.sig_combine_backward.restype = i32
+        lib.sig_combine_backward.argtypes = [vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, i64, vp]
+        lib.sig_combine_backward_workspace_bytes.restype = i64
+        lib.sig_combine_backward_workspace_bytes.argtypes = [i64, i32, i32, i32]
         lib.sig_combine_many.restype = i32
         lib.sig_combine_many.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, i64, vp]
         lib.sig_combine_many_workspace_bytes.restype = i64
@@ -612,3 +618,47 @@ def sig_combine_many(sigs, d: int, N: int, out=None, workspace=None):
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out
+
+
+def sig_combine_backward_workspace_bytes(B: int, d: int, N: int, dtype: int = SIG_F32) -> int:
+    return int(load_library().sig_combine_backward_workspace_bytes(B, d, N, dtype))
+
+
+def sig_combine_backward(a, b, grad_out, d: int, N: int, grad_a=None, grad_b=None, workspace=None):
+    """Gradients `(grad_a, grad_b)` of a loss with respect to the factors of `sig_combine(a, b, d, N)`, given its
+    gradient `grad_out` with respect to the product; all `[B, S]`.  `workspace` (uint8, GPU) is allocated through
+    torch if not given."""
+    import torch
+
+    _check_gpu("sig_combine_backward", a)
+    dtype = _dtype_of(a)
+    S = sig_signature_channels(d, N)
+    if S < 0 or a.dim() != 2 or a.shape[1] != S:
+        raise ValueError(f"signatures of d={d}, N={N} are [B, {S}] tensors")
+    for t in (b, grad_out):
+        if not isinstance(t, torch.Tensor) or t.dtype != a.dtype or t.device != a.device or t.shape != a.shape:
+            raise ValueError("a, b and grad_out must agree in dtype, shape and device")
+    if not (a.is_contiguous() and b.is_contiguous() and grad_out.is_contiguous()):
+        raise ValueError("a, b and grad_out must be contiguous")
+    outs = []
+    for t in (grad_a, grad_b):
+        if t is None:
+            t = torch.empty_like(a)
+        elif t.dtype != a.dtype or t.device != a.device or t.shape != a.shape or not t.is_contiguous():
+            raise ValueError("grad_a and grad_b must match a")
+        outs.append(t)
+    lib = load_library()
+    with torch.cuda.device(a.device):
+        need = int(lib.sig_combine_backward_workspace_bytes(a.shape[0], d, N, dtype))
+        if need < 0:
+            raise SigError(SIG_ERR_UNSUPPORTED, "no workspace size for this shape")
+        if workspace is None and need > 0:
+            workspace = torch.empty(need, dtype=torch.uint8, device=a.device)
+        ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) \
+            if workspace is not None else (0, 0)
+        status = int(lib.sig_combine_backward(a.data_ptr(), b.data_ptr(), grad_out.data_ptr(), a.shape[0], d, N, dtype,
+                                              outs[0].data_ptr(), outs[1].data_ptr(), ws_ptr, ws_bytes,
+                                              torch.cuda.current_stream().cuda_stream))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return outs[0], outs[1]

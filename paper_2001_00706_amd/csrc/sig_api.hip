@@ -494,6 +494,37 @@ sig_status sig_log_backward(const void *sig, const void *grad_log, int64_t rows,
     return err == hipSuccess ? SIG_OK : err == hipErrorNotSupported ? SIG_ERR_UNSUPPORTED : SIG_ERR_HIP;
 }
 
+int64_t sig_combine_backward_workspace_bytes(int64_t B, int d, int N, sig_dtype dtype)
+{
+    return sig_log_backward_workspace_bytes(B, d, N, dtype);
+}
+
+sig_status sig_combine_backward(const void *a, const void *b, const void *grad_out, int64_t B, int d, int N, sig_dtype dtype,
+                                void *grad_a, void *grad_b, void *workspace, int64_t workspace_bytes, hipStream_t hip_stream)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
+    sig::Shape sh;
+    const sig_status st = make_rows_shape(B, d, N, sh);
+    if (st != SIG_OK) return st;
+    if (B == 0) return SIG_OK;
+    if (a == nullptr || b == nullptr || grad_out == nullptr || grad_a == nullptr || grad_b == nullptr || grad_a == grad_b ||
+        grad_a == grad_out || grad_b == grad_out || grad_a == a || grad_a == b || grad_b == a || grad_b == b)
+        return SIG_ERR_INVALID_ARG;
+    if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
+    const int64_t need = sig::log_backward_workspace_bytes(sh, dtype);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16 != 0))
+        return SIG_ERR_INVALID_ARG;
+    const hipError_t err =
+        dtype == SIG_F32
+            ? sig::launch_combine_backward_f32(sh, static_cast<const float *>(a), static_cast<const float *>(b),
+                                               static_cast<const float *>(grad_out), static_cast<float *>(grad_a),
+                                               static_cast<float *>(grad_b), workspace, hip_stream)
+            : sig::launch_combine_backward_f64(sh, static_cast<const double *>(a), static_cast<const double *>(b),
+                                               static_cast<const double *>(grad_out), static_cast<double *>(grad_a),
+                                               static_cast<double *>(grad_b), workspace, hip_stream);
+    return err == hipSuccess ? SIG_OK : err == hipErrorNotSupported ? SIG_ERR_UNSUPPORTED : SIG_ERR_HIP;
+}
+
 sig_status sig_lyndon_scatter(const void *grad_logsig, int64_t rows, int d, int N, const int64_t *indices, int64_t n,
                               sig_dtype dtype, void *grad_log, hipStream_t hip_stream)
 {

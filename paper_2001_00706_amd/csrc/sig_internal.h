@@ -90,6 +90,11 @@ hipError_t launch_log_backward_f32(const Shape &sh, const float *sig, const floa
                                    hipStream_t st);
 hipError_t launch_log_backward_f64(const Shape &sh, const double *sig, const double *grad_log, double *grad_sig, void *workspace,
                                    hipStream_t st);
+// Gradient of the group product out = a [x] b; same workspace as the logarithm's gradient.
+hipError_t launch_combine_backward_f32(const Shape &sh, const float *a, const float *b, const float *g, float *ga, float *gb,
+                                       void *workspace, hipStream_t st);
+hipError_t launch_combine_backward_f64(const Shape &sh, const double *a, const double *b, const double *g, double *ga, double *gb,
+                                       void *workspace, hipStream_t st);
 hipError_t launch_scatter_f32(const Shape &sh, const float *in, const int64_t *index, int64_t n, float *out, hipStream_t st);
 hipError_t launch_scatter_f64(const Shape &sh, const double *in, const int64_t *index, int64_t n, double *out, hipStream_t st);
 

@@ -199,13 +199,15 @@ log_bwd_main_kernel(LbStep stp, const T *__restrict__ x, int64_t x_stride, const
 
 // Adds the partial sums of a step: G_{m+1} (unless this is the last step) and gx.
 //   first: gx is written, not added to.   last: G_{m+1} = G_N has one level and goes straight into gx with c_N.
+//   plus_g: the column sums are the gradient of the right factor of a group product, whose unit term adds G
+//           itself at every level (G_next then has as many levels as G).
 template <typename T>
 __global__ void __launch_bounds__(kLbThreads)
-log_bwd_finish_kernel(LbStep stp, int64_t rows, T c_m, T c_last, int first, int last, const T *__restrict__ G,
+log_bwd_finish_kernel(LbStep stp, int64_t rows, T c_m, T c_last, int first, int last, int plus_g, const T *__restrict__ G,
                       int64_t g_stride, const T *__restrict__ apart, const T *__restrict__ bpart, T *__restrict__ G_next,
                       int64_t gn_stride, T *__restrict__ gx, int64_t gx_stride)
 {
-    const int64_t per_row = int64_t(stp.S_next) + stp.S_cur;
+    const int64_t per_row = int64_t(stp.S_next) + stp.S_cur + (plus_g ? stp.S_cur - stp.S_next : 0);
     const int64_t gid = int64_t(blockIdx.x) * kLbThreads + threadIdx.x;
     if (gid >= rows * per_row) return;
     const int64_t row = gid / per_row;
@@ -223,7 +225,13 @@ log_bwd_finish_kernel(LbStep stp, int64_t rows, T c_m, T c_last, int first, int 
         T s = T(0);
 #pragma unroll 8
         for (uint32_t k = 0; k < lv.chunks; ++k) s += p[uint64_t(k) * lv.C];
+        if (plus_g) s += G[row * g_stride + q];
         G_next[row * gn_stride + q] = s;
+        return;
+    }
+    if (q >= stp.S_next + stp.S_cur) {   // plus_g: the top level of G_next is that of G
+        const uint32_t top = q - stp.S_cur;
+        G_next[row * gn_stride + top] = G[row * g_stride + top];
         return;
     }
     const uint32_t rho = q - stp.S_next;
@@ -403,12 +411,40 @@ hipError_t launch_log_backward(const Shape &sh, const T *x, const T *g, T *gx, v
         if (err != hipSuccess) return err;
         const int64_t threads = sh.B * (int64_t(stp.S_next) + stp.S_cur);
         hipLaunchKernelGGL((log_bwd_finish_kernel<T>), dim3(unsigned((threads + kLbThreads - 1) / kLbThreads)), dim3(kLbThreads),
-                           0, st, stp, sh.B, coef(m), coef(N), int(m == 1), int(m == N - 1), G, g_stride, apart, bpart, G_next,
+                           0, st, stp, sh.B, coef(m), coef(N), int(m == 1), int(m == N - 1), 0, G, g_stride, apart, bpart, G_next,
                            ws.g_stride, gx, sh.S);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
     return hipSuccess;
+}
+
+// Gradient of out = a [x] b: grad_a[u] = g[u] + sum_v g[u v] b[v], grad_b[v] = g[v] + sum_u a[u] g[u v]: one step of the
+// scheme above with x = a, R = b, G = g and unit coefficients.
+template <typename T>
+hipError_t launch_combine_backward(const Shape &sh, const T *a, const T *b, const T *g, T *ga, T *gb, void *workspace,
+                                   hipStream_t st)
+{
+    if (sh.N == 1) {
+        hipError_t err = hipMemcpyAsync(ga, g, size_t(sh.B * sh.S) * sizeof(T), hipMemcpyDeviceToDevice, st);
+        if (err != hipSuccess) return err;
+        return hipMemcpyAsync(gb, g, size_t(sh.B * sh.S) * sizeof(T), hipMemcpyDeviceToDevice, st);
+    }
+    const LbWorkspace ws = plan_workspace(sh, int64_t(sizeof(T)));
+    char *base = static_cast<char *>(workspace);
+    T *apart = reinterpret_cast<T *>(base + ws.a_off);
+    T *bpart = reinterpret_cast<T *>(base + ws.b_off);
+    const LbStep stp = plan_step(sh, sh.N);
+    const int64_t wgs = sh.B * int64_t(stp.wgs);
+    if (wgs > 0x7fffffff) return hipErrorNotSupported;
+    hipLaunchKernelGGL((log_bwd_main_kernel<T>), dim3(unsigned(wgs)), dim3(kLbThreads), 0, st, stp, a, sh.S, g, sh.S, b, sh.S,
+                       apart, bpart);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    const int64_t threads = sh.B * 2 * int64_t(stp.S_cur);
+    hipLaunchKernelGGL((log_bwd_finish_kernel<T>), dim3(unsigned((threads + kLbThreads - 1) / kLbThreads)), dim3(kLbThreads), 0,
+                       st, stp, sh.B, T(1), T(0), 1, 0, 1, g, sh.S, apart, bpart, gb, sh.S, ga, sh.S);
+    return hipGetLastError();
 }
 
 template <typename T>
@@ -443,6 +479,18 @@ hipError_t launch_log_backward_f64(const Shape &sh, const double *sig, const dou
                                    hipStream_t st)
 {
     return launch_log_backward<double>(sh, sig, grad_log, grad_sig, workspace, st);
+}
+
+hipError_t launch_combine_backward_f32(const Shape &sh, const float *a, const float *b, const float *g, float *ga, float *gb,
+                                       void *workspace, hipStream_t st)
+{
+    return launch_combine_backward<float>(sh, a, b, g, ga, gb, workspace, st);
+}
+
+hipError_t launch_combine_backward_f64(const Shape &sh, const double *a, const double *b, const double *g, double *ga, double *gb,
+                                       void *workspace, hipStream_t st)
+{
+    return launch_combine_backward<double>(sh, a, b, g, ga, gb, workspace, st);
 }
 
 hipError_t launch_scatter_f32(const Shape &sh, const float *in, const int64_t *index, int64_t n, float *out, hipStream_t st)

@@ -170,6 +170,14 @@ def test_signature_invert_and_strided_combine_validation(lib):
     assert h(p, -1, p, 6, 2, 2, 2, sig.SIG_F32, p, 6, 0) == sig.SIG_ERR_INVALID_ARG
     assert h(p, 0, 0, 6, 2, 2, 2, sig.SIG_F32, p, 6, 0) == sig.SIG_ERR_INVALID_ARG
     assert h(0, 0, 0, 0, 0, 2, 2, sig.SIG_F32, 0, 6, 0) == sig.SIG_OK
+    cb, cbw = lib.sig_combine_backward, lib.sig_combine_backward_workspace_bytes
+    # a, b, grad_out, B, d, N, dtype, grad_a, grad_b, workspace, workspace_bytes, hip_stream
+    assert cbw(3, 2, 1, sig.SIG_F32) == 0 and cbw(3, 2, 4, sig.SIG_F64) > 0 and cbw(-1, 2, 4, sig.SIG_F32) == -1
+    assert cb(p, p + 64, p + 128, 2, 2, 3, sig.SIG_F32, p + 192, p + 192, p, 1 << 20, 0) == sig.SIG_ERR_INVALID_ARG
+    assert cb(p, p + 64, p + 128, 2, 2, 3, sig.SIG_F32, p, p + 256, p, 1 << 20, 0) == sig.SIG_ERR_INVALID_ARG
+    assert cb(p, p + 64, p + 128, 2, 2, 3, sig.SIG_F32, p + 192, p + 256, 0, 0, 0) == sig.SIG_ERR_INVALID_ARG
+    assert cb(p, p + 64, 0, 2, 2, 3, sig.SIG_F32, p + 192, p + 256, p, 1 << 20, 0) == sig.SIG_ERR_INVALID_ARG
+    assert cb(0, 0, 0, 0, 2, 3, sig.SIG_F32, 0, 0, 0, 0, 0) == sig.SIG_OK
     m, mb = lib.sig_combine_many, lib.sig_combine_many_workspace_bytes
     # sigs, B, n, d, N, dtype, out, workspace, workspace_bytes, hip_stream
     assert mb(3, 1, 2, 2, sig.SIG_F32) == 0 and mb(3, 2, 2, 2, sig.SIG_F32) == 0

@@ -215,3 +215,55 @@ def test_autograd_through_inverse_and_basepoint_value():
     bp = dev(uniform_paths(2, 1, 2, seed=10)[:, 0].astype(np.float64)).requires_grad_(True)
     assert torch.autograd.gradcheck(lambda p, q: sig.signature(p, 3, True, q, True), (x, bp), eps=1e-6, atol=1e-7, rtol=1e-6)
     assert torch.autograd.gradcheck(lambda p: sig.signature(p, 4, False, False, True), (x,), eps=1e-6, atol=1e-7, rtol=1e-6)
+
+
+# ---- gradient of the group product ---------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("B,d,N", [(3, 2, 9), (2, 2, 10), (4, 3, 6), (5, 4, 5), (2, 7, 4), (3, 1, 4), (2, 5, 1), (3, 4, 2),
+                                   (2, 8, 4), (2, 9, 3)])
+def test_gradient_of_the_group_product(B, d, N, dtype):
+    rng = np.random.default_rng(B + 10 * d + 100 * N)
+    a = orc.signature(brownian_paths(B, 6, d, seed=d + N), N).astype(dtype)
+    b = orc.signature(brownian_paths(B, 7, d, seed=d * N), N).astype(dtype)
+    g = rng.standard_normal(a.shape).astype(dtype)
+    ga, gb = sig.sig_combine_backward(dev(a), dev(b), dev(g), d, N)
+    want = [orc.group_mul_backward(a[i], b[i], g[i], d, N) for i in range(B)]
+    # every term of the gradient is a product of one cotangent with one factor: the yardstick is that sum with
+    # absolute values
+    scale = [orc.group_mul_backward(np.abs(a[i]), np.abs(b[i]), np.abs(g[i]), d, N) for i in range(B)]
+    tol = 1e-5 if dtype == np.float32 else 1e-13
+    for got, k in ((host(ga), 0), (host(gb), 1)):
+        w = np.stack([t[k] for t in want])
+        sc = np.stack([t[k] for t in scale])
+        for sl in orc.level_slices(d, N):
+            assert np.linalg.norm(got[:, sl] - w[:, sl]) <= tol * np.linalg.norm(sc[:, sl])
+
+
+def test_gradcheck_through_products_and_initial():
+    import torch
+    d, N = 2, 3
+    sigs = [dev(orc.signature(brownian_paths(2, 4, d, seed=s), N)).requires_grad_(True) for s in range(5)]
+    assert torch.autograd.gradcheck(lambda p, q: sig.signature_combine(p, q, d, N), tuple(sigs[:2]), eps=1e-6,
+                                    atol=1e-7, rtol=1e-6)
+    assert torch.autograd.gradcheck(lambda *t: sig.multi_signature_combine(list(t), d, N), tuple(sigs), eps=1e-6,
+                                    atol=1e-7, rtol=1e-6)
+    x = dev(brownian_paths(2, 5, d, seed=11).astype(np.float64)).requires_grad_(True)
+    assert torch.autograd.gradcheck(lambda p, i: sig.signature(p, N, initial=i), (x, sigs[0]), eps=1e-6, atol=1e-7,
+                                    rtol=1e-6)
+    assert torch.autograd.gradcheck(lambda p, i: sig.signature(p, N, initial=i, inverse=True, basepoint=True),
+                                    (x, sigs[1]), eps=1e-6, atol=1e-7, rtol=1e-6)
+
+
+def test_multi_signature_combine_equals_the_signature_of_the_whole_path():
+    import torch
+    d, N = 3, 4
+    x = brownian_paths(3, 13, d, seed=4).astype(np.float64)
+    cuts = [0, 3, 4, 9, 12]
+    pieces = [dev(orc.signature(x[:, cuts[i]:cuts[i + 1] + 1], N)) for i in range(4)]
+    got = host(sig.multi_signature_combine(pieces, d, N))
+    assert_levels_close(got, orc.signature(x, N), d, N, np.float64)
+    # `initial` in final mode: the signature of everything so far
+    first = dev(orc.signature(x[:, :6], N))
+    got = host(sig.signature(dev(x[:, 5:]), N, initial=first))
+    assert_levels_close(got, orc.signature(x, N), d, N, np.float64)

@@ -170,3 +170,29 @@ def test_bad_arguments_raise():
         orc.signature_backward(x, np.zeros((1, 5)), 2)          # S = 6
     with pytest.raises(ValueError):
         orc.signature_backward(np.zeros((1, 1, 2)), np.zeros((1, 6)), 2)   # one point, no basepoint
+
+
+# ---- gradient of one group product --------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("d,N", [(2, 4), (3, 3), (1, 5), (4, 2)])
+def test_product_gradient_matches_finite_differences_of_the_pinned_product(d, N):
+    rng = np.random.default_rng(7 * d + N)
+    S = orc.channels(d, N)
+    A, B, g = rng.standard_normal(S), rng.standard_normal(S), rng.standard_normal(S)
+    gA, gB = orc.group_mul_backward(A, B, g, d, N)
+    h = 1e-6
+    for _ in range(5):
+        vA, vB = rng.standard_normal(S), rng.standard_normal(S)
+        fd = np.dot(g, orc.group_mul(A + h * vA, B + h * vB, d, N) - orc.group_mul(A - h * vA, B - h * vB, d, N)) / (2 * h)
+        assert abs(np.dot(gA, vA) + np.dot(gB, vB) - fd) <= 1e-8 * (1 + abs(fd))
+
+
+def test_product_gradient_closed_form_at_depth_two():
+    # C_1 = A_1 + B_1, C_2 = A_2 + B_2 + A_1 (x) B_1  =>  gA_1 = g_1 + g_2 B_1,  gB_1 = g_1 + g_2^T A_1,  gA_2 = gB_2 = g_2
+    d = 3
+    rng = np.random.default_rng(12)
+    A, B, g = (rng.standard_normal(d + d * d) for _ in range(3))
+    g2 = g[d:].reshape(d, d)
+    gA, gB = orc.group_mul_backward(A, B, g, d, 2)
+    np.testing.assert_allclose(gA, np.concatenate([g[:d] + g2 @ B[:d], g[d:]]), rtol=0, atol=1e-14)
+    np.testing.assert_allclose(gB, np.concatenate([g[:d] + g2.T @ A[:d], g[d:]]), rtol=0, atol=1e-14)
