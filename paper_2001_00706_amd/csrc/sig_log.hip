@@ -13,6 +13,7 @@
 // with an index table that `sig_lyndon_indices` computes on the host.
 #include "sig_internal.h"
 
+#include <type_traits>
 #include <vector>
 
 namespace sig {
@@ -138,6 +139,15 @@ sig_log_fixed_kernel(int64_t rows, const T *__restrict__ in, T *__restrict__ out
 // whole chip without synchronisation.
 constexpr int kDirectMaxDepth = 9;
 
+template <int I, int End, typename F>
+__device__ __forceinline__ void static_for(F &&f)   // f(integral_constant<int, I>), ..., f(integral_constant<int, End - 1>)
+{
+    if constexpr (I < End) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, End>(f);
+    }
+}
+
 template <typename T, int D, int K>
 __device__ __forceinline__ T log_of_word(const T *__restrict__ x, uint32_t idx, uint32_t d, const uint32_t (&off)[kDirectMaxDepth + 2])
 {
@@ -150,36 +160,38 @@ __device__ __forceinline__ T log_of_word(const T *__restrict__ x, uint32_t idx, 
             rest = D > 0 ? rest / uint32_t(D) : rest / d;
         }
     }
-    T xs[K][K + 1];  // xs[i][j] = x[w_{i+1}..w_j], 0 <= i < j <= K
-#pragma unroll
-    for (int i = 0; i < K; ++i) {
+    // xs[at(i, j)] = x[w_{i+1}..w_j], 0 <= i < j <= K, packed.  Every index below is a compile-time constant
+    // (static_for, not a loop the compiler may or may not unroll: at K = 9 it left some of them rolled, which put
+    // this array in scratch memory and made the kernel 6 times slower), so the arrays live in registers.
+    constexpr auto at = [](int i, int j) { return i * K - i * (i - 1) / 2 + (j - i - 1); };
+    T xs[K * (K + 1) / 2];
+    static_for<0, K>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
         uint32_t val = 0;
-#pragma unroll
-        for (int j = i + 1; j <= K; ++j) {
+        static_for<i + 1, K + 1>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
             val = val * (D > 0 ? uint32_t(D) : d) + w[j - 1];
-            xs[i][j] = x[off[j - i] + val];
-        }
-    }
+            xs[at(i, j)] = x[off[j - i] + val];
+        });
+    });
+    // P_1[j] = x[w_1..w_j]; P_m[j] = sum_{m-1 <= i < j} P_{m-1}[i] x[w_{i+1}..w_j]
     T prev[K + 1], cur[K + 1];
-#pragma unroll
-    for (int j = 0; j <= K; ++j) prev[j] = T(0);
-    prev[0] = T(1);
-    T result = T(0);
-#pragma unroll
-    for (int m = 1; m <= K; ++m) {
-#pragma unroll
-        for (int j = 0; j <= K; ++j) {
+    static_for<1, K + 1>([&](auto jc) { prev[decltype(jc)::value] = xs[at(0, decltype(jc)::value)]; });
+    T result = prev[K];
+    static_for<2, K + 1>([&](auto mc) {
+        constexpr int m = decltype(mc)::value;
+        static_for<m, K + 1>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
             T acc = T(0);
-            if (j >= m) {
-#pragma unroll
-                for (int i = m - 1; i < j; ++i) acc += prev[i] * xs[i][j];
-            }
+            static_for<m - 1, j>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                acc += prev[i] * xs[at(i, j)];
+            });
             cur[j] = acc;
-        }
+        });
         result += ((m & 1) ? T(1) : T(-1)) / T(m) * cur[K];
-#pragma unroll
-        for (int j = 0; j <= K; ++j) prev[j] = cur[j];
-    }
+        static_for<m, K + 1>([&](auto jc) { prev[decltype(jc)::value] = cur[decltype(jc)::value]; });
+    });
     return result;
 }
 

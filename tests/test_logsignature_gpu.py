@@ -48,7 +48,7 @@ def assert_log_close(got, want, sig_ref, d, N, dt):
 
 
 SHAPES = [(3, 9, 2, 6), (2, 6, 3, 5), (4, 12, 4, 4), (2, 5, 4, 6), (2, 4, 7, 3), (3, 5, 1, 4), (2, 6, 5, 1),
-          (1, 20, 2, 8), (2, 5, 8, 4)]
+          (1, 20, 2, 8), (2, 5, 8, 4), (2, 7, 2, 9), (1, 5, 3, 9), (1, 6, 2, 10)]
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
