@@ -77,7 +77,9 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
             if (mfma_ok) return Family::Mfma;
             if (d16_ok) return Family::MfmaD16;
             if (d8_ok) return Family::MfmaD8;
-            if (small_ok) return Family::Small;
+            // up to 128 scalars (two words per lane) the one-wavefront kernel wins; beyond, its lanes carry 4 or 8
+            // words each and the prefix-tree kernel is up to 6 times faster (d = 2, N = 8: 38 us against 194)
+            if (small_ok && (sh.S <= 128 || !tree_ok)) return Family::Small;
             if (tree_ok) return Family::Tree;
             return generic_ok ? Family::Generic : Family::None;
         case SIG_VARIANT_GENERIC: return generic_ok ? Family::Generic : Family::None;
