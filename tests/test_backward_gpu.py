@@ -87,6 +87,16 @@ def test_register_resident_kernels_every_depth(d, N):
             check(x, N, stream=stream, basepoint=basepoint)
 
 
+def test_final_mode_families_on_both_sides_of_their_batch_thresholds():
+    # with one gradient per path the prefix-tree kernels serve most shapes; d = 2, N = 9 goes to the register-resident
+    # kernel above 512 paths, d = 4 at N >= 5 below 512 paths
+    check(brownian_paths(520, 6, 2, seed=3), 9, sample=[0, 1, 255, 519])
+    check(brownian_paths(8, 6, 2, seed=4), 9)
+    check(brownian_paths(515, 7, 4, seed=5), 5, sample=[0, 300, 514])
+    check(brownian_paths(515, 5, 4, seed=6), 6, basepoint=True, sample=[1, 2, 513])
+    check(brownian_paths(5, 70, 4, seed=7), 6)
+
+
 @pytest.mark.parametrize("B,L,d,N", [
     (2, 6, 7, 7),      # 16 807 threads per path over 66 workgroups, 960 799 scalars per signature
     (2, 8, 4, 9), (2, 10, 4, 8), (2, 9, 4, 7), (3, 40, 3, 7), (2, 12, 5, 7), (2, 9, 6, 7), (2, 70, 5, 4),
