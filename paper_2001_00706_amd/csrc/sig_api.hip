@@ -73,10 +73,15 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
         case SIG_VARIANT_AUTO:
             // four wavefronts per path when one per path would leave most of the chip idle, when every
             // prefix is stored (stream mode) or when the state does not fit one wavefront (N = 7)
+            // (measured at L = 128: from 1024 paths on, stream mode at N >= 5 is a pure HBM write stream, which the
+            // prefix-tree kernel sustains at 4.0 TB/s against 3.5)
+            if (shard_ok && sh.stream && sh.N >= 5 && sh.B >= 1024 && tree_ok) return Family::Tree;
             if (shard_ok && (!mfma_ok || sh.B < 512)) return Family::MfmaShard;
             if (mfma_ok) return Family::Mfma;
             if (d16_ok) return Family::MfmaD16;
-            if (d8_ok) return Family::MfmaD8;
+            // 64 wavefronts per path pay off while paths are few; from 512 paths on each shard's own prefix sums
+            // are pure overhead (N = 4 at B = 2048: 170 us against 62 for the prefix-tree kernel); N = 6 stays
+            if (d8_ok && !(sh.N <= 5 && sh.B >= 512 && tree_ok)) return Family::MfmaD8;
             // up to 128 scalars (two words per lane) the one-wavefront kernel wins; beyond, its lanes carry 4 or 8
             // words each and the prefix-tree kernel is up to 6 times faster (d = 2, N = 8: 38 us against 194)
             if (small_ok && (sh.S <= 128 || !tree_ok)) return Family::Small;
