@@ -65,3 +65,11 @@ class Path:
             return out
         a_rows = self._inv[0].reshape(-1)[(start - 1) * self.S:]
         return binding.sig_combine_strided(a_rows, row, b_rows, row, self.B, self.d, self.depth, out, self.S)
+
+    def logsignature(self, start: int = 0, end: int | None = None, mode: str = "words"):
+        """Logsignature of the points `start..end` inclusive (sections 2.3, 4.3): `sig_log` of that interval's
+        signature, then for mode "words" the coefficients of the Lyndon words ("expand" keeps every word)."""
+        if mode not in ("words", "expand"):
+            raise ValueError('mode must be "words" or "expand"')
+        full = binding.sig_log(self.signature(start, end), self.d, self.depth)
+        return full if mode == "expand" else binding.sig_lyndon_gather(full, self.d, self.depth)

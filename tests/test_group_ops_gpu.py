@@ -267,3 +267,13 @@ def test_multi_signature_combine_equals_the_signature_of_the_whole_path():
     first = dev(orc.signature(x[:, :6], N))
     got = host(sig.signature(dev(x[:, 5:]), N, initial=first))
     assert_levels_close(got, orc.signature(x, N), d, N, np.float64)
+
+
+def test_path_logsignature_queries():
+    x = brownian_paths(3, 12, 3, seed=21).astype(np.float64)
+    N = 4
+    p = sig.Path(dev(x), N)
+    for i, j in ((0, 11), (2, 9), (5, 6)):
+        got = host(p.logsignature(i, j))
+        np.testing.assert_allclose(got, orc.logsignature(x[:, i:j + 1], N), rtol=0, atol=1e-10)
+    assert host(p.logsignature(1, 4, mode="expand")).shape == (3, orc.channels(3, N))
