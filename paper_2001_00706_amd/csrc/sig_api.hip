@@ -1,5 +1,5 @@
 // C ABI of libsig: argument validation, size helpers and kernel-family dispatch.
-// The operations are those declared in sig.h; nothing here touches device memory.
+// The operations are those declared in sig.h; nothing here dereferences a device pointer.
 #include "sig_internal.h"
 
 namespace {
@@ -52,6 +52,22 @@ sig_status make_shape(int64_t B, int64_t L, int d, int N, int stream, int basepo
         per_path_out = sh.n_inc * sh.S;
     }
     if (B > 0 && per_path_out > kMaxElems / B) return SIG_ERR_OVERFLOW;
+    return SIG_OK;
+}
+
+// Shape of a batch of `rows` signatures with no path attached.
+sig_status make_rows_shape(int64_t rows, int d, int N, sig::Shape &sh)
+{
+    if (rows < 0 || d < 1 || N < 1 || N > SIG_MAX_DEPTH) return SIG_ERR_INVALID_ARG;
+    if (!fill_levels(d, N, sh)) return SIG_ERR_OVERFLOW;
+    if (rows > 0 && sh.S > kMaxElems / rows) return SIG_ERR_OVERFLOW;
+    sh.B = rows;
+    sh.L = 0;
+    sh.n_inc = 0;
+    sh.stream = sh.basepoint = 0;
+    sh.basepoint_value = nullptr;
+    sh.chunks = 1;
+    sh.chunk_len = 0;
     return SIG_OK;
 }
 
@@ -180,17 +196,9 @@ sig_status sig_combine(const void *a, const void *b, int64_t B, int d, int N, si
                        void *out, hipStream_t hip_stream)
 {
     if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
-    if (B < 0 || d < 1 || N < 1 || N > SIG_MAX_DEPTH) return SIG_ERR_INVALID_ARG;
     sig::Shape sh;
-    if (!fill_levels(d, N, sh)) return SIG_ERR_OVERFLOW;
-    if (B > 0 && sh.S > kMaxElems / B) return SIG_ERR_OVERFLOW;
-    sh.B = B;
-    sh.L = 0;
-    sh.n_inc = 0;
-    sh.stream = sh.basepoint = 0;
-    sh.basepoint_value = nullptr;
-    sh.chunks = 1;
-    sh.chunk_len = 0;
+    const sig_status st = make_rows_shape(B, d, N, sh);
+    if (st != SIG_OK) return st;
     if (B == 0) return SIG_OK;
     if (a == nullptr || b == nullptr || out == nullptr) return SIG_ERR_INVALID_ARG;
     if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
@@ -236,22 +244,6 @@ sig_status sig_backward(const void *path, const void *sig, const void *grad_out,
                                        static_cast<const double *>(grad_out), static_cast<double *>(grad_path),
                                        static_cast<double *>(grad_basepoint), workspace, workspace_bytes, hip_stream);
     return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
-}
-
-// Shape of a batch of `rows` signatures with no path attached.
-static sig_status make_rows_shape(int64_t rows, int d, int N, sig::Shape &sh)
-{
-    if (rows < 0 || d < 1 || N < 1 || N > SIG_MAX_DEPTH) return SIG_ERR_INVALID_ARG;
-    if (!fill_levels(d, N, sh)) return SIG_ERR_OVERFLOW;
-    if (rows > 0 && sh.S > kMaxElems / rows) return SIG_ERR_OVERFLOW;
-    sh.B = rows;
-    sh.L = 0;
-    sh.n_inc = 0;
-    sh.stream = sh.basepoint = 0;
-    sh.basepoint_value = nullptr;
-    sh.chunks = 1;
-    sh.chunk_len = 0;
-    return SIG_OK;
 }
 
 sig_status sig_invert(const void *sig, int64_t rows, int d, int N, sig_dtype dtype, void *out, hipStream_t hip_stream)

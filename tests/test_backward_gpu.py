@@ -264,7 +264,7 @@ def test_autograd_sum_backward_as_in_the_papers_example():
 
 
 def test_a_training_step_can_be_captured_in_a_graph_and_replayed():
-    # forward, logarithm, gradient and a group product in one HIP graph: none of the calls allocates,
+    # forward, logarithm, group product and all three gradients in one HIP graph: none of the calls allocates,
     # synchronises or memsets; every replay is checked against the same calls made eagerly
     import torch
     x_host = brownian_paths(8, 40, 4, seed=17)
@@ -276,12 +276,19 @@ def test_a_training_step_can_be_captured_in_a_graph_and_replayed():
     prod = torch.empty_like(s)
     g = torch.from_numpy(np.random.default_rng(2).standard_normal((8, S)).astype(np.float32)).to("cuda:0")
     gp = torch.empty_like(x)
+    g_words = torch.from_numpy(np.random.default_rng(3).standard_normal((8, sig.sig_logsignature_channels(4, N)))
+                               .astype(np.float32)).to("cuda:0")
+    g_log, g_sig, g_a, g_b = (torch.empty_like(s) for _ in range(4))
+    ws = torch.empty(sig.sig_log_backward_workspace_bytes(8, 4, N), dtype=torch.uint8, device="cuda:0")
 
     def step():
         sig.sig_forward(x, N, out=s)
         sig.sig_log(s, 4, N, out=lg)
         sig.sig_backward(x, s, g, N, grad_path=gp)
         sig.sig_combine(s, s, 4, N, out=prod)
+        sig.sig_lyndon_scatter(g_words, 4, N, out=g_log)
+        sig.sig_log_backward(s, g_log, 4, N, out=g_sig, workspace=ws)
+        sig.sig_combine_backward(s, lg, g, 4, N, grad_a=g_a, grad_b=g_b, workspace=ws)
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -294,13 +301,13 @@ def test_a_training_step_can_be_captured_in_a_graph_and_replayed():
         step()
     for rep in range(3):
         x.copy_(torch.from_numpy(x_host * (1.0 + 0.5 * rep)).to("cuda:0"))
-        for t in (s, lg, gp, prod):
+        for t in (s, lg, gp, prod, g_log, g_sig, g_a, g_b):
             t.fill_(float("nan"))
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        got = [t.clone() for t in (s, lg, gp, prod)]
+        got = [t.clone() for t in (s, lg, gp, prod, g_log, g_sig, g_a, g_b)]
         step()
         torch.cuda.synchronize()
-        for a, b in zip(got, (s, lg, gp, prod)):
+        for a, b in zip(got, (s, lg, gp, prod, g_log, g_sig, g_a, g_b)):
             assert torch.equal(a, b), rep
