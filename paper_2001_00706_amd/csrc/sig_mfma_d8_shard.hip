@@ -59,30 +59,31 @@ struct State8 {
 template <int N>
 constexpr int kRow8 = kD8 * (N - 2);
 
-// Inclusive prefix sum over the 64 lanes (lane i receives v_0 + .. + v_i).
-__device__ __forceinline__ float wave_inclusive_scan(float v, int lane)
+// DPP move that leaves 0 in the lanes of the rows (of 16 lanes) not named in ROWS and in lanes whose source lies
+// outside their row.
+template <int CTRL, int ROWS>
+__device__ __forceinline__ float dpp_or_zero(float v)
 {
-    const int in_row = lane & 15;
-    float t;
-    t = quad_swap<0x111>(v);   // row_shr:1
-    if (in_row >= 1) v += t;
-    t = quad_swap<0x112>(v);   // row_shr:2
-    if (in_row >= 2) v += t;
-    t = quad_swap<0x114>(v);   // row_shr:4
-    if (in_row >= 4) v += t;
-    t = quad_swap<0x118>(v);   // row_shr:8
-    if (in_row >= 8) v += t;
-    t = quad_swap<0x142>(v);   // row_bcast:15: the last lane of a row, to the next row
-    if ((lane & 31) >= 16) v += t;
-    t = quad_swap<0x143>(v);   // row_bcast:31: lane 31, to the upper two rows
-    if (lane >= 32) v += t;
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROWS, 0xf, false));
+}
+
+// Inclusive prefix sum over the 64 lanes (lane i receives v_0 + .. + v_i): doubling steps inside each row of 16
+// lanes (a shift past the start of the row brings 0), then the row totals passed on to the rows after them.
+__device__ __forceinline__ float wave_inclusive_scan(float v)
+{
+    v += dpp_or_zero<0x111, 0xf>(v);   // row_shr:1
+    v += dpp_or_zero<0x112, 0xf>(v);   // row_shr:2
+    v += dpp_or_zero<0x114, 0xf>(v);   // row_shr:4
+    v += dpp_or_zero<0x118, 0xf>(v);   // row_shr:8
+    v += dpp_or_zero<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3: the last lane of the row before
+    v += dpp_or_zero<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3: lane 31
     return v;
 }
 
 // Exclusive prefix sum (lane i receives v_0 + .. + v_{i-1}) and, in `total`, the sum over all lanes.
-__device__ __forceinline__ float wave_exclusive_scan(float v, int lane, float &total)
+__device__ __forceinline__ float wave_exclusive_scan(float v, float &total)
 {
-    const float incl = wave_inclusive_scan(v, lane);
+    const float incl = wave_inclusive_scan(v);
     total = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, incl), 63));
     return incl - v;
 }
@@ -254,7 +255,7 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
 #pragma unroll
             for (int k = 2; k <= N; ++k) t1[k] = __builtin_fmaf(zf1, 1.0f / k, a1);
             float sum2;
-            const float a2 = A2 + wave_exclusive_scan(t1[2] * zf2, lane, sum2);
+            const float a2 = A2 + wave_exclusive_scan(t1[2] * zf2, sum2);
             A2 += sum2;
 #pragma unroll
             for (int k = 3; k <= N; ++k) t2[k] = __builtin_fmaf(t1[k], zf2 * (1.0f / (k - 1)), a2);
@@ -263,7 +264,7 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
             for (int w = 0; w < kD8; ++w) {
                 const float zw = w < 4 ? z0[w & 3] : z1[w & 3];
                 float sum3;
-                const float a3 = A3[w] + wave_exclusive_scan(t2[3] * zw, lane, sum3);
+                const float a3 = A3[w] + wave_exclusive_scan(t2[3] * zw, sum3);
                 A3[w] += sum3;
 #pragma unroll
                 for (int k = 4; k <= N; ++k)
