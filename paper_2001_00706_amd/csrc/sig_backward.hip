@@ -319,10 +319,9 @@ hipError_t launch_backward_f32(const Shape &sh, const float *path, const float *
     const bool aligned = (reinterpret_cast<uintptr_t>(path) | reinterpret_cast<uintptr_t>(sig) |
                           reinterpret_cast<uintptr_t>(gout) | reinterpret_cast<uintptr_t>(sh.basepoint_value)) % 16 == 0;
     // Measured at L = 128 over B = 1..2048: with one gradient per path (final mode) the prefix-tree kernels beat the
-    // two register-resident families (by up to 3.6 times at d = 8) except at d = 4, N >= 5 below 512 paths and at
-    // d = 2, N = 9 above; with a gradient per prefix (stream mode) the register-resident families stay ahead.
-    const bool tree_first = !sh.stream && tree_backward_supported(sh) && !(sh.d == 4 && sh.N >= 5 && sh.B < 512) &&
-                            !(sh.d == 2 && sh.N == 9 && sh.B > 512);
+    // two register-resident families (by up to 3.6 times at d = 8) except at d = 4, N >= 5 below 512 paths; with a
+    // gradient per prefix (stream mode) the register-resident families stay ahead.
+    const bool tree_first = !sh.stream && tree_backward_supported(sh) && !(sh.d == 4 && sh.N >= 5 && sh.B < 512);
     if (aligned && !tree_first && backward_d4_supported(sh))
         return launch_backward_d4_f32(sh, path, sig, gout, gpath, gbase, st);
     if (aligned && !tree_first && backward_pow2_supported(sh))

@@ -108,15 +108,21 @@ bool backward_pow2_supported(const Shape &sh);
 hipError_t launch_backward_pow2_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
                                     float *gbase, hipStream_t st);
 
-// Prefix-tree family (final mode, d = 2..8, N = 2..9): a thread per word of N-2 letters carries the word's
+// Prefix-tree family (d = 2..8 at N = 2..9, d = 9..16 at N = 2..6): a thread per word of N-2 letters carries the word's
 // prefixes and the two levels below it; no communication, any number of workgroups per path.
 bool tree_supported(const Shape &sh);
+hipError_t launch_tree_wide(const Shape &sh, const float *path, float *out, hipStream_t st);    // d = 9..16
+hipError_t launch_tree_wide(const Shape &sh, const double *path, double *out, hipStream_t st);
 hipError_t launch_tree_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_tree_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
 
-// Prefix-tree gradient kernels (d = 2..8, N = 2..9, any alignment): no communication between threads; the
+// Prefix-tree gradient kernels (d = 2..8 at N = 2..9, d = 9..16 at N = 2..6, any alignment): no communication between threads; the
 // per-increment partial gradients go to a workspace of `tree_backward_workspace_bytes` and are summed by a second
 // kernel.
+hipError_t launch_tree_backward_wide(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
+                                     float *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st);   // d = 9..16
+hipError_t launch_tree_backward_wide(const Shape &sh, const double *path, const double *sig, const double *gout,
+                                     double *gpath, double *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st);
 bool tree_backward_supported(const Shape &sh);
 int64_t tree_backward_workspace_bytes(const Shape &sh, sig_dtype dtype);
 hipError_t launch_tree_backward_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,

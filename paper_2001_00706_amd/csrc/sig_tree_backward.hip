@@ -13,7 +13,7 @@ int64_t tree_backward_workspace_bytes(const Shape &sh, sig_dtype dtype)
 hipError_t launch_tree_backward_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
                                     float *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st)
 {
-    return launch_tb<float>(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
+    return launch_tb<float, false>(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
 }
 
 }  // namespace sig

@@ -1,9 +1,9 @@
-// Gradient of the signature with respect to the path, prefix-tree family (fp32, d = 2..8, N = 2..9, final and
-// stream mode): the recurrences of sig_backward.hip with no communication between threads, so that the
+// Gradient of the signature with respect to the path, prefix-tree family (d = 2..8 at N = 2..9, d = 9..16 at N = 2..6,
+// final and stream mode): the recurrences of sig_backward.hip with no communication between threads, so that the
 // state of one path can be spread over any number of workgroups (paper section 5.3, appendix C).
 //
 // A thread stands for a word u of P = N - U letters and owns the subtree of the words u c and u c c'
-// below it (U = 2 levels, in registers), exactly as in sig_tree.hip.
+// below it (U = 2 levels, in registers; U = 1 beyond 8 channels), exactly as in sig_tree_impl.h.
 //   * "Up" (undo the increment, Horner terms T^(k)_i) needs the signature at the prefixes of u only; every
 //     thread carries its own copy of them.
 //   * "Down" moves cotangent from a word to its prefixes, D^(k)_{i-1}[p] = sum_c D^(k)_i[p c] z[c]/(k-i+1).
@@ -12,9 +12,9 @@
 //     a thread keeps, for each of its prefixes, only the part that came up through its own word, and the
 //     gradient of an increment is the sum of every thread's contribution.  (The cotangent a prefix has of
 //     its own in the output gradient is given to the first thread below it.)
-//   * That one sum, over all threads of a path and per increment, is left to a second kernel: every
-//     workgroup (or, for paths of fewer than 256 words, every thread) writes its partial sums to a
-//     workspace [row][group][increment][d].
+//   * That one sum, over all threads of a path and per increment, is finished by a second kernel: every
+//     workgroup (for paths of at most 64 words: every thread) writes its partial sums to a workspace
+//     [row][group][increment][d].
 #ifndef SIG_TREE_BACKWARD_IMPL_H_
 #define SIG_TREE_BACKWARD_IMPL_H_
 
@@ -40,13 +40,21 @@ __host__ __device__ constexpr int64_t tb_off(int d, int k)   // offset of level 
 
 template <int D, int N>
 struct TbShape {
-    static constexpr int U = N >= 3 ? 2 : N - 1;
+    // levels kept per thread below its word: two (d + d^2 scalars) up to 8 channels, one (d scalars) beyond
+    static constexpr int U = N - 1 < (D <= 8 ? 2 : 1) ? N - 1 : (D <= 8 ? 2 : 1);
     static constexpr int P = N - U;
-    static constexpr int64_t kWords = tb_off(D, P + 1) - tb_off(D, P);
-    static constexpr bool kWide = kWords >= 256;   // one path per workgroup, partial sums per wavefront
-    static constexpr int kPathsPerGroup = kWide ? 1 : (256 / kWords < kTbMaxPaths ? int(256 / kWords) : kTbMaxPaths);
-    static constexpr int64_t kGroupsPerPath = kWide ? (kWords + 255) / 256 : 1;   // workgroups per path
-    static constexpr int64_t kPartials = kWide ? kGroupsPerPath : kWords;         // partial sums per path and increment
+    static constexpr int64_t kWords = tb_off(D, P + 1) - tb_off(D, P);   // threads a path needs
+    static constexpr bool kMulti = kWords >= 256;   // a path spans several workgroups
+    // From 65 words on, a path takes whole wavefronts (2..4, idle lanes at the end), each wavefront sums its lanes'
+    // parts of an increment's gradient and the sums meet in LDS once per tile: one partial sum per path and
+    // workgroup.  Shorter paths are packed thread after thread and every thread writes its own part (summing
+    // over a wavefront costs d x 7 instructions per increment, which a path of one wavefront does not win back).
+    static constexpr bool kWide = kWords > 64;
+    static constexpr int kWavesPerPath = kMulti ? 4 : int((kWords + 63) / 64);
+    static constexpr int kPathsPerGroup =
+        kWide ? (kMulti ? 1 : 4 / kWavesPerPath) : (256 / kWords < kTbMaxPaths ? int(256 / kWords) : kTbMaxPaths);
+    static constexpr int64_t kGroupsPerPath = kMulti ? (kWords + 255) / 256 : 1;   // workgroups per path
+    static constexpr int64_t kPartials = kWide ? kGroupsPerPath : kWords;          // partial sums per path and increment
     static constexpr int64_t kS = tb_off(D, N + 1);
 };
 
@@ -65,11 +73,14 @@ sig_tree_backward_kernel(Shape sh, const T *__restrict__ path, const T *__restri
     __shared__ T zt[PPG * kTbTile * D];
     __shared__ T part[TS::kWide ? kTbTile * 4 * D : 1];   // [increment of the tile][wavefront][channel]
 
+    constexpr int WPP = TS::kWavesPerPath;
     const int tid = threadIdx.x;
-    const int slot_raw = TS::kWide ? 0 : tid / int(TS::kWords);
+    const int slot_raw = TS::kMulti ? 0 : TS::kWide ? (tid >> 6) / WPP : tid / int(TS::kWords);
     const int slot = slot_raw < PPG ? slot_raw : PPG - 1;
-    const int64_t u_raw = TS::kWide ? int64_t(blockIdx.x % TS::kGroupsPerPath) * 256 + tid : tid % int(TS::kWords);
-    const int64_t row = TS::kWide ? int64_t(blockIdx.x / TS::kGroupsPerPath) : int64_t(blockIdx.x) * PPG + slot;
+    const int64_t u_raw = TS::kMulti  ? int64_t(blockIdx.x % TS::kGroupsPerPath) * 256 + tid
+                          : TS::kWide ? int64_t(tid - slot_raw * WPP * 64)
+                                      : int64_t(tid % int(TS::kWords));
+    const int64_t row = TS::kMulti ? int64_t(blockIdx.x / TS::kGroupsPerPath) : int64_t(blockIdx.x) * PPG + slot;
     const bool live = u_raw < TS::kWords && slot_raw < PPG && row < sh.B;
     const int64_t u = live ? u_raw : 0;   // idle threads shadow word 0 of a valid row and contribute nothing
     const int64_t my_row = live ? row : (row < sh.B ? row : 0);
@@ -128,11 +139,12 @@ sig_tree_backward_kernel(Shape sh, const T *__restrict__ path, const T *__restri
     if constexpr (!STREAM) A = load_share(sg, false, U >= 2, false);
 
     // rows served by this workgroup, for the staging of their increments
-    const int64_t row0 = TS::kWide ? int64_t(blockIdx.x / TS::kGroupsPerPath) : int64_t(blockIdx.x) * PPG;
+    const int64_t row0 = TS::kMulti ? int64_t(blockIdx.x / TS::kGroupsPerPath) : int64_t(blockIdx.x) * PPG;
     const T *bpv = static_cast<const T *>(sh.basepoint_value);
-    // where this thread's (or wavefront's) partial sums go: [row][group][increment][D]
-    const int64_t group = TS::kWide ? int64_t(blockIdx.x % TS::kGroupsPerPath) : u;
-    T *pp = partial + (my_row * TS::kPartials + group) * sh.n_inc * D;
+    // where the partial sums go: [row][group][increment][D]; group = the workgroup's number inside its path (wavefront
+    // sums) or the thread's word (short paths)
+    const int64_t wg_group = TS::kMulti ? int64_t(blockIdx.x % TS::kGroupsPerPath) : 0;
+    T *pp = partial + (my_row * TS::kPartials + (TS::kWide ? wg_group : u)) * sh.n_inc * D;
 
     for (int64_t t0 = ((sh.n_inc - 1) / kTbTile) * kTbTile; t0 >= 0; t0 -= kTbTile) {
         const int nt = int(sh.n_inc - t0 < kTbTile ? sh.n_inc - t0 : kTbTile);
@@ -287,10 +299,14 @@ sig_tree_backward_kernel(Shape sh, const T *__restrict__ path, const T *__restri
         }
         if constexpr (TS::kWide) {
             __syncthreads();
-            for (int e = tid; e < nt * D; e += 256) {
-                const int i = e / D, c = e % D;
-                const T *q = part + i * 4 * D + c;
-                pp[(t0 + i) * D + c] = (q[0] + q[D]) + (q[2 * D] + q[3 * D]);
+            for (int e = tid; e < PPG * nt * D; e += 256) {
+                const int p = e / (nt * D), i = (e / D) % nt, c = e % D;
+                if (row0 + p >= sh.B) continue;
+                const T *q = part + (i * 4 + p * WPP) * D + c;
+                T total = q[0];
+#pragma unroll
+                for (int w = 1; w < WPP; ++w) total += q[w * D];
+                partial[(((row0 + p) * TS::kPartials + wg_group) * sh.n_inc + t0 + i) * D + c] = total;
             }
         }
     }
@@ -334,7 +350,7 @@ hipError_t launch_tb_dn(const Shape &sh, const T *path, const T *sig, const T *g
                         T *gbase, T *partial, hipStream_t st)
 {
     using TS = TbShape<D, N>;
-    const int64_t groups = TS::kWide ? sh.B * TS::kGroupsPerPath : (sh.B + TS::kPathsPerGroup - 1) / TS::kPathsPerGroup;
+    const int64_t groups = TS::kMulti ? sh.B * TS::kGroupsPerPath : (sh.B + TS::kPathsPerGroup - 1) / TS::kPathsPerGroup;
     if (groups > 0x7fffffff) return hipErrorNotSupported;
     if (sh.stream)
         hipLaunchKernelGGL((sig_tree_backward_kernel<T, D, N, true>), dim3(unsigned(groups)), dim3(256), 0, st, sh, path, sig,
@@ -354,6 +370,9 @@ hipError_t launch_tb_dn(const Shape &sh, const T *path, const T *sig, const T *g
 template <int D, int N>
 int64_t tb_partials() { return TbShape<D, N>::kPartials; }
 
+constexpr int kTbMaxDepth = 9;       // d = 2..8
+constexpr int kTbWideMaxDepth = 6;   // d = 9..16
+
 template <int D>
 int64_t tb_partials_d(int N)
 {
@@ -363,9 +382,13 @@ int64_t tb_partials_d(int N)
         case 4: return tb_partials<D, 4>();
         case 5: return tb_partials<D, 5>();
         case 6: return tb_partials<D, 6>();
-        case 7: return tb_partials<D, 7>();
-        case 8: return tb_partials<D, 8>();
-        case 9: return tb_partials<D, 9>();
+    }
+    if constexpr (D <= 8) {
+        switch (N) {
+            case 7: return tb_partials<D, 7>();
+            case 8: return tb_partials<D, 8>();
+            case 9: return tb_partials<D, 9>();
+        }
     }
     return -1;
 }
@@ -380,9 +403,13 @@ hipError_t launch_tb_d(const Shape &sh, const T *path, const T *sig, const T *go
         case 4: return launch_tb_dn<T, D, 4>(sh, path, sig, gout, gpath, gbase, partial, st);
         case 5: return launch_tb_dn<T, D, 5>(sh, path, sig, gout, gpath, gbase, partial, st);
         case 6: return launch_tb_dn<T, D, 6>(sh, path, sig, gout, gpath, gbase, partial, st);
-        case 7: return launch_tb_dn<T, D, 7>(sh, path, sig, gout, gpath, gbase, partial, st);
-        case 8: return launch_tb_dn<T, D, 8>(sh, path, sig, gout, gpath, gbase, partial, st);
-        case 9: return launch_tb_dn<T, D, 9>(sh, path, sig, gout, gpath, gbase, partial, st);
+    }
+    if constexpr (D <= 8) {
+        switch (sh.N) {
+            case 7: return launch_tb_dn<T, D, 7>(sh, path, sig, gout, gpath, gbase, partial, st);
+            case 8: return launch_tb_dn<T, D, 8>(sh, path, sig, gout, gpath, gbase, partial, st);
+            case 9: return launch_tb_dn<T, D, 9>(sh, path, sig, gout, gpath, gbase, partial, st);
+        }
     }
     return hipErrorNotSupported;
 }
@@ -391,7 +418,8 @@ hipError_t launch_tb_d(const Shape &sh, const T *path, const T *sig, const T *go
 // Bytes of partial gradients for this shape with elements of `elem` bytes; -1 if the family does not serve it.
 inline int64_t tb_workspace_bytes(const Shape &sh, int64_t elem)
 {
-    if (sh.d < 2 || sh.d > 8 || sh.N < 2 || sh.N > 9 || sh.S >= (int64_t(1) << 31)) return -1;
+    if (sh.d < 2 || sh.d > 16 || sh.N < 2 || sh.N > (sh.d <= 8 ? kTbMaxDepth : kTbWideMaxDepth) || sh.S >= (int64_t(1) << 31))
+        return -1;
     int64_t partials = -1;
     switch (sh.d) {
         case 2: partials = tb_partials_d<2>(sh.N); break;
@@ -401,12 +429,21 @@ inline int64_t tb_workspace_bytes(const Shape &sh, int64_t elem)
         case 6: partials = tb_partials_d<6>(sh.N); break;
         case 7: partials = tb_partials_d<7>(sh.N); break;
         case 8: partials = tb_partials_d<8>(sh.N); break;
+        case 9: partials = tb_partials_d<9>(sh.N); break;
+        case 10: partials = tb_partials_d<10>(sh.N); break;
+        case 11: partials = tb_partials_d<11>(sh.N); break;
+        case 12: partials = tb_partials_d<12>(sh.N); break;
+        case 13: partials = tb_partials_d<13>(sh.N); break;
+        case 14: partials = tb_partials_d<14>(sh.N); break;
+        case 15: partials = tb_partials_d<15>(sh.N); break;
+        case 16: partials = tb_partials_d<16>(sh.N); break;
     }
     if (partials < 0) return -1;
     return sh.B * partials * sh.n_inc * sh.d * elem;
 }
 
-template <typename T>
+// WIDE: the translation unit that instantiates d = 9..16; the other one instantiates d = 2..8 and hands wider calls on.
+template <typename T, bool WIDE>
 hipError_t launch_tb(const Shape &sh, const T *path, const T *sig, const T *gout, T *gpath, T *gbase, void *workspace,
                      int64_t workspace_bytes, hipStream_t st)
 {
@@ -414,14 +451,28 @@ hipError_t launch_tb(const Shape &sh, const T *path, const T *sig, const T *gout
     if (need < 0) return hipErrorNotSupported;
     if (workspace == nullptr || workspace_bytes < need) return hipErrorInvalidValue;
     T *partial = static_cast<T *>(workspace);
-    switch (sh.d) {
-        case 2: return launch_tb_d<T, 2>(sh, path, sig, gout, gpath, gbase, partial, st);
-        case 3: return launch_tb_d<T, 3>(sh, path, sig, gout, gpath, gbase, partial, st);
-        case 4: return launch_tb_d<T, 4>(sh, path, sig, gout, gpath, gbase, partial, st);
-        case 5: return launch_tb_d<T, 5>(sh, path, sig, gout, gpath, gbase, partial, st);
-        case 6: return launch_tb_d<T, 6>(sh, path, sig, gout, gpath, gbase, partial, st);
-        case 7: return launch_tb_d<T, 7>(sh, path, sig, gout, gpath, gbase, partial, st);
-        case 8: return launch_tb_d<T, 8>(sh, path, sig, gout, gpath, gbase, partial, st);
+    if constexpr (WIDE) {
+        switch (sh.d) {
+            case 9: return launch_tb_d<T, 9>(sh, path, sig, gout, gpath, gbase, partial, st);
+            case 10: return launch_tb_d<T, 10>(sh, path, sig, gout, gpath, gbase, partial, st);
+            case 11: return launch_tb_d<T, 11>(sh, path, sig, gout, gpath, gbase, partial, st);
+            case 12: return launch_tb_d<T, 12>(sh, path, sig, gout, gpath, gbase, partial, st);
+            case 13: return launch_tb_d<T, 13>(sh, path, sig, gout, gpath, gbase, partial, st);
+            case 14: return launch_tb_d<T, 14>(sh, path, sig, gout, gpath, gbase, partial, st);
+            case 15: return launch_tb_d<T, 15>(sh, path, sig, gout, gpath, gbase, partial, st);
+            case 16: return launch_tb_d<T, 16>(sh, path, sig, gout, gpath, gbase, partial, st);
+        }
+    } else {
+        if (sh.d > 8) return launch_tree_backward_wide(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
+        switch (sh.d) {
+            case 2: return launch_tb_d<T, 2>(sh, path, sig, gout, gpath, gbase, partial, st);
+            case 3: return launch_tb_d<T, 3>(sh, path, sig, gout, gpath, gbase, partial, st);
+            case 4: return launch_tb_d<T, 4>(sh, path, sig, gout, gpath, gbase, partial, st);
+            case 5: return launch_tb_d<T, 5>(sh, path, sig, gout, gpath, gbase, partial, st);
+            case 6: return launch_tb_d<T, 6>(sh, path, sig, gout, gpath, gbase, partial, st);
+            case 7: return launch_tb_d<T, 7>(sh, path, sig, gout, gpath, gbase, partial, st);
+            case 8: return launch_tb_d<T, 8>(sh, path, sig, gout, gpath, gbase, partial, st);
+        }
     }
     return hipErrorNotSupported;
 }

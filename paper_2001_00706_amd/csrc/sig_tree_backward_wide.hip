@@ -1,0 +1,12 @@
+// fp32 instantiation of the prefix-tree gradient kernels for d = 9..16 (see sig_tree_backward_impl.h).
+#include "sig_tree_backward_impl.h"
+
+namespace sig {
+
+hipError_t launch_tree_backward_wide(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
+                                     float *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st)
+{
+    return launch_tb<float, true>(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
+}
+
+}  // namespace sig

@@ -88,8 +88,7 @@ def test_register_resident_kernels_every_depth(d, N):
 
 
 def test_final_mode_families_on_both_sides_of_their_batch_thresholds():
-    # with one gradient per path the prefix-tree kernels serve most shapes; d = 2, N = 9 goes to the register-resident
-    # kernel above 512 paths, d = 4 at N >= 5 below 512 paths
+    # with one gradient per path the prefix-tree kernels serve every shape but d = 4 at N >= 5 below 512 paths
     check(brownian_paths(520, 6, 2, seed=3), 9, sample=[0, 1, 255, 519])
     check(brownian_paths(8, 6, 2, seed=4), 9)
     check(brownian_paths(515, 7, 4, seed=5), 5, sample=[0, 300, 514])
@@ -102,6 +101,8 @@ def test_final_mode_families_on_both_sides_of_their_batch_thresholds():
     (2, 8, 4, 9), (2, 10, 4, 8), (2, 9, 4, 7), (3, 40, 3, 7), (2, 12, 5, 7), (2, 9, 6, 7), (2, 70, 5, 4),
     (37, 6, 3, 4),     # 9 threads per path: 16 paths share a workgroup, the last workgroup is ragged
     (5, 5, 7, 2), (3, 7, 6, 3), (4, 9, 3, 2),
+    # 9 to 16 channels (one level per thread below its word), depths 2..6
+    (3, 9, 9, 2), (20, 7, 16, 2), (2, 40, 16, 3), (3, 9, 10, 4), (2, 6, 16, 4), (2, 5, 11, 5), (1, 4, 9, 6), (2, 70, 13, 3),
 ])
 def test_prefix_tree_kernels(B, L, d, N):
     # fp32 shapes that neither the d = 4 nor the power-of-two register kernels serve
@@ -119,6 +120,13 @@ def test_prefix_tree_kernels_on_unaligned_buffers(d, N):
     x = brownian_paths(3, 40, d, seed=d + N)
     for stream in (False, True):
         check(x, N, stream=stream, basepoint=stream, misalign=True)
+
+
+def test_prefix_tree_kernels_wide_in_fp64():
+    for B, L, d, N in [(2, 9, 16, 3), (3, 6, 10, 4), (5, 7, 12, 2)]:
+        x = brownian_paths(B, L, d, seed=B + d).astype(np.float64)
+        check(x, N)
+        check(x, N, stream=True, basepoint=True)
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])

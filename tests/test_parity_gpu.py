@@ -433,6 +433,9 @@ def test_chunked_scan_argument_checks():
     (2, 20, 4, 9), (2, 12, 4, 8), (3, 15, 5, 7), (2, 10, 6, 7), (5, 40, 3, 7), (4, 70, 2, 9),
     (37, 6, 3, 4),     # 9 words per path: 16 paths share a workgroup, the last workgroup is ragged
     (5, 5, 8, 2), (3, 7, 6, 3), (1, 2, 2, 2),
+    # 9 to 16 channels: one level of d scalars per thread below its word, depths 2..6
+    (3, 9, 9, 2), (20, 7, 16, 2), (2, 40, 16, 3), (3, 9, 10, 4), (2, 6, 16, 4), (2, 5, 11, 5), (1, 4, 9, 6), (2, 70, 13, 3),
+    (2, 6, 12, 4), (1, 5, 14, 3), (1, 5, 15, 3),
 ])
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 def test_prefix_tree_family(B, L, d, N, dtype):
