@@ -94,7 +94,9 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
             if (shard_ok && sh.stream && sh.N >= 5 && sh.B >= 1024 && tree_ok) return Family::Tree;
             if (shard_ok && (!mfma_ok || sh.B < 512)) return Family::MfmaShard;
             if (mfma_ok) return Family::Mfma;
-            if (d16_ok) return Family::MfmaD16;
+            // one workgroup per path leaves the chip idle below ~48 paths (B = 8: 45 us against 25 for the prefix-tree
+            // kernel, which spreads a path over 16 workgroups)
+            if (d16_ok && !(sh.B < 48 && tree_ok)) return Family::MfmaD16;
             // 64 wavefronts per path pay off while paths are few; from 512 paths on each shard's own prefix sums
             // are pure overhead (N = 4 at B = 2048: 170 us against 62 for the prefix-tree kernel); N = 6 stays
             if (d8_ok && !(sh.N <= 5 && sh.B >= 512 && tree_ok)) return Family::MfmaD8;
