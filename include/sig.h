@@ -229,8 +229,9 @@ sig_status sig_lyndon_gather(const void *log_sig, int64_t rows, int d, int N, co
  * grad_sig = dLoss/d sig.  Deterministic: partial sums are added in a fixed order, no atomics.
  *   sig, grad_log  DEVICE pointers [rows][S], read only.   grad_sig  DEVICE pointer [rows][S], overwritten; must
  *              not overlap the other two.
- *   workspace  DEVICE pointer, 16-byte aligned, at least sig_log_backward_workspace_bytes(...) bytes (0 for N = 1,
- *              then it may be NULL); contents undefined on return.
+ *   workspace  DEVICE pointer, 16-byte aligned, at least sig_log_backward_workspace_bytes(...) bytes (0 for N = 1
+ *              and for signatures small enough for the single-launch kernel; then it may be NULL); contents
+ *              undefined on return.
  * Errors as for sig_combine; a missing, short or misaligned workspace is SIG_ERR_INVALID_ARG. */
 sig_status sig_log_backward(const void *sig, const void *grad_log, int64_t rows, int d, int N, sig_dtype dtype,
                             void *grad_sig, void *workspace, int64_t workspace_bytes, hipStream_t hip_stream);

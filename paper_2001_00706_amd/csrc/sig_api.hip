@@ -497,7 +497,10 @@ sig_status sig_log_backward(const void *sig, const void *grad_log, int64_t rows,
 
 int64_t sig_combine_backward_workspace_bytes(int64_t B, int d, int N, sig_dtype dtype)
 {
-    return sig_log_backward_workspace_bytes(B, d, N, dtype);
+    if (dtype != SIG_F32 && dtype != SIG_F64) return -1;
+    sig::Shape sh;
+    if (make_rows_shape(B, d, N, sh) != SIG_OK || !sig::combine_supported(sh)) return -1;
+    return sig::combine_backward_workspace_bytes(sh, dtype);
 }
 
 sig_status sig_combine_backward(const void *a, const void *b, const void *grad_out, int64_t B, int d, int N, sig_dtype dtype,
@@ -512,7 +515,7 @@ sig_status sig_combine_backward(const void *a, const void *b, const void *grad_o
         grad_a == grad_out || grad_b == grad_out || grad_a == a || grad_a == b || grad_b == a || grad_b == b)
         return SIG_ERR_INVALID_ARG;
     if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
-    const int64_t need = sig::log_backward_workspace_bytes(sh, dtype);
+    const int64_t need = sig::combine_backward_workspace_bytes(sh, dtype);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16 != 0))
         return SIG_ERR_INVALID_ARG;
     const hipError_t err =

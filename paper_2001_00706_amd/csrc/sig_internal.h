@@ -86,11 +86,12 @@ int64_t lyndon_indices_host(const Shape &sh, int64_t *indices, int64_t cap);
 
 // Gradient through the logarithm (sh.B rows; S < 2^31) and through the selection of the Lyndon words.
 int64_t log_backward_workspace_bytes(const Shape &sh, sig_dtype dtype);
+int64_t combine_backward_workspace_bytes(const Shape &sh, sig_dtype dtype);
 hipError_t launch_log_backward_f32(const Shape &sh, const float *sig, const float *grad_log, float *grad_sig, void *workspace,
                                    hipStream_t st);
 hipError_t launch_log_backward_f64(const Shape &sh, const double *sig, const double *grad_log, double *grad_sig, void *workspace,
                                    hipStream_t st);
-// Gradient of the group product out = a [x] b; same workspace as the logarithm's gradient.
+// Gradient of the group product out = a [x] b; workspace: combine_backward_workspace_bytes.
 hipError_t launch_combine_backward_f32(const Shape &sh, const float *a, const float *b, const float *g, float *ga, float *gb,
                                        void *workspace, hipStream_t st);
 hipError_t launch_combine_backward_f64(const Shape &sh, const double *a, const double *b, const double *g, double *ga, double *gb,

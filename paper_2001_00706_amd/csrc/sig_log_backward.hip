@@ -254,6 +254,173 @@ log_bwd_finish_kernel(LbStep stp, int64_t rows, T c_m, T c_last, int first, int 
     gx[row * gx_stride + rho] = val;
 }
 
+// Everything above in one launch for signatures small enough to live in LDS: one workgroup per signature keeps x,
+// the R_m, two cotangent buffers and the gradient on chip and walks the same matrices M_l, a whole matrix at a
+// time, so that column sums stay in registers (or, beyond 256 columns, in LDS) and row dots are added straight
+// into the gradient: no partial sums, no second kernel, no workspace.  A barrier separates the matrices of a
+// step (they all add into the first rows of the gradient).
+// The incoming gradient is copied into LDS first: a pass that waited for global memory at every barrier took
+// ten times longer.
+//   LDS layout (scalars): x[S] | R_N .. R_2 [r_stride] | Ga[S] (G_1, G_3, ..) | Gb[S(N-1)] (G_2, G_4, ..) | gx[S] |
+//                         prod[2][NT] | wsum[NT / 64]
+// NT = 256 threads for the smallest signatures (several workgroups per compute unit), 1024 beyond 2048 scalars,
+// where one signature fills the LDS of a compute unit anyway and four wavefronts per SIMD issue faster than one.
+template <typename T, int NT>
+__global__ void __launch_bounds__(NT)
+log_bwd_fused_kernel(Shape sh, int64_t r_stride, const T *__restrict__ x_g, const T *__restrict__ g_g, T *__restrict__ gx_g)
+{
+    extern __shared__ __align__(16) unsigned char lb_smem[];
+    __shared__ uint32_t off[SIG_MAX_DEPTH + 2], pw[SIG_MAX_DEPTH + 1];
+    const int N = sh.N;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t d = uint32_t(sh.d), S = uint32_t(sh.S);
+    if (tid <= uint32_t(N) + 1) off[tid] = uint32_t(sh.off[tid]);
+    if (tid <= uint32_t(N)) pw[tid] = uint32_t(sh.pw[tid]);
+    __syncthreads();
+    const uint32_t S_low = off[N];   // S(N - 1)
+    T *xs = reinterpret_cast<T *>(lb_smem);
+    T *Rs = xs + S;
+    T *Gb[2] = {Rs + r_stride + S, Rs + r_stride};   // Gb[m & 1] holds G_m: odd m in the long buffer
+    T *gxs = Gb[0] + S_low;
+    T *prod = gxs + S;               // [2][256]
+    T *wsum = prod + 2 * NT;  // [NT / 64]
+    auto coef = [](int m) { return (m & 1 ? T(1) : T(-1)) / T(m); };
+    auto r_at = [&](int m) {   // R_m inside Rs: R_N first
+        uint32_t o = 0;
+        for (int mm = N; mm > m; --mm) o += off[N - mm + 2];
+        return Rs + o;
+    };
+
+    for (int64_t row = blockIdx.x; row < sh.B; row += gridDim.x) {
+        const T *g_row = g_g + row * S;
+        __syncthreads();   // the previous signature's gradient has been written out
+        for (uint32_t i = tid; i < S; i += NT) {
+            xs[i] = x_g[row * S + i];
+            Gb[1][i] = g_row[i];
+        }
+        __syncthreads();
+        // R_m = c_m x + x * R_{m+1}, levels 1..N-m+1
+        for (int m = N; m >= 2; --m) {
+            const int n = N - m + 1;
+            const T c = coef(m);
+            T *r_out = r_at(m);
+            const T *r_next = m == N ? nullptr : r_at(m + 1);
+            for (uint32_t q = tid; q < off[n + 1]; q += NT) {
+                int k = 1;
+                while (k < n && q >= off[k + 1]) ++k;
+                T acc = c * xs[q];
+                if (r_next != nullptr) {
+                    uint32_t prefix = q - off[k], suffix = 0, scale = 1;
+                    for (int j = k - 1; j >= 1; --j) {
+                        const uint32_t letter = prefix % d;
+                        prefix /= d;
+                        suffix += letter * scale;
+                        scale *= d;
+                        acc += xs[off[j] + prefix] * r_next[off[k - j] + suffix];
+                    }
+                }
+                r_out[q] = acc;
+            }
+            __syncthreads();
+        }
+        for (int m = 1; m <= N - 1; ++m) {
+            const int n = N - m + 1;
+            const T *G = Gb[m & 1];
+            T *Gn = Gb[(m + 1) & 1];
+            const T *R = r_at(m + 1);
+            const T c = coef(m);
+            for (uint32_t q = tid; q < off[n + 1]; q += NT) gxs[q] = (m == 1 ? T(0) : gxs[q]) + c * G[q];
+            __syncthreads();
+            for (int l = 1; l <= n - 1; ++l) {
+                const uint32_t C = pw[l], U = off[n - l + 1];
+                const T *M = G + off[l + 1];
+                const T *Rl = R + off[l];
+                T *Gl = Gn + off[l];
+                if (C <= uint32_t(NT)) {
+                    const uint32_t rpw = uint32_t(NT) / C;
+                    uint32_t tpr = uint32_t(NT) / rpw, lg = 0;
+                    tpr = tpr > 64 ? 64 : tpr;
+                    while ((2u << lg) <= tpr) ++lg;
+                    tpr = 1u << lg;
+                    const bool on = tid < rpw * C;
+                    const uint32_t prow = on ? tid / C : 0, col = on ? tid - prow * C : 0;
+                    const T rl = on ? Rl[col] : T(0);
+                    const uint32_t srow = tid >> lg, sub = tid & (tpr - 1);
+                    T acc = T(0);
+                    // pass r: products of rpw rows into prod[buf]; barrier; row sums out of prod[buf] into gx.  The
+                    // products of the next pass are formed before the sums of this one are taken, so that the two
+                    // chains of LDS round trips overlap.
+                    auto form = [&](uint32_t r, int buf) {
+                        const uint32_t mine = r + prow;
+                        T g = T(0);
+                        if (on && mine < U) {
+                            g = M[mine * C + col];
+                            acc += xs[mine] * g;
+                        }
+                        prod[buf * NT + tid] = g * rl;
+                    };
+                    form(0, 0);
+                    int buf = 0;
+                    for (uint32_t r = 0; r < U; r += rpw, buf ^= 1) {
+                        __syncthreads();
+                        if (r + rpw < U) form(r + rpw, buf ^ 1);
+                        T t = T(0);
+                        if (srow < rpw)
+                            for (uint32_t cc = sub; cc < C; cc += tpr) t += prod[buf * NT + srow * C + cc];
+                        t = lanes_sum(t, lg);
+                        if (sub == 0 && srow < rpw && r + srow < U) gxs[r + srow] += t;
+                    }
+                    // column sums: the rpw lanes of a column are folded in two stages (up to 16 at a time, then the
+                    // up to 16 group sums), never one long loop in a single thread
+                    __syncthreads();
+                    prod[tid] = acc;
+                    __syncthreads();
+                    const uint32_t groups = (rpw + 15) / 16;
+                    if (tid < groups * C) {
+                        const uint32_t grp = tid / C, cc = tid - grp * C;
+                        const uint32_t p_end = grp * 16 + 16 < rpw ? grp * 16 + 16 : rpw;
+                        T t = T(0);
+                        for (uint32_t pr = grp * 16; pr < p_end; ++pr) t += prod[pr * C + cc];
+                        prod[NT + tid] = t;
+                    }
+                    __syncthreads();
+                    if (tid < C) {
+                        T t = T(0);
+                        for (uint32_t grp = 0; grp < groups; ++grp) t += prod[NT + grp * C + tid];
+                        Gl[tid] = t;
+                    }
+                } else {
+                    // a row at a time, the lanes striding over its columns; column sums accumulate in LDS
+                    for (uint32_t r = 0; r < U; ++r) {
+                        const T xv = xs[r];
+                        T part = T(0);
+                        for (uint32_t col = tid; col < C; col += NT) {
+                            const T g = M[r * C + col];
+                            Gl[col] = (r == 0 ? T(0) : Gl[col]) + xv * g;
+                            part += g * Rl[col];
+                        }
+                        part = group_sum<0, 6, T>(part);
+                        if ((tid & 63) == 0) wsum[tid >> 6] = part;
+                        __syncthreads();
+                        if (tid == 0) {
+                            T total = wsum[0];
+                            for (int v = 1; v < NT / 64; ++v) total += wsum[v];
+                            gxs[r] += total;
+                        }
+                        __syncthreads();
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        // G_N has one level
+        const T *G_last = Gb[N & 1];
+        if (tid < d) gxs[tid] += coef(N) * G_last[tid];
+        __syncthreads();
+        for (uint32_t i = tid; i < S; i += NT) gx_g[row * S + i] = gxs[i];
+    }
+}
+
 template <typename T>
 __global__ void __launch_bounds__(kLbThreads)
 fill_zero_kernel(T *__restrict__ p, int64_t n)
@@ -351,6 +518,23 @@ LbWorkspace plan_workspace(const Shape &sh, int64_t elem)
     return ws;
 }
 
+// The single-launch kernel: its workgroup size, the LDS it needs (x, the R_m, two cotangent buffers, the gradient,
+// products and wavefront sums) and when it is used.  Measured against the chain of launches at d = 4, L = 128:
+// N <= 5 (S <= 1364): 14-34 us against 31-61 whatever the batch; N = 6 (S = 5460): 60 us against 73 at 32 signatures,
+// but 186-230 us against 174 at 1024, where a compute unit holds one or two signatures at a time.
+constexpr size_t kLbFusedMaxLds = 128 * 1024;
+constexpr int64_t kLbFusedSmall = 2048;   // scalars up to which the kernel is used at any batch size
+int fused_threads(const Shape &sh) { return sh.S <= kLbFusedSmall ? 256 : 1024; }
+size_t fused_lds_bytes(const Shape &sh, const LbWorkspace &ws, size_t elem)
+{
+    const int nt = fused_threads(sh);
+    return size_t(3 * sh.S + ws.r_stride + ws.g_stride + 2 * nt + nt / 64) * elem;
+}
+bool use_fused(const Shape &sh, const LbWorkspace &ws, size_t elem)
+{
+    return fused_lds_bytes(sh, ws, elem) <= kLbFusedMaxLds && (sh.S <= kLbFusedSmall || sh.B <= 256);
+}
+
 // offset, inside a batch row's share of the R buffer, of R_m (m = 2..N): R_N first
 int64_t r_offset(const Shape &sh, int m)
 {
@@ -373,6 +557,19 @@ hipError_t launch_log_backward(const Shape &sh, const T *x, const T *g, T *gx, v
     const int N = sh.N;
     if (N == 1) return hipMemcpyAsync(gx, g, size_t(sh.B * sh.S) * sizeof(T), hipMemcpyDeviceToDevice, st);
     const LbWorkspace ws = plan_workspace(sh, int64_t(sizeof(T)));
+    if (use_fused(sh, ws, sizeof(T))) {
+        const size_t fused_lds = fused_lds_bytes(sh, ws, sizeof(T));
+        const bool small = fused_threads(sh) == 256;
+        auto kernel = small ? log_bwd_fused_kernel<T, 256> : log_bwd_fused_kernel<T, 1024>;
+        if (fused_lds > 64 * 1024) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, int(fused_lds));
+            if (e != hipSuccess) return e;
+        }
+        const unsigned grid = unsigned(sh.B < (int64_t(1) << 20) ? sh.B : (int64_t(1) << 20));
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(small ? 256 : 1024), fused_lds, st, sh, ws.r_stride, x, g, gx);
+        return hipGetLastError();
+    }
     char *base = static_cast<char *>(workspace);
     T *Rs = reinterpret_cast<T *>(base + ws.r_off);
     T *Gb[2] = {reinterpret_cast<T *>(base + ws.g0_off), reinterpret_cast<T *>(base + ws.g1_off)};
@@ -465,6 +662,13 @@ hipError_t launch_scatter(const Shape &sh, const T *in, const int64_t *index, in
 }  // namespace
 
 int64_t log_backward_workspace_bytes(const Shape &sh, sig_dtype dtype)
+{
+    const int64_t elem = dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double));
+    const LbWorkspace ws = plan_workspace(sh, elem);
+    return sh.N >= 2 && use_fused(sh, ws, size_t(elem)) ? 0 : ws.total;   // the single-launch kernel needs none
+}
+
+int64_t combine_backward_workspace_bytes(const Shape &sh, sig_dtype dtype)
 {
     return plan_workspace(sh, dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double))).total;
 }

@@ -287,7 +287,8 @@ def test_a_training_step_can_be_captured_in_a_graph_and_replayed():
     g_words = torch.from_numpy(np.random.default_rng(3).standard_normal((8, sig.sig_logsignature_channels(4, N)))
                                .astype(np.float32)).to("cuda:0")
     g_log, g_sig, g_a, g_b = (torch.empty_like(s) for _ in range(4))
-    ws = torch.empty(sig.sig_log_backward_workspace_bytes(8, 4, N), dtype=torch.uint8, device="cuda:0")
+    ws = torch.empty(max(sig.sig_log_backward_workspace_bytes(8, 4, N), sig.sig_combine_backward_workspace_bytes(8, 4, N)),
+                     dtype=torch.uint8, device="cuda:0")
 
     def step():
         sig.sig_forward(x, N, out=s)

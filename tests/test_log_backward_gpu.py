@@ -87,7 +87,7 @@ def test_scatter_is_the_transpose_of_gather():
 
 def test_workspace_is_checked():
     import torch
-    d, N = 2, 4
+    d, N = 4, 7     # 21 844 scalars per signature: the chain of launches, which needs a workspace
     x = dev(orc.signature(brownian_paths(2, 5, d, seed=1), N))
     need = sig.sig_log_backward_workspace_bytes(2, d, N, sig.SIG_F64)
     assert need > 0
@@ -95,6 +95,20 @@ def test_workspace_is_checked():
     with pytest.raises(sig.SigError):
         sig.sig_log_backward(x, x.clone(), d, N, workspace=short)
     assert sig.sig_log_backward_workspace_bytes(2, d, 1, sig.SIG_F64) == 0
+    assert sig.sig_log_backward_workspace_bytes(2, 2, 4, sig.SIG_F64) == 0      # single launch, everything in LDS
+
+
+def test_both_routes_agree_on_the_same_shape():
+    # d = 4, N = 6: 8 signatures go through the single-launch kernel, 300 through the chain of launches
+    d, N = 4, 6
+    x = orc.signature(brownian_paths(300, 6, d, seed=12), N).astype(np.float64)
+    g = np.random.default_rng(4).standard_normal(x.shape)
+    many = host(sig.sig_log_backward(dev(x), dev(g), d, N))
+    few = host(sig.sig_log_backward(dev(x[:8]), dev(g[:8]), d, N))
+    want = orc.tensor_log_backward(x[:8], g[:8], d, N)
+    scale = orc.tensor_log_backward(-np.abs(x[:8]), np.abs(g[:8]), d, N)
+    assert_grad_close(few, want, scale, d, N, np.float64)
+    assert_grad_close(many[:8], want, scale, d, N, np.float64)
 
 
 @pytest.mark.parametrize("stream", [False, True])
