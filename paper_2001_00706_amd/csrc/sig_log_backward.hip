@@ -27,6 +27,7 @@ constexpr int kLbThreads = 256;
 constexpr int kLbWideRows = 16;   // rows between two workgroup barriers in a matrix with more than 256 columns
 constexpr int kLbWideCols = 8;    // columns per lane there: a workgroup spans 2048 columns
 constexpr uint32_t kLbMaxPartials = 32;   // partial sums per output the planner aims for
+constexpr int kFusedRows = 4;             // passes the single-launch kernel forms between two barriers
 
 struct LbLevel {               // the matrix M_l of one step
     uint32_t C;                // columns, d^l
@@ -259,10 +260,10 @@ log_bwd_finish_kernel(LbStep stp, int64_t rows, T c_m, T c_last, int first, int 
 // time, so that column sums stay in registers (or, beyond 256 columns, in LDS) and row dots are added straight
 // into the gradient: no partial sums, no second kernel, no workspace.  A barrier separates the matrices of a
 // step (they all add into the first rows of the gradient).
-// The incoming gradient is copied into LDS first: a pass that waited for global memory at every barrier took
-// ten times longer.
-//   LDS layout (scalars): x[S] | R_N .. R_2 [r_stride] | Ga[S] (G_1, G_3, ..) | Gb[S(N-1)] (G_2, G_4, ..) | gx[S] |
-//                         prod[2][NT] | wsum[NT / 64]
+// The incoming gradient G_1 is read from global memory (staging it in LDS as well changed nothing), kFusedRows
+// passes are formed between two barriers.
+//   LDS layout (scalars): x[S] | R_N .. R_2 [r_stride] | G[2][S(N-1)] (G_2, G_3, ..) | gx[S] |
+//                         prod[2][kFusedRows][NT] | wsum[NT / 64]
 // NT = 256 threads for the smallest signatures (several workgroups per compute unit), 1024 beyond 2048 scalars,
 // where one signature fills the LDS of a compute unit anyway and four wavefronts per SIMD issue faster than one.
 template <typename T, int NT>
@@ -280,10 +281,10 @@ log_bwd_fused_kernel(Shape sh, int64_t r_stride, const T *__restrict__ x_g, cons
     const uint32_t S_low = off[N];   // S(N - 1)
     T *xs = reinterpret_cast<T *>(lb_smem);
     T *Rs = xs + S;
-    T *Gb[2] = {Rs + r_stride + S, Rs + r_stride};   // Gb[m & 1] holds G_m: odd m in the long buffer
-    T *gxs = Gb[0] + S_low;
+    T *Gb[2] = {Rs + r_stride, Rs + r_stride + S_low};   // Gb[m & 1] holds G_m, m >= 2
+    T *gxs = Gb[1] + S_low;
     T *prod = gxs + S;               // [2][256]
-    T *wsum = prod + 2 * NT;  // [NT / 64]
+    T *wsum = prod + 2 * kFusedRows * NT;  // [NT / 64]
     auto coef = [](int m) { return (m & 1 ? T(1) : T(-1)) / T(m); };
     auto r_at = [&](int m) {   // R_m inside Rs: R_N first
         uint32_t o = 0;
@@ -294,10 +295,7 @@ log_bwd_fused_kernel(Shape sh, int64_t r_stride, const T *__restrict__ x_g, cons
     for (int64_t row = blockIdx.x; row < sh.B; row += gridDim.x) {
         const T *g_row = g_g + row * S;
         __syncthreads();   // the previous signature's gradient has been written out
-        for (uint32_t i = tid; i < S; i += NT) {
-            xs[i] = x_g[row * S + i];
-            Gb[1][i] = g_row[i];
-        }
+        for (uint32_t i = tid; i < S; i += NT) xs[i] = x_g[row * S + i];
         __syncthreads();
         // R_m = c_m x + x * R_{m+1}, levels 1..N-m+1
         for (int m = N; m >= 2; --m) {
@@ -325,7 +323,7 @@ log_bwd_fused_kernel(Shape sh, int64_t r_stride, const T *__restrict__ x_g, cons
         }
         for (int m = 1; m <= N - 1; ++m) {
             const int n = N - m + 1;
-            const T *G = Gb[m & 1];
+            const T *G = m == 1 ? g_row : Gb[m & 1];
             T *Gn = Gb[(m + 1) & 1];
             const T *R = r_at(m + 1);
             const T c = coef(m);
@@ -351,42 +349,59 @@ log_bwd_fused_kernel(Shape sh, int64_t r_stride, const T *__restrict__ x_g, cons
                     // products of the next pass are formed before the sums of this one are taken, so that the two
                     // chains of LDS round trips overlap.
                     auto form = [&](uint32_t r, int buf) {
-                        const uint32_t mine = r + prow;
-                        T g = T(0);
-                        if (on && mine < U) {
-                            g = M[mine * C + col];
-                            acc += xs[mine] * g;
+#pragma unroll
+                        for (int v = 0; v < kFusedRows; ++v) {
+                            const uint32_t mine = r + v * rpw + prow;
+                            T g = T(0);
+                            if (on && mine < U) {
+                                g = M[mine * C + col];
+                                acc += xs[mine] * g;
+                            }
+                            prod[(buf * kFusedRows + v) * NT + tid] = g * rl;
                         }
-                        prod[buf * NT + tid] = g * rl;
                     };
                     form(0, 0);
                     int buf = 0;
-                    for (uint32_t r = 0; r < U; r += rpw, buf ^= 1) {
+                    for (uint32_t r = 0; r < U; r += kFusedRows * rpw, buf ^= 1) {
                         __syncthreads();
-                        if (r + rpw < U) form(r + rpw, buf ^ 1);
-                        T t = T(0);
-                        if (srow < rpw)
-                            for (uint32_t cc = sub; cc < C; cc += tpr) t += prod[buf * NT + srow * C + cc];
-                        t = lanes_sum(t, lg);
-                        if (sub == 0 && srow < rpw && r + srow < U) gxs[r + srow] += t;
+                        if (r + kFusedRows * rpw < U) form(r + kFusedRows * rpw, buf ^ 1);
+#pragma unroll
+                        for (int v = 0; v < kFusedRows; ++v) {
+                            const uint32_t r_v = r + v * rpw;
+                            if (r_v >= U) break;   // the same for every thread
+                            const T *pv = prod + (buf * kFusedRows + v) * NT;
+                            T t = T(0);
+                            if (srow < rpw)
+                                for (uint32_t cc = sub; cc < C; cc += tpr) t += pv[srow * C + cc];
+                            t = lanes_sum(t, lg);
+                            if (sub == 0 && srow < rpw && r_v + srow < U) gxs[r_v + srow] += t;
+                        }
                     }
                     // column sums: the rpw lanes of a column are folded in two stages (up to 16 at a time, then the
                     // up to 16 group sums), never one long loop in a single thread
                     __syncthreads();
                     prod[tid] = acc;
                     __syncthreads();
-                    const uint32_t groups = (rpw + 15) / 16;
+                    const uint32_t groups = (rpw + 15) / 16;   // groups * C <= NT: the second half of prod holds them
                     if (tid < groups * C) {
                         const uint32_t grp = tid / C, cc = tid - grp * C;
-                        const uint32_t p_end = grp * 16 + 16 < rpw ? grp * 16 + 16 : rpw;
                         T t = T(0);
-                        for (uint32_t pr = grp * 16; pr < p_end; ++pr) t += prod[pr * C + cc];
+#pragma unroll
+                        for (uint32_t k = 0; k < 16; ++k) {   // fixed trip count: the 16 reads are in flight together
+                            const uint32_t pr = grp * 16 + k;
+                            t += pr < rpw ? prod[pr * C + cc] : T(0);
+                        }
                         prod[NT + tid] = t;
                     }
                     __syncthreads();
                     if (tid < C) {
                         T t = T(0);
-                        for (uint32_t grp = 0; grp < groups; ++grp) t += prod[NT + grp * C + tid];
+                        if (groups <= 16) {
+#pragma unroll
+                            for (uint32_t grp = 0; grp < 16; ++grp) t += grp < groups ? prod[NT + grp * C + tid] : T(0);
+                        } else {
+                            for (uint32_t grp = 0; grp < groups; ++grp) t += prod[NT + grp * C + tid];
+                        }
                         Gl[tid] = t;
                     }
                 } else {
@@ -528,7 +543,7 @@ int fused_threads(const Shape &sh) { return sh.S <= kLbFusedSmall ? 256 : 1024; 
 size_t fused_lds_bytes(const Shape &sh, const LbWorkspace &ws, size_t elem)
 {
     const int nt = fused_threads(sh);
-    return size_t(3 * sh.S + ws.r_stride + ws.g_stride + 2 * nt + nt / 64) * elem;
+    return size_t(2 * sh.S + ws.r_stride + 2 * ws.g_stride + 2 * kFusedRows * nt + nt / 64) * elem;
 }
 bool use_fused(const Shape &sh, const LbWorkspace &ws, size_t elem)
 {
