@@ -260,15 +260,34 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
 #pragma unroll
             for (int k = 3; k <= N; ++k) t2[k] = __builtin_fmaf(t1[k], zf2 * (1.0f / (k - 1)), a2);
             f4 tab[N + 1][2];   // T_k^(3)[w], k = 4..N
+            // the eight prefix sums of level 3 advance together, step by step, so that the latency of one lane
+            // exchange is covered by the seven others
+            float zw[kD8], v3[kD8], in3[kD8];
 #pragma unroll
             for (int w = 0; w < kD8; ++w) {
-                const float zw = w < 4 ? z0[w & 3] : z1[w & 3];
-                float sum3;
-                const float a3 = A3[w] + wave_exclusive_scan(t2[3] * zw, sum3);
-                A3[w] += sum3;
+                zw[w] = w < 4 ? z0[w & 3] : z1[w & 3];
+                in3[w] = v3[w] = t2[3] * zw[w];
+            }
+#pragma unroll
+            for (int w = 0; w < kD8; ++w) v3[w] += dpp_or_zero<0x111, 0xf>(v3[w]);
+#pragma unroll
+            for (int w = 0; w < kD8; ++w) v3[w] += dpp_or_zero<0x112, 0xf>(v3[w]);
+#pragma unroll
+            for (int w = 0; w < kD8; ++w) v3[w] += dpp_or_zero<0x114, 0xf>(v3[w]);
+#pragma unroll
+            for (int w = 0; w < kD8; ++w) v3[w] += dpp_or_zero<0x118, 0xf>(v3[w]);
+#pragma unroll
+            for (int w = 0; w < kD8; ++w) v3[w] += dpp_or_zero<0x142, 0xa>(v3[w]);
+#pragma unroll
+            for (int w = 0; w < kD8; ++w) v3[w] += dpp_or_zero<0x143, 0xc>(v3[w]);
+#pragma unroll
+            for (int w = 0; w < kD8; ++w) {
+                const float total = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v3[w]), 63));
+                const float a3 = A3[w] + (v3[w] - in3[w]);   // exclusive prefix sum
+                A3[w] += total;
 #pragma unroll
                 for (int k = 4; k <= N; ++k)
-                    tab[k][w >> 2][w & 3] = __builtin_fmaf(t2[k], zw * (1.0f / (k - 2)), a3) * (1.0f / (k - 3));
+                    tab[k][w >> 2][w & 3] = __builtin_fmaf(t2[k], zw[w] * (1.0f / (k - 2)), a3) * (1.0f / (k - 3));
             }
             if (lane < nt) {
 #pragma unroll
