@@ -16,8 +16,9 @@
  * under the identification of appendix A.2.2.
  *
  * All functions are thread-safe and keep no state between calls.  Nothing here allocates
- * or frees device memory (sig_backward takes its workspace from the caller), and nothing
- * synchronises the device.
+ * or frees device memory: the calls that need scratch memory (sig_backward, sig_forward_chunked,
+ * sig_combine_many, sig_combine_backward, sig_log_backward) take a workspace from the caller,
+ * sized by their *_workspace_bytes companions.  Nothing synchronises the device.
  */
 #ifndef SIG_H_
 #define SIG_H_
@@ -54,8 +55,9 @@ typedef enum {
     SIG_VARIANT_MFMA_SHARD = 3,/* fp32, d = 4, N = 4..7, final and stream mode: four independent wavefronts
                                  per path, one per first letter */
     SIG_VARIANT_SMALL = 4,    /* any dtype and mode, S <= 512, N <= 8, d <= 64: one wavefront per path, state in LDS */
-    SIG_VARIANT_TREE = 5      /* any dtype and mode, d = 2..8, N = 2..9: a thread per word of N-2 letters, state in
-                                 registers, any number of workgroups per path (large signatures, few paths) */
+    SIG_VARIANT_TREE = 5      /* any dtype and mode; d = 2..8 at N = 2..9: a thread per word of N-2 letters; d = 9..16 at
+                                 N = 2..6: a thread per word of N-1 letters; state in registers, any number of
+                                 workgroups per path (large signatures, few paths) */
 } sig_variant;
 
 /* Largest depth the kernels accept. */
@@ -98,7 +100,10 @@ int64_t sig_fused_fmas(int d, int N);
  * untouched: SIG_ERR_INVALID_ARG for null pointers (with B > 0), B < 0, d < 1, N < 1 or
  * N > SIG_MAX_DEPTH, L < 2 (L < 1 with basepoint), an unknown dtype; SIG_ERR_OVERFLOW if a
  * size overflows; SIG_ERR_HIP if the launch failed.  B == 0 is SIG_OK and enqueues nothing.
- * Results are deterministic: the same inputs give bit-identical outputs on every call. */
+ * Results are deterministic: the same inputs give bit-identical outputs on every call.
+ * sig_forward scans every path (or every word-prefix shard of it) from end to end and never splits a path over
+ * its length, since it has no workspace for partial results: a few very long paths (B * shards far below the
+ * number of compute units, L in the tens of thousands) are served many times faster by sig_forward_chunked. */
 sig_status sig_forward(const void *path, int64_t B, int64_t L, int d, int N,
                        int stream, int basepoint, sig_dtype dtype,
                        void *out, hipStream_t hip_stream);

@@ -30,15 +30,13 @@
  * closed forms; the logarithm and its gradient (third part) by tests/test_oracle_log_pins.py.
  * Nothing here is "parity unpinned".
  *
- * SIG_ORACLE_MUTANT (never defined in a normal build) plants one deliberate mistake, numbered
- * below, so that tests/test_oracle_mutants.py can check that the pins notice each of them.
+ * The entry points are declared, each with the passage it follows, in sig_oracle.h.
  */
-#ifndef SIG_ORACLE_MUTANT
-#define SIG_ORACLE_MUTANT 0
-#endif
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+
+#include "sig_oracle.h"
 
 #ifdef _OPENMP
 #include <omp.h>
@@ -73,7 +71,6 @@ static int64_t level_offset(int d, int k)
 {
     int64_t off = 0;
     for (int j = 1; j < k; ++j) off += ipow64(d, j);
-    if (SIG_ORACLE_MUTANT == 8 && k == 3) off -= 1; /* mutant 8: level 3 overlaps level 2 */
     return off;
 }
 
@@ -88,7 +85,7 @@ void sig_oracle_exp(const double *z, int d, int N, double *E)
         const int64_t n_prev = ipow64(d, k - 1);
         for (int64_t w = 0; w < n_prev; ++w)
             for (int j = 0; j < d; ++j)
-                cur[w * d + j] = prev[w] * z[j] / (double)(SIG_ORACLE_MUTANT == 1 ? 2 : k); /* mutant 1: wrong factorial */
+                cur[w * d + j] = prev[w] * z[j] / (double)k;
     }
 }
 
@@ -103,8 +100,8 @@ void sig_oracle_mul(const double *A, const double *B, int d, int N, double *C)
         const int64_t n_k = ipow64(d, k);
         double *Ck = C + off_k;
         for (int64_t w = 0; w < n_k; ++w)
-            Ck[w] = B[off_k + w] + (SIG_ORACLE_MUTANT == 2 ? 0.0 : A[off_k + w]); /* mutant 2: A_k (x) B_0 dropped */
-        for (int j = (SIG_ORACLE_MUTANT == 3 ? 2 : 1); j <= k - 1; ++j) { /* mutant 3: the j = 1 term dropped */
+            Ck[w] = B[off_k + w] + A[off_k + w];
+        for (int j = 1; j <= k - 1; ++j) {
             const int m = k - j;
             const double *Aj = A + level_offset(d, j);
             const double *Bm = B + level_offset(d, m);
@@ -112,7 +109,7 @@ void sig_oracle_mul(const double *A, const double *B, int d, int N, double *C)
             const int64_t n_m = ipow64(d, m);
             for (int64_t u = 0; u < n_j; ++u)
                 for (int64_t v = 0; v < n_m; ++v)
-                    Ck[SIG_ORACLE_MUTANT == 4 ? v * n_j + u : u * n_m + v] += Aj[u] * Bm[v]; /* mutant 4: operands transposed */
+                    Ck[u * n_m + v] += Aj[u] * Bm[v];
         }
     }
 }
@@ -145,8 +142,7 @@ static int one_path(const double *x, int64_t L, int d, int N, int stream, int ba
                 hi = x[(s + 1) * d + c];
                 lo = x[s * d + c];
             }
-            z[c] = SIG_ORACLE_MUTANT == 5 ? lo - hi : hi - lo; /* mutant 5: sign of the increment */
-            if (SIG_ORACLE_MUTANT == 6 && basepoint && s == 0) z[c] = 0.0; /* mutant 6: basepoint ignored */
+            z[c] = hi - lo;
         }
         if (s == 0) {
             sig_oracle_exp(z, d, N, cur);
@@ -155,9 +151,7 @@ static int one_path(const double *x, int64_t L, int d, int N, int stream, int ba
             sig_oracle_mul(cur, E, d, N, nxt);
             double *t = cur; cur = nxt; nxt = t;
         }
-        if (stream && !(SIG_ORACLE_MUTANT == 7 && s + 1 < n_inc)) /* mutant 7: only the last prefix written */
-            memcpy(out + s * S, cur, sizeof(double) * (size_t)S);
-        if (stream && SIG_ORACLE_MUTANT == 7 && s + 1 < n_inc) memset(out + s * S, 0, sizeof(double) * (size_t)S);
+        if (stream) memcpy(out + s * S, cur, sizeof(double) * (size_t)S);
     }
     if (!stream) memcpy(out, cur, sizeof(double) * (size_t)S);
     free(z); free(cur); free(E); free(nxt);
@@ -210,7 +204,7 @@ static void mul_adjoint(const double *A, const double *B, const double *gC, int 
         const int64_t n_k = ipow64(d, k);
         const double *gk = gC + off_k;
         for (int64_t w = 0; w < n_k; ++w) {
-            if (SIG_ORACLE_MUTANT != 9) gB[off_k + w] += gk[w]; /* mutant 9: the A_0 (x) B_k term forgotten */
+            gB[off_k + w] += gk[w];
             gA[off_k + w] += gk[w];
         }
         for (int j = 1; j <= k - 1; ++j) {
@@ -245,7 +239,7 @@ static void exp_adjoint(const double *z, const double *E, double *gE, int d, int
         double *g_prev = gE + level_offset(d, k - 1);
         const double *g_cur = gE + level_offset(d, k);
         const int64_t n_prev = ipow64(d, k - 1);
-        const double div = (double)(SIG_ORACLE_MUTANT == 10 ? 1 : k); /* mutant 10: the 1/k of the recurrence forgotten */
+        const double div = (double)k;
         for (int64_t w = 0; w < n_prev; ++w)
             for (int j = 0; j < d; ++j) {
                 const double g = g_cur[w * d + j];
@@ -292,7 +286,7 @@ static int one_path_backward(const double *x, const double *gout, int64_t L, int
     if (!stream) memcpy(gA, gout, sizeof(double) * (size_t)S);
     for (int64_t s = n_inc - 1; s >= 0; --s) {
         if (stream) { /* entry s of the output is A[s+1] */
-            const double *g = gout + (SIG_ORACLE_MUTANT == 11 && s > 0 ? s - 1 : s) * S; /* mutant 11: stream gradients shifted by one entry */
+            const double *g = gout + s * S;
             for (int64_t w = 0; w < S; ++w) gA[w] += g[w];
         }
         memset(gA_prev, 0, sizeof(double) * (size_t)S);
@@ -305,7 +299,7 @@ static int one_path_backward(const double *x, const double *gout, int64_t L, int
                 if (s > 0) gx[(s - 1) * d + c] -= gz[c];
             } else {
                 gx[(s + 1) * d + c] += gz[c];
-                gx[s * d + c] -= (SIG_ORACLE_MUTANT == 12 ? -gz[c] : gz[c]); /* mutant 12: sign of the lower end point */
+                gx[s * d + c] -= gz[c];
             }
         }
         double *t = gA; gA = gA_prev; gA_prev = t;
@@ -381,8 +375,8 @@ int sig_oracle_log(const double *x, int d, int N, double *out)
     for (int m = 2; m <= N; ++m) {
         mul_no_unit(power, x, d, N, next);           /* x^m = x^{m-1} [x] x */
         double *t = power; power = next; next = t;
-        const double sign = (SIG_ORACLE_MUTANT == 13 || m % 2 == 0) ? -1.0 : 1.0; /* mutant 13: every term after the first subtracted */
-        const double div = (double)(SIG_ORACLE_MUTANT == 14 && m == 3 ? 2 : m);   /* mutant 14: the cube divided by 2 */
+        const double sign = (m % 2 == 0) ? -1.0 : 1.0;
+        const double div = (double)m;
         for (int64_t i = 0; i < S; ++i) out[i] += sign * power[i] / div;
     }
     free(power); free(next);
@@ -401,9 +395,7 @@ static void mul_no_unit_adjoint(const double *A, const double *B, const double *
             for (int64_t u = 0; u < n_j; ++u)
                 for (int64_t v = 0; v < n_m; ++v) {
                     const double g = gk[u * n_m + v];
-                    /* mutant 15: for the first factor the cotangent is read as if the word were split the other way
-                     * round (for both factors at once that would be the mirrored, equally valid, chain rule) */
-                    gA[off_j + u] += (SIG_ORACLE_MUTANT == 15 ? gk[v * n_j + u] : g) * B[off_m + v];
+                    gA[off_j + u] += g * B[off_m + v];
                     gB[off_m + v] += A[off_j + u] * g;
                 }
         }
@@ -429,8 +421,7 @@ int sig_oracle_log_backward(const double *x, const double *g, int d, int N, doub
     /* out = sum_m sign_m x^m / m: the cotangent of x^m is sign_m g / m plus what x^{m+1} = x^m * x sends back */
     for (int m = N; m >= 1; --m) {
         const double sign = (m % 2 == 0) ? -1.0 : 1.0;
-        /* mutant 16: the 1/m of the series left out of the gradient */
-        const double div = (double)(SIG_ORACLE_MUTANT == 16 ? 1 : m);
+        const double div = (double)m;
         for (int64_t i = 0; i < S; ++i) g_pow[i] += sign * g[i] / div;
         if (m == 1) break;
         for (int64_t i = 0; i < S; ++i) g_prev[i] = 0.0;

@@ -22,10 +22,10 @@ _lock = threading.Lock()
 _lib = None
 
 
-def _compile(out_path: str, defines=()) -> None:
+def _compile(out_path: str, src: str = _SRC, extra=()) -> None:
     tmp = out_path + f".tmp{os.getpid()}"
     cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
-           "-Wall", "-Wextra", *[f"-D{d}" for d in defines], "-o", tmp, _SRC]
+           "-Wall", "-Wextra", "-I", _HERE, *extra, "-o", tmp, src]
     subprocess.run(cmd, check=True)
     os.replace(tmp, out_path)
 
@@ -62,13 +62,29 @@ def _declare(lib):
     return lib
 
 
-class use_mutant:
-    """Context manager for the mutation tests: inside it, every function of this module runs a copy
-    of the oracle compiled with one deliberate mistake (`-DSIG_ORACLE_MUTANT=n`) into `workdir`."""
+def compile_copy(out_path: str, extra=()) -> str:
+    """Compiles `sig_oracle.c` as it stands into `out_path` with extra compiler flags (e.g. sanitizers)."""
+    _compile(out_path, _SRC, extra)
+    return out_path
 
-    def __init__(self, number: int, workdir: str):
-        self.path = os.path.join(workdir, f"libsig_oracle_mutant{number}.so")
-        _compile(self.path, [f"SIG_ORACLE_MUTANT={number}"])
+
+def source_text() -> str:
+    """The text of `sig_oracle.c` (for tests that build altered copies of it)."""
+    with open(_SRC) as fh:
+        return fh.read()
+
+
+class use_source:
+    """Context manager for tests of the checker itself: inside it, every function of this module runs a library
+    compiled from `text` (a copy of `sig_oracle.c`, e.g. with a mistake planted by the mutation tests, or the original
+    built with sanitizers through `extra` compiler flags) into `workdir`."""
+
+    def __init__(self, text: str, workdir: str, tag: str = "alt", extra=()):
+        src = os.path.join(workdir, f"sig_oracle_{tag}.c")
+        with open(src, "w") as fh:
+            fh.write(text)
+        self.path = os.path.join(workdir, f"libsig_oracle_{tag}.so")
+        _compile(self.path, src, extra)
 
     def __enter__(self):
         global _lib
@@ -88,7 +104,8 @@ def _load():
     global _lib
     with _lock:
         if _lib is None:
-            lib = _declare(ctypes.CDLL(build()))
+            # SIG_ORACLE_LIB names another build of this same source (the sanitizer leg of the tests sets it)
+            lib = _declare(ctypes.CDLL(os.environ.get("SIG_ORACLE_LIB") or build()))
             _lib = lib
     return _lib
 

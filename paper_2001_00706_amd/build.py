@@ -13,6 +13,8 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB_PATH = os.path.join(PKG_DIR, "libsig.so")
+PEAKS_SRC = os.path.join(PKG_DIR, "peaks", "peak_probe.hip")
+PEAKS_LIB_PATH = os.path.join(PKG_DIR, "libsig_peaks.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",
@@ -64,5 +66,22 @@ def build_lib(verbose: bool = False, jobs: int = 8) -> str:
     return LIB_PATH
 
 
+def build_peaks_lib(verbose: bool = False) -> str:
+    """Compiles the microbenchmarks of the device limits (`peaks/peak_probe.hip`, used by bench.py only) into
+    `libsig_peaks.so`; returns its path."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = PEAKS_LIB_PATH + f".tmp{os.getpid()}"
+    flags = [f for f in HIPCC_FLAGS if f not in ("-mllvm", "-amdgpu-mfma-vgpr-form=1")]
+    cmd = [hipcc, *flags, "-I", INCLUDE, "-shared", PEAKS_SRC, "-o", tmp]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {PEAKS_SRC}:\n{res.stdout}\n{res.stderr}")
+    os.replace(tmp, PEAKS_LIB_PATH)
+    return PEAKS_LIB_PATH
+
+
 if __name__ == "__main__":
     print(build_lib(verbose=True))
+    print(build_peaks_lib(verbose=True))

@@ -236,13 +236,37 @@ def test_deterministic_and_inputs_untouched():
     assert torch.equal(x, x0) and torch.equal(s, s0) and torch.equal(g, g0)
 
 
-@pytest.mark.parametrize("w", [WORKLOADS[0], WORKLOADS[1], WORKLOADS[3]], ids=lambda w: w.name)
-def test_benchmark_workloads_full_size(w):
-    """The forward workloads' shapes, full size; the oracle recomputes a seeded sample of whole paths."""
-    x = workload_paths(w)
-    rng = np.random.default_rng(w.seed)
-    sample = np.unique(np.concatenate([[0, w.B - 1], rng.choice(w.B, size=min(w.B, 6), replace=False)]))
-    check(x, w.N, stream=w.stream, basepoint=w.basepoint, sample=sample)
+@pytest.mark.parametrize("dtype", [np.float32, np.float64], ids=["float32", "float64"])
+@pytest.mark.parametrize("w", WORKLOADS[:4], ids=lambda w: w.name)
+def test_benchmark_workloads_full_size_every_path(w, dtype):
+    """The shapes of the first four forward workloads at full size, as `bench.py --op backward` launches them: the
+    gradient of every path is compared with the oracle's, element by element."""
+    check(workload_paths(w).astype(dtype), w.N, stream=w.stream, basepoint=w.basepoint)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64], ids=["float32", "float64"])
+def test_largest_workload_full_size(dtype):
+    """d = 16, N = 4, 256 paths of 1024 points (1023 increments undone one after the other, appendix C.1).  The
+    oracle's stored-forward gradient of this shape costs about 1.5 core-minutes per path, so it recomputes 16 whole
+    paths spread over the launch; EVERY path is then checked through a property that holds at any size: the
+    derivative of <g, Sig(x + t u)> at t = 0, which is <grad, u>, against central differences of the oracle's
+    (pinned) forward pass in fp64."""
+    w = WORKLOADS[4]
+    x = workload_paths(w).astype(dtype)
+    sample = np.unique(np.concatenate([[0, 1, w.B // 2, w.B - 2, w.B - 1],
+                                       np.random.default_rng(w.seed).choice(w.B, size=11, replace=False)]))
+    got = check(x, w.N, sample=sample).astype(np.float64)
+    rng = np.random.default_rng(31 * w.L + w.d + w.N)          # the output gradient `check` drew
+    g = rng.standard_normal(out_shape(w.B, w.L, w.d, w.N, False, False)).astype(dtype).astype(np.float64)
+    u = brownian_paths(w.B, w.L, w.d, seed=w.seed + 1000).astype(np.float64)
+    h = 1e-3
+    x64 = x.astype(np.float64)
+    hi = np.einsum("bs,bs->b", g, orc.signature(x64 + h * u, w.N))
+    lo = np.einsum("bs,bs->b", g, orc.signature(x64 - h * u, w.N))
+    want = (hi - lo) / (2 * h)
+    have = np.einsum("bld,bld->b", got, u)
+    scale = np.sqrt(np.mean(want ** 2))
+    assert np.max(np.abs(have - want)) <= 2e-3 * scale, (np.max(np.abs(have - want)), scale)
 
 
 def test_long_path_reversibility_error_stays_small():

@@ -36,6 +36,34 @@ def test_library_exports_every_declared_symbol(lib):
         assert getattr(lib, name) is not None
 
 
+def _declared(header, prefix):
+    text = open(header).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(" + prefix + r"[a-z0-9_]+)\s*\(", text)))
+
+
+def test_oracle_library_exports_every_symbol_its_header_declares():
+    # the checker's own boundary (host pointers, fp64); nothing is computed here
+    from oracle import sig_oracle
+    declared = _declared(os.path.join(ROOT, "oracle", "sig_oracle.h"), "sig_oracle_")
+    assert "sig_oracle_forward_f64" in declared and len(declared) == 9
+    olib = ctypes.CDLL(sig_oracle.build())
+    for name in declared:
+        assert getattr(olib, name) is not None
+
+
+def test_peaks_library_exports_every_symbol_its_header_declares():
+    # the device-limit microbenchmarks bench.py times beside the kernels; loading needs no GPU
+    from paper_2001_00706_amd.build import PEAKS_LIB_PATH, build_peaks_lib
+    if not os.path.exists(PEAKS_LIB_PATH):
+        build_peaks_lib()
+    declared = _declared(os.path.join(ROOT, "include", "sig_peaks.h"), "sig_peak_")
+    assert len(declared) == 5
+    plib = ctypes.CDLL(PEAKS_LIB_PATH)
+    for name in declared:
+        assert getattr(plib, name) is not None
+
+
 def test_channels(lib):
     assert sig.sig_signature_channels(2, 4) == 30
     assert sig.sig_signature_channels(4, 6) == 5460

@@ -11,7 +11,7 @@ import pytest
 
 import paper_2001_00706_amd as sig
 from oracle import sig_oracle as orc
-from paper_2001_00706_amd.inputs import brownian_paths
+from paper_2001_00706_amd.inputs import WORKLOADS, brownian_paths, workload_paths
 
 pytestmark = pytest.mark.gpu
 
@@ -98,17 +98,62 @@ def test_workspace_is_checked():
     assert sig.sig_log_backward_workspace_bytes(2, 2, 4, sig.SIG_F64) == 0      # single launch, everything in LDS
 
 
-def test_both_routes_agree_on_the_same_shape():
-    # d = 4, N = 6: 8 signatures go through the single-launch kernel, 300 through the chain of launches
+@pytest.mark.parametrize("dtype", [np.float32, np.float64], ids=["float32", "float64"])
+def test_both_routes_agree_on_the_same_shape(dtype):
+    # d = 4, N = 6 in fp32: 8 signatures go through the single-launch kernel (no workspace), 300 through the chain
+    # of launches (workspace); in fp64 the working set of a signature exceeds the LDS and both take the chain
     d, N = 4, 6
-    x = orc.signature(brownian_paths(300, 6, d, seed=12), N).astype(np.float64)
-    g = np.random.default_rng(4).standard_normal(x.shape)
+    code = sig.SIG_F32 if dtype == np.float32 else sig.SIG_F64
+    assert sig.sig_log_backward_workspace_bytes(300, d, N, code) > 0
+    assert (sig.sig_log_backward_workspace_bytes(8, d, N, code) == 0) == (dtype == np.float32)
+    x = orc.signature(brownian_paths(300, 6, d, seed=12), N).astype(dtype)
+    g = np.random.default_rng(4).standard_normal(x.shape).astype(dtype)
     many = host(sig.sig_log_backward(dev(x), dev(g), d, N))
     few = host(sig.sig_log_backward(dev(x[:8]), dev(g[:8]), d, N))
     want = orc.tensor_log_backward(x[:8], g[:8], d, N)
-    scale = orc.tensor_log_backward(-np.abs(x[:8]), np.abs(g[:8]), d, N)
-    assert_grad_close(few, want, scale, d, N, np.float64)
-    assert_grad_close(many[:8], want, scale, d, N, np.float64)
+    scale = orc.tensor_log_backward(-np.abs(x[:8].astype(np.float64)), np.abs(g[:8].astype(np.float64)), d, N)
+    assert_grad_close(few, want, scale, d, N, dtype)
+    assert_grad_close(many[:8], want, scale, d, N, dtype)
+    want = orc.tensor_log_backward(x, g, d, N)
+    scale = orc.tensor_log_backward(-np.abs(x.astype(np.float64)), np.abs(g.astype(np.float64)), d, N)
+    assert_grad_close(many, want, scale, d, N, dtype)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64], ids=["float32", "float64"])
+@pytest.mark.parametrize("rows", [1024, 256], ids=["1024rows-chain", "256rows-single-launch-in-fp32"])
+def test_benchmark_shape_every_row(rows, dtype):
+    """d = 4, N = 6 at 1024 rows is what `bench.py --op logsignature_backward` times (the chain of launches); at
+    256 rows the fp32 call takes the single-launch kernel.  Every row against the oracle, batch-wide and row by row."""
+    w = WORKLOADS[1]
+    code = sig.SIG_F32 if dtype == np.float32 else sig.SIG_F64
+    need = sig.sig_log_backward_workspace_bytes(rows, w.d, w.N, code)
+    assert (need == 0) == (rows == 256 and dtype == np.float32)
+    x = orc.signature(workload_paths(w)[:rows], w.N).astype(dtype)
+    g = np.random.default_rng(w.seed).standard_normal(x.shape).astype(dtype)
+    got = host(sig.sig_log_backward(dev(x), dev(g), w.d, w.N))
+    want = orc.tensor_log_backward(x, g, w.d, w.N)
+    scale = orc.tensor_log_backward(-np.abs(x.astype(np.float64)), np.abs(g.astype(np.float64)), w.d, w.N)
+    assert_grad_close(got, want, scale, w.d, w.N, dtype)
+    for r in range(0, rows, 29):
+        assert_grad_close(got[r:r + 1], want[r:r + 1], scale[r:r + 1], w.d, w.N, dtype)
+
+
+def test_logsignature_gradient_on_the_benchmark_shape():
+    """The whole gradient of the logsignature (scatter, logarithm, signature) with respect to the path on all 1024
+    paths of d = 4, N = 6, L = 128, in fp32, against the oracle's."""
+    import torch
+    w = WORKLOADS[1]
+    x = workload_paths(w)
+    n_words = len(orc.lyndon_indices(w.d, w.N))
+    g = np.random.default_rng(w.seed + 1).standard_normal((w.B, n_words)).astype(np.float32)
+    p = dev(x).requires_grad_(True)
+    sig.logsignature(p, w.N).backward(dev(g))
+    got = host(p.grad).astype(np.float64)
+    want = orc.logsignature_backward(x, g, w.N)
+    err = np.linalg.norm((got - want).reshape(w.B, -1), axis=1)
+    den = np.linalg.norm(want.reshape(w.B, -1), axis=1)
+    assert np.linalg.norm(err) <= 1e-4 * np.linalg.norm(den), np.linalg.norm(err) / np.linalg.norm(den)
+    assert np.max(err / den) <= 5e-4, np.max(err / den)
 
 
 @pytest.mark.parametrize("stream", [False, True])

@@ -11,7 +11,7 @@ import pytest
 
 import paper_2001_00706_amd as sig
 from oracle import sig_oracle as orc
-from paper_2001_00706_amd.inputs import brownian_paths, uniform_paths
+from paper_2001_00706_amd.inputs import WORKLOADS, brownian_paths, uniform_paths, workload_paths
 
 pytestmark = pytest.mark.gpu
 
@@ -74,6 +74,32 @@ def test_logsignature_words_and_expand(B, L, d, N, dtype):
         assert got.shape[-1] == sig.sig_logsignature_channels(d, N) == len(idx)
         # the gather itself is exact
         np.testing.assert_array_equal(got, got_full[..., idx])
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64], ids=["float32", "float64"])
+def test_benchmark_shape_every_row(dtype):
+    """1024 signatures of d = 4, N = 6 (the shape `bench.py --op logsignature` times): the logarithm of every row and
+    the whole logsignature pipeline on every path, against the oracle."""
+    w = WORKLOADS[1]
+    x = workload_paths(w).astype(dtype)
+    s = orc.signature(x, w.N)
+    want = orc.tensor_log(s.astype(dtype), w.d, w.N)
+    got = host(sig.sig_log(dev(s.astype(dtype)), w.d, w.N))
+    assert_log_close(got, want, s, w.d, w.N, dtype)
+    # row by row as well: a row computed from another row's data would pass a batch-wide norm only by luck
+    for r in range(0, w.B, 37):
+        assert_log_close(got[r:r + 1], want[r:r + 1], s[r:r + 1], w.d, w.N, dtype)
+    idx = orc.lyndon_indices(w.d, w.N)
+    words = host(sig.sig_logsignature(dev(x), w.N))
+    full = orc.tensor_log(s, w.d, w.N)
+    scale = term_scale(s, w.d, w.N)
+    pos = 0
+    for k, sl in enumerate(orc.level_slices(w.d, w.N)):
+        cols = [i for i, off in enumerate(idx) if sl.start <= off < sl.stop]
+        err = np.linalg.norm(words[:, cols] - full[:, [idx[i] for i in cols]])
+        assert err <= TOL[dtype] * scale[k], (k + 1, err, scale[k])
+        pos += len(cols)
+    assert pos == len(idx) == words.shape[1]
 
 
 def test_inverted_logsignature_is_minus_the_logsignature():

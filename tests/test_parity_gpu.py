@@ -3,6 +3,8 @@
 Error measure (per level k): e_k = ||G_k - O_k||_2 / ||O_k||_2 with the norm taken over
 all paths and stream positions of that level.  Bars: fp32 e_k <= 1e-4, fp64 e_k <= 1e-10.
 """
+import functools
+
 import numpy as np
 import pytest
 
@@ -35,11 +37,12 @@ def gpu_signature(x, N, stream=False, basepoint=False, variant=sig.SIG_VARIANT_A
     return got.cpu().numpy()
 
 
-def level_errors(got, want, d, N):
-    """Batch-wide and worst-single-path relative L2 error of every level."""
+def level_errors(got, want, d, N, elementwise=False):
+    """Batch-wide and worst-single-path relative L2 error of every level; with `elementwise` also the worst
+    single element of a path's level, relative to the largest element of that level of that path."""
     got = np.asarray(got, dtype=np.float64)
     B = got.shape[0]
-    batch, single = [], []
+    batch, single, element = [], [], []
     for sl in orc.level_slices(d, N):
         g, w = got[..., sl].reshape(B, -1), want[..., sl].reshape(B, -1)
         den = np.linalg.norm(w)
@@ -47,6 +50,11 @@ def level_errors(got, want, d, N):
         dens = np.linalg.norm(w, axis=1)
         dens[dens == 0] = 1.0
         single.append(float(np.max(np.linalg.norm(g - w, axis=1) / dens)))
+        tops = np.max(np.abs(w), axis=1)
+        tops[tops == 0] = 1.0
+        element.append(float(np.max(np.max(np.abs(g - w), axis=1) / tops)))
+    if elementwise:
+        return np.array(batch), np.array(single), np.array(element)
     return np.array(batch), np.array(single)
 
 
@@ -56,46 +64,60 @@ def served(x, N, stream, basepoint, variant):
     return sig.sig_variant_name(B, L, d, N, stream, basepoint, dtype, variant) != "unsupported"
 
 
-def check(x, N, stream=False, basepoint=False, variant=sig.SIG_VARIANT_AUTO, sample=None):
-    """Runs the HIP path and compares with the oracle; returns None (nothing compared) when the
-    forced kernel family does not serve the shape."""
+def check(x, N, stream=False, basepoint=False, variant=sig.SIG_VARIANT_AUTO, sample=None, want=None):
+    """Runs the HIP path and compares with the oracle (or with `want`, an oracle result computed earlier for the
+    same input); returns None (nothing compared) when the forced kernel family does not serve the shape."""
     if not served(x, N, stream, basepoint, variant):
         return None
     dt = x.dtype.type
     got = gpu_signature(x, N, stream, basepoint, variant)
     assert np.all(np.isfinite(got)), "output not fully written"
     idx = np.arange(x.shape[0]) if sample is None else np.asarray(sample)
-    want = orc.signature(x[idx], N, stream=stream, basepoint=basepoint)
-    batch, single = level_errors(got[idx], want, x.shape[2], N)
+    if want is None:
+        want = orc.signature(x[idx], N, stream=stream, basepoint=basepoint)
+    batch, single, element = level_errors(got[idx], want, x.shape[2], N, elementwise=True)
     assert np.all(batch <= TOL[dt]), f"per-level rel L2 {batch}"
     assert np.all(single <= TOL_SINGLE[dt]), f"worst single-path rel L2 {single}"
+    # element by element: max |G - O| <= c * max |O| over the same level of the same path (and stream position set)
+    assert np.all(element <= TOL[dt]), f"worst element, relative to the level's largest {element}"
     return got
 
 
 VARIANTS = [sig.SIG_VARIANT_AUTO, sig.SIG_VARIANT_GENERIC, sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_SHARD,
             sig.SIG_VARIANT_SMALL, sig.SIG_VARIANT_TREE]
 VARIANT_IDS = ["auto", "generic", "mfma", "mfma_shard", "small", "tree"]
+MODES = [(False, False), (False, True), (True, False), (True, True)]     # (stream, basepoint)
+
+
+def serving_variants(B, L, d, N, dtype, modes):
+    """The kernel families that serve this shape in at least one of `modes`, as pytest parameters; asked of the
+    library itself (`sig_variant_name` is a host function), so that no case is generated only to be skipped."""
+    code = sig.SIG_F32 if dtype == np.float32 else sig.SIG_F64
+    return [pytest.param(v, id=name) for v, name in zip(VARIANTS, VARIANT_IDS)
+            if any(sig.sig_variant_name(B, L, d, N, st, bp, code, v) != "unsupported" for st, bp in modes)]
 
 
 # ------------------------------------------------------------------ benchmark workloads
-@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
-@pytest.mark.parametrize("w", WORKLOADS, ids=lambda w: w.name)
-def test_benchmark_workloads_full_size(w, variant):
-    """Full-size launch, as bench.py times it; the oracle recomputes a seeded sample of
-    whole paths (every element of those paths is compared)."""
-    x = workload_paths(w)
-    rng = np.random.default_rng(w.seed)
-    n_sample = min(w.B, 24 if w.channels * w.L < 2_000_000 else 6)
-    sample = np.sort(rng.choice(w.B, size=n_sample, replace=False))
-    if n_sample < w.B:
-        sample = np.unique(np.concatenate([[0, w.B - 1], sample]))
-    if check(x, w.N, stream=w.stream, basepoint=w.basepoint, variant=variant, sample=sample) is None:
-        pytest.skip("kernel family does not serve this workload")
+@functools.lru_cache(maxsize=2)
+def workload_oracle(index):
+    """The oracle's signatures of every path of a workload (the fp64 input is the exact widening of the fp32 one,
+    so one result serves both precisions)."""
+    w = WORKLOADS[index - 1]
+    return orc.signature(workload_paths(w), w.N, stream=w.stream, basepoint=w.basepoint)
 
 
-@pytest.mark.parametrize("w", [WORKLOADS[0], WORKLOADS[3]], ids=lambda w: w.name)
-def test_small_workloads_every_path(w):
-    check(workload_paths(w), w.N, stream=w.stream, basepoint=w.basepoint)
+WORKLOAD_CASES = [pytest.param(w, dtype, v.values[0], id=f"{w.name}-{np.dtype(dtype).name}-{v.id}")
+                  for w in WORKLOADS for dtype in (np.float32, np.float64)
+                  for v in serving_variants(w.B, w.L, w.d, w.N, dtype, [(w.stream, w.basepoint)])]
+
+
+@pytest.mark.parametrize("w,dtype,variant", WORKLOAD_CASES)
+def test_benchmark_workloads_full_size_every_path(w, dtype, variant):
+    """The five workloads at full size, in the launch configuration bench.py times and under every kernel family
+    that serves them, in fp32 and in fp64 (the fp64 input is the exact widening of the fp32 one): every element of
+    every path, and of every prefix in stream mode, is compared with the oracle."""
+    x = workload_paths(w).astype(dtype)
+    assert check(x, w.N, stream=w.stream, basepoint=w.basepoint, variant=variant, want=workload_oracle(w.index)) is not None
 
 
 # ------------------------------------------------------------------------ shape sweep
@@ -108,17 +130,16 @@ SWEEP = [
 ]
 
 
-@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
-@pytest.mark.parametrize("dtype", [np.float32, np.float64])
-@pytest.mark.parametrize("B,L,d,N", SWEEP)
+SWEEP_CASES = [pytest.param(B, L, d, N, dtype, v.values[0], id=f"{B}-{L}-{d}-{N}-{np.dtype(dtype).name}-{v.id}")
+               for (B, L, d, N) in SWEEP for dtype in (np.float32, np.float64)
+               for v in serving_variants(B, L, d, N, dtype, MODES)]
+
+
+@pytest.mark.parametrize("B,L,d,N,dtype,variant", SWEEP_CASES)
 def test_shape_sweep(B, L, d, N, dtype, variant):
     x = uniform_paths(B, L, d, seed=1000 + 7 * L + d, lo=-0.5, hi=0.5).astype(dtype)
-    ran = []
-    for stream in (False, True):
-        for basepoint in (False, True):
-            ran.append(check(x, N, stream=stream, basepoint=basepoint, variant=variant) is not None)
-    if not any(ran):
-        pytest.skip("kernel family does not serve this shape")
+    ran = [check(x, N, stream=stream, basepoint=basepoint, variant=variant) is not None for stream, basepoint in MODES]
+    assert any(ran)
 
 
 @pytest.mark.parametrize("variant", VARIANTS[:2], ids=VARIANT_IDS[:2])
@@ -140,20 +161,22 @@ D4_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("variant", [sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_SHARD], ids=["mfma", "mfma_shard"])
-@pytest.mark.parametrize("B,L,N", D4_SHAPES)
+def d4_modes(L):
+    return [m for m in MODES if not (m[0] and L > 140)]
+
+
+D4_CASES = [pytest.param(B, L, N, v.values[0], id=f"{B}-{L}-{N}-{v.id}")
+            for (B, L, N) in D4_SHAPES
+            for v in serving_variants(B, L, 4, N, np.float32, d4_modes(L)) if v.id in ("mfma", "mfma_shard")]
+
+
+@pytest.mark.parametrize("B,L,N,variant", D4_CASES)
 def test_d4_matrix_core_kernels(B, L, N, variant):
     x = uniform_paths(B, L, 4, seed=2000 + 3 * L + N, lo=-0.5, hi=0.5)
     if L > 40:
         x = brownian_paths(B, L, 4, seed=2000 + 3 * L + N)
-    ran = []
-    for stream in (False, True):
-        if stream and L > 140:
-            continue
-        for bp in (False, True):
-            ran.append(check(x, N, stream=stream, basepoint=bp, variant=variant) is not None)
-    if not any(ran):
-        pytest.skip("kernel family does not serve this shape")
+    ran = [check(x, N, stream=stream, basepoint=bp, variant=variant) is not None for stream, bp in d4_modes(L)]
+    assert any(ran)
 
 
 def test_d4_depth_seven():
