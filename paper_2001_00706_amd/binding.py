@@ -69,6 +69,9 @@ def load_library() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(
                 f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+        # torch ships its own HIP runtime: it has to be in the process before libsig.so is, so that the library's
+        # calls and the streams and buffers torch hands over belong to one and the same runtime
+        import torch  # noqa: F401
         lib = ctypes.CDLL(LIB_PATH)
         i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
         lib.sig_signature_channels.restype = i64
