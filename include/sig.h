@@ -35,7 +35,8 @@ typedef enum {
     SIG_ERR_INVALID_ARG = 1,  /* null pointer, negative size, d < 1, N < 1, too few points, bad enum */
     SIG_ERR_UNSUPPORTED = 2,  /* valid request that no kernel variant can serve */
     SIG_ERR_OVERFLOW = 3,     /* a size does not fit the library's 64-bit index budget */
-    SIG_ERR_HIP = 4           /* the HIP runtime refused the launch */
+    SIG_ERR_HIP = 4,          /* the HIP runtime refused the launch */
+    SIG_ERR_TOO_LARGE = 5     /* sig_forward_chunked_static only: the request needs more than SIG_STATIC_SCRATCH_BYTES */
 } sig_status;
 
 typedef enum {
@@ -132,6 +133,31 @@ sig_status sig_forward_chunked(const void *path, int64_t B, int64_t L, int d, in
 
 /* Bytes of workspace sig_forward_chunked needs; -1 on invalid arguments. */
 int64_t sig_forward_chunked_workspace_bytes(int64_t B, int64_t L, int d, int N, int basepoint, int chunks, sig_dtype dtype);
+
+/* Size of the scratch array built into the library for sig_forward_chunked_static: 32 MiB of device memory that
+ * every GPU the library runs on holds from the moment the library is loaded until the process ends. */
+#define SIG_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
+
+/* sig_forward_chunked for callers that can neither allocate device memory nor hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical
+ * results; the chunk signatures and the partial products live in the library's own fixed scratch array instead of a
+ * caller's workspace.  The call allocates and frees nothing and calls no allocating routine.
+ *   Limit: sig_forward_chunked_workspace_bytes(...) for the same arguments must not exceed
+ *          SIG_STATIC_SCRATCH_BYTES (= sig_forward_chunked_static_max_bytes()), else SIG_ERR_TOO_LARGE with nothing
+ *          enqueued and `out` untouched.
+ *   Device: the scratch array used is the one of the device that is current at the call, which must be the device
+ *          of `path`, `out` and `hip_stream`.  Its address is looked up once per device, on the first call made with
+ *          that device current (that first call is therefore not a call to make under graph capture).
+ *   Sharing: all calls on one GPU use the same array, which keeps the previous call's contents (every scalar a call
+ *          reads it has written first, so nothing needs clearing).  Calls that overlap in time on one GPU (two
+ *          streams, two threads) race on it: serialise them, or use sig_forward_chunked with separate workspaces.
+ * Other errors as for sig_forward_chunked; SIG_ERR_HIP also if the array's address cannot be obtained. */
+sig_status sig_forward_chunked_static(const void *path, int64_t B, int64_t L, int d, int N, int basepoint,
+                                      const void *basepoint_value, int chunks, sig_dtype dtype, void *out,
+                                      hipStream_t hip_stream);
+
+/* SIG_STATIC_SCRATCH_BYTES as the library was built. */
+int64_t sig_forward_chunked_static_max_bytes(void);
 
 /* Group product of two batches of signatures: out[b] = a[b] [x] b[b], with
  * (A [x] B)_k = sum_{j=0..k} A_j (x) B_{k-j}, A_0 = B_0 = 1 (section 2.2).  By Chen's identity

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     SIG_ERR_HIP,
     SIG_ERR_INVALID_ARG,
     SIG_ERR_OVERFLOW,
+    SIG_ERR_TOO_LARGE,
     SIG_ERR_UNSUPPORTED,
     SIG_VARIANT_AUTO,
     SIG_VARIANT_GENERIC,
@@ -40,6 +41,8 @@ from .binding import (  # noqa: F401
     sig_forward,
     sig_forward_chunked,
     sig_forward_chunked_workspace_bytes,
+    sig_forward_chunked_static,
+    sig_forward_chunked_static_max_bytes,
     sig_forward_raw,
     sig_fused_fmas,
     sig_output_elems,

@@ -14,7 +14,7 @@ import threading
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(PKG_DIR, "libsig.so")
 
-SIG_OK, SIG_ERR_INVALID_ARG, SIG_ERR_UNSUPPORTED, SIG_ERR_OVERFLOW, SIG_ERR_HIP = range(5)
+SIG_OK, SIG_ERR_INVALID_ARG, SIG_ERR_UNSUPPORTED, SIG_ERR_OVERFLOW, SIG_ERR_HIP, SIG_ERR_TOO_LARGE = range(6)
 SIG_F32, SIG_F64 = 0, 1
 SIG_VARIANT_AUTO, SIG_VARIANT_GENERIC, SIG_VARIANT_MFMA, SIG_VARIANT_MFMA_SHARD, SIG_VARIANT_SMALL = 0, 1, 2, 3, 4
 SIG_VARIANT_TREE = 5
@@ -29,6 +29,8 @@ EXPORTED_SYMBOLS = (
     "sig_forward_variant",
     "sig_forward_chunked",
     "sig_forward_chunked_workspace_bytes",
+    "sig_forward_chunked_static",
+    "sig_forward_chunked_static_max_bytes",
     "sig_combine",
     "sig_backward",
     "sig_combine_strided",
@@ -88,6 +90,10 @@ def load_library() -> ctypes.CDLL:
         lib.sig_forward_chunked.argtypes = [vp, i64, i64, i32, i32, i32, vp, i32, i32, vp, vp, i64, vp]
         lib.sig_forward_chunked_workspace_bytes.restype = i64
         lib.sig_forward_chunked_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32, i32]
+        lib.sig_forward_chunked_static.restype = i32
+        lib.sig_forward_chunked_static.argtypes = [vp, i64, i64, i32, i32, i32, vp, i32, i32, vp, vp]
+        lib.sig_forward_chunked_static_max_bytes.restype = i64
+        lib.sig_forward_chunked_static_max_bytes.argtypes = []
         lib.sig_combine.restype = i32
         lib.sig_combine.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
         lib.sig_backward.restype = i32
@@ -590,6 +596,38 @@ def sig_forward_chunked(path, N: int, chunks: int, basepoint=False, out=None, wo
             path.data_ptr(), B, L, d, N, bp_flag, bp_value.data_ptr() if bp_value is not None else 0, chunks, dtype,
             out.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
             torch.cuda.current_stream().cuda_stream))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return out
+
+
+def sig_forward_chunked_static_max_bytes() -> int:
+    return int(load_library().sig_forward_chunked_static_max_bytes())
+
+
+def sig_forward_chunked_static(path, N: int, chunks: int, basepoint=False, out=None):
+    """`sig_forward_chunked` on the library's own fixed scratch array: nothing is allocated by the call itself when
+    `out` is given (without it the result tensor comes from torch).  Raises `SigError` with `SIG_ERR_TOO_LARGE` when
+    the request needs more than `sig_forward_chunked_static_max_bytes()`."""
+    import torch
+
+    _check_gpu("sig_forward_chunked_static", path)
+    if path.dim() != 3 or not path.is_contiguous():
+        raise ValueError("path must be a contiguous tensor of shape [B, L, d]")
+    dtype = _dtype_of(path)
+    B, L, d = path.shape
+    bp_flag, bp_value = _basepoint_args(path, basepoint)
+    S = sig_signature_channels(d, N)
+    if S < 0:
+        raise SigError(SIG_ERR_INVALID_ARG, "bad d or N")
+    if out is None:
+        out = torch.empty((B, S), dtype=path.dtype, device=path.device)
+    elif out.dtype != path.dtype or out.device != path.device or tuple(out.shape) != (B, S) or not out.is_contiguous():
+        raise ValueError(f"out must be a contiguous {path.dtype} tensor of shape {(B, S)} on {path.device}")
+    with torch.cuda.device(path.device):
+        status = int(load_library().sig_forward_chunked_static(
+            path.data_ptr(), B, L, d, N, bp_flag, bp_value.data_ptr() if bp_value is not None else 0, chunks, dtype,
+            out.data_ptr(), torch.cuda.current_stream().cuda_stream))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out

@@ -2,10 +2,34 @@
 // The operations are those declared in sig.h; nothing here dereferences a device pointer.
 #include "sig_internal.h"
 
+#include <atomic>
+
+// Scratch memory of sig_forward_chunked_static, the one entry point for callers that cannot allocate: every GPU the
+// library runs on holds its own copy of this array, at its own address, until the process ends.  In host code the
+// name is only a handle for hipGetSymbolAddress: kernels and copies are given the address that call returns.
+static __device__ __align__(256) unsigned char scratch[SIG_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int64_t kMaxChannels = int64_t(1) << 40;
 constexpr int64_t kMaxElems = int64_t(1) << 60;
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> scratch_address[kMaxDevices];   // per device, filled on the first call made with that device current
+
+// Device address of `scratch` on the current device; nullptr if the runtime refuses.  The look-up is done once per
+// device (threads that race to it obtain the same address, so the race is harmless).
+void *scratch_on_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void *ptr = scratch_address[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return nullptr;
+        scratch_address[dev].store(ptr, std::memory_order_release);
+    }
+    return ptr;
+}
 
 // Fills pw/off/S; false if d, N are invalid or S exceeds kMaxChannels.
 bool fill_levels(int d, int N, sig::Shape &sh)
@@ -307,9 +331,10 @@ int64_t sig_forward_chunked_workspace_bytes(int64_t B, int64_t L, int d, int N, 
     return (sh.B + sh.B / 2) * sh.S * int64_t(dtype == SIG_F32 ? sizeof(float) : sizeof(double));
 }
 
-sig_status sig_forward_chunked(const void *path, int64_t B, int64_t L, int d, int N, int basepoint,
-                               const void *basepoint_value, int chunks, sig_dtype dtype, void *out,
-                               void *workspace, int64_t workspace_bytes, hipStream_t hip_stream)
+// The chunked scan itself; `use_static_scratch` selects the library's own scratch array instead of `workspace`.
+static sig_status forward_chunked(const void *path, int64_t B, int64_t L, int d, int N, int basepoint,
+                                  const void *basepoint_value, int chunks, sig_dtype dtype, void *out,
+                                  void *workspace, int64_t workspace_bytes, bool use_static_scratch, hipStream_t hip_stream)
 {
     if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
     sig::Shape sh;
@@ -317,8 +342,15 @@ sig_status sig_forward_chunked(const void *path, int64_t B, int64_t L, int d, in
     if (st != SIG_OK) return st;
     if (!sh.basepoint && basepoint_value != nullptr) return SIG_ERR_INVALID_ARG;
     if (B == 0) return SIG_OK;
-    if (path == nullptr || out == nullptr || workspace == nullptr) return SIG_ERR_INVALID_ARG;
     const int64_t elem = dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double));
+    if (use_static_scratch) {
+        if (path == nullptr || out == nullptr) return SIG_ERR_INVALID_ARG;
+        if ((sh.B + sh.B / 2) * sh.S * elem > int64_t(SIG_STATIC_SCRATCH_BYTES)) return SIG_ERR_TOO_LARGE;
+        workspace = scratch_on_current_device();
+        if (workspace == nullptr) return SIG_ERR_HIP;
+        workspace_bytes = int64_t(SIG_STATIC_SCRATCH_BYTES);
+    }
+    if (path == nullptr || out == nullptr || workspace == nullptr) return SIG_ERR_INVALID_ARG;
     if (workspace_bytes < (sh.B + sh.B / 2) * sh.S * elem || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)
         return SIG_ERR_INVALID_ARG;
     if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
@@ -350,6 +382,23 @@ sig_status sig_forward_chunked(const void *path, int64_t B, int64_t L, int d, in
     }
     return SIG_OK;
 }
+
+sig_status sig_forward_chunked(const void *path, int64_t B, int64_t L, int d, int N, int basepoint,
+                               const void *basepoint_value, int chunks, sig_dtype dtype, void *out,
+                               void *workspace, int64_t workspace_bytes, hipStream_t hip_stream)
+{
+    return forward_chunked(path, B, L, d, N, basepoint, basepoint_value, chunks, dtype, out, workspace, workspace_bytes,
+                           false, hip_stream);
+}
+
+sig_status sig_forward_chunked_static(const void *path, int64_t B, int64_t L, int d, int N, int basepoint,
+                                      const void *basepoint_value, int chunks, sig_dtype dtype, void *out,
+                                      hipStream_t hip_stream)
+{
+    return forward_chunked(path, B, L, d, N, basepoint, basepoint_value, chunks, dtype, out, nullptr, 0, true, hip_stream);
+}
+
+int64_t sig_forward_chunked_static_max_bytes(void) { return int64_t(SIG_STATIC_SCRATCH_BYTES); }
 
 int64_t sig_combine_many_workspace_bytes(int64_t B, int64_t n, int d, int N, sig_dtype dtype)
 {
@@ -617,6 +666,7 @@ const char *sig_status_string(sig_status status)
         case SIG_ERR_UNSUPPORTED: return "no kernel variant supports this request";
         case SIG_ERR_OVERFLOW: return "size overflow";
         case SIG_ERR_HIP: return "HIP launch failed";
+        case SIG_ERR_TOO_LARGE: return "the request needs more scratch memory than the library's fixed buffer holds";
     }
     return "unknown status";
 }

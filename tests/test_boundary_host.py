@@ -109,8 +109,8 @@ def test_fused_fma_count_of_the_benchmark_shapes(lib):
 
 
 def test_status_strings(lib):
-    texts = [sig.sig_status_string(s) for s in range(5)]
-    assert texts[0] == "ok" and len(set(texts)) == 5
+    texts = [sig.sig_status_string(s) for s in range(6)]
+    assert texts[0] == "ok" and len(set(texts)) == 6 and "scratch" in texts[sig.SIG_ERR_TOO_LARGE]
     assert sig.sig_status_string(99) == "unknown status"
 
 
