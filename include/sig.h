@@ -56,9 +56,12 @@ typedef enum {
     SIG_VARIANT_MFMA_SHARD = 3,/* fp32, d = 4, N = 4..7, final and stream mode: four independent wavefronts
                                  per path, one per first letter */
     SIG_VARIANT_SMALL = 4,    /* any dtype and mode, S <= 512, N <= 8, d <= 64: one wavefront per path, state in LDS */
-    SIG_VARIANT_TREE = 5      /* any dtype and mode; d = 2..8 at N = 2..9: a thread per word of N-2 letters; d = 9..16 at
+    SIG_VARIANT_TREE = 5,     /* any dtype and mode; d = 2..8 at N = 2..9: a thread per word of N-2 letters; d = 9..16 at
                                  N = 2..6: a thread per word of N-1 letters; state in registers, any number of
                                  workgroups per path (large signatures, few paths) */
+    SIG_VARIANT_MFMA_STREAM = 6 /* fp32, d = 4, N = 4..6, stream mode only: the four first-letter wavefronts of a path in
+                                 one workgroup; prefix signatures are assembled in LDS and written out in whole runs
+                                 cut at 128-byte boundaries (what sig_forward picks for outputs beyond ~300 MB) */
 } sig_variant;
 
 /* Largest depth the kernels accept. */

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     SIG_VARIANT_GENERIC,
     SIG_VARIANT_MFMA,
     SIG_VARIANT_MFMA_SHARD,
+    SIG_VARIANT_MFMA_STREAM,
     SIG_VARIANT_SMALL,
     SIG_VARIANT_TREE,
     SigError,

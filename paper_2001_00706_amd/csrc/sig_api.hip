@@ -95,7 +95,7 @@ sig_status make_rows_shape(int64_t rows, int d, int N, sig::Shape &sh)
     return SIG_OK;
 }
 
-enum class Family { Generic, Mfma, MfmaShard, MfmaD16, MfmaD8, Small, Tree, None };
+enum class Family { Generic, Mfma, MfmaShard, MfmaStream, MfmaD16, MfmaD8, Small, Tree, None };
 
 // The pointers decide only alignment: the matrix-core family loads and stores 16 bytes per lane.
 Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const void *path, const void *out)
@@ -104,6 +104,7 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
                          reinterpret_cast<uintptr_t>(sh.basepoint_value) % 16 == 0;
     const bool mfma_ok = dtype == SIG_F32 && aligned && sig::mfma_kernel_name(sh) != nullptr;
     const bool shard_ok = dtype == SIG_F32 && aligned && sig::mfma_shard_kernel_name(sh) != nullptr;
+    const bool stream_ok = dtype == SIG_F32 && aligned && sig::mfma_stream_kernel_name(sh) != nullptr;
     const bool d16_ok = dtype == SIG_F32 && aligned && sig::mfma_d16_kernel_name(sh) != nullptr;
     const bool d8_ok = dtype == SIG_F32 && aligned && sig::mfma_d8_kernel_name(sh) != nullptr;
     const bool generic_ok = sig::generic_supported(sh, dtype);
@@ -113,9 +114,7 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
         case SIG_VARIANT_AUTO:
             // four wavefronts per path when one per path would leave most of the chip idle, when every
             // prefix is stored (stream mode) or when the state does not fit one wavefront (N = 7)
-            // (measured at L = 128: from 1024 paths on, stream mode at N >= 5 is a pure HBM write stream, which the
-            // prefix-tree kernel sustains at 4.0 TB/s against 3.5)
-            if (shard_ok && sh.stream && sh.N >= 5 && sh.B >= 1024 && tree_ok) return Family::Tree;
+            if (stream_ok && sig::mfma_stream_preferred(sh)) return Family::MfmaStream;
             if (shard_ok && (!mfma_ok || sh.B < 512)) return Family::MfmaShard;
             if (mfma_ok) return Family::Mfma;
             // one workgroup per path leaves the chip idle below ~48 paths (B = 8: 45 us against 25 for the prefix-tree
@@ -133,6 +132,7 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
         case SIG_VARIANT_MFMA:
             return mfma_ok ? Family::Mfma : d16_ok ? Family::MfmaD16 : d8_ok ? Family::MfmaD8 : Family::None;
         case SIG_VARIANT_MFMA_SHARD: return shard_ok ? Family::MfmaShard : Family::None;
+        case SIG_VARIANT_MFMA_STREAM: return stream_ok ? Family::MfmaStream : Family::None;
         case SIG_VARIANT_SMALL: return small_ok ? Family::Small : Family::None;
         case SIG_VARIANT_TREE: return tree_ok ? Family::Tree : Family::None;
     }
@@ -148,6 +148,8 @@ hipError_t launch_family(Family family, const sig::Shape &sh, sig_dtype dtype, c
             return sig::launch_mfma_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
         case Family::MfmaShard:
             return sig::launch_mfma_shard_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
+        case Family::MfmaStream:
+            return sig::launch_mfma_stream_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
         case Family::MfmaD16:
             return sig::launch_mfma_d16_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
         case Family::MfmaD8:
@@ -173,7 +175,8 @@ bool valid_enums(sig_dtype dtype, sig_variant variant)
 {
     return (dtype == SIG_F32 || dtype == SIG_F64) &&
            (variant == SIG_VARIANT_AUTO || variant == SIG_VARIANT_GENERIC || variant == SIG_VARIANT_MFMA ||
-            variant == SIG_VARIANT_MFMA_SHARD || variant == SIG_VARIANT_SMALL || variant == SIG_VARIANT_TREE);
+            variant == SIG_VARIANT_MFMA_SHARD || variant == SIG_VARIANT_SMALL || variant == SIG_VARIANT_TREE ||
+            variant == SIG_VARIANT_MFMA_STREAM);
 }
 
 }  // namespace
@@ -648,6 +651,7 @@ const char *sig_variant_name(int64_t B, int64_t L, int d, int N, int stream, int
     switch (resolve(sh, dtype, variant, nullptr, nullptr)) {
         case Family::Mfma: return sig::mfma_kernel_name(sh);
         case Family::MfmaShard: return sig::mfma_shard_kernel_name(sh);
+        case Family::MfmaStream: return sig::mfma_stream_kernel_name(sh);
         case Family::MfmaD16: return sig::mfma_d16_kernel_name(sh);
         case Family::MfmaD8: return sig::mfma_d8_kernel_name(sh);
         case Family::Small: return "small";

@@ -146,6 +146,13 @@ hipError_t launch_mfma_f32(const Shape &sh, const float *path, float *out, hipSt
 const char *mfma_shard_kernel_name(const Shape &sh);
 hipError_t launch_mfma_shard_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 
+// Stream mode of that family for N = 4..6 with the four wavefronts of a path in one workgroup: prefix signatures are
+// assembled in LDS and written in whole runs.  `mfma_stream_preferred`: the output is too large for the last-level
+// cache, which is when this store pattern pays.
+const char *mfma_stream_kernel_name(const Shape &sh);
+bool mfma_stream_preferred(const Shape &sh);
+hipError_t launch_mfma_stream_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
+
 // Matrix-core kernel for d = 16, N = 4, final mode: one workgroup of 8 wavefronts per path.
 const char *mfma_d16_kernel_name(const Shape &sh);
 hipError_t launch_mfma_d16_f32(const Shape &sh, const float *path, float *out, hipStream_t st);

@@ -268,6 +268,136 @@ sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out
     if constexpr (!STREAM) store_shard<N>(S, make_rsrc(o, kS * 4u), 0, plan, lane);
 }
 
+
+// ---- stream mode for N <= 6: one workgroup of four wavefronts (the four first-letter shards) per path ----
+//
+// A stream-mode launch is a pure HBM write stream, and what the memory system rewards is long runs of whole
+// 128-byte lines written by one wavefront.  The shards' own slices of a prefix signature are short and end inside
+// lines, so here they are first assembled in LDS, in output order, kRowsPerFlush prefix signatures at a time (two
+// such buffers take turns), and after a barrier the four wavefronts copy the assembled run to `out`: each takes a
+// contiguous quarter of it, cut at 128-byte boundaries of the output address, 16 bytes per lane.
+template <int N>
+constexpr int kRowsPerFlush = N == 4 ? 16 : N == 5 ? 4 : 1;   // about 21.8 KB per buffer at every depth
+
+template <int N>
+__device__ __forceinline__ void lds_store_shard(const ShardState<N> &S, char *row, const StorePlan &p, int lane)
+{
+    const unsigned low = (__builtin_bit_cast(unsigned, S.A1) & p.m1) | (__builtin_bit_cast(unsigned, S.A2) & p.m2) |
+                         (__builtin_bit_cast(unsigned, S.A3) & p.m3);
+    *reinterpret_cast<unsigned *>(row + p.low_off) = low;
+    *reinterpret_cast<float *>(row + p.off4) = S.A4;
+    if constexpr (N >= 5) *reinterpret_cast<f4 *>(row + p.off5) = N == 5 ? S.A5[0] : quad_transpose(S.A5[0], lane);
+    if constexpr (N >= 6) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) *reinterpret_cast<f4 *>(row + p.off6 + 64 * g) = S.A6[g];
+    }
+}
+
+template <int N>
+__global__ void __launch_bounds__(256)
+sig_mfma_d4_stream_kernel(const float *__restrict__ path, float *__restrict__ out, int64_t L, int64_t n_inc, int basepoint,
+                          const float *__restrict__ bpv)
+{
+    static_assert(N >= 4 && N <= 6, "depths served by this kernel");
+    constexpr int kRow = 4 * (N - 1);   // floats per staged increment
+    constexpr int kTile = 128;          // increments staged at a time
+    constexpr int kS = kLevelOff[N + 1];
+    constexpr int kFlush = kRowsPerFlush<N>;
+    __shared__ __align__(16) float tab[kTile * kRow];
+    __shared__ __align__(16) float rows[2][kFlush * kS];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int f = __builtin_amdgcn_readfirstlane(tid >> 6);       // wavefront number = first letter (a scalar)
+    const int w2 = lane >> 4, w3 = (lane >> 2) & 3, q = lane & 3;
+    const int64_t b = blockIdx.x;
+    const f4 *x4 = reinterpret_cast<const f4 *>(path) + b * L;
+    char *o = reinterpret_cast<char *>(out + b * n_inc * kS);
+    const StorePlan plan = make_store_plan<N>(f, lane);
+
+    ShardState<N> S;
+    S.A5[0] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int g = 0; g < (N >= 6 ? 4 : 1); ++g) S.A6[g] = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+
+    f4 p_hi, p_lo;
+    auto fetch_points = [&](int64_t s) {
+        p_hi = p_lo = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+        if (s < n_inc) {
+            const int64_t i_hi = basepoint ? s : s + 1;
+            p_hi = x4[i_hi];
+            if (i_hi > 0) p_lo = x4[i_hi - 1];
+            else if (bpv != nullptr) p_lo = reinterpret_cast<const f4 *>(bpv)[b];
+        }
+    };
+    if (tid < kTile) fetch_points(tid);
+
+    int fill = 0, cur = 0;     // prefix signatures assembled in rows[cur] so far
+    int64_t flushed = 0;       // prefix signatures already copied to `out`
+    // every wavefront of the workgroup takes the same trips through these loops, so the barriers below are met by all
+    constexpr int kRunBytes = kFlush * kS * 4;                         // a full buffer
+    constexpr int kPieces = (kRunBytes / 4 + 127 + 1023) / 1024;       // 1 KB pieces in a wavefront's share of it
+    auto flush = [&]() {
+        // a barrier that orders the LDS traffic only: __syncthreads() would also wait for the global stores of the
+        // previous run to complete, and the scan would then advance at the latency of HBM writes
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+        char *run = o + flushed * (kS * 4);
+        const int bytes = fill * (kS * 4), quarter = bytes / 4;
+        const int mis = int(reinterpret_cast<uintptr_t>(run) & 127);
+        // this wavefront's share [lo, hi) of the run, in bytes from its start, cut where the ADDRESS is a multiple of 128
+        int lo = f == 0 ? 0 : ((mis + quarter * f) & ~127) - mis;
+        int hi = f == 3 ? bytes : ((mis + quarter * (f + 1)) & ~127) - mis;
+        lo = lo < 0 ? 0 : lo;
+        hi = hi < 0 ? 0 : hi;
+        const char *src = reinterpret_cast<const char *>(rows[cur]);
+        f4 piece[kPieces];
+#pragma unroll
+        for (int j = 0; j < kPieces; ++j) {
+            const int at = lo + lane * 16 + j * 1024;
+            if (at < hi) piece[j] = *reinterpret_cast<const f4 *>(src + at);
+        }
+#pragma unroll
+        for (int j = 0; j < kPieces; ++j) {
+            const int at = lo + lane * 16 + j * 1024;
+            if (at < hi) *reinterpret_cast<f4 *>(run + at) = piece[j];
+        }
+        flushed += fill;
+        fill = 0;
+        cur ^= 1;
+    };
+
+    for (int64_t t0 = 0; t0 < n_inc; t0 += kTile) {
+        const int nt = int(n_inc - t0 < kTile ? n_inc - t0 : kTile);
+        __syncthreads();
+        if (tid < nt) {
+            const f4 z = p_hi - p_lo;
+            f4 *row = reinterpret_cast<f4 *>(tab + tid * kRow);
+            row[0] = z;
+#pragma unroll
+            for (int m = 2; m <= N - 1; ++m) row[m - 1] = z * (1.0f / m);
+        }
+        __syncthreads();
+        if (tid < kTile) fetch_points(t0 + kTile + tid);
+        for (int s = 0; s < nt; s += 4) {
+            const int m = nt - s < 4 ? nt - s : 4;
+            ShardRow<N> R[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (i < m) R[i] = load_shard_row<N>(tab + (s + i) * kRow, f, w2, w3, q);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (i < m) {
+                    shard_step<N>(S, R[i]);
+                    lds_store_shard<N>(S, reinterpret_cast<char *>(rows[cur]) + fill * (kS * 4), plan, lane);
+                    if (++fill == kFlush) flush();
+                }
+            }
+        }
+    }
+    if (fill > 0) flush();
+}
+
 template <int N>
 hipError_t launch_shard(const Shape &sh, const float *path, float *out, hipStream_t st)
 {
@@ -288,6 +418,36 @@ const char *mfma_shard_kernel_name(const Shape &sh)
 {
     if (sh.d != 4 || sh.N < 4 || sh.N > 7 || sh.B > 0x1fffffff) return nullptr;
     return "mfma_d4_shard";
+}
+
+const char *mfma_stream_kernel_name(const Shape &sh)
+{
+    if (sh.d != 4 || sh.N < 4 || sh.N > 6 || !sh.stream || sh.chunks > 1 || sh.B > 0x7fffffff) return nullptr;
+    return "mfma_d4_stream";
+}
+
+bool mfma_stream_preferred(const Shape &sh)
+{
+    // An output that fits the 256 MB last-level cache is absorbed there at more than 6 TB/s whatever the store
+    // pattern, and four independent wavefronts per path get there fastest (B = 192, L = 256, N = 5: 6.4 TB/s).
+    // Beyond it the writes go to HBM at the pace of the store pattern: pieces that end inside 128-byte lines
+    // reach 3.7 TB/s at B = 1024, whole runs assembled in LDS 5.1 to 5.3 TB/s.
+    constexpr int64_t kCacheBytes = 300 * 1000 * 1000;
+    return mfma_stream_kernel_name(sh) != nullptr && sh.B * sh.n_inc * sh.S * 4 > kCacheBytes;
+}
+
+hipError_t launch_mfma_stream_f32(const Shape &sh, const float *path, float *out, hipStream_t st)
+{
+    if (mfma_stream_kernel_name(sh) == nullptr) return hipErrorNotSupported;
+    const dim3 grid(static_cast<unsigned>(sh.B)), block(256);
+    const float *bpv = static_cast<const float *>(sh.basepoint_value);
+    switch (sh.N) {
+        case 4: hipLaunchKernelGGL(sig_mfma_d4_stream_kernel<4>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint, bpv); break;
+        case 5: hipLaunchKernelGGL(sig_mfma_d4_stream_kernel<5>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint, bpv); break;
+        case 6: hipLaunchKernelGGL(sig_mfma_d4_stream_kernel<6>, grid, block, 0, st, path, out, sh.L, sh.n_inc, sh.basepoint, bpv); break;
+        default: return hipErrorNotSupported;
+    }
+    return hipGetLastError();
 }
 
 hipError_t launch_mfma_shard_f32(const Shape &sh, const float *path, float *out, hipStream_t st)

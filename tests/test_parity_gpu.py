@@ -84,8 +84,8 @@ def check(x, N, stream=False, basepoint=False, variant=sig.SIG_VARIANT_AUTO, sam
 
 
 VARIANTS = [sig.SIG_VARIANT_AUTO, sig.SIG_VARIANT_GENERIC, sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_SHARD,
-            sig.SIG_VARIANT_SMALL, sig.SIG_VARIANT_TREE]
-VARIANT_IDS = ["auto", "generic", "mfma", "mfma_shard", "small", "tree"]
+            sig.SIG_VARIANT_SMALL, sig.SIG_VARIANT_TREE, sig.SIG_VARIANT_MFMA_STREAM]
+VARIANT_IDS = ["auto", "generic", "mfma", "mfma_shard", "small", "tree", "mfma_stream"]
 MODES = [(False, False), (False, True), (True, False), (True, True)]     # (stream, basepoint)
 
 
@@ -167,7 +167,7 @@ def d4_modes(L):
 
 D4_CASES = [pytest.param(B, L, N, v.values[0], id=f"{B}-{L}-{N}-{v.id}")
             for (B, L, N) in D4_SHAPES
-            for v in serving_variants(B, L, 4, N, np.float32, d4_modes(L)) if v.id in ("mfma", "mfma_shard")]
+            for v in serving_variants(B, L, 4, N, np.float32, d4_modes(L)) if v.id in ("mfma", "mfma_shard", "mfma_stream")]
 
 
 @pytest.mark.parametrize("B,L,N,variant", D4_CASES)
@@ -177,6 +177,31 @@ def test_d4_matrix_core_kernels(B, L, N, variant):
         x = brownian_paths(B, L, 4, seed=2000 + 3 * L + N)
     ran = [check(x, N, stream=stream, basepoint=bp, variant=variant) is not None for stream, bp in d4_modes(L)]
     assert any(ran)
+
+
+def test_large_stream_outputs_take_the_run_assembling_kernel():
+    """Beyond the last-level cache (about 300 MB of output) sig_forward hands stream mode at d = 4 to the kernel
+    that assembles whole runs in LDS; the shape below (B = 1024 of the stream workload's 128) is compared with the
+    oracle on every prefix of a sample of paths and checked for complete, finite coverage on the rest."""
+    torch = torch_mod()
+    w = WORKLOADS[3]
+    B = 1024
+    assert sig.sig_variant_name(B, w.L, w.d, w.N, True, False) == "mfma_d4_stream"
+    assert sig.sig_variant_name(w.B, w.L, w.d, w.N, True, False) == "mfma_d4_shard"
+    x = brownian_paths(B, w.L, w.d, seed=w.seed + 50)
+    out = torch.full((B, w.L - 1, w.channels), float("nan"), device="cuda:0")
+    sig.sig_forward(torch.from_numpy(x).to("cuda:0"), w.N, stream=True, out=out)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    forced = sig.sig_forward(torch.from_numpy(x).to("cuda:0"), w.N, stream=True, variant=sig.SIG_VARIANT_MFMA_SHARD)
+    torch.cuda.synchronize()
+    # every element of every path against the independent four-wavefront kernel (same arithmetic per word: same bits)
+    assert torch.equal(out, forced)
+    del forced
+    idx = np.unique(np.concatenate([[0, 1, B - 1], np.random.default_rng(5).choice(B, size=29, replace=False)]))
+    want = orc.signature(x[idx], w.N, stream=True)
+    batch, single, element = level_errors(out[torch.from_numpy(idx).to("cuda:0")].cpu().numpy(), want, w.d, w.N, elementwise=True)
+    assert np.all(batch <= 1e-4) and np.all(single <= 5e-4) and np.all(element <= 1e-4), (batch, single, element)
 
 
 def test_d4_depth_seven():
@@ -315,6 +340,10 @@ def test_long_paths_cross_many_tiles():
     # every family with a staged tile: several tiles, ragged last tile
     check(brownian_paths(2, 1000, 4, seed=31), 6)                                  # mfma_d4, 64-increment tiles
     check(brownian_paths(1, 333, 4, seed=32), 5, stream=True)                      # mfma_d4_shard
+    for N, L in [(4, 301), (5, 333), (6, 140)]:                                     # mfma_d4_stream: 128-increment tiles,
+        x = brownian_paths(3, L, 4, seed=40 + N)                                    # runs of 16 / 4 / 1 prefix signatures
+        assert check(x, N, stream=True, variant=sig.SIG_VARIANT_MFMA_STREAM) is not None
+        assert check(x, N, stream=True, basepoint=True, variant=sig.SIG_VARIANT_MFMA_STREAM) is not None
     check(brownian_paths(1, 333, 4, seed=32), 7, basepoint=True)                   # mfma_d4_shard, depth 7
     check(brownian_paths(1, 450, 8, seed=33), 5)                                   # mfma_d8_shard
     check(brownian_paths(1, 700, 16, seed=34), 4)                                  # mfma_d16, 128-increment tiles
