@@ -104,6 +104,13 @@ bool backward_d4_supported(const Shape &sh);
 hipError_t launch_backward_d4_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
                                   float *gbase, hipStream_t st);
 
+// Gradient kernel for d = 16, N = 4, final mode, fp32, 16-byte aligned buffers: one workgroup of 512 threads per path
+// with the top level's cotangent in registers; workspace: one gradient per increment, [B][n_inc][16] floats.
+bool backward_d16_supported(const Shape &sh);
+int64_t backward_d16_workspace_bytes(const Shape &sh);
+hipError_t launch_backward_d16_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
+                                   float *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st);
+
 // The same scheme for d = 2 (N = 2..9) and d = 8 (N = 2..5); buffers aligned to min(d, 4) floats.
 bool backward_pow2_supported(const Shape &sh);
 hipError_t launch_backward_pow2_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
