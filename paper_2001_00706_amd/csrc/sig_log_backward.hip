@@ -436,6 +436,277 @@ log_bwd_fused_kernel(Shape sh, int64_t r_stride, const T *__restrict__ x_g, cons
     }
 }
 
+// The single-launch kernel for d = 2, 4, 8 written as gathers: no products parked in LDS, two barriers per step.
+// Both sums of a step are dot products along the flat order of a truncated element:
+//     G_{m+1}[v] = sum_t x[t] G_m[u_t v]          t runs over the flat positions of the words u_t of 1..n-|v| letters
+//     gx[u]     += sum_t G_m[u v_t] R_{m+1}[t]    t runs over the flat positions of the words v_t of 1..n-|u| letters
+// and the word u v of k letters sits at off_k + (u << |v| log2 d) + v.  An output of level lambda has S(n - lambda)
+// terms and there are d^lambda of them, so every level holds about the same number of terms: the whole workgroup
+// takes the levels one after the other, NT / d^lambda threads per output, each with every (NT / d^lambda)-th word of
+// every length.  In the first sum consecutive threads hold consecutive v, in the second consecutive threads hold
+// consecutive t, so that both read consecutive addresses.  The threads of an output meet by lane exchanges inside a
+// wavefront and, where an output spans several wavefronts, through partial sums in LDS that are added, in a fixed
+// order, after the step's first barrier.  d, N and the workgroup size are compile-time constants: every loop below
+// unrolls and every offset folds (with run-time bounds the loop control was five sixths of the instructions).
+// LDS: x[S] | R_N .. R_2 [r_stride] | G[2][S(N-1)] | gx[S] | partial sums.
+template <int LOGD>
+__host__ __device__ constexpr uint32_t gather_off(int k)   // offset of level k (1-based) in a flat element
+{
+    uint32_t o = 0;
+    for (int j = 1; j < k; ++j) o += 1u << uint32_t(LOGD * j);
+    return o;
+}
+
+template <int LOGD>
+__host__ __device__ constexpr uint32_t gather_partials(int n, uint32_t nt)   // partial sums of the first kind in one step
+{
+    uint32_t total = 0;
+    for (int lam = 1; lam <= n - 1; ++lam) {
+        const uint32_t shl = uint32_t(LOGD * lam);
+        if (shl >= 31 || (1u << shl) >= nt) break;
+        total += (1u << shl) < 64 ? (nt >> 6) << shl : nt;
+    }
+    return total;
+}
+constexpr uint32_t kGatherPartB = 64;   // partial sums of the second kind (outputs that span several wavefronts)
+
+template <typename T, int LOGD, int NT, int n, bool FIRST, typename GPtr>
+__device__ __forceinline__ void gather_step(T c, GPtr G, T *__restrict__ Gn, const T *__restrict__ R, const T *__restrict__ xs,
+                                            T *__restrict__ gxs, T *__restrict__ part, T *__restrict__ part_b, uint32_t tid)
+{
+    constexpr uint32_t lg_nt = NT == 1024 ? 10 : NT == 512 ? 9 : 8, waves = NT / 64;
+    static_assert(NT == 1024 || NT == 512 || NT == 256, "workgroup sizes of this kernel");
+    const uint32_t lane = tid & 63, wave = tid >> 6;
+    // the top level of G_m reaches the gradient only through its coefficient
+    for (uint32_t q = gather_off<LOGD>(n) + tid; q < gather_off<LOGD>(n + 1); q += NT) gxs[q] = (FIRST ? T(0) : gxs[q]) + c * G[q];
+
+    // ---- every level's dot products first (all their loads are independent of one another) ...
+    T acc_a[n], acc_b[n];
+#pragma unroll
+    for (int lam = 1; lam <= n - 1; ++lam) {
+        const uint32_t shl = uint32_t(LOGD * lam);
+        const int jmax = n - lam;
+        acc_a[lam] = acc_b[lam] = T(0);
+        if (shl >= lg_nt) {
+            // at least as many outputs as threads: a thread takes whole outputs (they have few terms)
+            const uint32_t outputs = 1u << shl;
+            for (uint32_t v = tid; v < outputs; v += NT) {
+                T acc = T(0), accb = T(0);
+#pragma unroll
+                for (int j = 1; j <= jmax; ++j) {
+                    const uint32_t cnt = 1u << uint32_t(LOGD * j), lo = gather_off<LOGD>(j);
+                    const uint32_t base_a = gather_off<LOGD>(j + lam) + v;
+                    const uint32_t base_b = gather_off<LOGD>(lam + j) + (v << uint32_t(LOGD * j));
+#pragma unroll 8
+                    for (uint32_t p = 0; p < cnt; ++p) {
+                        acc += xs[lo + p] * G[base_a + (p << shl)];
+                        accb += G[base_b + p] * R[lo + p];
+                    }
+                }
+                const uint32_t q = gather_off<LOGD>(lam) + v;
+                Gn[q] = acc;
+                gxs[q] = (FIRST ? T(0) : gxs[q]) + c * G[q] + accb;
+            }
+            continue;
+        }
+        const uint32_t outputs = 1u << shl, lg_tl = lg_nt - shl, tl_count = 1u << lg_tl;   // threads per output
+        {   // level lambda of G_{m+1}: thread = (tl, v), v fastest
+            const uint32_t v = tid & (outputs - 1), tl = tid >> shl;
+#pragma unroll
+            for (int j = 1; j <= jmax; ++j) {
+                const uint32_t cnt = 1u << uint32_t(LOGD * j), lo = gather_off<LOGD>(j), base = gather_off<LOGD>(j + lam) + v;
+                if (cnt >= tl_count) {
+#pragma unroll
+                    for (uint32_t k = 0; k < cnt / tl_count; ++k) {
+                        const uint32_t p = tl + k * tl_count;
+                        acc_a[lam] += xs[lo + p] * G[base + (p << shl)];
+                    }
+                } else if (tl < cnt) {
+                    acc_a[lam] += xs[lo + tl] * G[base + (tl << shl)];
+                }
+            }
+        }
+        {   // gx at the words u of lambda letters: thread = (u, tl), tl fastest
+            const uint32_t tl = tid & (tl_count - 1), u = tid >> lg_tl;
+#pragma unroll
+            for (int l = 1; l <= jmax; ++l) {
+                const uint32_t cnt = 1u << uint32_t(LOGD * l), lo = gather_off<LOGD>(l);
+                const uint32_t base = gather_off<LOGD>(lam + l) + (u << uint32_t(LOGD * l));
+                if (cnt >= tl_count) {
+#pragma unroll
+                    for (uint32_t k = 0; k < cnt / tl_count; ++k) {
+                        const uint32_t p = tl + k * tl_count;
+                        acc_b[lam] += G[base + p] * R[lo + p];
+                    }
+                } else if (tl < cnt) {
+                    acc_b[lam] += G[base + tl] * R[lo + tl];
+                }
+            }
+        }
+    }
+    // ---- ... then the lane exchanges, one distance at a time for all levels together, so that the exchanges of the
+    // levels overlap instead of forming one long chain
+#pragma unroll
+    for (uint32_t mask = 1; mask < 64; mask <<= 1) {
+#pragma unroll
+        for (int lam = 1; lam <= n - 1; ++lam) {
+            const uint32_t shl = uint32_t(LOGD * lam);
+            if (shl >= lg_nt) continue;
+            const uint32_t outputs = 1u << shl, tl_count = 1u << (lg_nt - shl);
+            if (outputs < 64 && mask >= outputs) acc_a[lam] += __shfl_xor(acc_a[lam], int(mask));
+            if (mask < (tl_count < 64 ? tl_count : 64u)) acc_b[lam] += __shfl_xor(acc_b[lam], int(mask));
+        }
+    }
+    uint32_t pbase = 0, pbase_b = 0;
+#pragma unroll
+    for (int lam = 1; lam <= n - 1; ++lam) {
+        const uint32_t shl = uint32_t(LOGD * lam);
+        if (shl >= lg_nt) continue;
+        const uint32_t outputs = 1u << shl, lg_tl = lg_nt - shl, tl_count = 1u << lg_tl;
+        if (outputs < 64) {
+            if (lane < outputs) part[pbase + wave * outputs + lane] = acc_a[lam];
+            pbase += waves << shl;
+        } else {
+            part[pbase + tid] = acc_a[lam];   // = [tl][v]
+            pbase += NT;
+        }
+        const uint32_t tl = tid & (tl_count - 1), u = tid >> lg_tl;
+        if (tl_count <= 64) {
+            const uint32_t q = gather_off<LOGD>(lam) + u;
+            if (tl == 0) gxs[q] = (FIRST ? T(0) : gxs[q]) + c * G[q] + acc_b[lam];
+        } else {
+            const uint32_t per = tl_count >> 6;   // wavefronts per output
+            if (lane == 0) part_b[pbase_b + u * per + (wave & (per - 1))] = acc_b[lam];
+            pbase_b += outputs * per;
+        }
+    }
+    __syncthreads();
+    // the partial sums, in a fixed order
+    pbase = 0;
+    pbase_b = 0;
+#pragma unroll
+    for (int lam = 1; lam <= n - 1; ++lam) {
+        const uint32_t shl = uint32_t(LOGD * lam);
+        if (shl >= lg_nt) break;
+        const uint32_t outputs = 1u << shl, tl_count = 1u << (lg_nt - shl);
+        const uint32_t count = outputs < 64 ? waves : tl_count;
+        for (uint32_t v = tid; v < outputs; v += NT) {
+            T total = T(0);
+#pragma unroll
+            for (uint32_t k = 0; k < count; ++k) total += part[pbase + k * outputs + v];
+            Gn[gather_off<LOGD>(lam) + v] = total;
+        }
+        pbase += outputs < 64 ? waves << shl : uint32_t(NT);
+        if (tl_count > 64) {
+            const uint32_t per = tl_count >> 6;
+            for (uint32_t u = tid; u < outputs; u += NT) {
+                T total = T(0);
+#pragma unroll
+                for (uint32_t k = 0; k < per; ++k) total += part_b[pbase_b + u * per + k];
+                const uint32_t q = gather_off<LOGD>(lam) + u;
+                gxs[q] = (FIRST ? T(0) : gxs[q]) + c * G[q] + total;
+            }
+            pbase_b += outputs * per;
+        }
+    }
+}
+
+// R_m = c_m x + x * R_{m+1} at levels 1..n (n = N - m + 1) for m = M down to 2, a barrier after each; the word w of k
+// letters takes its k - 1 cuts w = (prefix)(suffix) with compile-time shifts, so its loads do not wait for one another.
+template <typename T, int LOGD, int NT, int N, int M>
+__device__ __forceinline__ void gather_horner(const T *__restrict__ xs, T *__restrict__ rs, uint32_t tid)
+{
+    if constexpr (M >= 2) {
+        constexpr int n = N - M + 1;
+        const T c = (M & 1 ? T(1) : T(-1)) / T(M);
+        uint32_t o_out = 0, o_next = 0;   // R_M and R_{M+1} inside rs (R_N first)
+        for (int mm = N; mm > M; --mm) o_out += gather_off<LOGD>(N - mm + 2);
+        for (int mm = N; mm > M + 1; --mm) o_next += gather_off<LOGD>(N - mm + 2);
+        T *r_out = rs + o_out;
+        const T *r_next = rs + o_next;
+#pragma unroll
+        for (int k = 1; k <= n; ++k) {
+            constexpr uint32_t one = 1;
+            const uint32_t cnt = one << uint32_t(LOGD * k);
+            for (uint32_t w = tid; w < cnt; w += NT) {
+                T acc = c * xs[gather_off<LOGD>(k) + w];
+                if constexpr (M < N) {
+#pragma unroll
+                    for (int j = 1; j <= k - 1; ++j) {   // prefix of j letters, suffix of k - j
+                        const uint32_t sh = uint32_t(LOGD * (k - j));
+                        acc += xs[gather_off<LOGD>(j) + (w >> sh)] * r_next[gather_off<LOGD>(k - j) + (w & ((one << sh) - 1))];
+                    }
+                }
+                r_out[gather_off<LOGD>(k) + w] = acc;
+            }
+        }
+        __syncthreads();
+        gather_horner<T, LOGD, NT, N, M - 1>(xs, rs, tid);
+    }
+}
+
+// Steps m = M .. N-1 of the reverse pass, the depth of G_m a compile-time constant in each.
+template <typename T, int LOGD, int NT, int N, int M>
+__device__ __forceinline__ void gather_steps(T *gbuf, uint32_t s_low, const T *rs, const T *xs, T *gxs, T *part, T *part_b,
+                                             uint32_t tid)
+{
+    if constexpr (M <= N - 1) {
+        constexpr int n = N - M + 1;
+        // R_{M+1} inside rs (R_N first), G_M and G_{M+1} inside the two cotangent buffers
+        uint32_t r_off = 0;
+        for (int mm = N; mm > M + 1; --mm) r_off += gather_off<LOGD>(N - mm + 2);
+        const T c = (M & 1 ? T(1) : T(-1)) / T(M);
+        gather_step<T, LOGD, NT, n, false>(c, static_cast<const T *>(gbuf + (M & 1) * s_low), gbuf + ((M + 1) & 1) * s_low,
+                                           rs + r_off, xs, gxs, part, part_b, tid);
+        __syncthreads();
+        gather_steps<T, LOGD, NT, N, M + 1>(gbuf, s_low, rs, xs, gxs, part, part_b, tid);
+    }
+}
+
+template <typename T, int LOGD, int NT, int N>
+__global__ void __launch_bounds__(NT)
+log_bwd_gather_kernel(int64_t rows, const T *__restrict__ x_g, const T *__restrict__ g_g, T *__restrict__ gx_g)
+{
+    extern __shared__ __align__(16) unsigned char lb_smem[];
+    constexpr uint32_t d = 1u << LOGD;
+    constexpr uint32_t S = gather_off<LOGD>(N + 1), S_low = gather_off<LOGD>(N);
+    uint32_t r_stride_c = 0;
+    for (int k = 1; k <= N - 1; ++k) r_stride_c += gather_off<LOGD>(k + 1);
+    const uint32_t r_stride = r_stride_c;
+    const uint32_t tid = threadIdx.x;
+    T *xs = reinterpret_cast<T *>(lb_smem);
+    T *Rs = xs + S;
+    T *gbuf = Rs + r_stride;                                   // two cotangent buffers of S(N-1) scalars: G_m at (m & 1)
+    T *gxs = gbuf + 2 * S_low;
+    T *part = gxs + S;                                         // partial sums of one step
+    T *part_b = part + gather_partials<LOGD>(N, NT);
+    auto coef = [](int m) { return (m & 1 ? T(1) : T(-1)) / T(m); };
+    auto r_at = [&](int m) {   // R_m inside Rs: R_N first
+        uint32_t o = 0;
+        for (int mm = N; mm > m; --mm) o += gather_off<LOGD>(N - mm + 2);
+        return Rs + o;
+    };
+
+    for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
+        const T *g_row = g_g + row * S;
+        __syncthreads();   // the previous signature's gradient has been written out
+        for (uint32_t i = tid; i < S; i += NT) xs[i] = x_g[row * S + i];
+        __syncthreads();
+        gather_horner<T, LOGD, NT, N, N>(xs, Rs, tid);
+        if constexpr (N >= 2) {
+            gather_step<T, LOGD, NT, N, true>(coef(1), g_row, gbuf + (2 & 1) * S_low, static_cast<const T *>(r_at(2)), xs, gxs, part,
+                                              part_b, tid);
+            __syncthreads();
+            gather_steps<T, LOGD, NT, N, 2>(gbuf, S_low, Rs, xs, gxs, part, part_b, tid);
+        }
+        // G_N has one level
+        const T *G_last = gbuf + (N & 1) * S_low;
+        if (tid < d) gxs[tid] += coef(N) * G_last[tid];
+        __syncthreads();
+        for (uint32_t i = tid; i < S; i += NT) gx_g[row * S + i] = gxs[i];
+    }
+}
+
 template <typename T>
 __global__ void __launch_bounds__(kLbThreads)
 fill_zero_kernel(T *__restrict__ p, int64_t n)
@@ -540,13 +811,34 @@ LbWorkspace plan_workspace(const Shape &sh, int64_t elem)
 constexpr size_t kLbFusedMaxLds = 128 * 1024;
 constexpr int64_t kLbFusedSmall = 2048;   // scalars up to which the kernel is used at any batch size
 int fused_threads(const Shape &sh) { return sh.S <= kLbFusedSmall ? 256 : 1024; }
+int gather_threads(const Shape &sh) { return sh.S <= kLbFusedSmall ? 256 : 512; }   // as instantiated in launch_gather
 size_t fused_lds_bytes(const Shape &sh, const LbWorkspace &ws, size_t elem)
 {
     const int nt = fused_threads(sh);
     return size_t(2 * sh.S + ws.r_stride + 2 * ws.g_stride + 2 * kFusedRows * nt + nt / 64) * elem;
 }
+// The gather form of the single-launch kernel: d = 2 to depth 10, d = 4 to depth 6, d = 8 to depth 4 (the depths
+// instantiated below); LDS for x, the R_m, two cotangent buffers, the gradient and the partial sums.
+int gather_log_d(const Shape &sh)
+{
+    if (sh.N < 2) return 0;
+    return sh.d == 2 && sh.N <= 10 ? 1 : sh.d == 4 && sh.N <= 6 ? 2 : sh.d == 8 && sh.N <= 4 ? 3 : 0;
+}
+size_t gather_lds_bytes(const Shape &sh, const LbWorkspace &ws, size_t elem)
+{
+    const uint32_t nt = uint32_t(gather_threads(sh));
+    const uint32_t partials = sh.d == 2 ? gather_partials<1>(sh.N, nt) : sh.d == 4 ? gather_partials<2>(sh.N, nt)
+                                                                                    : gather_partials<3>(sh.N, nt);
+    return size_t(2 * sh.S + ws.r_stride + 2 * ws.g_stride + partials + kGatherPartB) * elem;
+}
+bool use_gather(const Shape &sh, const LbWorkspace &ws, size_t elem)
+{
+    // up to what one workgroup may have on this device (160 KB) less a margin
+    return gather_log_d(sh) != 0 && gather_lds_bytes(sh, ws, elem) <= 159 * 1024;
+}
 bool use_fused(const Shape &sh, const LbWorkspace &ws, size_t elem)
 {
+    if (use_gather(sh, ws, elem)) return true;
     return fused_lds_bytes(sh, ws, elem) <= kLbFusedMaxLds && (sh.S <= kLbFusedSmall || sh.B <= 256);
 }
 
@@ -566,12 +858,53 @@ void launch_horner(const Shape &sh, int n, T c_m, const T *x, const T *r_next, T
                        0, st, sh, n, c_m, x, r_next, r_out, r_stride);
 }
 
+template <typename T, int LOGD, int NT, int N>
+hipError_t launch_gather_n(const Shape &sh, size_t lds, const T *x, const T *g, T *gx, hipStream_t st)
+{
+    auto kernel = log_bwd_gather_kernel<T, LOGD, NT, N>;
+    if (lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
+        if (e != hipSuccess) return e;
+    }
+    const unsigned grid = unsigned(sh.B < (int64_t(1) << 20) ? sh.B : (int64_t(1) << 20));
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(NT), lds, st, sh.B, x, g, gx);
+    return hipGetLastError();
+}
+
+// The workgroup size follows from the size of a signature (gather_threads): 256 threads up to 2048 scalars, 512 beyond.
+template <typename T>
+hipError_t launch_gather(const Shape &sh, size_t lds, const T *x, const T *g, T *gx, hipStream_t st)
+{
+    switch (sh.d * 100 + sh.N) {
+        case 202: return launch_gather_n<T, 1, 256, 2>(sh, lds, x, g, gx, st);
+        case 203: return launch_gather_n<T, 1, 256, 3>(sh, lds, x, g, gx, st);
+        case 204: return launch_gather_n<T, 1, 256, 4>(sh, lds, x, g, gx, st);
+        case 205: return launch_gather_n<T, 1, 256, 5>(sh, lds, x, g, gx, st);
+        case 206: return launch_gather_n<T, 1, 256, 6>(sh, lds, x, g, gx, st);
+        case 207: return launch_gather_n<T, 1, 256, 7>(sh, lds, x, g, gx, st);
+        case 208: return launch_gather_n<T, 1, 256, 8>(sh, lds, x, g, gx, st);
+        case 209: return launch_gather_n<T, 1, 256, 9>(sh, lds, x, g, gx, st);
+        case 210: return launch_gather_n<T, 1, 256, 10>(sh, lds, x, g, gx, st);
+        case 402: return launch_gather_n<T, 2, 256, 2>(sh, lds, x, g, gx, st);
+        case 403: return launch_gather_n<T, 2, 256, 3>(sh, lds, x, g, gx, st);
+        case 404: return launch_gather_n<T, 2, 256, 4>(sh, lds, x, g, gx, st);
+        case 405: return launch_gather_n<T, 2, 256, 5>(sh, lds, x, g, gx, st);
+        case 406: return launch_gather_n<T, 2, 512, 6>(sh, lds, x, g, gx, st);
+        case 802: return launch_gather_n<T, 3, 256, 2>(sh, lds, x, g, gx, st);
+        case 803: return launch_gather_n<T, 3, 256, 3>(sh, lds, x, g, gx, st);
+        case 804: return launch_gather_n<T, 3, 512, 4>(sh, lds, x, g, gx, st);
+    }
+    return hipErrorNotSupported;
+}
+
 template <typename T>
 hipError_t launch_log_backward(const Shape &sh, const T *x, const T *g, T *gx, void *workspace, hipStream_t st)
 {
     const int N = sh.N;
     if (N == 1) return hipMemcpyAsync(gx, g, size_t(sh.B * sh.S) * sizeof(T), hipMemcpyDeviceToDevice, st);
     const LbWorkspace ws = plan_workspace(sh, int64_t(sizeof(T)));
+    if (use_gather(sh, ws, sizeof(T))) return launch_gather<T>(sh, gather_lds_bytes(sh, ws, sizeof(T)), x, g, gx, st);
     if (use_fused(sh, ws, sizeof(T))) {
         const size_t fused_lds = fused_lds_bytes(sh, ws, sizeof(T));
         const bool small = fused_threads(sh) == 256;

@@ -100,9 +100,9 @@ def test_workspace_is_checked():
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64], ids=["float32", "float64"])
 def test_both_routes_agree_on_the_same_shape(dtype):
-    # d = 4, N = 6 in fp32: 8 signatures go through the single-launch kernel (no workspace), 300 through the chain
-    # of launches (workspace); in fp64 the working set of a signature exceeds the LDS and both take the chain
-    d, N = 4, 6
+    # d = 3, N = 7 (3279 scalars): 8 signatures go through the single-launch kernel (no workspace), 300 through the
+    # chain of launches (workspace); in fp64 the working set of a signature exceeds the LDS and both take the chain
+    d, N = 3, 7
     code = sig.SIG_F32 if dtype == np.float32 else sig.SIG_F64
     assert sig.sig_log_backward_workspace_bytes(300, d, N, code) > 0
     assert (sig.sig_log_backward_workspace_bytes(8, d, N, code) == 0) == (dtype == np.float32)
@@ -120,14 +120,31 @@ def test_both_routes_agree_on_the_same_shape(dtype):
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64], ids=["float32", "float64"])
-@pytest.mark.parametrize("rows", [1024, 256], ids=["1024rows-chain", "256rows-single-launch-in-fp32"])
+@pytest.mark.parametrize("rows,d,N", [(5, 2, 2), (300, 2, 9), (3, 2, 10), (70, 4, 3), (9, 4, 6), (2, 8, 2), (40, 8, 3), (3, 8, 4)])
+def test_power_of_two_channels_take_one_launch_at_any_batch_size(rows, d, N, dtype):
+    # d = 2, 4, 8: the gather form of the single-launch kernel whenever a signature's working set fits the LDS (all of
+    # these do, in both precisions: the largest, d = 4, N = 6 in fp64, takes 140 KB)
+    code = sig.SIG_F32 if dtype == np.float32 else sig.SIG_F64
+    assert sig.sig_log_backward_workspace_bytes(rows, d, N, code) == 0
+    x = orc.signature(1.3 * brownian_paths(rows, 7, d, seed=rows + d + N), N).astype(dtype)
+    g = np.random.default_rng(rows + N).standard_normal(x.shape).astype(dtype)
+    got = host(sig.sig_log_backward(dev(x), dev(g), d, N))
+    want = orc.tensor_log_backward(x, g, d, N)
+    scale = orc.tensor_log_backward(-np.abs(x.astype(np.float64)), np.abs(g.astype(np.float64)), d, N)
+    assert_grad_close(got, want, scale, d, N, dtype)
+    for r in range(0, rows, 17):
+        assert_grad_close(got[r:r + 1], want[r:r + 1], scale[r:r + 1], d, N, dtype)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64], ids=["float32", "float64"])
+@pytest.mark.parametrize("rows", [1024, 256])
 def test_benchmark_shape_every_row(rows, dtype):
-    """d = 4, N = 6 at 1024 rows is what `bench.py --op logsignature_backward` times (the chain of launches); at
-    256 rows the fp32 call takes the single-launch kernel.  Every row against the oracle, batch-wide and row by row."""
+    """d = 4, N = 6 at 1024 rows is what `bench.py --op logsignature_backward` times: one launch, with 61 KB of LDS per
+    signature in fp32 and 140 KB in fp64.  Every row against the oracle, batch-wide and row by row."""
     w = WORKLOADS[1]
     code = sig.SIG_F32 if dtype == np.float32 else sig.SIG_F64
     need = sig.sig_log_backward_workspace_bytes(rows, w.d, w.N, code)
-    assert (need == 0) == (rows == 256 and dtype == np.float32)
+    assert need == 0
     x = orc.signature(workload_paths(w)[:rows], w.N).astype(dtype)
     g = np.random.default_rng(w.seed).standard_normal(x.shape).astype(dtype)
     got = host(sig.sig_log_backward(dev(x), dev(g), w.d, w.N))
