@@ -243,9 +243,11 @@ def test_lyndon_table_is_built_on_the_host(lib):
     assert lib.sig_lyndon_scatter(0, 0, 2, 2, 0, 3, sig.SIG_F32, 0, 0) == sig.SIG_OK
     lb, lbw = lib.sig_log_backward, lib.sig_log_backward_workspace_bytes
     # sig, grad_log, rows, d, N, dtype, grad_sig, workspace, workspace_bytes, hip_stream
-    # small signatures are served by a single launch that needs no workspace; large ones, or many mid-sized ones, do
+    # signatures that fit the LDS are served by a single launch that needs no workspace (at d = 2, 4, 8 whatever the
+    # batch; otherwise mid-sized ones only in small batches); large ones need one
     assert lbw(3, 2, 1, sig.SIG_F32) == 0 and lbw(3, 2, 4, sig.SIG_F32) == 0 and lbw(3, 0, 4, sig.SIG_F32) == -1
-    assert lbw(3, 4, 8, sig.SIG_F32) > 0 and lbw(1024, 4, 6, sig.SIG_F32) > 0 and lbw(8, 4, 6, sig.SIG_F32) == 0
+    assert lbw(3, 4, 8, sig.SIG_F32) > 0 and lbw(1024, 4, 6, sig.SIG_F32) == 0 and lbw(8, 4, 6, sig.SIG_F32) == 0
+    assert lbw(1024, 3, 7, sig.SIG_F32) > 0 and lbw(8, 3, 7, sig.SIG_F32) == 0
     assert lbw(3, 2, 4, 7) == -1
     assert lb(p, p + 64, 2, 2, 3, sig.SIG_F32, p, p, 1 << 20, 0) == sig.SIG_ERR_INVALID_ARG          # in place
     assert lb(p, p + 64, 2, 4, 8, sig.SIG_F32, p + 128, 0, 0, 0) == sig.SIG_ERR_INVALID_ARG          # no workspace
