@@ -123,11 +123,13 @@ def measure_peaks(torch, dev):
     valu = wgs * 256 * 4000 * 16 * 2 / (t * 1e-3) / 1e12
     t = best_ms(lambda: lib.sig_peak_hbm_write(big.data_ptr(), big.numel() * 4, hs))
     write = big.numel() * 4 / (t * 1e-3) / 1e9
+    t = best_ms(lambda: lib.sig_peak_hbm_write(big.data_ptr(), 128 << 20, hs))     # fits the 256 MB last-level cache
+    write_cached = (128 << 20) / (t * 1e-3) / 1e9
     t = best_ms(lambda: lib.sig_peak_hbm_copy(big.data_ptr() + half, big.data_ptr(), half, hs))
     copy = 2 * half / (t * 1e-3) / 1e9
     del big, sink
     return {"mfma_f32_32x32x2_tflops": mfma, "mfma_f32_4x4x1_tflops": mfma4, "valu_f32_fma_tflops": valu,
-            "hbm_write_1GiB_gbs": write, "hbm_copy_512MiB_gbs": copy}
+            "hbm_write_1GiB_gbs": write, "write_128MiB_last_level_cache_gbs": write_cached, "hbm_copy_512MiB_gbs": copy}
 
 
 def main() -> int:
@@ -322,8 +324,10 @@ def main() -> int:
         roofline = {"bound": "hbm", "achieved": bytes_io / (kern_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                     "unit": "GB/s"}
         if measured_peaks:
-            roofline["peak_measured"] = measured_peaks["hbm_copy_512MiB_gbs" if args.op == "combine"
-                                                       else "hbm_write_1GiB_gbs"]
+            # an output that fits the 256 MB last-level cache is priced against what that cache absorbs
+            write_key = "write_128MiB_last_level_cache_gbs" if bytes_io <= 256 * 1000 * 1000 else "hbm_write_1GiB_gbs"
+            roofline["peak_measured"] = measured_peaks["hbm_copy_512MiB_gbs" if args.op == "combine" else write_key]
+            roofline["peak_measured_is"] = "hbm_copy_512MiB_gbs" if args.op == "combine" else write_key
     else:
         bound = "mfma" if kernel.startswith("mfma") else "alu"
         roofline = {"bound": bound, "achieved": flops / (kern_ms * 1e-3) / 1e12, "peak": PEAK_FP32_TFLOPS,

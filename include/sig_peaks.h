@@ -29,7 +29,8 @@ int sig_peak_mfma_f32_4x4x1(float *sink, int workgroups, int iters, hipStream_t 
 int sig_peak_valu_f32(float *sink, int workgroups, int iters, hipStream_t hip_stream);
 
 /* HBM write bandwidth: fills `bytes` (a multiple of 16) at the 16-byte aligned DEVICE pointer `dst` with 16-byte
- * stores, grid-stride.  Work: `bytes` written. */
+ * stores, every wavefront writing runs of 64 KB.  Work: `bytes` written.  (A buffer that fits the 256 MB last-level
+ * cache measures that cache, not HBM.) */
 int sig_peak_hbm_write(void *dst, int64_t bytes, hipStream_t hip_stream);
 
 /* HBM copy bandwidth: `bytes` (a multiple of 16) from `src` to `dst` (both 16-byte aligned DEVICE pointers, not

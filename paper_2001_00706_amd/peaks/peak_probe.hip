@@ -62,11 +62,21 @@ __global__ __launch_bounds__(kThreads) void valu_fma_kernel(float *__restrict__ 
     sink[blockIdx.x * kThreads + threadIdx.x] = s;
 }
 
+// Every wavefront writes runs of 64 consecutive 1 KB pieces (64 KB), the runs of the wavefronts interleaved: the
+// pattern this device's memory system absorbs fastest (1 KB pieces interleaved across wavefronts reach about a
+// quarter less).
+constexpr int kRunPieces = 64;
+
 __global__ __launch_bounds__(kThreads) void hbm_write_kernel(f4 *__restrict__ dst, int64_t n16)
 {
     const f4 v = f4{1.0f, 2.0f, 3.0f, 4.0f};
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += (int64_t)gridDim.x * kThreads)
-        __builtin_nontemporal_store(v, dst + i);
+    const int64_t wave = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6, waves = (int64_t)gridDim.x * (kThreads / 64);
+    const int lane = threadIdx.x & 63;
+    for (int64_t base = wave * kRunPieces * 64; base < n16; base += waves * kRunPieces * 64)
+        for (int r = 0; r < kRunPieces; ++r) {
+            const int64_t i = base + r * 64 + lane;
+            if (i < n16) dst[i] = v;
+        }
 }
 
 __global__ __launch_bounds__(kThreads) void hbm_copy_kernel(f4 *__restrict__ dst, const f4 *__restrict__ src, int64_t n16)
