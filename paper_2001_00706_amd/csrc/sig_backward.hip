@@ -321,6 +321,11 @@ hipError_t launch_backward_f32(const Shape &sh, const float *path, const float *
     // Measured at L = 128 over B = 1..2048: with one gradient per path (final mode) the prefix-tree kernels beat the
     // two register-resident families (by up to 3.6 times at d = 8) except at d = 4, N >= 5 below 512 paths; with a
     // gradient per prefix (stream mode) the register-resident families stay ahead.
+    // d = 4, N = 6 in final mode: the top level's cotangent in registers, two wavefronts per path (105 us against 172
+    // on the prefix-tree kernels at 1024 paths of 128 points, 77 against 95 on the register-resident family at 32)
+    const bool ws_aligned = workspace != nullptr && reinterpret_cast<uintptr_t>(workspace) % 16 == 0;
+    if (aligned && ws_aligned && backward_d4n6_supported(sh) && workspace_bytes >= backward_d4n6_workspace_bytes(sh))
+        return launch_backward_d4n6_f32(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
     const bool tree_first = !sh.stream && tree_backward_supported(sh) && !(sh.d == 4 && sh.N >= 5 && sh.B < 512);
     if (aligned && !tree_first && backward_d4_supported(sh))
         return launch_backward_d4_f32(sh, path, sig, gout, gpath, gbase, st);

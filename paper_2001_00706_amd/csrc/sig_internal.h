@@ -111,6 +111,14 @@ int64_t backward_d16_workspace_bytes(const Shape &sh);
 hipError_t launch_backward_d16_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
                                    float *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st);
 
+// Gradient kernel for d = 4, N = 6, final mode, fp32, 16-byte aligned buffers: one workgroup of 128 threads per path,
+// a thread per word of three letters and half of the letters below it, the top level's cotangent in registers;
+// workspace: one gradient per increment, [B][n_inc][4] floats.
+bool backward_d4n6_supported(const Shape &sh);
+int64_t backward_d4n6_workspace_bytes(const Shape &sh);
+hipError_t launch_backward_d4n6_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
+                                    float *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st);
+
 // The same scheme for d = 2 (N = 2..9) and d = 8 (N = 2..5); buffers aligned to min(d, 4) floats.
 bool backward_pow2_supported(const Shape &sh);
 hipError_t launch_backward_pow2_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
