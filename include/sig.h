@@ -211,6 +211,31 @@ sig_status sig_combine_backward(const void *a, const void *b, const void *grad_o
 /* Bytes of workspace sig_combine_backward needs; -1 on invalid arguments or S >= 2^31. */
 int64_t sig_combine_backward_workspace_bytes(int64_t B, int d, int N, sig_dtype dtype);
 
+/* One left factor for a group of right factors: out[b][s] = a[b] [x] sigs[b][s], s < group.  This is what `initial`
+ * does to a stream-mode output (section 5.5, "keeping the signature up-to-date": a[b] the signature of what came
+ * before, sigs[b][s] the signatures of the prefixes of path b), offered on its own so that the prefix signatures
+ * themselves remain available, which the gradient below needs.
+ *   a          DEVICE pointer [B][S]; read only.
+ *   sigs, out  DEVICE pointers [B][group][S]; `out` may be `sigs` itself (in place) but must not overlap it otherwise.
+ * Errors as for sig_combine; group < 1 is SIG_ERR_INVALID_ARG. */
+sig_status sig_combine_grouped(const void *a, const void *sigs, int64_t B, int64_t group, int d, int N, sig_dtype dtype,
+                               void *out, hipStream_t hip_stream);
+
+/* Gradient through sig_combine_grouped (section 5.3; with it `initial` is differentiable in stream mode as well):
+ *   grad_sigs[b][s] as grad_b of sig_combine_backward for the product a[b] [x] sigs[b][s];
+ *   grad_a[b] = the sum over s, in the order of s, of what sig_combine_backward gives as grad_a for those products.
+ *   a  DEVICE [B][S];  sigs, grad_out  DEVICE [B][group][S]; read only.
+ *   grad_a  DEVICE [B][S], grad_sigs  DEVICE [B][group][S]: overwritten; must differ from each other and the inputs.
+ *   workspace  DEVICE pointer, 16-byte aligned, at least sig_combine_grouped_backward_workspace_bytes(...) bytes (it
+ *              holds one signature per product besides the partial sums); contents undefined on return.
+ * Errors as for sig_combine_backward. */
+sig_status sig_combine_grouped_backward(const void *a, const void *sigs, const void *grad_out, int64_t B, int64_t group, int d,
+                                        int N, sig_dtype dtype, void *grad_a, void *grad_sigs, void *workspace,
+                                        int64_t workspace_bytes, hipStream_t hip_stream);
+
+/* Bytes of workspace sig_combine_grouped_backward needs; -1 on invalid arguments or S >= 2^31. */
+int64_t sig_combine_grouped_backward_workspace_bytes(int64_t B, int64_t group, int d, int N, sig_dtype dtype);
+
 /* Group inverse of `rows` signatures: out[r] = sig[r]^{-1}, which is the signature of the same path traversed
  * backwards (section 5.4).  It is a signed permutation of the scalars: level k of the inverse holds
  * (-1)^k times the coefficient of the reversed word.

@@ -27,6 +27,9 @@ from .binding import (  # noqa: F401
     sig_combine,
     sig_combine_backward,
     sig_combine_backward_workspace_bytes,
+    sig_combine_grouped,
+    sig_combine_grouped_backward,
+    sig_combine_grouped_backward_workspace_bytes,
     sig_combine_many,
     sig_combine_strided,
     sig_invert,

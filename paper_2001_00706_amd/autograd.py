@@ -51,6 +51,22 @@ class _Combine(torch.autograd.Function):
         return grad_a, grad_b, None, None
 
 
+class _CombineGrouped(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, a, sigs, channels, depth):
+        a, sigs = a.contiguous(), sigs.contiguous()
+        ctx.save_for_backward(a, sigs)
+        ctx.args = (channels, depth)
+        return binding.sig_combine_grouped(a, sigs, channels, depth)
+
+    @staticmethod
+    def backward(ctx, grad_out):
+        a, sigs = ctx.saved_tensors
+        channels, depth = ctx.args
+        grad_a, grad_sigs = binding.sig_combine_grouped_backward(a, sigs, grad_out.contiguous(), channels, depth)
+        return grad_a, grad_sigs, None, None
+
+
 def signature_combine(sig1, sig2, channels: int, depth: int):
     """Group product `sig1 [x] sig2` of two batches of signatures `[B, S]` (section 5.5, "combining adjacent
     intervals"), differentiable in both."""
@@ -75,21 +91,23 @@ def signature(path, depth: int, stream: bool = False, basepoint=False, inverse: 
     """Depth-`depth` signature of a batch of paths `[B, L, d]` on the GPU, differentiable in `path`,
     in `basepoint` when that is a `[B, d]` tensor, and in `initial` (argument names as in section 5.5).
 
-    `initial` `[B, S]` is the signature of the data that came before; the result is `initial [x] Sig(path)`
-    (inverted as a whole if `inverse`).  With a gradient flowing into `initial` only final mode is served here
-    (in stream mode `sig_signature` applies it without a gradient)."""
+    `initial` `[B, S]` is the signature of the data that came before; the result is `initial [x] Sig(path)`, in
+    stream mode for every prefix (inverted as a whole if `inverse`)."""
     value = basepoint if isinstance(basepoint, torch.Tensor) else None
     flag = value is not None or bool(basepoint)
     if initial is None:
         return _Signature.apply(path, value, int(depth), bool(stream), flag, bool(inverse))
-    if stream:
-        if initial.requires_grad or path.requires_grad or (value is not None and value.requires_grad):
-            raise NotImplementedError("stream mode with `initial` is not differentiable here")
-        bp = value.contiguous() if value is not None else flag
-        return binding.sig_signature(path.contiguous(), int(depth), stream=True, basepoint=bp, inverse=bool(inverse),
-                                     initial=initial.contiguous())
     d = path.shape[2]
-    joined = signature_combine(initial, _Signature.apply(path, value, int(depth), False, flag, False), d, depth)
+    needs_grad = torch.is_grad_enabled() and any(t is not None and t.requires_grad for t in (path, value, initial))
+    if not needs_grad:   # one call, `initial` applied in place behind the scan
+        bp = value.contiguous() if value is not None else flag
+        return binding.sig_signature(path.contiguous(), int(depth), stream=bool(stream), basepoint=bp, inverse=bool(inverse),
+                                     initial=initial.contiguous())
+    plain = _Signature.apply(path, value, int(depth), bool(stream), flag, False)
+    if stream:
+        joined = _CombineGrouped.apply(initial, plain, d, int(depth))
+    else:
+        joined = signature_combine(initial, plain, d, depth)
     return _Invert.apply(joined, d, int(depth)) if inverse else joined
 
 

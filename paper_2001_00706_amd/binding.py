@@ -37,6 +37,9 @@ EXPORTED_SYMBOLS = (
     "sig_combine_strided",
     "sig_combine_backward",
     "sig_combine_backward_workspace_bytes",
+    "sig_combine_grouped",
+    "sig_combine_grouped_backward",
+    "sig_combine_grouped_backward_workspace_bytes",
     "sig_combine_many",
     "sig_combine_many_workspace_bytes",
     "sig_invert",
@@ -103,6 +106,12 @@ def load_library() -> ctypes.CDLL:
         lib.sig_combine_backward.argtypes = [vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, i64, vp]
         lib.sig_combine_backward_workspace_bytes.restype = i64
         lib.sig_combine_backward_workspace_bytes.argtypes = [i64, i32, i32, i32]
+        lib.sig_combine_grouped.restype = i32
+        lib.sig_combine_grouped.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, vp]
+        lib.sig_combine_grouped_backward.restype = i32
+        lib.sig_combine_grouped_backward.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, vp, vp, vp, i64, vp]
+        lib.sig_combine_grouped_backward_workspace_bytes.restype = i64
+        lib.sig_combine_grouped_backward_workspace_bytes.argtypes = [i64, i64, i32, i32, i32]
         lib.sig_combine_many.restype = i32
         lib.sig_combine_many.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, i64, vp]
         lib.sig_combine_many_workspace_bytes.restype = i64
@@ -701,6 +710,76 @@ def sig_combine_backward(a, b, grad_out, d: int, N: int, grad_a=None, grad_b=Non
         status = int(lib.sig_combine_backward(a.data_ptr(), b.data_ptr(), grad_out.data_ptr(), a.shape[0], d, N, dtype,
                                               outs[0].data_ptr(), outs[1].data_ptr(), ws_ptr, ws_bytes,
                                               torch.cuda.current_stream().cuda_stream))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return outs[0], outs[1]
+
+
+def _check_grouped(name, a, sigs, d, N):
+    import torch
+
+    _check_gpu(name, a)
+    S = sig_signature_channels(d, N)
+    if S < 0 or a.dim() != 2 or a.shape[1] != S:
+        raise ValueError(f"signatures of d={d}, N={N} are [B, {S}] tensors")
+    if not isinstance(sigs, torch.Tensor) or sigs.dtype != a.dtype or sigs.device != a.device or sigs.dim() != 3 or \
+            sigs.shape[0] != a.shape[0] or sigs.shape[2] != S or sigs.shape[1] < 1:
+        raise ValueError(f"sigs must be a [B, group, {S}] tensor of a's dtype on a's device")
+    if not (a.is_contiguous() and sigs.is_contiguous()):
+        raise ValueError("a and sigs must be contiguous")
+    return S
+
+
+def sig_combine_grouped(a, sigs, d: int, N: int, out=None):
+    """`out[b, s] = a[b] [x] sigs[b, s]`: one left factor `[B, S]` for a group of right factors `[B, group, S]`."""
+    import torch
+
+    _check_grouped("sig_combine_grouped", a, sigs, d, N)
+    if out is None:
+        out = torch.empty_like(sigs)
+    elif out.dtype != sigs.dtype or out.device != sigs.device or out.shape != sigs.shape or not out.is_contiguous():
+        raise ValueError("out must match sigs")
+    with torch.cuda.device(a.device):
+        status = int(load_library().sig_combine_grouped(a.data_ptr(), sigs.data_ptr(), sigs.shape[0], sigs.shape[1], d, N,
+                                                        _dtype_of(a), out.data_ptr(), torch.cuda.current_stream().cuda_stream))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return out
+
+
+def sig_combine_grouped_backward_workspace_bytes(B: int, group: int, d: int, N: int, dtype: int = SIG_F32) -> int:
+    return int(load_library().sig_combine_grouped_backward_workspace_bytes(B, group, d, N, dtype))
+
+
+def sig_combine_grouped_backward(a, sigs, grad_out, d: int, N: int, grad_a=None, grad_sigs=None, workspace=None):
+    """Gradients `(grad_a [B, S], grad_sigs [B, group, S])` of a loss with respect to the arguments of
+    `sig_combine_grouped(a, sigs, d, N)`, given its gradient `grad_out` `[B, group, S]` with respect to the result.
+    `workspace` (uint8, GPU) is allocated through torch if not given."""
+    import torch
+
+    _check_grouped("sig_combine_grouped_backward", a, sigs, d, N)
+    if not isinstance(grad_out, torch.Tensor) or grad_out.dtype != a.dtype or grad_out.device != a.device or \
+            grad_out.shape != sigs.shape or not grad_out.is_contiguous():
+        raise ValueError("grad_out must match sigs and be contiguous")
+    outs = []
+    for t, like in ((grad_a, a), (grad_sigs, sigs)):
+        if t is None:
+            t = torch.empty_like(like)
+        elif t.dtype != like.dtype or t.device != like.device or t.shape != like.shape or not t.is_contiguous():
+            raise ValueError("grad_a must match a and grad_sigs must match sigs")
+        outs.append(t)
+    lib = load_library()
+    dtype = _dtype_of(a)
+    with torch.cuda.device(a.device):
+        need = int(lib.sig_combine_grouped_backward_workspace_bytes(sigs.shape[0], sigs.shape[1], d, N, dtype))
+        if need < 0:
+            raise SigError(SIG_ERR_UNSUPPORTED, "no workspace size for this shape")
+        if workspace is None:
+            workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=a.device)
+        status = int(lib.sig_combine_grouped_backward(a.data_ptr(), sigs.data_ptr(), grad_out.data_ptr(), sigs.shape[0],
+                                                      sigs.shape[1], d, N, dtype, outs[0].data_ptr(), outs[1].data_ptr(),
+                                                      workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                                      torch.cuda.current_stream().cuda_stream))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return outs[0], outs[1]

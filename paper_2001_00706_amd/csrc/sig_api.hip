@@ -581,6 +581,64 @@ sig_status sig_combine_backward(const void *a, const void *b, const void *grad_o
     return err == hipSuccess ? SIG_OK : err == hipErrorNotSupported ? SIG_ERR_UNSUPPORTED : SIG_ERR_HIP;
 }
 
+sig_status sig_combine_grouped(const void *a, const void *sigs, int64_t B, int64_t group, int d, int N, sig_dtype dtype,
+                               void *out, hipStream_t hip_stream)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
+    if (B < 0 || group < 1 || (B > 0 && group > INT64_MAX / B)) return SIG_ERR_INVALID_ARG;
+    sig::Shape sh;
+    const sig_status st = make_rows_shape(B * group, d, N, sh);
+    if (st != SIG_OK) return st;
+    if (B == 0) return SIG_OK;
+    if (a == nullptr || sigs == nullptr || out == nullptr || out == a) return SIG_ERR_INVALID_ARG;
+    if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
+    const size_t elem = dtype == SIG_F32 ? sizeof(float) : sizeof(double);
+    if (out != sigs && hipMemcpyAsync(out, sigs, size_t(sh.B) * size_t(sh.S) * elem, hipMemcpyDeviceToDevice, hip_stream) != hipSuccess)
+        return SIG_ERR_HIP;
+    const hipError_t err =
+        dtype == SIG_F32 ? sig::launch_left_mul_f32(sh, static_cast<const float *>(a), group, static_cast<float *>(out), hip_stream)
+                         : sig::launch_left_mul_f64(sh, static_cast<const double *>(a), group, static_cast<double *>(out), hip_stream);
+    return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
+int64_t sig_combine_grouped_backward_workspace_bytes(int64_t B, int64_t group, int d, int N, sig_dtype dtype)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return -1;
+    if (B < 0 || group < 1 || (B > 0 && group > INT64_MAX / B)) return -1;
+    sig::Shape sh;
+    if (make_rows_shape(B * group, d, N, sh) != SIG_OK || !sig::combine_supported(sh)) return -1;
+    return sig::combine_grouped_backward_workspace_bytes(sh, dtype);
+}
+
+sig_status sig_combine_grouped_backward(const void *a, const void *sigs, const void *grad_out, int64_t B, int64_t group, int d,
+                                        int N, sig_dtype dtype, void *grad_a, void *grad_sigs, void *workspace,
+                                        int64_t workspace_bytes, hipStream_t hip_stream)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
+    if (B < 0 || group < 1 || (B > 0 && group > INT64_MAX / B)) return SIG_ERR_INVALID_ARG;
+    sig::Shape sh;
+    const sig_status st = make_rows_shape(B * group, d, N, sh);
+    if (st != SIG_OK) return st;
+    if (B == 0) return SIG_OK;
+    if (a == nullptr || sigs == nullptr || grad_out == nullptr || grad_a == nullptr || grad_sigs == nullptr ||
+        grad_a == grad_sigs || grad_a == grad_out || grad_sigs == grad_out || grad_a == a || grad_a == sigs || grad_sigs == a ||
+        grad_sigs == sigs)
+        return SIG_ERR_INVALID_ARG;
+    if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
+    const int64_t need = sig::combine_grouped_backward_workspace_bytes(sh, dtype);
+    if (workspace == nullptr || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)
+        return SIG_ERR_INVALID_ARG;
+    const hipError_t err =
+        dtype == SIG_F32
+            ? sig::launch_combine_grouped_backward_f32(sh, group, static_cast<const float *>(a), static_cast<const float *>(sigs),
+                                                       static_cast<const float *>(grad_out), static_cast<float *>(grad_a),
+                                                       static_cast<float *>(grad_sigs), workspace, hip_stream)
+            : sig::launch_combine_grouped_backward_f64(sh, group, static_cast<const double *>(a), static_cast<const double *>(sigs),
+                                                       static_cast<const double *>(grad_out), static_cast<double *>(grad_a),
+                                                       static_cast<double *>(grad_sigs), workspace, hip_stream);
+    return err == hipSuccess ? SIG_OK : err == hipErrorNotSupported ? SIG_ERR_UNSUPPORTED : SIG_ERR_HIP;
+}
+
 sig_status sig_lyndon_scatter(const void *grad_logsig, int64_t rows, int d, int N, const int64_t *indices, int64_t n,
                               sig_dtype dtype, void *grad_log, hipStream_t hip_stream)
 {

@@ -96,6 +96,14 @@ hipError_t launch_combine_backward_f32(const Shape &sh, const float *a, const fl
                                        void *workspace, hipStream_t st);
 hipError_t launch_combine_backward_f64(const Shape &sh, const double *a, const double *b, const double *g, double *ga, double *gb,
                                        void *workspace, hipStream_t st);
+// The same for rows that share their left factor in groups: row r is a[r / group] [x] b[r] (sh.B rows, a multiple of
+// `group`); ga has sh.B / group rows, each the sum over its group in row order.  The workspace is that of the plain
+// product's gradient, rounded up to 256 bytes, followed by one signature per row.
+int64_t combine_grouped_backward_workspace_bytes(const Shape &sh, sig_dtype dtype);
+hipError_t launch_combine_grouped_backward_f32(const Shape &sh, int64_t group, const float *a, const float *b, const float *g,
+                                               float *ga, float *gb, void *workspace, hipStream_t st);
+hipError_t launch_combine_grouped_backward_f64(const Shape &sh, int64_t group, const double *a, const double *b, const double *g,
+                                               double *ga, double *gb, void *workspace, hipStream_t st);
 hipError_t launch_scatter_f32(const Shape &sh, const float *in, const int64_t *index, int64_t n, float *out, hipStream_t st);
 hipError_t launch_scatter_f64(const Shape &sh, const double *in, const int64_t *index, int64_t n, double *out, hipStream_t st);
 

@@ -98,8 +98,8 @@ log_bwd_horner_kernel(Shape sh, int n, T c_m, const T *__restrict__ x, const T *
 // One step: partial column sums (x^T M_l) and row dots (M_l R_l) of every matrix of the step.
 template <typename T>
 __global__ void __launch_bounds__(kLbThreads)
-log_bwd_main_kernel(LbStep stp, const T *__restrict__ x, int64_t x_stride, const T *__restrict__ G, int64_t g_stride,
-                    const T *__restrict__ R, int64_t r_stride, T *__restrict__ apart, T *__restrict__ bpart)
+log_bwd_main_kernel(LbStep stp, const T *__restrict__ x, int64_t x_stride, int64_t x_group, const T *__restrict__ G,
+                    int64_t g_stride, const T *__restrict__ R, int64_t r_stride, T *__restrict__ apart, T *__restrict__ bpart)
 {
     __shared__ T prod[2][kLbThreads];
     __shared__ T wsum[kLbWideRows][kLbThreads / 64];
@@ -111,7 +111,7 @@ log_bwd_main_kernel(LbStep stp, const T *__restrict__ x, int64_t x_stride, const
         if (wg >= stp.lv[i].wg_start) li = i;
     const LbLevel lv = stp.lv[li];
     const uint32_t C = lv.C, U = lv.U;
-    const T *xr = x + row * x_stride;
+    const T *xr = x + (row / x_group) * x_stride;   // x_group consecutive rows share one left factor
     const T *M = G + row * g_stride + lv.base;
     const T *Rl = R + row * r_stride + (lv.base - C);   // level l of R_{m+1}
     T *ap = apart + row * stp.apart_stride + lv.apart_off;
@@ -950,7 +950,7 @@ hipError_t launch_log_backward(const Shape &sh, const T *x, const T *g, T *gx, v
         T *G_next = Gb[(m + 1) & 1];
         const int64_t wgs = sh.B * int64_t(stp.wgs);
         if (wgs > 0x7fffffff) return hipErrorNotSupported;
-        hipLaunchKernelGGL((log_bwd_main_kernel<T>), dim3(unsigned(wgs)), dim3(kLbThreads), 0, st, stp, x, sh.S, G, g_stride,
+        hipLaunchKernelGGL((log_bwd_main_kernel<T>), dim3(unsigned(wgs)), dim3(kLbThreads), 0, st, stp, x, sh.S, int64_t(1), G, g_stride,
                            Rs + r_offset(sh, m + 1), ws.r_stride, apart, bpart);
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
@@ -966,29 +966,55 @@ hipError_t launch_log_backward(const Shape &sh, const T *x, const T *g, T *gx, v
 
 // Gradient of out = a [x] b: grad_a[u] = g[u] + sum_v g[u v] b[v], grad_b[v] = g[v] + sum_u a[u] g[u v]: one step of the
 // scheme above with x = a, R = b, G = g and unit coefficients.
+// out[b][s] = sum over the rows s of group b, summed in the order of s.
+template <typename T>
+__global__ void __launch_bounds__(kLbThreads)
+group_sum_kernel(const T *__restrict__ in, int64_t groups, int64_t group, int64_t S, T *__restrict__ out)
+{
+    const int64_t total = groups * S;
+    for (int64_t i = int64_t(blockIdx.x) * kLbThreads + threadIdx.x; i < total; i += int64_t(gridDim.x) * kLbThreads) {
+        const int64_t b = i / S, q = i - b * S;
+        const T *p = in + b * group * S + q;
+        T s = T(0);
+        for (int64_t r = 0; r < group; ++r) s += p[r * S];
+        out[i] = s;
+    }
+}
+
+// The gradient of the rows a[r / a_group] [x] b[r]; with a_group > 1 the per-row gradients of the left factor go to
+// the end of the workspace and are summed over each group afterwards.
 template <typename T>
 hipError_t launch_combine_backward(const Shape &sh, const T *a, const T *b, const T *g, T *ga, T *gb, void *workspace,
-                                   hipStream_t st)
+                                   hipStream_t st, int64_t a_group = 1)
 {
-    if (sh.N == 1) {
-        hipError_t err = hipMemcpyAsync(ga, g, size_t(sh.B * sh.S) * sizeof(T), hipMemcpyDeviceToDevice, st);
-        if (err != hipSuccess) return err;
-        return hipMemcpyAsync(gb, g, size_t(sh.B * sh.S) * sizeof(T), hipMemcpyDeviceToDevice, st);
-    }
     const LbWorkspace ws = plan_workspace(sh, int64_t(sizeof(T)));
     char *base = static_cast<char *>(workspace);
+    T *ga_rows = a_group > 1 ? reinterpret_cast<T *>(base + ((ws.total + 255) / 256) * 256) : ga;
+    const int64_t groups = sh.B / a_group;
+    const int64_t sum_wgs = (groups * sh.S + kLbThreads - 1) / kLbThreads;
+    const unsigned sum_grid = unsigned(sum_wgs < 65536 ? sum_wgs : 65536);
+    if (sh.N == 1) {
+        hipError_t err = hipMemcpyAsync(gb, g, size_t(sh.B * sh.S) * sizeof(T), hipMemcpyDeviceToDevice, st);
+        if (err != hipSuccess) return err;
+        if (a_group == 1) return hipMemcpyAsync(ga, g, size_t(sh.B * sh.S) * sizeof(T), hipMemcpyDeviceToDevice, st);
+        hipLaunchKernelGGL((group_sum_kernel<T>), dim3(sum_grid), dim3(kLbThreads), 0, st, g, groups, a_group, int64_t(sh.S), ga);
+        return hipGetLastError();
+    }
     T *apart = reinterpret_cast<T *>(base + ws.a_off);
     T *bpart = reinterpret_cast<T *>(base + ws.b_off);
     const LbStep stp = plan_step(sh, sh.N);
     const int64_t wgs = sh.B * int64_t(stp.wgs);
     if (wgs > 0x7fffffff) return hipErrorNotSupported;
-    hipLaunchKernelGGL((log_bwd_main_kernel<T>), dim3(unsigned(wgs)), dim3(kLbThreads), 0, st, stp, a, sh.S, g, sh.S, b, sh.S,
-                       apart, bpart);
+    hipLaunchKernelGGL((log_bwd_main_kernel<T>), dim3(unsigned(wgs)), dim3(kLbThreads), 0, st, stp, a, sh.S, a_group, g, sh.S, b,
+                       sh.S, apart, bpart);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     const int64_t threads = sh.B * 2 * int64_t(stp.S_cur);
     hipLaunchKernelGGL((log_bwd_finish_kernel<T>), dim3(unsigned((threads + kLbThreads - 1) / kLbThreads)), dim3(kLbThreads), 0,
-                       st, stp, sh.B, T(1), T(0), 1, 0, 1, g, sh.S, apart, bpart, gb, sh.S, ga, sh.S);
+                       st, stp, sh.B, T(1), T(0), 1, 0, 1, g, sh.S, apart, bpart, gb, sh.S, ga_rows, sh.S);
+    err = hipGetLastError();
+    if (err != hipSuccess || a_group == 1) return err;
+    hipLaunchKernelGGL((group_sum_kernel<T>), dim3(sum_grid), dim3(kLbThreads), 0, st, ga_rows, groups, a_group, int64_t(sh.S), ga);
     return hipGetLastError();
 }
 
@@ -1021,6 +1047,12 @@ int64_t combine_backward_workspace_bytes(const Shape &sh, sig_dtype dtype)
     return plan_workspace(sh, dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double))).total;
 }
 
+int64_t combine_grouped_backward_workspace_bytes(const Shape &sh, sig_dtype dtype)
+{
+    const int64_t elem = dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double));
+    return ((plan_workspace(sh, elem).total + 255) / 256) * 256 + sh.B * sh.S * elem;
+}
+
 hipError_t launch_log_backward_f32(const Shape &sh, const float *sig, const float *grad_log, float *grad_sig, void *workspace,
                                    hipStream_t st)
 {
@@ -1043,6 +1075,18 @@ hipError_t launch_combine_backward_f64(const Shape &sh, const double *a, const d
                                        void *workspace, hipStream_t st)
 {
     return launch_combine_backward<double>(sh, a, b, g, ga, gb, workspace, st);
+}
+
+hipError_t launch_combine_grouped_backward_f32(const Shape &sh, int64_t group, const float *a, const float *b, const float *g,
+                                               float *ga, float *gb, void *workspace, hipStream_t st)
+{
+    return launch_combine_backward<float>(sh, a, b, g, ga, gb, workspace, st, group);
+}
+
+hipError_t launch_combine_grouped_backward_f64(const Shape &sh, int64_t group, const double *a, const double *b, const double *g,
+                                               double *ga, double *gb, void *workspace, hipStream_t st)
+{
+    return launch_combine_backward<double>(sh, a, b, g, ga, gb, workspace, st, group);
 }
 
 hipError_t launch_scatter_f32(const Shape &sh, const float *in, const int64_t *index, int64_t n, float *out, hipStream_t st)

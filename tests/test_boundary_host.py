@@ -206,6 +206,24 @@ def test_signature_invert_and_strided_combine_validation(lib):
     assert cb(p, p + 64, p + 128, 2, 2, 3, sig.SIG_F32, p + 192, p + 256, 0, 0, 0) == sig.SIG_ERR_INVALID_ARG
     assert cb(p, p + 64, 0, 2, 2, 3, sig.SIG_F32, p + 192, p + 256, p, 1 << 20, 0) == sig.SIG_ERR_INVALID_ARG
     assert cb(0, 0, 0, 0, 2, 3, sig.SIG_F32, 0, 0, 0, 0, 0) == sig.SIG_OK
+    cg, cgb, cgw = lib.sig_combine_grouped, lib.sig_combine_grouped_backward, lib.sig_combine_grouped_backward_workspace_bytes
+    # a, sigs, B, group, d, N, dtype, out, hip_stream
+    assert cg(p, p + 64, 2, 0, 2, 3, sig.SIG_F32, p + 64, 0) == sig.SIG_ERR_INVALID_ARG
+    assert cg(p, 0, 2, 3, 2, 3, sig.SIG_F32, p + 64, 0) == sig.SIG_ERR_INVALID_ARG
+    assert cg(p, p + 64, 2, 3, 2, 3, sig.SIG_F32, p, 0) == sig.SIG_ERR_INVALID_ARG           # out is the left factor
+    assert cg(p, p + 64, 2, 1 << 62, 2, 3, sig.SIG_F32, p + 64, 0) == sig.SIG_ERR_INVALID_ARG  # B * group overflows
+    assert cg(p, p + 64, 2, 3, 2, 32, sig.SIG_F32, p + 64, 0) == sig.SIG_ERR_UNSUPPORTED
+    assert cg(0, 0, 0, 3, 2, 3, sig.SIG_F32, 0, 0) == sig.SIG_OK
+    # the plain gradient's workspace for all B * group products, rounded up, plus one signature per product
+    plain = cbw(6, 2, 3, sig.SIG_F32)
+    assert cgw(2, 3, 2, 3, sig.SIG_F32) == (plain + 255) // 256 * 256 + 6 * 14 * 4
+    assert cgw(2, 0, 2, 3, sig.SIG_F32) == -1 and cgw(2, 3, 2, 3, 9) == -1 and cgw(-1, 3, 2, 3, sig.SIG_F32) == -1
+    # a, sigs, grad_out, B, group, d, N, dtype, grad_a, grad_sigs, workspace, workspace_bytes, hip_stream
+    assert cgb(p, p + 64, p + 128, 2, 3, 2, 3, sig.SIG_F32, p + 192, p + 192, p, 1 << 20, 0) == sig.SIG_ERR_INVALID_ARG
+    assert cgb(p, p + 64, p + 128, 2, 3, 2, 3, sig.SIG_F32, p + 192, p + 256, 0, 0, 0) == sig.SIG_ERR_INVALID_ARG
+    assert cgb(p, p + 64, p + 128, 2, 3, 2, 3, sig.SIG_F32, p + 192, p + 256, p + 8, 1 << 20, 0) == sig.SIG_ERR_INVALID_ARG
+    assert cgb(p, p + 64, p + 128, 2, 0, 2, 3, sig.SIG_F32, p + 192, p + 256, p, 1 << 20, 0) == sig.SIG_ERR_INVALID_ARG
+    assert cgb(0, 0, 0, 0, 3, 2, 3, sig.SIG_F32, 0, 0, 0, 0, 0) == sig.SIG_OK
     m, mb = lib.sig_combine_many, lib.sig_combine_many_workspace_bytes
     # sigs, B, n, d, N, dtype, out, workspace, workspace_bytes, hip_stream
     assert mb(3, 1, 2, 2, sig.SIG_F32) == 0 and mb(3, 2, 2, 2, sig.SIG_F32) == 0

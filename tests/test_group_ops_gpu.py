@@ -240,6 +240,113 @@ def test_gradient_of_the_group_product(B, d, N, dtype):
             assert np.linalg.norm(got[:, sl] - w[:, sl]) <= tol * np.linalg.norm(sc[:, sl])
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("B,group,d,N", [(3, 5, 2, 6), (2, 9, 4, 5), (4, 1, 3, 4), (1, 37, 4, 6), (2, 3, 8, 4), (3, 4, 5, 1),
+                                         (2, 6, 7, 2), (130, 2, 2, 3)])
+def test_one_left_factor_for_a_group_of_right_factors_and_its_gradient(B, group, d, N, dtype):
+    # what `initial` does to a stream-mode output: row (b, s) is a[b] [x] sigs[b, s]; the oracle does every product
+    # on its own and the gradients of the shared factor are added up here
+    rng = np.random.default_rng(B + 10 * d + 100 * N + group)
+    S = orc.channels(d, N)
+    a = orc.signature(brownian_paths(B, 6, d, seed=d + N), N).astype(dtype)
+    sigs = orc.signature(brownian_paths(B * group, 5, d, seed=d * N + 1), N).astype(dtype).reshape(B, group, S)
+    g = rng.standard_normal(sigs.shape).astype(dtype)
+    got = host(sig.sig_combine_grouped(dev(a), dev(sigs), d, N))
+    want = np.stack([np.stack([orc.group_mul(a[b], sigs[b, s], d, N) for s in range(group)]) for b in range(B)])
+    assert_levels_close(got, want, d, N, dtype)
+    # in place
+    buf = dev(sigs.copy())
+    assert sig.sig_combine_grouped(dev(a), buf, d, N, out=buf) is buf
+    np.testing.assert_array_equal(host(buf), got)
+
+    ga, gs = sig.sig_combine_grouped_backward(dev(a), dev(sigs), dev(g), d, N)
+    ga, gs = host(ga), host(gs)
+    tol = 1e-5 if dtype == np.float32 else 1e-13
+    want_a, want_s = np.zeros((B, S)), np.zeros((B, group, S))
+    scale_a, scale_s = np.zeros((B, S)), np.zeros((B, group, S))
+    for b in range(B):
+        for s in range(group):
+            wa, ws = orc.group_mul_backward(a[b], sigs[b, s], g[b, s], d, N)
+            sa, ss = orc.group_mul_backward(np.abs(a[b]), np.abs(sigs[b, s]), np.abs(g[b, s]), d, N)
+            want_a[b] += wa
+            scale_a[b] += sa
+            want_s[b, s], scale_s[b, s] = ws, ss
+    for sl in orc.level_slices(d, N):
+        assert np.linalg.norm(ga[:, sl] - want_a[:, sl]) <= tol * np.linalg.norm(scale_a[:, sl])
+        assert np.linalg.norm(gs[..., sl] - want_s[..., sl]) <= tol * np.linalg.norm(scale_s[..., sl])
+
+
+def test_grouped_product_argument_errors():
+    import torch
+    d, N = 3, 3
+    S = orc.channels(d, N)
+    a = torch.zeros(2, S, device="cuda:0")
+    sigs = torch.zeros(2, 4, S, device="cuda:0")
+    lib = sig.binding.load_library()
+    f, fb = lib.sig_combine_grouped, lib.sig_combine_grouped_backward
+    assert f(a.data_ptr(), sigs.data_ptr(), 2, 0, d, N, sig.SIG_F32, sigs.data_ptr(), 0) == sig.SIG_ERR_INVALID_ARG
+    assert f(0, sigs.data_ptr(), 2, 4, d, N, sig.SIG_F32, sigs.data_ptr(), 0) == sig.SIG_ERR_INVALID_ARG
+    assert f(a.data_ptr(), sigs.data_ptr(), 2, 4, d, N, 7, sigs.data_ptr(), 0) == sig.SIG_ERR_INVALID_ARG
+    assert f(a.data_ptr(), sigs.data_ptr(), 0, 4, d, N, sig.SIG_F32, sigs.data_ptr(), 0) == sig.SIG_OK
+    need = sig.sig_combine_grouped_backward_workspace_bytes(2, 4, d, N)
+    assert need >= 2 * 4 * S * 4
+    assert sig.sig_combine_grouped_backward_workspace_bytes(2, 0, d, N) == -1
+    ga, gs, g = torch.full_like(a, 7.0), torch.full_like(sigs, 7.0), torch.ones_like(sigs)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    # a short workspace, a missing one, outputs that alias: refused, outputs untouched
+    args = (a.data_ptr(), sigs.data_ptr(), g.data_ptr(), 2, 4, d, N, sig.SIG_F32)
+    assert fb(*args, ga.data_ptr(), gs.data_ptr(), ws.data_ptr(), need - 1, 0) == sig.SIG_ERR_INVALID_ARG
+    assert fb(*args, ga.data_ptr(), gs.data_ptr(), 0, need, 0) == sig.SIG_ERR_INVALID_ARG
+    assert fb(*args, ga.data_ptr(), g.data_ptr(), ws.data_ptr(), need, 0) == sig.SIG_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert bool((ga == 7).all()) and bool((gs == 7).all())
+    assert fb(*args, ga.data_ptr(), gs.data_ptr(), ws.data_ptr(), need, 0) == sig.SIG_OK
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("inverse", [False, True])
+def test_initial_is_differentiable_in_stream_mode(inverse):
+    import torch
+    d, N = 2, 3
+    x = dev(brownian_paths(2, 5, d, seed=12).astype(np.float64)).requires_grad_(True)
+    init = dev(orc.signature(brownian_paths(2, 4, d, seed=3), N)).requires_grad_(True)
+    bp = dev(uniform_paths(2, 1, d, seed=10)[:, 0].astype(np.float64)).requires_grad_(True)
+    assert torch.autograd.gradcheck(lambda p, i: sig.signature(p, N, stream=True, initial=i, inverse=inverse), (x, init),
+                                    eps=1e-6, atol=1e-7, rtol=1e-6)
+    assert torch.autograd.gradcheck(lambda p, i, q: sig.signature(p, N, stream=True, basepoint=q, initial=i, inverse=inverse),
+                                    (x, init, bp), eps=1e-6, atol=1e-7, rtol=1e-6)
+    # the differentiable route and the single call that applies `initial` in place give the same values
+    with torch.no_grad():
+        direct = sig.signature(x, N, stream=True, initial=init, inverse=inverse)
+    np.testing.assert_allclose(host(sig.signature(x, N, stream=True, initial=init, inverse=inverse).detach()), host(direct),
+                               rtol=1e-13, atol=1e-15)
+
+
+def test_stream_gradient_through_initial_against_the_oracle():
+    # loss = sum of g * (initial [x] Sig(prefixes of x)): with y the earlier data whose signature is `initial`, the
+    # oracle's gradient of the stream signature of the joined path, taken at the points of x after the junction, is
+    # the path gradient; the gradient of `initial` is checked through the oracle's product gradient
+    import torch
+    B, L, d, N = 3, 9, 4, 5
+    S = orc.channels(d, N)
+    x = brownian_paths(B, L, d, seed=31).astype(np.float64)
+    init = orc.signature(brownian_paths(B, 6, d, seed=32).astype(np.float64), N)
+    g = np.random.default_rng(5).standard_normal((B, L - 1, S))
+    xt, it = dev(x).requires_grad_(True), dev(init).requires_grad_(True)
+    out = sig.signature(xt, N, stream=True, initial=it)
+    out.backward(dev(g))
+    plain = orc.signature(x, N, stream=True)
+    want_i, want_plain = np.zeros((B, S)), np.zeros((B, L - 1, S))
+    for b in range(B):
+        for s in range(L - 1):
+            wa, ws = orc.group_mul_backward(init[b], plain[b, s], g[b, s], d, N)
+            want_i[b] += wa
+            want_plain[b, s] = ws
+    want_x = orc.signature_backward(x, want_plain, N, stream=True)
+    np.testing.assert_allclose(host(it.grad), want_i, rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(host(xt.grad), want_x, rtol=1e-9, atol=1e-11)
+
+
 def test_gradcheck_through_products_and_initial():
     import torch
     d, N = 2, 3
