@@ -45,6 +45,7 @@ from .binding import (  # noqa: F401
     sig_forward,
     sig_forward_chunked,
     sig_forward_chunked_workspace_bytes,
+    sig_forward_chunks_hint,
     sig_forward_chunked_static,
     sig_forward_chunked_static_max_bytes,
     sig_forward_raw,

@@ -13,8 +13,12 @@ class _Signature(torch.autograd.Function):
     def forward(ctx, path, basepoint_value, depth, stream, basepoint, inverse):
         path = path.contiguous()
         bp = basepoint_value.contiguous() if basepoint_value is not None else bool(basepoint)
-        plain = binding.sig_signature(path, depth, stream=stream, basepoint=bp)
-        d = path.shape[2]
+        B, L, d = path.shape
+        chunks = 1 if stream else binding.sig_forward_chunks_hint(B, L, d, depth, bool(basepoint), binding._dtype_of(path))
+        if chunks > 1:   # few long paths: the scan as a reduction over the length (section 5.1)
+            plain = binding.sig_forward_chunked(path, depth, chunks, basepoint=bp)
+        else:
+            plain = binding.sig_signature(path, depth, stream=stream, basepoint=bp)
         out = binding.sig_invert(plain, d, depth) if inverse else plain
         ctx.save_for_backward(path, plain, basepoint_value)
         ctx.args = (depth, stream, basepoint, inverse, d)

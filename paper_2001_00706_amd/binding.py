@@ -30,6 +30,7 @@ EXPORTED_SYMBOLS = (
     "sig_forward_variant",
     "sig_forward_chunked",
     "sig_forward_chunked_workspace_bytes",
+    "sig_forward_chunks_hint",
     "sig_forward_chunked_static",
     "sig_forward_chunked_static_max_bytes",
     "sig_combine",
@@ -94,6 +95,8 @@ def load_library() -> ctypes.CDLL:
         lib.sig_forward_chunked.argtypes = [vp, i64, i64, i32, i32, i32, vp, i32, i32, vp, vp, i64, vp]
         lib.sig_forward_chunked_workspace_bytes.restype = i64
         lib.sig_forward_chunked_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32, i32]
+        lib.sig_forward_chunks_hint.restype = i32
+        lib.sig_forward_chunks_hint.argtypes = [i64, i64, i32, i32, i32, i32]
         lib.sig_forward_chunked_static.restype = i32
         lib.sig_forward_chunked_static.argtypes = [vp, i64, i64, i32, i32, i32, vp, i32, i32, vp, vp]
         lib.sig_forward_chunked_static_max_bytes.restype = i64
@@ -577,6 +580,11 @@ def sig_logsignature(path, N: int, stream: bool = False, basepoint=False, invers
 def sig_forward_chunked_workspace_bytes(B: int, L: int, d: int, N: int, basepoint: bool, chunks: int,
                                         dtype: int = SIG_F32) -> int:
     return int(load_library().sig_forward_chunked_workspace_bytes(B, L, d, N, int(bool(basepoint)), chunks, dtype))
+
+
+def sig_forward_chunks_hint(B: int, L: int, d: int, N: int, basepoint: bool = False, dtype: int = SIG_F32) -> int:
+    """The number of chunks `sig_forward_chunked` should be given for this shape; 1 where `sig_forward` is faster."""
+    return int(load_library().sig_forward_chunks_hint(B, L, d, N, int(bool(basepoint)), dtype))
 
 
 def sig_forward_chunked(path, N: int, chunks: int, basepoint=False, out=None, workspace=None):

@@ -334,6 +334,27 @@ int64_t sig_forward_chunked_workspace_bytes(int64_t B, int64_t L, int d, int N, 
     return (sh.B + sh.B / 2) * sh.S * int64_t(dtype == SIG_F32 ? sizeof(float) : sizeof(double));
 }
 
+int sig_forward_chunks_hint(int64_t B, int64_t L, int d, int N, int basepoint, sig_dtype dtype)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return 0;
+    sig::Shape sh;
+    if (make_shape(B, L, d, N, 0, basepoint, sh) != SIG_OK) return 0;
+    // the d = 8 matrix family already spreads a path over 64 wavefronts; everything else scans a path in one
+    // workgroup and gains from 512 increments on
+    const int64_t shortest = (d == 8 && N >= 4 && N <= 6 && dtype == SIG_F32) ? 4096 : 512;
+    if (B < 1 || B > 64 || sh.n_inc < shortest) return 1;
+    const int64_t elem = dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double));
+    int chunks = 1;
+    for (;;) {
+        const int64_t next = int64_t(chunks) * 2;
+        if (next > 65536 || next * B > 1024 || sh.n_inc / next < 64) break;
+        if (next * B > (int64_t(256) << 20) / (sh.S * elem)) break;   // the products move every stretch's signature
+        if (sig_forward_chunked_workspace_bytes(B, L, d, N, basepoint, int(next), dtype) < 0) break;
+        chunks = int(next);
+    }
+    return chunks;
+}
+
 // The chunked scan itself; `use_static_scratch` selects the library's own scratch array instead of `workspace`.
 static sig_status forward_chunked(const void *path, int64_t B, int64_t L, int d, int N, int basepoint,
                                   const void *basepoint_value, int chunks, sig_dtype dtype, void *out,

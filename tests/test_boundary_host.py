@@ -238,6 +238,23 @@ def test_signature_invert_and_strided_combine_validation(lib):
     assert m(0, 0, 5, 2, 2, sig.SIG_F32, 0, 0, 0, 0) == sig.SIG_OK
 
 
+def test_chunk_hint(lib):
+    h = lib.sig_forward_chunks_hint
+    # B, L, d, N, basepoint, dtype
+    assert h(1, 65536, 4, 6, 0, sig.SIG_F32) == 512          # 65535 increments: 1024 chunks would be 63 each
+    assert h(1, 65537, 4, 6, 0, sig.SIG_F32) == 1024
+    assert h(1, 65536, 4, 6, 1, sig.SIG_F32) == 1024         # the basepoint adds an increment
+    assert h(32, 128, 8, 5, 0, sig.SIG_F32) == 1             # the cfg3 shape: short
+    assert h(1024, 128, 4, 6, 0, sig.SIG_F32) == 1 and h(65, 100000, 4, 6, 0, sig.SIG_F32) == 1
+    assert h(1, 512, 4, 6, 0, sig.SIG_F32) == 1 and h(1, 513, 4, 6, 0, sig.SIG_F32) == 8
+    assert h(1, 2049, 8, 4, 0, sig.SIG_F32) == 1 and h(1, 4097, 8, 4, 0, sig.SIG_F32) == 64
+    assert h(1, 2049, 8, 4, 0, sig.SIG_F64) == 32            # no 64-wavefront kernels in fp64
+    assert h(64, 65537, 4, 6, 0, sig.SIG_F32) == 16          # 1024 stretches at most
+    assert h(64, 65537, 16, 4, 0, sig.SIG_F32) == 8          # 256 MiB of signatures at most
+    assert h(1, 1, 4, 6, 0, sig.SIG_F32) == 0 and h(1, 4096, 4, 6, 0, 9) == 0 and h(1, 4096, 0, 6, 0, sig.SIG_F32) == 0
+    assert h(0, 4096, 4, 6, 0, sig.SIG_F32) == 1
+
+
 def test_lyndon_table_is_built_on_the_host(lib):
     # appendix A.2.1; d = 2, N = 4: a, b, ab, aab, abb, aaab, aabb, abbb at offsets 0,1 | 2+1 | 6+1, 6+3 | 14+1, 14+3, 14+7
     assert sig.sig_lyndon_indices(2, 4) == [0, 1, 3, 7, 9, 15, 17, 21]

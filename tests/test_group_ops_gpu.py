@@ -347,6 +347,26 @@ def test_stream_gradient_through_initial_against_the_oracle():
     np.testing.assert_allclose(host(xt.grad), want_x, rtol=1e-9, atol=1e-11)
 
 
+@pytest.mark.parametrize("B,L,d,N,basepoint", [(2, 700, 3, 4, False), (1, 5000, 4, 6, True), (3, 4200, 8, 4, False)])
+def test_differentiable_signature_chunks_few_long_paths_by_itself(B, L, d, N, basepoint):
+    # final mode with at most 64 long paths goes through sig_forward_chunked (the hint says how many chunks); values
+    # and gradients are those of the plain scan
+    import torch
+    for dtype in (np.float32, np.float64):
+        code = sig.SIG_F32 if dtype == np.float32 else sig.SIG_F64
+        assert sig.sig_forward_chunks_hint(B, L, d, N, basepoint, code) > 1
+        x = (brownian_paths(B, L, d, seed=L) + 0.5).astype(dtype)
+        g = np.random.default_rng(L).standard_normal((B, orc.channels(d, N))).astype(dtype)
+        xt = dev(x).requires_grad_(True)
+        out = sig.signature(xt, N, basepoint=basepoint)
+        out.backward(dev(g))
+        full = np.concatenate([np.zeros((B, 1, d)), x], axis=1) if basepoint else x
+        assert_levels_close(host(out.detach()), orc.signature(full, N), d, N, dtype)
+        want = orc.signature_backward(full, g, N)[:, 1 if basepoint else 0:]
+        err = np.linalg.norm(host(xt.grad) - want) / np.linalg.norm(want)
+        assert err <= (1e-4 if dtype == np.float32 else 1e-9), err
+
+
 def test_gradcheck_through_products_and_initial():
     import torch
     d, N = 2, 3
