@@ -64,6 +64,7 @@ sig_status make_shape(int64_t B, int64_t L, int d, int N, int stream, int basepo
     sh.basepoint = basepoint ? 1 : 0;
     sh.basepoint_value = nullptr;
     sh.chunks = 1;
+    sh.rows_in_stream = 0;
     sh.chunk_len = 0;
     sh.n_inc = basepoint ? L : L - 1;
     // path elements B*L*d and output elements B*[n_inc*]S must stay below kMaxElems
@@ -91,6 +92,7 @@ sig_status make_rows_shape(int64_t rows, int d, int N, sig::Shape &sh)
     sh.stream = sh.basepoint = 0;
     sh.basepoint_value = nullptr;
     sh.chunks = 1;
+    sh.rows_in_stream = 0;
     sh.chunk_len = 0;
     return SIG_OK;
 }
@@ -139,9 +141,9 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
     return Family::None;
 }
 
-// Launches the scan of one kernel family (not Family::None).
-hipError_t launch_family(Family family, const sig::Shape &sh, sig_dtype dtype, const void *path, void *out,
-                         hipStream_t hip_stream)
+// Launches the scan of one kernel family (not Family::None) as the shape stands.
+hipError_t launch_scan(Family family, const sig::Shape &sh, sig_dtype dtype, const void *path, void *out,
+                       hipStream_t hip_stream)
 {
     switch (family) {
         case Family::Mfma:
@@ -169,6 +171,50 @@ hipError_t launch_family(Family family, const sig::Shape &sh, sig_dtype dtype, c
         case Family::None: break;
     }
     return hipErrorNotSupported;
+}
+
+// Stream mode of the small-state and prefix-tree families, into how many chunks a path is cut (1: not at all).  These
+// kernels scan a path in one wavefront or a few threads, so with few paths the chain of increments is all there is to
+// wait for (128 paths of 256 points, d = 8, N = 3: 357 us, 0.2 TB/s).  The scan is a reduction (section 5.1), in stream
+// mode as well: the prefix signatures of a chunk are those of the chunk alone multiplied on the left by the
+// signature of everything before it.
+int stream_chunks(Family family, const sig::Shape &sh)
+{
+    if (!sh.stream || sh.chunks != 1 || (family != Family::Small && family != Family::Tree)) return 1;
+    if (sh.S >= (int64_t(1) << 31)) return 1;
+    // Two scans of n_inc / chunks increments each and a chain of chunks - 1 products (about the cost of an increment
+    // each) are shortest near sqrt(n_inc) chunks; more than ~2048 rows at a time add no parallelism.  Measured at
+    // L = 256, B = 128: 8 chunks take 97 us against 359 at d = 8, N = 3 (4, 16: 146, 94), 57 against 89 at d = 3, N = 5,
+    // 78 against 195 at d = 16, N = 2; at B = 1024 nothing is gained, and below ~128 increments the two extra launches
+    // cost more than the shorter chain saves.
+    if (sh.n_inc < 128) return 1;
+    int chunks = 1;
+    while (int64_t(chunks) * 2 * chunks * 2 <= sh.n_inc && int64_t(chunks) * 2 * sh.B <= 2048) chunks *= 2;
+    return chunks >= 4 ? chunks : 1;
+}
+
+// Launches the scan of one kernel family (not Family::None); few long paths in stream mode are cut into chunks:
+// every chunk's own signature goes to the row of its last increment, a running product along those rows turns them
+// into the path's prefix signatures there (final values), and every chunk is scanned again from the row before it,
+// writing the rows in between.  The output is written once and nothing else is needed for scratch.
+hipError_t launch_family(Family family, const sig::Shape &sh, sig_dtype dtype, const void *path, void *out,
+                         hipStream_t hip_stream)
+{
+    const int chunks = stream_chunks(family, sh);
+    if (chunks <= 1) return launch_scan(family, sh, dtype, path, out, hip_stream);
+    sig::Shape ch = sh;
+    ch.chunks = chunks;
+    ch.chunk_len = (sh.n_inc + chunks - 1) / chunks;
+    ch.B = sh.B * chunks;
+    ch.rows_in_stream = 1;
+    ch.stream = 0;
+    hipError_t err = launch_scan(family, ch, dtype, path, out, hip_stream);
+    if (err != hipSuccess) return err;
+    err = dtype == SIG_F32 ? sig::launch_chunk_prefix_f32(sh, sh.B, sh.n_inc, ch.chunk_len, static_cast<float *>(out), hip_stream)
+                           : sig::launch_chunk_prefix_f64(sh, sh.B, sh.n_inc, ch.chunk_len, static_cast<double *>(out), hip_stream);
+    if (err != hipSuccess) return err;
+    ch.stream = 1;
+    return launch_scan(family, ch, dtype, path, out, hip_stream);
 }
 
 bool valid_enums(sig_dtype dtype, sig_variant variant)

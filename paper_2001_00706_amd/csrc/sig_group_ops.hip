@@ -76,6 +76,116 @@ sig_left_mul_inplace_kernel(Shape sh, const T *__restrict__ a, int64_t group, T 
     }
 }
 
+// Running product along the chunk ends of a stream-mode output [paths][n_inc][S], in place: with e_c the last row
+// of chunk c (chunks of chunk_len rows, the last one shorter), row e_c <- row e_{c-1} [x] row e_c for c = 1, 2, ..
+// in turn.  Coming in, row e_c holds the signature of chunk c alone; going out, that of the path up to and
+// including chunk c (Chen's identity, eq. "grouplike").  One workgroup per path; the product as in the kernel above.
+template <typename T>
+__global__ void __launch_bounds__(256)
+sig_chunk_prefix_kernel(Shape sh, int64_t paths, int64_t n_inc, int64_t chunk_len, T *out)
+{
+    const uint32_t d = uint32_t(sh.d);
+    const int N = sh.N;
+    for (int64_t p = blockIdx.x; p < paths; p += gridDim.x) {
+        T *rows = out + p * n_inc * sh.S;
+        int64_t prev = (chunk_len < n_inc ? chunk_len : n_inc) - 1;
+        for (int64_t start = chunk_len; start < n_inc; start += chunk_len) {
+            const int64_t end = (start + chunk_len < n_inc ? start + chunk_len : n_inc) - 1;
+            const T *ap = rows + prev * sh.S;
+            T *bp = rows + end * sh.S;
+            for (int k = N; k >= 1; --k) {
+                const uint32_t n_k = uint32_t(sh.pw[k]), off_k = uint32_t(sh.off[k]);
+                for (uint32_t idx = threadIdx.x; idx < n_k; idx += blockDim.x) {
+                    T acc = ap[off_k + idx] + bp[off_k + idx];
+                    uint32_t prefix = idx, suffix = 0, scale = 1;
+                    for (int j = k - 1; j >= 1; --j) {
+                        const uint32_t letter = prefix % d;
+                        prefix /= d;
+                        suffix += letter * scale;
+                        scale *= d;
+                        acc += ap[uint32_t(sh.off[j]) + prefix] * bp[uint32_t(sh.off[k - j]) + suffix];
+                    }
+                    bp[off_k + idx] = acc;
+                }
+                __syncthreads();   // also makes this row visible to the threads that read it as the next left factor
+            }
+            prev = end;
+        }
+    }
+}
+
+// The same with the running product kept in LDS (signatures of at most kPrefixLdsWords scalars): the chain from one
+// chunk end to the next then holds no trip to memory (the next right factor is fetched while the current product is
+// formed) and one barrier pair per product: the product is formed in place over the left factor, levels highest
+// first, which needs no barrier between levels because a level reads only lower levels of the left factor and, of
+// its own level, only the word it then overwrites.
+constexpr int kPrefixPerThread = 32;
+constexpr int kPrefixLdsWords = 256 * kPrefixPerThread;
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+sig_chunk_prefix_lds_kernel(Shape sh, int64_t paths, int64_t n_inc, int64_t chunk_len, T *out)
+{
+    extern __shared__ __align__(16) unsigned char prefix_smem[];
+    const uint32_t S = uint32_t(sh.S), d = uint32_t(sh.d);
+    const int N = sh.N;
+    T *A = reinterpret_cast<T *>(prefix_smem);   // the product so far
+    T *R = A + S;                                // the right factor: the signature of the current chunk alone
+    const uint32_t tid = threadIdx.x;
+    for (int64_t p = blockIdx.x; p < paths; p += gridDim.x) {
+        T *rows = out + p * n_inc * sh.S;
+        const int64_t first_end = (chunk_len < n_inc ? chunk_len : n_inc) - 1;
+        for (uint32_t i = tid; i < S; i += 256) A[i] = rows[first_end * sh.S + i];
+        T next[kPrefixPerThread];
+        auto fetch = [&](int64_t start) {
+            if (start >= n_inc) return;
+            const T *src = rows + ((start + chunk_len < n_inc ? start + chunk_len : n_inc) - 1) * sh.S;
+#pragma unroll
+            for (int j = 0; j < kPrefixPerThread; ++j)
+                if (tid + 256u * j < S) next[j] = src[tid + 256u * j];
+        };
+        fetch(chunk_len);
+        for (int64_t start = chunk_len; start < n_inc; start += chunk_len) {
+            T *dst = rows + ((start + chunk_len < n_inc ? start + chunk_len : n_inc) - 1) * sh.S;
+#pragma unroll
+            for (int j = 0; j < kPrefixPerThread; ++j)
+                if (tid + 256u * j < S) R[tid + 256u * j] = next[j];
+            fetch(start + chunk_len);
+            __syncthreads();
+            for (int k = N; k >= 1; --k) {
+                const uint32_t n_k = uint32_t(sh.pw[k]), off_k = uint32_t(sh.off[k]);
+                for (uint32_t idx = tid; idx < n_k; idx += 256) {
+                    T acc = A[off_k + idx] + R[off_k + idx];
+                    uint32_t prefix = idx, suffix = 0, scale = 1;
+                    for (int j = k - 1; j >= 1; --j) {
+                        const uint32_t letter = prefix % d;
+                        prefix /= d;
+                        suffix += letter * scale;
+                        scale *= d;
+                        acc += A[uint32_t(sh.off[j]) + prefix] * R[uint32_t(sh.off[k - j]) + suffix];
+                    }
+                    A[off_k + idx] = acc;
+                    dst[off_k + idx] = acc;
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+template <typename T>
+hipError_t launch_chunk_prefix(const Shape &sh, int64_t paths, int64_t n_inc, int64_t chunk_len, T *out, hipStream_t st)
+{
+    const unsigned grid = unsigned(paths < (int64_t(1) << 20) ? paths : (int64_t(1) << 20));
+    const size_t lds = 2 * size_t(sh.S) * sizeof(T);
+    if (sh.S <= kPrefixLdsWords && lds <= 64 * 1024) {
+        hipLaunchKernelGGL((sig_chunk_prefix_lds_kernel<T>), dim3(grid), dim3(256), lds, st, sh, paths, n_inc, chunk_len, out);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL((sig_chunk_prefix_kernel<T>), dim3(grid), dim3(256), 0, st, sh, paths, n_inc, chunk_len, out);
+    return hipGetLastError();
+}
+
 template <typename T>
 hipError_t launch_invert(const Shape &sh, const T *in, T *out, hipStream_t st)
 {
@@ -97,6 +207,14 @@ hipError_t launch_left_mul(const Shape &sh, const T *a, int64_t group, T *out, h
 
 hipError_t launch_invert_f32(const Shape &sh, const float *in, float *out, hipStream_t st) { return launch_invert(sh, in, out, st); }
 hipError_t launch_invert_f64(const Shape &sh, const double *in, double *out, hipStream_t st) { return launch_invert(sh, in, out, st); }
+hipError_t launch_chunk_prefix_f32(const Shape &sh, int64_t paths, int64_t n_inc, int64_t chunk_len, float *out, hipStream_t st)
+{
+    return launch_chunk_prefix(sh, paths, n_inc, chunk_len, out, st);
+}
+hipError_t launch_chunk_prefix_f64(const Shape &sh, int64_t paths, int64_t n_inc, int64_t chunk_len, double *out, hipStream_t st)
+{
+    return launch_chunk_prefix(sh, paths, n_inc, chunk_len, out, st);
+}
 hipError_t launch_left_mul_f32(const Shape &sh, const float *a, int64_t group, float *out, hipStream_t st)
 {
     return launch_left_mul(sh, a, group, out, st);

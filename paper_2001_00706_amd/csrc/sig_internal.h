@@ -23,6 +23,11 @@ struct Shape {
     // basepoint_value is indexed by path.  chunks == 1: B counts paths.
     int chunks;
     int64_t chunk_len;
+    // Chunked scans whose rows live inside a stream-mode output [paths][n_inc][S] (served by the small-state and the
+    // prefix-tree families only): with stream == 0 a chunk that has increments writes its signature to the row of its
+    // last increment; with stream != 0 a chunk starts from the row before its first increment (the empty signature
+    // at the start of a path) and writes the row of every increment of its own but the last.  0: rows are packed.
+    int rows_in_stream;
     int64_t pw[SIG_MAX_DEPTH + 1];   // pw[k] = d^k, k = 0..N
     int64_t off[SIG_MAX_DEPTH + 2];  // off[k] = offset of level k (1-based) in a signature; off[N+1] = S
 };
@@ -62,6 +67,10 @@ hipError_t launch_combine_f64(const Shape &sh, const double *a, const double *b,
 // left in place: out[r] <- a[r / group] [x] out[r] for sh.B rows.  Both need S < 2^31.
 hipError_t launch_invert_f32(const Shape &sh, const float *in, float *out, hipStream_t st);
 hipError_t launch_invert_f64(const Shape &sh, const double *in, double *out, hipStream_t st);
+// Running product along the chunk ends of a stream-mode output [paths][n_inc][S], in place (sh: d, N and the level
+// tables): the last row of every chunk of chunk_len rows is multiplied on the left by the last row of the chunk before.
+hipError_t launch_chunk_prefix_f32(const Shape &sh, int64_t paths, int64_t n_inc, int64_t chunk_len, float *out, hipStream_t st);
+hipError_t launch_chunk_prefix_f64(const Shape &sh, int64_t paths, int64_t n_inc, int64_t chunk_len, double *out, hipStream_t st);
 hipError_t launch_left_mul_f32(const Shape &sh, const float *a, int64_t group, float *out, hipStream_t st);
 hipError_t launch_left_mul_f64(const Shape &sh, const double *a, int64_t group, double *out, hipStream_t st);
 

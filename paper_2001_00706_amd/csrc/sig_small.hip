@@ -69,8 +69,12 @@ sig_small_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
         const int64_t n_inc = cv.n;
         const T *x = path + cv.path * sh.L * d;
         const T *bpv = static_cast<const T *>(sh.basepoint_value);
-        T *o = out + b * (sh.stream ? sh.n_inc * int64_t(S) : int64_t(S));
-        for (int i = lane; i <= S; i += 64) st[i] = T(0);
+        // rows of a stream-mode output when the chunks are laid out there: o is then the row of the first increment
+        const int64_t first_row = cv.path * sh.n_inc + cv.inc0;
+        T *o = out + (sh.rows_in_stream ? first_row : sh.stream ? b * sh.n_inc : b) * int64_t(S);
+        const bool resume = sh.rows_in_stream && sh.stream && cv.inc0 > 0 && n_inc > 0;
+        for (int i = lane; i <= S; i += 64) st[i] = resume && i < S ? o[i - S] : T(0);   // o - S: the row before
+        const int64_t n_rows = sh.rows_in_stream ? n_inc - 1 : n_inc;   // a chunk's last row holds its value already
 
         for (int64_t t0 = 0; t0 < n_inc; t0 += kSmallTile) {
             const int nt = int(n_inc - t0 < kSmallTile ? n_inc - t0 : kSmallTile);
@@ -115,14 +119,14 @@ sig_small_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
                     const int wi = lane + 64 * j;
                     if (wi < S) {
                         st[wi] = fresh[j];
-                        if (sh.stream) o[(t0 + s) * S + wi] = fresh[j];
+                        if (sh.stream && t0 + s < n_rows) o[(t0 + s) * S + wi] = fresh[j];
                     }
                 }
                 __syncthreads();
             }
         }
-        if (!sh.stream)
-            for (int i = lane; i < S; i += 64) o[i] = st[i];
+        if (!sh.stream && !(sh.rows_in_stream && n_inc == 0))
+            for (int i = lane; i < S; i += 64) o[(sh.rows_in_stream ? (n_inc - 1) * int64_t(S) : 0) + i] = st[i];
         __syncthreads();
     }
 }

@@ -97,6 +97,26 @@ sig_tree_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
             n_max = cv.n > n_max ? cv.n : n_max;
         }
     const T *bpv = static_cast<const T *>(sh.basepoint_value);
+    // chunks laid out in a stream-mode output: this thread's chunk, and the rows it reads and writes
+    const ChunkView mine = chunk_view(live ? row : 0, sh.chunks, sh.chunk_len, sh.n_inc);
+    const int64_t first_row = mine.path * sh.n_inc + mine.inc0;   // the row of the chunk's first increment
+    if (sh.rows_in_stream && sh.stream && live && mine.inc0 > 0 && mine.n > 0) {
+        const T *o = out + (first_row - 1) * TS::kS;   // the signature of everything before the chunk
+        int64_t q = u;
+#pragma unroll
+        for (int i = P; i >= 1; --i) {
+            A[i] = o[tree_off(D, i) + q];
+            q /= D;
+        }
+        if constexpr (U >= 1) {
+#pragma unroll
+            for (int c = 0; c < D; ++c) B1[c] = o[tree_off(D, P + 1) + u * D + c];
+        }
+        if constexpr (U >= 2) {
+#pragma unroll
+            for (int c = 0; c < D * D; ++c) B2[c] = o[tree_off(D, P + 2) + u * (D * D) + c];
+        }
+    }
 
     // this thread's words of one signature; a prefix is written by the first thread below it
     auto store = [&](T *o) {
@@ -170,12 +190,22 @@ sig_tree_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
                     }
                 }
             }
-            // stream mode (never chunked: every row has all n_max = n_inc increments): the signature so far
-            if (sh.stream && live) store(out + (row * sh.n_inc + t0 + s) * TS::kS);
+            // stream mode: the signature so far (a chunk leaves out its last row, which holds its final value already)
+            if (sh.stream && live) {
+                if (!sh.rows_in_stream)
+                    store(out + (row * sh.n_inc + t0 + s) * TS::kS);
+                else if (t0 + s + 1 < mine.n)
+                    store(out + (first_row + t0 + s) * TS::kS);
+            }
         }
     }
 
-    if (live && !sh.stream) store(out + row * TS::kS);
+    if (live && !sh.stream) {
+        if (!sh.rows_in_stream)
+            store(out + row * TS::kS);
+        else if (mine.n > 0)
+            store(out + (first_row + mine.n - 1) * TS::kS);
+    }
 }
 
 template <typename T, int D, int N>

@@ -479,6 +479,45 @@ def test_chunked_scan_argument_checks():
         sig.sig_forward_chunked(x, 4, 4, workspace=torch.empty(need - 4, dtype=torch.uint8, device="cuda:0"))
 
 
+# ------------------------------------------------------------------ stream mode cut into chunks
+# From 128 increments on (and up to 512 paths) the small-state and prefix-tree families cut a stream-mode scan into
+# chunks: chunk signatures at the chunk ends, a running product along them, every chunk scanned again from the row
+# before it.  Shapes: several paths per workgroup (d = 3, 8, 6), several workgroups per path (d = 5, N = 6), one level
+# below a thread's word (d = 12), the one-wavefront kernel (d = 2, 3, 20); lengths that leave a ragged last chunk, a
+# last chunk of one increment (n_inc = 129 in 4 chunks of 33) and many chunks (n_inc = 1100: 16 chunks).
+@pytest.mark.parametrize("B,L,d,N", [
+    (3, 130, 3, 5), (2, 257, 8, 3), (5, 200, 6, 3), (1, 130, 5, 6), (2, 140, 12, 3), (3, 1101, 3, 4), (17, 129, 7, 2),
+    (4, 130, 2, 5), (2, 300, 3, 3), (3, 129, 20, 1), (2, 513, 2, 8),
+])
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_stream_mode_cut_into_chunks(B, L, d, N, dtype):
+    x = (brownian_paths(B, L, d, seed=L + d + N) + 0.1).astype(dtype)
+    for basepoint in (False, True):
+        got = check(x, N, stream=True, basepoint=basepoint)
+        assert got is not None
+        # the last prefix signature is the signature of the whole path, which the final-mode call computes unchunked
+        final = gpu_signature(x, N, False, basepoint, sig.SIG_VARIANT_AUTO)
+        batch, _ = level_errors(got[:, -1], final.astype(np.float64), d, N)
+        assert np.all(batch <= 10 * TOL[dtype])
+
+
+def test_chunked_stream_with_initial_and_inverse():
+    # what follows the scan works on the rows in place, whichever way they were produced
+    import torch
+    B, L, d, N = 2, 200, 3, 4
+    x = brownian_paths(B, L, d, seed=77).astype(np.float64)
+    y = brownian_paths(B, 9, d, seed=78).astype(np.float64)
+    y += x[:, :1] - y[:, -1:]
+    initial = orc.signature(y, N)
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    got = sig.sig_signature(to_dev(x), N, stream=True, initial=to_dev(initial), inverse=True)
+    torch.cuda.synchronize()
+    whole = np.concatenate([y, x[:, 1:]], axis=1)
+    for j in (0, 57, L - 2):
+        want = orc.signature(whole[:, :9 + j + 1][:, ::-1], N)   # inverse = the signature of the reversed path
+        np.testing.assert_allclose(got[:, j].cpu().numpy(), want, rtol=1e-9, atol=1e-12)
+
+
 # ------------------------------------------------------------------ prefix-tree family
 @pytest.mark.parametrize("B,L,d,N", [
     (3, 9, 7, 7),      # 16 807 words per path over 66 workgroups; 960 799 scalars per signature
