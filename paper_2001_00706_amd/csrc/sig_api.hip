@@ -127,7 +127,10 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
             if (d8_ok && !(sh.N <= 5 && sh.B >= 512 && tree_ok)) return Family::MfmaD8;
             // up to 128 scalars (two words per lane) the one-wavefront kernel wins; beyond, its lanes carry 4 or 8
             // words each and the prefix-tree kernel is up to 6 times faster (d = 2, N = 8: 38 us against 194)
-            if (small_ok && (sh.S <= 128 || !tree_ok)) return Family::Small;
+            // (in stream mode up to depth 3 as well: its lanes store 64 consecutive scalars per instruction, the
+            // prefix-tree kernel's lanes store d^2 scalars apart: d = 16, N = 2: 52 us against 75, d = 7, N = 3: 67 against 85
+            // at 128 paths of 256 points)
+            if (small_ok && (sh.S <= 128 || !tree_ok || (sh.stream && sh.N <= 3))) return Family::Small;
             if (tree_ok) return Family::Tree;
             return generic_ok ? Family::Generic : Family::None;
         case SIG_VARIANT_GENERIC: return generic_ok ? Family::Generic : Family::None;
