@@ -97,7 +97,7 @@ sig_status make_rows_shape(int64_t rows, int d, int N, sig::Shape &sh)
     return SIG_OK;
 }
 
-enum class Family { Generic, Mfma, MfmaShard, MfmaStream, MfmaD16, MfmaD8, Small, Tree, None };
+enum class Family { Generic, Mfma, MfmaShard, MfmaStream, MfmaD16, MfmaD8, Small, Tree, RowStream, None };
 
 // The pointers decide only alignment: the matrix-core family loads and stores 16 bytes per lane.
 Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const void *path, const void *out)
@@ -112,6 +112,7 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
     const bool generic_ok = sig::generic_supported(sh, dtype);
     const bool small_ok = sig::small_supported(sh);
     const bool tree_ok = sig::tree_supported(sh);
+    const bool rows_ok = sh.stream && sig::row_stream_supported(sh, dtype);
     switch (variant) {
         case SIG_VARIANT_AUTO:
             // four wavefronts per path when one per path would leave most of the chip idle, when every
@@ -125,6 +126,8 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
             // 64 wavefronts per path pay off while paths are few; from 512 paths on each shard's own prefix sums
             // are pure overhead (N = 4 at B = 2048: 170 us against 62 for the prefix-tree kernel); N = 6 stays
             if (d8_ok && !(sh.N <= 5 && sh.B >= 512 && tree_ok)) return Family::MfmaD8;
+            // every prefix stored: a wavefront per row with whole-row stores, wherever it applies
+            if (rows_ok) return Family::RowStream;
             // up to 128 scalars (two words per lane) the one-wavefront kernel wins; beyond, its lanes carry 4 or 8
             // words each and the prefix-tree kernel is up to 6 times faster (d = 2, N = 8: 38 us against 194)
             // (in stream mode up to depth 3 as well: its lanes store 64 consecutive scalars per instruction, the
@@ -140,6 +143,7 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
         case SIG_VARIANT_MFMA_STREAM: return stream_ok ? Family::MfmaStream : Family::None;
         case SIG_VARIANT_SMALL: return small_ok ? Family::Small : Family::None;
         case SIG_VARIANT_TREE: return tree_ok ? Family::Tree : Family::None;
+        case SIG_VARIANT_ROW_STREAM: return rows_ok ? Family::RowStream : Family::None;
     }
     return Family::None;
 }
@@ -163,6 +167,10 @@ hipError_t launch_scan(Family family, const sig::Shape &sh, sig_dtype dtype, con
             return dtype == SIG_F32
                        ? sig::launch_tree_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
                        : sig::launch_tree_f64(sh, static_cast<const double *>(path), static_cast<double *>(out), hip_stream);
+        case Family::RowStream:
+            return dtype == SIG_F32
+                       ? sig::launch_row_stream_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
+                       : sig::launch_row_stream_f64(sh, static_cast<const double *>(path), static_cast<double *>(out), hip_stream);
         case Family::Small:
             return dtype == SIG_F32
                        ? sig::launch_small_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
@@ -183,7 +191,8 @@ hipError_t launch_scan(Family family, const sig::Shape &sh, sig_dtype dtype, con
 // signature of everything before it.
 int stream_chunks(Family family, const sig::Shape &sh)
 {
-    if (!sh.stream || sh.chunks != 1 || (family != Family::Small && family != Family::Tree)) return 1;
+    if (!sh.stream || sh.chunks != 1 || (family != Family::Small && family != Family::Tree && family != Family::RowStream))
+        return 1;
     if (sh.S >= (int64_t(1) << 31)) return 1;
     // Two scans of n_inc / chunks increments each and a chain of chunks - 1 products (about the cost of an increment
     // each) are shortest near sqrt(n_inc) chunks; more than ~2048 rows at a time add no parallelism.  Measured at
@@ -225,7 +234,7 @@ bool valid_enums(sig_dtype dtype, sig_variant variant)
     return (dtype == SIG_F32 || dtype == SIG_F64) &&
            (variant == SIG_VARIANT_AUTO || variant == SIG_VARIANT_GENERIC || variant == SIG_VARIANT_MFMA ||
             variant == SIG_VARIANT_MFMA_SHARD || variant == SIG_VARIANT_SMALL || variant == SIG_VARIANT_TREE ||
-            variant == SIG_VARIANT_MFMA_STREAM);
+            variant == SIG_VARIANT_MFMA_STREAM || variant == SIG_VARIANT_ROW_STREAM);
 }
 
 }  // namespace
@@ -784,6 +793,7 @@ const char *sig_variant_name(int64_t B, int64_t L, int d, int N, int stream, int
         case Family::MfmaD8: return sig::mfma_d8_kernel_name(sh);
         case Family::Small: return "small";
         case Family::Tree: return "tree";
+        case Family::RowStream: return "row_stream";
         case Family::Generic: return "generic";
         case Family::None: break;
     }

@@ -116,9 +116,22 @@ sig_chunk_prefix_kernel(Shape sh, int64_t paths, int64_t n_inc, int64_t chunk_le
 
 // The same with the running product kept in LDS (signatures of at most kPrefixLdsWords scalars): the chain from one
 // chunk end to the next then holds no trip to memory (the next right factor is fetched while the current product is
-// formed) and one barrier pair per product: the product is formed in place over the left factor, levels highest
-// first, which needs no barrier between levels because a level reads only lower levels of the left factor and, of
-// its own level, only the word it then overwrites.
+// formed) and two barriers per product.  A product is written to a buffer of its own (two buffers take turns as
+// left factor and result), so its levels need no barrier between them.
+// A workgroup barrier that orders the LDS traffic only: __syncthreads() would also wait for the global loads and
+// stores in flight (the next right factor on its way in, the last product on its way out), which is the latency
+// this kernel is built to keep off the chain.
+__device__ __forceinline__ void prefix_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// n / d for n < 2^16 and 2 <= d <= 64 with magic = ceil(2^32 / d): the excess n (magic d - 2^32) / (d 2^32) stays
+// below n / 2^32 < 1 / d, so it never carries into the quotient.
+__device__ __forceinline__ uint32_t prefix_div(uint32_t n, uint32_t magic) { return __umulhi(n, magic); }
+
 constexpr int kPrefixPerThread = 32;
 constexpr int kPrefixLdsWords = 256 * kPrefixPerThread;
 
@@ -129,8 +142,22 @@ sig_chunk_prefix_lds_kernel(Shape sh, int64_t paths, int64_t n_inc, int64_t chun
     extern __shared__ __align__(16) unsigned char prefix_smem[];
     const uint32_t S = uint32_t(sh.S), d = uint32_t(sh.d);
     const int N = sh.N;
-    T *A = reinterpret_cast<T *>(prefix_smem);   // the product so far
-    T *R = A + S;                                // the right factor: the signature of the current chunk alone
+    const uint32_t magic = uint32_t(((uint64_t(1) << 32) + d - 1) / d);   // level sizes here stay below 2^16
+    // the level tables where a run-time index costs an LDS read (indexing the kernel argument would go through scratch)
+    __shared__ uint32_t lv_off[SIG_MAX_DEPTH + 2], lv_size[SIG_MAX_DEPTH + 2];
+    if (threadIdx.x >= 1 && threadIdx.x <= uint32_t(N) + 1) {   // level t: d^t words after d + .. + d^(t-1) others
+        uint32_t size = d, before = 0;
+        for (uint32_t t = 1; t < threadIdx.x; ++t) {
+            before += size;
+            size *= d;
+        }
+        lv_off[threadIdx.x] = before;
+        lv_size[threadIdx.x] = size;
+    }
+    __syncthreads();
+    T *A = reinterpret_cast<T *>(prefix_smem);   // the product so far,
+    T *C = A + S;                                // the product being formed (the two swap after every product),
+    T *R = C + S;                                // the right factor: the signature of the current chunk alone
     const uint32_t tid = threadIdx.x;
     for (int64_t p = blockIdx.x; p < paths; p += gridDim.x) {
         T *rows = out + p * n_inc * sh.S;
@@ -141,8 +168,8 @@ sig_chunk_prefix_lds_kernel(Shape sh, int64_t paths, int64_t n_inc, int64_t chun
             if (start >= n_inc) return;
             const T *src = rows + ((start + chunk_len < n_inc ? start + chunk_len : n_inc) - 1) * sh.S;
 #pragma unroll
-            for (int j = 0; j < kPrefixPerThread; ++j)
-                if (tid + 256u * j < S) next[j] = src[tid + 256u * j];
+            for (int j = 0; j < kPrefixPerThread; ++j)   // unconditional, on a clamped index: the loads stay in flight together
+                if (256u * j < S) next[j] = src[tid + 256u * j < S ? tid + 256u * j : S - 1];
         };
         fetch(chunk_len);
         for (int64_t start = chunk_len; start < n_inc; start += chunk_len) {
@@ -151,33 +178,255 @@ sig_chunk_prefix_lds_kernel(Shape sh, int64_t paths, int64_t n_inc, int64_t chun
             for (int j = 0; j < kPrefixPerThread; ++j)
                 if (tid + 256u * j < S) R[tid + 256u * j] = next[j];
             fetch(start + chunk_len);
-            __syncthreads();
+            prefix_lds_barrier();
             for (int k = N; k >= 1; --k) {
-                const uint32_t n_k = uint32_t(sh.pw[k]), off_k = uint32_t(sh.off[k]);
+                const uint32_t n_k = lv_size[k], off_k = lv_off[k];
                 for (uint32_t idx = tid; idx < n_k; idx += 256) {
                     T acc = A[off_k + idx] + R[off_k + idx];
                     uint32_t prefix = idx, suffix = 0, scale = 1;
                     for (int j = k - 1; j >= 1; --j) {
-                        const uint32_t letter = prefix % d;
-                        prefix /= d;
+                        const uint32_t q = prefix_div(prefix, magic);
+                        const uint32_t letter = prefix - q * d;
+                        prefix = q;
                         suffix += letter * scale;
                         scale *= d;
-                        acc += A[uint32_t(sh.off[j]) + prefix] * R[uint32_t(sh.off[k - j]) + suffix];
+                        acc += A[lv_off[j] + prefix] * R[lv_off[k - j] + suffix];
                     }
-                    A[off_k + idx] = acc;
+                    C[off_k + idx] = acc;
                     dst[off_k + idx] = acc;
                 }
             }
-            __syncthreads();
+            prefix_lds_barrier();
+            T *swap = A;
+            A = C;
+            C = swap;
+        }
+        __syncthreads();   // the next path's first row overwrites a buffer that may still be read
+    }
+}
+
+// The same with every chunk signature of the path brought into LDS at once (one trip to memory for the whole chain):
+// for paths whose chunk signatures fit together.
+template <typename T>
+__global__ void __launch_bounds__(256)
+sig_chunk_prefix_all_kernel(Shape sh, int64_t paths, int64_t n_inc, int64_t chunk_len, int n_chunks, T *out)
+{
+    extern __shared__ __align__(16) unsigned char prefix_smem[];
+    const uint32_t S = uint32_t(sh.S), d = uint32_t(sh.d);
+    const int N = sh.N;
+    const uint32_t magic = uint32_t(((uint64_t(1) << 32) + d - 1) / d);   // level sizes here stay below 2^16
+    // the level tables where a run-time index costs an LDS read (indexing the kernel argument would go through scratch)
+    __shared__ uint32_t lv_off[SIG_MAX_DEPTH + 2], lv_size[SIG_MAX_DEPTH + 2];
+    if (threadIdx.x >= 1 && threadIdx.x <= uint32_t(N) + 1) {   // level t: d^t words after d + .. + d^(t-1) others
+        uint32_t size = d, before = 0;
+        for (uint32_t t = 1; t < threadIdx.x; ++t) {
+            before += size;
+            size *= d;
+        }
+        lv_off[threadIdx.x] = before;
+        lv_size[threadIdx.x] = size;
+    }
+    __syncthreads();
+    T *all = reinterpret_cast<T *>(prefix_smem);   // chunk c at all + c * S, one spare signature behind them: the
+                                                   // product so far and the product being formed take turns in chunk
+                                                   // 0's place and the spare, so the levels of a product need no barrier
+    const uint32_t tid = threadIdx.x;
+    for (int64_t p = blockIdx.x; p < paths; p += gridDim.x) {
+        T *rows = out + p * n_inc * sh.S;
+        {
+            // scalar e of the chunk signatures laid end to end is scalar i of chunk c; eight loads in flight per thread
+            // (every one of them unconditional, on a clamped index: a load under a branch would be waited for there)
+            const uint32_t total = uint32_t(n_chunks) * S;
+            const uint32_t magic_s = uint32_t(((uint64_t(1) << 32) + S - 1) / S);   // total < 2^16
+            for (uint32_t e0 = tid; e0 < total; e0 += 256 * 8) {
+                T v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t e = e0 + 256u * j < total ? e0 + 256u * j : total - 1;
+                    const uint32_t c = prefix_div(e, magic_s), i = e - c * S;
+                    const int64_t end = ((int64_t(c) + 1) * chunk_len < n_inc ? (int64_t(c) + 1) * chunk_len : n_inc) - 1;
+                    v[j] = rows[end * sh.S + i];
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (e0 + 256u * j < total) all[e0 + 256u * j] = v[j];
+            }
+        }
+        __syncthreads();
+        T *A = all, *C = all + uint32_t(n_chunks) * S;
+        for (int c = 1; c < n_chunks; ++c) {
+            const T *R = all + uint32_t(c) * S;
+            T *dst = rows + (((c + 1) * chunk_len < n_inc ? (c + 1) * chunk_len : n_inc) - 1) * sh.S;
+            for (int k = N; k >= 1; --k) {
+                const uint32_t n_k = lv_size[k], off_k = lv_off[k];
+                for (uint32_t idx = tid; idx < n_k; idx += 256) {
+                    T acc = A[off_k + idx] + R[off_k + idx];
+                    uint32_t prefix = idx, suffix = 0, scale = 1;
+                    for (int j = k - 1; j >= 1; --j) {
+                        const uint32_t q = prefix_div(prefix, magic);
+                        const uint32_t letter = prefix - q * d;
+                        prefix = q;
+                        suffix += letter * scale;
+                        scale *= d;
+                        acc += A[lv_off[j] + prefix] * R[lv_off[k - j] + suffix];
+                    }
+                    C[off_k + idx] = acc;
+                    dst[off_k + idx] = acc;
+                }
+            }
+            prefix_lds_barrier();
+            T *swap = A;
+            A = C;
+            C = swap;
+        }
+        __syncthreads();   // the next path's loads overwrite the chunk signatures
+    }
+}
+
+
+
+// The same for signatures of at most 1024 scalars, with everything that does not depend on the data taken out of the
+// chain: a thread owns up to four words, and which scalars of the two factors make up each of them (N - 1 pairs of
+// LDS indices per word, pointing at a zero kept behind every signature where a word has fewer terms) is worked out
+// once, into registers.  A product is then one batch of independent LDS reads and multiply-adds: one LDS latency
+// instead of one per term.  NT = N - 1.
+constexpr int kPrefixSmallWords = 1024;
+
+template <typename T, int NT>
+__global__ void __launch_bounds__(256)
+sig_chunk_prefix_small_kernel(Shape sh, int64_t paths, int64_t n_inc, int64_t chunk_len, int n_chunks, T *out)
+{
+    constexpr int W = kPrefixSmallWords / 256;
+    extern __shared__ __align__(16) unsigned char prefix_smem[];
+    const uint32_t S = uint32_t(sh.S), d = uint32_t(sh.d);
+    const uint32_t row = S + 1;                        // a signature and a zero behind it
+    T *X = reinterpret_cast<T *>(prefix_smem);         // chunk c at X + c * row, one spare row behind them: the product
+                                                       // so far and the product being formed take turns in chunk 0's
+                                                       // place and the spare
+    const uint32_t tid = threadIdx.x;
+    const uint32_t magic = uint32_t(((uint64_t(1) << 32) + d - 1) / d);
+    const uint32_t magic_s = uint32_t(((uint64_t(1) << 32) + S - 1) / S);
+    uint32_t own[W], term[W][NT > 0 ? NT : 1];
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+        const uint32_t i = tid + 256u * w;
+        own[w] = i < S ? i : S;
+        uint32_t k = 1, before = 0, size = d;
+        while (i < S && i >= before + size) {   // the level of word i
+            before += size;
+            size *= d;
+            ++k;
+        }
+        // peel letters off the end of the word: prefix w_1..w_j (level j) and suffix w_{j+1}..w_k (level k - j)
+        uint32_t prefix = i - before, suffix = 0, scale = 1, suf_size = 1, suf_off = 0;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            uint32_t entry = (S << 16) | S;   // no such term: zero times zero
+            if (i < S && uint32_t(t) + 1 < k) {
+                const uint32_t q = prefix_div(prefix, magic);
+                suffix += (prefix - q * d) * scale;
+                prefix = q;
+                scale *= d;
+                suf_size *= d;                      // d^(t+1); suf_off is the offset of level t + 1
+                uint32_t pre_off = 0, pre_size = d;   // offset of level k - 1 - t
+                for (uint32_t l = 1; l + 1 + uint32_t(t) < k; ++l) {
+                    pre_off += pre_size;
+                    pre_size *= d;
+                }
+                entry = ((pre_off + prefix) << 16) | (suf_off + suffix);
+                suf_off += suf_size;
+            }
+            term[w][t] = entry;
         }
     }
+    for (int64_t p = blockIdx.x; p < paths; p += gridDim.x) {
+        T *rows = out + p * n_inc * sh.S;
+        const uint32_t total = uint32_t(n_chunks) * S;
+        for (uint32_t e0 = tid; e0 < total; e0 += 256 * 8) {
+            T v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {   // unconditional loads on a clamped index: all in flight together
+                const uint32_t e = e0 + 256u * j < total ? e0 + 256u * j : total - 1;
+                const uint32_t c = prefix_div(e, magic_s), i = e - c * S;
+                const int64_t end = ((int64_t(c) + 1) * chunk_len < n_inc ? (int64_t(c) + 1) * chunk_len : n_inc) - 1;
+                v[j] = rows[end * sh.S + i];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t e = e0 + 256u * j;
+                if (e < total) {
+                    const uint32_t c = prefix_div(e, magic_s);
+                    X[c * row + (e - c * S)] = v[j];
+                }
+            }
+        }
+        if (tid <= uint32_t(n_chunks)) X[tid * row + S] = T(0);
+        __syncthreads();
+        T *A = X, *C = X + uint32_t(n_chunks) * row;
+        for (int c = 1; c < n_chunks; ++c) {
+            const T *R = X + uint32_t(c) * row;
+            T *dst = rows + (((int64_t(c) + 1) * chunk_len < n_inc ? (int64_t(c) + 1) * chunk_len : n_inc) - 1) * sh.S;
+            T acc[W];
+#pragma unroll
+            for (int w = 0; w < W; ++w) acc[w] = A[own[w]] + R[own[w]];
+#pragma unroll
+            for (int w = 0; w < W; ++w)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[w] += A[term[w][t] >> 16] * R[term[w][t] & 0xffffu];
+#pragma unroll
+            for (int w = 0; w < W; ++w)
+                if (tid + 256u * w < S) {
+                    C[own[w]] = acc[w];
+                    dst[own[w]] = acc[w];
+                }
+            prefix_lds_barrier();
+            T *swap = A;
+            A = C;
+            C = swap;
+        }
+        __syncthreads();   // the next path's loads overwrite the chunk signatures
+    }
+}
+
+template <typename T>
+hipError_t launch_chunk_prefix_small(const Shape &sh, int64_t paths, int64_t n_inc, int64_t chunk_len, int n_chunks, T *out,
+                                     unsigned grid, size_t lds, hipStream_t st)
+{
+    switch (sh.N) {
+#define SIG_PREFIX_SMALL_CASE(n)                                                                                        \
+    case n:                                                                                                             \
+        hipLaunchKernelGGL((sig_chunk_prefix_small_kernel<T, n - 1>), dim3(grid), dim3(256), lds, st, sh, paths, n_inc,    \
+                           chunk_len, n_chunks, out);                                                                   \
+        return hipGetLastError();
+        SIG_PREFIX_SMALL_CASE(1)
+        SIG_PREFIX_SMALL_CASE(2)
+        SIG_PREFIX_SMALL_CASE(3)
+        SIG_PREFIX_SMALL_CASE(4)
+        SIG_PREFIX_SMALL_CASE(5)
+        SIG_PREFIX_SMALL_CASE(6)
+        SIG_PREFIX_SMALL_CASE(7)
+        SIG_PREFIX_SMALL_CASE(8)
+        SIG_PREFIX_SMALL_CASE(9)
+#undef SIG_PREFIX_SMALL_CASE
+    }
+    return hipErrorNotSupported;
 }
 
 template <typename T>
 hipError_t launch_chunk_prefix(const Shape &sh, int64_t paths, int64_t n_inc, int64_t chunk_len, T *out, hipStream_t st)
 {
     const unsigned grid = unsigned(paths < (int64_t(1) << 20) ? paths : (int64_t(1) << 20));
-    const size_t lds = 2 * size_t(sh.S) * sizeof(T);
+    const int64_t n_chunks = (n_inc + chunk_len - 1) / chunk_len;
+    const size_t lds_small = size_t(n_chunks + 1) * size_t(sh.S + 1) * sizeof(T);
+    if (sh.S <= kPrefixSmallWords && sh.N <= 9 && sh.d <= 64 && n_chunks <= 255 && n_chunks * sh.S < 65536 && lds_small <= 60 * 1024)
+        return launch_chunk_prefix_small(sh, paths, n_inc, chunk_len, int(n_chunks), out, grid, lds_small, st);
+    const size_t lds_all = size_t(n_chunks + 1) * size_t(sh.S) * sizeof(T);
+    if (n_chunks <= 64 && lds_all <= 60 * 1024) {
+        hipLaunchKernelGGL((sig_chunk_prefix_all_kernel<T>), dim3(grid), dim3(256), lds_all, st, sh, paths, n_inc, chunk_len,
+                           int(n_chunks), out);
+        return hipGetLastError();
+    }
+    const size_t lds = 3 * size_t(sh.S) * sizeof(T);
     if (sh.S <= kPrefixLdsWords && lds <= 64 * 1024) {
         hipLaunchKernelGGL((sig_chunk_prefix_lds_kernel<T>), dim3(grid), dim3(256), lds, st, sh, paths, n_inc, chunk_len, out);
         return hipGetLastError();

@@ -149,6 +149,12 @@ hipError_t launch_tree_wide(const Shape &sh, const double *path, double *out, hi
 hipError_t launch_tree_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_tree_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
 
+// Row-stream family (d = 2..16 with one or two levels below a word of at most 64 per row; see sig_row_stream.hip): stream
+// mode, and both passes of a stream scan cut into chunks (Shape::rows_in_stream); not for plain final mode.
+bool row_stream_supported(const Shape &sh, sig_dtype dtype);
+hipError_t launch_row_stream_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
+hipError_t launch_row_stream_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
+
 // Prefix-tree gradient kernels (d = 2..8 at N = 2..9, d = 9..16 at N = 2..6, any alignment): no communication between threads; the
 // per-increment partial gradients go to a workspace of `tree_backward_workspace_bytes` and are summed by a second
 // kernel.

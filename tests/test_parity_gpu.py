@@ -84,8 +84,8 @@ def check(x, N, stream=False, basepoint=False, variant=sig.SIG_VARIANT_AUTO, sam
 
 
 VARIANTS = [sig.SIG_VARIANT_AUTO, sig.SIG_VARIANT_GENERIC, sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_SHARD,
-            sig.SIG_VARIANT_SMALL, sig.SIG_VARIANT_TREE, sig.SIG_VARIANT_MFMA_STREAM]
-VARIANT_IDS = ["auto", "generic", "mfma", "mfma_shard", "small", "tree", "mfma_stream"]
+            sig.SIG_VARIANT_SMALL, sig.SIG_VARIANT_TREE, sig.SIG_VARIANT_MFMA_STREAM, sig.SIG_VARIANT_ROW_STREAM]
+VARIANT_IDS = ["auto", "generic", "mfma", "mfma_shard", "small", "tree", "mfma_stream", "row_stream"]
 MODES = [(False, False), (False, True), (True, False), (True, True)]     # (stream, basepoint)
 
 
@@ -487,7 +487,7 @@ def test_chunked_scan_argument_checks():
 # last chunk of one increment (n_inc = 129 in 4 chunks of 33) and many chunks (n_inc = 1100: 16 chunks).
 @pytest.mark.parametrize("B,L,d,N", [
     (3, 130, 3, 5), (2, 257, 8, 3), (5, 200, 6, 3), (1, 130, 5, 6), (2, 140, 12, 3), (3, 1101, 3, 4), (17, 129, 7, 2),
-    (4, 130, 2, 5), (2, 300, 3, 3), (3, 129, 20, 1), (2, 513, 2, 8),
+    (4, 130, 2, 5), (2, 300, 3, 3), (3, 129, 20, 1), (2, 513, 2, 8), (4, 130, 2, 3), (2, 200, 8, 4), (3, 131, 16, 2),
 ])
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 def test_stream_mode_cut_into_chunks(B, L, d, N, dtype):
