@@ -15,10 +15,12 @@
  * sum_m i_m d^{k-m} (0-based letters, first letter slowest) — lexicographic word order
  * under the identification of appendix A.2.2.
  *
- * All functions are thread-safe and keep no state between calls.  Nothing here allocates
+ * All functions but one are thread-safe and keep no state between calls.  Nothing here allocates
  * or frees device memory: the calls that need scratch memory (sig_backward, sig_forward_chunked,
- * sig_combine_many, sig_combine_backward, sig_log_backward) take a workspace from the caller,
- * sized by their *_workspace_bytes companions.  Nothing synchronises the device.
+ * sig_combine_many, sig_combine_backward, sig_combine_grouped_backward, sig_log_backward) take a workspace
+ * from the caller, sized by their *_workspace_bytes companions; the exception is
+ * sig_forward_chunked_static, whose scratch is an array inside the library that all its calls on a GPU
+ * share.  Nothing synchronises the device.
  */
 #ifndef SIG_H_
 #define SIG_H_
@@ -109,9 +111,13 @@ int64_t sig_fused_fmas(int d, int N);
  * N > SIG_MAX_DEPTH, L < 2 (L < 1 with basepoint), an unknown dtype; SIG_ERR_OVERFLOW if a
  * size overflows; SIG_ERR_HIP if the launch failed.  B == 0 is SIG_OK and enqueues nothing.
  * Results are deterministic: the same inputs give bit-identical outputs on every call.
- * sig_forward scans every path (or every word-prefix shard of it) from end to end and never splits a path over
- * its length, since it has no workspace for partial results: a few very long paths (B * shards far below the
- * number of compute units, L in the tens of thousands) are served many times faster by sig_forward_chunked. */
+ * In final mode sig_forward scans every path (or every word-prefix shard of it) from end to end and never splits a
+ * path over its length, since it has no workspace for partial results: a few very long paths (B * shards far below
+ * the number of compute units, L in the tens of thousands) are served many times faster by sig_forward_chunked
+ * (sig_forward_chunks_hint says when, and into how many chunks).  In stream mode the output itself has room for
+ * partial results, and up to 512 paths of at least 128 increments are cut into chunks internally where the kernel
+ * family gains from it (everything but the d = 4 matrix-core kernels); the values then differ from an end-to-end
+ * scan by rounding only, and `out` is read as well as written while the call runs. */
 sig_status sig_forward(const void *path, int64_t B, int64_t L, int d, int N,
                        int stream, int basepoint, sig_dtype dtype,
                        void *out, hipStream_t hip_stream);
