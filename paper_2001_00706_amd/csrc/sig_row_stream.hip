@@ -203,15 +203,45 @@ sig_row_stream_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
         for (int j0 = 0; j0 < kPieces; j0 += kBatch) {
             T v[kBatch];
 #pragma unroll
-            for (int j = 0; j < kBatch; ++j) {
+            for (int j = 0; j < kBatch; ++j) {   // unconditional reads (index clamped in the last piece): none waits for a branch
                 const int i = lane + 64 * (j0 + j);
-                if (j0 + j < kPieces && (64 * (j0 + j + 1) <= int(kS) || i < int(kS))) v[j] = src[rs_skew<T, D, N>(i)];
+                if (j0 + j < kPieces) v[j] = src[rs_skew<T, D, N>(64 * (j0 + j + 1) <= int(kS) || i < int(kS) ? i : int(kS) - 1)];
             }
 #pragma unroll
             for (int j = 0; j < kBatch; ++j) {
                 const int i = lane + 64 * (j0 + j);
                 if (j0 + j < kPieces && (64 * (j0 + j + 1) <= int(kS) || i < int(kS))) dst[i] = v[j];
             }
+        }
+    };
+
+    // the rows of stream position `step` of every slot that has one: all LDS reads first, so that a wavefront with
+    // several short rows waits for the LDS once per increment, not once per row
+    constexpr int kPiecesAll = int((kS + 63) / 64);
+    auto copy_step = [&](int step) {
+        if constexpr (R > 1 && R * kPiecesAll <= 48) {
+            T v[R][kPiecesAll];
+#pragma unroll
+            for (int p = 0; p < R; ++p)
+#pragma unroll
+                for (int j = 0; j < kPiecesAll; ++j) {
+                    const int i = lane + 64 * j;
+                    v[p][j] = stage[p * kStageRow + rs_skew<T, D, N>(64 * (j + 1) <= int(kS) || i < int(kS) ? i : int(kS) - 1)];
+                }
+#pragma unroll
+            for (int p = 0; p < R; ++p)
+                if (step < write_of[p]) {
+                    T *dst = out + (first_of[p] + step) * kS;
+#pragma unroll
+                    for (int j = 0; j < kPiecesAll; ++j) {
+                        const int i = lane + 64 * j;
+                        if (64 * (j + 1) <= int(kS) || i < int(kS)) dst[i] = v[p][j];
+                    }
+                }
+        } else {
+#pragma unroll
+            for (int p = 0; p < R; ++p)
+                if (step < write_of[p]) copy_out(p, first_of[p] + step);
         }
     };
 
@@ -267,9 +297,7 @@ sig_row_stream_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
             if (sh.stream) {
                 if (live) stage_words();
                 rs_lds_barrier();
-#pragma unroll
-                for (int p = 0; p < R; ++p)
-                    if (t0 + s < write_of[p]) copy_out(p, first_of[p] + t0 + s);
+                copy_step(t0 + s);
                 rs_lds_barrier();
             }
         }
