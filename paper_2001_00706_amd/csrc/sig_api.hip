@@ -112,7 +112,8 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
     const bool generic_ok = sig::generic_supported(sh, dtype);
     const bool small_ok = sig::small_supported(sh);
     const bool tree_ok = sig::tree_supported(sh);
-    const bool rows_ok = sh.stream && sig::row_stream_supported(sh, dtype);
+    const bool rows_any = sig::row_stream_supported(sh, dtype);
+    const bool rows_ok = sh.stream && rows_any;
     switch (variant) {
         case SIG_VARIANT_AUTO:
             // four wavefronts per path when one per path would leave most of the chip idle, when every
@@ -126,8 +127,11 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
             // 64 wavefronts per path pay off while paths are few; from 512 paths on each shard's own prefix sums
             // are pure overhead (N = 4 at B = 2048: 170 us against 62 for the prefix-tree kernel); N = 6 stays
             if (d8_ok && !(sh.N <= 5 && sh.B >= 512 && tree_ok)) return Family::MfmaD8;
-            // every prefix stored: a wavefront per row with whole-row stores, wherever it applies
-            if (rows_ok) return Family::RowStream;
+            // every prefix stored: a wavefront per row with whole-row stores, wherever it applies; in final mode where
+            // one level lies below a lane's word and the state is more than a wavefront's worth of scalars (measured
+            // at 128 points: d = 8, N = 3: 19 us against 47 at 32 paths, 30 against 56 at 4096; d = 3, N = 4: 17 against
+            // 23 and 23 against 47; with two levels below the word the prefix-tree kernel is as fast or faster)
+            if (rows_ok || (rows_any && sh.S > 64 && sig::row_stream_one_level(sh))) return Family::RowStream;
             // up to 128 scalars (two words per lane) the one-wavefront kernel wins; beyond, its lanes carry 4 or 8
             // words each and the prefix-tree kernel is up to 6 times faster (d = 2, N = 8: 38 us against 194)
             // (in stream mode up to depth 3 as well: its lanes store 64 consecutive scalars per instruction, the
@@ -143,7 +147,7 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
         case SIG_VARIANT_MFMA_STREAM: return stream_ok ? Family::MfmaStream : Family::None;
         case SIG_VARIANT_SMALL: return small_ok ? Family::Small : Family::None;
         case SIG_VARIANT_TREE: return tree_ok ? Family::Tree : Family::None;
-        case SIG_VARIANT_ROW_STREAM: return rows_ok ? Family::RowStream : Family::None;
+        case SIG_VARIANT_ROW_STREAM: return rows_any ? Family::RowStream : Family::None;
     }
     return Family::None;
 }

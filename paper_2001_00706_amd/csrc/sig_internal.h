@@ -150,8 +150,9 @@ hipError_t launch_tree_f32(const Shape &sh, const float *path, float *out, hipSt
 hipError_t launch_tree_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
 
 // Row-stream family (d = 2..16 with one or two levels below a word of at most 64 per row; see sig_row_stream.hip): stream
-// mode, and both passes of a stream scan cut into chunks (Shape::rows_in_stream); not for plain final mode.
+// mode, both passes of a stream scan cut into chunks (Shape::rows_in_stream), and final mode.
 bool row_stream_supported(const Shape &sh, sig_dtype dtype);
+bool row_stream_one_level(const Shape &sh);   // one level below a lane's word (N - 1 letters fit a wavefront)
 hipError_t launch_row_stream_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_row_stream_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
 
