@@ -301,6 +301,18 @@ def test_variant_names(lib):
     assert sig.sig_variant_name(32, 16, 4, 7, False, False, variant=sig.SIG_VARIANT_MFMA_SHARD) == "mfma_d4_shard"
     assert sig.sig_variant_name(32, 16, 2, 4, True, True, sig.SIG_F64, sig.SIG_VARIANT_SMALL) == "small"
     assert sig.sig_variant_name(32, 16, 4, 6, True, False, variant=sig.SIG_VARIANT_MFMA) == "unsupported"
+    # the row kernel: stream mode wherever a lane per word leaves one or two levels below it (two up to 8 channels) ...
+    auto = lambda *a, **k: sig.sig_variant_name(*a, **k)
+    assert auto(128, 256, 8, 3, True, False) == auto(128, 256, 8, 4, True, False, sig.SIG_F64) == "row_stream"
+    assert auto(128, 256, 3, 5, True, False) == auto(128, 256, 2, 8, True, True) == auto(4, 9, 16, 2, True, False) == "row_stream"
+    assert auto(128, 256, 8, 5, True, False) == auto(128, 256, 3, 6, True, False) == auto(128, 256, 12, 3, True, False) == "tree"
+    assert auto(128, 256, 2, 3, True, False) == "small"                       # 4 lanes per row: left to the one-wavefront kernel
+    assert auto(128, 256, 4, 5, True, False) == "mfma_d4_shard"               # the matrix-core stream kernels come first
+    assert auto(128, 256, 12, 3, True, False, variant=sig.SIG_VARIANT_ROW_STREAM) == "unsupported"
+    # ... and final mode where one level lies below the word and the state exceeds 64 scalars
+    assert auto(32, 128, 8, 3, False, False) == auto(32, 128, 3, 4, False, True) == auto(32, 128, 2, 7, False, False) == "row_stream"
+    assert auto(32, 128, 5, 4, False, False) == "tree" and auto(32, 128, 2, 5, False, False) == "small"
+    assert auto(32, 128, 5, 4, False, False, variant=sig.SIG_VARIANT_ROW_STREAM) == "row_stream"
 
 
 def test_python_binding_refuses_cpu_tensors(lib):
