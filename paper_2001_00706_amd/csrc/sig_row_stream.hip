@@ -251,16 +251,30 @@ sig_row_stream_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
     const T *bpv = static_cast<const T *>(sh.basepoint_value);
     for (int t0 = 0; t0 < n_max; t0 += kRsTile) {
         rs_lds_barrier();   // the increments of the tile before are no longer needed
-        for (int e = lane; e < R * kRsTile * D; e += 64) {
-            const int p = e / (kRsTile * D), i = (e / D) % kRsTile, c = e % D;
-            T z = T(0);   // rows past the end of the batch and increments past the end of a row add nothing
-            if (t0 + i < row_n[p]) {
+        // the tile's increments, R * kRsTile * D scalars, eight per lane at a time: every load is unconditional (on an
+        // index clamped into the path) and issued before the first use, so a batch costs one trip to memory, not
+        // one per scalar; rows past the end of the batch and increments past the end of a row add nothing
+        constexpr int kStaged = R * kRsTile * D, kStageBatch = 8;
+#pragma unroll 1
+        for (int e0 = 0; e0 < kStaged; e0 += 64 * kStageBatch) {
+            T hi[kStageBatch], lo[kStageBatch];
+            bool on[kStageBatch], first[kStageBatch];
+#pragma unroll
+            for (int j = 0; j < kStageBatch; ++j) {
+                const int e = e0 + 64 * j + lane < kStaged ? e0 + 64 * j + lane : kStaged - 1;
+                const int p = e / (kRsTile * D), i = (e / D) % kRsTile, c = e % D;
+                on[j] = t0 + i < row_n[p];
                 const T *x = path + row_x[p] * sh.L * D;
-                const int64_t i_hi = row_inc0[p] + t0 + i + (sh.basepoint ? 0 : 1);
-                const T lo = i_hi > 0 ? x[(i_hi - 1) * D + c] : bpv != nullptr ? bpv[row_x[p] * D + c] : T(0);
-                z = x[i_hi * D + c] - lo;
+                const int64_t i_hi = on[j] ? row_inc0[p] + t0 + i + (sh.basepoint ? 0 : 1) : (sh.basepoint ? 0 : 1);
+                first[j] = i_hi == 0;   // the increment from the basepoint
+                hi[j] = x[i_hi * D + c];
+                lo[j] = bpv != nullptr && first[j] ? bpv[row_x[p] * D + c] : x[(first[j] ? 0 : i_hi - 1) * D + c];
             }
-            zt[e] = z;
+#pragma unroll
+            for (int j = 0; j < kStageBatch; ++j) {
+                const int e = e0 + 64 * j + lane;
+                if (e < kStaged) zt[e] = on[j] ? hi[j] - (first[j] && bpv == nullptr ? T(0) : lo[j]) : T(0);
+            }
         }
         rs_lds_barrier();
         const int nt = n_max - t0 < kRsTile ? n_max - t0 : kRsTile;
