@@ -141,17 +141,16 @@ sig_tree_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
         __syncthreads();
         for (int e = tid; e < PPG * kTreeTile * D; e += 256) {
             const int p = e / (kTreeTile * D), i = (e / D) % kTreeTile, c = e % D;
-            T z = T(0);   // rows past the end of the batch and increments past the end of a row add nothing
-            if (row0 + p < sh.B) {
-                const ChunkView cv = chunk_view(row0 + p, sh.chunks, sh.chunk_len, sh.n_inc);
-                if (t0 + i < cv.n) {
-                    const T *x = path + cv.path * sh.L * D;
-                    const int64_t i_hi = cv.inc0 + t0 + i + (sh.basepoint ? 0 : 1);
-                    const T lo = i_hi > 0 ? x[(i_hi - 1) * D + c] : bpv != nullptr ? bpv[cv.path * D + c] : T(0);
-                    z = x[i_hi * D + c] - lo;
-                }
-            }
-            zt[e] = z;
+            // rows past the end of the batch and increments past the end of a row add nothing; both loads are
+            // unconditional, on indices clamped into a path, so that they are in flight together
+            const ChunkView cv = chunk_view(row0 + p < sh.B ? row0 + p : 0, sh.chunks, sh.chunk_len, sh.n_inc);
+            const bool on = row0 + p < sh.B && t0 + i < cv.n;
+            const T *x = path + cv.path * sh.L * D;
+            const int64_t i_hi = on ? cv.inc0 + t0 + i + (sh.basepoint ? 0 : 1) : (sh.basepoint ? 0 : 1);
+            const bool first = i_hi == 0;   // the increment from the basepoint
+            const T hi = x[i_hi * D + c];
+            const T lo = bpv != nullptr && first ? bpv[cv.path * D + c] : x[(first ? 0 : i_hi - 1) * D + c];
+            zt[e] = on ? hi - (first && bpv == nullptr ? T(0) : lo) : T(0);
         }
         __syncthreads();
         const int nt = int(n_max - t0 < kTreeTile ? n_max - t0 : kTreeTile);
