@@ -20,6 +20,7 @@ SIG_VARIANT_AUTO, SIG_VARIANT_GENERIC, SIG_VARIANT_MFMA, SIG_VARIANT_MFMA_SHARD,
 SIG_VARIANT_TREE = 5
 SIG_VARIANT_MFMA_STREAM = 6
 SIG_VARIANT_ROW_STREAM = 7
+SIG_VARIANT_WIDE = 8
 SIG_MAX_DEPTH = 32
 
 # every symbol include/sig.h declares

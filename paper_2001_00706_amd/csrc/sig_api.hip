@@ -97,7 +97,7 @@ sig_status make_rows_shape(int64_t rows, int d, int N, sig::Shape &sh)
     return SIG_OK;
 }
 
-enum class Family { Generic, Mfma, MfmaShard, MfmaStream, MfmaD16, MfmaD8, Small, Tree, RowStream, None };
+enum class Family { Generic, Mfma, MfmaShard, MfmaStream, MfmaD16, MfmaD8, Small, Tree, RowStream, Wide, None };
 
 // The pointers decide only alignment: the matrix-core family loads and stores 16 bytes per lane.
 Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const void *path, const void *out)
@@ -112,6 +112,7 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
     const bool generic_ok = sig::generic_supported(sh, dtype);
     const bool small_ok = sig::small_supported(sh);
     const bool tree_ok = sig::tree_supported(sh);
+    const bool wide_ok = sig::wide_supported(sh, dtype);
     const bool rows_any = sig::row_stream_supported(sh, dtype);
     const bool rows_ok = sh.stream && rows_any;
     switch (variant) {
@@ -139,6 +140,9 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
             // at 128 paths of 256 points)
             if (small_ok && (sh.S <= 128 || !tree_ok || (sh.stream && sh.N <= 3))) return Family::Small;
             if (tree_ok) return Family::Tree;
+            // beyond 16 channels at depths 2..4: the run-time-d kernel (d = 32, N = 2 at 32 paths of 128 points: 0.72 ms
+            // on the generic kernel)
+            if (wide_ok) return Family::Wide;
             return generic_ok ? Family::Generic : Family::None;
         case SIG_VARIANT_GENERIC: return generic_ok ? Family::Generic : Family::None;
         case SIG_VARIANT_MFMA:
@@ -148,6 +152,7 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
         case SIG_VARIANT_SMALL: return small_ok ? Family::Small : Family::None;
         case SIG_VARIANT_TREE: return tree_ok ? Family::Tree : Family::None;
         case SIG_VARIANT_ROW_STREAM: return rows_any ? Family::RowStream : Family::None;
+        case SIG_VARIANT_WIDE: return wide_ok ? Family::Wide : Family::None;
     }
     return Family::None;
 }
@@ -175,6 +180,10 @@ hipError_t launch_scan(Family family, const sig::Shape &sh, sig_dtype dtype, con
             return dtype == SIG_F32
                        ? sig::launch_row_stream_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
                        : sig::launch_row_stream_f64(sh, static_cast<const double *>(path), static_cast<double *>(out), hip_stream);
+        case Family::Wide:
+            return dtype == SIG_F32
+                       ? sig::launch_wide_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
+                       : sig::launch_wide_f64(sh, static_cast<const double *>(path), static_cast<double *>(out), hip_stream);
         case Family::Small:
             return dtype == SIG_F32
                        ? sig::launch_small_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
@@ -238,7 +247,7 @@ bool valid_enums(sig_dtype dtype, sig_variant variant)
     return (dtype == SIG_F32 || dtype == SIG_F64) &&
            (variant == SIG_VARIANT_AUTO || variant == SIG_VARIANT_GENERIC || variant == SIG_VARIANT_MFMA ||
             variant == SIG_VARIANT_MFMA_SHARD || variant == SIG_VARIANT_SMALL || variant == SIG_VARIANT_TREE ||
-            variant == SIG_VARIANT_MFMA_STREAM || variant == SIG_VARIANT_ROW_STREAM);
+            variant == SIG_VARIANT_MFMA_STREAM || variant == SIG_VARIANT_ROW_STREAM || variant == SIG_VARIANT_WIDE);
 }
 
 }  // namespace
@@ -798,6 +807,7 @@ const char *sig_variant_name(int64_t B, int64_t L, int d, int N, int stream, int
         case Family::Small: return "small";
         case Family::Tree: return "tree";
         case Family::RowStream: return "row_stream";
+        case Family::Wide: return "wide";
         case Family::Generic: return "generic";
         case Family::None: break;
     }

@@ -156,6 +156,11 @@ bool row_stream_one_level(const Shape &sh);   // one level below a lane's word (
 hipError_t launch_row_stream_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_row_stream_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
 
+// Many channels at low depth (any d >= 2 at N = 2..4; see sig_wide.hip): what serves d > 16; not for chunked scans.
+bool wide_supported(const Shape &sh, sig_dtype dtype);
+hipError_t launch_wide_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
+hipError_t launch_wide_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
+
 // Prefix-tree gradient kernels (d = 2..8 at N = 2..9, d = 9..16 at N = 2..6, any alignment): no communication between threads; the
 // per-increment partial gradients go to a workspace of `tree_backward_workspace_bytes` and are summed by a second
 // kernel.

@@ -1,0 +1,186 @@
+// Many channels at low depth (any d at N = 2, 3, 4; fp32 and fp64; final and stream mode): the kernel for d > 16, where
+// the prefix-tree family has no instantiation (its channel count is a compile-time constant) and a signature is
+// too large for the one-wavefront kernel.
+//
+// Arithmetic of the prefix-tree family (paper section 4.1, eq. "fusedterm": the new coefficient of a word needs the
+// coefficients of that word's prefixes only) with the channel count a run-time value: a thread stands for a word u of
+// N - 1 letters and a block of 16 last letters, carries the coefficients of u and of its prefixes (every thread below a
+// prefix updates its own copy identically) and keeps the 16 top-level coefficients u j, j in its block, in
+// registers.  Nothing is exchanged between threads, so the d^(N-1) * ceil(d / 16) threads of a path may sit in any
+// number of workgroups; paths with fewer than 256 threads share a workgroup.  The chain along the word is repeated
+// by the ceil(d / 16) threads of a word: a few multiply-adds against 16.
+#include "sig_internal.h"
+
+namespace sig {
+namespace {
+
+constexpr int kWideBlock = 16;   // last letters per thread
+constexpr int kWideTile = 32;    // increments staged in LDS at a time
+
+__device__ __forceinline__ float wide_fma(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ double wide_fma(double a, double b, double c) { return __builtin_fma(a, b, c); }
+
+struct WidePlan {
+    int jblocks;              // ceil(d / 16)
+    int dpad;                 // jblocks * 16: floats per staged increment (zeros behind the d-th)
+    int64_t threads;          // threads per path: d^(N-1) * jblocks
+    int paths_per_group;      // paths sharing a workgroup (1 when a path has 256 threads or more)
+    int64_t groups_per_path;  // workgroups per path (1 when paths share a workgroup)
+};
+
+template <typename T, int N>
+__global__ void __launch_bounds__(256)
+sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict__ out)
+{
+    constexpr int P = N - 1;
+    extern __shared__ __align__(16) unsigned char wide_smem[];
+    T *zt = reinterpret_cast<T *>(wide_smem);   // [paths_per_group][kWideTile][dpad]
+
+    const int tid = threadIdx.x;
+    const int d = sh.d;
+    const bool shared_group = pl.threads < 256;
+    const int slot_raw = shared_group ? tid / int(pl.threads) : 0;
+    const int slot = slot_raw < pl.paths_per_group ? slot_raw : pl.paths_per_group - 1;   // threads beyond the last path idle along
+    const int64_t t = shared_group ? tid - slot_raw * int(pl.threads) : int64_t(blockIdx.x % pl.groups_per_path) * 256 + tid;
+    const int64_t row0 = shared_group ? int64_t(blockIdx.x) * pl.paths_per_group : int64_t(blockIdx.x / pl.groups_per_path);
+    const int64_t row = row0 + slot;
+    const bool live = t < pl.threads && slot_raw < pl.paths_per_group && row < sh.B;
+    const int64_t u = (live ? t : 0) / pl.jblocks;          // the word of N - 1 letters
+    const int jb = int((live ? t : 0) - u * pl.jblocks);    // the block of last letters
+    const int j0 = jb * kWideBlock;
+
+    int cl[P + 1];   // letters of the word
+    {
+        int64_t rest = u;
+#pragma unroll
+        for (int i = P; i >= 1; --i) {
+            cl[i] = int(rest % d);
+            rest /= d;
+        }
+    }
+    T rk[N + 2];
+#pragma unroll
+    for (int m = 1; m <= N + 1; ++m) rk[m] = T(1) / T(m);
+
+    T A[P + 1];             // coefficients of the prefixes of the word, and of the word itself (level N - 1)
+    T top[kWideBlock];      // words u j, j = j0 .. j0 + 15
+#pragma unroll
+    for (int i = 0; i <= P; ++i) A[i] = T(0);
+#pragma unroll
+    for (int c = 0; c < kWideBlock; ++c) top[c] = T(0);
+
+    const T *bpv = static_cast<const T *>(sh.basepoint_value);
+    const int64_t n_inc = sh.n_inc;
+
+    // this thread's scalars of one signature; a prefix is written by the first thread below it
+    auto store = [&](T *o) {
+        if (jb == 0) {
+            int64_t q = u, width = 1;
+#pragma unroll
+            for (int i = P; i >= 1; --i) {
+                if (u % width == 0) o[sh.off[i] + q] = A[i];
+                q /= d;
+                width *= d;
+            }
+        }
+        T *o_top = o + sh.off[N] + u * d + j0;
+#pragma unroll
+        for (int c = 0; c < kWideBlock; ++c)
+            if (j0 + c < d) o_top[c] = top[c];
+    };
+
+    const int row_floats = kWideTile * pl.dpad;
+    for (int64_t t0 = 0; t0 < n_inc; t0 += kWideTile) {
+        __syncthreads();
+        for (int e = tid; e < pl.paths_per_group * row_floats; e += 256) {
+            const int p = e / row_floats, r = e - p * row_floats, i = r / pl.dpad, c = r - i * pl.dpad;
+            // rows past the end of the batch, increments past the end of the path and the padding behind the last channel
+            // add nothing; both loads are unconditional, on indices clamped into a path, so that they are in flight together
+            const bool on = row0 + p < sh.B && t0 + i < n_inc && c < d;
+            const T *x = path + (row0 + p < sh.B ? row0 + p : 0) * sh.L * d;
+            const int cc = c < d ? c : 0;
+            const int64_t i_hi = on ? t0 + i + (sh.basepoint ? 0 : 1) : (sh.basepoint ? 0 : 1);
+            const bool first = i_hi == 0;   // the increment from the basepoint
+            const T hi = x[i_hi * d + cc];
+            const T lo = bpv != nullptr && first ? bpv[(row0 + p < sh.B ? row0 + p : 0) * d + cc] : x[(first ? 0 : i_hi - 1) * d + cc];
+            zt[e] = on ? hi - (first && bpv == nullptr ? T(0) : lo) : T(0);
+        }
+        __syncthreads();
+        const int nt = int(n_inc - t0 < kWideTile ? n_inc - t0 : kWideTile);
+        const T *zrow = zt + slot * row_floats;
+        for (int s = 0; s < nt; ++s, zrow += pl.dpad) {
+            // Horner terms along the word: Hn[k] = T^(k)_i for the level i just passed, k > i
+            T Hn[N + 2];
+            {
+                const T zc = zrow[cl[1]];
+#pragma unroll
+                for (int k = 2; k <= N; ++k) Hn[k] = wide_fma(zc, rk[k], A[1]);
+                A[1] += zc;
+            }
+#pragma unroll
+            for (int i = 2; i <= P; ++i) {
+                const T zc = zrow[cl[i]];
+                const T a = A[i];
+                A[i] = wide_fma(Hn[i], zc, a);
+#pragma unroll
+                for (int k = i + 1; k <= N; ++k) Hn[k] = wide_fma(Hn[k], zc * rk[k - i + 1], a);
+            }
+#pragma unroll
+            for (int c = 0; c < kWideBlock; ++c) top[c] = wide_fma(Hn[N], zrow[j0 + c], top[c]);
+            if (sh.stream && live) store(out + (row * n_inc + t0 + s) * sh.S);
+        }
+    }
+    if (live && !sh.stream) store(out + row * sh.S);
+}
+
+bool wide_plan(const Shape &sh, WidePlan &pl)
+{
+    if (sh.N < 2 || sh.N > 4 || sh.d < 2 || sh.chunks > 1 || sh.S >= (int64_t(1) << 31)) return false;
+    pl.jblocks = (sh.d + kWideBlock - 1) / kWideBlock;
+    pl.dpad = pl.jblocks * kWideBlock;
+    pl.threads = sh.pw[sh.N - 1] * pl.jblocks;
+    if (pl.threads > (int64_t(1) << 24)) return false;
+    if (pl.threads >= 256) {
+        pl.paths_per_group = 1;
+        pl.groups_per_path = (pl.threads + 255) / 256;
+    } else {
+        const int fit = int(256 / pl.threads);
+        pl.paths_per_group = fit < 16 ? fit : 16;
+        pl.groups_per_path = 1;
+    }
+    return true;
+}
+
+template <typename T>
+hipError_t launch_wide_t(const Shape &sh, const T *path, T *out, hipStream_t st)
+{
+    WidePlan pl;
+    if (!wide_plan(sh, pl)) return hipErrorNotSupported;
+    const size_t lds = size_t(pl.paths_per_group) * kWideTile * size_t(pl.dpad) * sizeof(T);
+    if (lds > 64 * 1024) return hipErrorNotSupported;
+    const int64_t groups = pl.threads >= 256 ? sh.B * pl.groups_per_path : (sh.B + pl.paths_per_group - 1) / pl.paths_per_group;
+    if (groups > 0x7fffffff) return hipErrorNotSupported;
+    const dim3 grid{unsigned(groups)}, block{256};
+    switch (sh.N) {
+        case 2: hipLaunchKernelGGL((sig_wide_kernel<T, 2>), grid, block, lds, st, sh, pl, path, out); break;
+        case 3: hipLaunchKernelGGL((sig_wide_kernel<T, 3>), grid, block, lds, st, sh, pl, path, out); break;
+        case 4: hipLaunchKernelGGL((sig_wide_kernel<T, 4>), grid, block, lds, st, sh, pl, path, out); break;
+        default: return hipErrorNotSupported;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool wide_supported(const Shape &sh, sig_dtype dtype)
+{
+    WidePlan pl;
+    if (!wide_plan(sh, pl)) return false;
+    const size_t elem = dtype == SIG_F32 ? sizeof(float) : sizeof(double);
+    return size_t(pl.paths_per_group) * kWideTile * size_t(pl.dpad) * elem <= 64 * 1024;
+}
+
+hipError_t launch_wide_f32(const Shape &sh, const float *path, float *out, hipStream_t st) { return launch_wide_t<float>(sh, path, out, st); }
+hipError_t launch_wide_f64(const Shape &sh, const double *path, double *out, hipStream_t st) { return launch_wide_t<double>(sh, path, out, st); }
+
+}  // namespace sig

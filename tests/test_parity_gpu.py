@@ -84,8 +84,9 @@ def check(x, N, stream=False, basepoint=False, variant=sig.SIG_VARIANT_AUTO, sam
 
 
 VARIANTS = [sig.SIG_VARIANT_AUTO, sig.SIG_VARIANT_GENERIC, sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_SHARD,
-            sig.SIG_VARIANT_SMALL, sig.SIG_VARIANT_TREE, sig.SIG_VARIANT_MFMA_STREAM, sig.SIG_VARIANT_ROW_STREAM]
-VARIANT_IDS = ["auto", "generic", "mfma", "mfma_shard", "small", "tree", "mfma_stream", "row_stream"]
+            sig.SIG_VARIANT_SMALL, sig.SIG_VARIANT_TREE, sig.SIG_VARIANT_MFMA_STREAM, sig.SIG_VARIANT_ROW_STREAM,
+            sig.SIG_VARIANT_WIDE]
+VARIANT_IDS = ["auto", "generic", "mfma", "mfma_shard", "small", "tree", "mfma_stream", "row_stream", "wide"]
 MODES = [(False, False), (False, True), (True, False), (True, True)]     # (stream, basepoint)
 
 
@@ -516,6 +517,25 @@ def test_chunked_stream_with_initial_and_inverse():
     for j in (0, 57, L - 2):
         want = orc.signature(whole[:, :9 + j + 1][:, ::-1], N)   # inverse = the signature of the reversed path
         np.testing.assert_allclose(got[:, j].cpu().numpy(), want, rtol=1e-9, atol=1e-12)
+
+
+# ------------------------------------------------------------------ many channels at low depth
+@pytest.mark.parametrize("B,L,d,N", [
+    (3, 9, 20, 2), (2, 40, 32, 2), (37, 6, 18, 2),      # several paths per workgroup, a ragged last workgroup
+    (1, 4, 64, 2), (2, 35, 100, 2),                     # 256 and 700 threads per path
+    (5, 7, 17, 3), (2, 5, 33, 3), (2, 70, 24, 3),       # a last block of 1 letter, 3267 threads per path, several tiles
+    (1, 5, 20, 4), (2, 3, 18, 4),                       # depth 4: 16 000 and 11 664 threads per path
+    (3, 9, 5, 3), (2, 6, 16, 2),                        # channel counts the other families serve as well
+])
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_wide_channel_family(B, L, d, N, dtype):
+    x = (brownian_paths(B, L, d, seed=B + L + d + N) + 0.2).astype(dtype)
+    code = sig.SIG_F32 if dtype == np.float32 else sig.SIG_F64
+    for stream in (False, True):
+        for basepoint in (False, True):
+            assert check(x, N, stream=stream, basepoint=basepoint, variant=sig.SIG_VARIANT_WIDE) is not None
+    if d > 16:   # ... and it is what serves these shapes
+        assert sig.sig_variant_name(B, L, d, N, False, False, code) == ("wide" if orc.channels(d, N) > 512 else "small")
 
 
 # ------------------------------------------------------------------ prefix-tree family
