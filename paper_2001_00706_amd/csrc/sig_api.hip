@@ -138,6 +138,7 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
             // (in stream mode up to depth 3 as well: its lanes store 64 consecutive scalars per instruction, the
             // prefix-tree kernel's lanes store d^2 scalars apart: d = 16, N = 2: 52 us against 75, d = 7, N = 3: 67 against 85
             // at 128 paths of 256 points)
+            if (wide_ok && sh.d > 16 && sh.S > 128) return Family::Wide;   // d = 20, N = 2: 52 us against 57 on `small`
             if (small_ok && (sh.S <= 128 || !tree_ok || (sh.stream && sh.N <= 3))) return Family::Small;
             if (tree_ok) return Family::Tree;
             // beyond 16 channels at depths 2..4: the run-time-d kernel (d = 32, N = 2 at 32 paths of 128 points: 0.72 ms

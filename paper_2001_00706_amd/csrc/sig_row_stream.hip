@@ -251,10 +251,10 @@ sig_row_stream_kernel(Shape sh, const T *__restrict__ path, T *__restrict__ out)
     const T *bpv = static_cast<const T *>(sh.basepoint_value);
     for (int t0 = 0; t0 < n_max; t0 += kRsTile) {
         rs_lds_barrier();   // the increments of the tile before are no longer needed
-        // the tile's increments, R * kRsTile * D scalars, eight per lane at a time: every load is unconditional (on an
+        // the tile's increments, R * kRsTile * D scalars, up to sixteen per lane at a time: every load is unconditional (on an
         // index clamped into the path) and issued before the first use, so a batch costs one trip to memory, not
         // one per scalar; rows past the end of the batch and increments past the end of a row add nothing
-        constexpr int kStaged = R * kRsTile * D, kStageBatch = 8;
+        constexpr int kStaged = R * kRsTile * D, kStageBatch = (kStaged + 63) / 64 < 16 ? (kStaged + 63) / 64 : 16;
 #pragma unroll 1
         for (int e0 = 0; e0 < kStaged; e0 += 64 * kStageBatch) {
             T hi[kStageBatch], lo[kStageBatch];

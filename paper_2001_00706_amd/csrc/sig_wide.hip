@@ -92,18 +92,32 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
     const int row_floats = kWideTile * pl.dpad;
     for (int64_t t0 = 0; t0 < n_inc; t0 += kWideTile) {
         __syncthreads();
-        for (int e = tid; e < pl.paths_per_group * row_floats; e += 256) {
-            const int p = e / row_floats, r = e - p * row_floats, i = r / pl.dpad, c = r - i * pl.dpad;
-            // rows past the end of the batch, increments past the end of the path and the padding behind the last channel
-            // add nothing; both loads are unconditional, on indices clamped into a path, so that they are in flight together
-            const bool on = row0 + p < sh.B && t0 + i < n_inc && c < d;
-            const T *x = path + (row0 + p < sh.B ? row0 + p : 0) * sh.L * d;
-            const int cc = c < d ? c : 0;
-            const int64_t i_hi = on ? t0 + i + (sh.basepoint ? 0 : 1) : (sh.basepoint ? 0 : 1);
-            const bool first = i_hi == 0;   // the increment from the basepoint
-            const T hi = x[i_hi * d + cc];
-            const T lo = bpv != nullptr && first ? bpv[(row0 + p < sh.B ? row0 + p : 0) * d + cc] : x[(first ? 0 : i_hi - 1) * d + cc];
-            zt[e] = on ? hi - (first && bpv == nullptr ? T(0) : lo) : T(0);
+        // rows past the end of the batch, increments past the end of the path and the padding behind the last channel
+        // add nothing; the loads are unconditional, on indices clamped into a path, and issued four scalars at a time
+        // before the first use: a batch costs one trip to memory
+        const int staged = pl.paths_per_group * row_floats;
+        for (int e0 = 0; e0 < staged; e0 += 256 * 4) {
+            T hi[4], lo[4];
+            bool on[4], first[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (e0 + 256 * j >= staged) break;   // the same for every thread: nothing left to stage
+                const int e = e0 + 256 * j + tid < staged ? e0 + 256 * j + tid : staged - 1;
+                const int p = e / row_floats, r = e - p * row_floats, i = r / pl.dpad, c = r - i * pl.dpad;
+                on[j] = row0 + p < sh.B && t0 + i < n_inc && c < d;
+                const int64_t rp = row0 + p < sh.B ? row0 + p : 0;
+                const T *x = path + rp * sh.L * d;
+                const int cc = c < d ? c : 0;
+                const int64_t i_hi = on[j] ? t0 + i + (sh.basepoint ? 0 : 1) : (sh.basepoint ? 0 : 1);
+                first[j] = i_hi == 0;   // the increment from the basepoint
+                hi[j] = x[i_hi * d + cc];
+                lo[j] = bpv != nullptr && first[j] ? bpv[rp * d + cc] : x[(first[j] ? 0 : i_hi - 1) * d + cc];
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int e = e0 + 256 * j + tid;
+                if (e < staged) zt[e] = on[j] ? hi[j] - (first[j] && bpv == nullptr ? T(0) : lo[j]) : T(0);
+            }
         }
         __syncthreads();
         const int nt = int(n_inc - t0 < kWideTile ? n_inc - t0 : kWideTile);

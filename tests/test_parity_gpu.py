@@ -535,7 +535,7 @@ def test_wide_channel_family(B, L, d, N, dtype):
         for basepoint in (False, True):
             assert check(x, N, stream=stream, basepoint=basepoint, variant=sig.SIG_VARIANT_WIDE) is not None
     if d > 16:   # ... and it is what serves these shapes
-        assert sig.sig_variant_name(B, L, d, N, False, False, code) == ("wide" if orc.channels(d, N) > 512 else "small")
+        assert sig.sig_variant_name(B, L, d, N, False, False, code) == "wide"
 
 
 # ------------------------------------------------------------------ prefix-tree family
