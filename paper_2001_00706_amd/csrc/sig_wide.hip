@@ -71,6 +71,10 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
 
     const T *bpv = static_cast<const T *>(sh.basepoint_value);
     const int64_t n_inc = sh.n_inc;
+    // every block of 16 top-level scalars starts on a 16-byte boundary: signatures, levels and rows of d are whole
+    // multiples of 16 bytes and so is the output's address
+    constexpr int kPer16 = 16 / int(sizeof(T));
+    const bool vec_ok = d % kPer16 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0;
 
     // this thread's scalars of one signature; a prefix is written by the first thread below it
     auto store = [&](T *o) {
@@ -84,9 +88,21 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
             }
         }
         T *o_top = o + sh.off[N] + u * d + j0;
+        if (vec_ok && j0 + kWideBlock <= d) {   // 16 bytes per store instead of one scalar
+            constexpr int kVec = 16 / int(sizeof(T));
+            typedef T TV __attribute__((ext_vector_type(kVec)));
 #pragma unroll
-        for (int c = 0; c < kWideBlock; ++c)
-            if (j0 + c < d) o_top[c] = top[c];
+            for (int c = 0; c < kWideBlock; c += kVec) {
+                TV v;
+#pragma unroll
+                for (int k = 0; k < kVec; ++k) v[k] = top[c + k];
+                *reinterpret_cast<TV *>(o_top + c) = v;
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < kWideBlock; ++c)
+                if (j0 + c < d) o_top[c] = top[c];
+        }
     };
 
     const int row_floats = kWideTile * pl.dpad;
