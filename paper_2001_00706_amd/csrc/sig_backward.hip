@@ -304,6 +304,7 @@ bool backward_supported(const Shape &sh)
 int64_t backward_workspace_bytes(const Shape &sh, sig_dtype dtype)
 {
     // signatures of up to 8 channels and depth 9 never reach the generic kernel
+    if (backward_n2_supported(sh, dtype)) return 0;   // depth 2 in final mode: a closed form, nothing to keep
     if (tree_backward_supported(sh)) return tree_backward_workspace_bytes(sh, dtype);
     BackwardPlan pl;
     if (!backward_supported(sh) || !make_plan(sh, kBackwardThreads, pl)) return -1;
@@ -316,6 +317,7 @@ int64_t backward_workspace_bytes(const Shape &sh, sig_dtype dtype)
 hipError_t launch_backward_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
                                float *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st)
 {
+    if (backward_n2_supported(sh, SIG_F32)) return launch_backward_n2_f32(sh, path, gout, gpath, gbase, st);
     const bool aligned = (reinterpret_cast<uintptr_t>(path) | reinterpret_cast<uintptr_t>(sig) |
                           reinterpret_cast<uintptr_t>(gout) | reinterpret_cast<uintptr_t>(sh.basepoint_value)) % 16 == 0;
     // Measured at L = 128 over B = 1..2048: with one gradient per path (final mode) the prefix-tree kernels beat the
@@ -344,6 +346,7 @@ hipError_t launch_backward_f32(const Shape &sh, const float *path, const float *
 hipError_t launch_backward_f64(const Shape &sh, const double *path, const double *sig, const double *gout, double *gpath,
                                double *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st)
 {
+    if (backward_n2_supported(sh, SIG_F64)) return launch_backward_n2_f64(sh, path, gout, gpath, gbase, st);
     if (tree_backward_supported(sh))
         return launch_tree_backward_f64(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
     return launch_backward<double>(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);

@@ -161,6 +161,13 @@ bool wide_supported(const Shape &sh, sig_dtype dtype);
 hipError_t launch_wide_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_wide_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
 
+// Gradient of the depth-2 signature in final mode by its closed form (no scan, no workspace; see sig_backward_n2.hip):
+// any channel count whose d x (d + 1) output gradient fits the LDS (d <= 122 in fp32, 85 in fp64).
+bool backward_n2_supported(const Shape &sh, sig_dtype dtype);
+hipError_t launch_backward_n2_f32(const Shape &sh, const float *path, const float *gout, float *gpath, float *gbase, hipStream_t st);
+hipError_t launch_backward_n2_f64(const Shape &sh, const double *path, const double *gout, double *gpath, double *gbase,
+                                  hipStream_t st);
+
 // Prefix-tree gradient kernels (d = 2..8 at N = 2..9, d = 9..16 at N = 2..6, any alignment): no communication between threads; the
 // per-increment partial gradients go to a workspace of `tree_backward_workspace_bytes` and are summed by a second
 // kernel.

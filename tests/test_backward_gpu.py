@@ -193,6 +193,33 @@ def test_short_workspace_of_the_prefix_tree_kernels_is_refused():
     assert e.value.status == sig.SIG_ERR_INVALID_ARG
 
 
+# ---- depth 2 in final mode: the closed form (no scan), any channel count up to 122 (85 in fp64)
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("B,L,d", [(3, 2, 5), (2, 3, 1), (4, 40, 32), (1, 300, 7), (2, 9, 100), (5, 17, 16), (2, 130, 64), (3, 5, 85),
+                                   (2, 260, 3)])
+def test_depth_two_gradient_by_its_closed_form(B, L, d, dtype):
+    import torch
+    if d == 100 and dtype == np.float64:   # 100 x 101 doubles do not fit the LDS, and no other gradient kernel takes d > 64
+        assert sig.sig_backward_workspace_bytes(B, L, d, 2, False, False, sig.SIG_F64) == -1
+        return
+    x = (brownian_paths(B, L, d, seed=L + d) + 0.3).astype(dtype)
+    for basepoint in (False, True):
+        check(x, 2, basepoint=basepoint, seed=d)
+    # a basepoint given by value, and its own gradient
+    bp = uniform_paths(B, 1, d, seed=d + 1)[:, 0].astype(dtype)
+    g = np.random.default_rng(d).standard_normal((B, d + d * d)).astype(dtype)
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    xt, bt = to_dev(x), to_dev(bp)
+    st = sig.sig_signature(xt, 2, basepoint=bt)
+    gb = torch.full_like(bt, float("nan"))
+    gp = sig.sig_backward(xt, st, to_dev(g), 2, basepoint=bt, grad_basepoint=gb)
+    torch.cuda.synchronize()
+    want = orc.signature_backward(np.concatenate([bp[:, None], x], axis=1).astype(np.float64), g.astype(np.float64), 2)
+    tol = 1e-4 if dtype == np.float32 else 1e-9
+    assert np.linalg.norm(gp.cpu().numpy() - want[:, 1:]) <= tol * np.linalg.norm(want)
+    assert np.linalg.norm(gb.cpu().numpy() - want[:, 0]) <= tol * np.linalg.norm(want)
+
+
 def test_unsupported_and_invalid_arguments():
     import torch
     x = torch.zeros((1, 3, 65), device="cuda:0")
