@@ -42,7 +42,8 @@ void sig_oracle_mul_backward(const double *A, const double *B, const double *gC,
  *   num_threads <= 0 lets OpenMP choose (the only parallelism is a loop over the batch).
  * Returns 0, 1 on bad arguments (d < 1, N < 1, B < 0, fewer than two points once the basepoint is counted, null
  * pointers), 2 if memory ran out.
- * This is the function the survey's boundary sketch called sig_forward_host_oracle_f64. */
+ * The host-side fp64 counterpart of the library's sig_forward (its "host oracle" entry point, sig_forward_host_oracle_f64
+ * under another name). */
 int sig_oracle_forward_f64(const double *path, int64_t B, int64_t L, int d, int N, int stream, int basepoint,
                            double *out, int num_threads);
 
