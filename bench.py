@@ -138,7 +138,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2, help="configuration number 1..5 (default: the metric's)")
-    ap.add_argument("--variant", choices=["auto", "generic", "mfma", "mfma_shard", "small", "tree", "mfma_stream", "row_stream", "wide"], default="auto")
+    ap.add_argument("--variant", choices=["auto", "generic", "mfma", "mfma_shard", "small", "tree", "mfma_stream", "row_stream", "wide", "depth2"], default="auto")
     ap.add_argument("--shape", default=None, metavar="B,L,d,N[,stream]",
                     help="a shape of your own instead of one of the five workloads (same input recipe, seed index 0), "
                          "e.g. 32,128,7,7 for the largest case of the paper's benchmark grid")
@@ -181,7 +181,7 @@ def main() -> int:
     variant = {"auto": sig.SIG_VARIANT_AUTO, "generic": sig.SIG_VARIANT_GENERIC, "mfma": sig.SIG_VARIANT_MFMA,
                "mfma_shard": sig.SIG_VARIANT_MFMA_SHARD, "small": sig.SIG_VARIANT_SMALL,
                "tree": sig.SIG_VARIANT_TREE, "mfma_stream": sig.SIG_VARIANT_MFMA_STREAM,
-               "row_stream": sig.SIG_VARIANT_ROW_STREAM, "wide": sig.SIG_VARIANT_WIDE}[args.variant]
+               "row_stream": sig.SIG_VARIANT_ROW_STREAM, "wide": sig.SIG_VARIANT_WIDE, "depth2": sig.SIG_VARIANT_DEPTH2}[args.variant]
     x_host = workload_paths(w)
     dev = torch.device("cuda:0")
     x = torch.from_numpy(x_host).to(dev)

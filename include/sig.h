@@ -66,6 +66,8 @@ typedef enum {
                                  cut at 128-byte boundaries (what sig_forward picks for outputs beyond ~300 MB) */
     SIG_VARIANT_WIDE = 8,     /* any dtype and mode, any d >= 2 at N = 2..4 (what serves d > 16): a thread per word of
                                  N-1 letters and block of 16 last letters, channel count a run-time value */
+    SIG_VARIANT_DEPTH2 = 9,   /* any dtype, final mode, N = 2, d <= 1024: level 2 as a contraction over the increments,
+                                 a thread per 4 x 4 block of coefficients, no scan (what serves N = 2 in final mode) */
     SIG_VARIANT_ROW_STREAM = 7 /* any dtype and mode, d = 2..16 where a lane per word of P letters (d^P <= 64)
                                  leaves one level below it, or two up to d = 8 (d = 8: N = 2..4; d = 3: N = 3..5;
                                  d = 2: N = 4..8; d = 9..16: N = 2): a wavefront per row or few rows, state in registers,

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     SIG_VARIANT_MFMA_STREAM,
     SIG_VARIANT_ROW_STREAM,
     SIG_VARIANT_WIDE,
+    SIG_VARIANT_DEPTH2,
     SIG_VARIANT_SMALL,
     SIG_VARIANT_TREE,
     SigError,

@@ -21,6 +21,7 @@ SIG_VARIANT_TREE = 5
 SIG_VARIANT_MFMA_STREAM = 6
 SIG_VARIANT_ROW_STREAM = 7
 SIG_VARIANT_WIDE = 8
+SIG_VARIANT_DEPTH2 = 9
 SIG_MAX_DEPTH = 32
 
 # every symbol include/sig.h declares

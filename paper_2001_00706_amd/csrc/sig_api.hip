@@ -97,7 +97,7 @@ sig_status make_rows_shape(int64_t rows, int d, int N, sig::Shape &sh)
     return SIG_OK;
 }
 
-enum class Family { Generic, Mfma, MfmaShard, MfmaStream, MfmaD16, MfmaD8, Small, Tree, RowStream, Wide, None };
+enum class Family { Generic, Mfma, MfmaShard, MfmaStream, MfmaD16, MfmaD8, Small, Tree, RowStream, Wide, Depth2, None };
 
 // The pointers decide only alignment: the matrix-core family loads and stores 16 bytes per lane.
 Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const void *path, const void *out)
@@ -113,10 +113,12 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
     const bool small_ok = sig::small_supported(sh);
     const bool tree_ok = sig::tree_supported(sh);
     const bool wide_ok = sig::wide_supported(sh, dtype);
+    const bool depth2_ok = sig::forward_n2_supported(sh, dtype);
     const bool rows_any = sig::row_stream_supported(sh, dtype);
     const bool rows_ok = sh.stream && rows_any;
     switch (variant) {
         case SIG_VARIANT_AUTO:
+            if (depth2_ok) return Family::Depth2;   // depth 2 in final mode needs no scan
             // four wavefronts per path when one per path would leave most of the chip idle, when every
             // prefix is stored (stream mode) or when the state does not fit one wavefront (N = 7)
             if (stream_ok && sig::mfma_stream_preferred(sh)) return Family::MfmaStream;
@@ -154,6 +156,7 @@ Family resolve(const sig::Shape &sh, sig_dtype dtype, sig_variant variant, const
         case SIG_VARIANT_TREE: return tree_ok ? Family::Tree : Family::None;
         case SIG_VARIANT_ROW_STREAM: return rows_any ? Family::RowStream : Family::None;
         case SIG_VARIANT_WIDE: return wide_ok ? Family::Wide : Family::None;
+        case SIG_VARIANT_DEPTH2: return depth2_ok ? Family::Depth2 : Family::None;
     }
     return Family::None;
 }
@@ -181,6 +184,10 @@ hipError_t launch_scan(Family family, const sig::Shape &sh, sig_dtype dtype, con
             return dtype == SIG_F32
                        ? sig::launch_row_stream_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
                        : sig::launch_row_stream_f64(sh, static_cast<const double *>(path), static_cast<double *>(out), hip_stream);
+        case Family::Depth2:
+            return dtype == SIG_F32
+                       ? sig::launch_forward_n2_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
+                       : sig::launch_forward_n2_f64(sh, static_cast<const double *>(path), static_cast<double *>(out), hip_stream);
         case Family::Wide:
             return dtype == SIG_F32
                        ? sig::launch_wide_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
@@ -248,7 +255,7 @@ bool valid_enums(sig_dtype dtype, sig_variant variant)
     return (dtype == SIG_F32 || dtype == SIG_F64) &&
            (variant == SIG_VARIANT_AUTO || variant == SIG_VARIANT_GENERIC || variant == SIG_VARIANT_MFMA ||
             variant == SIG_VARIANT_MFMA_SHARD || variant == SIG_VARIANT_SMALL || variant == SIG_VARIANT_TREE ||
-            variant == SIG_VARIANT_MFMA_STREAM || variant == SIG_VARIANT_ROW_STREAM || variant == SIG_VARIANT_WIDE);
+            variant == SIG_VARIANT_MFMA_STREAM || variant == SIG_VARIANT_ROW_STREAM || variant == SIG_VARIANT_WIDE || variant == SIG_VARIANT_DEPTH2);
 }
 
 }  // namespace
@@ -809,6 +816,7 @@ const char *sig_variant_name(int64_t B, int64_t L, int d, int N, int stream, int
         case Family::Tree: return "tree";
         case Family::RowStream: return "row_stream";
         case Family::Wide: return "wide";
+        case Family::Depth2: return "depth2";
         case Family::Generic: return "generic";
         case Family::None: break;
     }

@@ -161,6 +161,11 @@ bool wide_supported(const Shape &sh, sig_dtype dtype);
 hipError_t launch_wide_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_wide_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
 
+// Depth-2 signature in final mode as a contraction over the increments (no scan; see sig_forward_n2.hip): any d.
+bool forward_n2_supported(const Shape &sh, sig_dtype dtype);
+hipError_t launch_forward_n2_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
+hipError_t launch_forward_n2_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
+
 // Gradient of the depth-2 signature in final mode by its closed form (no scan, no workspace; see sig_backward_n2.hip):
 // any channel count whose d x (d + 1) output gradient fits the LDS (d <= 122 in fp32, 85 in fp64).
 bool backward_n2_supported(const Shape &sh, sig_dtype dtype);

@@ -128,7 +128,7 @@ def test_validation_happens_before_any_device_work(lib):
     assert raw(dummy, 2, 4, 2, 2, 0, 0, sig.SIG_F32, 0, 0) == sig.SIG_ERR_INVALID_ARG
     assert raw(dummy, 2, 4, 1024, 5, 0, 0, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_OVERFLOW
     assert raw(dummy, 2 ** 40, 2 ** 30, 2, 20, 1, 0, sig.SIG_F32, dummy, 0) == sig.SIG_ERR_OVERFLOW
-    assert raw(dummy, 2, 4, 2, 2, 0, 0, sig.SIG_F32, dummy, 0, variant=9) == sig.SIG_ERR_INVALID_ARG
+    assert raw(dummy, 2, 4, 2, 2, 0, 0, sig.SIG_F32, dummy, 0, variant=99) == sig.SIG_ERR_INVALID_ARG
     # the matrix-core family is fp32 only
     assert raw(dummy, 2, 4, 4, 3, 0, 0, sig.SIG_F64, dummy, 0, variant=sig.SIG_VARIANT_MFMA) \
         == sig.SIG_ERR_UNSUPPORTED

@@ -85,8 +85,8 @@ def check(x, N, stream=False, basepoint=False, variant=sig.SIG_VARIANT_AUTO, sam
 
 VARIANTS = [sig.SIG_VARIANT_AUTO, sig.SIG_VARIANT_GENERIC, sig.SIG_VARIANT_MFMA, sig.SIG_VARIANT_MFMA_SHARD,
             sig.SIG_VARIANT_SMALL, sig.SIG_VARIANT_TREE, sig.SIG_VARIANT_MFMA_STREAM, sig.SIG_VARIANT_ROW_STREAM,
-            sig.SIG_VARIANT_WIDE]
-VARIANT_IDS = ["auto", "generic", "mfma", "mfma_shard", "small", "tree", "mfma_stream", "row_stream", "wide"]
+            sig.SIG_VARIANT_WIDE, sig.SIG_VARIANT_DEPTH2]
+VARIANT_IDS = ["auto", "generic", "mfma", "mfma_shard", "small", "tree", "mfma_stream", "row_stream", "wide", "depth2"]
 MODES = [(False, False), (False, True), (True, False), (True, True)]     # (stream, basepoint)
 
 
@@ -519,6 +519,43 @@ def test_chunked_stream_with_initial_and_inverse():
         np.testing.assert_allclose(got[:, j].cpu().numpy(), want, rtol=1e-9, atol=1e-12)
 
 
+# ------------------------------------------------------------------ depth 2 without a scan
+@pytest.mark.parametrize("B,L,d", [(3, 2, 5), (2, 3, 1), (37, 9, 2), (4, 40, 32), (1, 300, 7), (2, 9, 100), (20, 17, 16), (2, 130, 64),
+                                   (1, 70, 300), (5, 65, 3),
+                                   # enough paths that several share a workgroup, over two tiles and a ragged last group
+                                   (5000, 140, 2), (2100, 20, 4), (1100, 33, 6)])
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_depth_two_as_a_contraction_over_the_increments(B, L, d, dtype):
+    x = (brownian_paths(B, L, d, seed=L + d) + 0.3).astype(dtype)
+    for basepoint in (False, True):
+        assert check(x, 2, basepoint=basepoint, variant=sig.SIG_VARIANT_DEPTH2) is not None
+    assert sig.sig_variant_name(B, L, d, 2, False, False, sig.SIG_F32 if dtype == np.float32 else sig.SIG_F64) == "depth2"
+    # a basepoint given by value
+    import torch
+    bp = uniform_paths(B, 1, d, seed=d + 1)[:, 0].astype(dtype)
+    got = sig.sig_signature(torch.from_numpy(x).to("cuda:0"), 2, basepoint=torch.from_numpy(bp).to("cuda:0"))
+    torch.cuda.synchronize()
+    want = orc.signature(np.concatenate([bp[:, None], x], axis=1).astype(np.float64), 2)
+    batch, _ = level_errors(got.cpu().numpy(), want, d, 2)
+    assert np.all(batch <= TOL[dtype])
+
+
+@pytest.mark.parametrize("shift,dtype", [(1, np.float32), (2, np.float32), (1, np.float64)])   # 4, 8 and 8 bytes off
+def test_depth_two_on_a_path_that_starts_off_a_16_byte_boundary(shift, dtype):
+    # the staging loads are 16 bytes wide only where every point starts on such a boundary
+    import torch
+    B, L, d = 6, 50, 8
+    x = (brownian_paths(B, L, d, seed=3) - 0.1).astype(dtype)
+    flat = torch.empty(B * L * d + shift, dtype=torch.from_numpy(x).dtype, device="cuda:0")
+    dev = flat[shift:].view(B, L, d)
+    dev.copy_(torch.from_numpy(x))
+    assert dev.data_ptr() % 16 != 0 and dev.is_contiguous()
+    got = sig.sig_forward(dev, 2, variant=sig.SIG_VARIANT_DEPTH2)
+    torch.cuda.synchronize()
+    batch, _ = level_errors(got.cpu().numpy(), orc.signature(x.astype(np.float64), 2), d, 2)
+    assert np.all(batch <= TOL[dtype])
+
+
 # ------------------------------------------------------------------ many channels at low depth
 @pytest.mark.parametrize("B,L,d,N", [
     (3, 9, 20, 2), (2, 40, 32, 2), (37, 6, 18, 2),      # several paths per workgroup, a ragged last workgroup
@@ -535,7 +572,8 @@ def test_wide_channel_family(B, L, d, N, dtype):
         for basepoint in (False, True):
             assert check(x, N, stream=stream, basepoint=basepoint, variant=sig.SIG_VARIANT_WIDE) is not None
     if d > 16:   # ... and it is what serves these shapes
-        assert sig.sig_variant_name(B, L, d, N, False, False, code) == "wide"
+        assert sig.sig_variant_name(B, L, d, N, False, False, code) == ("depth2" if N == 2 else "wide")
+        assert sig.sig_variant_name(B, L, d, N, True, False, code) == "wide"
 
 
 # ------------------------------------------------------------------ prefix-tree family
