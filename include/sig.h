@@ -345,10 +345,11 @@ sig_status sig_lyndon_scatter(const void *grad_logsig, int64_t rows, int d, int 
  *   workspace  DEVICE pointer to at least sig_backward_workspace_bytes(...) bytes, 16-byte aligned, contents
  *              irrelevant on entry and undefined on return; may be NULL when that size is 0.  Calls that overlap
  *              in time must not share a workspace.
- * Enqueued on `hip_stream`, no wait.  d <= 64 and S < 2^30 (else SIG_ERR_UNSUPPORTED), except depth 2 in final mode,
- * which a closed form serves up to d = 122 (85 in fp64) and which is fast at any channel count: beyond 16 channels
- * every other gradient runs on a kernel two to three orders of magnitude slower per increment.  Other errors as for
- * sig_forward; a missing or short workspace is SIG_ERR_INVALID_ARG.  Deterministic. */
+ * Enqueued on `hip_stream`, no wait.  Served: d <= 16 at the depths of the register-resident and prefix-tree
+ * kernels; any d at N = 2..4 (up to 204 channels, 102 in fp64; depth 2 in final mode by a closed form up to d = 122,
+ * 85 in fp64); everything else with d <= 64 and S < 2^30 on a generic kernel that is two to three orders of
+ * magnitude slower per increment; otherwise SIG_ERR_UNSUPPORTED.  Other errors as for sig_forward; a missing or
+ * short workspace is SIG_ERR_INVALID_ARG.  Deterministic. */
 sig_status sig_backward(const void *path, const void *sig, const void *grad_out, int64_t B, int64_t L, int d, int N,
                         int stream, int basepoint, const void *basepoint_value, sig_dtype dtype, void *grad_path,
                         void *grad_basepoint, void *workspace, int64_t workspace_bytes, hipStream_t hip_stream);

@@ -306,6 +306,7 @@ int64_t backward_workspace_bytes(const Shape &sh, sig_dtype dtype)
     // signatures of up to 8 channels and depth 9 never reach the generic kernel
     if (backward_n2_supported(sh, dtype)) return 0;   // depth 2 in final mode: a closed form, nothing to keep
     if (tree_backward_supported(sh)) return tree_backward_workspace_bytes(sh, dtype);
+    if (wide_backward_supported(sh, dtype)) return wide_backward_workspace_bytes(sh, dtype);   // beyond 16 channels
     BackwardPlan pl;
     if (!backward_supported(sh) || !make_plan(sh, kBackwardThreads, pl)) return -1;
     const bool lds = dtype == SIG_F32 ? fits_lds<float>(pl) : fits_lds<double>(pl);
@@ -340,6 +341,8 @@ hipError_t launch_backward_f32(const Shape &sh, const float *path, const float *
         return launch_backward_d16_f32(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
     if (tree_backward_supported(sh))
         return launch_tree_backward_f32(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
+    if (wide_backward_supported(sh, SIG_F32))
+        return launch_wide_backward_f32(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
     return launch_backward<float>(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
 }
 
@@ -349,6 +352,8 @@ hipError_t launch_backward_f64(const Shape &sh, const double *path, const double
     if (backward_n2_supported(sh, SIG_F64)) return launch_backward_n2_f64(sh, path, gout, gpath, gbase, st);
     if (tree_backward_supported(sh))
         return launch_tree_backward_f64(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
+    if (wide_backward_supported(sh, SIG_F64))
+        return launch_wide_backward_f64(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
     return launch_backward<double>(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
 }
 

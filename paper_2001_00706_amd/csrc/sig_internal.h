@@ -166,6 +166,15 @@ bool forward_n2_supported(const Shape &sh, sig_dtype dtype);
 hipError_t launch_forward_n2_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_forward_n2_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
 
+// Gradient for many channels at low depth (any d at N = 2..4, both modes; see sig_wide_backward.hip); the workspace
+// holds one partial gradient per workgroup of a path.
+bool wide_backward_supported(const Shape &sh, sig_dtype dtype);
+int64_t wide_backward_workspace_bytes(const Shape &sh, sig_dtype dtype);
+hipError_t launch_wide_backward_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
+                                    float *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st);
+hipError_t launch_wide_backward_f64(const Shape &sh, const double *path, const double *sig, const double *gout, double *gpath,
+                                    double *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st);
+
 // Gradient of the depth-2 signature in final mode by its closed form (no scan, no workspace; see sig_backward_n2.hip):
 // any channel count whose d x (d + 1) output gradient fits the LDS (d <= 122 in fp32, 85 in fp64).
 bool backward_n2_supported(const Shape &sh, sig_dtype dtype);

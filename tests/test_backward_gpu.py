@@ -220,6 +220,21 @@ def test_depth_two_gradient_by_its_closed_form(B, L, d, dtype):
     assert np.linalg.norm(gb.cpu().numpy() - want[:, 0]) <= tol * np.linalg.norm(want)
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("B,L,d,N", [
+    (2, 9, 17, 3), (1, 40, 20, 3),    # a last block of one letter; three tiles of increments
+    (3, 5, 33, 2), (1, 6, 70, 2),     # depth 2 (stream mode; final mode has its closed form): 3 and 5 blocks of letters
+    (2, 7, 40, 3), (1, 4, 18, 4),     # 75 and 365 wavefronts per path
+])
+def test_many_channels_at_low_depth(B, L, d, N, dtype):
+    x = uniform_paths(B, L, d, seed=4000 + L + d, lo=-0.4, hi=0.4).astype(dtype)
+    code = sig.SIG_F32 if dtype == np.float32 else sig.SIG_F64
+    for stream in (False, True):
+        assert sig.sig_backward_workspace_bytes(B, L, d, N, stream, False, code) >= 0
+        for basepoint in (False, True):
+            check(x, N, stream=stream, basepoint=basepoint)
+
+
 def test_unsupported_and_invalid_arguments():
     import torch
     x = torch.zeros((1, 3, 65), device="cuda:0")
@@ -250,16 +265,18 @@ def test_zero_increments_and_repeated_points():
     check(np.zeros((2, 5, 3)), 3, stream=True)
 
 
-def test_deterministic_and_inputs_untouched():
+@pytest.mark.parametrize("B,L,d,N", [(6, 30, 4, 5), (3, 40, 20, 3)])   # the second: sums through LDS atomic adds
+def test_deterministic_and_inputs_untouched(B, L, d, N):
     import torch
-    x = torch.from_numpy(brownian_paths(6, 30, 4, seed=3)).to("cuda:0")
-    s = sig.sig_forward(x, 5)
+    x = torch.from_numpy(brownian_paths(B, L, d, seed=3)).to("cuda:0")
+    s = sig.sig_forward(x, N)
     g = torch.randn_like(s)
     x0, s0, g0 = x.clone(), s.clone(), g.clone()
-    a = sig.sig_backward(x, s, g, 5).clone()
-    b = sig.sig_backward(x, s, g, 5)
-    torch.cuda.synchronize()
-    assert torch.equal(a, b)
+    a = sig.sig_backward(x, s, g, N).clone()
+    for _ in range(3):
+        b = sig.sig_backward(x, s, g, N)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b)
     assert torch.equal(x, x0) and torch.equal(s, s0) and torch.equal(g, g0)
 
 
