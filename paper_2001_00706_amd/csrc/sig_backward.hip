@@ -301,10 +301,21 @@ bool backward_supported(const Shape &sh)
     return sh.d <= 64 && make_plan(sh, kBackwardThreads, pl);
 }
 
+// Final mode at depths 3 and 4 from 9 channels on, where the prefix-tree kernels also keep one level per thread: the
+// kernel for many channels is ahead from 12 channels on (128 points, N = 3, d = 16: 98 us against 274 at 32 paths, 183
+// against 336 at 1024; d = 12, N = 4: 144 against 261 and 1260 against 1500) and below 256 paths from 9 on (d = 9,
+// N = 3: 128 against 167 at 32 paths, 204 against 176 at 1024).  d = 16, N = 4 has a kernel of its own.
+bool wide_backward_preferred(const Shape &sh, sig_dtype dtype)
+{
+    return !sh.stream && (sh.N == 3 || sh.N == 4) && sh.d >= 9 && sh.d <= 16 && (sh.d >= 12 || sh.B < 256) &&
+           !(sh.d == 16 && sh.N == 4) && wide_backward_supported(sh, dtype);
+}
+
 int64_t backward_workspace_bytes(const Shape &sh, sig_dtype dtype)
 {
     // signatures of up to 8 channels and depth 9 never reach the generic kernel
     if (backward_n2_supported(sh, dtype)) return 0;   // depth 2 in final mode: a closed form, nothing to keep
+    if (wide_backward_preferred(sh, dtype)) return wide_backward_workspace_bytes(sh, dtype);
     if (tree_backward_supported(sh)) return tree_backward_workspace_bytes(sh, dtype);
     if (wide_backward_supported(sh, dtype)) return wide_backward_workspace_bytes(sh, dtype);   // beyond 16 channels
     BackwardPlan pl;
@@ -339,6 +350,8 @@ hipError_t launch_backward_f32(const Shape &sh, const float *path, const float *
     if (aligned && backward_d16_supported(sh) && workspace != nullptr && workspace_bytes >= backward_d16_workspace_bytes(sh) &&
         reinterpret_cast<uintptr_t>(workspace) % 16 == 0)
         return launch_backward_d16_f32(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
+    if (wide_backward_preferred(sh, SIG_F32))
+        return launch_wide_backward_f32(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
     if (tree_backward_supported(sh))
         return launch_tree_backward_f32(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
     if (wide_backward_supported(sh, SIG_F32))
@@ -350,6 +363,8 @@ hipError_t launch_backward_f64(const Shape &sh, const double *path, const double
                                double *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st)
 {
     if (backward_n2_supported(sh, SIG_F64)) return launch_backward_n2_f64(sh, path, gout, gpath, gbase, st);
+    if (wide_backward_preferred(sh, SIG_F64))
+        return launch_wide_backward_f64(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
     if (tree_backward_supported(sh))
         return launch_tree_backward_f64(sh, path, sig, gout, gpath, gbase, workspace, workspace_bytes, st);
     if (wide_backward_supported(sh, SIG_F64))

@@ -12,9 +12,9 @@
 //   * The 64 lanes of a wavefront share their block of letters.  Their 16 x 64 products are summed over the lanes by a
 //     butterfly that halves the number of values a lane still holds at every step (15 exchanges instead of 96), then
 //     over the four rows of 16 lanes.
-//   * A wavefront adds its sums and the scalars of its lanes' words into its own LDS row of the increment (LDS atomic
-//     adds: lanes whose words share a letter meet there, and nothing else writes to that row meanwhile); at the end
-//     of a tile the rows of the workgroup's four
+//   * A wavefront adds its sums and the scalars of its lanes' words into its own LDS row of the increment (lanes whose
+//     words share a letter are summed first; nothing else writes to that row meanwhile); at the end of a tile the
+//     rows of the workgroup's four
 //     wavefronts are added in a fixed order and written to a workspace [path][workgroup][increment][d].
 //   * A second kernel adds the workgroups' partial sums and turns gradients of increments into gradients of points.
 #include "sig_internal.h"
@@ -53,6 +53,45 @@ __device__ __forceinline__ T row_transpose_sum(const T (&a)[16], int lane)
     return (b0 ? s2[1] : s2[0]) + neighbour<1>(b0 ? s2[0] : s2[1]);
 }
 
+// v summed over the four rows of 16 lanes, in every lane, with the two row swaps of this device (odd rows of one
+// register against even rows of another; the upper two rows against the lower two) on two copies of the value.
+struct WbPair {
+    unsigned first, second;
+};
+
+__device__ __forceinline__ WbPair swap_rows_16(unsigned v)
+{
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    const u2 r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return {r[0], r[1]};   // as scalars: a bit cast of a vector element reads the vector's first one
+}
+
+__device__ __forceinline__ WbPair swap_rows_32(unsigned v)
+{
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    const u2 r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return {r[0], r[1]};
+}
+
+__device__ __forceinline__ float rows_sum(float v)
+{
+    const WbPair r = swap_rows_16(__builtin_bit_cast(unsigned, v));
+    const float s = __builtin_bit_cast(float, r.first) + __builtin_bit_cast(float, r.second);
+    const WbPair q = swap_rows_32(__builtin_bit_cast(unsigned, s));
+    return __builtin_bit_cast(float, q.first) + __builtin_bit_cast(float, q.second);
+}
+
+__device__ __forceinline__ double rows_sum(double v)
+{
+    const auto low = [](double x) { return unsigned(__builtin_bit_cast(unsigned long long, x)); };
+    const auto high = [](double x) { return unsigned(__builtin_bit_cast(unsigned long long, x) >> 32); };
+    const auto whole = [](unsigned lo, unsigned hi) { return __builtin_bit_cast(double, (unsigned long long)(hi) << 32 | lo); };
+    const WbPair rl = swap_rows_16(low(v)), rh = swap_rows_16(high(v));
+    const double s = whole(rl.first, rh.first) + whole(rl.second, rh.second);
+    const WbPair ql = swap_rows_32(low(s)), qh = swap_rows_32(high(s));
+    return whole(ql.first, qh.first) + whole(ql.second, qh.second);
+}
+
 template <typename T, int N, bool STREAM>
 __global__ void __launch_bounds__(256)
 sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const T *__restrict__ sig,
@@ -88,13 +127,20 @@ sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const 
             width *= d;
         }
     }
-    bool with_leader[P + 1];   // whether letter i is that of the first lane of this lane's row of 16
+    // Words that share an earlier letter lie side by side, in runs of at least d words: where d >= 16 a row of 16 lanes
+    // holds at most two such letters, that of its first lane and that of its last.
+    bool with_first[P + 1], with_last[P + 1];   // whether letter i of this lane's word is the one or (else) the other
+    int first_letter[P + 1], last_letter[P + 1];
     {
-        int64_t rest = u - (lane & 15);   // that lane's word (live whenever this one is)
+        int64_t rest_first = u_raw - (lane & 15), rest_last = rest_first + 15;
 #pragma unroll
         for (int i = P; i >= 1; --i) {
-            with_leader[i] = live && cl[i] == int(rest % d);
-            rest /= d;
+            first_letter[i] = int(rest_first % d);
+            last_letter[i] = int(rest_last % d);
+            with_first[i] = live && cl[i] == first_letter[i];
+            with_last[i] = live && !with_first[i] && cl[i] == last_letter[i];
+            rest_first /= d;
+            rest_last /= d;
         }
     }
     T rk[N + 2];
@@ -229,19 +275,33 @@ sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const 
 
             // ---- this wavefront's part of the increment's gradient
             T *acc_row = my_part + i * 4 * pl.dpad;
-            T total = row_transpose_sum(dzb, lane);
-            total += neighbour<16>(total);
-            total += neighbour<32>(total);
-            if (lane < kWbBlock) atomicAdd(acc_row + j0 + lane, total);
-            // Words that share an earlier letter lie side by side: a row of 16 lanes first sums the scalars of the lanes
-            // that have its first lane's letter, so that few lanes meet at one address (all 64 would otherwise).
+            // A float add in LDS takes about 3 clocks per active lane whether or not the lanes meet, a plain read or
+            // write of 64 lanes about 6 in all: atomic adds are kept for the few lanes that may meet at an address,
+            // everything else is brought to distinct lanes first and added by a read and a write.
+            {
+                const T total = rows_sum(row_transpose_sum(dzb, lane));
+                if (lane < kWbBlock) acc_row[j0 + lane] += total;
+            }
+            // earlier letters: a row's two sums, added by its first and its last lane (rows may share a letter)
 #pragma unroll
             for (int j = 1; j < P; ++j) {
-                const T row_total = group_sum<0, 4, T>(with_leader[j] ? chain[j] : T(0));
-                if (live && (lane & 15) == 0) atomicAdd(acc_row + cl[j], row_total);
-                if (live && !with_leader[j]) atomicAdd(acc_row + cl[j], chain[j]);
+                const T of_first = group_sum<0, 4, T>(with_first[j] ? chain[j] : T(0));
+                const T of_last = group_sum<0, 4, T>(with_last[j] ? chain[j] : T(0));
+                const int pos = lane & 15;
+                if (pos == 0 || pos == 15)
+                    atomicAdd(acc_row + (pos == 0 ? first_letter[j] : last_letter[j]), pos == 0 ? of_first : of_last);
+                if (live && !with_first[j] && !with_last[j]) atomicAdd(acc_row + cl[j], chain[j]);   // only where d < 16
             }
-            if (live) atomicAdd(acc_row + cl[P], chain[P]);
+            // last letter: consecutive words have consecutive letters, lanes d apart share one
+            {
+                T mine = live ? chain[P] : T(0);
+                const T own = mine;
+                for (int k = d; k < 64; k += d) {
+                    const T other = __shfl_down(own, unsigned(k));
+                    mine += lane + k < 64 ? other : T(0);
+                }
+                if (live && lane < d) acc_row[cl[P]] += mine;
+            }
 
             if constexpr (STREAM) {
                 if (s > 0) {
