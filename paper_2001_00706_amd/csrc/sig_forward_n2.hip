@@ -18,7 +18,7 @@
 namespace sig {
 namespace {
 
-constexpr int kBatch = 4;   // staging loads a thread has in flight
+constexpr int kBatch = 4;   // staging loads a thread has in flight: a tile is at most 256 * kBatch loads
 
 struct N2Plan {
     int dq;                   // ceil(d / 4): blocks per row of level 2
@@ -79,29 +79,47 @@ sig_forward_n2_kernel(Shape sh, N2Plan pl, const T *__restrict__ path, T *__rest
 #pragma unroll
         for (int b = 0; b < 4; ++b) acc[a][b] = T(0);
     T4 p_i = T4(0);
-    const int staged = pl.paths_per_group * rows * cvecs;
+    const int staged = pl.paths_per_group * rows * cvecs;   // at most 256 * kBatch: a tile is one batch of loads
+    // Every load is unconditional, on indices clamped into a path, so that the loads of a tile are in flight together;
+    // rows past the end of the batch, points past the end of the path and the padding behind the last channel become
+    // zeros when the tile is written to LDS.  The loads of the next tile are issued before this tile's arithmetic.
+    // Which point of which path an entry of the tile holds does not change from tile to tile: worked out once.
+    TV held[kBatch];
+    const T *entry_row[kBatch];   // channel c of point 0 of the entry's path (of path 0 for entries that stay zero)
+    int entry_point[kBatch];      // the entry's point inside the tile
+    bool entry_on[kBatch];
+    const T *entry_base[kBatch];  // the entry's channels of a basepoint given by value
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) {
+        const int e = 256 * k + tid < staged ? 256 * k + tid : staged - 1;
+        const int p = e / (rows * cvecs), rem = e - p * rows * cvecs, pt = rem / cvecs, c = (rem - pt * cvecs) * V;
+        entry_on[k] = row0 + p < sh.B && c < d;
+        entry_point[k] = pt;
+        entry_row[k] = path + (entry_on[k] ? (row0 + p) * sh.L * d + c : 0);
+        entry_base[k] = bpv != nullptr && entry_on[k] ? bpv + (row0 + p) * d + c : bpv;
+    }
+    const auto load_tile = [&](int64_t t0) {
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) {
+            if (256 * k >= staged) break;   // the same for every thread
+            const int64_t point = t0 + entry_point[k];
+            const bool on = entry_on[k] && point <= sh.n_inc;
+            const bool from_base = on && sh.basepoint && point == 0;
+            const T *src = from_base && bpv != nullptr ? entry_base[k] : entry_row[k] + (on && !from_base ? point - shift : 0) * d;
+            held[k] = *reinterpret_cast<const TV *>(src);
+        }
+    };
+    load_tile(0);
     for (int64_t t0 = 0; t0 < sh.n_inc; t0 += pl.tile) {
         __syncthreads();
-        // kBatch loads per thread at a time, every one unconditional on indices clamped into a path, so that the loads
-        // of a batch are in flight together; rows past the end of the batch, points past the end of the path and the
-        // padding behind the last channel are zeros
-        for (int e0 = 0; e0 < staged; e0 += 256 * kBatch) {
-            TV v[kBatch];
-            bool on[kBatch];
 #pragma unroll
-            for (int k = 0; k < kBatch; ++k) {
-                if (e0 + 256 * k >= staged) break;   // the same for every thread
-                const int e = e0 + 256 * k + tid < staged ? e0 + 256 * k + tid : staged - 1;
-                const int p = e / (rows * cvecs), rem = e - p * rows * cvecs, s = rem / cvecs, c = (rem - s * cvecs) * V;
-                on[k] = row0 + p < sh.B && t0 + s <= sh.n_inc && c < d;
-                v[k] = scan_point(on[k] ? row0 + p : 0, on[k] ? t0 + s : shift, on[k] ? c : 0);
-            }
-#pragma unroll
-            for (int k = 0; k < kBatch; ++k) {
-                const int e = e0 + 256 * k + tid;
-                if (e0 + 256 * k < staged && e < staged) *reinterpret_cast<TV *>(pts + int64_t(e) * V) = on[k] ? v[k] : TV(0);
-            }
+        for (int k = 0; k < kBatch; ++k) {
+            if (256 * k >= staged) break;
+            const int64_t point = t0 + entry_point[k];
+            const bool zero = !entry_on[k] || point > sh.n_inc || (sh.basepoint && point == 0 && bpv == nullptr);
+            if (256 * k + tid < staged) *reinterpret_cast<TV *>(pts + int64_t(256 * k + tid) * V) = zero ? TV(0) : held[k];
         }
+        if (t0 + pl.tile < sh.n_inc) load_tile(t0 + pl.tile);
         __syncthreads();
         if (t0 == 0) p_i = *reinterpret_cast<const T4 *>(start + slot * dpad + 4 * ib);
         const T *lp = pts + slot * rows * dpad + 4 * ib, *rp = pts + slot * rows * dpad + 4 * jb;
@@ -196,6 +214,10 @@ bool n2_plan(const Shape &sh, size_t elem, const void *path, N2Plan &pl)
             break;
         }
     }
+    // ... and within one batch of loads: (tile + 1) points of dpad / vec loads each for every path of the workgroup
+    const int64_t loads_per_point = int64_t(pl.paths_per_group) * (4 * pl.dq / pl.vec);
+    if (2 * loads_per_point > 256 * kBatch) return false;
+    if ((pl.tile + 1) * loads_per_point > 256 * kBatch) pl.tile = int(256 * kBatch / loads_per_point) - 1;
     const int64_t groups = blocks >= 256 ? sh.B * pl.groups_per_path : (sh.B + pl.paths_per_group - 1) / pl.paths_per_group;
     return groups <= 0x7fffffff && n2_lds(pl, elem) <= 64 * 1024;
 }
