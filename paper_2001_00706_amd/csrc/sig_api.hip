@@ -185,6 +185,12 @@ hipError_t launch_scan(Family family, const sig::Shape &sh, sig_dtype dtype, con
                        ? sig::launch_row_stream_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
                        : sig::launch_row_stream_f64(sh, static_cast<const double *>(path), static_cast<double *>(out), hip_stream);
         case Family::Depth2:
+            // From 49 channels on, where padding to whole 16 x 16 tiles adds at most 30 % of work, the contraction runs
+            // on the matrix cores (fp32; d = 64: 1.2 to 1.6 times the vector kernel from 32 to 16 384 paths).
+            if (dtype == SIG_F32 && sig::forward_n2_mfma_preferred(sh)) {
+                const hipError_t err = sig::launch_forward_n2_mfma_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream);
+                if (err != hipErrorNotSupported) return err;
+            }
             return dtype == SIG_F32
                        ? sig::launch_forward_n2_f32(sh, static_cast<const float *>(path), static_cast<float *>(out), hip_stream)
                        : sig::launch_forward_n2_f64(sh, static_cast<const double *>(path), static_cast<double *>(out), hip_stream);

@@ -165,6 +165,11 @@ hipError_t launch_wide_f64(const Shape &sh, const double *path, double *out, hip
 bool forward_n2_supported(const Shape &sh, sig_dtype dtype);
 hipError_t launch_forward_n2_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_forward_n2_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
+// The same on the matrix cores (fp32, 17 to 256 channels; see sig_forward_n2_mfma.hip).  The launch returns
+// hipErrorNotSupported, with nothing enqueued, where unaligned buffers leave no room for a tile of four increments.
+bool forward_n2_mfma_supported(const Shape &sh);
+bool forward_n2_mfma_preferred(const Shape &sh);   // ... and measured faster than the vector kernel
+hipError_t launch_forward_n2_mfma_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 
 // Gradient for many channels at low depth (any d at N = 2..4, both modes; see sig_wide_backward.hip); the workspace
 // holds one partial gradient per workgroup of a path.

@@ -523,7 +523,10 @@ def test_chunked_stream_with_initial_and_inverse():
 @pytest.mark.parametrize("B,L,d", [(3, 2, 5), (2, 3, 1), (37, 9, 2), (4, 40, 32), (1, 300, 7), (2, 9, 100), (20, 17, 16), (2, 130, 64),
                                    (1, 70, 300), (5, 65, 3),
                                    # enough paths that several share a workgroup, over two tiles and a ragged last group
-                                   (5000, 140, 2), (2100, 20, 4), (1100, 33, 6)])
+                                   (5000, 140, 2), (2100, 20, 4), (1100, 33, 6),
+                                   # fp32 on the matrix cores: 4, 5, 8 and 16 tiles per side, several staged tiles, a
+                                   # last step of 1, 2 and 3 increments
+                                   (3, 50, 60), (2, 14, 75), (1, 40, 128), (2, 7, 250), (300, 6, 64)])
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 def test_depth_two_as_a_contraction_over_the_increments(B, L, d, dtype):
     x = (brownian_paths(B, L, d, seed=L + d) + 0.3).astype(dtype)
@@ -544,7 +547,13 @@ def test_depth_two_as_a_contraction_over_the_increments(B, L, d, dtype):
 def test_depth_two_on_a_path_that_starts_off_a_16_byte_boundary(shift, dtype):
     # the staging loads are 16 bytes wide only where every point starts on such a boundary
     import torch
-    B, L, d = 6, 50, 8
+    _depth_two_off_boundary(6, 50, 8, shift, dtype)
+    _depth_two_off_boundary(3, 11, 64, shift, dtype)   # fp32: the matrix-core kernel
+    _depth_two_off_boundary(2, 7, 250, shift, dtype)   # ... which steps aside where scalar loads leave no room for a tile
+
+
+def _depth_two_off_boundary(B, L, d, shift, dtype):
+    import torch
     x = (brownian_paths(B, L, d, seed=3) - 0.1).astype(dtype)
     flat = torch.empty(B * L * d + shift, dtype=torch.from_numpy(x).dtype, device="cuda:0")
     dev = flat[shift:].view(B, L, d)
