@@ -329,6 +329,9 @@ int64_t backward_workspace_bytes(const Shape &sh, sig_dtype dtype)
 hipError_t launch_backward_f32(const Shape &sh, const float *path, const float *sig, const float *gout, float *gpath,
                                float *gbase, void *workspace, int64_t workspace_bytes, hipStream_t st)
 {
+    // depth 2 in final mode: the closed form, from 8 channels on as a product on the matrix cores (1024 paths of 128
+    // points: d = 16: 14.5 us against 24, d = 64: 50 against 192, d = 100: 136 against 665)
+    if (backward_n2_mfma_supported(sh)) return launch_backward_n2_mfma_f32(sh, path, gout, gpath, gbase, st);
     if (backward_n2_supported(sh, SIG_F32)) return launch_backward_n2_f32(sh, path, gout, gpath, gbase, st);
     const bool aligned = (reinterpret_cast<uintptr_t>(path) | reinterpret_cast<uintptr_t>(sig) |
                           reinterpret_cast<uintptr_t>(gout) | reinterpret_cast<uintptr_t>(sh.basepoint_value)) % 16 == 0;

@@ -183,6 +183,10 @@ hipError_t launch_wide_backward_f64(const Shape &sh, const double *path, const d
 // Gradient of the depth-2 signature in final mode by its closed form (no scan, no workspace; see sig_backward_n2.hip):
 // any channel count whose d x (d + 1) output gradient fits the LDS (d <= 122 in fp32, 85 in fp64).
 bool backward_n2_supported(const Shape &sh, sig_dtype dtype);
+// ... and on the matrix cores (fp32, 8 to 112 channels; see sig_backward_n2_mfma.hip)
+bool backward_n2_mfma_supported(const Shape &sh);
+hipError_t launch_backward_n2_mfma_f32(const Shape &sh, const float *path, const float *gout, float *gpath, float *gbase,
+                                       hipStream_t st);
 hipError_t launch_backward_n2_f32(const Shape &sh, const float *path, const float *gout, float *gpath, float *gbase, hipStream_t st);
 hipError_t launch_backward_n2_f64(const Shape &sh, const double *path, const double *gout, double *gpath, double *gbase,
                                   hipStream_t st);

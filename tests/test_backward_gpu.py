@@ -196,10 +196,13 @@ def test_short_workspace_of_the_prefix_tree_kernels_is_refused():
 # ---- depth 2 in final mode: the closed form (no scan), any channel count up to 122 (85 in fp64)
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 @pytest.mark.parametrize("B,L,d", [(3, 2, 5), (2, 3, 1), (4, 40, 32), (1, 300, 7), (2, 9, 100), (5, 17, 16), (2, 130, 64), (3, 5, 85),
-                                   (2, 260, 3)])
+                                   (2, 260, 3),
+                                   # fp32 from 8 channels on: the matrix-core kernel; two points only, several workgroups
+                                   # per path, several rounds per workgroup, rounds of 16 points
+                                   (3, 2, 24), (2, 700, 40), (1200, 200, 9), (2, 50, 112), (3, 3, 8)])
 def test_depth_two_gradient_by_its_closed_form(B, L, d, dtype):
     import torch
-    if d == 100 and dtype == np.float64:   # 100 x 101 doubles do not fit the LDS, and no other gradient kernel takes d > 64
+    if d >= 100 and dtype == np.float64:   # 100 x 101 doubles do not fit the LDS, and no other fp64 gradient kernel takes them
         assert sig.sig_backward_workspace_bytes(B, L, d, 2, False, False, sig.SIG_F64) == -1
         return
     x = (brownian_paths(B, L, d, seed=L + d) + 0.3).astype(dtype)
