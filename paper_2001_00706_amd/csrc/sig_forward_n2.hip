@@ -14,6 +14,7 @@
 // Paths with fewer than 256 blocks share a workgroup once there are enough workgroups; threads left over split a
 // tile's increments between them and add their partial sums up through LDS at the end.
 #include "sig_internal.h"
+#include "sig_lane_ops.h"
 
 namespace sig {
 namespace {
@@ -111,7 +112,7 @@ sig_forward_n2_kernel(Shape sh, N2Plan pl, const T *__restrict__ path, T *__rest
     };
     load_tile(0);
     for (int64_t t0 = 0; t0 < sh.n_inc; t0 += pl.tile) {
-        __syncthreads();
+        lds_barrier();   // not __syncthreads(): the loads of the next tile stay in flight
 #pragma unroll
         for (int k = 0; k < kBatch; ++k) {
             if (256 * k >= staged) break;
@@ -120,7 +121,7 @@ sig_forward_n2_kernel(Shape sh, N2Plan pl, const T *__restrict__ path, T *__rest
             if (256 * k + tid < staged) *reinterpret_cast<TV *>(pts + int64_t(256 * k + tid) * V) = zero ? TV(0) : held[k];
         }
         if (t0 + pl.tile < sh.n_inc) load_tile(t0 + pl.tile);
-        __syncthreads();
+        lds_barrier();
         if (t0 == 0) p_i = *reinterpret_cast<const T4 *>(start + slot * dpad + 4 * ib);
         const T *lp = pts + slot * rows * dpad + 4 * ib, *rp = pts + slot * rows * dpad + 4 * jb;
         const int nt = int(sh.n_inc - t0 < pl.tile ? sh.n_inc - t0 : pl.tile);

@@ -12,6 +12,7 @@
 // bounded the kernel).  The tile of points is staged as in the vector kernel: the next tile's loads are issued before
 // this tile's arithmetic.
 #include "sig_internal.h"
+#include "sig_lane_ops.h"
 
 #include <type_traits>
 
@@ -47,7 +48,8 @@ sig_forward_n2_mfma_kernel(Shape sh, N2mPlan pl, const float *__restrict__ path,
     float *pts = reinterpret_cast<float *>(n2m_smem);        // [paths_per_group][tile + 1][stride]: points of the scan
     float *start = pts + pl.paths_per_group * rows * stride;   // [paths_per_group][stride]: p
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: what follows from it is uniform
     const bool shared_group = pl.paths_per_group > 1 || pl.groups_per_path == 1;
     const int slot = pl.paths_per_group > 1 ? wave / pl.items : 0;
     const int item = pl.paths_per_group > 1 ? wave - slot * pl.items : int(blockIdx.x % pl.groups_per_path) * 4 + wave;
@@ -114,7 +116,7 @@ sig_forward_n2_mfma_kernel(Shape sh, N2mPlan pl, const float *__restrict__ path,
     float p_i = 0.f;
     load_tile(0);
     for (int64_t t0 = 0; t0 < sh.n_inc; t0 += pl.tile) {
-        __syncthreads();
+        lds_barrier();   // not __syncthreads(): the loads of the next tile stay in flight
 #pragma unroll
         for (int k = 0; k < kN2mBatch; ++k) {
             if (256 * k >= staged) break;
@@ -126,7 +128,7 @@ sig_forward_n2_mfma_kernel(Shape sh, N2mPlan pl, const float *__restrict__ path,
             }
         }
         if (t0 + pl.tile < sh.n_inc) load_tile(t0 + pl.tile);
-        __syncthreads();
+        lds_barrier();
         if (t0 == 0) p_i = start[slot * stride + n2m_pos(16 * ti + c16)];
         const int nt = int(sh.n_inc - t0 < pl.tile ? sh.n_inc - t0 : pl.tile);
         if (live) {

@@ -48,6 +48,15 @@ __device__ __forceinline__ T group_sum(T v)
     }
 }
 
+// A workgroup barrier that orders the LDS traffic only: __syncthreads() would also wait for the global loads and stores a
+// wavefront has in flight, which is the latency a kernel that fetches its next tile ahead is built to hide.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 }  // namespace sig
 
 #endif  // SIG_LANE_OPS_H_
