@@ -4,31 +4,31 @@
 //
 // Arithmetic of the prefix-tree family (paper section 4.1, eq. "fusedterm": the new coefficient of a word needs the
 // coefficients of that word's prefixes only) with the channel count a run-time value: a thread stands for a word u of
-// N - 1 letters and a block of 16 last letters, carries the coefficients of u and of its prefixes (every thread below a
+// N - 1 letters and a block of 16 (32, 64) last letters, carries the coefficients of u and of its prefixes (every thread below a
 // prefix updates its own copy identically) and keeps the 16 top-level coefficients u j, j in its block, in
-// registers.  Nothing is exchanged between threads, so the d^(N-1) * ceil(d / 16) threads of a path may sit in any
+// registers.  Nothing is exchanged between threads, so the d^(N-1) * ceil(d / block) threads of a path may sit in any
 // number of workgroups; paths with fewer than 256 threads share a workgroup.  The chain along the word is repeated
-// by the ceil(d / 16) threads of a word: a few multiply-adds against 16.
+// by the ceil(d / block) threads of a word: a few multiply-adds against the block's 16 to 64.
 #include "sig_internal.h"
 
 namespace sig {
 namespace {
 
-constexpr int kWideBlock = 16;   // last letters per thread
 constexpr int kWideTile = 32;    // increments staged in LDS at a time
 
 __device__ __forceinline__ float wide_fma(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
 __device__ __forceinline__ double wide_fma(double a, double b, double c) { return __builtin_fma(a, b, c); }
 
 struct WidePlan {
-    int jblocks;              // ceil(d / 16)
-    int dpad;                 // jblocks * 16: floats per staged increment (zeros behind the d-th)
+    int block;                // last letters per thread: 16, 32 or 64
+    int jblocks;              // ceil(d / block)
+    int dpad;                 // jblocks * block: floats per staged increment (zeros behind the d-th)
     int64_t threads;          // threads per path: d^(N-1) * jblocks
     int paths_per_group;      // paths sharing a workgroup (1 when a path has 256 threads or more)
     int64_t groups_per_path;  // workgroups per path (1 when paths share a workgroup)
 };
 
-template <typename T, int N>
+template <typename T, int N, int WB>   // WB: last letters per thread, 16 or 32
 __global__ void __launch_bounds__(256)
 sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict__ out)
 {
@@ -47,7 +47,7 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
     const bool live = t < pl.threads && slot_raw < pl.paths_per_group && row < sh.B;
     const int64_t u = (live ? t : 0) / pl.jblocks;          // the word of N - 1 letters
     const int jb = int((live ? t : 0) - u * pl.jblocks);    // the block of last letters
-    const int j0 = jb * kWideBlock;
+    const int j0 = jb * WB;
 
     int cl[P + 1];   // letters of the word
     {
@@ -63,11 +63,11 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
     for (int m = 1; m <= N + 1; ++m) rk[m] = T(1) / T(m);
 
     T A[P + 1];             // coefficients of the prefixes of the word, and of the word itself (level N - 1)
-    T top[kWideBlock];      // words u j, j = j0 .. j0 + 15
+    T top[WB];              // words u j, j = j0 .. j0 + WB - 1
 #pragma unroll
     for (int i = 0; i <= P; ++i) A[i] = T(0);
 #pragma unroll
-    for (int c = 0; c < kWideBlock; ++c) top[c] = T(0);
+    for (int c = 0; c < WB; ++c) top[c] = T(0);
 
     const T *bpv = static_cast<const T *>(sh.basepoint_value);
     const int64_t n_inc = sh.n_inc;
@@ -88,11 +88,11 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
             }
         }
         T *o_top = o + sh.off[N] + u * d + j0;
-        if (vec_ok && j0 + kWideBlock <= d) {   // 16 bytes per store instead of one scalar
+        if (vec_ok && j0 + WB <= d) {   // 16 bytes per store instead of one scalar
             constexpr int kVec = 16 / int(sizeof(T));
             typedef T TV __attribute__((ext_vector_type(kVec)));
 #pragma unroll
-            for (int c = 0; c < kWideBlock; c += kVec) {
+            for (int c = 0; c < WB; c += kVec) {
                 TV v;
 #pragma unroll
                 for (int k = 0; k < kVec; ++k) v[k] = top[c + k];
@@ -100,7 +100,7 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
             }
         } else {
 #pragma unroll
-            for (int c = 0; c < kWideBlock; ++c)
+            for (int c = 0; c < WB; ++c)
                 if (j0 + c < d) o_top[c] = top[c];
         }
     };
@@ -156,7 +156,12 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
                 for (int k = i + 1; k <= N; ++k) Hn[k] = wide_fma(Hn[k], zc * rk[k - i + 1], a);
             }
 #pragma unroll
-            for (int c = 0; c < kWideBlock; ++c) top[c] = wide_fma(Hn[N], zrow[j0 + c], top[c]);
+            for (int c = 0; c < WB; c += kPer16) {   // the block's increments, 16 bytes per LDS read
+                typedef T TZ __attribute__((ext_vector_type(kPer16)));
+                const TZ zv = *reinterpret_cast<const TZ *>(zrow + j0 + c);
+#pragma unroll
+                for (int k = 0; k < kPer16; ++k) top[c + k] = wide_fma(Hn[N], zv[k], top[c + k]);
+            }
             if (sh.stream && live) store(out + (row * n_inc + t0 + s) * sh.S);
         }
     }
@@ -166,8 +171,12 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
 bool wide_plan(const Shape &sh, WidePlan &pl)
 {
     if (sh.N < 2 || sh.N > 4 || sh.d < 2 || sh.chunks > 1 || sh.S >= (int64_t(1) << 31)) return false;
-    pl.jblocks = (sh.d + kWideBlock - 1) / kWideBlock;
-    pl.dpad = pl.jblocks * kWideBlock;
+    // From depth 3 on a thread also walks the chain along its word, about 12 multiply-adds' worth per increment: where the
+    // channels fill whole blocks of 32 or 64 letters, the larger block halves or quarters the chain's share (1024 paths of
+    // 128 points at d = 32, N = 3: 210 us against 337 with blocks of 16).
+    pl.block = sh.N >= 3 && sh.d % 64 == 0 ? 64 : sh.N >= 3 && sh.d % 32 == 0 ? 32 : 16;
+    pl.jblocks = (sh.d + pl.block - 1) / pl.block;
+    pl.dpad = pl.jblocks * pl.block;
     pl.threads = sh.pw[sh.N - 1] * pl.jblocks;
     if (pl.threads > (int64_t(1) << 24)) return false;
     if (pl.threads >= 256) {
@@ -191,12 +200,20 @@ hipError_t launch_wide_t(const Shape &sh, const T *path, T *out, hipStream_t st)
     const int64_t groups = pl.threads >= 256 ? sh.B * pl.groups_per_path : (sh.B + pl.paths_per_group - 1) / pl.paths_per_group;
     if (groups > 0x7fffffff) return hipErrorNotSupported;
     const dim3 grid{unsigned(groups)}, block{256};
+#define SIG_WIDE_LAUNCH(NN)                                                                                   \
+    if (pl.block == 64)                                                                                       \
+        hipLaunchKernelGGL((sig_wide_kernel<T, NN, 64>), grid, block, lds, st, sh, pl, path, out);            \
+    else if (pl.block == 32)                                                                                  \
+        hipLaunchKernelGGL((sig_wide_kernel<T, NN, 32>), grid, block, lds, st, sh, pl, path, out);            \
+    else                                                                                                      \
+        hipLaunchKernelGGL((sig_wide_kernel<T, NN, 16>), grid, block, lds, st, sh, pl, path, out)
     switch (sh.N) {
-        case 2: hipLaunchKernelGGL((sig_wide_kernel<T, 2>), grid, block, lds, st, sh, pl, path, out); break;
-        case 3: hipLaunchKernelGGL((sig_wide_kernel<T, 3>), grid, block, lds, st, sh, pl, path, out); break;
-        case 4: hipLaunchKernelGGL((sig_wide_kernel<T, 4>), grid, block, lds, st, sh, pl, path, out); break;
+        case 2: SIG_WIDE_LAUNCH(2); break;
+        case 3: SIG_WIDE_LAUNCH(3); break;
+        case 4: SIG_WIDE_LAUNCH(4); break;
         default: return hipErrorNotSupported;
     }
+#undef SIG_WIDE_LAUNCH
     return hipGetLastError();
 }
 

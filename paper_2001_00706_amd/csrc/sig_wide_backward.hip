@@ -3,12 +3,12 @@
 // instantiation (paper section 5.3, appendix C.1).
 //
 // The recurrences are those of sig_tree_backward_impl.h with one level below a thread's word and the channel count a
-// run-time value.  A thread stands for a word u of N - 1 letters and a block of 16 last letters j: it keeps the
-// cotangents of the 16 words u j in registers, carries the signature at the prefixes of u ("up": undoing the increment
+// run-time value.  A thread stands for a word u of N - 1 letters and a block of 16 (or 32) last letters j: it keeps the
+// cotangents of the words u j in registers, carries the signature at the prefixes of u ("up": undoing the increment
 // needs nothing else) and, for each prefix, the part of that prefix's cotangent that arrived through its own block
 // ("down" is linear, so the parts may stay apart; a prefix's own cotangent goes to the first thread below it).
 // Nothing is exchanged between threads except the one sum that ends an increment: its gradient is the sum of
-// every thread's 16 products for the letters of its block and of one scalar per letter of its word.
+// every thread's products for the letters of its block and of one scalar per letter of its word.
 //   * The 64 lanes of a wavefront share their block of letters.  Their 16 x 64 products are summed over the lanes by a
 //     butterfly that halves the number of values a lane still holds at every step (15 exchanges instead of 96), then
 //     over the four rows of 16 lanes.
@@ -23,15 +23,15 @@
 namespace sig {
 namespace {
 
-constexpr int kWbBlock = 16;   // last letters per thread
 constexpr int kWbTile = 16;    // increments staged in LDS at a time
 
 __device__ __forceinline__ float wb_fma(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
 __device__ __forceinline__ double wb_fma(double a, double b, double c) { return __builtin_fma(a, b, c); }
 
 struct WbPlan {
-    int jblocks;               // ceil(d / 16)
-    int dpad;                  // jblocks * 16
+    int block;                 // last letters per thread: 16 or 32
+    int jblocks;               // ceil(d / block)
+    int dpad;                  // jblocks * block
     int64_t words;             // d^(N-1)
     int64_t waves_per_block;   // wavefronts that cover the words once: ceil(words / 64)
     int64_t groups_per_path;   // workgroups of four wavefronts per path
@@ -92,7 +92,7 @@ __device__ __forceinline__ double rows_sum(double v)
     return whole(ql.first, qh.first) + whole(ql.second, qh.second);
 }
 
-template <typename T, int N, bool STREAM>
+template <typename T, int N, bool STREAM, int WB>   // WB: last letters per thread, 16 or 32
 __global__ void __launch_bounds__(256)
 sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const T *__restrict__ sig,
                          const T *__restrict__ gout, T *__restrict__ partial)
@@ -111,7 +111,7 @@ sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const 
     const bool live = jb_raw < pl.jblocks && u_raw < pl.words;
     const int64_t u = live ? u_raw : 0;   // idle threads shadow word 0 and contribute nothing
     const int jb = jb_raw < pl.jblocks ? jb_raw : 0;   // the same in every lane of a wavefront
-    const int j0 = jb * kWbBlock;
+    const int j0 = jb * WB;
 
     int cl[P + 1];        // letters of the word
     int64_t pre[P + 1];   // index of its prefix of i letters inside level i
@@ -151,7 +151,7 @@ sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const 
     const T *sg = sig + row * per_row;
     const T *go = gout + row * per_row;
 
-    T Glo[P + 1], Gtop[kWbBlock];   // cotangents: this thread's part at its prefixes, whole at its 16 words
+    T Glo[P + 1], Gtop[WB];   // cotangents: this thread's part at its prefixes, whole at the words of its block
     T Alo[P + 1];                   // the signature at the prefixes
     {
         const T *g_last = STREAM ? go + (sh.n_inc - 1) * sh.S : go;
@@ -161,7 +161,7 @@ sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const 
             Alo[i] = STREAM ? T(0) : sg[sh.off[i] + pre[i]];
         }
 #pragma unroll
-        for (int c = 0; c < kWbBlock; ++c) {
+        for (int c = 0; c < WB; ++c) {
             const bool on = live && j0 + c < d;
             const T v = g_last[sh.off[N] + u * d + (on ? j0 + c : 0)];
             Gtop[c] = on ? v : T(0);
@@ -194,22 +194,22 @@ sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const 
         // otherwise hold back the reads of the next one
         typedef T T4 __attribute__((ext_vector_type(4)));
         T zc_next[P + 1];
-        T4 zb_next[kWbBlock / 4];
+        T4 zb_next[WB / 4];
         auto read_step = [&](int i) {
             const T *zrow = zt + i * pl.dpad;
 #pragma unroll
             for (int j = 1; j <= P; ++j) zc_next[j] = zrow[cl[j]];
 #pragma unroll
-            for (int q = 0; q < kWbBlock / 4; ++q) zb_next[q] = *reinterpret_cast<const T4 *>(zrow + j0 + 4 * q);
+            for (int q = 0; q < WB / 4; ++q) zb_next[q] = *reinterpret_cast<const T4 *>(zrow + j0 + 4 * q);
         };
         read_step(nt - 1);
         for (int i = nt - 1; i >= 0; --i) {
             const int64_t s = t0 + i;
-            T zc[P + 1], zb[kWbBlock];
+            T zc[P + 1], zb[WB];
 #pragma unroll
             for (int j = 1; j <= P; ++j) zc[j] = zc_next[j];
 #pragma unroll
-            for (int c = 0; c < kWbBlock; ++c) zb[c] = zb_next[c / 4][c % 4];
+            for (int c = 0; c < WB; ++c) zb[c] = zb_next[c / 4][c % 4];
             read_step(i > 0 ? i - 1 : 0);
             if constexpr (STREAM) {
                 // the signature after s increments is output entry s - 1 (the identity for s = 0)
@@ -237,8 +237,8 @@ sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const 
                 for (int j = 1; j <= P; ++j) Alo[j] = a_lo[j];
             }
 
-            // ---- down, top level: the 16 words below this thread's
-            T dzb[kWbBlock];
+            // ---- down, top level: the words of this thread's block
+            T dzb[WB];
             T Dc[N + 2];   // Dc[k] = this thread's part of D^(k)_j at its prefix of the level j being processed
 #pragma unroll
             for (int k = 0; k <= N + 1; ++k) Dc[k] = T(0);
@@ -246,7 +246,7 @@ sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const 
                 const T top_term = Hn[P][N];
                 T acc = T(0);
 #pragma unroll
-                for (int c = 0; c < kWbBlock; ++c) {
+                for (int c = 0; c < WB; ++c) {
                     dzb[c] = top_term * Gtop[c];
                     acc = wb_fma(Gtop[c], zb[c], acc);
                 }
@@ -279,8 +279,12 @@ sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const 
             // write of 64 lanes about 6 in all: atomic adds are kept for the few lanes that may meet at an address,
             // everything else is brought to distinct lanes first and added by a read and a write.
             {
-                const T total = rows_sum(row_transpose_sum(dzb, lane));
-                if (lane < kWbBlock) acc_row[j0 + lane] += total;
+                T total = rows_sum(row_transpose_sum(*reinterpret_cast<const T(*)[16]>(&dzb[0]), lane));
+                if constexpr (WB == 32) {   // the block's second half the same way; lanes 16 .. 31 add it
+                    const T second = rows_sum(row_transpose_sum(*reinterpret_cast<const T(*)[16]>(&dzb[16]), lane));
+                    total = lane & 16 ? second : total;
+                }
+                if (lane < WB) acc_row[j0 + lane] += total;
             }
             // earlier letters: a row's two sums, added by its first and its last lane (rows may share a letter)
 #pragma unroll
@@ -312,7 +316,7 @@ sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const 
                         Glo[j] += first[j] ? v : T(0);
                     }
 #pragma unroll
-                    for (int c = 0; c < kWbBlock; ++c) {
+                    for (int c = 0; c < WB; ++c) {
                         const bool on = live && j0 + c < d;
                         const T v = g_row[sh.off[N] + u * d + (on ? j0 + c : 0)];
                         Gtop[c] += on ? v : T(0);
@@ -366,10 +370,14 @@ sig_wide_backward_reduce_kernel(Shape sh, int64_t n_partials, const T *__restric
 bool wb_plan(const Shape &sh, size_t elem, WbPlan &pl)
 {
     if (sh.N < 2 || sh.N > 4 || sh.d < 2 || sh.chunks > 1 || sh.S >= (int64_t(1) << 31) || sh.n_inc < 1) return false;
-    pl.jblocks = (sh.d + kWbBlock - 1) / kWbBlock;
-    pl.dpad = pl.jblocks * kWbBlock;
+    // from depth 3 on, where the channels fill whole blocks of 32 letters, the larger block halves the share of everything a
+    // thread does per word rather than per letter (the chain along the word, the sums of its scalars)
+    // ... as long as that leaves a thousand workgroups: below, a wavefront's latency per increment is what counts
     pl.words = sh.pw[sh.N - 1];
     pl.waves_per_block = (pl.words + 63) / 64;
+    pl.block = sh.N >= 3 && sh.d % 32 == 0 && sh.B * ((pl.waves_per_block * (sh.d / 32) + 3) / 4) >= 1024 ? 32 : 16;
+    pl.jblocks = (sh.d + pl.block - 1) / pl.block;
+    pl.dpad = pl.jblocks * pl.block;
     pl.groups_per_path = (pl.waves_per_block * pl.jblocks + 3) / 4;
     if (sh.B * pl.groups_per_path > 0x7fffffff) return false;
     return elem * size_t(5 * kWbTile) * size_t(pl.dpad) <= 64 * 1024;
@@ -386,11 +394,17 @@ hipError_t launch_wb_t(const Shape &sh, const T *path, const T *sig, const T *go
     T *partial = static_cast<T *>(workspace);
     const dim3 grid{unsigned(sh.B * pl.groups_per_path)}, block{256};
     const size_t lds = sizeof(T) * size_t(5 * kWbTile) * size_t(pl.dpad);
-#define SIG_WB_LAUNCH(NN)                                                                                                        \
+#define SIG_WB_LAUNCH_B(NN, BB)                                                                                                  \
     if (sh.stream)                                                                                                               \
-        hipLaunchKernelGGL((sig_wide_backward_kernel<T, NN, true>), grid, block, lds, st, sh, pl, path, sig, gout, partial);     \
+        hipLaunchKernelGGL((sig_wide_backward_kernel<T, NN, true, BB>), grid, block, lds, st, sh, pl, path, sig, gout, partial); \
     else                                                                                                                         \
-        hipLaunchKernelGGL((sig_wide_backward_kernel<T, NN, false>), grid, block, lds, st, sh, pl, path, sig, gout, partial)
+        hipLaunchKernelGGL((sig_wide_backward_kernel<T, NN, false, BB>), grid, block, lds, st, sh, pl, path, sig, gout, partial)
+#define SIG_WB_LAUNCH(NN)          \
+    if (pl.block == 32) {          \
+        SIG_WB_LAUNCH_B(NN, 32);   \
+    } else {                       \
+        SIG_WB_LAUNCH_B(NN, 16);   \
+    }
     switch (sh.N) {
         case 2: SIG_WB_LAUNCH(2); break;
         case 3: SIG_WB_LAUNCH(3); break;
@@ -398,6 +412,7 @@ hipError_t launch_wb_t(const Shape &sh, const T *path, const T *sig, const T *go
         default: return hipErrorNotSupported;
     }
 #undef SIG_WB_LAUNCH
+#undef SIG_WB_LAUNCH_B
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     const int64_t total = sh.B * (sh.n_inc + 1) * sh.d;
