@@ -136,6 +136,8 @@ sig_status sig_forward_variant(const void *path, int64_t B, int64_t L, int d, in
  * `chunks` stretches of ceil(n_inc / chunks) increments, all B * chunks stretches are scanned at once by the
  * kernels of sig_forward, and neighbouring results are joined pairwise by sig_combine's product (Chen's identity,
  * eq. "grouplike") in log2(chunks) rounds.  Worth it when B alone cannot fill the device and L is long.
+ * At depth 2 nothing is multiplied: level 2 is a plain sum over the increments of (midpoint - first point) (x)
+ * increment (sections 2.1, 2.2), so every stretch adds up its own terms and a second launch adds the stretches.
  *   chunks     a power of two, 2 .. 65536 (stretches past the end of a short path are empty and count as the
  *              identity).
  *   basepoint_value  as for sig_signature.
@@ -156,7 +158,10 @@ int64_t sig_forward_chunked_workspace_bytes(int64_t B, int64_t L, int d, int N, 
  * 512 increments (4096 at d = 8, N = 4..6 in fp32, whose kernels already spread a path over 64 wavefronts); measured:
  * B = 1, L = 65536, d = 4, N = 6 takes 6.5 ms plain and 0.09 ms in 512 chunks.  The hint is the largest power of two
  * that leaves every stretch at least 64 increments, keeps B * chunks within 1024 stretches and their signatures
- * within 256 MiB (the products that join them move every one of them).  0 on invalid arguments. */
+ * within 256 MiB (the products that join them move every one of them).  At depth 2 (a sum, two launches of about
+ * 22 us in all): up to 1024 paths, from 24 staged tiles of increments on (3072 increments up to 28 channels, 1512 at
+ * 64), stretches of at least 128 increments, 2048 at most; B = 1, L = 131073, d = 64 takes 7.8 ms plain and 0.03 to
+ * 0.07 ms cut into 256 to 1024 stretches.  0 on invalid arguments. */
 int sig_forward_chunks_hint(int64_t B, int64_t L, int d, int N, int basepoint, sig_dtype dtype);
 
 /* Size of the scratch array built into the library for sig_forward_chunked_static: 32 MiB of device memory that

@@ -426,6 +426,21 @@ int sig_forward_chunks_hint(int64_t B, int64_t L, int d, int N, int basepoint, s
     if (make_shape(B, L, d, N, 0, basepoint, sh) != SIG_OK) return 0;
     // the d = 8 matrix family already spreads a path over 64 wavefronts; everything else scans a path in one
     // workgroup and gains from 512 increments on
+    if (N == 2) {
+        // Depth 2 is one sum over the increments: a path alone takes about 1.5 us per staged tile (128 increments up to
+        // 28 channels, 63 at 64, 39 at 100), cut into stretches two launches of about 22 us in all: from 24 tiles on;
+        // stretches of at least 128 increments, at most 2048 of them.
+        const int64_t padded = (d + 3) / 4 * 4;
+        const int64_t tile = 4096 / padded - 1 < 128 ? (4096 / padded - 1 < 1 ? 1 : 4096 / padded - 1) : 128;
+        if (B < 1 || B > 1024 || sh.n_inc < 24 * tile) return 1;
+        int chunks = 1;
+        const int64_t elem2 = dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double));
+        while (int64_t(chunks) * 2 * B <= 2048 && sh.n_inc / (int64_t(chunks) * 2) >= 128 &&
+               int64_t(chunks) * 2 * B * sh.S * elem2 <= (int64_t(256) << 20) &&
+               sig_forward_chunked_workspace_bytes(B, L, d, N, basepoint, chunks * 2, dtype) >= 0)
+            chunks *= 2;
+        return chunks;
+    }
     const int64_t shortest = (d == 8 && N >= 4 && N <= 6 && dtype == SIG_F32) ? 4096 : 512;
     if (B < 1 || B > 64 || sh.n_inc < shortest) return 1;
     const int64_t elem = dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double));
@@ -462,8 +477,17 @@ static sig_status forward_chunked(const void *path, int64_t B, int64_t L, int d,
     if (path == nullptr || out == nullptr || workspace == nullptr) return SIG_ERR_INVALID_ARG;
     if (workspace_bytes < (sh.B + sh.B / 2) * sh.S * elem || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)
         return SIG_ERR_INVALID_ARG;
-    if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
     sh.basepoint_value = basepoint_value;
+    // Depth 2 is a plain sum over the increments (see sig_forward_n2.hip): the stretches' sums are added, not multiplied
+    if (sig::forward_n2_chunked_supported(sh, dtype)) {
+        const hipError_t err =
+            dtype == SIG_F32 ? sig::launch_forward_n2_chunked_f32(sh, static_cast<const float *>(path), static_cast<float *>(workspace),
+                                                                  static_cast<float *>(out), hip_stream)
+                             : sig::launch_forward_n2_chunked_f64(sh, static_cast<const double *>(path), static_cast<double *>(workspace),
+                                                                  static_cast<double *>(out), hip_stream);
+        return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+    }
+    if (!sig::combine_supported(sh)) return SIG_ERR_UNSUPPORTED;
     const Family family = resolve(sh, dtype, SIG_VARIANT_AUTO, path, workspace);
     if (family == Family::None) return SIG_ERR_UNSUPPORTED;
     // every chunk scanned on its own ...

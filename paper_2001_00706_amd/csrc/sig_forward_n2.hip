@@ -70,7 +70,7 @@ sig_forward_n2_kernel(Shape sh, N2Plan pl, const T *__restrict__ path, T *__rest
     for (int e = tid; e < pl.paths_per_group * cvecs; e += 256) {
         const int p = e / cvecs, c = (e - p * cvecs) * V;
         const bool on = row0 + p < sh.B && c < d;
-        const TV v = scan_point(on ? row0 + p : 0, 0, on ? c : 0);
+        const TV v = scan_point(on ? chunk_view(row0 + p, sh.chunks, sh.chunk_len, sh.n_inc).path : 0, 0, on ? c : 0);
         *reinterpret_cast<TV *>(start + p * dpad + c) = on ? v : TV(0);
     }
 
@@ -86,45 +86,53 @@ sig_forward_n2_kernel(Shape sh, N2Plan pl, const T *__restrict__ path, T *__rest
     // zeros when the tile is written to LDS.  The loads of the next tile are issued before this tile's arithmetic.
     // Which point of which path an entry of the tile holds does not change from tile to tile: worked out once.
     TV held[kBatch];
-    const T *entry_row[kBatch];   // channel c of point 0 of the entry's path (of path 0 for entries that stay zero)
+    const T *entry_row[kBatch];   // channel c of the first point of the entry's row (of path 0 for entries that stay zero)
     int entry_point[kBatch];      // the entry's point inside the tile
-    bool entry_on[kBatch];
+    int64_t entry_n[kBatch];      // increments of the entry's row; -1 for entries that stay zero
+    bool entry_first[kBatch];     // the row starts at the scan's first point
     const T *entry_base[kBatch];  // the entry's channels of a basepoint given by value
 #pragma unroll
     for (int k = 0; k < kBatch; ++k) {
         const int e = 256 * k + tid < staged ? 256 * k + tid : staged - 1;
         const int p = e / (rows * cvecs), rem = e - p * rows * cvecs, pt = rem / cvecs, c = (rem - pt * cvecs) * V;
-        entry_on[k] = row0 + p < sh.B && c < d;
+        const ChunkView cv = chunk_view(row0 + p < sh.B ? row0 + p : 0, sh.chunks, sh.chunk_len, sh.n_inc);
+        const bool on = row0 + p < sh.B && c < d && cv.n > 0;
         entry_point[k] = pt;
-        entry_row[k] = path + (entry_on[k] ? (row0 + p) * sh.L * d + c : 0);
-        entry_base[k] = bpv != nullptr && entry_on[k] ? bpv + (row0 + p) * d + c : bpv;
+        entry_n[k] = on ? cv.n : -1;
+        entry_first[k] = cv.inc0 == 0;
+        entry_row[k] = path + (on ? (cv.path * sh.L + cv.inc0) * d + c : 0);
+        entry_base[k] = bpv != nullptr && on ? bpv + cv.path * d + c : bpv;
     }
     const auto load_tile = [&](int64_t t0) {
 #pragma unroll
         for (int k = 0; k < kBatch; ++k) {
             if (256 * k >= staged) break;   // the same for every thread
             const int64_t point = t0 + entry_point[k];
-            const bool on = entry_on[k] && point <= sh.n_inc;
-            const bool from_base = on && sh.basepoint && point == 0;
+            const bool on = point <= entry_n[k];
+            const bool from_base = on && sh.basepoint && entry_first[k] && point == 0;
             const T *src = from_base && bpv != nullptr ? entry_base[k] : entry_row[k] + (on && !from_base ? point - shift : 0) * d;
             held[k] = *reinterpret_cast<const TV *>(src);
         }
     };
+    // a row is a whole path, or a stretch of chunk_len increments of one (the last stretches of a path may be shorter or empty)
+    const ChunkView mine = chunk_view(row < sh.B ? row : 0, sh.chunks, sh.chunk_len, sh.n_inc);
+    const int64_t n_longest = sh.chunks > 1 ? sh.chunk_len : sh.n_inc;
     load_tile(0);
-    for (int64_t t0 = 0; t0 < sh.n_inc; t0 += pl.tile) {
+    for (int64_t t0 = 0; t0 < n_longest; t0 += pl.tile) {
         lds_barrier();   // not __syncthreads(): the loads of the next tile stay in flight
 #pragma unroll
         for (int k = 0; k < kBatch; ++k) {
             if (256 * k >= staged) break;
             const int64_t point = t0 + entry_point[k];
-            const bool zero = !entry_on[k] || point > sh.n_inc || (sh.basepoint && point == 0 && bpv == nullptr);
+            const bool zero = point > entry_n[k] || (sh.basepoint && entry_first[k] && point == 0 && bpv == nullptr);
             if (256 * k + tid < staged) *reinterpret_cast<TV *>(pts + int64_t(256 * k + tid) * V) = zero ? TV(0) : held[k];
         }
-        if (t0 + pl.tile < sh.n_inc) load_tile(t0 + pl.tile);
+        if (t0 + pl.tile < n_longest) load_tile(t0 + pl.tile);
         lds_barrier();
         if (t0 == 0) p_i = *reinterpret_cast<const T4 *>(start + slot * dpad + 4 * ib);
         const T *lp = pts + slot * rows * dpad + 4 * ib, *rp = pts + slot * rows * dpad + 4 * jb;
-        const int nt = int(sh.n_inc - t0 < pl.tile ? sh.n_inc - t0 : pl.tile);
+        const int64_t left = mine.n - t0;
+        const int nt = int(left < 0 ? 0 : left < pl.tile ? left : pl.tile);
         const int share = (nt + pl.splits - 1) / pl.splits;
         const int lo = works ? ks * share : nt, hi = lo + share < nt ? lo + share : nt;   // this thread's increments
         if (lo < hi) {
@@ -142,7 +150,7 @@ sig_forward_n2_kernel(Shape sh, N2Plan pl, const T *__restrict__ path, T *__rest
             }
         }
         // the last tile ends at the scan's last point: level 1, by the threads of the first row of blocks
-        if (live && ib == 0 && t0 + pl.tile >= sh.n_inc) {
+        if (live && ib == 0 && sh.chunks <= 1 && t0 + pl.tile >= sh.n_inc) {
             const T4 q_j = *reinterpret_cast<const T4 *>(rp + nt * dpad), p_j = *reinterpret_cast<const T4 *>(start + slot * dpad + 4 * jb);
 #pragma unroll
             for (int b = 0; b < 4; ++b)
@@ -183,9 +191,45 @@ size_t n2_lds(const N2Plan &pl, size_t elem)
     return points > sums ? points : sums;
 }
 
-bool n2_plan(const Shape &sh, size_t elem, const void *path, N2Plan &pl)
+// Adds up the rows of the stretches of a path (level 2: the terms of the sum over increments in any grouping) and forms
+// level 1 from the scan's end points: out[b] = (q - p, sum_c partial[b][c]).  A workgroup serves 16 scalars of a path:
+// thread (part, w) adds the stretches part, part + 16, .., the 16 parts meet in LDS and are added in order.
+template <typename T>
+__global__ void __launch_bounds__(256)
+sig_forward_n2_sum_kernel(Shape sh, const T *__restrict__ path, const T *__restrict__ partial, T *__restrict__ out)
 {
-    if (sh.N != 2 || sh.stream || sh.chunks > 1 || sh.d < 1 || sh.d > 1024) return false;
+    __shared__ T parts[16][17];
+    const int d = sh.d;
+    const int64_t groups_per_path = (sh.S + 15) / 16;
+    const int64_t b = blockIdx.x / groups_per_path;
+    const int part = threadIdx.x >> 4, lane16 = threadIdx.x & 15;
+    const int64_t w = (blockIdx.x % groups_per_path) * 16 + lane16;
+    T acc = T(0);
+    if (w >= d && w < sh.S) {
+        const T *q = partial + b * sh.chunks * sh.S + w;
+        for (int c = part; c < sh.chunks; c += 16) acc += q[int64_t(c) * sh.S];
+    }
+    parts[part][lane16] = acc;
+    __syncthreads();
+    if (part == 0 && w < sh.S) {
+        if (w < d) {
+            const T *x = path + b * sh.L * d;
+            const T *bpv = static_cast<const T *>(sh.basepoint_value);
+            const T first = sh.basepoint ? (bpv != nullptr ? bpv[b * d + w] : T(0)) : x[w];
+            out[b * sh.S + w] = x[(sh.L - 1) * d + w] - first;
+        } else {
+            T total = parts[0][lane16];
+#pragma unroll
+            for (int k = 1; k < 16; ++k) total += parts[k][lane16];
+            out[b * sh.S + w] = total;
+        }
+    }
+}
+
+// `stretches`: rows may be stretches of a path (Shape::chunks > 1), their level-2 sums going to a workspace
+bool n2_plan(const Shape &sh, size_t elem, const void *path, N2Plan &pl, bool stretches = false)
+{
+    if (sh.N != 2 || sh.stream || (sh.chunks > 1 && !stretches) || sh.d < 1 || sh.d > 1024) return false;
     pl.dq = (sh.d + 3) / 4;
     const int64_t blocks = int64_t(pl.dq) * pl.dq;
     if (blocks >= 256) {
@@ -224,10 +268,10 @@ bool n2_plan(const Shape &sh, size_t elem, const void *path, N2Plan &pl)
 }
 
 template <typename T>
-hipError_t launch_forward_n2_t(const Shape &sh, const T *path, T *out, hipStream_t st)
+hipError_t launch_forward_n2_t(const Shape &sh, const T *path, T *out, hipStream_t st, bool stretches = false)
 {
     N2Plan pl;
-    if (!n2_plan(sh, sizeof(T), path, pl)) return hipErrorNotSupported;
+    if (!n2_plan(sh, sizeof(T), path, pl, stretches)) return hipErrorNotSupported;
     const int64_t blocks = int64_t(pl.dq) * pl.dq;
     const int64_t groups = blocks >= 256 ? sh.B * pl.groups_per_path : (sh.B + pl.paths_per_group - 1) / pl.paths_per_group;
     const dim3 grid{unsigned(groups)}, block{256};
@@ -246,6 +290,33 @@ bool forward_n2_supported(const Shape &sh, sig_dtype dtype)
 {
     N2Plan pl;
     return n2_plan(sh, dtype == SIG_F32 ? sizeof(float) : sizeof(double), nullptr, pl);
+}
+
+template <typename T>
+hipError_t launch_forward_n2_chunked_t(const Shape &sh, const T *path, T *partial, T *out, hipStream_t st)
+{
+    const hipError_t err = launch_forward_n2_t<T>(sh, path, partial, st, true);
+    if (err != hipSuccess) return err;
+    const int64_t groups = sh.B / sh.chunks * ((sh.S + 15) / 16);
+    if (groups > 0x7fffffff) return hipErrorNotSupported;
+    hipLaunchKernelGGL((sig_forward_n2_sum_kernel<T>), dim3(unsigned(groups)), dim3(256), 0, st, sh, path, partial, out);
+    return hipGetLastError();
+}
+
+bool forward_n2_chunked_supported(const Shape &sh, sig_dtype dtype)
+{
+    N2Plan pl;
+    return sh.chunks > 1 && n2_plan(sh, dtype == SIG_F32 ? sizeof(float) : sizeof(double), nullptr, pl, true);
+}
+
+hipError_t launch_forward_n2_chunked_f32(const Shape &sh, const float *path, float *partial, float *out, hipStream_t st)
+{
+    return launch_forward_n2_chunked_t<float>(sh, path, partial, out, st);
+}
+
+hipError_t launch_forward_n2_chunked_f64(const Shape &sh, const double *path, double *partial, double *out, hipStream_t st)
+{
+    return launch_forward_n2_chunked_t<double>(sh, path, partial, out, st);
 }
 
 hipError_t launch_forward_n2_f32(const Shape &sh, const float *path, float *out, hipStream_t st)

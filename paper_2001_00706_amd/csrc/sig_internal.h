@@ -165,6 +165,11 @@ hipError_t launch_wide_f64(const Shape &sh, const double *path, double *out, hip
 bool forward_n2_supported(const Shape &sh, sig_dtype dtype);
 hipError_t launch_forward_n2_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_forward_n2_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
+// A chunked scan at depth 2 (Shape::chunks > 1, B counting stretches): the stretches' sums, [B][S] scalars in `partial`,
+// then their sum per path in `out`.
+bool forward_n2_chunked_supported(const Shape &sh, sig_dtype dtype);
+hipError_t launch_forward_n2_chunked_f32(const Shape &sh, const float *path, float *partial, float *out, hipStream_t st);
+hipError_t launch_forward_n2_chunked_f64(const Shape &sh, const double *path, double *partial, double *out, hipStream_t st);
 // The same on the matrix cores (fp32, 17 to 256 channels; see sig_forward_n2_mfma.hip).  The launch returns
 // hipErrorNotSupported, with nothing enqueued, where unaligned buffers leave no room for a tile of four increments.
 bool forward_n2_mfma_supported(const Shape &sh);

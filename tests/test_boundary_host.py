@@ -253,6 +253,11 @@ def test_chunk_hint(lib):
     assert h(64, 65537, 16, 4, 0, sig.SIG_F32) == 8          # 256 MiB of signatures at most
     assert h(1, 1, 4, 6, 0, sig.SIG_F32) == 0 and h(1, 4096, 4, 6, 0, 9) == 0 and h(1, 4096, 0, 6, 0, sig.SIG_F32) == 0
     assert h(0, 4096, 4, 6, 0, sig.SIG_F32) == 1
+    # depth 2, a plain sum over the increments: from 24 staged tiles on, stretches of at least 128 increments, 2048 at most
+    assert h(1, 3072, 4, 2, 0, sig.SIG_F32) == 1 and h(1, 3073, 4, 2, 0, sig.SIG_F32) == 16
+    assert h(1, 131073, 8, 2, 0, sig.SIG_F64) == 1024 and h(64, 131073, 8, 2, 0, sig.SIG_F32) == 32
+    assert h(1, 1513, 64, 2, 0, sig.SIG_F32) == 8 and h(1, 1512, 64, 2, 0, sig.SIG_F32) == 1
+    assert h(1024, 8193, 2, 2, 0, sig.SIG_F32) == 2 and h(1025, 8193, 2, 2, 0, sig.SIG_F32) == 1
 
 
 def test_lyndon_table_is_built_on_the_host(lib):

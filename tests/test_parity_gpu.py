@@ -449,6 +449,9 @@ def test_chunked_scan_plus_combine_equals_the_whole_scan():
     (2, 33, 5, 3, 4),      # fallback family
     (2, 5, 3, 4, 8),       # more chunks than increments: empty chunks are the identity
     (1, 2, 4, 4, 2),
+    # depth 2: the stretches' sums are added (no products); ragged and empty last stretches, many channels, stretches of
+    # several tiles
+    (3, 1000, 3, 2, 16), (2, 40, 20, 2, 64), (1, 700, 64, 2, 4), (5, 2, 6, 2, 2), (2, 2000, 8, 2, 8),
 ])
 def test_chunked_scan_equals_the_plain_scan(B, L, d, N, chunks, dtype):
     torch = torch_mod()
