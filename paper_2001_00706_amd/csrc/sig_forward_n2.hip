@@ -13,6 +13,8 @@
 // needs (the old point's stay in registers), forms its pieces of m_s - p and z_s and does 16 multiply-adds.
 // Paths with fewer than 256 blocks share a workgroup once there are enough workgroups; threads left over split a
 // tile's increments between them and add their partial sums up through LDS at the end.
+// The sum may also be split over the length of a path (a chunked scan: a row is then a stretch of a path, its terms
+// still taken against the first point of the whole path; a second kernel adds the stretches).
 #include "sig_internal.h"
 #include "sig_lane_ops.h"
 
