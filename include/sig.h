@@ -64,7 +64,8 @@ typedef enum {
     SIG_VARIANT_MFMA_STREAM = 6,/* fp32, d = 4, N = 4..6, stream mode only: the four first-letter wavefronts of a path in
                                  one workgroup; prefix signatures are assembled in LDS and written out in whole runs
                                  cut at 128-byte boundaries (what sig_forward picks for outputs beyond ~300 MB) */
-    SIG_VARIANT_WIDE = 8,     /* any dtype and mode, any d >= 2 at N = 2..4 (what serves d > 16): a thread per word of
+    SIG_VARIANT_WIDE = 8,     /* any dtype and mode, any d >= 2 at N = 2..9 up to 2^28 words of N-1 letters (what serves
+                                 d > 16, and d = 9..16 beyond depth 6): a thread per word of
                                  N-1 letters and block of 16 last letters, channel count a run-time value */
     SIG_VARIANT_DEPTH2 = 9,   /* any dtype, final mode, N = 2, d <= 1024: level 2 as a contraction over the increments,
                                  a thread per 4 x 4 block of coefficients, no scan (what serves N = 2 in final mode) */
@@ -351,7 +352,7 @@ sig_status sig_lyndon_scatter(const void *grad_logsig, int64_t rows, int d, int 
  *              irrelevant on entry and undefined on return; may be NULL when that size is 0.  Calls that overlap
  *              in time must not share a workspace.
  * Enqueued on `hip_stream`, no wait.  Served: d <= 16 at the depths of the register-resident and prefix-tree
- * kernels; any d at N = 2..4 (up to 204 channels, 102 in fp64; depth 2 in final mode by a closed form up to d = 122,
+ * kernels; any d at N = 2..9 (up to 204 channels, 102 in fp64; depth 2 in final mode by a closed form up to d = 122,
  * 85 in fp64); everything else with d <= 64 and S < 2^30 on a generic kernel that is two to three orders of
  * magnitude slower per increment; otherwise SIG_ERR_UNSUPPORTED.  Other errors as for sig_forward; a missing or
  * short workspace is SIG_ERR_INVALID_ARG.  Deterministic. */

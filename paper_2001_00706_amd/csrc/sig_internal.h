@@ -156,7 +156,8 @@ bool row_stream_one_level(const Shape &sh);   // one level below a lane's word (
 hipError_t launch_row_stream_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_row_stream_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
 
-// Many channels at low depth (any d >= 2 at N = 2..4; see sig_wide.hip): what serves d > 16; not for chunked scans.
+// Many channels (any d >= 2 at N = 2..9; see sig_wide.hip): what serves d > 16, and 9 to 16 channels beyond depth 6; not for
+// chunked scans.
 bool wide_supported(const Shape &sh, sig_dtype dtype);
 hipError_t launch_wide_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_wide_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
@@ -176,7 +177,7 @@ bool forward_n2_mfma_supported(const Shape &sh);
 bool forward_n2_mfma_preferred(const Shape &sh);   // ... and measured faster than the vector kernel
 hipError_t launch_forward_n2_mfma_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 
-// Gradient for many channels at low depth (any d at N = 2..4, both modes; see sig_wide_backward.hip); the workspace
+// Gradient for many channels (any d at N = 2..9, both modes; see sig_wide_backward.hip); the workspace
 // holds one partial gradient per workgroup of a path.
 bool wide_backward_supported(const Shape &sh, sig_dtype dtype);
 int64_t wide_backward_workspace_bytes(const Shape &sh, sig_dtype dtype);

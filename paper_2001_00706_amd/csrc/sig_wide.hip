@@ -1,4 +1,4 @@
-// Many channels at low depth (any d at N = 2, 3, 4; fp32 and fp64; final and stream mode): the kernel for d > 16, where
+// Many channels (any d at N = 2 .. 9 up to 2^28 words of N - 1 letters; fp32 and fp64; final and stream mode): the kernel for d > 16, where
 // the prefix-tree family has no instantiation (its channel count is a compile-time constant) and a signature is
 // too large for the one-wavefront kernel.
 //
@@ -170,15 +170,15 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
 
 bool wide_plan(const Shape &sh, WidePlan &pl)
 {
-    if (sh.N < 2 || sh.N > 4 || sh.d < 2 || sh.chunks > 1 || sh.S >= (int64_t(1) << 31)) return false;
+    if (sh.N < 2 || sh.N > 9 || sh.d < 2 || sh.chunks > 1 || sh.S >= (int64_t(1) << 31)) return false;
     // From depth 3 on a thread also walks the chain along its word, about 12 multiply-adds' worth per increment: where the
     // channels fill whole blocks of 32 or 64 letters, the larger block halves or quarters the chain's share (1024 paths of
     // 128 points at d = 32, N = 3: 210 us against 337 with blocks of 16).
-    pl.block = sh.N >= 3 && sh.d % 64 == 0 ? 64 : sh.N >= 3 && sh.d % 32 == 0 ? 32 : 16;
+    pl.block = sh.N >= 3 && sh.N <= 4 && sh.d % 64 == 0 ? 64 : sh.N >= 3 && sh.N <= 4 && sh.d % 32 == 0 ? 32 : 16;
     pl.jblocks = (sh.d + pl.block - 1) / pl.block;
     pl.dpad = pl.jblocks * pl.block;
     pl.threads = sh.pw[sh.N - 1] * pl.jblocks;
-    if (pl.threads > (int64_t(1) << 24)) return false;
+    if (pl.threads > (int64_t(1) << 28)) return false;
     if (pl.threads >= 256) {
         pl.paths_per_group = 1;
         pl.groups_per_path = (pl.threads + 255) / 256;
@@ -211,6 +211,12 @@ hipError_t launch_wide_t(const Shape &sh, const T *path, T *out, hipStream_t st)
         case 2: SIG_WIDE_LAUNCH(2); break;
         case 3: SIG_WIDE_LAUNCH(3); break;
         case 4: SIG_WIDE_LAUNCH(4); break;
+        // deeper: blocks of 16 only
+        case 5: hipLaunchKernelGGL((sig_wide_kernel<T, 5, 16>), grid, block, lds, st, sh, pl, path, out); break;
+        case 6: hipLaunchKernelGGL((sig_wide_kernel<T, 6, 16>), grid, block, lds, st, sh, pl, path, out); break;
+        case 7: hipLaunchKernelGGL((sig_wide_kernel<T, 7, 16>), grid, block, lds, st, sh, pl, path, out); break;
+        case 8: hipLaunchKernelGGL((sig_wide_kernel<T, 8, 16>), grid, block, lds, st, sh, pl, path, out); break;
+        case 9: hipLaunchKernelGGL((sig_wide_kernel<T, 9, 16>), grid, block, lds, st, sh, pl, path, out); break;
         default: return hipErrorNotSupported;
     }
 #undef SIG_WIDE_LAUNCH

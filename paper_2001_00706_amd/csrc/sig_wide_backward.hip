@@ -1,4 +1,4 @@
-// Gradient of the signature with respect to the path for many channels at low depth (any d >= 2 at N = 2..4, fp32 and
+// Gradient of the signature with respect to the path for many channels (any d >= 2 at N = 2..9, fp32 and
 // fp64, final and stream mode): what serves more than 16 channels, where the prefix-tree gradient kernels have no
 // instantiation (paper section 5.3, appendix C.1).
 //
@@ -369,13 +369,13 @@ sig_wide_backward_reduce_kernel(Shape sh, int64_t n_partials, const T *__restric
 
 bool wb_plan(const Shape &sh, size_t elem, WbPlan &pl)
 {
-    if (sh.N < 2 || sh.N > 4 || sh.d < 2 || sh.chunks > 1 || sh.S >= (int64_t(1) << 31) || sh.n_inc < 1) return false;
+    if (sh.N < 2 || sh.N > 9 || sh.d < 2 || sh.chunks > 1 || sh.S >= (int64_t(1) << 31) || sh.n_inc < 1) return false;
     // from depth 3 on, where the channels fill whole blocks of 32 letters, the larger block halves the share of everything a
     // thread does per word rather than per letter (the chain along the word, the sums of its scalars)
     // ... as long as that leaves a thousand workgroups: below, a wavefront's latency per increment is what counts
     pl.words = sh.pw[sh.N - 1];
     pl.waves_per_block = (pl.words + 63) / 64;
-    pl.block = sh.N >= 3 && sh.d % 32 == 0 && sh.B * ((pl.waves_per_block * (sh.d / 32) + 3) / 4) >= 1024 ? 32 : 16;
+    pl.block = sh.N >= 3 && sh.N <= 4 && sh.d % 32 == 0 && sh.B * ((pl.waves_per_block * (sh.d / 32) + 3) / 4) >= 1024 ? 32 : 16;
     pl.jblocks = (sh.d + pl.block - 1) / pl.block;
     pl.dpad = pl.jblocks * pl.block;
     pl.groups_per_path = (pl.waves_per_block * pl.jblocks + 3) / 4;
@@ -409,6 +409,12 @@ hipError_t launch_wb_t(const Shape &sh, const T *path, const T *sig, const T *go
         case 2: SIG_WB_LAUNCH(2); break;
         case 3: SIG_WB_LAUNCH(3); break;
         case 4: SIG_WB_LAUNCH(4); break;
+        // deeper: blocks of 16 only
+        case 5: SIG_WB_LAUNCH_B(5, 16); break;
+        case 6: SIG_WB_LAUNCH_B(6, 16); break;
+        case 7: SIG_WB_LAUNCH_B(7, 16); break;
+        case 8: SIG_WB_LAUNCH_B(8, 16); break;
+        case 9: SIG_WB_LAUNCH_B(9, 16); break;
         default: return hipErrorNotSupported;
     }
 #undef SIG_WB_LAUNCH

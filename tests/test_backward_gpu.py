@@ -229,6 +229,7 @@ def test_depth_two_gradient_by_its_closed_form(B, L, d, dtype):
     (3, 5, 33, 2), (1, 6, 70, 2),     # depth 2 (stream mode; final mode has its closed form): 3 and 5 blocks of letters
     (2, 7, 40, 3), (1, 4, 18, 4),     # 75 and 365 wavefronts per path
     (3, 20, 12, 3), (2, 6, 9, 4),     # final mode from 9 channels on at few paths: picked over the prefix-tree kernels
+    (2, 5, 17, 5), (1, 3, 9, 7),      # deeper
 ])
 def test_many_channels_at_low_depth(B, L, d, N, dtype):
     x = uniform_paths(B, L, d, seed=4000 + L + d, lo=-0.4, hi=0.4).astype(dtype)

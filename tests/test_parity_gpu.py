@@ -575,6 +575,7 @@ def _depth_two_off_boundary(B, L, d, shift, dtype):
     (5, 7, 17, 3), (2, 5, 33, 3), (2, 70, 24, 3),       # a last block of 1 letter, 3267 threads per path, several tiles
     (1, 5, 20, 4), (2, 3, 18, 4),                       # depth 4: 16 000 and 11 664 threads per path
     (3, 9, 5, 3), (2, 6, 16, 2),                        # channel counts the other families serve as well
+    (2, 5, 17, 5), (1, 3, 9, 7), (1, 4, 3, 9),          # deeper: beyond 16 channels, and where no other family goes
 ])
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 def test_wide_channel_family(B, L, d, N, dtype):
@@ -583,6 +584,8 @@ def test_wide_channel_family(B, L, d, N, dtype):
     for stream in (False, True):
         for basepoint in (False, True):
             assert check(x, N, stream=stream, basepoint=basepoint, variant=sig.SIG_VARIANT_WIDE) is not None
+    if N >= 7 and d >= 9:
+        assert sig.sig_variant_name(B, L, d, N, False, False, code) == "wide"
     if d > 16:   # ... and it is what serves these shapes
         assert sig.sig_variant_name(B, L, d, N, False, False, code) == ("depth2" if N == 2 else "wide")
         assert sig.sig_variant_name(B, L, d, N, True, False, code) == "wide"
