@@ -156,8 +156,8 @@ bool row_stream_one_level(const Shape &sh);   // one level below a lane's word (
 hipError_t launch_row_stream_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_row_stream_f64(const Shape &sh, const double *path, double *out, hipStream_t st);
 
-// Many channels (any d >= 2 at N = 2..9; see sig_wide.hip): what serves d > 16, and 9 to 16 channels beyond depth 6; not for
-// chunked scans.
+// Many channels (any d >= 2 at N = 2..9; see sig_wide.hip): what serves d > 16, and 9 to 16 channels beyond depth 6; chunked
+// scans in final mode only.
 bool wide_supported(const Shape &sh, sig_dtype dtype);
 hipError_t launch_wide_f32(const Shape &sh, const float *path, float *out, hipStream_t st);
 hipError_t launch_wide_f64(const Shape &sh, const double *path, double *out, hipStream_t st);

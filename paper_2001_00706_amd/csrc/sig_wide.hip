@@ -70,7 +70,9 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
     for (int c = 0; c < WB; ++c) top[c] = T(0);
 
     const T *bpv = static_cast<const T *>(sh.basepoint_value);
-    const int64_t n_inc = sh.n_inc;
+    // a row is a path or, in a chunked scan (final mode), a stretch of one: every row of a workgroup then walks chunk_len
+    // increments, those past the end of a shorter stretch being zeros (which leave the state as it is)
+    const int64_t n_inc = sh.chunks > 1 ? sh.chunk_len : sh.n_inc;
     // every block of 16 top-level scalars starts on a 16-byte boundary: signatures, levels and rows of d are whole
     // multiples of 16 bytes and so is the output's address
     constexpr int kPer16 = 16 / int(sizeof(T));
@@ -120,11 +122,12 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
                 if (e0 + 256 * j >= staged) break;   // the same for every thread: nothing left to stage
                 const int e = e0 + 256 * j + tid < staged ? e0 + 256 * j + tid : staged - 1;
                 const int p = e / row_floats, r = e - p * row_floats, i = r / pl.dpad, c = r - i * pl.dpad;
-                on[j] = row0 + p < sh.B && t0 + i < n_inc && c < d;
-                const int64_t rp = row0 + p < sh.B ? row0 + p : 0;
+                const ChunkView cv = chunk_view(row0 + p < sh.B ? row0 + p : 0, sh.chunks, sh.chunk_len, sh.n_inc);
+                on[j] = row0 + p < sh.B && t0 + i < cv.n && c < d;
+                const int64_t rp = cv.path;
                 const T *x = path + rp * sh.L * d;
                 const int cc = c < d ? c : 0;
-                const int64_t i_hi = on[j] ? t0 + i + (sh.basepoint ? 0 : 1) : (sh.basepoint ? 0 : 1);
+                const int64_t i_hi = (on[j] ? cv.inc0 + t0 + i : 0) + (sh.basepoint ? 0 : 1);
                 first[j] = i_hi == 0;   // the increment from the basepoint
                 hi[j] = x[i_hi * d + cc];
                 lo[j] = bpv != nullptr && first[j] ? bpv[rp * d + cc] : x[(first[j] ? 0 : i_hi - 1) * d + cc];
@@ -170,7 +173,7 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
 
 bool wide_plan(const Shape &sh, WidePlan &pl)
 {
-    if (sh.N < 2 || sh.N > 9 || sh.d < 2 || sh.chunks > 1 || sh.S >= (int64_t(1) << 31)) return false;
+    if (sh.N < 2 || sh.N > 9 || sh.d < 2 || (sh.chunks > 1 && sh.stream) || sh.S >= (int64_t(1) << 31)) return false;
     // From depth 3 on a thread also walks the chain along its word, about 12 multiply-adds' worth per increment: where the
     // channels fill whole blocks of 32 or 64 letters, the larger block halves or quarters the chain's share (1024 paths of
     // 128 points at d = 32, N = 3: 210 us against 337 with blocks of 16).

@@ -452,6 +452,8 @@ def test_chunked_scan_plus_combine_equals_the_whole_scan():
     # depth 2: the stretches' sums are added (no products); ragged and empty last stretches, many channels, stretches of
     # several tiles
     (3, 1000, 3, 2, 16), (2, 40, 20, 2, 64), (1, 700, 64, 2, 4), (5, 2, 6, 2, 2), (2, 2000, 8, 2, 8),
+    # beyond 16 channels: the stretches on the kernel for many channels (several share a workgroup; ragged and empty ones)
+    (2, 150, 20, 3, 8), (1, 70, 17, 4, 4), (3, 9, 33, 3, 16),
 ])
 def test_chunked_scan_equals_the_plain_scan(B, L, d, N, chunks, dtype):
     torch = torch_mod()
