@@ -226,7 +226,9 @@ int stream_chunks(Family family, const sig::Shape &sh)
     // L = 256, B = 128: 8 chunks take 97 us against 359 at d = 8, N = 3 (4, 16: 146, 94), 57 against 89 at d = 3, N = 5,
     // 78 against 195 at d = 16, N = 2; at B = 1024 nothing is gained, and below ~128 increments the two extra launches
     // cost more than the shorter chain saves.
-    if (sh.n_inc < 128) return 1;
+    // ... for the prefix-tree and one-wavefront kernels; the row kernel gains from 96 increments on (32 paths of 128
+    // points: d = 16, N = 2: 35 us against 79, d = 3, N = 4: 25 against 41; 65 points: no gain)
+    if (sh.n_inc < (family == Family::RowStream ? 96 : 128)) return 1;
     int chunks = 1;
     while (int64_t(chunks) * 2 * chunks * 2 <= sh.n_inc && int64_t(chunks) * 2 * sh.B <= 2048) chunks *= 2;
     return chunks >= 4 ? chunks : 1;

@@ -1,4 +1,4 @@
-// Gradient of the signature with respect to the path for many channels (any d >= 2 at N = 2..9, fp32 and
+// Gradient of the signature with respect to the path for many channels (any d at N = 2..9, fp32 and
 // fp64, final and stream mode): what serves more than 16 channels, where the prefix-tree gradient kernels have no
 // instantiation (paper section 5.3, appendix C.1).
 //
@@ -300,7 +300,7 @@ sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const 
             {
                 T mine = live ? chain[P] : T(0);
                 const T own = mine;
-                for (int k = d; k < 64; k += d) {
+                for (int k = d; k < 64 && pl.words > 1; k += d) {   // (a single word: a single live lane)
                     const T other = __shfl_down(own, unsigned(k));
                     mine += lane + k < 64 ? other : T(0);
                 }
@@ -369,7 +369,7 @@ sig_wide_backward_reduce_kernel(Shape sh, int64_t n_partials, const T *__restric
 
 bool wb_plan(const Shape &sh, size_t elem, WbPlan &pl)
 {
-    if (sh.N < 2 || sh.N > 9 || sh.d < 2 || sh.chunks > 1 || sh.S >= (int64_t(1) << 31) || sh.n_inc < 1) return false;
+    if (sh.N < 2 || sh.N > 9 || sh.d < 1 || sh.chunks > 1 || sh.S >= (int64_t(1) << 31) || sh.n_inc < 1) return false;
     // from depth 3 on, where the channels fill whole blocks of 32 letters, the larger block halves the share of everything a
     // thread does per word rather than per letter (the chain along the word, the sums of its scalars)
     // ... as long as that leaves a thousand workgroups: below, a wavefront's latency per increment is what counts

@@ -60,7 +60,7 @@ def check(x, N, stream=False, basepoint=False, sample=None, seed=0, misalign=Fal
 
 SWEEP = [
     # (B, L, d, N)
-    (1, 2, 1, 1), (3, 2, 1, 5), (2, 5, 2, 1), (5, 3, 2, 2), (4, 17, 3, 4), (2, 9, 5, 3), (3, 6, 7, 3),
+    (1, 2, 1, 1), (3, 2, 1, 5), (2, 40, 1, 3), (2, 5, 2, 1), (5, 3, 2, 2), (4, 17, 3, 4), (2, 9, 5, 3), (3, 6, 7, 3),
     (2, 33, 2, 7), (1, 4, 6, 4), (7, 12, 4, 4), (2, 5, 9, 2), (3, 20, 3, 5), (2, 11, 4, 6), (5, 9, 8, 3),
     (2, 7, 16, 3), (1, 3, 33, 2), (2, 4, 64, 1), (2, 3, 64, 2), (1, 5, 22, 2), (2, 6, 17, 3),
 ]
