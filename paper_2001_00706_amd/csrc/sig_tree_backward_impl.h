@@ -137,6 +137,12 @@ sig_tree_backward_kernel(Shape sh, const T *__restrict__ path, const T *__restri
     if (!live) G = Share{};
     Share A = {};
     if constexpr (!STREAM) A = load_share(sg, false, U >= 2, false);
+    // Stream mode reads a row of the forward output and a row of its cotangent at every increment: both are fetched an
+    // increment ahead of their use, so that a trip to memory is not part of every step of the chain.
+    Share A_ahead = {};
+    if constexpr (STREAM) {
+        if (sh.n_inc >= 2) A_ahead = load_share(sg + (sh.n_inc - 2) * kS, false, U >= 2, false);
+    }
 
     // rows served by this workgroup, for the staging of their increments
     const int64_t row0 = TS::kMulti ? int64_t(blockIdx.x / TS::kGroupsPerPath) : int64_t(blockIdx.x) * PPG;
@@ -172,9 +178,12 @@ sig_tree_backward_kernel(Shape sh, const T *__restrict__ path, const T *__restri
 #pragma unroll
             for (int c = 0; c < D; ++c) zu[c] = zrow[c];
 
+            Share G_ahead = {};
             if constexpr (STREAM) {
                 // the signature after s increments is output entry s-1 (the identity for s = 0)
-                A = s > 0 ? load_share(sg + (s - 1) * kS, false, U >= 2, false) : Share{};
+                A = s > 0 ? A_ahead : Share{};
+                if (s >= 2) A_ahead = load_share(sg + (s - 2) * kS, false, U >= 2, false);
+                if (s > 0 && live) G_ahead = load_share(go + (s - 1) * kS, true, true, true);   // added at the end of this step
             }
 
             // ---- up: Hn[j][k] = T^(k)_j at this thread's word; the signature before the increment
@@ -283,7 +292,7 @@ sig_tree_backward_kernel(Shape sh, const T *__restrict__ path, const T *__restri
 
             if constexpr (STREAM) {
                 if (s > 0 && live) {
-                    const Share add = load_share(go + (s - 1) * kS, true, true, true);
+                    const Share &add = G_ahead;
 #pragma unroll
                     for (int j = 1; j <= P; ++j) G.lo[j] += add.lo[j];
                     if constexpr (U >= 1) {

@@ -168,6 +168,10 @@ sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const 
         }
     }
 
+    T Alo_ahead[P + 1];   // stream mode: the signature before the next increment to be undone
+#pragma unroll
+    for (int i = 1; i <= P; ++i) Alo_ahead[i] = STREAM && sh.n_inc >= 2 ? sg[(sh.n_inc - 2) * sh.S + sh.off[i] + pre[i]] : T(0);
+
     const T *x = path + row * sh.L * d;
     const T *bpv = static_cast<const T *>(sh.basepoint_value);
     T *my_part = part + wave_in_group * pl.dpad;   // + increment * 4 * dpad
@@ -211,13 +215,21 @@ sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const 
 #pragma unroll
             for (int c = 0; c < WB; ++c) zb[c] = zb_next[c / 4][c % 4];
             read_step(i > 0 ? i - 1 : 0);
+            T Glo_ahead[P + 1], Gtop_ahead[WB];
             if constexpr (STREAM) {
-                // the signature after s increments is output entry s - 1 (the identity for s = 0)
+                // the signature after s increments is output entry s - 1 (the identity for s = 0): fetched an increment
+                // ahead, like the row of the cotangent that is added at the end of this step, so that a trip to memory
+                // is not part of every step of the chain
 #pragma unroll
                 for (int j = 1; j <= P; ++j) {
-                    const T v = sg[(s > 0 ? s - 1 : 0) * sh.S + sh.off[j] + pre[j]];
-                    Alo[j] = s > 0 ? v : T(0);
+                    Alo[j] = s > 0 ? Alo_ahead[j] : T(0);
+                    Alo_ahead[j] = sg[(s > 1 ? s - 2 : 0) * sh.S + sh.off[j] + pre[j]];
                 }
+                const T *g_row = go + (s > 0 ? s - 1 : 0) * sh.S;
+#pragma unroll
+                for (int j = 1; j <= P; ++j) Glo_ahead[j] = g_row[sh.off[j] + pre[j]];
+#pragma unroll
+                for (int c = 0; c < WB; ++c) Gtop_ahead[c] = g_row[sh.off[N] + u * d + (live && j0 + c < d ? j0 + c : 0)];
             }
 
             // ---- up: Hn[j][k] = T^(k)_j at this thread's word; the signature before the increment
@@ -309,18 +321,10 @@ sig_wide_backward_kernel(Shape sh, WbPlan pl, const T *__restrict__ path, const 
 
             if constexpr (STREAM) {
                 if (s > 0) {
-                    const T *g_row = go + (s - 1) * sh.S;
 #pragma unroll
-                    for (int j = 1; j <= P; ++j) {
-                        const T v = g_row[sh.off[j] + pre[j]];
-                        Glo[j] += first[j] ? v : T(0);
-                    }
+                    for (int j = 1; j <= P; ++j) Glo[j] += first[j] ? Glo_ahead[j] : T(0);
 #pragma unroll
-                    for (int c = 0; c < WB; ++c) {
-                        const bool on = live && j0 + c < d;
-                        const T v = g_row[sh.off[N] + u * d + (on ? j0 + c : 0)];
-                        Gtop[c] += on ? v : T(0);
-                    }
+                    for (int c = 0; c < WB; ++c) Gtop[c] += live && j0 + c < d ? Gtop_ahead[c] : T(0);
                 }
             }
         }
