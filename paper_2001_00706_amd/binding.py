@@ -70,9 +70,47 @@ class SigError(RuntimeError):
         self.status = status
 
 
+class _NoGuard:
+    """Stands in for `torch.cuda.device(...)` when the tensor's device is the current one already."""
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        return False
+
+
+_NO_GUARD = _NoGuard()
+
+
+def _on_device(device):
+    """A context in which `device` is the current HIP device (the library launches on the current device): a guard only
+    when it is not already; entering `torch.cuda.device` costs about 2 us per call."""
+    import torch
+
+    index = device.index
+    if index is None or index == torch.cuda.current_device():
+        return _NO_GUARD
+    return torch.cuda.device(device)
+
+
+def _current_stream() -> int:
+    """The raw handle of torch's current stream on the current device (`torch.cuda.current_stream().cuda_stream` builds a
+    Stream object on every call: 2.7 us against 0.1)."""
+    import torch
+
+    try:
+        return torch._C._cuda_getCurrentRawStream(torch.cuda.current_device())
+    except AttributeError:   # a torch without the raw accessor
+        return torch.cuda.current_stream().cuda_stream
+
+
+
 def load_library() -> ctypes.CDLL:
     """Loads `libsig.so`; raises if it has not been built (`__graft_entry__.build()`)."""
     global _lib
+    if _lib is not None:
+        return _lib
     with _lock:
         if _lib is not None:
             return _lib
@@ -220,8 +258,8 @@ def sig_forward(path, N: int, stream: bool = False, basepoint: bool = False, out
         if out.dtype != path.dtype or out.device != path.device or tuple(out.shape) != shape \
                 or not out.is_contiguous():
             raise ValueError(f"out must be a contiguous {path.dtype} tensor of shape {shape} on {path.device}")
-    with torch.cuda.device(path.device):
-        hip_stream = torch.cuda.current_stream().cuda_stream
+    with _on_device(path.device):
+        hip_stream = _current_stream()
         status = sig_forward_raw(path.data_ptr(), B, L, d, N, int(stream), int(basepoint), dtype,
                                  out.data_ptr(), hip_stream, variant)
     if status != SIG_OK:
@@ -254,9 +292,9 @@ def sig_combine(a, b, d: int, N: int, out=None):
         out = torch.empty_like(a)
     elif out.dtype != a.dtype or out.device != a.device or out.shape != a.shape or not out.is_contiguous():
         raise ValueError("out must match a")
-    with torch.cuda.device(a.device):
+    with _on_device(a.device):
         status = int(load_library().sig_combine(a.data_ptr(), b.data_ptr(), a.shape[0], d, N, dtype,
-                                                out.data_ptr(), torch.cuda.current_stream().cuda_stream))
+                                                out.data_ptr(), _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out
@@ -329,7 +367,7 @@ def sig_backward(path, sig, grad_out, N: int, stream: bool = False, basepoint=Fa
     if grad_basepoint is not None and (grad_basepoint.dtype != path.dtype or grad_basepoint.device != path.device
                                        or tuple(grad_basepoint.shape) != (B, d) or not grad_basepoint.is_contiguous()):
         raise ValueError("grad_basepoint must be a contiguous [B, d] tensor like path")
-    with torch.cuda.device(path.device):
+    with _on_device(path.device):
         need = sig_backward_workspace_bytes(B, L, d, N, stream, bool(bp_flag), dtype)
         if need > 0 and workspace is None:
             workspace = torch.empty(need, dtype=torch.uint8, device=path.device)
@@ -339,7 +377,7 @@ def sig_backward(path, sig, grad_out, N: int, stream: bool = False, basepoint=Fa
             path.data_ptr(), sig.data_ptr(), grad_out.data_ptr(), B, L, d, N, int(stream), bp_flag,
             bp_value.data_ptr() if bp_value is not None else 0, dtype, grad_path.data_ptr(),
             grad_basepoint.data_ptr() if grad_basepoint is not None else 0,
-            ws_ptr, ws_bytes, torch.cuda.current_stream().cuda_stream))
+            ws_ptr, ws_bytes, _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return grad_path
@@ -371,11 +409,11 @@ def sig_signature(path, N: int, stream: bool = False, basepoint=False, inverse: 
         out = torch.empty(shape, dtype=path.dtype, device=path.device)
     elif out.dtype != path.dtype or out.device != path.device or tuple(out.shape) != shape or not out.is_contiguous():
         raise ValueError(f"out must be a contiguous {path.dtype} tensor of shape {shape} on {path.device}")
-    with torch.cuda.device(path.device):
+    with _on_device(path.device):
         status = int(load_library().sig_signature(
             path.data_ptr(), B, L, d, N, int(stream), bp_flag, bp_value.data_ptr() if bp_value is not None else 0,
             initial.data_ptr() if initial is not None else 0, int(bool(inverse)), dtype, out.data_ptr(),
-            torch.cuda.current_stream().cuda_stream))
+            _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out
@@ -395,9 +433,9 @@ def sig_invert(sig, d: int, N: int, out=None):
     elif out.dtype != sig.dtype or out.device != sig.device or out.shape != sig.shape or not out.is_contiguous():
         raise ValueError("out must match sig")
     rows = sig.numel() // S if S > 0 else 0
-    with torch.cuda.device(sig.device):
+    with _on_device(sig.device):
         status = int(load_library().sig_invert(sig.data_ptr(), rows, d, N, dtype, out.data_ptr(),
-                                               torch.cuda.current_stream().cuda_stream))
+                                               _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out
@@ -416,10 +454,10 @@ def sig_combine_strided(a, a_stride: int, b, b_stride: int, B: int, d: int, N: i
             raise ValueError("a, b and out must be contiguous tensors of one dtype on one device")
         if B > 0 and (B - 1) * stride + S > t.numel():
             raise ValueError("an operand is too small for B signatures at this stride")
-    with torch.cuda.device(a.device):
+    with _on_device(a.device):
         status = int(load_library().sig_combine_strided(a.data_ptr(), a_stride, b.data_ptr(), b_stride, B, d, N, dtype,
                                                         out.data_ptr(), out_stride,
-                                                        torch.cuda.current_stream().cuda_stream))
+                                                        _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out
@@ -456,9 +494,9 @@ def sig_log(sig, d: int, N: int, out=None):
             or out.data_ptr() == sig.data_ptr():
         raise ValueError("out must match sig and be a different tensor")
     rows = sig.numel() // S
-    with torch.cuda.device(sig.device):
+    with _on_device(sig.device):
         status = int(load_library().sig_log(sig.data_ptr(), rows, d, N, dtype, out.data_ptr(),
-                                            torch.cuda.current_stream().cuda_stream))
+                                            _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out
@@ -497,9 +535,9 @@ def sig_lyndon_gather(log_sig, d: int, N: int, out=None):
     elif out.dtype != log_sig.dtype or out.device != log_sig.device or tuple(out.shape) != shape or not out.is_contiguous():
         raise ValueError(f"out must be a contiguous tensor of shape {shape}")
     rows = log_sig.numel() // S
-    with torch.cuda.device(log_sig.device):
+    with _on_device(log_sig.device):
         status = int(load_library().sig_lyndon_gather(log_sig.data_ptr(), rows, d, N, table.data_ptr(), n, dtype,
-                                                      out.data_ptr(), torch.cuda.current_stream().cuda_stream))
+                                                      out.data_ptr(), _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out
@@ -523,9 +561,9 @@ def sig_lyndon_scatter(grad_logsig, d: int, N: int, out=None):
             or not out.is_contiguous():
         raise ValueError(f"out must be a contiguous tensor of shape {shape}")
     rows = out.numel() // S
-    with torch.cuda.device(out.device):
+    with _on_device(out.device):
         status = int(load_library().sig_lyndon_scatter(grad_logsig.data_ptr(), rows, d, N, table.data_ptr(), n, dtype,
-                                                       out.data_ptr(), torch.cuda.current_stream().cuda_stream))
+                                                       out.data_ptr(), _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out
@@ -555,7 +593,7 @@ def sig_log_backward(sig, grad_log, d: int, N: int, out=None, workspace=None):
         raise ValueError("out must match sig and be a different tensor")
     rows = sig.numel() // S
     lib = load_library()
-    with torch.cuda.device(sig.device):
+    with _on_device(sig.device):
         need = int(lib.sig_log_backward_workspace_bytes(rows, d, N, dtype))
         if need < 0:
             raise SigError(SIG_ERR_UNSUPPORTED, "no workspace size for this shape")
@@ -564,7 +602,7 @@ def sig_log_backward(sig, grad_log, d: int, N: int, out=None, workspace=None):
         ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) \
             if workspace is not None else (0, 0)
         status = int(lib.sig_log_backward(sig.data_ptr(), grad_log.data_ptr(), rows, d, N, dtype, out.data_ptr(), ws_ptr,
-                                          ws_bytes, torch.cuda.current_stream().cuda_stream))
+                                          ws_bytes, _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out
@@ -610,13 +648,13 @@ def sig_forward_chunked(path, N: int, chunks: int, basepoint=False, out=None, wo
         out = torch.empty((B, S), dtype=path.dtype, device=path.device)
     elif out.dtype != path.dtype or out.device != path.device or tuple(out.shape) != (B, S) or not out.is_contiguous():
         raise ValueError(f"out must be a contiguous {path.dtype} tensor of shape {(B, S)} on {path.device}")
-    with torch.cuda.device(path.device):
+    with _on_device(path.device):
         if workspace is None:
             workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=path.device)
         status = int(load_library().sig_forward_chunked(
             path.data_ptr(), B, L, d, N, bp_flag, bp_value.data_ptr() if bp_value is not None else 0, chunks, dtype,
             out.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-            torch.cuda.current_stream().cuda_stream))
+            _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out
@@ -645,10 +683,10 @@ def sig_forward_chunked_static(path, N: int, chunks: int, basepoint=False, out=N
         out = torch.empty((B, S), dtype=path.dtype, device=path.device)
     elif out.dtype != path.dtype or out.device != path.device or tuple(out.shape) != (B, S) or not out.is_contiguous():
         raise ValueError(f"out must be a contiguous {path.dtype} tensor of shape {(B, S)} on {path.device}")
-    with torch.cuda.device(path.device):
+    with _on_device(path.device):
         status = int(load_library().sig_forward_chunked_static(
             path.data_ptr(), B, L, d, N, bp_flag, bp_value.data_ptr() if bp_value is not None else 0, chunks, dtype,
-            out.data_ptr(), torch.cuda.current_stream().cuda_stream))
+            out.data_ptr(), _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out
@@ -669,14 +707,14 @@ def sig_combine_many(sigs, d: int, N: int, out=None, workspace=None):
     elif out.dtype != sigs.dtype or out.device != sigs.device or tuple(out.shape) != (B, S) or not out.is_contiguous():
         raise ValueError(f"out must be a contiguous tensor of shape {(B, S)} like sigs")
     lib = load_library()
-    with torch.cuda.device(sigs.device):
+    with _on_device(sigs.device):
         need = int(lib.sig_combine_many_workspace_bytes(B, n, d, N, dtype))
         if need > 0 and workspace is None:
             workspace = torch.empty(need, dtype=torch.uint8, device=sigs.device)
         ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) \
             if workspace is not None else (0, 0)
         status = int(lib.sig_combine_many(sigs.data_ptr(), B, n, d, N, dtype, out.data_ptr(), ws_ptr, ws_bytes,
-                                          torch.cuda.current_stream().cuda_stream))
+                                          _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out
@@ -710,7 +748,7 @@ def sig_combine_backward(a, b, grad_out, d: int, N: int, grad_a=None, grad_b=Non
             raise ValueError("grad_a and grad_b must match a")
         outs.append(t)
     lib = load_library()
-    with torch.cuda.device(a.device):
+    with _on_device(a.device):
         need = int(lib.sig_combine_backward_workspace_bytes(a.shape[0], d, N, dtype))
         if need < 0:
             raise SigError(SIG_ERR_UNSUPPORTED, "no workspace size for this shape")
@@ -720,7 +758,7 @@ def sig_combine_backward(a, b, grad_out, d: int, N: int, grad_a=None, grad_b=Non
             if workspace is not None else (0, 0)
         status = int(lib.sig_combine_backward(a.data_ptr(), b.data_ptr(), grad_out.data_ptr(), a.shape[0], d, N, dtype,
                                               outs[0].data_ptr(), outs[1].data_ptr(), ws_ptr, ws_bytes,
-                                              torch.cuda.current_stream().cuda_stream))
+                                              _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return outs[0], outs[1]
@@ -750,9 +788,9 @@ def sig_combine_grouped(a, sigs, d: int, N: int, out=None):
         out = torch.empty_like(sigs)
     elif out.dtype != sigs.dtype or out.device != sigs.device or out.shape != sigs.shape or not out.is_contiguous():
         raise ValueError("out must match sigs")
-    with torch.cuda.device(a.device):
+    with _on_device(a.device):
         status = int(load_library().sig_combine_grouped(a.data_ptr(), sigs.data_ptr(), sigs.shape[0], sigs.shape[1], d, N,
-                                                        _dtype_of(a), out.data_ptr(), torch.cuda.current_stream().cuda_stream))
+                                                        _dtype_of(a), out.data_ptr(), _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return out
@@ -781,7 +819,7 @@ def sig_combine_grouped_backward(a, sigs, grad_out, d: int, N: int, grad_a=None,
         outs.append(t)
     lib = load_library()
     dtype = _dtype_of(a)
-    with torch.cuda.device(a.device):
+    with _on_device(a.device):
         need = int(lib.sig_combine_grouped_backward_workspace_bytes(sigs.shape[0], sigs.shape[1], d, N, dtype))
         if need < 0:
             raise SigError(SIG_ERR_UNSUPPORTED, "no workspace size for this shape")
@@ -790,7 +828,7 @@ def sig_combine_grouped_backward(a, sigs, grad_out, d: int, N: int, grad_a=None,
         status = int(lib.sig_combine_grouped_backward(a.data_ptr(), sigs.data_ptr(), grad_out.data_ptr(), sigs.shape[0],
                                                       sigs.shape[1], d, N, dtype, outs[0].data_ptr(), outs[1].data_ptr(),
                                                       workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                                                      torch.cuda.current_stream().cuda_stream))
+                                                      _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return outs[0], outs[1]
