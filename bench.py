@@ -193,7 +193,7 @@ def main() -> int:
     def step():
         # the C call on raw device addresses, on torch's current stream
         st = sig.sig_forward_raw(x.data_ptr(), w.B, w.L, w.d, w.N, int(w.stream), int(w.basepoint), sig.SIG_F32,
-                                 out.data_ptr(), torch.cuda.current_stream().cuda_stream, variant)
+                                 out.data_ptr(), sig.current_stream_handle(), variant)
         if st != sig.SIG_OK:
             raise sig.SigError(st, sig.sig_status_string(st))
 

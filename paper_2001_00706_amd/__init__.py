@@ -52,6 +52,7 @@ from .binding import (  # noqa: F401
     sig_forward_chunked_static,
     sig_forward_chunked_static_max_bytes,
     sig_forward_raw,
+    current_stream_handle,
     sig_fused_fmas,
     sig_output_elems,
     sig_signature_channels,

@@ -94,6 +94,11 @@ def _on_device(device):
     return torch.cuda.device(device)
 
 
+def current_stream_handle() -> int:
+    """The raw handle of torch's current stream on the current device, for callers of the `*_raw` functions."""
+    return _current_stream()
+
+
 def _current_stream() -> int:
     """The raw handle of torch's current stream on the current device (`torch.cuda.current_stream().cuda_stream` builds a
     Stream object on every call: 2.7 us against 0.1)."""
