@@ -218,8 +218,13 @@ hipError_t launch_scan(Family family, const sig::Shape &sh, sig_dtype dtype, con
 // signature of everything before it.
 int stream_chunks(Family family, const sig::Shape &sh)
 {
-    if (!sh.stream || sh.chunks != 1 || (family != Family::Small && family != Family::Tree && family != Family::RowStream))
+    if (!sh.stream || sh.chunks != 1 ||
+        (family != Family::Small && family != Family::Tree && family != Family::RowStream && family != Family::Wide))
         return 1;
+    // the kernel for many channels: at depth 2 up to 64 channels only (32 below 192 increments; beyond, a path has
+    // workgroups enough, and from depth 3 on the chain of products along the chunk ends costs more than it saves: 32 paths of 128 points at d = 20, N = 3
+    // take 283 us in chunks against 103)
+    if (family == Family::Wide && (sh.N != 2 || sh.d > 64 || (sh.d > 32 && sh.n_inc < 192))) return 1;
     if (sh.S >= (int64_t(1) << 31)) return 1;
     // Two scans of n_inc / chunks increments each and a chain of chunks - 1 products (about the cost of an increment
     // each) are shortest near sqrt(n_inc) chunks; more than ~2048 rows at a time add no parallelism.  Measured at
@@ -228,7 +233,7 @@ int stream_chunks(Family family, const sig::Shape &sh)
     // cost more than the shorter chain saves.
     // ... for the prefix-tree and one-wavefront kernels; the row kernel gains from 96 increments on (32 paths of 128
     // points: d = 16, N = 2: 35 us against 79, d = 3, N = 4: 25 against 41; 65 points: no gain)
-    if (sh.n_inc < (family == Family::RowStream ? 96 : 128)) return 1;
+    if (sh.n_inc < (family == Family::RowStream || family == Family::Wide ? 96 : 128)) return 1;
     int chunks = 1;
     while (int64_t(chunks) * 2 * chunks * 2 <= sh.n_inc && int64_t(chunks) * 2 * sh.B <= 2048) chunks *= 2;
     return chunks >= 4 ? chunks : 1;

@@ -23,8 +23,8 @@ struct Shape {
     // basepoint_value is indexed by path.  chunks == 1: B counts paths.
     int chunks;
     int64_t chunk_len;
-    // Chunked scans whose rows live inside a stream-mode output [paths][n_inc][S] (served by the small-state and the
-    // prefix-tree families only): with stream == 0 a chunk that has increments writes its signature to the row of its
+    // Chunked scans whose rows live inside a stream-mode output [paths][n_inc][S] (served by the small-state, prefix-tree,
+    // row and many-channel families): with stream == 0 a chunk that has increments writes its signature to the row of its
     // last increment; with stream != 0 a chunk starts from the row before its first increment (the empty signature
     // at the start of a path) and writes the row of every increment of its own but the last.  0: rows are packed.
     int rows_in_stream;

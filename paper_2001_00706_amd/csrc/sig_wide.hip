@@ -70,9 +70,15 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
     for (int c = 0; c < WB; ++c) top[c] = T(0);
 
     const T *bpv = static_cast<const T *>(sh.basepoint_value);
-    // a row is a path or, in a chunked scan (final mode), a stretch of one: every row of a workgroup then walks chunk_len
-    // increments, those past the end of a shorter stretch being zeros (which leave the state as it is)
+    // a row is a path or, in a chunked scan, a stretch of one: every row of a workgroup then walks chunk_len increments,
+    // those past the end of a shorter stretch being zeros (which leave the state as it is)
     const int64_t n_inc = sh.chunks > 1 ? sh.chunk_len : sh.n_inc;
+    // Stretches laid out inside a stream-mode output (Shape::rows_in_stream): in final mode a stretch writes its
+    // signature to the row of its last increment; in stream mode it starts from the row before its first increment
+    // and writes the rows of its increments but the last, which holds its final value already.
+    const ChunkView mine = chunk_view(row < sh.B ? row : 0, sh.chunks, sh.chunk_len, sh.n_inc);
+    T *stream_rows = out + (sh.rows_in_stream ? mine.path * sh.n_inc + mine.inc0 : row * sh.n_inc) * sh.S;
+    const int64_t rows_to_write = sh.rows_in_stream ? mine.n - 1 : mine.n;
     // every block of 16 top-level scalars starts on a 16-byte boundary: signatures, levels and rows of d are whole
     // multiples of 16 bytes and so is the output's address
     constexpr int kPer16 = 16 / int(sizeof(T));
@@ -106,6 +112,18 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
                 if (j0 + c < d) o_top[c] = top[c];
         }
     };
+
+    if (sh.rows_in_stream && sh.stream && live && mine.inc0 > 0 && mine.n > 0) {
+        const T *before = stream_rows - sh.S;   // the path's signature up to this stretch
+        int64_t q = u;
+#pragma unroll
+        for (int i = P; i >= 1; --i) {
+            A[i] = before[sh.off[i] + q];
+            q /= d;
+        }
+#pragma unroll
+        for (int c = 0; c < WB; ++c) top[c] = j0 + c < d ? before[sh.off[N] + u * d + j0 + c] : T(0);
+    }
 
     const int row_floats = kWideTile * pl.dpad;
     for (int64_t t0 = 0; t0 < n_inc; t0 += kWideTile) {
@@ -165,15 +183,20 @@ sig_wide_kernel(Shape sh, WidePlan pl, const T *__restrict__ path, T *__restrict
 #pragma unroll
                 for (int k = 0; k < kPer16; ++k) top[c + k] = wide_fma(Hn[N], zv[k], top[c + k]);
             }
-            if (sh.stream && live) store(out + (row * n_inc + t0 + s) * sh.S);
+            if (sh.stream && live && t0 + s < rows_to_write) store(stream_rows + (t0 + s) * sh.S);
         }
     }
-    if (live && !sh.stream) store(out + row * sh.S);
+    if (live && !sh.stream) {
+        if (!sh.rows_in_stream)
+            store(out + row * sh.S);
+        else if (mine.n > 0)
+            store(stream_rows + (mine.n - 1) * sh.S);
+    }
 }
 
 bool wide_plan(const Shape &sh, WidePlan &pl)
 {
-    if (sh.N < 2 || sh.N > 9 || sh.d < 2 || (sh.chunks > 1 && sh.stream) || sh.S >= (int64_t(1) << 31)) return false;
+    if (sh.N < 2 || sh.N > 9 || sh.d < 2 || (sh.chunks > 1 && sh.stream && !sh.rows_in_stream) || sh.S >= (int64_t(1) << 31)) return false;
     // From depth 3 on a thread also walks the chain along its word, about 12 multiply-adds' worth per increment: where the
     // channels fill whole blocks of 32 or 64 letters, the larger block halves or quarters the chain's share (1024 paths of
     // 128 points at d = 32, N = 3: 210 us against 337 with blocks of 16).

@@ -489,11 +489,13 @@ def test_chunked_scan_argument_checks():
 # From 128 increments on (and up to 512 paths) the small-state and prefix-tree families cut a stream-mode scan into
 # chunks: chunk signatures at the chunk ends, a running product along them, every chunk scanned again from the row
 # before it.  Shapes: several paths per workgroup (d = 3, 8, 6), several workgroups per path (d = 5, N = 6), one level
-# below a thread's word (d = 12), the one-wavefront kernel (d = 2, 3, 20); lengths that leave a ragged last chunk, a
+# below a thread's word (d = 12), the one-wavefront kernel (d = 2, 3, 20), the kernel for many channels (d = 17, 20, 32);
+# lengths that leave a ragged last chunk, a
 # last chunk of one increment (n_inc = 129 in 4 chunks of 33) and many chunks (n_inc = 1100: 16 chunks).
 @pytest.mark.parametrize("B,L,d,N", [
     (3, 130, 3, 5), (2, 257, 8, 3), (5, 200, 6, 3), (1, 130, 5, 6), (2, 140, 12, 3), (3, 1101, 3, 4), (17, 129, 7, 2),
     (4, 130, 2, 5), (2, 300, 3, 3), (3, 129, 20, 1), (2, 513, 2, 8), (4, 130, 2, 3), (2, 200, 8, 4), (3, 131, 16, 2),
+    (2, 150, 20, 3), (3, 130, 17, 2), (1, 140, 32, 3), (2, 129, 9, 7 - 2),   # beyond 16 channels: the kernel for many channels
 ])
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 def test_stream_mode_cut_into_chunks(B, L, d, N, dtype):
