@@ -301,12 +301,14 @@ bool backward_supported(const Shape &sh)
     return sh.d <= 64 && make_plan(sh, kBackwardThreads, pl);
 }
 
-// Final mode at depths 3 and 4 from 9 channels on, where the prefix-tree kernels also keep one level per thread: the
+// Final mode at depths 3 to 6 from 9 channels on, where the prefix-tree kernels also keep one level per thread: the
 // kernel for many channels is ahead from 12 channels on (128 points, N = 3, d = 16: 98 us against 274 at 32 paths, 183
 // against 336 at 1024; d = 12, N = 4: 144 against 261 and 1260 against 1500) and below 256 paths from 9 on (d = 9,
 // N = 3: 128 against 167 at 32 paths, 204 against 176 at 1024).  d = 16, N = 4 has a kernel of its own.
 bool wide_backward_preferred(const Shape &sh, sig_dtype dtype)
 {
+    if (sh.N == 5 || sh.N == 6)   // d = 16: 1.4 to 1.65 times the prefix-tree kernels, d = 12: 1.0 to 1.15, d = 9: 0.6 to 0.7
+        return !sh.stream && sh.d >= 13 && sh.d <= 16 && wide_backward_supported(sh, dtype);
     return !sh.stream && (sh.N == 3 || sh.N == 4) && sh.d >= 9 && sh.d <= 16 && (sh.d >= 12 || sh.B < 256) &&
            !(sh.d == 16 && sh.N == 4) && wide_backward_supported(sh, dtype);
 }

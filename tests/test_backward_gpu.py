@@ -230,6 +230,7 @@ def test_depth_two_gradient_by_its_closed_form(B, L, d, dtype):
     (2, 7, 40, 3), (1, 4, 18, 4),     # 75 and 365 wavefronts per path
     (3, 20, 12, 3), (2, 6, 9, 4),     # final mode from 9 channels on at few paths: picked over the prefix-tree kernels
     (2, 5, 17, 5), (1, 3, 9, 7),      # deeper
+    (1, 4, 14, 5),                    # final mode at depths 5 and 6 from 13 channels on: picked over the prefix-tree kernels
 ])
 def test_many_channels_at_low_depth(B, L, d, N, dtype):
     x = uniform_paths(B, L, d, seed=4000 + L + d, lo=-0.4, hi=0.4).astype(dtype)
