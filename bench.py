@@ -127,9 +127,18 @@ def measure_peaks(torch, dev):
     write_cached = (128 << 20) / (t * 1e-3) / 1e9
     t = best_ms(lambda: lib.sig_peak_hbm_copy(big.data_ptr() + half, big.data_ptr(), half, hs))
     copy = 2 * half / (t * 1e-3) / 1e9
+    # adding into LDS: ns per wavefront operation and compute unit, 8 workgroups of 4 wavefronts on each of 256 units
+    lib.sig_peak_lds_add.restype = i32
+    lib.sig_peak_lds_add.argtypes = [vp, i32, i32, i32, i32, i32, vp]
+    lds = {}
+    for key, active, stride, atomic in (("lds_atomic_add_64_lanes_ns", 64, 1, 1), ("lds_atomic_add_16_lanes_ns", 16, 1, 1),
+                                        ("lds_atomic_add_4_lanes_ns", 4, 1, 1), ("lds_atomic_add_64_lanes_one_address_ns", 64, 0, 1),
+                                        ("lds_read_add_write_64_lanes_ns", 64, 1, 0)):
+        t = best_ms(lambda: lib.sig_peak_lds_add(sink.data_ptr(), 256 * 8, 4096, active, stride, atomic, hs))
+        lds[key] = t * 1e6 / (8 * 4 * 4096)
     del big, sink
     return {"mfma_f32_32x32x2_tflops": mfma, "mfma_f32_4x4x1_tflops": mfma4, "valu_f32_fma_tflops": valu,
-            "hbm_write_1GiB_gbs": write, "write_128MiB_last_level_cache_gbs": write_cached, "hbm_copy_512MiB_gbs": copy}
+            "hbm_write_1GiB_gbs": write, "write_128MiB_last_level_cache_gbs": write_cached, "hbm_copy_512MiB_gbs": copy, **lds}
 
 
 def main() -> int:

@@ -37,6 +37,13 @@ int sig_peak_hbm_write(void *dst, int64_t bytes, hipStream_t hip_stream);
  * overlapping).  Work: `bytes` read + `bytes` written. */
 int sig_peak_hbm_copy(void *dst, const void *src, int64_t bytes, hipStream_t hip_stream);
 
+/* Adding into LDS: `workgroups` x 4 wavefronts, each repeating `iters` times one float add into its own row of 64
+ * scalars, `active_lanes` (1..64) lanes taking part, lane l at scalar (l * stride) % 64 (stride 1: an address per lane,
+ * 0: one address for all).  atomic != 0: an LDS atomic add; 0: a read, an add and a write (only meaningful with distinct
+ * addresses).  Work: workgroups * 4 * iters wavefront operations; with 8 workgroups per compute unit the time per
+ * operation and compute unit shows what the LDS port sustains. */
+int sig_peak_lds_add(float *sink, int workgroups, int iters, int active_lanes, int stride, int atomic, hipStream_t hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

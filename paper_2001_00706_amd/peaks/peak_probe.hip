@@ -85,6 +85,30 @@ __global__ __launch_bounds__(kThreads) void hbm_copy_kernel(f4 *__restrict__ dst
         __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+// The cost of adding into LDS: every wavefront of a workgroup repeats one float add into its own row of 64 scalars,
+// with `active` lanes taking part and lane l adding at scalar (l * stride) % 64 (stride 1: every lane its own address,
+// 0: all lanes one address).  ATOMIC: ds_add_f32; otherwise a read, an add and a write.
+template <bool ATOMIC>
+__global__ __launch_bounds__(kThreads) void lds_add_kernel(float *__restrict__ sink, int iters, int active, int stride)
+{
+    __shared__ float row[kThreads / 64][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    row[w][lane] = 0.f;
+    __syncthreads();
+    const float v = float(lane) * 1e-3f;
+    float *slot = &row[w][(lane * stride) & 63];
+    for (int it = 0; it < iters; ++it) {
+        if (lane < active) {
+            if (ATOMIC)
+                atomicAdd(slot, v);
+            else
+                *slot = *slot + v;
+        }
+    }
+    __syncthreads();
+    sink[blockIdx.x * kThreads + threadIdx.x] = row[w][lane];
+}
+
 int finish()
 {
     const hipError_t e = hipGetLastError();
@@ -145,5 +169,16 @@ extern "C" int sig_peak_hbm_copy(void *dst, const void *src, int64_t bytes, hipS
     const int64_t n16 = bytes / 16;
     hipLaunchKernelGGL(hbm_copy_kernel, dim3(memory_grid(n16)), dim3(kThreads), 0, hip_stream,
                        static_cast<f4 *>(dst), static_cast<const f4 *>(src), n16);
+    return finish();
+}
+
+extern "C" int sig_peak_lds_add(float *sink, int workgroups, int iters, int active_lanes, int stride, int atomic,
+                                hipStream_t hip_stream)
+{
+    if (bad_compute_args(sink, workgroups, iters) || active_lanes < 1 || active_lanes > 64 || stride < 0 || stride > 64) return -1;
+    if (atomic)
+        hipLaunchKernelGGL(lds_add_kernel<true>, dim3(workgroups), dim3(kThreads), 0, hip_stream, sink, iters, active_lanes, stride);
+    else
+        hipLaunchKernelGGL(lds_add_kernel<false>, dim3(workgroups), dim3(kThreads), 0, hip_stream, sink, iters, active_lanes, stride);
     return finish();
 }
