@@ -58,7 +58,7 @@ def test_peaks_library_exports_every_symbol_its_header_declares():
     if not os.path.exists(PEAKS_LIB_PATH):
         build_peaks_lib()
     declared = _declared(os.path.join(ROOT, "include", "sig_peaks.h"), "sig_peak_")
-    assert len(declared) == 5
+    assert len(declared) == 6
     plib = ctypes.CDLL(PEAKS_LIB_PATH)
     for name in declared:
         assert getattr(plib, name) is not None
