@@ -68,16 +68,20 @@ sig_backward_n2_kernel(Shape sh, int points_per_group, int passes, const T *__re
         };
         T a = T(0), bb = T(0);
         if (exists) {
+            // Differences of points only (a path far from the origin loses nothing): m_e - p is (X_{k-1} - p) plus half
+            // of increment e, and an interior point keeps m_{k-1} - m_k = (X_{k-1} - X_{k+1}) / 2 alone.
             const T p = scan_point(0), q = scan_point(sh.n_inc), here = scan_point(k);
-            if (ends) {
-                const T m = (scan_point(k - 1) + here) * T(0.5);
-                a += m - p;
-                bb += q - m;
-            }
-            if (starts) {
-                const T m = (here + scan_point(k + 1)) * T(0.5);
-                a -= m - p;
-                bb -= q - m;
+            if (ends && starts) {
+                a = (scan_point(k - 1) - scan_point(k + 1)) * T(0.5);
+                bb = -a;
+            } else if (ends) {
+                const T before = scan_point(k - 1), half = (here - before) * T(0.5);
+                a = (before - p) + half;
+                bb = (q - here) + half;
+            } else if (starts) {
+                const T after = scan_point(k + 1), half = (after - here) * T(0.5);
+                a = -((here - p) + half);
+                bb = -((q - after) + half);
             }
         }
         va[e] = a;

@@ -65,9 +65,10 @@ sig_backward_n2_mfma_kernel(Shape sh, B2mPlan pl, const float *__restrict__ path
         for (int e = tid; e < 2 * d; e += 256) {
             const int which = e / d, c = e - which * d;   // 0: the first increment, 1: the last
             const int64_t s = which == 0 ? 0 : n - 1;
-            const float m = (scan_point(s, c) + scan_point(s + 1, c)) * 0.5f;
-            ends[(2 * which) * d + c] = m - scan_point(0, c);
-            ends[(2 * which + 1) * d + c] = scan_point(n, c) - m;
+            // differences of points only, so that a path far from the origin loses nothing
+            const float xs = scan_point(s, c), xt = scan_point(s + 1, c), half = (xt - xs) * 0.5f;
+            ends[(2 * which) * d + c] = (xs - scan_point(0, c)) + half;
+            ends[(2 * which + 1) * d + c] = (scan_point(n, c) - xt) + half;
         }
     }
     __syncthreads();

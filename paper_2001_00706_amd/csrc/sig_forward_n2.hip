@@ -10,7 +10,8 @@
 // a thread per 4 x 4 block of output coefficients.  A tile of consecutive points of the path is copied to LDS as it
 // lies in memory (16 bytes per load where the rows allow it, every point read once, rows padded with zeros to a
 // multiple of four channels); per increment a thread reads the two 4-channel pieces of the new point that its block
-// needs (the old point's stay in registers), forms its pieces of m_s - p and z_s and does 16 multiply-adds.
+// needs (the old point's stay in registers), forms its pieces of 2 (m_s - p) = (a_s - p) + (b_s - p) and of z_s (differences of
+// points only: where the path lies does not matter) and does 16 multiply-adds; the sums are halved at the end.
 // Paths with fewer than 256 blocks share a workgroup once there are enough workgroups; threads left over split a
 // tile's increments between them and add their partial sums up through LDS at the end.
 // The sum may also be split over the length of a path (a chunked scan: a row is then a stretch of a path, its terms
@@ -138,16 +139,18 @@ sig_forward_n2_kernel(Shape sh, N2Plan pl, const T *__restrict__ path, T *__rest
         const int share = (nt + pl.splits - 1) / pl.splits;
         const int lo = works ? ks * share : nt, hi = lo + share < nt ? lo + share : nt;   // this thread's increments
         if (lo < hi) {
-            T4 a_i = *reinterpret_cast<const T4 *>(lp + lo * dpad), a_j = *reinterpret_cast<const T4 *>(rp + lo * dpad);
+            // Only differences of points enter (a path far from the origin loses nothing): twice the left factor is
+            // (a - p) + (b - p), each term rounded relative to its own size; the sums are halved at the end.
+            T4 ya_i = *reinterpret_cast<const T4 *>(lp + lo * dpad) - p_i, a_j = *reinterpret_cast<const T4 *>(rp + lo * dpad);
 #pragma unroll 4
             for (int s = lo + 1; s <= hi; ++s) {
-                const T4 b_i = *reinterpret_cast<const T4 *>(lp + s * dpad), b_j = *reinterpret_cast<const T4 *>(rp + s * dpad);
-                const T4 l = (a_i + b_i) * T(0.5) - p_i, r = b_j - a_j;
+                const T4 yb_i = *reinterpret_cast<const T4 *>(lp + s * dpad) - p_i, b_j = *reinterpret_cast<const T4 *>(rp + s * dpad);
+                const T4 l = ya_i + yb_i, r = b_j - a_j;
 #pragma unroll
                 for (int a = 0; a < 4; ++a)
 #pragma unroll
                     for (int b = 0; b < 4; ++b) acc[a][b] += l[a] * r[b];
-                a_i = b_i;
+                ya_i = yb_i;
                 a_j = b_j;
             }
         }
@@ -159,6 +162,10 @@ sig_forward_n2_kernel(Shape sh, N2Plan pl, const T *__restrict__ path, T *__rest
                 if (4 * jb + b < d) out[row * sh.S + 4 * jb + b] = q_j[b] - p_j[b];
         }
     }
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] *= T(0.5);
     if (pl.splits > 1) {
         // partial sums of the splits, coefficient-major so that a wavefront's accesses spread over the banks
         __syncthreads();

@@ -5,8 +5,8 @@
 // (m_s the midpoint of increment s, z_s the increment, p and q the scan's first and last point; paper sections 2.1,
 // 2.2): a product [d x n_inc] [n_inc x d] per path.  Here a wavefront owns a strip of up to four 16 x 16 tiles of
 // A_2 and advances four increments per v_mfma_f32_16x16x4_f32: lane (k, c), k = lane / 16, c = lane % 16, forms the
-// operand scalars (m - p)[16 ti + c] and z[16 tj + c] of increment s + k from two consecutive points of the staged
-// tile.  A point is kept in LDS with the channels c, 16 + c, 32 + c, 48 + c of a strip side by side, so that one
+// operand scalars 2 (m - p)[16 ti + c] = (a - p) + (b - p) and z[16 tj + c] of increment s + k from two consecutive points of
+// the staged tile (differences of points only; the sums are halved at the end).  A point is kept in LDS with the channels c, 16 + c, 32 + c, 48 + c of a strip side by side, so that one
 // 16-byte read fetches a lane's scalars for all four tiles of its strip (an LDS read instruction costs about 6 clocks
 // of the compute unit's LDS port whatever its width; with one 4-byte read per scalar the port, not the matrix cores,
 // bounded the kernel).  The tile of points is staged as in the vector kernel: the next tile's loads are issued before
@@ -147,7 +147,7 @@ sig_forward_n2_mfma_kernel(Shape sh, N2mPlan pl, const float *__restrict__ path,
                     a0 = x0[a_off];
                     a1 = x1[a_off];
                 }
-                const float l = on ? (a0 + a1) * 0.5f - p_i : 0.f;
+                const float l = on ? (a0 - p_i) + (a1 - p_i) : 0.f;   // twice m - p, from differences of points only
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     if (t < strip_tiles) {   // the same for the whole wavefront
@@ -171,7 +171,7 @@ sig_forward_n2_mfma_kernel(Shape sh, N2mPlan pl, const float *__restrict__ path,
         }
     }
     if (live) {
-        // register r of lane (k4, c16) holds A_2[16 ti + 4 k4 + r][16 tj + c16]
+        // register r of lane (k4, c16) holds twice A_2[16 ti + 4 k4 + r][16 tj + c16]
         float *o = out + row * sh.S + d;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -180,7 +180,7 @@ sig_forward_n2_mfma_kernel(Shape sh, N2mPlan pl, const float *__restrict__ path,
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int i = 16 * ti + 4 * k4 + r;
-                    if (i < d) o[int64_t(i) * d + j] = acc[t][r];
+                    if (i < d) o[int64_t(i) * d + j] = 0.5f * acc[t][r];
                 }
             }
         }

@@ -223,6 +223,13 @@ def test_depth_two_gradient_by_its_closed_form(B, L, d, dtype):
     assert np.linalg.norm(gb.cpu().numpy() - want[:, 0]) <= tol * np.linalg.norm(want)
 
 
+@pytest.mark.parametrize("B,L,d", [(3, 200, 3), (2, 150, 12), (2, 100, 64)])
+def test_depth_two_gradient_far_from_the_origin(B, L, d):
+    # as for the forward pass: only differences of points may enter, a path around 10 000 loses nothing
+    x = (brownian_paths(B, L, d, seed=L + d) + 10000.0).astype(np.float32)
+    check(x, 2, seed=d)
+
+
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 @pytest.mark.parametrize("B,L,d,N", [
     (2, 9, 17, 3), (1, 40, 20, 3),    # a last block of one letter; three tiles of increments

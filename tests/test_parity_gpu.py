@@ -550,6 +550,24 @@ def test_depth_two_as_a_contraction_over_the_increments(B, L, d, dtype):
     assert np.all(batch <= TOL[dtype])
 
 
+@pytest.mark.parametrize("B,L,d", [(4, 300, 3), (3, 200, 12), (2, 150, 64), (2, 120, 40)])
+def test_depth_two_far_from_the_origin(B, L, d):
+    # the signature does not see where a path lies (section 2.1: it is built from increments): a path around 10 000 must
+    # come out as exactly as one around 0, which rules out forming midpoints before subtracting the first point
+    x = (brownian_paths(B, L, d, seed=L + d) + 10000.0).astype(np.float32)
+    for basepoint in (False, True):
+        if basepoint:   # a basepoint at the origin would make the first increment 10 000 long
+            import torch
+            bp = np.full((B, d), 10000.0, dtype=np.float32)
+            got = sig.sig_signature(torch.from_numpy(x).to("cuda:0"), 2, basepoint=torch.from_numpy(bp).to("cuda:0"))
+            torch.cuda.synchronize()
+            want = orc.signature(np.concatenate([bp[:, None], x], axis=1).astype(np.float64), 2)
+            batch, _ = level_errors(got.cpu().numpy(), want, d, 2)
+            assert np.all(batch <= TOL[np.float32]), batch
+        else:
+            assert check(x, 2, variant=sig.SIG_VARIANT_DEPTH2) is not None
+
+
 @pytest.mark.parametrize("shift,dtype", [(1, np.float32), (2, np.float32), (1, np.float64)])   # 4, 8 and 8 bytes off
 def test_depth_two_on_a_path_that_starts_off_a_16_byte_boundary(shift, dtype):
     # the staging loads are 16 bytes wide only where every point starts on such a boundary
