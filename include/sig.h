@@ -16,7 +16,7 @@
  * under the identification of appendix A.2.2.
  *
  * All functions but one are thread-safe and keep no state between calls.  Nothing here allocates
- * or frees device memory: the calls that need scratch memory (sig_backward, sig_forward_chunked,
+ * or frees device memory: the calls that need scratch memory (sig_backward, sig_backward_chunked, sig_forward_chunked,
  * sig_combine_many, sig_combine_backward, sig_combine_grouped_backward, sig_log_backward) take a workspace
  * from the caller, sized by their *_workspace_bytes companions; the exception is
  * sig_forward_chunked_static, whose scratch is an array inside the library that all its calls on a GPU
@@ -364,6 +364,31 @@ sig_status sig_backward(const void *path, const void *sig, const void *grad_out,
  * working set (the signature, its cotangent and the Horner terms, about 2.7 S scalars) fits on chip.
  * -1 on invalid or unsupported arguments. */
 int64_t sig_backward_workspace_bytes(int64_t B, int64_t L, int d, int N, int stream, int basepoint, sig_dtype dtype);
+
+/* sig_backward in final mode for few long paths (sections 5.1 and 5.3): the walk back along a path, one increment
+ * after the other, is cut into at most `chunks` stretches of ceil(n_inc / chunks) increments that are walked at the
+ * same time.  The stretches' signatures are computed first; their running products (Chen's identity, section 2.2) are
+ * the signatures at the ends of the stretches, and the gradient with respect to each of those follows from the one
+ * after it, because a product is linear in its left factor.  The result is that of sig_backward up to rounding; the
+ * forward output is not an argument (it is the last of the running products).
+ *   path, grad_out, basepoint_value, grad_path, grad_basepoint: as for sig_backward with stream = 0.
+ *   chunks     2 .. 65536 (any number; more stretches than increments are not made).
+ *   workspace  DEVICE pointer, 16-byte aligned, at least sig_backward_chunked_workspace_bytes(...) bytes, contents
+ *              irrelevant on entry and undefined on return; overlapping calls must not share one.
+ * Enqueued on `hip_stream` (chunks + 6 launches or so), no wait.  Needs B <= 65535, the stretches' shape served by
+ * sig_forward and sig_backward, S < 2^31: otherwise SIG_ERR_UNSUPPORTED; other errors as for sig_backward.
+ * Deterministic. */
+sig_status sig_backward_chunked(const void *path, const void *grad_out, int64_t B, int64_t L, int d, int N, int basepoint,
+                                const void *basepoint_value, int chunks, sig_dtype dtype, void *grad_path, void *grad_basepoint,
+                                void *workspace, int64_t workspace_bytes, hipStream_t hip_stream);
+
+/* Bytes of workspace sig_backward_chunked needs (the stretches' points and point gradients, three signatures per
+ * stretch, and what sig_backward needs for the stretches); -1 on invalid or unsupported arguments. */
+int64_t sig_backward_chunked_workspace_bytes(int64_t B, int64_t L, int d, int N, int basepoint, int chunks, sig_dtype dtype);
+
+/* The number of stretches to give sig_backward_chunked for this shape, a power of two; 1 where sig_backward is the
+ * faster call (short paths, many paths, depth below 3); 0 on invalid arguments. */
+int sig_backward_chunks_hint(int64_t B, int64_t L, int d, int N, int basepoint, sig_dtype dtype);
 
 /* Name of the kernel family that `variant` resolves to for this shape ("generic",
  * "mfma_d4", ...), or "unsupported" / "invalid".  The string is static. */

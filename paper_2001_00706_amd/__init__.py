@@ -26,6 +26,9 @@ from .binding import (  # noqa: F401
     SigError,
     load_library,
     sig_backward,
+    sig_backward_chunked,
+    sig_backward_chunked_workspace_bytes,
+    sig_backward_chunks_hint,
     sig_backward_workspace_bytes,
     sig_combine,
     sig_combine_backward,

@@ -38,6 +38,9 @@ EXPORTED_SYMBOLS = (
     "sig_forward_chunked_static_max_bytes",
     "sig_combine",
     "sig_backward",
+    "sig_backward_chunked",
+    "sig_backward_chunked_workspace_bytes",
+    "sig_backward_chunks_hint",
     "sig_combine_strided",
     "sig_combine_backward",
     "sig_combine_backward_workspace_bytes",
@@ -151,6 +154,12 @@ def load_library() -> ctypes.CDLL:
         lib.sig_combine.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
         lib.sig_backward.restype = i32
         lib.sig_backward.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, i32, vp, i32, vp, vp, vp, i64, vp]
+        lib.sig_backward_chunked.restype = i32
+        lib.sig_backward_chunked.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, i32, i32, vp, vp, vp, i64, vp]
+        lib.sig_backward_chunked_workspace_bytes.restype = i64
+        lib.sig_backward_chunked_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32, i32]
+        lib.sig_backward_chunks_hint.restype = i32
+        lib.sig_backward_chunks_hint.argtypes = [i64, i64, i32, i32, i32, i32]
         lib.sig_combine_backward.restype = i32
         lib.sig_combine_backward.argtypes = [vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, i64, vp]
         lib.sig_combine_backward_workspace_bytes.restype = i64
@@ -383,6 +392,55 @@ def sig_backward(path, sig, grad_out, N: int, stream: bool = False, basepoint=Fa
             bp_value.data_ptr() if bp_value is not None else 0, dtype, grad_path.data_ptr(),
             grad_basepoint.data_ptr() if grad_basepoint is not None else 0,
             ws_ptr, ws_bytes, _current_stream()))
+    if status != SIG_OK:
+        raise SigError(status, sig_status_string(status))
+    return grad_path
+
+
+def sig_backward_chunked_workspace_bytes(B: int, L: int, d: int, N: int, basepoint: bool, chunks: int,
+                                         dtype: int = SIG_F32) -> int:
+    return int(load_library().sig_backward_chunked_workspace_bytes(B, L, d, N, int(bool(basepoint)), chunks, dtype))
+
+
+def sig_backward_chunks_hint(B: int, L: int, d: int, N: int, basepoint: bool = False, dtype: int = SIG_F32) -> int:
+    """The number of stretches `sig_backward_chunked` should be given for this shape; 1 where `sig_backward` is faster."""
+    return int(load_library().sig_backward_chunks_hint(B, L, d, N, int(bool(basepoint)), dtype))
+
+
+def sig_backward_chunked(path, grad_out, N: int, chunks: int, basepoint=False, grad_path=None, workspace=None,
+                         grad_basepoint=None):
+    """`sig_backward` in final mode with every path cut into at most `chunks` stretches that are walked back at the same
+    time; the forward output is not needed.  `workspace` (uint8, GPU) is allocated through torch if not given."""
+    import torch
+
+    _check_gpu("sig_backward_chunked", path, grad_out)
+    if path.dim() != 3 or not path.is_contiguous():
+        raise ValueError("path must be a contiguous tensor of shape [B, L, d]")
+    dtype = _dtype_of(path)
+    B, L, d = path.shape
+    bp_flag, bp_value = _basepoint_args(path, basepoint)
+    S = sig_signature_channels(d, N)
+    if grad_out.dtype != path.dtype or grad_out.device != path.device or tuple(grad_out.shape) != (B, S) \
+            or not grad_out.is_contiguous():
+        raise ValueError(f"grad_out must be a contiguous {path.dtype} tensor of shape {(B, S)} on {path.device}")
+    if grad_path is None:
+        grad_path = torch.empty_like(path)
+    elif grad_path.dtype != path.dtype or grad_path.device != path.device or grad_path.shape != path.shape \
+            or not grad_path.is_contiguous():
+        raise ValueError("grad_path must match path")
+    if grad_basepoint is not None and (grad_basepoint.dtype != path.dtype or grad_basepoint.device != path.device
+                                       or tuple(grad_basepoint.shape) != (B, d) or not grad_basepoint.is_contiguous()):
+        raise ValueError("grad_basepoint must be a contiguous [B, d] tensor like path")
+    with _on_device(path.device):
+        need = sig_backward_chunked_workspace_bytes(B, L, d, N, bool(bp_flag), chunks, dtype)
+        if need > 0 and workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=path.device)
+        ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) \
+            if workspace is not None else (0, 0)
+        status = int(load_library().sig_backward_chunked(
+            path.data_ptr(), grad_out.data_ptr(), B, L, d, N, bp_flag,
+            bp_value.data_ptr() if bp_value is not None else 0, chunks, dtype, grad_path.data_ptr(),
+            grad_basepoint.data_ptr() if grad_basepoint is not None else 0, ws_ptr, ws_bytes, _current_stream()))
     if status != SIG_OK:
         raise SigError(status, sig_status_string(status))
     return grad_path

@@ -367,6 +367,124 @@ sig_status sig_backward(const void *path, const void *sig, const void *grad_out,
     return err == hipSuccess ? SIG_OK : SIG_ERR_HIP;
 }
 
+// Layout of a gradient computed stretch by stretch: K stretches of m increments per path, served as the B K short paths
+// of `rows`; the workspace holds, each 256-byte aligned, the stretches' points, their signatures, the running products,
+// the gradients with respect to those, the stretches' point gradients and the workspace of the gradient kernels.
+struct StretchPlan {
+    int64_t K, m;
+    sig::Shape rows;
+    int64_t at_points, at_sigs, at_prefix, at_grads, at_point_grads, at_inner, inner_bytes, total;
+};
+
+static sig_status plan_backward_chunked(int64_t B, int64_t L, int d, int N, int basepoint, int chunks, sig_dtype dtype, sig::Shape &sh,
+                                        StretchPlan &pl)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;
+    const sig_status st = make_shape(B, L, d, N, 0, basepoint, sh);
+    if (st != SIG_OK) return st;
+    if (chunks < 2 || chunks > 65536) return SIG_ERR_INVALID_ARG;
+    if (B > 65535) return SIG_ERR_UNSUPPORTED;
+    pl.m = (sh.n_inc + chunks - 1) / chunks;
+    pl.K = (sh.n_inc + pl.m - 1) / pl.m;
+    if (B > 0 && pl.K > kMaxElems / B) return SIG_ERR_OVERFLOW;
+    const sig_status rs = make_shape(B * pl.K, pl.m + 1, d, N, 0, 0, pl.rows);
+    if (rs != SIG_OK) return rs;
+    if (B == 0) {
+        pl.total = 0;
+        return SIG_OK;
+    }
+    if (!sig::combine_supported(pl.rows)) return SIG_ERR_UNSUPPORTED;
+    pl.inner_bytes = sig::backward_workspace_bytes(pl.rows, dtype);
+    if (pl.inner_bytes < 0) return SIG_ERR_UNSUPPORTED;
+    const int64_t elem = dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double));
+    const auto round_up = [](int64_t bytes) { return (bytes + 255) / 256 * 256; };
+    const int64_t points = round_up(pl.rows.B * (pl.m + 1) * d * elem), sigs = round_up(pl.rows.B * sh.S * elem);
+    if (sigs > kMaxElems || points > kMaxElems) return SIG_ERR_OVERFLOW;
+    pl.at_points = 0;
+    pl.at_sigs = pl.at_points + points;
+    pl.at_prefix = pl.at_sigs + sigs;
+    pl.at_grads = pl.at_prefix + sigs;
+    pl.at_point_grads = pl.at_grads + sigs;
+    pl.at_inner = pl.at_point_grads + points;
+    pl.total = pl.at_inner + round_up(pl.inner_bytes);
+    return SIG_OK;
+}
+
+int64_t sig_backward_chunked_workspace_bytes(int64_t B, int64_t L, int d, int N, int basepoint, int chunks, sig_dtype dtype)
+{
+    sig::Shape sh;
+    StretchPlan pl;
+    if (plan_backward_chunked(B, L, d, N, basepoint, chunks, dtype, sh, pl) != SIG_OK) return -1;
+    if (B > 0 && resolve(pl.rows, dtype, SIG_VARIANT_AUTO, nullptr, nullptr) == Family::None) return -1;
+    return pl.total;
+}
+
+sig_status sig_backward_chunked(const void *path, const void *grad_out, int64_t B, int64_t L, int d, int N, int basepoint,
+                                const void *basepoint_value, int chunks, sig_dtype dtype, void *grad_path, void *grad_basepoint,
+                                void *workspace, int64_t workspace_bytes, hipStream_t hip_stream)
+{
+    sig::Shape sh;
+    StretchPlan pl;
+    const sig_status st = plan_backward_chunked(B, L, d, N, basepoint, chunks, dtype, sh, pl);
+    if (st != SIG_OK) return st;
+    if (B == 0) return SIG_OK;
+    if (path == nullptr || grad_out == nullptr || grad_path == nullptr) return SIG_ERR_INVALID_ARG;
+    if (!sh.basepoint && (basepoint_value != nullptr || grad_basepoint != nullptr)) return SIG_ERR_INVALID_ARG;
+    if (workspace == nullptr || workspace_bytes < pl.total || reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return SIG_ERR_INVALID_ARG;
+    sh.basepoint_value = basepoint_value;
+    char *ws = static_cast<char *>(workspace);
+    void *points = ws + pl.at_points, *sigs = ws + pl.at_sigs, *prefix = ws + pl.at_prefix, *grads = ws + pl.at_grads,
+         *point_grads = ws + pl.at_point_grads, *inner = ws + pl.at_inner;
+    const Family family = resolve(pl.rows, dtype, SIG_VARIANT_AUTO, points, sigs);
+    if (family == Family::None) return SIG_ERR_UNSUPPORTED;
+    // the stretches as paths of their own, and their signatures
+    if (sig::launch_stretch_gather(sh, dtype, pl.K, pl.m, path, points, hip_stream) != hipSuccess) return SIG_ERR_HIP;
+    if (launch_family(family, pl.rows, dtype, points, sigs, hip_stream) != hipSuccess) return SIG_ERR_HIP;
+    // the signature of the path up to the end of every stretch: a running product along each path's stretches
+    if (sig::launch_copy_rows(dtype, sigs, sh.S, prefix, sh.S, sh.S, pl.rows.B, hip_stream) != hipSuccess) return SIG_ERR_HIP;
+    if (pl.K > 1) {
+        const hipError_t err = dtype == SIG_F32
+                                   ? sig::launch_chunk_prefix_f32(pl.rows, B, pl.K, 1, static_cast<float *>(prefix), hip_stream)
+                                   : sig::launch_chunk_prefix_f64(pl.rows, B, pl.K, 1, static_cast<double *>(prefix), hip_stream);
+        if (err != hipSuccess) return SIG_ERR_HIP;
+    }
+    // the gradient with respect to each of them, from the last stretch back
+    const int64_t elem = dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double));
+    if (sig::launch_copy_rows(dtype, grad_out, sh.S, static_cast<char *>(grads) + (pl.K - 1) * sh.S * elem, pl.K * sh.S, sh.S, B,
+                              hip_stream) != hipSuccess)
+        return SIG_ERR_HIP;
+    if (sig::launch_stretch_adjoint_chain(pl.rows, dtype, pl.K, sigs, grads, hip_stream) != hipSuccess) return SIG_ERR_HIP;
+    // every stretch walked backwards on its own, then the point gradients added up
+    const hipError_t err =
+        dtype == SIG_F32
+            ? sig::launch_backward_f32(pl.rows, static_cast<const float *>(points), static_cast<const float *>(prefix),
+                                       static_cast<const float *>(grads), static_cast<float *>(point_grads), nullptr, inner,
+                                       pl.inner_bytes, hip_stream)
+            : sig::launch_backward_f64(pl.rows, static_cast<const double *>(points), static_cast<const double *>(prefix),
+                                       static_cast<const double *>(grads), static_cast<double *>(point_grads), nullptr, inner,
+                                       pl.inner_bytes, hip_stream);
+    if (err != hipSuccess) return SIG_ERR_HIP;
+    if (sig::launch_stretch_scatter(sh, dtype, pl.K, pl.m, point_grads, grad_path, grad_basepoint, hip_stream) != hipSuccess)
+        return SIG_ERR_HIP;
+    return SIG_OK;
+}
+
+int sig_backward_chunks_hint(int64_t B, int64_t L, int d, int N, int basepoint, sig_dtype dtype)
+{
+    if (dtype != SIG_F32 && dtype != SIG_F64) return 0;
+    sig::Shape sh;
+    if (make_shape(B, L, d, N, 0, basepoint, sh) != SIG_OK) return 0;
+    // depth 2 has a closed form with no walk at all; otherwise the walk is one increment after the other, and cutting it
+    // pays once the stretches' walks are shorter by more than the chain of gradients between them costs
+    if (N < 3 || B < 1 || B > 256 || sh.n_inc < 512) return 1;
+    int chunks = 1;
+    while (int64_t(chunks) * 2 * B <= 1024 && sh.n_inc / (int64_t(chunks) * 2) >= 32 && int64_t(chunks) * int64_t(chunks) * 64 <= sh.n_inc &&
+           sig_backward_chunked_workspace_bytes(B, L, d, N, basepoint, chunks * 2, dtype) >= 0 &&
+           sig_backward_chunked_workspace_bytes(B, L, d, N, basepoint, chunks * 2, dtype) <= (int64_t(2) << 30))
+        chunks *= 2;
+    return chunks;
+}
+
 sig_status sig_invert(const void *sig, int64_t rows, int d, int N, sig_dtype dtype, void *out, hipStream_t hip_stream)
 {
     if (dtype != SIG_F32 && dtype != SIG_F64) return SIG_ERR_INVALID_ARG;

@@ -93,6 +93,15 @@ hipError_t launch_gather_f32(const Shape &sh, const float *in, const int64_t *in
 hipError_t launch_gather_f64(const Shape &sh, const double *in, const int64_t *index, int64_t n, double *out, hipStream_t st);
 int64_t lyndon_indices_host(const Shape &sh, int64_t *indices, int64_t cap);
 
+// Plumbing of the gradient computed stretch by stretch (sig_backward_chunked.hip); `sh` is the whole call's shape
+// except for the chain, which takes the shape of the B K stretches.  K stretches of m increments per path.
+hipError_t launch_stretch_gather(const Shape &sh, sig_dtype dtype, int64_t K, int64_t m, const void *path, void *rows, hipStream_t st);
+hipError_t launch_copy_rows(sig_dtype dtype, const void *src, int64_t src_stride, void *dst, int64_t dst_stride, int64_t len,
+                            int64_t rows, hipStream_t st);
+hipError_t launch_stretch_adjoint_chain(const Shape &sh, sig_dtype dtype, int64_t K, const void *C, void *g, hipStream_t st);
+hipError_t launch_stretch_scatter(const Shape &sh, sig_dtype dtype, int64_t K, int64_t m, const void *grows, void *gpath, void *gbase,
+                                  hipStream_t st);
+
 // Gradient through the logarithm (sh.B rows; S < 2^31) and through the selection of the Lyndon words.
 int64_t log_backward_workspace_bytes(const Shape &sh, sig_dtype dtype);
 int64_t combine_backward_workspace_bytes(const Shape &sh, sig_dtype dtype);
