@@ -217,6 +217,17 @@ def main() -> int:
         def step():  # noqa: F811
             sig.sig_backward(x, out, grad_out, w.N, stream=w.stream, basepoint=w.basepoint, grad_path=grad_path,
                              workspace=workspace)
+
+        # few long paths: the library's hint asks for the walk back to be cut into stretches, as the autograd op does
+        stretches = 1 if w.stream else sig.sig_backward_chunks_hint(w.B, w.L, w.d, w.N, w.basepoint)
+        if stretches > 1:
+            need = sig.sig_backward_chunked_workspace_bytes(w.B, w.L, w.d, w.N, w.basepoint, stretches)
+            workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+            kernel = f"backward_chunked({stretches})"
+
+            def step():  # noqa: F811
+                sig.sig_backward_chunked(x, grad_out, w.N, stretches, basepoint=w.basepoint, grad_path=grad_path,
+                                         workspace=workspace)
     elif args.op == "logsignature":
         log_full = torch.empty_like(out)
         n_words = sig.sig_logsignature_channels(w.d, w.N)

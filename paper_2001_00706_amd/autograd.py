@@ -1,6 +1,6 @@
 """`signature` and `logsignature` as differentiable PyTorch operations (paper section 5.3): the forward passes
 are `sig_signature`, `sig_log` and `sig_lyndon_gather`, the backward passes `sig_lyndon_scatter`,
-`sig_log_backward` and `sig_backward`; all run in the HIP library.  Glue only."""
+`sig_log_backward` and `sig_backward` (`sig_backward_chunked` for few long paths); all run in the HIP library.  Glue only."""
 from __future__ import annotations
 
 import torch
@@ -34,8 +34,13 @@ class _Signature(torch.autograd.Function):
             grad_out = binding.sig_invert(grad_out, d, depth)
         bp = basepoint_value.contiguous() if basepoint_value is not None else bool(basepoint)
         grad_bp = torch.empty_like(basepoint_value) if basepoint_value is not None else None
-        grad_path = binding.sig_backward(path, plain, grad_out, depth, stream=stream, basepoint=bp,
-                                         grad_basepoint=grad_bp)
+        B, L, _ = path.shape
+        chunks = 1 if stream else binding.sig_backward_chunks_hint(B, L, d, depth, bool(basepoint), binding._dtype_of(path))
+        if chunks > 1:   # few long paths: the walk back along the path cut into stretches
+            grad_path = binding.sig_backward_chunked(path, grad_out, depth, chunks, basepoint=bp, grad_basepoint=grad_bp)
+        else:
+            grad_path = binding.sig_backward(path, plain, grad_out, depth, stream=stream, basepoint=bp,
+                                             grad_basepoint=grad_bp)
         return grad_path, grad_bp, None, None, None, None
 
 

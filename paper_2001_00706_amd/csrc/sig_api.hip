@@ -440,16 +440,36 @@ sig_status sig_backward_chunked(const void *path, const void *grad_out, int64_t 
     // the stretches as paths of their own, and their signatures
     if (sig::launch_stretch_gather(sh, dtype, pl.K, pl.m, path, points, hip_stream) != hipSuccess) return SIG_ERR_HIP;
     if (launch_family(family, pl.rows, dtype, points, sigs, hip_stream) != hipSuccess) return SIG_ERR_HIP;
-    // the signature of the path up to the end of every stretch: a running product along each path's stretches
-    if (sig::launch_copy_rows(dtype, sigs, sh.S, prefix, sh.S, sh.S, pl.rows.B, hip_stream) != hipSuccess) return SIG_ERR_HIP;
-    if (pl.K > 1) {
-        const hipError_t err = dtype == SIG_F32
-                                   ? sig::launch_chunk_prefix_f32(pl.rows, B, pl.K, 1, static_cast<float *>(prefix), hip_stream)
-                                   : sig::launch_chunk_prefix_f64(pl.rows, B, pl.K, 1, static_cast<double *>(prefix), hip_stream);
-        if (err != hipSuccess) return SIG_ERR_HIP;
+    // the signature of the path up to the end of every stretch: a running product along each path's stretches, by one
+    // workgroup per path while a signature fits its LDS three times over, else a launch per product
+    const int64_t elem = dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double));
+    if (3 * sh.S * elem <= 64 * 1024 || pl.K == 1) {
+        if (sig::launch_copy_rows(dtype, sigs, sh.S, prefix, sh.S, sh.S, pl.rows.B, hip_stream) != hipSuccess) return SIG_ERR_HIP;
+        if (pl.K > 1) {
+            const hipError_t err = dtype == SIG_F32
+                                       ? sig::launch_chunk_prefix_f32(pl.rows, B, pl.K, 1, static_cast<float *>(prefix), hip_stream)
+                                       : sig::launch_chunk_prefix_f64(pl.rows, B, pl.K, 1, static_cast<double *>(prefix), hip_stream);
+            if (err != hipSuccess) return SIG_ERR_HIP;
+        }
+    } else {
+        const int64_t per_path = pl.K * sh.S;
+        if (sig::launch_copy_rows(dtype, sigs, per_path, prefix, per_path, sh.S, B, hip_stream) != hipSuccess) return SIG_ERR_HIP;
+        sig::Shape paths = pl.rows;
+        paths.B = B;
+        const int64_t strides[7] = {per_path, per_path, per_path, 0, 0, 0, 0};
+        for (int64_t c = 1; c < pl.K; ++c) {
+            const char *left = static_cast<const char *>(prefix) + (c - 1) * sh.S * elem;
+            const char *right = static_cast<const char *>(sigs) + c * sh.S * elem;
+            char *product = static_cast<char *>(prefix) + c * sh.S * elem;
+            const hipError_t err =
+                dtype == SIG_F32 ? sig::launch_combine_f32(paths, reinterpret_cast<const float *>(left), reinterpret_cast<const float *>(right),
+                                                           reinterpret_cast<float *>(product), hip_stream, strides)
+                                 : sig::launch_combine_f64(paths, reinterpret_cast<const double *>(left), reinterpret_cast<const double *>(right),
+                                                           reinterpret_cast<double *>(product), hip_stream, strides);
+            if (err != hipSuccess) return SIG_ERR_HIP;
+        }
     }
     // the gradient with respect to each of them, from the last stretch back
-    const int64_t elem = dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double));
     if (sig::launch_copy_rows(dtype, grad_out, sh.S, static_cast<char *>(grads) + (pl.K - 1) * sh.S * elem, pl.K * sh.S, sh.S, B,
                               hip_stream) != hipSuccess)
         return SIG_ERR_HIP;
@@ -474,14 +494,22 @@ int sig_backward_chunks_hint(int64_t B, int64_t L, int d, int N, int basepoint, 
     if (dtype != SIG_F32 && dtype != SIG_F64) return 0;
     sig::Shape sh;
     if (make_shape(B, L, d, N, 0, basepoint, sh) != SIG_OK) return 0;
-    // depth 2 has a closed form with no walk at all; otherwise the walk is one increment after the other, and cutting it
-    // pays once the stretches' walks are shorter by more than the chain of gradients between them costs
-    if (N < 3 || B < 1 || B > 256 || sh.n_inc < 512) return 1;
+    // Depth 2 has a closed form with no walk at all.  Otherwise the walk is one increment after the other, and cutting
+    // it pays once the stretches' walks are shorter by more than the two chains between them cost (the running
+    // products and the gradients with respect to them, a few microseconds per stretch each): measured from 512
+    // increments on, best near sqrt(n_inc) / 2 stretches for signatures up to 2048 scalars, fewer for larger ones
+    // (a quarter of sqrt(n_inc) once the chains take a launch per stretch).
+    if (N < 3 || B < 1 || B > 128 || sh.n_inc < 512) return 1;
+    const int64_t elem = dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double));
+    const int64_t per_stretch = sh.S <= 2048 ? 4 : 3 * sh.S * elem <= 64 * 1024 ? 8 : 16;
     int chunks = 1;
-    while (int64_t(chunks) * 2 * B <= 1024 && sh.n_inc / (int64_t(chunks) * 2) >= 32 && int64_t(chunks) * int64_t(chunks) * 64 <= sh.n_inc &&
-           sig_backward_chunked_workspace_bytes(B, L, d, N, basepoint, chunks * 2, dtype) >= 0 &&
-           sig_backward_chunked_workspace_bytes(B, L, d, N, basepoint, chunks * 2, dtype) <= (int64_t(2) << 30))
-        chunks *= 2;
+    for (;;) {
+        const int64_t next = int64_t(chunks) * 2;
+        if (next * B > 1024 || sh.n_inc / next < 32 || next * next * per_stretch > sh.n_inc) break;
+        const int64_t bytes = sig_backward_chunked_workspace_bytes(B, L, d, N, basepoint, int(next), dtype);
+        if (bytes < 0 || bytes > (int64_t(2) << 30)) break;
+        chunks = int(next);
+    }
     return chunks;
 }
 

@@ -13,6 +13,7 @@
 // point shared by two stretches ends an increment of one and starts one of the other; the repeated last points sum to
 // the gradient of the increment that ends at the real one).
 #include "sig_internal.h"
+#include "sig_lane_ops.h"
 
 namespace sig {
 namespace {
@@ -52,49 +53,137 @@ sig_copy_rows_kernel(const T *__restrict__ src, int64_t src_stride, T *__restric
     }
 }
 
-// g[b][c - 1] = the gradient g[b][c] carried through the right multiplication by C[b][c] (rows of K signatures per
-// path).  For a word u of level i the sum over the words v of level j is a dot product of d^j consecutive scalars of
-// level i + j of g with level j of C.  Words whose sums are long (levels up to `wave_levels`) take a wavefront each,
-// lanes striding over v, the rest a lane each; either way the order of the additions is fixed.
-template <typename T>
-__global__ void __launch_bounds__(256)
-sig_stretch_adjoint_kernel(Shape sh, int64_t K, int64_t c, int wave_levels, const T *__restrict__ C, T *g)
+// How the words of each level are spread over a wavefront's lanes in the chain of gradients: a word of level i sums
+// sum_{j = 1 .. N - i} d^j products, and teams of 2^team_log2[i] lanes (1, 4, 16 or 64) share a word's sums.
+struct ChainTeams {
+    unsigned char team_log2[SIG_MAX_DEPTH + 1];
+};
+
+// gout = the gradient gin carried through the right multiplication by the signature cs.  For a word u of level i the
+// sum over the words v of level j is a dot product of d^j consecutive scalars of level i + j of gin with level j of cs.
+// An item is a wavefront's worth of teams of one level; the calling wavefront takes the items item0, item0 + step, .. of
+// every level (STEP > 0: step is that constant, and the levels' items are dealt out in turn so that no wavefront is
+// always first).  The order of the additions is fixed.  The result goes to gout and, if given, to gout2 as well.
+// `lv` is the level table in LDS (see below): d^j and the offsets of levels j and i + j are built up as j grows.
+struct ChainLevels {
+    int words[SIG_MAX_DEPTH + 2];   // d^i
+    int off[SIG_MAX_DEPTH + 2];     // offset of level i; off[N + 1] = S
+    int team_log2[SIG_MAX_DEPTH + 2];
+};
+
+// The level tables as 32-bit numbers in LDS (S < 2^31), written by one thread at positions known at compile time: the
+// shape sits in scalar registers, where a run-time index would move it to scratch memory.  Needs a barrier after it.
+__device__ __forceinline__ void chain_levels_fill(const Shape &sh, const ChainTeams &teams, ChainLevels *lv)
 {
-    const int64_t b = blockIdx.y;
-    const T *gin = g + (b * K + c) * sh.S, *cs = C + (b * K + c) * sh.S;
-    T *gout = g + (b * K + c - 1) * sh.S;
-    const int N = sh.N, lane = threadIdx.x & 63;
-    const int64_t wave_words = sh.off[wave_levels + 1];   // words of levels 1 .. wave_levels
-    const int64_t lane_waves = (sh.S - wave_words + 63) / 64;
-    const int64_t waves = wave_words + lane_waves;
-    for (int64_t w = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6); w < waves; w += int64_t(gridDim.x) * 4) {
-        if (w < wave_words) {
-            const int64_t e = w;
-            int i = 1;
-            while (e >= sh.off[i + 1]) ++i;
-            const int64_t u = e - sh.off[i];
-            T acc = T(0);
-            for (int j = 1; i + j <= N; ++j) {
-                const T *seg = gin + sh.off[i + j] + u * sh.pw[j], *cj = cs + sh.off[j];
-                for (int64_t v = lane; v < sh.pw[j]; v += 64) acc += seg[v] * cj[v];
-            }
+    if (threadIdx.x == 0) {
 #pragma unroll
-            for (int step = 32; step >= 1; step >>= 1) acc += __shfl_xor(acc, step, 64);
-            if (lane == 0) gout[e] = gin[e] + acc;
-        } else {
-            const int64_t e = wave_words + (w - wave_words) * 64 + lane;
-            if (e < sh.S) {
-                int i = 1;
-                while (e >= sh.off[i + 1]) ++i;
-                const int64_t u = e - sh.off[i];
-                T acc = gin[e];
-                for (int j = 1; i + j <= N; ++j) {
-                    const T *seg = gin + sh.off[i + j] + u * sh.pw[j], *cj = cs + sh.off[j];
-                    for (int64_t v = 0; v < sh.pw[j]; ++v) acc += seg[v] * cj[v];
+        for (int k = 0; k <= SIG_MAX_DEPTH; ++k) {
+            lv->words[k] = int(sh.pw[k]);
+            lv->off[k] = int(sh.off[k]);
+            lv->team_log2[k] = teams.team_log2[k];
+        }
+        lv->off[SIG_MAX_DEPTH + 1] = int(sh.off[SIG_MAX_DEPTH + 1]);
+    }
+}
+
+template <typename T, int STEP>
+__device__ __forceinline__ void stretch_adjoint_items(int N, int d, const ChainLevels *lv, const T *gin, const T *cs, T *gout, T *gout2,
+                                                      int item0, int step_runtime)
+{
+    const int lane = threadIdx.x & 63;
+    const int step = STEP > 0 ? STEP : step_runtime;
+    int dealt = 0;
+    for (int i = 1; i <= N; ++i) {
+        const int words = lv->words[i], base = lv->off[i], after = lv->off[i + 1];
+        const int log2 = lv->team_log2[i], team = 1 << log2, per_item = 64 >> log2;
+        const int items = (words + per_item - 1) >> (6 - log2);
+        const int member = lane & (team - 1);
+        const int first = STEP > 0 ? ((item0 - dealt) & (STEP - 1)) : item0;
+        for (int t = first; t < items; t += step) {
+            const int word = t * per_item + (lane >> log2);
+            const bool on = word < words;
+            T acc = T(0);
+            if (on) {
+                int pwj = 1, offj = 0, offn = after;   // d^j, the offset of level j, the offset of level i + j
+                for (int j = 1; j <= N - i; ++j) {
+                    pwj *= d;
+                    const T *seg = gin + offn + word * pwj, *cj = cs + offj;
+#pragma unroll 4
+                    for (int v = member; v < pwj; v += team) acc += seg[v] * cj[v];
+                    offj += pwj;
+                    offn += words * pwj;
                 }
-                gout[e] = acc;
+            }
+            for (int hop = team >> 1; hop >= 1; hop >>= 1) acc += __shfl_xor(acc, hop, 64);   // the same for every lane
+            if (on && member == 0) {
+                acc += gin[base + word];
+                gout[base + word] = acc;
+                if (gout2 != nullptr) gout2[base + word] = acc;
             }
         }
+        if (STEP > 0) dealt = (dealt + items) & (STEP - 1);
+    }
+}
+
+// One step of the chain, g[b][c - 1] from g[b][c] and C[b][c], spread over the grid (rows of K signatures per path).
+template <typename T>
+__global__ void __launch_bounds__(256)
+sig_stretch_adjoint_kernel(Shape sh, ChainTeams teams, int64_t K, int64_t c, const T *__restrict__ C, T *g)
+{
+    __shared__ ChainLevels lv;
+    chain_levels_fill(sh, teams, &lv);
+    __syncthreads();
+    const int64_t b = blockIdx.y;
+    stretch_adjoint_items<T, 0>(sh.N, sh.d, &lv, g + (b * K + c) * sh.S, C + (b * K + c) * sh.S, g + (b * K + c - 1) * sh.S, nullptr,
+                                int(blockIdx.x) * 4 + (threadIdx.x >> 6), int(gridDim.x) * 4);
+}
+
+constexpr int kChainPerThread = 8;   // scalars of a stretch's signature a thread fetches ahead: `used` <= 8192
+
+// The whole chain of a path in one workgroup of 16 wavefronts, while two gradients and the `used` scalars of a signature
+// that take part (its levels below N) fit the LDS: the
+// gradient being carried stays in LDS (two buffers take turns as source and result), the next stretch's signature is
+// fetched into registers while the current step computes, and the barriers order LDS traffic only, so a step waits
+// for no memory access but its own signature's arrival.
+template <typename T>
+__global__ void __launch_bounds__(1024)
+sig_stretch_adjoint_chain_kernel(Shape sh, ChainTeams teams, int64_t K, int used, const T *__restrict__ C, T *__restrict__ g)
+{
+    extern __shared__ __align__(16) unsigned char chain_smem[];
+    __shared__ ChainLevels lv;
+    chain_levels_fill(sh, teams, &lv);   // the barrier of the first step comes before its first use
+    const int S = int(sh.S), tid = threadIdx.x;
+    T *from = reinterpret_cast<T *>(chain_smem), *to = from + S, *cl = to + S;
+    const int64_t b = blockIdx.x;
+    // of a stretch's signature the levels below N are used: the words v of the sums have at most N - 1 letters
+    T creg[kChainPerThread];
+    const T *c_next = C + (b * K + K - 1) * sh.S, *g_last = g + (b * K + K - 1) * sh.S;
+#pragma unroll
+    for (int r = 0; r < kChainPerThread; ++r) {
+        const int e = tid + 1024 * r;
+        creg[r] = e < used ? c_next[e] : T(0);
+    }
+    for (int e = tid; e < S; e += 1024) from[e] = g_last[e];
+    for (int64_t c = K - 1; c >= 1; --c) {
+#pragma unroll
+        for (int r = 0; r < kChainPerThread; ++r) {
+            const int e = tid + 1024 * r;
+            if (e < used) cl[e] = creg[r];
+        }
+        lds_barrier();
+        if (c > 1) {
+            c_next = C + (b * K + c - 1) * sh.S;
+#pragma unroll
+            for (int r = 0; r < kChainPerThread; ++r) {
+                const int e = tid + 1024 * r;
+                creg[r] = e < used ? c_next[e] : T(0);
+            }
+        }
+        stretch_adjoint_items<T, 16>(sh.N, sh.d, &lv, from, cl, to, g + (b * K + c - 1) * sh.S, tid >> 6, 16);
+        lds_barrier();
+        T *spare = from;
+        from = to;
+        to = spare;
     }
 }
 
@@ -156,18 +245,29 @@ hipError_t copy_rows(const T *src, int64_t src_stride, T *dst, int64_t dst_strid
 template <typename T>
 hipError_t stretch_adjoint_chain(const Shape &sh, int64_t K, const T *C, T *g, hipStream_t st)
 {
-    // a word's sums are sum_{j = 1 .. N - i} d^j multiply-adds long: a wavefront each from 256 on
-    int wave_levels = 0;
-    for (int i = 1; i < sh.N; ++i) {
+    if (K < 2) return hipSuccess;
+    ChainTeams teams;
+    int64_t items = 0;
+    for (int i = 0; i <= SIG_MAX_DEPTH; ++i) teams.team_log2[i] = 0;
+    for (int i = 1; i <= sh.N; ++i) {
         int64_t cost = 0;
         for (int j = 1; i + j <= sh.N; ++j) cost += sh.pw[j];
-        if (cost >= 256) wave_levels = i;
+        teams.team_log2[i] = cost <= 8 ? 0 : cost <= 64 ? 2 : cost <= 512 ? 4 : 6;
+        const int64_t per_item = 64 >> teams.team_log2[i];
+        items += (sh.pw[i] + per_item - 1) / per_item;
     }
-    const int64_t waves = sh.off[wave_levels + 1] + (sh.S - sh.off[wave_levels + 1] + 63) / 64;
-    const int64_t groups = (waves + 3) / 4;
-    const dim3 grid(unsigned(groups < 4096 ? groups : 4096), unsigned(sh.B / K));   // sh.B counts stretches
+    const int64_t paths = sh.B / K;   // sh.B counts stretches
+    const int64_t used = sh.off[sh.N];   // levels 1 .. N - 1 of a stretch's signature
+    const size_t lds = (2 * size_t(sh.S) + size_t(used)) * sizeof(T);
+    if (lds + sizeof(ChainLevels) <= 64 * 1024 && used <= 1024 * kChainPerThread) {
+        hipLaunchKernelGGL((sig_stretch_adjoint_chain_kernel<T>), dim3(unsigned(paths)), dim3(1024), lds, st, sh, teams, K, int(used), C,
+                           g);
+        return hipGetLastError();
+    }
+    const int64_t groups = (items + 3) / 4;
+    const dim3 grid(unsigned(groups < 4096 ? groups : 4096), unsigned(paths));
     for (int64_t c = K - 1; c >= 1; --c) {
-        hipLaunchKernelGGL((sig_stretch_adjoint_kernel<T>), grid, dim3(256), 0, st, sh, K, c, wave_levels, C, g);
+        hipLaunchKernelGGL((sig_stretch_adjoint_kernel<T>), grid, dim3(256), 0, st, sh, teams, K, c, C, g);
         const hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
     }

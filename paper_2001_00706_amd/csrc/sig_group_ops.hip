@@ -135,8 +135,8 @@ __device__ __forceinline__ uint32_t prefix_div(uint32_t n, uint32_t magic) { ret
 constexpr int kPrefixPerThread = 32;
 constexpr int kPrefixLdsWords = 256 * kPrefixPerThread;
 
-template <typename T>
-__global__ void __launch_bounds__(256)
+template <typename T, int THREADS>
+__global__ void __launch_bounds__(THREADS)
 sig_chunk_prefix_lds_kernel(Shape sh, int64_t paths, int64_t n_inc, int64_t chunk_len, T *out)
 {
     extern __shared__ __align__(16) unsigned char prefix_smem[];
@@ -162,26 +162,27 @@ sig_chunk_prefix_lds_kernel(Shape sh, int64_t paths, int64_t n_inc, int64_t chun
     for (int64_t p = blockIdx.x; p < paths; p += gridDim.x) {
         T *rows = out + p * n_inc * sh.S;
         const int64_t first_end = (chunk_len < n_inc ? chunk_len : n_inc) - 1;
-        for (uint32_t i = tid; i < S; i += 256) A[i] = rows[first_end * sh.S + i];
-        T next[kPrefixPerThread];
+        for (uint32_t i = tid; i < S; i += THREADS) A[i] = rows[first_end * sh.S + i];
+        constexpr int kPerThread = kPrefixLdsWords / THREADS;
+        T next[kPerThread];
         auto fetch = [&](int64_t start) {
             if (start >= n_inc) return;
             const T *src = rows + ((start + chunk_len < n_inc ? start + chunk_len : n_inc) - 1) * sh.S;
 #pragma unroll
-            for (int j = 0; j < kPrefixPerThread; ++j)   // unconditional, on a clamped index: the loads stay in flight together
-                if (256u * j < S) next[j] = src[tid + 256u * j < S ? tid + 256u * j : S - 1];
+            for (int j = 0; j < kPerThread; ++j)   // unconditional, on a clamped index: the loads stay in flight together
+                if (uint32_t(THREADS) * j < S) next[j] = src[tid + uint32_t(THREADS) * j < S ? tid + uint32_t(THREADS) * j : S - 1];
         };
         fetch(chunk_len);
         for (int64_t start = chunk_len; start < n_inc; start += chunk_len) {
             T *dst = rows + ((start + chunk_len < n_inc ? start + chunk_len : n_inc) - 1) * sh.S;
 #pragma unroll
-            for (int j = 0; j < kPrefixPerThread; ++j)
-                if (tid + 256u * j < S) R[tid + 256u * j] = next[j];
+            for (int j = 0; j < kPerThread; ++j)
+                if (tid + uint32_t(THREADS) * j < S) R[tid + uint32_t(THREADS) * j] = next[j];
             fetch(start + chunk_len);
             prefix_lds_barrier();
             for (int k = N; k >= 1; --k) {
                 const uint32_t n_k = lv_size[k], off_k = lv_off[k];
-                for (uint32_t idx = tid; idx < n_k; idx += 256) {
+                for (uint32_t idx = tid; idx < n_k; idx += THREADS) {
                     T acc = A[off_k + idx] + R[off_k + idx];
                     uint32_t prefix = idx, suffix = 0, scale = 1;
                     for (int j = k - 1; j >= 1; --j) {
@@ -428,7 +429,11 @@ hipError_t launch_chunk_prefix(const Shape &sh, int64_t paths, int64_t n_inc, in
     }
     const size_t lds = 3 * size_t(sh.S) * sizeof(T);
     if (sh.S <= kPrefixLdsWords && lds <= 64 * 1024) {
-        hipLaunchKernelGGL((sig_chunk_prefix_lds_kernel<T>), dim3(grid), dim3(256), lds, st, sh, paths, n_inc, chunk_len, out);
+        // a product is about N multiply-adds per scalar, instruction-bound: 16 wavefronts for the larger signatures
+        if (sh.S >= 1024)
+            hipLaunchKernelGGL((sig_chunk_prefix_lds_kernel<T, 1024>), dim3(grid), dim3(1024), lds, st, sh, paths, n_inc, chunk_len, out);
+        else
+            hipLaunchKernelGGL((sig_chunk_prefix_lds_kernel<T, 256>), dim3(grid), dim3(256), lds, st, sh, paths, n_inc, chunk_len, out);
         return hipGetLastError();
     }
     hipLaunchKernelGGL((sig_chunk_prefix_kernel<T>), dim3(grid), dim3(256), 0, st, sh, paths, n_inc, chunk_len, out);

@@ -87,6 +87,18 @@ def test_the_hinted_count_on_a_long_path():
     assert sig.sig_backward_chunks_hint(1024, 128, 4, 6) == 1 and sig.sig_backward_chunks_hint(1, 100000, 4, 2) == 1
 
 
+def test_autograd_takes_the_stretches_for_a_long_path():
+    import torch
+    B, L, d, N = 2, 1025, 3, 4
+    assert sig.sig_backward_chunks_hint(B, L, d, N) > 1
+    x = brownian_paths(B, L, d, seed=8).astype(np.float64)
+    w = np.random.default_rng(9).standard_normal((B, orc.channels(d, N)))
+    xt = dev(x).requires_grad_(True)
+    (sig.signature(xt, N) * dev(w)).sum().backward()
+    want = orc.signature_backward(x, w, N)
+    np.testing.assert_allclose(xt.grad.cpu().numpy(), want, rtol=1e-8, atol=1e-10)
+
+
 def test_same_result_twice_and_inputs_untouched():
     import torch
     x = dev(brownian_paths(2, 200, 4, seed=2))

@@ -260,6 +260,27 @@ def test_chunk_hint(lib):
     assert h(1024, 8193, 2, 2, 0, sig.SIG_F32) == 2 and h(1025, 8193, 2, 2, 0, sig.SIG_F32) == 1
 
 
+def test_backward_chunk_hint_and_workspace(lib):
+    h = lib.sig_backward_chunks_hint
+    # B, L, d, N, basepoint, dtype: about sqrt(n_inc) / 2 stretches for small signatures, fewer for larger ones
+    assert h(1, 4097, 4, 4, 0, sig.SIG_F32) == 32 and h(1, 65537, 4, 6, 0, sig.SIG_F32) == 64
+    assert h(1, 2049, 5, 7, 0, sig.SIG_F32) == 8               # signatures beyond the LDS: a launch per stretch
+    assert h(1, 512, 4, 4, 0, sig.SIG_F32) == 1 and h(1, 513, 4, 4, 0, sig.SIG_F32) == 8
+    assert h(1, 512, 4, 4, 1, sig.SIG_F32) == 8                # the basepoint adds an increment
+    assert h(128, 100001, 3, 4, 0, sig.SIG_F32) == 8 and h(129, 100001, 3, 4, 0, sig.SIG_F32) == 1   # 1024 rows at most
+    assert h(1, 100001, 4, 2, 0, sig.SIG_F32) == 1             # depth 2 walks nothing
+    assert h(1024, 128, 4, 6, 0, sig.SIG_F32) == 1
+    assert h(1, 1, 4, 6, 0, sig.SIG_F32) == 0 and h(1, 4096, 4, 6, 0, 9) == 0 and h(1, 4096, 0, 6, 0, sig.SIG_F32) == 0
+    w = lib.sig_backward_chunked_workspace_bytes
+    # 10 increments in 4 stretches of 3: 8 rows of 4 points (256-byte pieces: points, 3 x signatures, point gradients)
+    S = 3 + 9 + 27
+    piece = lambda n: (n + 255) // 256 * 256
+    inner = lib.sig_backward_workspace_bytes(8, 4, 3, 3, 0, 0, sig.SIG_F32)
+    assert w(2, 11, 3, 3, 0, 4, sig.SIG_F32) == 2 * piece(8 * 4 * 3 * 4) + 3 * piece(8 * S * 4) + piece(inner)
+    assert w(2, 11, 3, 3, 0, 1, sig.SIG_F32) == -1 and w(2, 11, 3, 3, 0, 65537, sig.SIG_F32) == -1
+    assert w(70000, 11, 3, 3, 0, 4, sig.SIG_F32) == -1 and w(0, 11, 3, 3, 0, 4, sig.SIG_F32) == 0
+
+
 def test_lyndon_table_is_built_on_the_host(lib):
     # appendix A.2.1; d = 2, N = 4: a, b, ab, aab, abb, aaab, aabb, abbb at offsets 0,1 | 2+1 | 6+1, 6+3 | 14+1, 14+3, 14+7
     assert sig.sig_lyndon_indices(2, 4) == [0, 1, 3, 7, 9, 15, 17, 21]
