@@ -9,24 +9,32 @@
 // a product [points x d] [d x d] with the antisymmetric part of G_2.  A workgroup stages G_2 of its path in LDS, serves
 // the two end points with vector arithmetic from it (they keep the G_1 term and both products), replaces it by
 // G_2 - G_2^T in place and then multiplies: tiles of 16 points x 16 channels, four channels of the sum per
-// v_mfma_f32_16x16x4_f32, the rows v_k formed from the path a round of points at a time.
+// v_mfma_f32_16x16x4_f32.  The path is staged a round of points at a time as it lies in memory (every point read once);
+// a lane forms its scalar of v_k from the two neighbours' rows as it feeds the matrix instruction.  The next round's
+// points are fetched into registers before the current round is multiplied, and the barriers order LDS traffic only,
+// so loads and stores stay in flight across rounds.
 #include "sig_internal.h"
+#include "sig_lane_ops.h"
 
 namespace sig {
 namespace {
 
 typedef float b2m_f4 __attribute__((ext_vector_type(4)));
+// loads of a round's points a thread has in flight: 6 of 16 bytes where rows allow them, else 8 of 4 bytes
+constexpr int b2m_slots(int V) { return V == 4 ? 6 : 8; }
 
 struct B2mPlan {
     int tiles;             // T = ceil(d / 16)
     int dk;                // d rounded up to a multiple of 4: rows of the staged matrix, length of a staged row v_k
     int ldg;               // floats per staged row of the matrix: 16 T + 1
-    int lda;               // floats per staged v_k: dk + 1
+    int lda;               // floats per staged point: dk or dk + 4
     int round_points;      // interior points per round: 64, 32 or 16
     int rounds;            // rounds per workgroup
     int64_t groups_per_path;
+    int V;                 // scalars per load of the path: 4 (d a multiple of four, 16-byte aligned rows) or 1
 };
 
+template <int V>
 __global__ void __launch_bounds__(256)
 sig_backward_n2_mfma_kernel(Shape sh, B2mPlan pl, const float *__restrict__ path, const float *__restrict__ gout,
                             float *__restrict__ gpath, float *__restrict__ gbase)
@@ -34,8 +42,8 @@ sig_backward_n2_mfma_kernel(Shape sh, B2mPlan pl, const float *__restrict__ path
     extern __shared__ __align__(16) unsigned char b2m_smem[];
     const int d = sh.d, ldg = pl.ldg, lda = pl.lda, dk = pl.dk, cols = 16 * pl.tiles;
     float *Gs = reinterpret_cast<float *>(b2m_smem);   // [dk][ldg]: G_2, later G_2 - G_2^T; zeros beyond d x d
-    float *As = Gs + dk * ldg;                         // [round_points][lda]: the rows v_k of a round
-    float *ends = As + pl.round_points * lda;          // [4][d]: m_0 - p, q - m_0, m_e - p, q - m_e
+    float *Xs = Gs + dk * ldg;                         // [round_points + 2][lda]: the points k0 - 1 .. k0 + round_points
+    float *ends = Xs + (pl.round_points + 2) * lda;    // [4][d]: m_0 - p, q - m_0, m_e - p, q - m_e
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t b = blockIdx.x / pl.groups_per_path, group = blockIdx.x % pl.groups_per_path;
@@ -107,27 +115,54 @@ sig_backward_n2_mfma_kernel(Shape sh, B2mPlan pl, const float *__restrict__ path
     const int64_t k_group = 1 + group * int64_t(pl.round_points) * pl.rounds;
     const int k4 = lane >> 4, c16 = lane & 15;
     const int blocks = pl.round_points / 16, items = blocks * pl.tiles;   // 16 x 16 tiles of a round's result
+    constexpr int kSlots = b2m_slots(V);
+    typedef float b2m_load __attribute__((ext_vector_type(V)));
+    const int per_row = dk / V, entries = (pl.round_points + 2) * per_row;   // loads per point, per round
+    b2m_load ahead[kSlots];
+    // the points k0 - 1 .. k0 + round_points of the scan (clamped at its end) into registers: loads only, every one
+    // unconditional on a clamped index, so they are all in flight together
+    const auto fetch = [&](int64_t k0) {
+#pragma unroll
+        for (int u = 0; u < kSlots; ++u) {
+            if (256 * u < entries) {   // the same for every thread
+                const int e = tid + 256 * u < entries ? tid + 256 * u : 0;
+                const int pt = e / per_row, i = (e - pt * per_row) * V;
+                int64_t k = k0 - 1 + pt;
+                k = k <= n ? k : n;
+                const bool from_base = sh.basepoint && k == 0;
+                const float *src = from_base ? (bpv != nullptr ? bpv + b * d : x) : x + (k - shift) * d;
+                const b2m_load v = *reinterpret_cast<const b2m_load *>(src + (i < d ? i : 0));
+                ahead[u] = from_base && bpv == nullptr ? b2m_load(0.f) : v;
+            }
+        }
+    };
+    if (k_group <= n - 1) fetch(k_group);
     for (int round = 0; round < pl.rounds; ++round) {
         const int64_t k0 = k_group + int64_t(round) * pl.round_points;
         if (k0 > n - 1) break;   // the same for every thread
-        __syncthreads();   // the matrix is ready; the round before has been multiplied
-        for (int e = tid; e < pl.round_points * dk; e += 256) {
-            const int pt = e / dk, i = e - pt * dk;
-            const int64_t k = k0 + pt;
-            const bool on = k <= n - 1 && i < d;
-            const int64_t kk = on ? k : 1;
-            const int ii = on ? i : 0;
-            const float before = scan_point(kk - 1, ii), after = scan_point(kk + 1 <= n ? kk + 1 : n, ii);
-            As[pt * lda + i] = on ? (before - after) * 0.5f : 0.f;
+#pragma unroll
+        for (int u = 0; u < kSlots; ++u) {
+            if (256 * u < entries && tid + 256 * u < entries) {
+                const int e = tid + 256 * u;
+                const int pt = e / per_row, i = (e - pt * per_row) * V;
+                if constexpr (V == 4) {   // d is a multiple of four here: no columns beyond it
+                    *reinterpret_cast<b2m_load *>(Xs + pt * lda + i) = ahead[u];   // rows are a multiple of 16 bytes
+                } else {
+                    Xs[pt * lda + i] = i < d ? ahead[u][0] : 0.f;
+                }
+            }
         }
-        __syncthreads();
+        lds_barrier();   // the points are staged (and, before the first round, the matrix is ready)
+        if (round + 1 < pl.rounds && k0 + pl.round_points <= n - 1) fetch(k0 + pl.round_points);
         for (int item = wave; item < items; item += 4) {
             const int blk = item / pl.tiles, t = item - blk * pl.tiles;
             if (k0 + 16 * blk > n - 1) continue;   // a block of points past the end
-            const float *ap = As + (16 * blk + c16) * lda + k4, *bp = Gs + k4 * ldg + 16 * t + c16;
+            // point 16 blk + c16 of the round is X_k with its neighbours in rows 16 blk + c16 and 16 blk + c16 + 2
+            const float *xp = Xs + (16 * blk + c16) * lda + k4, *bp = Gs + k4 * ldg + 16 * t + c16;
             b2m_f4 acc = b2m_f4(0.f);
 #pragma unroll 4
-            for (int kq = 0; kq < dk; kq += 4) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[kq], bp[kq * ldg], acc, 0, 0, 0);
+            for (int kq = 0; kq < dk; kq += 4)
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32((xp[kq] - xp[2 * lda + kq]) * 0.5f, bp[kq * ldg], acc, 0, 0, 0);
             // register r of lane (k4, c16): point 16 blk + 4 k4 + r of the round, channel 16 t + c16
             const int j = 16 * t + c16;
 #pragma unroll
@@ -136,27 +171,32 @@ sig_backward_n2_mfma_kernel(Shape sh, B2mPlan pl, const float *__restrict__ path
                 if (k <= n - 1 && j < d) gpath[(b * sh.L + k - shift) * d + j] = acc[r];
             }
         }
+        lds_barrier();   // the round has been multiplied: its points may be overwritten
     }
 }
 
 size_t b2m_lds(const B2mPlan &pl, int d)
 {
-    return sizeof(float) * (size_t(pl.dk) * pl.ldg + size_t(pl.round_points) * pl.lda + 4 * size_t(d));
+    return sizeof(float) * (size_t(pl.dk) * pl.ldg + size_t(pl.round_points + 2) * pl.lda + 4 * size_t(d));
 }
 
-bool b2m_plan(const Shape &sh, B2mPlan &pl)
+bool b2m_plan(const Shape &sh, bool vector_loads, B2mPlan &pl)
 {
     if (sh.N != 2 || sh.stream || sh.chunks > 1 || sh.d < 8 || sh.d > 112 || sh.n_inc < 1) return false;
     pl.tiles = (sh.d + 15) / 16;
     pl.dk = (sh.d + 3) / 4 * 4;
     pl.ldg = 16 * pl.tiles + 1;
-    pl.lda = pl.dk + 1;
+    // an odd multiple of four scalars: the 64 lanes' reads of a matrix instruction's left operand (16 rows, 4 consecutive
+    // columns) then fall on every LDS bank exactly twice
+    pl.lda = (pl.dk / 4) % 2 == 1 ? pl.dk : pl.dk + 4;
     pl.round_points = 64;
-    while (pl.round_points > 16 && b2m_lds(pl, sh.d) > 64 * 1024) pl.round_points /= 2;
-    if (b2m_lds(pl, sh.d) > 64 * 1024) return false;
-    // a workgroup stages the matrix once and serves up to 8 rounds, fewer while that leaves under 1024 workgroups
+    pl.V = vector_loads && sh.d % 4 == 0 ? 4 : 1;
+    const auto fits = [&]() { return b2m_lds(pl, sh.d) <= 64 * 1024 && (pl.round_points + 2) * (pl.dk / pl.V) <= b2m_slots(pl.V) * 256; };
+    while (pl.round_points > 16 && !fits()) pl.round_points /= 2;
+    if (!fits()) return false;
+    // a workgroup stages the matrix once and serves up to 16 rounds, fewer while that leaves under 1024 workgroups
     const int64_t interior = sh.n_inc - 1;
-    pl.rounds = 8;
+    pl.rounds = 16;
     const auto groups = [&]() { return interior <= 0 ? int64_t(1) : (interior + int64_t(pl.round_points) * pl.rounds - 1) / (int64_t(pl.round_points) * pl.rounds); };
     while (pl.rounds > 1 && sh.B * groups() < 1024) pl.rounds /= 2;
     pl.groups_per_path = groups();
@@ -168,16 +208,20 @@ bool b2m_plan(const Shape &sh, B2mPlan &pl)
 bool backward_n2_mfma_supported(const Shape &sh)
 {
     B2mPlan pl;
-    return b2m_plan(sh, pl);
+    return b2m_plan(sh, false, pl);
 }
 
 hipError_t launch_backward_n2_mfma_f32(const Shape &sh, const float *path, const float *gout, float *gpath, float *gbase,
                                        hipStream_t st)
 {
     B2mPlan pl;
-    if (!b2m_plan(sh, pl)) return hipErrorNotSupported;
-    hipLaunchKernelGGL(sig_backward_n2_mfma_kernel, dim3(unsigned(sh.B * pl.groups_per_path)), dim3(256), b2m_lds(pl, sh.d), st, sh, pl,
-                       path, gout, gpath, gbase);
+    const bool aligned = (reinterpret_cast<uintptr_t>(path) | reinterpret_cast<uintptr_t>(sh.basepoint_value)) % 16 == 0;
+    if (!b2m_plan(sh, aligned, pl)) return hipErrorNotSupported;
+    const dim3 grid(unsigned(sh.B * pl.groups_per_path));
+    if (pl.V == 4)
+        hipLaunchKernelGGL(sig_backward_n2_mfma_kernel<4>, grid, dim3(256), b2m_lds(pl, sh.d), st, sh, pl, path, gout, gpath, gbase);
+    else
+        hipLaunchKernelGGL(sig_backward_n2_mfma_kernel<1>, grid, dim3(256), b2m_lds(pl, sh.d), st, sh, pl, path, gout, gpath, gbase);
     return hipGetLastError();
 }
 
