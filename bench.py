@@ -321,6 +321,9 @@ def main() -> int:
     units, metric = w.B, "signatures/sec (paths/s)"
     if args.op == "backward":
         flops = w.B * w.n_inc * backward_flops_per_increment(w.d, w.N, M, S)
+        if w.N == 2 and not w.stream:
+            # closed form, no recurrences: a point's gradient is its row of [points x d] [d x d] with G_2 - G_2^T
+            flops = 2 * w.B * w.n_inc * w.d * w.d
         bytes_io = 4 * (2 * w.B * w.L * w.d + 2 * int(np.prod(out_shape)))
         metric = "signature gradients/sec (paths/s)"
     elif args.op == "logsignature":
@@ -341,7 +344,10 @@ def main() -> int:
         flops = 2 * units * sum((k - 1) * w.d ** k for k in range(2, w.N + 1))
         bytes_io = 4 * 3 * units * S
         metric = "group products/sec"
-    if (w.stream and args.op == "forward") or args.op == "combine":
+    # the roof that lies lower for this call: moving its algorithmic bytes at the HBM peak against doing its algorithmic
+    # flops at the fp32 peak (final-mode scans and gradients of few channels at low depth move more than they compute)
+    memory_bound = args.op in ("forward", "backward") and bytes_io / (PEAK_HBM_GBS * 1e9) > flops / (PEAK_FP32_TFLOPS * 1e12)
+    if (w.stream and args.op == "forward") or args.op == "combine" or memory_bound:
         roofline = {"bound": "hbm", "achieved": bytes_io / (kern_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                     "unit": "GB/s"}
         if measured_peaks:
