@@ -50,14 +50,23 @@ struct State8 {
 //   A_1[f_1] before increment s is a coordinate of the path itself,
 //   A_2[f] = sum over earlier increments of T_2^(1) z[f_2],    T_k^(1) = z[f_1]/k + A_1,
 //   A_3[f w_3] = sum over earlier increments of T_3^(2) z[w_3], T_k^(2) = T_k^(1) z[f_2]/(k-1) + A_2.
-// So a whole tile of increments is handled at once, one lane per increment, with prefix sums over the lanes,
-// and what the sequential part of the scan needs from the low levels, T_k^(3)[w_3] = T_k^(2) z[w_3]/(k-2) +
-// A_3[w_3] for k = 4..N, is tabulated in LDS next to the increment.  Every one of the 64 shards of a path
-// would otherwise repeat that arithmetic in each lane at each increment.
+// So a whole tile of increments is handled at once, and what the sequential part of the scan needs from the low
+// levels, T_k^(3)[w_3] = T_k^(2) z[w_3]/(k-2) + A_3[w_3] for k = 4..N, is tabulated in LDS next to the increment.
+// Every one of the 64 shards of a path would otherwise repeat that arithmetic in each lane at each increment.
 //
-// Columns of the table: z[0..7], then T_k^(3)[0..7] / (k - 3) for k = 4..N; kTile8 increments per column.
+// The table is built in two steps.  First a lane per increment: z, T^(1), the prefix sum of level 2 over the
+// wavefront, T_k^(2); z and the T_k^(2) (scaled) go to LDS.  Then a lane per (letter w_3, run of eight increments):
+// the eight terms of A_3[f w_3] of the run are accumulated in registers (one multiply-add each), the run totals are
+// summed over the eight runs of the letter with three lane moves, and the lane writes the table entries of its eight
+// increments.  (One lane per increment for all eight letters costs eight prefix sums over the wavefront, six
+// dependent lane moves each, per tile: two and a half times the instructions.)
+//
+// Columns of the table: z[0..7], then T_k^(3)[0..7] / (k - 3) for k = 4..N, then T_3^(2) and T_k^(2) / ((k-2)(k-3))
+// for k = 4..N (read by the second step only); kTile8 increments per column.
 template <int N>
 constexpr int kRow8 = kD8 * (N - 2);
+template <int N>
+constexpr int kCols8 = kRow8<N> + (N - 2);
 
 // DPP move that leaves 0 in the lanes of the rows (of 16 lanes) not named in ROWS and in lanes whose source lies
 // outside their row.
@@ -65,6 +74,13 @@ template <int CTRL, int ROWS>
 __device__ __forceinline__ float dpp_or_zero(float v)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROWS, 0xf, false));
+}
+
+// The same with a choice of banks (groups of four lanes inside a row) that receive the moved value.
+template <int CTRL, int BANKS>
+__device__ __forceinline__ float dpp_banks_or_zero(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, BANKS, false));
 }
 
 // Inclusive prefix sum over the 64 lanes (lane i receives v_0 + .. + v_i): doubling steps inside each row of 16
@@ -188,10 +204,11 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
     static_assert(N >= 4 && N <= 6, "depths served by this kernel");
     constexpr int kRow = kRow8<N>;
     constexpr int kS = level_off8(N + 1);
-    __shared__ __align__(16) float lds[kCol8 * kRow];
+    __shared__ __align__(16) float lds[kCol8 * kCols8<N>];
 
     const int lane = threadIdx.x;
     const int w3 = lane >> 3, w4 = lane & 7, q = lane & 3;
+    const int seg = lane & 7;   // while a table is built: this lane's run of eight increments, for the letter w3
     const int64_t b = blockIdx.x >> 6;   // output row: a path, or one chunk of a path
     const int f1 = (blockIdx.x >> 3) & 7, f2 = blockIdx.x & 7;
     const ChunkView cv = chunk_view(b, chunks, chunk_len, n_inc_total);
@@ -218,39 +235,41 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
         x_last = pick8(x4[(i_first + n_inc) * 2], x4[(i_first + n_inc) * 2 + 1], f1);
     }
     float A2 = 0.0f;   // A_2[f] before the current tile
-    float A3[kD8];     // A_3[f w], w = 0..7, before the current tile
-#pragma unroll
-    for (int w = 0; w < kD8; ++w) A3[w] = 0.0f;
+    float A3 = 0.0f;   // A_3[f w3] before the current tile
 
     // the two points around increment number s (zeros past the end of the scan); the points of a
     // tile are fetched while the tile before it is being scanned
-    f4 hi0, hi1, lo0, lo1;
+    struct Points {
+        f4 hi0, hi1, lo0, lo1;
+    };
     auto fetch_points = [&](int64_t s) {
-        hi0 = hi1 = lo0 = lo1 = zero4;
+        Points P;
+        P.hi0 = P.hi1 = P.lo0 = P.lo1 = zero4;
         if (s < n_inc) {
             const int64_t i_hi = cv.inc0 + (basepoint ? s : s + 1);
-            hi0 = x4[i_hi * 2];
-            hi1 = x4[i_hi * 2 + 1];
+            P.hi0 = x4[i_hi * 2];
+            P.hi1 = x4[i_hi * 2 + 1];
             if (i_hi > 0) {
-                lo0 = x4[(i_hi - 1) * 2];
-                lo1 = x4[(i_hi - 1) * 2 + 1];
+                P.lo0 = x4[(i_hi - 1) * 2];
+                P.lo1 = x4[(i_hi - 1) * 2 + 1];
             } else {
-                lo0 = base0;
-                lo1 = base1;
+                P.lo0 = base0;
+                P.lo1 = base1;
             }
         }
+        return P;
     };
-    fetch_points(lane);
+    Points P0 = fetch_points(lane);
 
     for (int64_t t0 = 0; t0 < n_inc; t0 += kTile8) {
         const int nt = int(n_inc - t0 < kTile8 ? n_inc - t0 : kTile8);
         __syncthreads();
         {
-            // lane r stages increment t0 + r; lanes past the end of the scan carry zero increments, which add
-            // nothing to the running sums
-            const f4 z0 = hi0 - lo0, z1 = hi1 - lo1;
+            // first step, lane r = increment t0 + r; lanes past the end of the scan carry zero increments, which
+            // add nothing to the running sums (their table entries are never read)
+            const f4 z0 = P0.hi0 - P0.lo0, z1 = P0.hi1 - P0.lo1;
             const float zf1 = pick8(z0, z1, f1), zf2 = pick8(z0, z1, f2);
-            const float a1 = lane < nt ? pick8(lo0, lo1, f1) - x_first : 0.0f;   // A_1[f_1] before this increment
+            const float a1 = lane < nt ? pick8(P0.lo0, P0.lo1, f1) - x_first : 0.0f;   // A_1[f_1] before this increment
             float t1[N + 1], t2[N + 1];
 #pragma unroll
             for (int k = 2; k <= N; ++k) t1[k] = __builtin_fmaf(zf1, 1.0f / k, a1);
@@ -259,47 +278,56 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
             A2 += sum2;
 #pragma unroll
             for (int k = 3; k <= N; ++k) t2[k] = __builtin_fmaf(t1[k], zf2 * (1.0f / (k - 1)), a2);
-            f4 tab[N + 1][2];   // T_k^(3)[w], k = 4..N
-            // the eight prefix sums of level 3 advance together, step by step, so that the latency of one lane
-            // exchange is covered by the seven others
-            float zw[kD8], v3[kD8], in3[kD8];
 #pragma unroll
-            for (int w = 0; w < kD8; ++w) {
-                zw[w] = w < 4 ? z0[w & 3] : z1[w & 3];
-                in3[w] = v3[w] = t2[3] * zw[w];
-            }
+            for (int w = 0; w < kD8; ++w) lds[w * kCol8 + lane] = w < 4 ? z0[w & 3] : z1[w & 3];
+            lds[kRow * kCol8 + lane] = t2[3];
 #pragma unroll
-            for (int w = 0; w < kD8; ++w) v3[w] += dpp_or_zero<0x111, 0xf>(v3[w]);
+            for (int k = 4; k <= N; ++k) lds[(kRow + k - 3) * kCol8 + lane] = t2[k] * (1.0f / ((k - 2) * (k - 3)));
+        }
+        __syncthreads();
+        {
+            // second step, lane (w3, seg): increments 8 seg .. 8 seg + 7 of the tile, letter w3
+            const float *zc = lds + w3 * kCol8 + 8 * seg, *tc = lds + kRow * kCol8 + 8 * seg;
+            const f4 za = *reinterpret_cast<const f4 *>(zc), zb = *reinterpret_cast<const f4 *>(zc + 4);
+            const f4 ta = *reinterpret_cast<const f4 *>(tc), tb = *reinterpret_cast<const f4 *>(tc + 4);
+            float zz[8], p[8];   // p[j]: the terms of A_3[f w3] of the run up to and with increment j
 #pragma unroll
-            for (int w = 0; w < kD8; ++w) v3[w] += dpp_or_zero<0x112, 0xf>(v3[w]);
+            for (int j = 0; j < 8; ++j) zz[j] = j < 4 ? za[j & 3] : zb[j & 3];
+            p[0] = ta[0] * zz[0];
 #pragma unroll
-            for (int w = 0; w < kD8; ++w) v3[w] += dpp_or_zero<0x114, 0xf>(v3[w]);
+            for (int j = 1; j < 8; ++j) p[j] = __builtin_fmaf(j < 4 ? ta[j & 3] : tb[j & 3], zz[j], p[j - 1]);
+            // totals of the runs before this one (the eight runs of a letter sit in eight consecutive lanes)
+            float incl = p[7], moved;
+            moved = dpp_or_zero<0x111, 0xf>(incl);   // row_shr:1
+            incl += seg >= 1 ? moved : 0.0f;
+            moved = dpp_or_zero<0x112, 0xf>(incl);   // row_shr:2
+            incl += seg >= 2 ? moved : 0.0f;
+            incl += dpp_banks_or_zero<0x114, 0xa>(incl);   // row_shr:4 into the upper half of each group of eight
+            const float total = __builtin_bit_cast(
+                float, __builtin_amdgcn_ds_bpermute(4 * (lane | 7), __builtin_bit_cast(int, incl)));
+            const float before = A3 + (incl - p[7]);
+            A3 += total;
+            float a3[8];   // A_3[f w3] before increment j of the run
+            a3[0] = before;
 #pragma unroll
-            for (int w = 0; w < kD8; ++w) v3[w] += dpp_or_zero<0x118, 0xf>(v3[w]);
+            for (int j = 1; j < 8; ++j) a3[j] = before + p[j - 1];
 #pragma unroll
-            for (int w = 0; w < kD8; ++w) v3[w] += dpp_or_zero<0x142, 0xa>(v3[w]);
+            for (int k = 4; k <= N; ++k) {
+                const float *uc = lds + (kRow + k - 3) * kCol8 + 8 * seg;
+                const f4 ua = *reinterpret_cast<const f4 *>(uc), ub = *reinterpret_cast<const f4 *>(uc + 4);
+                f4 ea, eb;   // T_k^(3)[w3] / (k - 3)
 #pragma unroll
-            for (int w = 0; w < kD8; ++w) v3[w] += dpp_or_zero<0x143, 0xc>(v3[w]);
-#pragma unroll
-            for (int w = 0; w < kD8; ++w) {
-                const float total = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v3[w]), 63));
-                const float a3 = A3[w] + (v3[w] - in3[w]);   // exclusive prefix sum
-                A3[w] += total;
-#pragma unroll
-                for (int k = 4; k <= N; ++k)
-                    tab[k][w >> 2][w & 3] = __builtin_fmaf(t2[k], zw[w] * (1.0f / (k - 2)), a3) * (1.0f / (k - 3));
-            }
-            if (lane < nt) {
-#pragma unroll
-                for (int w = 0; w < kD8; ++w) {
-                    lds[w * kCol8 + lane] = w < 4 ? z0[w & 3] : z1[w & 3];
-#pragma unroll
-                    for (int k = 4; k <= N; ++k) lds[(kD8 * (k - 3) + w) * kCol8 + lane] = tab[k][w >> 2][w & 3];
+                for (int j = 0; j < 4; ++j) {
+                    ea[j] = __builtin_fmaf(ua[j], zz[j], k == 4 ? a3[j] : a3[j] * (1.0f / (k - 3)));
+                    eb[j] = __builtin_fmaf(ub[j], zz[4 + j], k == 4 ? a3[4 + j] : a3[4 + j] * (1.0f / (k - 3)));
                 }
+                float *ec = lds + (kD8 * (k - 3) + w3) * kCol8 + 8 * seg;
+                *reinterpret_cast<f4 *>(ec) = ea;
+                *reinterpret_cast<f4 *>(ec + 4) = eb;
             }
         }
         __syncthreads();
-        fetch_points(t0 + kTile8 + lane);
+        P0 = fetch_points(t0 + kTile8 + lane);
         int s = 0;
         if (nt >= 4) {
             // four increments per LDS round trip, the next four fetched while these are folded in (two sets of
@@ -307,9 +335,11 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
             Rows8<N> V0 = load_rows8<N>(lds, 0, w3, w4, q);
             for (; s + 12 <= nt; s += 8) {
                 const Rows8<N> V1 = load_rows8<N>(lds, s + 4, w3, w4, q);
+                __builtin_amdgcn_sched_barrier(0);   // the reads are issued before the arithmetic they hide behind
 #pragma unroll
                 for (int i = 0; i < 4; ++i) step8<N>(S, pick_row8<N>(V0, i));
                 V0 = load_rows8<N>(lds, s + 8, w3, w4, q);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) step8<N>(S, pick_row8<N>(V1, i));
             }
@@ -325,16 +355,11 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
         }
         for (; s < nt; ++s) step8<N>(S, load_row8<N>(lds, s, w3, w4, q));
     }
-    // this lane's A_3[f w_3]
-    float a3_mine = A3[0];
-#pragma unroll
-    for (int w = 1; w < kD8; ++w) a3_mine = w3 == w ? A3[w] : a3_mine;
-
     // store this shard's slice of every level
     const int f = f1 * 8 + f2;
     if (f2 == 0 && lane == 0) o[f1] = x_last - x_first;   // level 1 is the total displacement
     if (lane == 0) o[level_off8(2) + f] = A2;
-    if (w4 == 0) o[level_off8(3) + f * 8 + w3] = a3_mine;
+    if (w4 == 0) o[level_off8(3) + f * 8 + w3] = A3;
     o[level_off8(4) + f * 64 + lane] = S.A4;
     if constexpr (N == 5) {
         // register r, lane (block, q) of group g: word 8*(lane/4 * 4 + q) + 4*g + r of the 512-word slice
