@@ -137,10 +137,15 @@ sig_tree_backward_kernel(Shape sh, const T *__restrict__ path, const T *__restri
     if (!live) G = Share{};
     Share A = {};
     if constexpr (!STREAM) A = load_share(sg, false, U >= 2, false);
-    // Stream mode reads a row of the forward output and a row of its cotangent at every increment: both are fetched an
-    // increment ahead of their use, so that a trip to memory is not part of every step of the chain.
+    // Stream mode reads a row of the forward output and a row of its cotangent at every increment.  In fp32 both are
+    // fetched an increment ahead of their use, so that a trip to memory is not part of every step of the chain.  In
+    // fp64 they are fetched where they are used: two more shares of a flat element (up to 94 registers each at d = 6)
+    // take these kernels to 350 and more registers per lane, and the code generated for d = 4, N = 8; d = 5, N = 7;
+    // d = 6, N = 6 and d = 8, N = 6 then lost the cotangent of the levels above a thread's word at the first
+    // increment (tests/test_backward_gpu.py: test_tree_gradient_every_shape).
+    constexpr bool kAhead = STREAM && sizeof(T) == 4;
     Share A_ahead = {};
-    if constexpr (STREAM) {
+    if constexpr (kAhead) {
         if (sh.n_inc >= 2) A_ahead = load_share(sg + (sh.n_inc - 2) * kS, false, U >= 2, false);
     }
 
@@ -179,11 +184,13 @@ sig_tree_backward_kernel(Shape sh, const T *__restrict__ path, const T *__restri
             for (int c = 0; c < D; ++c) zu[c] = zrow[c];
 
             Share G_ahead = {};
-            if constexpr (STREAM) {
+            if constexpr (kAhead) {
                 // the signature after s increments is output entry s-1 (the identity for s = 0)
                 A = s > 0 ? A_ahead : Share{};
                 if (s >= 2) A_ahead = load_share(sg + (s - 2) * kS, false, U >= 2, false);
                 if (s > 0 && live) G_ahead = load_share(go + (s - 1) * kS, true, true, true);   // added at the end of this step
+            } else if constexpr (STREAM) {
+                A = s > 0 ? load_share(sg + (s - 1) * kS, false, U >= 2, false) : Share{};
             }
 
             // ---- up: Hn[j][k] = T^(k)_j at this thread's word; the signature before the increment
@@ -292,6 +299,7 @@ sig_tree_backward_kernel(Shape sh, const T *__restrict__ path, const T *__restri
 
             if constexpr (STREAM) {
                 if (s > 0 && live) {
+                    if constexpr (!kAhead) G_ahead = load_share(go + (s - 1) * kS, true, true, true);
                     const Share &add = G_ahead;
 #pragma unroll
                     for (int j = 1; j <= P; ++j) G.lo[j] += add.lo[j];

@@ -129,6 +129,26 @@ def test_prefix_tree_kernels_wide_in_fp64():
         check(x, N, stream=True, basepoint=True)
 
 
+def tree_gradient_shapes(max_scalars):
+    """Every (d, N) the prefix-tree gradient kernels are instantiated for (d = 2..8 to depth 9, d = 9..16 to depth
+    6), up to signatures of `max_scalars` scalars."""
+    return [(d, N) for d in range(2, 17) for N in range(2, (9 if d <= 8 else 6) + 1)
+            if sig.sig_signature_channels(d, N) <= max_scalars]
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("stream", [False, True], ids=["final", "stream"])
+def test_tree_gradient_every_shape(dtype, stream):
+    """One instantiation of the prefix-tree gradient kernels per (d, N), mode and precision, some at 350 and more
+    registers per lane: every one of them on two paths of three points (two increments: the last one and the first
+    one, which in stream mode takes the identity for the signature before it), misaligned so that no other family
+    takes the call.  In fp64 stream mode at d = 4, N = 8; d = 5, N = 7; d = 6, N = 6 and d = 8, N = 6 the first
+    increment once lost the cotangent of the levels above a thread's word."""
+    for d, N in tree_gradient_shapes(3_000_000 if not stream else 1_000_000):
+        x = uniform_paths(2, 3, d, seed=100 * d + N, lo=-0.4, hi=0.4).astype(dtype)
+        check(x, N, stream=stream, misalign=True)
+
+
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 def test_more_paths_than_compute_units(dtype):
     x = brownian_paths(515, 9, 3, seed=77).astype(dtype)
