@@ -128,9 +128,10 @@ __device__ __forceinline__ void prefix_lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// n / d for n < 2^16 and 2 <= d <= 64 with magic = ceil(2^32 / d): the excess n (magic d - 2^32) / (d 2^32) stays
-// below n / 2^32 < 1 / d, so it never carries into the quotient.
-__device__ __forceinline__ uint32_t prefix_div(uint32_t n, uint32_t magic) { return __umulhi(n, magic); }
+// n / d for n < 2^16 and 1 <= d < 2^16 with magic = ceil(2^32 / d) kept in 32 bits: the excess
+// n (magic d - 2^32) / (d 2^32) stays below n / 2^32 < 1 / d, so it never carries into the quotient.  For d = 1 the
+// magic number is 2^32, which 32 bits hold as 0: the quotient is n itself (one channel, or a signature of one scalar).
+__device__ __forceinline__ uint32_t prefix_div(uint32_t n, uint32_t magic) { return magic != 0 ? __umulhi(n, magic) : n; }
 
 constexpr int kPrefixPerThread = 32;
 constexpr int kPrefixLdsWords = 256 * kPrefixPerThread;

@@ -496,6 +496,7 @@ def test_chunked_scan_argument_checks():
     (3, 130, 3, 5), (2, 257, 8, 3), (5, 200, 6, 3), (1, 130, 5, 6), (2, 140, 12, 3), (3, 1101, 3, 4), (17, 129, 7, 2),
     (4, 130, 2, 5), (2, 300, 3, 3), (3, 129, 20, 1), (2, 513, 2, 8), (4, 130, 2, 3), (2, 200, 8, 4), (3, 131, 16, 2),
     (2, 150, 20, 3), (3, 130, 17, 2), (1, 140, 32, 3), (2, 129, 9, 7 - 2),   # beyond 16 channels: the kernel for many channels
+    (40, 1100, 1, 1), (3, 130, 1, 1), (2, 300, 1, 4), (5, 131, 2, 1),   # one channel, a signature of one scalar (divisions by 1)
 ])
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 def test_stream_mode_cut_into_chunks(B, L, d, N, dtype):
