@@ -145,10 +145,17 @@ typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 // Writes this shard's slice of every level of one signature.  The signature starts `row_bytes`
 // into the buffer described by `rsrc` (a wave-uniform scalar), so the stores need no per-lane
 // address arithmetic; stores beyond the descriptor's range would be dropped by the hardware.
-template <int N>
+template <int N, bool SETTLE = false>
 __device__ __forceinline__ void store_shard(const ShardState<N> &S, __amdgpu_buffer_rsrc_t rsrc, int row_bytes,
                                             const StorePlan &p, int lane)
 {
+    if constexpr (SETTLE) {
+        // idle issue slots between the matrix instructions of the step and the moves that read their results
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_nop 7");
+        asm volatile("s_nop 7");
+        __builtin_amdgcn_sched_barrier(0);
+    }
     const unsigned low = (__builtin_bit_cast(unsigned, S.A1) & p.m1) | (__builtin_bit_cast(unsigned, S.A2) & p.m2) |
                          (__builtin_bit_cast(unsigned, S.A3) & p.m3);
     __builtin_amdgcn_raw_buffer_store_b32(low, rsrc, p.low_off, row_bytes, 0);
@@ -250,19 +257,27 @@ sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out
         // stream mode: one descriptor per tile of prefix signatures (a tile is at most 64 * 87376 bytes)
         const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(o + (STREAM ? t0 * kS : 0), unsigned(STREAM ? nt : 1) * kS * 4u);
         int s = 0;
-        for (; s + 4 <= nt; s += 4) {
+        // Four increments per round of LDS reads, except in stream mode at depth 6, where level 5 is transposed (DPP
+        // moves on the results of matrix instructions) before every store.  There the first prefix signature of a
+        // round came out, now and then, with one register of level 5 stale in lanes 12..15 of every row of 16 (the
+        // blocks a 4x4x1 matrix instruction writes last) once a SIMD held more than one wavefront (more than 128
+        // paths).  Neither the increment-by-increment loop nor idle slots before the transposes (SETTLE) ever showed
+        // it at depth 6; both are used.  At depth 7 (levels 5 and 6 transposed) either still did, and stream mode
+        // there is left to the other kernel families.
+        constexpr bool kRoundsOfFour = !(STREAM && N >= 6);
+        for (; kRoundsOfFour && s + 4 <= nt; s += 4) {
             ShardRow<N> R[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) R[i] = load_shard_row<N>(lds + (s + i) * kRow, f, w2, w3, q);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 shard_step<N>(S, R[i]);
-                if constexpr (STREAM) store_shard<N>(S, rsrc, (s + i) * kS * 4, plan, lane);
+                if constexpr (STREAM) store_shard<N, (N >= 6)>(S, rsrc, (s + i) * kS * 4, plan, lane);
             }
         }
         for (; s < nt; ++s) {
             shard_step<N>(S, load_shard_row<N>(lds + s * kRow, f, w2, w3, q));
-            if constexpr (STREAM) store_shard<N>(S, rsrc, s * kS * 4, plan, lane);
+            if constexpr (STREAM) store_shard<N, (N >= 6)>(S, rsrc, s * kS * 4, plan, lane);
         }
     }
     if constexpr (!STREAM) store_shard<N>(S, make_rsrc(o, kS * 4u), 0, plan, lane);
@@ -417,6 +432,7 @@ hipError_t launch_shard(const Shape &sh, const float *path, float *out, hipStrea
 const char *mfma_shard_kernel_name(const Shape &sh)
 {
     if (sh.d != 4 || sh.N < 4 || sh.N > 7 || sh.B > 0x1fffffff) return nullptr;
+    if (sh.stream && sh.N == 7) return nullptr;   // see the note on rounds of four in the kernel
     return "mfma_d4_shard";
 }
 

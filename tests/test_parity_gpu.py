@@ -205,6 +205,28 @@ def test_large_stream_outputs_take_the_run_assembling_kernel():
     assert np.all(batch <= 1e-4) and np.all(single <= 5e-4) and np.all(element <= 1e-4), (batch, single, element)
 
 
+MANY_SHORT = [
+    # (B, L, N): more wavefronts than SIMDs (several wavefronts share a SIMD), rounds of four increments and tails
+    (700, 8, 6), (400, 30, 6), (1300, 9, 6), (2000, 5, 6), (700, 8, 5), (1300, 9, 4), (300, 8, 7), (500, 5, 7),
+]
+MANY_SHORT_CASES = [pytest.param(B, L, N, v.values[0], id=f"{B}-{L}-{N}-{v.id}")
+                    for (B, L, N) in MANY_SHORT
+                    for v in serving_variants(B, L, 4, N, np.float32, [(True, False)])
+                    if v.id in ("auto", "mfma_shard", "mfma_stream")]
+
+
+@pytest.mark.parametrize("B,L,N,variant", MANY_SHORT_CASES)
+def test_d4_stream_mode_many_short_paths(B, L, N, variant):
+    """Stream mode at d = 4 with hundreds to thousands of short paths, every path and prefix against the oracle, three
+    launches each.  With more than 128 paths a SIMD holds several wavefronts of the four-wavefront kernel; at depth
+    6 and 7 the first prefix signature of a round of four increments then came out, now and then, with one register
+    of a transposed level stale in lanes 12..15 of every row of 16 lanes."""
+    x = (0.2 * np.random.Generator(np.random.PCG64(B + L + N)).standard_normal((B, L, 4))).astype(np.float32)
+    want = orc.signature(x, N, stream=True)
+    for _ in range(3):
+        assert check(x, N, stream=True, variant=variant, want=want) is not None
+
+
 def test_d4_depth_seven():
     x = brownian_paths(3, 21, 4, seed=707)
     check(x, 7)
