@@ -65,6 +65,7 @@ sig_status make_shape(int64_t B, int64_t L, int d, int N, int stream, int basepo
     sh.basepoint_value = nullptr;
     sh.chunks = 1;
     sh.rows_in_stream = 0;
+    sh.from_identity = 1;
     sh.chunk_len = 0;
     sh.n_inc = basepoint ? L : L - 1;
     // path elements B*L*d and output elements B*[n_inc*]S must stay below kMaxElems
@@ -93,6 +94,7 @@ sig_status make_rows_shape(int64_t rows, int d, int N, sig::Shape &sh)
     sh.basepoint_value = nullptr;
     sh.chunks = 1;
     sh.rows_in_stream = 0;
+    sh.from_identity = 1;
     sh.chunk_len = 0;
     return SIG_OK;
 }
@@ -394,6 +396,7 @@ static sig_status plan_backward_chunked(int64_t B, int64_t L, int d, int N, int 
         return SIG_OK;
     }
     if (!sig::combine_supported(pl.rows)) return SIG_ERR_UNSUPPORTED;
+    pl.rows.from_identity = 0;   // a stretch is walked back from the signature of the path up to its end
     pl.inner_bytes = sig::backward_workspace_bytes(pl.rows, dtype);
     if (pl.inner_bytes < 0) return SIG_ERR_UNSUPPORTED;
     const int64_t elem = dtype == SIG_F32 ? int64_t(sizeof(float)) : int64_t(sizeof(double));

@@ -141,7 +141,8 @@ hipError_t launch_backward_n2_t(const Shape &sh, const T *path, const T *gout, T
 
 bool backward_n2_supported(const Shape &sh, sig_dtype dtype)
 {
-    if (sh.N != 2 || sh.stream || sh.chunks > 1 || sh.d < 1 || sh.d > 255) return false;
+    // the closed form is the gradient of a row's own signature: it does not serve a stretch of a longer path
+    if (sh.N != 2 || sh.stream || sh.chunks > 1 || !sh.from_identity || sh.d < 1 || sh.d > 255) return false;
     const int ppg = n2_points_per_group(sh.d);
     const size_t lds = dtype == SIG_F32 ? n2_lds_bytes<float>(sh.d, ppg) : n2_lds_bytes<double>(sh.d, ppg);
     return lds <= 64 * 1024 && sh.B * ((sh.L + ppg - 1) / ppg) <= 0x7fffffff;

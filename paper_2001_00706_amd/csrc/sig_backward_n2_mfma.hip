@@ -182,7 +182,7 @@ size_t b2m_lds(const B2mPlan &pl, int d)
 
 bool b2m_plan(const Shape &sh, bool vector_loads, B2mPlan &pl)
 {
-    if (sh.N != 2 || sh.stream || sh.chunks > 1 || sh.d < 8 || sh.d > 112 || sh.n_inc < 1) return false;
+    if (sh.N != 2 || sh.stream || sh.chunks > 1 || !sh.from_identity || sh.d < 8 || sh.d > 112 || sh.n_inc < 1) return false;
     pl.tiles = (sh.d + 15) / 16;
     pl.dk = (sh.d + 3) / 4 * 4;
     pl.ldg = 16 * pl.tiles + 1;

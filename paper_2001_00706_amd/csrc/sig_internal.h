@@ -28,6 +28,9 @@ struct Shape {
     // last increment; with stream != 0 a chunk starts from the row before its first increment (the empty signature
     // at the start of a path) and writes the row of every increment of its own but the last.  0: rows are packed.
     int rows_in_stream;
+    // Gradient calls: 0 when the signature handed in belongs to a longer path of which the rows are stretches (the
+    // walk back then starts from that signature and must not assume that a row's own increments make it up).
+    int from_identity;
     int64_t pw[SIG_MAX_DEPTH + 1];   // pw[k] = d^k, k = 0..N
     int64_t off[SIG_MAX_DEPTH + 2];  // off[k] = offset of level k (1-based) in a signature; off[N+1] = S
 };

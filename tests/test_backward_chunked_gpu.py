@@ -46,6 +46,9 @@ def check(x, N, chunks, basepoint=False, seed=0):
 @pytest.mark.parametrize("B,L,d,N,chunks", [
     (2, 65, 3, 4, 4), (3, 64, 4, 4, 8), (1, 130, 2, 6, 16), (2, 41, 5, 3, 5), (1, 100, 4, 6, 7), (2, 50, 16, 4, 4),
     (1, 33, 20, 3, 3), (2, 30, 6, 5, 6), (1, 40, 3, 10, 4), (4, 20, 8, 3, 2), (1, 300, 4, 5, 32), (2, 19, 3, 3, 18),
+    # depth 2 (a stretch is not a path of its own: the closed form of the depth-2 gradient must step aside) and depth 1
+    (1, 64, 4, 2, 2), (2, 300, 32, 2, 16), (5, 9, 64, 2, 4), (33, 64, 16, 2, 7), (2, 100, 1, 2, 8), (3, 50, 48, 2, 5),
+    (2, 40, 5, 1, 4), (1, 30, 1, 1, 3),
 ])
 def test_stretches_walked_back_side_by_side(B, L, d, N, chunks, dtype):
     check(brownian_paths(B, L, d, seed=L + d).astype(dtype), N, chunks)
