@@ -227,6 +227,27 @@ def test_d4_stream_mode_many_short_paths(B, L, N, variant):
         assert check(x, N, stream=True, variant=variant, want=want) is not None
 
 
+MANY_FINAL = [
+    # (B, L, d, N): every matrix-core family in final mode with several wavefronts per SIMD
+    (2500, 30, 4, 6), (2500, 9, 4, 5), (3000, 6, 4, 4), (1500, 12, 4, 7), (200, 20, 8, 5), (150, 9, 8, 6), (300, 70, 8, 4),
+    (700, 12, 16, 4),
+]
+MANY_FINAL_CASES = [pytest.param(B, L, d, N, v.values[0], id=f"{B}-{L}-{d}-{N}-{v.id}")
+                    for (B, L, d, N) in MANY_FINAL
+                    for v in serving_variants(B, L, d, N, np.float32, [(False, False)])
+                    if v.id in ("auto", "mfma", "mfma_shard")]
+
+
+@pytest.mark.parametrize("B,L,d,N,variant", MANY_FINAL_CASES)
+def test_matrix_core_kernels_with_several_wavefronts_per_simd(B, L, d, N, variant):
+    """Final mode on the matrix-core families with more wavefronts than the device has SIMDs (the benchmark workloads
+    put at most two on one): every path against the oracle, two launches each."""
+    x = (0.2 * np.random.Generator(np.random.PCG64(B + L + d + N)).standard_normal((B, L, d))).astype(np.float32)
+    want = orc.signature(x, N)
+    for _ in range(2):
+        assert check(x, N, variant=variant, want=want) is not None
+
+
 def test_d4_depth_seven():
     x = brownian_paths(3, 21, 4, seed=707)
     check(x, 7)
