@@ -55,8 +55,8 @@ typedef enum {
     SIG_VARIANT_MFMA = 2,     /* fp32, final mode, state in registers, outer products on the matrix cores:
                                  d = 4, N = 4..6 (one wavefront per path); d = 8, N = 4..6 (64 wavefronts per
                                  path); d = 16, N = 4 (8 wavefronts per path) */
-    SIG_VARIANT_MFMA_SHARD = 3,/* fp32, d = 4, N = 4..7 in final mode, N = 4..6 in stream mode: four independent
-                                 wavefronts per path, one per first letter */
+    SIG_VARIANT_MFMA_SHARD = 3,/* fp32, d = 4, N = 4..7, final and stream mode: four independent wavefronts
+                                 per path, one per first letter */
     SIG_VARIANT_SMALL = 4,    /* any dtype and mode, S <= 512, N <= 8, d <= 64: one wavefront per path, state in LDS */
     SIG_VARIANT_TREE = 5,     /* any dtype and mode; d = 2..8 at N = 2..9: a thread per word of N-2 letters; d = 9..16 at
                                  N = 2..6: a thread per word of N-1 letters; state in registers, any number of

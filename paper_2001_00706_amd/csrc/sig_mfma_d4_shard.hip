@@ -21,7 +21,7 @@
 // operands swapped: register r is then the LAST letter w_N and lane q the letter before it, a lane
 // holds 4 consecutive words, and a wavefront store covers 1 KB of contiguous output with no
 // shuffling at all.  Lower matrix-core levels (only present for N >= 6) are transposed inside each
-// lane quad with DPP moves before they are stored.  The 21 words of levels 1..3 go out in one store
+// lane quad with DPP moves before they are stored in final mode, and stored word by word in stream mode.  The 21 words of levels 1..3 go out in one store
 // instruction: every lane writes one of them (several lanes the same word with the same value).
 #include "sig_internal.h"
 #include "sig_mfma_common.h"
@@ -145,30 +145,48 @@ typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 // Writes this shard's slice of every level of one signature.  The signature starts `row_bytes`
 // into the buffer described by `rsrc` (a wave-uniform scalar), so the stores need no per-lane
 // address arithmetic; stores beyond the descriptor's range would be dropped by the hardware.
-template <int N, bool SETTLE = false>
+template <int N, bool IN_PLACE = false>
 __device__ __forceinline__ void store_shard(const ShardState<N> &S, __amdgpu_buffer_rsrc_t rsrc, int row_bytes,
                                             const StorePlan &p, int lane)
 {
-    if constexpr (SETTLE) {
-        // idle issue slots between the matrix instructions of the step and the moves that read their results
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_nop 7");
-        asm volatile("s_nop 7");
-        __builtin_amdgcn_sched_barrier(0);
-    }
     const unsigned low = (__builtin_bit_cast(unsigned, S.A1) & p.m1) | (__builtin_bit_cast(unsigned, S.A2) & p.m2) |
                          (__builtin_bit_cast(unsigned, S.A3) & p.m3);
     __builtin_amdgcn_raw_buffer_store_b32(low, rsrc, p.low_off, row_bytes, 0);
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, S.A4), rsrc, p.off4, row_bytes, 0);
+    // IN_PLACE (stream mode, where every increment ends in a store): a level below the top one goes out as it sits in
+    // the registers (register r = letter w_{k-1}, lane q = letter w_k): four one-word stores, 16 r - 12 q bytes from
+    // where the lane's transposed 16 bytes would start; the four lanes of a quad write 16 contiguous bytes per
+    // instruction.  Transposed in the lane quads (DPP moves on copies of the accumulators) and stored 16 bytes per
+    // lane, the first prefix signature of a round of four increments came out, now and then, with one register of
+    // the transposed level wrong in lanes 12..15 of every row of 16 lanes, once a SIMD held more than one wavefront
+    // (more than 128 paths; depth 6 and 7; the state itself stayed right).  Final mode transposes once, after the
+    // scan, and never showed it.
+    const int back = 12 * (lane & 3);
+    auto store_word = [&](float word, int offset) {
+        // through a vector register: handed the element of an accumulator tuple directly, the compiler stored element 0
+        // of the tuple four times
+        asm volatile("" : "+v"(word));
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, word), rsrc, offset, row_bytes, 0);
+    };
     if constexpr (N >= 5) {
-        const f4 v = N == 5 ? S.A5[0] : quad_transpose(S.A5[0], lane);
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), rsrc, p.off5, row_bytes, 0);
+        if constexpr (N >= 6 && IN_PLACE) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) store_word(S.A5[0][r], p.off5 - back + 16 * r);
+        } else {
+            const f4 v = N == 5 ? S.A5[0] : quad_transpose(S.A5[0], lane);
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), rsrc, p.off5, row_bytes, 0);
+        }
     }
     if constexpr (N >= 6) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const f4 v = N == 6 ? S.A6[g] : quad_transpose(S.A6[g], lane);
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), rsrc, p.off6 + 64 * g, row_bytes, 0);
+            if constexpr (N >= 7 && IN_PLACE) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) store_word(S.A6[g][r], p.off6 + 64 * g - back + 16 * r);
+            } else {
+                const f4 v = N == 6 ? S.A6[g] : quad_transpose(S.A6[g], lane);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), rsrc, p.off6 + 64 * g, row_bytes, 0);
+            }
         }
     }
     if constexpr (N >= 7) {
@@ -257,27 +275,19 @@ sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out
         // stream mode: one descriptor per tile of prefix signatures (a tile is at most 64 * 87376 bytes)
         const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(o + (STREAM ? t0 * kS : 0), unsigned(STREAM ? nt : 1) * kS * 4u);
         int s = 0;
-        // Four increments per round of LDS reads, except in stream mode at depth 6, where level 5 is transposed (DPP
-        // moves on the results of matrix instructions) before every store.  There the first prefix signature of a
-        // round came out, now and then, with one register of level 5 stale in lanes 12..15 of every row of 16 (the
-        // blocks a 4x4x1 matrix instruction writes last) once a SIMD held more than one wavefront (more than 128
-        // paths).  Neither the increment-by-increment loop nor idle slots before the transposes (SETTLE) ever showed
-        // it at depth 6; both are used.  At depth 7 (levels 5 and 6 transposed) either still did, and stream mode
-        // there is left to the other kernel families.
-        constexpr bool kRoundsOfFour = !(STREAM && N >= 6);
-        for (; kRoundsOfFour && s + 4 <= nt; s += 4) {
+        for (; s + 4 <= nt; s += 4) {
             ShardRow<N> R[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) R[i] = load_shard_row<N>(lds + (s + i) * kRow, f, w2, w3, q);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 shard_step<N>(S, R[i]);
-                if constexpr (STREAM) store_shard<N, (N >= 6)>(S, rsrc, (s + i) * kS * 4, plan, lane);
+                if constexpr (STREAM) store_shard<N, true>(S, rsrc, (s + i) * kS * 4, plan, lane);
             }
         }
         for (; s < nt; ++s) {
             shard_step<N>(S, load_shard_row<N>(lds + s * kRow, f, w2, w3, q));
-            if constexpr (STREAM) store_shard<N, (N >= 6)>(S, rsrc, s * kS * 4, plan, lane);
+            if constexpr (STREAM) store_shard<N, true>(S, rsrc, s * kS * 4, plan, lane);
         }
     }
     if constexpr (!STREAM) store_shard<N>(S, make_rsrc(o, kS * 4u), 0, plan, lane);
@@ -432,7 +442,6 @@ hipError_t launch_shard(const Shape &sh, const float *path, float *out, hipStrea
 const char *mfma_shard_kernel_name(const Shape &sh)
 {
     if (sh.d != 4 || sh.N < 4 || sh.N > 7 || sh.B > 0x1fffffff) return nullptr;
-    if (sh.stream && sh.N == 7) return nullptr;   // see the note on rounds of four in the kernel
     return "mfma_d4_shard";
 }
 

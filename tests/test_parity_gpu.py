@@ -220,7 +220,8 @@ def test_d4_stream_mode_many_short_paths(B, L, N, variant):
     """Stream mode at d = 4 with hundreds to thousands of short paths, every path and prefix against the oracle, three
     launches each.  With more than 128 paths a SIMD holds several wavefronts of the four-wavefront kernel; at depth
     6 and 7 the first prefix signature of a round of four increments then came out, now and then, with one register
-    of a transposed level stale in lanes 12..15 of every row of 16 lanes."""
+    of a level that was transposed in the lane quads before its store wrong in lanes 12..15 of every row of 16 lanes
+    (stream mode stores those levels untransposed now)."""
     x = (0.2 * np.random.Generator(np.random.PCG64(B + L + N)).standard_normal((B, L, 4))).astype(np.float32)
     want = orc.signature(x, N, stream=True)
     for _ in range(3):
