@@ -20,8 +20,8 @@
 // next stage.  The top level feeds no further stage, so its outer product is taken with the two
 // operands swapped: register r is then the LAST letter w_N and lane q the letter before it, a lane
 // holds 4 consecutive words, and a wavefront store covers 1 KB of contiguous output with no
-// shuffling at all.  Lower matrix-core levels (only present for N >= 6) are transposed inside each
-// lane quad with DPP moves before they are stored in final mode, and stored word by word in stream mode.  The 21 words of levels 1..3 go out in one store
+// shuffling at all.  Lower matrix-core levels (only present for N >= 6) are stored word by word, as
+// they sit in the registers (the four lanes of a quad write 16 contiguous bytes per instruction).  The 21 words of levels 1..3 go out in one store
 // instruction: every lane writes one of them (several lanes the same word with the same value).
 #include "sig_internal.h"
 #include "sig_mfma_common.h"
@@ -153,14 +153,14 @@ __device__ __forceinline__ void store_shard(const ShardState<N> &S, __amdgpu_buf
                          (__builtin_bit_cast(unsigned, S.A3) & p.m3);
     __builtin_amdgcn_raw_buffer_store_b32(low, rsrc, p.low_off, row_bytes, 0);
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, S.A4), rsrc, p.off4, row_bytes, 0);
-    // IN_PLACE (stream mode, where every increment ends in a store): a level below the top one goes out as it sits in
+    // IN_PLACE (what both modes of the four-wavefront kernel use): a level below the top one goes out as it sits in
     // the registers (register r = letter w_{k-1}, lane q = letter w_k): four one-word stores, 16 r - 12 q bytes from
     // where the lane's transposed 16 bytes would start; the four lanes of a quad write 16 contiguous bytes per
     // instruction.  Transposed in the lane quads (DPP moves on copies of the accumulators) and stored 16 bytes per
     // lane, the first prefix signature of a round of four increments came out, now and then, with one register of
     // the transposed level wrong in lanes 12..15 of every row of 16 lanes, once a SIMD held more than one wavefront
-    // (more than 128 paths; depth 6 and 7; the state itself stayed right).  Final mode transposes once, after the
-    // scan, and never showed it.
+    // (more than 128 paths; depth 6 and 7, stream mode, where every increment ends in a store; the state itself
+    // stayed right).  Final mode, with one store after the scan, never showed it and takes the same route.
     const int back = 12 * (lane & 3);
     auto store_word = [&](float word, int offset) {
         // through a vector register: handed the element of an accumulator tuple directly, the compiler stored element 0
@@ -290,7 +290,7 @@ sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out
             if constexpr (STREAM) store_shard<N, true>(S, rsrc, s * kS * 4, plan, lane);
         }
     }
-    if constexpr (!STREAM) store_shard<N>(S, make_rsrc(o, kS * 4u), 0, plan, lane);
+    if constexpr (!STREAM) store_shard<N, true>(S, make_rsrc(o, kS * 4u), 0, plan, lane);
 }
 
 
