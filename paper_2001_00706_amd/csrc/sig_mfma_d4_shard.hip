@@ -145,7 +145,7 @@ typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 // Writes this shard's slice of every level of one signature.  The signature starts `row_bytes`
 // into the buffer described by `rsrc` (a wave-uniform scalar), so the stores need no per-lane
 // address arithmetic; stores beyond the descriptor's range would be dropped by the hardware.
-template <int N, bool IN_PLACE = false>
+template <int N>
 __device__ __forceinline__ void store_shard(const ShardState<N> &S, __amdgpu_buffer_rsrc_t rsrc, int row_bytes,
                                             const StorePlan &p, int lane)
 {
@@ -153,10 +153,9 @@ __device__ __forceinline__ void store_shard(const ShardState<N> &S, __amdgpu_buf
                          (__builtin_bit_cast(unsigned, S.A3) & p.m3);
     __builtin_amdgcn_raw_buffer_store_b32(low, rsrc, p.low_off, row_bytes, 0);
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, S.A4), rsrc, p.off4, row_bytes, 0);
-    // IN_PLACE (what both modes of the four-wavefront kernel use): a level below the top one goes out as it sits in
-    // the registers (register r = letter w_{k-1}, lane q = letter w_k): four one-word stores, 16 r - 12 q bytes from
-    // where the lane's transposed 16 bytes would start; the four lanes of a quad write 16 contiguous bytes per
-    // instruction.  Transposed in the lane quads (DPP moves on copies of the accumulators) and stored 16 bytes per
+    // A level below the top one goes out as it sits in the registers (register r = letter w_{k-1}, lane q = letter
+    // w_k): four one-word stores, 16 r - 12 q bytes from where 16 bytes of four consecutive words would start; the
+    // four lanes of a quad write 16 contiguous bytes per instruction.  Transposed in the lane quads (DPP moves on copies of the accumulators) and stored 16 bytes per
     // lane, the first prefix signature of a round of four increments came out, now and then, with one register of
     // the transposed level wrong in lanes 12..15 of every row of 16 lanes, once a SIMD held more than one wavefront
     // (more than 128 paths; depth 6 and 7, stream mode, where every increment ends in a store; the state itself
@@ -169,23 +168,21 @@ __device__ __forceinline__ void store_shard(const ShardState<N> &S, __amdgpu_buf
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, word), rsrc, offset, row_bytes, 0);
     };
     if constexpr (N >= 5) {
-        if constexpr (N >= 6 && IN_PLACE) {
+        if constexpr (N >= 6) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) store_word(S.A5[0][r], p.off5 - back + 16 * r);
         } else {
-            const f4 v = N == 5 ? S.A5[0] : quad_transpose(S.A5[0], lane);
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), rsrc, p.off5, row_bytes, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, S.A5[0]), rsrc, p.off5, row_bytes, 0);
         }
     }
     if constexpr (N >= 6) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            if constexpr (N >= 7 && IN_PLACE) {
+            if constexpr (N >= 7) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) store_word(S.A6[g][r], p.off6 + 64 * g - back + 16 * r);
             } else {
-                const f4 v = N == 6 ? S.A6[g] : quad_transpose(S.A6[g], lane);
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), rsrc, p.off6 + 64 * g, row_bytes, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, S.A6[g]), rsrc, p.off6 + 64 * g, row_bytes, 0);
             }
         }
     }
@@ -282,15 +279,15 @@ sig_mfma_d4_shard_kernel(const float *__restrict__ path, float *__restrict__ out
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 shard_step<N>(S, R[i]);
-                if constexpr (STREAM) store_shard<N, true>(S, rsrc, (s + i) * kS * 4, plan, lane);
+                if constexpr (STREAM) store_shard<N>(S, rsrc, (s + i) * kS * 4, plan, lane);
             }
         }
         for (; s < nt; ++s) {
             shard_step<N>(S, load_shard_row<N>(lds + s * kRow, f, w2, w3, q));
-            if constexpr (STREAM) store_shard<N, true>(S, rsrc, s * kS * 4, plan, lane);
+            if constexpr (STREAM) store_shard<N>(S, rsrc, s * kS * 4, plan, lane);
         }
     }
-    if constexpr (!STREAM) store_shard<N, true>(S, make_rsrc(o, kS * 4u), 0, plan, lane);
+    if constexpr (!STREAM) store_shard<N>(S, make_rsrc(o, kS * 4u), 0, plan, lane);
 }
 
 
@@ -311,7 +308,12 @@ __device__ __forceinline__ void lds_store_shard(const ShardState<N> &S, char *ro
                          (__builtin_bit_cast(unsigned, S.A3) & p.m3);
     *reinterpret_cast<unsigned *>(row + p.low_off) = low;
     *reinterpret_cast<float *>(row + p.off4) = S.A4;
-    if constexpr (N >= 5) *reinterpret_cast<f4 *>(row + p.off5) = N == 5 ? S.A5[0] : quad_transpose(S.A5[0], lane);
+    if constexpr (N == 5) *reinterpret_cast<f4 *>(row + p.off5) = S.A5[0];
+    if constexpr (N >= 6) {
+        // level 5 as it sits in the registers (register r = letter w_4, lane q = letter w_5), a word per register
+#pragma unroll
+        for (int r = 0; r < 4; ++r) *reinterpret_cast<float *>(row + p.off5 - 12 * (lane & 3) + 16 * r) = S.A5[0][r];
+    }
     if constexpr (N >= 6) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) *reinterpret_cast<f4 *>(row + p.off6 + 64 * g) = S.A6[g];
