@@ -144,7 +144,7 @@ def test_tree_gradient_every_shape(dtype, stream):
     one, which in stream mode takes the identity for the signature before it), misaligned so that no other family
     takes the call.  In fp64 stream mode at d = 4, N = 8; d = 5, N = 7; d = 6, N = 6 and d = 8, N = 6 the first
     increment once lost the cotangent of the levels above a thread's word."""
-    for d, N in tree_gradient_shapes(3_000_000 if not stream else 1_000_000):
+    for d, N in tree_gradient_shapes(3_000_000):
         x = uniform_paths(2, 3, d, seed=100 * d + N, lo=-0.4, hi=0.4).astype(dtype)
         check(x, N, stream=stream, misalign=True)
 
