@@ -129,18 +129,6 @@ struct Rows8 {   // four consecutive increments
 };
 
 template <int N>
-__device__ __forceinline__ Row8<N> load_row8(const float *tab, int s, int w3, int w4, int q)
-{
-    Row8<N> R;
-    R.z4 = tab[w4 * kCol8 + s];
-    R.zlo = tab[q * kCol8 + s];
-    R.zhi = tab[(4 + q) * kCol8 + s];
-#pragma unroll
-    for (int k = 4; k <= N; ++k) R.t3[k] = tab[(kD8 * (k - 3) + w3) * kCol8 + s];
-    return R;
-}
-
-template <int N>
 __device__ __forceinline__ Rows8<N> load_rows8(const float *tab, int s, int w3, int w4, int q)   // s a multiple of 4
 {
     Rows8<N> R;
@@ -328,32 +316,31 @@ sig_mfma_d8_shard_kernel(const float *__restrict__ path, float *__restrict__ out
         }
         __syncthreads();
         P0 = fetch_points(t0 + kTile8 + lane);
+        // The tile is walked in rounds of four increments, the next four fetched from LDS while these are folded in
+        // (two sets of registers taking turns, so that nothing is copied).  The rows past the end of the scan hold
+        // zero increments, which leave the state as it is (T z + A with z = 0), so the last round needs no shorter
+        // variant.
+        const int nr = (nt + 3) & ~3;
         int s = 0;
-        if (nt >= 4) {
-            // four increments per LDS round trip, the next four fetched while these are folded in (two sets of
-            // registers taking turns, so that nothing is copied)
-            Rows8<N> V0 = load_rows8<N>(lds, 0, w3, w4, q);
-            for (; s + 12 <= nt; s += 8) {
-                const Rows8<N> V1 = load_rows8<N>(lds, s + 4, w3, w4, q);
-                __builtin_amdgcn_sched_barrier(0);   // the reads are issued before the arithmetic they hide behind
-#pragma unroll
-                for (int i = 0; i < 4; ++i) step8<N>(S, pick_row8<N>(V0, i));
-                V0 = load_rows8<N>(lds, s + 8, w3, w4, q);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) step8<N>(S, pick_row8<N>(V1, i));
-            }
+        Rows8<N> V0 = load_rows8<N>(lds, 0, w3, w4, q);
+        for (; s + 12 <= nr; s += 8) {
+            const Rows8<N> V1 = load_rows8<N>(lds, s + 4, w3, w4, q);
+            __builtin_amdgcn_sched_barrier(0);   // the reads are issued before the arithmetic they hide behind
 #pragma unroll
             for (int i = 0; i < 4; ++i) step8<N>(S, pick_row8<N>(V0, i));
-            s += 4;
-            if (s + 4 <= nt) {
-                const Rows8<N> V1 = load_rows8<N>(lds, s, w3, w4, q);
+            V0 = load_rows8<N>(lds, s + 8, w3, w4, q);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) step8<N>(S, pick_row8<N>(V1, i));
-                s += 4;
-            }
+            for (int i = 0; i < 4; ++i) step8<N>(S, pick_row8<N>(V1, i));
         }
-        for (; s < nt; ++s) step8<N>(S, load_row8<N>(lds, s, w3, w4, q));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) step8<N>(S, pick_row8<N>(V0, i));
+        s += 4;
+        if (s < nr) {
+            const Rows8<N> V1 = load_rows8<N>(lds, s, w3, w4, q);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) step8<N>(S, pick_row8<N>(V1, i));
+        }
     }
     // store this shard's slice of every level
     const int f = f1 * 8 + f2;
